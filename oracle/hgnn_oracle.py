@@ -1,0 +1,285 @@
+"""CPU oracle for the mini-batch HGNN layer hot path (TEST INFRASTRUCTURE ONLY).
+
+Plain, slow numpy in float64.  It evaluates the layer exactly as it is defined,
+*unmerged*: one vertex type and one relation (semantic graph) at a time, the
+four stages of an HGNN layer in the order the paper lists them (Section 2.2:
+semantic graph build, feature projection, neighbour aggregation, semantic
+fusion), and the backward pass as the step-by-step reverse of that forward.
+
+Only tests, the smoke check and the benchmark's `cpu_baseline` leg may import
+this module.  It shares no code with the HIP path and imports nothing from it.
+
+What the paper fixes and what it leaves open
+--------------------------------------------
+The paper names the stages and gives two algorithms (Algorithm 1: aggregation
+over type-first, merged features; Algorithm 2: edge-index selection).  Both are
+exact re-organisations: they change launch structure and data layout, never the
+result (Section 4.2).  It prints no layer equations; the R-GCN layer evaluated
+here is
+    h_v = act( x_v W_0^{type(v)} + b_{type(v)}
+               + sum_{r : dst(r)=type(v)}  mean_{u in N_r(v)} x_u W_r )
+with an empty neighbourhood contributing zero, the mean taken over the sampled
+edges of relation r that end in v.
+
+Pins (see tests/test_oracle_*.py): a hand-worked 4-vertex example, dense
+adjacency-matrix brute force, a scipy.sparse reduction for one relation,
+merged-vs-unmerged equality, constant-feature means, permutation equivariance,
+project/aggregate commutation, finite-difference gradients, numpy.lexsort for
+the index outputs, closed forms for the cross-entropy.
+
+Parity unpinned by the paper: the attention variant's definition (functions
+`rgat_*`): the paper cites R-GAT without equations, so those functions are
+pinned only by special cases that reduce to the mean layer, by softmax
+invariants and by finite differences.
+"""
+from __future__ import annotations
+
+import numpy as np
+
+F64 = np.float64
+
+
+# --------------------------------------------------------------------------- #
+# Stage 0: type-first feature layout (Section 4.2, "Reorganizing Features")
+# --------------------------------------------------------------------------- #
+def merge_features(stores, ids):
+    """Rows of the mini-batch, grouped by vertex type first and by position in the
+    type's id list second.  Returns (blocks, row_off, elem_off, flat) where block t
+    is `stores[t][ids[t]]`, `row_off[t]` counts rows before type t, `elem_off[t]`
+    counts scalars before type t and `flat` is the blocks laid end to end."""
+    T = len(stores)
+    blocks, row_off, elem_off = [], [0], [0]
+    for t in range(T):
+        blk = np.zeros((len(ids[t]), stores[t].shape[1]), dtype=stores[t].dtype)
+        for i, gid in enumerate(ids[t]):
+            blk[i, :] = stores[t][int(gid), :]
+        blocks.append(blk)
+        row_off.append(row_off[-1] + blk.shape[0])
+        elem_off.append(elem_off[-1] + blk.shape[0] * blk.shape[1])
+    flat = np.concatenate([b.ravel() for b in blocks]) if T else np.zeros(0)
+    return blocks, np.array(row_off, dtype=np.int32), np.array(elem_off, dtype=np.int64), flat
+
+
+# --------------------------------------------------------------------------- #
+# Stage 1: semantic graph build (Algorithm 2, then grouping by destination)
+# --------------------------------------------------------------------------- #
+def edge_index_select(edge_index, num_rels, edge_type=None, edge_id=None, global_edge_type=None):
+    """Algorithm 2 for one layer.  The layer's edge types are looked up through the
+    edge ids (or given directly); then, for each relation j in turn, the edges whose
+    type equals j are selected, keeping their input order.  Returns, per relation,
+    (src, dst, pos) with `pos` the selected edges' positions in the input list."""
+    if edge_type is None:
+        edge_type_layer = np.asarray(global_edge_type)[np.asarray(edge_id)]
+    else:
+        edge_type_layer = np.asarray(edge_type)
+    out = []
+    for j in range(num_rels):
+        mask = (edge_type_layer == j)
+        pos = np.nonzero(mask)[0]
+        out.append((np.asarray(edge_index[0])[mask].astype(np.int64),
+                    np.asarray(edge_index[1])[mask].astype(np.int64), pos.astype(np.int64)))
+    return out
+
+
+def semantic_csr(selected, rel_src, rel_dst, n_src, n_dst):
+    """One CSR over all relations.  Relation r owns rows
+    rel_row_off[r] .. rel_row_off[r+1]-1, one per destination vertex of type dst(r)
+    (also when r has no edge).  A row lists its edges in input order; `colidx` is the
+    source's row in the type-first feature matrix; `perm` the edge's input position.
+    The transpose groups the same edges by `colidx`, ascending CSR position inside a
+    group: `crow` is the edge's CSR row, `cperm` its CSR position."""
+    R, T = len(rel_src), len(n_src)
+    row_off = [0]
+    for t in range(T):
+        row_off.append(row_off[-1] + int(n_src[t]))
+    rel_row_off = [0]
+    for r in range(R):
+        rel_row_off.append(rel_row_off[-1] + int(n_dst[rel_dst[r]]))
+    rows = [[] for _ in range(rel_row_off[-1])]
+    rel_edge_off = [0]
+    for r in range(R):
+        src, dst, pos = selected[r]
+        for k in range(len(src)):
+            s, d = int(src[k]), int(dst[k])
+            if not (0 <= s < n_src[rel_src[r]] and 0 <= d < n_dst[rel_dst[r]]):
+                raise ValueError("edge endpoint out of range")
+            rows[rel_row_off[r] + d].append((row_off[rel_src[r]] + s, int(pos[k])))
+        rel_edge_off.append(rel_edge_off[-1] + len(src))
+    rowptr, colidx, perm = [0], [], []
+    for lst in rows:
+        for (c, p) in lst:
+            colidx.append(c); perm.append(p)
+        rowptr.append(len(colidx))
+    cols = [[] for _ in range(row_off[-1])]
+    for rho in range(len(rows)):
+        for k in range(rowptr[rho], rowptr[rho + 1]):
+            cols[colidx[k]].append((rho, k))
+    cptr, crow, cperm = [0], [], []
+    for lst in cols:
+        for (rho, k) in lst:
+            crow.append(rho); cperm.append(k)
+        cptr.append(len(crow))
+    i32 = lambda a: np.array(a, dtype=np.int32)
+    return dict(row_off=i32(row_off), rel_row_off=i32(rel_row_off), rel_edge_off=i32(rel_edge_off),
+                rowptr=i32(rowptr), colidx=i32(colidx), perm=i32(perm),
+                cptr=i32(cptr), crow=i32(crow), cperm=i32(cperm))
+
+
+def _neighbour_lists(src, dst, num_dst):
+    nb = [[] for _ in range(num_dst)]
+    for k in range(len(src)):
+        nb[int(dst[k])].append(int(src[k]))
+    return nb
+
+
+# --------------------------------------------------------------------------- #
+# Stages 2-4: R-GCN layer, forward and backward, unmerged
+# --------------------------------------------------------------------------- #
+def rgcn_layer_forward(x, rel_edges, rel_src, rel_dst, n_dst, w_rel, w_root, bias, relu):
+    """x: per type [N_t, F_t]; rel_edges: per relation (src_local, dst_local, ...);
+    w_rel[r]: [F_src(r), H]; w_root[t]: [F_t, H] or None; bias[t]: [H] or None.
+    Returns (h per type [n_dst[t], H], cache)."""
+    T, R = len(x), len(rel_src)
+    x = [np.asarray(a, dtype=F64) for a in x]
+    H = int(np.asarray(w_rel[0]).shape[1]) if R else int(np.asarray(w_root[0]).shape[1])
+    pre = []
+    for t in range(T):                                   # root term and bias
+        p = np.zeros((int(n_dst[t]), H), dtype=F64)
+        if n_dst[t] > 0:
+            if w_root[t] is not None:
+                p += x[t][: n_dst[t]] @ np.asarray(w_root[t], dtype=F64)
+            if bias[t] is not None:
+                p += np.asarray(bias[t], dtype=F64)[None, :]
+        pre.append(p)
+    nbrs = []
+    for r in range(R):
+        s, d = rel_src[r], rel_dst[r]
+        nb = _neighbour_lists(rel_edges[r][0], rel_edges[r][1], int(n_dst[d]))
+        nbrs.append(nb)
+        if n_dst[d] == 0 or len(rel_edges[r][0]) == 0:
+            continue
+        y = x[s] @ np.asarray(w_rel[r], dtype=F64)       # feature projection
+        for v in range(int(n_dst[d])):                   # neighbour aggregation (mean)
+            if nb[v]:
+                pre[d][v] += y[nb[v]].sum(axis=0) / len(nb[v])   # ... and fusion (sum over r)
+    h = [np.maximum(p, 0.0) if relu else p.copy() for p in pre]
+    cache = dict(x=x, nbrs=nbrs, pre=pre, rel_src=rel_src, rel_dst=rel_dst, n_dst=list(n_dst),
+                 w_rel=w_rel, w_root=w_root, bias=bias, relu=relu)
+    return h, cache
+
+
+def rgcn_layer_backward(cache, grad_h):
+    """Reverse of `rgcn_layer_forward`, one step at a time.  grad_h: per type
+    [n_dst[t], H].  Returns (dx per type, dw_rel, dw_root, dbias); parameters that
+    received no contribution get zeros (None where the parameter is None)."""
+    x, nbrs, pre = cache["x"], cache["nbrs"], cache["pre"]
+    rel_src, rel_dst, n_dst = cache["rel_src"], cache["rel_dst"], cache["n_dst"]
+    w_rel, w_root, bias = cache["w_rel"], cache["w_root"], cache["bias"]
+    T, R = len(x), len(rel_src)
+    gp = []
+    for t in range(T):
+        g = np.asarray(grad_h[t], dtype=F64).reshape(pre[t].shape)
+        gp.append(g * (pre[t] > 0) if cache["relu"] else g.copy())
+    dx = [np.zeros_like(a) for a in x]
+    dw_root, dbias = [], []
+    for t in range(T):
+        if w_root[t] is None:
+            dw_root.append(None)
+        else:
+            w0 = np.asarray(w_root[t], dtype=F64)
+            dw_root.append(x[t][: n_dst[t]].T @ gp[t])
+            dx[t][: n_dst[t]] += gp[t] @ w0.T
+        dbias.append(None if bias[t] is None else gp[t].sum(axis=0))
+    dw_rel = []
+    for r in range(R):
+        s, d = rel_src[r], rel_dst[r]
+        w = np.asarray(w_rel[r], dtype=F64)
+        dy = np.zeros((x[s].shape[0], w.shape[1]), dtype=F64)
+        for v in range(int(n_dst[d])):
+            nb = nbrs[r][v]
+            if nb:
+                np.add.at(dy, nb, gp[d][v] / len(nb))
+        dw_rel.append(x[s].T @ dy)
+        dx[s] += dy @ w.T
+    return dx, dw_rel, dw_root, dbias
+
+
+def rgcn_layer_forward_merged(flat, feat_dim, csr, rel_src, rel_dst, n_dst, w_rel, w_root, bias, relu):
+    """Same layer, but reading the type-first flat feature buffer through the merged
+    CSR (the data path of Algorithm 1): each merged row gathers its sources through
+    `colidx`, in row order.  Used to check that merging changes no value."""
+    T, R = len(feat_dim), len(rel_src)
+    row_off, rel_row_off = csr["row_off"], csr["rel_row_off"]
+    rowptr, colidx = csr["rowptr"], csr["colidx"]
+    blocks, e = [], 0
+    for t in range(T):
+        n = int(row_off[t + 1] - row_off[t])
+        blocks.append(np.asarray(flat[e: e + n * feat_dim[t]], dtype=F64).reshape(n, feat_dim[t]))
+        e += n * feat_dim[t]
+    H = int(np.asarray(w_rel[0]).shape[1])
+    pre = []
+    for t in range(T):
+        p = np.zeros((int(n_dst[t]), H), dtype=F64)
+        if n_dst[t] > 0:
+            if w_root[t] is not None:
+                p += blocks[t][: n_dst[t]] @ np.asarray(w_root[t], dtype=F64)
+            if bias[t] is not None:
+                p += np.asarray(bias[t], dtype=F64)[None, :]
+        pre.append(p)
+    for r in range(R):
+        s, d = rel_src[r], rel_dst[r]
+        if rel_row_off[r + 1] == rel_row_off[r]:
+            continue
+        y = blocks[s] @ np.asarray(w_rel[r], dtype=F64)
+        for v in range(int(n_dst[d])):
+            rho = int(rel_row_off[r]) + v
+            a, b = int(rowptr[rho]), int(rowptr[rho + 1])
+            if b > a:
+                pre[d][v] += y[colidx[a:b] - row_off[s]].sum(axis=0) / (b - a)
+    return [np.maximum(p, 0.0) if relu else p for p in pre]
+
+
+# --------------------------------------------------------------------------- #
+# Loss used by the two academic-graph configurations
+# --------------------------------------------------------------------------- #
+def softmax_xent(logits, labels):
+    """Mean softmax cross-entropy over the rows and its gradient w.r.t. the logits."""
+    z = np.asarray(logits, dtype=F64)
+    n = z.shape[0]
+    zs = z - z.max(axis=1, keepdims=True)
+    lse = np.log(np.exp(zs).sum(axis=1))
+    logp = zs - lse[:, None]
+    loss = -logp[np.arange(n), labels].mean()
+    g = np.exp(logp)
+    g[np.arange(n), labels] -= 1.0
+    return loss, g / n
+
+
+# --------------------------------------------------------------------------- #
+# Whole model: layers stacked, each layer's output rows are the next layer's input
+# --------------------------------------------------------------------------- #
+def rgcn_model_forward_backward(x0, blocks_sel, rel_src, rel_dst, blocks_n_dst, layers, loss,
+                                labels=None, grad_out=None, target_type=0):
+    """x0: per type first-layer input; blocks_sel[l]: per-relation selected edges of
+    layer l; layers[l]: dict(w_rel, w_root, bias, relu).  loss: "xent" (mean softmax
+    cross-entropy of the target type's last-layer rows) or "dot" (sum of grad_out*h).
+    Returns dict with per-layer outputs, loss value and all gradients."""
+    xs, caches, hs = [x0], [], []
+    for l, lw in enumerate(layers):
+        h, c = rgcn_layer_forward(xs[-1], blocks_sel[l], rel_src, rel_dst, blocks_n_dst[l],
+                                  lw["w_rel"], lw["w_root"], lw["bias"], lw["relu"])
+        caches.append(c); hs.append(h); xs.append(h)
+    T = len(x0)
+    if loss == "xent":
+        val, g_t = softmax_xent(hs[-1][target_type], labels)
+        g = [np.zeros_like(h) for h in hs[-1]]
+        g[target_type] = g_t
+    else:
+        g = [np.asarray(grad_out[t], dtype=F64) for t in range(T)]
+        val = sum(float((g[t] * hs[-1][t]).sum()) for t in range(T))
+    grads = [None] * len(layers)
+    for l in reversed(range(len(layers))):
+        dx, dw_rel, dw_root, dbias = rgcn_layer_backward(caches[l], g)
+        grads[l] = dict(dw_rel=dw_rel, dw_root=dw_root, dbias=dbias, dx=dx)
+        g = dx
+    return dict(h=hs, loss=val, grads=grads, dx0=g)
