@@ -1,0 +1,216 @@
+/*
+ * hgnn.h -- C ABI of the MI355X (gfx950) mini-batch HGNN layer library.
+ *
+ * The library runs the per-layer compute of mini-batch heterogeneous-GNN training
+ * -- the four stages the HiFuse paper (arXiv 2408.08490) lists in Section 2.2:
+ * semantic graph build, feature projection, neighbour aggregation, semantic fusion,
+ * forward and backward -- over ONE type-first merged feature matrix and ONE merged,
+ * relation-segmented CSR, so that every stage is a single kernel launch instead of
+ * one short launch per vertex type or relation (Section 4.2, Algorithm 1), with the
+ * integer-only semantic graph build done by host threads and uploaded on a side
+ * stream (Section 4.3, Algorithm 2 and "Pipelining").
+ *
+ * Conventions
+ *  - T vertex types, R relations (semantic graphs); relation r goes from type
+ *    rel_src_type[r] to type rel_dst_type[r].  Limits: T <= 32, R <= 128.
+ *  - "device" pointers are HIP device memory owned by the CALLER (the Python binding
+ *    uses PyTorch tensors); "host" pointers are ordinary host memory.  The library
+ *    owns only what hangs off hgnn_ctx / hgnn_graph.
+ *  - `stream` is a hipStream_t passed as void* (NULL = the default stream).  Compute
+ *    entry points only enqueue work; they do not synchronise the stream.
+ *  - Feature matrices are row-major.  dtype (hgnn_schema.dtype) is the storage type
+ *    of features, weights, activations and feature gradients; all sums accumulate in
+ *    fp32; weight and bias gradients are always fp32.
+ *  - Every feature width (in_dim[t]) must be a multiple of 16 bytes / sizeof(dtype)
+ *    (4 for fp32, 8 for bf16); out_dim may be any positive value.
+ *  - Every function returns HGNN_OK or a negative hgnn_status; hgnn_last_error gives
+ *    the text of the calling thread's most recent failure.  On failure no caller
+ *    output buffer has been handed to a kernel by that call.
+ */
+#ifndef HGNN_H
+#define HGNN_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+#define HGNN_MAX_TYPES 32
+#define HGNN_MAX_RELS 128
+
+typedef struct hgnn_ctx hgnn_ctx;     /* thread pool, pinned staging, side stream, buffer pool   */
+typedef struct hgnn_graph hgnn_graph; /* one mini-batch: merged CSR + transpose for every layer  */
+
+typedef enum {
+  HGNN_OK = 0,
+  HGNN_EINVAL = -1,       /* NULL pointer, bad size, index or edge type out of range            */
+  HGNN_ENOMEM = -2,       /* host or device allocation failed                                   */
+  HGNN_EHIP = -3,         /* a HIP runtime call failed (text in hgnn_last_error)                */
+  HGNN_EOVERFLOW = -4,    /* a row / edge / element count does not fit the int32 index outputs  */
+  HGNN_ENOTREADY = -5,    /* graph build failed or was never started                            */
+  HGNN_EUNSUPPORTED = -6  /* valid request outside what this build implements                   */
+} hgnn_status;
+
+typedef enum { HGNN_F32 = 0, HGNN_BF16 = 1 } hgnn_dtype;
+typedef enum { HGNN_AGG_MEAN = 0, HGNN_AGG_ATTN = 1 } hgnn_agg;
+typedef enum { HGNN_FUSE_SUM = 0, HGNN_FUSE_SEMATTN = 1 } hgnn_fuse;
+
+typedef struct {
+  int32_t num_types, num_rels;
+  const int32_t *rel_src_type; /* host [R] */
+  const int32_t *rel_dst_type; /* host [R] */
+  int32_t heads;               /* 1 for mean aggregation */
+  int32_t agg;                 /* hgnn_agg   */
+  int32_t fuse;                /* hgnn_fuse  */
+  int32_t dtype;               /* hgnn_dtype */
+} hgnn_schema;
+
+/* Create a context bound to HIP device `device` with `host_threads` builder threads
+ * (<= 0: one per online core, at most 16).  The schema is copied. */
+hgnn_status hgnn_create(hgnn_ctx **out, const hgnn_schema *schema, int device, int host_threads);
+void hgnn_destroy(hgnn_ctx *ctx);
+/* Message of the calling thread's last failed call; never NULL. */
+const char *hgnn_last_error(void);
+
+/* ---- Stage 0: type-first feature layout (Section 4.2 "Reorganizing Features") ------------
+ * Gathers the mini-batch's rows out of T device-resident per-type feature stores into one
+ * buffer ordered by vertex type first, by position in ids[t] second:
+ *     x_merged[elem_off[t] + i*feat_dim[t] + c] = store[t][ids[t][i]*feat_dim[t] + c].
+ * One kernel launch for all types.
+ *   store    host array [T] of device pointers, store[t] is [num_vertices_t x feat_dim[t]] (dtype)
+ *   ids      host array [T] of device pointers to int64 [n_rows[t]] (may be NULL when n_rows[t]==0);
+ *            every id must be a valid row of store[t] (not checked on the device)
+ *   x_merged device, at least elem_off[T] elements (caller computes the size the same way)
+ *   row_off  host out int32 [T+1]: rows before type t;  elem_off host out int64 [T+1]: scalars before type t
+ * Errors: EINVAL (NULL, negative count, bad feat_dim), EOVERFLOW (more than 2^31-1 rows). */
+hgnn_status hgnn_merge_features(hgnn_ctx *ctx, void *stream, const void *const *store,
+                                const int32_t *feat_dim, const int64_t *const *ids,
+                                const int64_t *n_rows, void *x_merged, int32_t *row_off,
+                                int64_t *elem_off);
+
+/* ---- Stage 1: semantic graph build on the host (Section 4.3, Algorithm 2) ----------------
+ * One mini-batch layer as the sampler hands it over: a COO edge list mixing all relations. */
+typedef struct {
+  int64_t num_edges;
+  const void *edge_index;          /* host [2 x num_edges]: row 0 = local source index within its type,
+                                      row 1 = local destination index within its type */
+  int32_t index_is_i64;            /* 1: int64 entries, 0: int32 entries */
+  const int32_t *edge_type;        /* host [num_edges] relation of each edge, or NULL, then: */
+  const int64_t *edge_id;          /* host [num_edges] ids into global_edge_type (Algorithm 2's EdgeID) */
+  const int32_t *global_edge_type; /* host [num_global_edges] (Algorithm 2's EdgeType) */
+  int64_t num_global_edges;
+  const int64_t *n_src;            /* host [T] source-side rows per type (rows of this layer's x_merged) */
+  const int64_t *n_dst;            /* host [T] destination rows per type; the destinations of type t are
+                                      the FIRST n_dst[t] of its n_src[t] source rows */
+} hgnn_coo_layer;
+
+/* Starts the build of all `num_layers` layers (execution order) on the context's host threads
+ * and returns; the threads select edges by relation (Algorithm 2), sort them stably into one
+ * merged CSR per layer plus its transpose, stage the arrays in pinned memory and upload them on
+ * the context's side stream.  The input arrays must stay valid and unchanged until
+ * hgnn_graph_wait returns (or until the first hgnn_layer_fwd/bwd on the graph returns).
+ * Validation errors (edge type outside [0,R), endpoint outside [0,n_src)/[0,n_dst),
+ * n_dst[t] > n_src[t], counts >= 2^31) are reported by hgnn_graph_wait / hgnn_layer_* as the
+ * status of the build.  Argument errors (NULL, num_layers outside 1..8) are reported here. */
+hgnn_status hgnn_build_semantic_csr(hgnn_ctx *ctx, int32_t num_layers, const hgnn_coo_layer *layers,
+                                    hgnn_graph **out);
+/* Blocks the calling host thread until the build and the upload have finished; returns the
+ * build's status. */
+hgnn_status hgnn_graph_wait(hgnn_ctx *ctx, hgnn_graph *g);
+
+/* Host-side view of one layer's index arrays (valid until hgnn_graph_release; waits for the
+ * build first).  All arrays int32:
+ *   rel_row_off [R+1]   merged row range of relation r: one row per destination vertex of type
+ *                       rel_dst_type[r], i.e. merged row = rel_row_off[r] + local destination
+ *   rel_edge_off[R+1]   CSR position range of relation r's edges
+ *   rowptr [rows+1], colidx [edges]  merged CSR; colidx = row of the source in x_merged
+ *                       (= row_off[src type] + local source); inside a row, input order is kept
+ *   perm   [edges]      input position of the CSR edge
+ *   cptr [src_rows+1], crow [edges], cperm [edges]  transpose: for every x_merged row the edges
+ *                       that read it, ascending CSR position; crow = merged CSR row, cperm = CSR position
+ * Any output pointer may be NULL. */
+typedef struct {
+  int64_t rows, edges, src_rows;
+  const int32_t *rel_row_off, *rel_edge_off, *rowptr, *colidx, *perm, *cptr, *crow, *cperm;
+} hgnn_csr_view;
+hgnn_status hgnn_graph_host_view(hgnn_ctx *ctx, hgnn_graph *g, int32_t layer, hgnn_csr_view *view);
+/* Returns the graph's buffers to the context's pool.  Work already enqueued that reads the
+ * graph must have been ordered before the next build on a stream the caller synchronises, or
+ * simply finished. */
+void hgnn_graph_release(hgnn_ctx *ctx, hgnn_graph *g);
+
+/* ---- Stages 2-4: projection, aggregation, fusion (Section 2.2; Algorithm 1) ---------------
+ * Layer parameters.  All arrays are HOST arrays of DEVICE pointers (dtype elements). */
+typedef struct {
+  const int32_t *in_dim;       /* host [T] input width per type */
+  int32_t out_dim;             /* H */
+  int32_t relu;                /* 1: ReLU after fusion + bias */
+  const void *const *w_rel;    /* [R] W_r  [in_dim[src(r)] x H]            (mean aggregation) */
+  const void *const *w_root;   /* [T] W_0^t [in_dim[t] x H] or NULL entry  (mean aggregation) */
+  const void *const *bias;     /* [T] b_t [H] or NULL entry; the array itself may be NULL      */
+} hgnn_layer_params;
+
+/* fp32 gradient buffers mirroring hgnn_layer_params (device, caller-owned, OVERWRITTEN).
+ * A NULL entry (or NULL array) skips that gradient. */
+typedef struct {
+  float *const *dw_rel;  /* [R] */
+  float *const *dw_root; /* [T] */
+  float *const *dbias;   /* [T] */
+} hgnn_layer_grads;
+
+/* Bytes of the two device work areas of one layer on this graph:
+ *   saved   written by hgnn_layer_fwd, read by hgnn_layer_bwd (per-relation aggregated features)
+ *   scratch temporary for either call (contents undefined afterwards)
+ * Both must be 256-byte aligned. */
+hgnn_status hgnn_layer_workspace_bytes(hgnn_ctx *ctx, hgnn_graph *g, int32_t layer,
+                                       const hgnn_layer_params *p, size_t *saved_bytes,
+                                       size_t *scratch_bytes);
+
+/* Forward of one R-GCN style layer (mean aggregation, sum fusion):
+ *   h[v] = act( x[v] W_0^{t} + b_t + sum_{r: dst(r)=t} mean_{u in N_r(v)} x[u] W_r ),  t = type(v),
+ * an empty neighbourhood contributing zero.  Evaluated as: one relation-segmented gather-mean over
+ * the merged CSR (aggregation of the raw features, which commutes with the linear projection),
+ * then one grouped GEMM per launch whose K dimension runs over [Z_r1 | Z_r2 | ... | x_dst] so that
+ * the semantic fusion is the GEMM's accumulation and bias/activation its epilogue.
+ *   x_merged device, type-first [sum_t n_src[t]*in_dim[t]] (layout of hgnn_merge_features)
+ *   h_out    device, type-first [sum_t n_dst[t] x H]; type t's block starts at row sum_{t'<t} n_dst[t'].
+ *            It is the next layer's x_merged.
+ * Waits (on the stream, not the host) for the graph upload; blocks the host only until the host
+ * build has been enqueued. */
+hgnn_status hgnn_layer_fwd(hgnn_ctx *ctx, void *stream, hgnn_graph *g, int32_t layer,
+                           const hgnn_layer_params *p, const void *x_merged, void *h_out,
+                           void *saved, size_t saved_bytes, void *scratch, size_t scratch_bytes);
+
+/* Backward of the same layer.  grad_h: device [sum_t n_dst[t] x H] (dtype), h_out: the forward's
+ * output (needed for the ReLU mask).  Outputs: grad_x_merged (device, layout of x_merged, dtype;
+ * NULL skips it) and the fp32 weight/bias gradients in `g_out`.  Gradients of parameters that no
+ * edge or row touches are exactly zero. */
+hgnn_status hgnn_layer_bwd(hgnn_ctx *ctx, void *stream, hgnn_graph *g, int32_t layer,
+                           const hgnn_layer_params *p, const void *x_merged, const void *h_out,
+                           const void *saved, const void *grad_h, void *grad_x_merged,
+                           const hgnn_layer_grads *g_out, void *scratch, size_t scratch_bytes);
+
+/* Launch-count baseline: the same results as hgnn_layer_fwd / hgnn_layer_bwd, but every stage is
+ * launched once per relation / per vertex type (the un-merged structure the paper's Section 3
+ * measures).  `launches` (host out, may be NULL) receives the number of kernels enqueued. */
+hgnn_status hgnn_layer_fwd_naive(hgnn_ctx *ctx, void *stream, hgnn_graph *g, int32_t layer,
+                                 const hgnn_layer_params *p, const void *x_merged, void *h_out,
+                                 void *saved, size_t saved_bytes, void *scratch,
+                                 size_t scratch_bytes, int32_t *launches);
+/* Number of kernels hgnn_layer_fwd / hgnn_layer_bwd enqueue for this layer. */
+hgnn_status hgnn_layer_launch_count(hgnn_ctx *ctx, hgnn_graph *g, int32_t layer,
+                                    const hgnn_layer_params *p, int32_t *fwd_launches,
+                                    int32_t *bwd_launches);
+
+/* ---- Loss of the node-classification configurations (model wrapper, not a paper stage) ----
+ * Mean softmax cross-entropy over `rows` rows of `logits` [rows x classes] (dtype) and its gradient
+ * w.r.t. the logits (dtype, same shape).  `loss` is a device float, overwritten. */
+hgnn_status hgnn_softmax_xent(hgnn_ctx *ctx, void *stream, const void *logits, const int64_t *labels,
+                              int64_t rows, int32_t classes, float *loss, void *grad_logits);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* HGNN_H */

@@ -1,0 +1,270 @@
+"""ctypes binding of libhgnn.so: argument marshalling only.
+
+Every function mirrors a C entry point of include/hgnn.h with the same name.
+PyTorch tensors are used as device memory (their `data_ptr()` is passed) and for
+the current stream; no step of the path is computed here.  There is no fallback:
+if the shared library has not been built, importing this module raises.
+"""
+from __future__ import annotations
+
+import ctypes as C
+import os
+from typing import List, Optional, Sequence
+
+import numpy as np
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+LIB_PATH = os.path.join(_HERE, "libhgnn.so")
+
+HGNN_OK = 0
+HGNN_F32, HGNN_BF16 = 0, 1
+STATUS_NAMES = {0: "HGNN_OK", -1: "HGNN_EINVAL", -2: "HGNN_ENOMEM", -3: "HGNN_EHIP",
+                -4: "HGNN_EOVERFLOW", -5: "HGNN_ENOTREADY", -6: "HGNN_EUNSUPPORTED"}
+
+
+class HgnnError(RuntimeError):
+    def __init__(self, status, msg):
+        super().__init__(f"{STATUS_NAMES.get(status, status)}: {msg}")
+        self.status = status
+
+
+class Schema(C.Structure):
+    _fields_ = [("num_types", C.c_int32), ("num_rels", C.c_int32),
+                ("rel_src_type", C.POINTER(C.c_int32)), ("rel_dst_type", C.POINTER(C.c_int32)),
+                ("heads", C.c_int32), ("agg", C.c_int32), ("fuse", C.c_int32), ("dtype", C.c_int32)]
+
+
+class CooLayer(C.Structure):
+    _fields_ = [("num_edges", C.c_int64), ("edge_index", C.c_void_p), ("index_is_i64", C.c_int32),
+                ("edge_type", C.c_void_p), ("edge_id", C.c_void_p), ("global_edge_type", C.c_void_p),
+                ("num_global_edges", C.c_int64), ("n_src", C.c_void_p), ("n_dst", C.c_void_p)]
+
+
+class CsrView(C.Structure):
+    _fields_ = [("rows", C.c_int64), ("edges", C.c_int64), ("src_rows", C.c_int64)] + \
+               [(k, C.POINTER(C.c_int32)) for k in
+                ("rel_row_off", "rel_edge_off", "rowptr", "colidx", "perm", "cptr", "crow", "cperm")]
+
+
+class LayerParams(C.Structure):
+    _fields_ = [("in_dim", C.POINTER(C.c_int32)), ("out_dim", C.c_int32), ("relu", C.c_int32),
+                ("w_rel", C.POINTER(C.c_void_p)), ("w_root", C.POINTER(C.c_void_p)),
+                ("bias", C.POINTER(C.c_void_p))]
+
+
+class LayerGrads(C.Structure):
+    _fields_ = [("dw_rel", C.POINTER(C.c_void_p)), ("dw_root", C.POINTER(C.c_void_p)),
+                ("dbias", C.POINTER(C.c_void_p))]
+
+
+def _load():
+    if not os.path.exists(LIB_PATH):
+        raise ImportError(f"{LIB_PATH} is missing: run `python -c 'import __graft_entry__ as g; g.build()'` "
+                          "(hipcc, gfx950) first; there is no CPU fallback")
+    lib = C.CDLL(LIB_PATH)
+    vp, i32, i64 = C.c_void_p, C.c_int32, C.c_int64
+    sig = {
+        "hgnn_create": [C.POINTER(vp), C.POINTER(Schema), C.c_int, C.c_int],
+        "hgnn_merge_features": [vp, vp, C.POINTER(vp), C.POINTER(i32), C.POINTER(vp), C.POINTER(i64), vp,
+                                C.POINTER(i32), C.POINTER(i64)],
+        "hgnn_build_semantic_csr": [vp, i32, C.POINTER(CooLayer), C.POINTER(vp)],
+        "hgnn_graph_wait": [vp, vp],
+        "hgnn_graph_host_view": [vp, vp, i32, C.POINTER(CsrView)],
+        "hgnn_layer_workspace_bytes": [vp, vp, i32, C.POINTER(LayerParams), C.POINTER(C.c_size_t),
+                                       C.POINTER(C.c_size_t)],
+        "hgnn_layer_fwd": [vp, vp, vp, i32, C.POINTER(LayerParams), vp, vp, vp, C.c_size_t, vp, C.c_size_t],
+        "hgnn_layer_fwd_naive": [vp, vp, vp, i32, C.POINTER(LayerParams), vp, vp, vp, C.c_size_t, vp, C.c_size_t,
+                                 C.POINTER(i32)],
+        "hgnn_layer_bwd": [vp, vp, vp, i32, C.POINTER(LayerParams), vp, vp, vp, vp, vp, C.POINTER(LayerGrads),
+                           vp, C.c_size_t],
+        "hgnn_layer_launch_count": [vp, vp, i32, C.POINTER(LayerParams), C.POINTER(i32), C.POINTER(i32)],
+        "hgnn_softmax_xent": [vp, vp, vp, vp, i64, i32, vp, vp],
+    }
+    for name, args in sig.items():
+        f = getattr(lib, name)
+        f.argtypes = args
+        f.restype = C.c_int
+    lib.hgnn_destroy.argtypes = [vp]; lib.hgnn_destroy.restype = None
+    lib.hgnn_graph_release.argtypes = [vp, vp]; lib.hgnn_graph_release.restype = None
+    lib.hgnn_last_error.argtypes = []; lib.hgnn_last_error.restype = C.c_char_p
+    return lib
+
+
+lib = _load()
+
+EXPORTS = ["hgnn_create", "hgnn_destroy", "hgnn_last_error", "hgnn_merge_features", "hgnn_build_semantic_csr",
+           "hgnn_graph_wait", "hgnn_graph_host_view", "hgnn_graph_release", "hgnn_layer_workspace_bytes",
+           "hgnn_layer_fwd", "hgnn_layer_bwd", "hgnn_layer_fwd_naive", "hgnn_layer_launch_count",
+           "hgnn_softmax_xent"]
+
+
+def _check(st):
+    if st != HGNN_OK:
+        raise HgnnError(st, lib.hgnn_last_error().decode())
+
+
+def _ptr(t) -> Optional[int]:
+    """Device pointer of a torch tensor (None -> NULL)."""
+    return None if t is None else t.data_ptr()
+
+
+def _stream_ptr():
+    import torch
+    return torch.cuda.current_stream().cuda_stream
+
+
+class Graph:
+    """Handle of one mini-batch's index arrays; keeps the host inputs alive while the build runs."""
+
+    def __init__(self, ctx, handle, keep):
+        self.ctx, self.handle, self._keep = ctx, handle, keep
+
+    def wait(self):
+        _check(lib.hgnn_graph_wait(self.ctx.handle, self.handle))
+        self._keep = None
+
+    def host_view(self, layer):
+        v = CsrView()
+        _check(lib.hgnn_graph_host_view(self.ctx.handle, self.handle, layer, C.byref(v)))
+        R = self.ctx.num_rels
+        out = dict(rows=v.rows, edges=v.edges, src_rows=v.src_rows)
+        for k, n in (("rel_row_off", R + 1), ("rel_edge_off", R + 1), ("rowptr", v.rows + 1), ("colidx", v.edges),
+                     ("perm", v.edges), ("cptr", v.src_rows + 1), ("crow", v.edges), ("cperm", v.edges)):
+            out[k] = np.ctypeslib.as_array(getattr(v, k), shape=(n,)).copy() if n > 0 else np.zeros(0, np.int32)
+        return out
+
+    def release(self):
+        if self.handle is not None:
+            lib.hgnn_graph_release(self.ctx.handle, self.handle)
+            self.handle = None
+
+    def __del__(self):
+        try:
+            self.release()
+        except Exception:
+            pass
+
+
+class Layer:
+    """Marshalled hgnn_layer_params (+ optional gradient table) for one layer; holds the tensors."""
+
+    def __init__(self, ctx, in_dim, out_dim, relu, w_rel, w_root, bias, dw_rel=None, dw_root=None, dbias=None):
+        T, R = ctx.num_types, ctx.num_rels
+        self.tensors = (w_rel, w_root, bias, dw_rel, dw_root, dbias)
+        self._in_dim = (C.c_int32 * T)(*in_dim)
+        self._w_rel = (C.c_void_p * R)(*[_ptr(w) for w in w_rel])
+        self._w_root = (C.c_void_p * T)(*[_ptr(w) for w in w_root])
+        self._bias = (C.c_void_p * T)(*[_ptr(b) for b in bias]) if bias is not None else None
+        self.params = LayerParams(self._in_dim, out_dim, int(relu), self._w_rel, self._w_root,
+                                  self._bias if self._bias is not None else C.POINTER(C.c_void_p)())
+        self.in_dim, self.out_dim, self.relu = list(in_dim), out_dim, bool(relu)
+        self.grads = None
+        if dw_rel is not None:
+            self._dw_rel = (C.c_void_p * R)(*[_ptr(w) for w in dw_rel])
+            self._dw_root = (C.c_void_p * T)(*[_ptr(w) for w in dw_root])
+            self._dbias = (C.c_void_p * T)(*[_ptr(b) for b in dbias]) if dbias is not None else None
+            self.grads = LayerGrads(self._dw_rel, self._dw_root,
+                                    self._dbias if self._dbias is not None else C.POINTER(C.c_void_p)())
+
+
+class Context:
+    def __init__(self, rel_src: Sequence[int], rel_dst: Sequence[int], num_types: int, dtype: str = "f32",
+                 device: int = 0, host_threads: int = 0):
+        R = len(rel_src)
+        self._rs = (C.c_int32 * R)(*rel_src)
+        self._rd = (C.c_int32 * R)(*rel_dst)
+        sch = Schema(num_types, R, self._rs, self._rd, 1, 0, 0, HGNN_BF16 if dtype == "bf16" else HGNN_F32)
+        h = C.c_void_p()
+        _check(lib.hgnn_create(C.byref(h), C.byref(sch), device, host_threads))
+        self.handle, self.num_types, self.num_rels, self.dtype = h, num_types, R, dtype
+        self.rel_src, self.rel_dst = list(rel_src), list(rel_dst)
+
+    def close(self):
+        if self.handle is not None:
+            lib.hgnn_destroy(self.handle)
+            self.handle = None
+
+    def __del__(self):
+        try:
+            self.close()
+        except Exception:
+            pass
+
+    # ---- hgnn_merge_features ----
+    def hgnn_merge_features(self, stores, ids, x_merged, feat_dim=None):
+        T = self.num_types
+        feat_dim = [s.shape[1] for s in stores] if feat_dim is None else feat_dim
+        st = (C.c_void_p * T)(*[_ptr(s) for s in stores])
+        idp = (C.c_void_p * T)(*[(_ptr(i) if i is not None and i.numel() > 0 else None) for i in ids])
+        fd = (C.c_int32 * T)(*feat_dim)
+        nr = (C.c_int64 * T)(*[(0 if i is None else i.numel()) for i in ids])
+        row_off = (C.c_int32 * (T + 1))()
+        elem_off = (C.c_int64 * (T + 1))()
+        _check(lib.hgnn_merge_features(self.handle, _stream_ptr(), st, fd, idp, nr, _ptr(x_merged), row_off, elem_off))
+        return np.array(row_off[:], dtype=np.int32), np.array(elem_off[:], dtype=np.int64)
+
+    # ---- hgnn_build_semantic_csr ----
+    def hgnn_build_semantic_csr(self, blocks, global_edge_type=None, use_edge_id=False) -> Graph:
+        """blocks: objects with n_src, n_dst, edge_index (2 x E, int64 or int32), edge_type / edge_id."""
+        n = len(blocks)
+        arr = (CooLayer * n)()
+        keep = []
+        for i, b in enumerate(blocks):
+            ei = np.ascontiguousarray(b.edge_index)
+            assert ei.dtype in (np.int64, np.int32) and ei.ndim == 2 and ei.shape[0] == 2
+            ns = np.ascontiguousarray(b.n_src, dtype=np.int64)
+            nd = np.ascontiguousarray(b.n_dst, dtype=np.int64)
+            keep += [ei, ns, nd]
+            arr[i].num_edges = ei.shape[1]
+            arr[i].edge_index = ei.ctypes.data
+            arr[i].index_is_i64 = 1 if ei.dtype == np.int64 else 0
+            if use_edge_id:
+                eid = np.ascontiguousarray(b.edge_id, dtype=np.int64)
+                get = np.ascontiguousarray(global_edge_type, dtype=np.int32)
+                keep += [eid, get]
+                arr[i].edge_type = None
+                arr[i].edge_id = eid.ctypes.data
+                arr[i].global_edge_type = get.ctypes.data
+                arr[i].num_global_edges = get.shape[0]
+            else:
+                et = np.ascontiguousarray(b.edge_type, dtype=np.int32)
+                keep.append(et)
+                arr[i].edge_type = et.ctypes.data
+            arr[i].n_src = ns.ctypes.data
+            arr[i].n_dst = nd.ctypes.data
+        h = C.c_void_p()
+        _check(lib.hgnn_build_semantic_csr(self.handle, n, arr, C.byref(h)))
+        return Graph(self, h, keep)
+
+    # ---- layer calls ----
+    def hgnn_layer_workspace_bytes(self, graph: Graph, layer: int, lp: Layer):
+        a, b = C.c_size_t(), C.c_size_t()
+        _check(lib.hgnn_layer_workspace_bytes(self.handle, graph.handle, layer, C.byref(lp.params), C.byref(a), C.byref(b)))
+        return a.value, b.value
+
+    def hgnn_layer_fwd(self, graph, layer, lp, x_merged, h_out, saved, scratch):
+        _check(lib.hgnn_layer_fwd(self.handle, _stream_ptr(), graph.handle, layer, C.byref(lp.params), _ptr(x_merged),
+                                  _ptr(h_out), _ptr(saved), saved.numel() * saved.element_size(), _ptr(scratch),
+                                  scratch.numel() * scratch.element_size()))
+
+    def hgnn_layer_fwd_naive(self, graph, layer, lp, x_merged, h_out, saved, scratch) -> int:
+        n = C.c_int32()
+        _check(lib.hgnn_layer_fwd_naive(self.handle, _stream_ptr(), graph.handle, layer, C.byref(lp.params),
+                                        _ptr(x_merged), _ptr(h_out), _ptr(saved), saved.numel() * saved.element_size(),
+                                        _ptr(scratch), scratch.numel() * scratch.element_size(), C.byref(n)))
+        return n.value
+
+    def hgnn_layer_bwd(self, graph, layer, lp, x_merged, h_out, saved, grad_h, grad_x_merged, scratch):
+        _check(lib.hgnn_layer_bwd(self.handle, _stream_ptr(), graph.handle, layer, C.byref(lp.params), _ptr(x_merged),
+                                  _ptr(h_out), _ptr(saved), _ptr(grad_h), _ptr(grad_x_merged), C.byref(lp.grads),
+                                  _ptr(scratch), scratch.numel() * scratch.element_size()))
+
+    def hgnn_layer_launch_count(self, graph, layer, lp):
+        a, b = C.c_int32(), C.c_int32()
+        _check(lib.hgnn_layer_launch_count(self.handle, graph.handle, layer, C.byref(lp.params), C.byref(a), C.byref(b)))
+        return a.value, b.value
+
+    def hgnn_softmax_xent(self, logits, labels, loss, grad_logits):
+        rows, classes = logits.shape
+        _check(lib.hgnn_softmax_xent(self.handle, _stream_ptr(), _ptr(logits), _ptr(labels), rows, classes,
+                                     _ptr(loss), _ptr(grad_logits)))

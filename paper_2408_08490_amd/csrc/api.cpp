@@ -1,0 +1,607 @@
+// C ABI entry points: argument checks, per-call planning (offset tables), launch sequences.
+#include <algorithm>
+#include <cstring>
+#include <unistd.h>
+
+#include "common.h"
+
+namespace hgnn {
+const char *get_error();
+
+static inline size_t align_up(size_t v, size_t a) { return (v + a - 1) / a * a; }
+static inline int esize(int dtype) { return dtype == HGNN_BF16 ? 2 : 4; }
+
+static void builder_main(hgnn_ctx *ctx) {
+  if (ctx->device >= 0) (void)hipSetDevice(ctx->device);
+  for (;;) {
+    hgnn_graph *g = nullptr;
+    {
+      std::unique_lock<std::mutex> lk(ctx->qm);
+      ctx->qcv.wait(lk, [&] { return ctx->stop || !ctx->queue.empty(); });
+      if (ctx->queue.empty()) return;  // stop requested and nothing left
+      g = ctx->queue.front();
+      ctx->queue.pop_front();
+    }
+    build_graph_job(ctx, g);
+  }
+}
+
+static void free_slab(hgnn_ctx *ctx, Slab &s) {
+  if (ctx->device >= 0) {
+    if (s.host) (void)hipHostFree(s.host);
+    if (s.dev) (void)hipFree(s.dev);
+  } else {
+    free(s.host);
+  }
+  s = Slab();
+}
+
+static hgnn_status wait_built(hgnn_graph *g) {
+  std::unique_lock<std::mutex> lk(g->m);
+  g->cv.wait(lk, [&] { return g->state != 0; });
+  if (g->state == 2) HGNN_FAIL((hgnn_status)g->status, "graph build failed: %s", g->err.c_str());
+  return HGNN_OK;
+}
+
+// Everything a layer call derives from (schema, graph, parameters) before launching.
+struct Plan {
+  TypeTab tt;
+  RelTab rt;
+  PtrTab pt;
+  WtTab wt;
+  LayerDev dev;
+  int H = 0, max_dim = 0, es = 4;
+  int64_t total_dst = 0;
+  size_t z_elems = 0, zroot_elems = 0, wt_elems = 0;
+  size_t saved_bytes = 0, scratch_bytes = 0;
+  size_t off_wt = 0, off_gp = 0, off_dz = 0, off_partial = 0, off_acc32 = 0;
+};
+
+static hgnn_status make_plan(hgnn_ctx *ctx, hgnn_graph *g, int32_t layer, const hgnn_layer_params *p, Plan &pl,
+                             bool need_built) {
+  if (!ctx || !g || !p) HGNN_FAIL(HGNN_EINVAL, "NULL context, graph or parameters");
+  if (layer < 0 || layer >= g->num_layers) HGNN_FAIL(HGNN_EINVAL, "layer %d outside [0,%d)", layer, g->num_layers);
+  if (ctx->agg != HGNN_AGG_MEAN || ctx->fuse != HGNN_FUSE_SUM)
+    HGNN_FAIL(HGNN_EUNSUPPORTED, "only mean aggregation with sum fusion is implemented");
+  if (!p->in_dim || !p->w_rel || !p->w_root || p->out_dim <= 0) HGNN_FAIL(HGNN_EINVAL, "incomplete layer parameters");
+  const int T = ctx->T, R = ctx->R;
+  const LayerHost &L = g->L[layer];
+  pl.es = esize(ctx->dtype);
+  const int vec = 16 / pl.es;
+  pl.H = p->out_dim;
+  std::memset(&pl.tt, 0, sizeof(pl.tt));
+  std::memset(&pl.rt, 0, sizeof(pl.rt));
+  std::memset(&pl.pt, 0, sizeof(pl.pt));
+  std::memset(&pl.wt, 0, sizeof(pl.wt));
+  pl.tt.num_types = T;
+  pl.rt.num_rels = R;
+  int64_t eo = 0;
+  for (int t = 0; t < T; ++t) {
+    if (p->in_dim[t] <= 0 || p->in_dim[t] % vec != 0)
+      HGNN_FAIL(HGNN_EUNSUPPORTED, "in_dim[%d]=%d is not a positive multiple of %d", t, p->in_dim[t], vec);
+    pl.tt.in_dim[t] = p->in_dim[t];
+    pl.tt.n_dst[t] = (int32_t)L.n_dst[t];
+    pl.tt.elem_off[t] = eo;
+    eo += L.n_src[t] * (int64_t)p->in_dim[t];
+    pl.tt.row_off[t + 1] = pl.tt.row_off[t] + (int32_t)L.n_src[t];
+    pl.tt.out_row_off[t + 1] = pl.tt.out_row_off[t] + (int32_t)L.n_dst[t];
+    if (L.n_src[t] > 0) pl.max_dim = std::max(pl.max_dim, p->in_dim[t]);
+    pl.pt.w_root[t] = p->w_root[t];
+    pl.pt.bias[t] = p->bias ? p->bias[t] : nullptr;
+  }
+  pl.tt.elem_off[T] = eo;
+  pl.total_dst = pl.tt.out_row_off[T];
+  if ((int64_t)pl.total_dst * pl.H >= (int64_t)1 << 40) HGNN_FAIL(HGNN_EOVERFLOW, "output too large");
+  size_t z = 0, w = 0;
+  for (int r = 0; r < R; ++r) {
+    const int s = ctx->rel_src[r], d = ctx->rel_dst[r];
+    if (!p->w_rel[r]) HGNN_FAIL(HGNN_EINVAL, "w_rel[%d] is NULL", r);
+    pl.rt.src[r] = (uint8_t)s;
+    pl.rt.dst[r] = (uint8_t)d;
+    pl.rt.z_off4[r] = (uint32_t)(z / 4);
+    z += (size_t)L.n_dst[d] * p->in_dim[s];
+    pl.pt.w_rel[r] = p->w_rel[r];
+    pl.wt.rel4[r] = (uint32_t)(w / 4);
+    w += (size_t)p->in_dim[s] * pl.H;
+  }
+  pl.rt.z_off4[R] = (uint32_t)(z / 4);
+  pl.z_elems = z;
+  size_t zr = z;
+  for (int t = 0; t < T; ++t) {
+    pl.rt.zroot_off4[t] = (uint32_t)(zr / 4);
+    if (p->w_root[t]) zr += (size_t)L.n_dst[t] * p->in_dim[t];
+    pl.wt.root4[t] = (uint32_t)(w / 4);
+    if (p->w_root[t]) w += (size_t)p->in_dim[t] * pl.H;
+  }
+  pl.rt.zroot_off4[T] = (uint32_t)(zr / 4);
+  pl.zroot_elems = zr - z;
+  pl.wt_elems = w;
+  if (zr / 4 >= ((size_t)1 << 32) || w / 4 >= ((size_t)1 << 32)) HGNN_FAIL(HGNN_EOVERFLOW, "work area too large");
+  pl.saved_bytes = align_up(std::max<size_t>(z, 1) * pl.es, 256);
+  size_t o = 0;
+  pl.off_wt = o;      o += align_up(std::max<size_t>(w, 1) * pl.es, 256);
+  pl.off_gp = o;      o += align_up(std::max<size_t>((size_t)pl.total_dst * pl.H, 1) * pl.es, 256);
+  pl.off_dz = o;      o += align_up(std::max<size_t>(zr, 1) * pl.es, 256);
+  pl.off_partial = o; o += align_up(std::max<size_t>((size_t)L.max_chunks * std::max(pl.max_dim, 1), 1) * 4, 256);
+  pl.off_acc32 = o;   o += align_up(std::max<size_t>((size_t)pl.total_dst * pl.H, 1) * 4, 256);
+  pl.scratch_bytes = o;
+  if (need_built) {
+    hgnn_status st = wait_built(g);
+    if (st != HGNN_OK) return st;
+    if (ctx->device < 0) HGNN_FAIL(HGNN_EUNSUPPORTED, "host-only context cannot run device work");
+    const int32_t *b = g->slab.dev;
+    LayerDev &D = pl.dev;
+    D.rel_row_off = b + L.o_rel_row_off; D.rel_edge_off = b + L.o_rel_edge_off;
+    D.rowptr = b + L.o_rowptr; D.colidx = b + L.o_colidx; D.cptr = b + L.o_cptr; D.crow = b + L.o_crow;
+    D.chunk_row = b + L.o_chunk_row; D.chunk_beg = b + L.o_chunk_beg;
+    D.long_row = b + L.o_long_row; D.long_chunk0 = b + L.o_long_chunk0;
+    D.rows = (int32_t)L.rows; D.edges = (int32_t)L.edges; D.src_rows = (int32_t)L.src_rows;
+    D.n_long = L.n_long; D.n_chunks = L.n_chunks;
+  }
+  return HGNN_OK;
+}
+
+static void fwd_tiles(const Plan &pl, SegTab &tl) {
+  std::memset(&tl, 0, sizeof(tl));
+  const int T = pl.tt.num_types, tn = (pl.H + 127) / 128;
+  for (int t = 0; t < T; ++t) tl.tile_off[t + 1] = tl.tile_off[t] + ((pl.tt.n_dst[t] + 127) / 128) * tn;
+  tl.num_segs = T;
+}
+
+}  // namespace hgnn
+
+using namespace hgnn;
+
+extern "C" {
+
+const char *hgnn_last_error(void) { return hgnn::get_error(); }
+
+hgnn_status hgnn_create(hgnn_ctx **out, const hgnn_schema *s, int device, int host_threads) {
+  if (!out || !s || !s->rel_src_type || !s->rel_dst_type) HGNN_FAIL(HGNN_EINVAL, "NULL argument");
+  *out = nullptr;
+  if (s->num_types < 1 || s->num_types > kMaxT) HGNN_FAIL(HGNN_EINVAL, "num_types %d outside [1,%d]", s->num_types, kMaxT);
+  if (s->num_rels < 1 || s->num_rels > kMaxR) HGNN_FAIL(HGNN_EINVAL, "num_rels %d outside [1,%d]", s->num_rels, kMaxR);
+  if (s->dtype != HGNN_F32 && s->dtype != HGNN_BF16) HGNN_FAIL(HGNN_EINVAL, "unknown dtype %d", s->dtype);
+  for (int r = 0; r < s->num_rels; ++r)
+    if (s->rel_src_type[r] < 0 || s->rel_src_type[r] >= s->num_types || s->rel_dst_type[r] < 0 ||
+        s->rel_dst_type[r] >= s->num_types)
+      HGNN_FAIL(HGNN_EINVAL, "relation %d has a vertex type outside [0,%d)", r, s->num_types);
+  hgnn_ctx *c = new (std::nothrow) hgnn_ctx();
+  if (!c) HGNN_FAIL(HGNN_ENOMEM, "out of host memory");
+  c->device = device;
+  c->T = s->num_types;
+  c->R = s->num_rels;
+  for (int r = 0; r < c->R; ++r) {
+    c->rel_src[r] = s->rel_src_type[r];
+    c->rel_dst[r] = s->rel_dst_type[r];
+  }
+  c->heads = s->heads < 1 ? 1 : s->heads;
+  c->agg = s->agg;
+  c->fuse = s->fuse;
+  c->dtype = s->dtype;
+  if (device >= 0) {
+    hipError_t e = hipSetDevice(device);
+    if (e == hipSuccess) e = hipStreamCreateWithFlags(&c->side, hipStreamNonBlocking);
+    if (e != hipSuccess) {
+      delete c;
+      HGNN_FAIL(HGNN_EHIP, "device %d: %s", device, hipGetErrorString(e));
+    }
+  }
+  int n = host_threads;
+  if (n <= 0) {
+    long on = sysconf(_SC_NPROCESSORS_ONLN);
+    n = (int)std::min<long>(16, std::max<long>(1, on));
+  }
+  c->pool = new ThreadPool(n);
+  c->builder = std::thread(builder_main, c);
+  *out = c;
+  return HGNN_OK;
+}
+
+void hgnn_destroy(hgnn_ctx *c) {
+  if (!c) return;
+  {
+    std::lock_guard<std::mutex> lk(c->qm);
+    c->stop = true;
+  }
+  c->qcv.notify_all();
+  if (c->builder.joinable()) c->builder.join();
+  delete c->pool;
+  if (c->device >= 0) {
+    (void)hipSetDevice(c->device);
+    (void)hipStreamSynchronize(c->side);
+  }
+  for (auto &s : c->free_slabs) free_slab(c, s);
+  for (auto e : c->free_events) (void)hipEventDestroy(e);
+  if (c->side) (void)hipStreamDestroy(c->side);
+  delete c;
+}
+
+hgnn_status hgnn_merge_features(hgnn_ctx *ctx, void *stream, const void *const *store, const int32_t *feat_dim,
+                                const int64_t *const *ids, const int64_t *n_rows, void *x_merged, int32_t *row_off,
+                                int64_t *elem_off) {
+  if (!ctx || !store || !feat_dim || !ids || !n_rows || !row_off || !elem_off) HGNN_FAIL(HGNN_EINVAL, "NULL argument");
+  const int T = ctx->T, vec = 16 / esize(ctx->dtype);
+  int64_t ro = 0, eo = 0;
+  int64_t tmp_eo[kMaxT + 1];
+  int32_t tmp_ro[kMaxT + 1];
+  for (int t = 0; t < T; ++t) {
+    if (n_rows[t] < 0) HGNN_FAIL(HGNN_EINVAL, "n_rows[%d] is negative", t);
+    if (feat_dim[t] <= 0 || feat_dim[t] % vec != 0)
+      HGNN_FAIL(HGNN_EINVAL, "feat_dim[%d]=%d is not a positive multiple of %d", t, feat_dim[t], vec);
+    if (n_rows[t] > 0 && (!store[t] || !ids[t])) HGNN_FAIL(HGNN_EINVAL, "type %d has rows but a NULL store or id list", t);
+    tmp_ro[t] = (int32_t)ro;
+    tmp_eo[t] = eo;
+    ro += n_rows[t];
+    eo += n_rows[t] * (int64_t)feat_dim[t];
+    if (ro > INT32_MAX) HGNN_FAIL(HGNN_EOVERFLOW, "more than 2^31-1 merged rows");
+  }
+  tmp_ro[T] = (int32_t)ro;
+  tmp_eo[T] = eo;
+  if (ro > 0 && !x_merged) HGNN_FAIL(HGNN_EINVAL, "x_merged is NULL");
+  if (ctx->device < 0) HGNN_FAIL(HGNN_EUNSUPPORTED, "host-only context cannot run device work");
+  hgnn_status st = launch_merge((hipStream_t)stream, ctx->dtype, T, store, feat_dim, ids, n_rows, tmp_eo, x_merged);
+  if (st != HGNN_OK) return st;
+  std::memcpy(row_off, tmp_ro, sizeof(int32_t) * (T + 1));
+  std::memcpy(elem_off, tmp_eo, sizeof(int64_t) * (T + 1));
+  return HGNN_OK;
+}
+
+hgnn_status hgnn_build_semantic_csr(hgnn_ctx *ctx, int32_t num_layers, const hgnn_coo_layer *layers, hgnn_graph **out) {
+  if (!ctx || !layers || !out) HGNN_FAIL(HGNN_EINVAL, "NULL argument");
+  *out = nullptr;
+  if (num_layers < 1 || num_layers > kMaxLayers) HGNN_FAIL(HGNN_EINVAL, "num_layers %d outside [1,%d]", num_layers, kMaxLayers);
+  const int T = ctx->T, R = ctx->R;
+  hgnn_graph *g = new (std::nothrow) hgnn_graph();
+  if (!g) HGNN_FAIL(HGNN_ENOMEM, "out of host memory");
+  g->num_layers = num_layers;
+  size_t o = 0;
+  auto take = [&](size_t n) {
+    size_t at = o;
+    o += (n + 63) / 64 * 64;  // keep every array 256-byte aligned
+    return at;
+  };
+  for (int l = 0; l < num_layers; ++l) {
+    const hgnn_coo_layer &in = layers[l];
+    LayerHost &L = g->L[l];
+    auto bad = [&](hgnn_status st) { delete g; return st; };
+    if (in.num_edges < 0 || !in.n_src || !in.n_dst) { set_error("layer %d: bad edge count or NULL n_src/n_dst", l); return bad(HGNN_EINVAL); }
+    if (in.num_edges > 0 && (!in.edge_index || (!in.edge_type && (!in.edge_id || !in.global_edge_type)))) {
+      set_error("layer %d: NULL edge arrays", l);
+      return bad(HGNN_EINVAL);
+    }
+    if (in.num_edges > INT32_MAX) { set_error("layer %d: more than 2^31-1 edges", l); return bad(HGNN_EOVERFLOW); }
+    L.in = in;
+    L.edges = in.num_edges;
+    int64_t src_rows = 0, rows = 0;
+    for (int t = 0; t < T; ++t) {
+      if (in.n_src[t] < 0 || in.n_dst[t] < 0 || in.n_dst[t] > in.n_src[t]) {
+        set_error("layer %d: type %d has n_dst=%lld, n_src=%lld (need 0 <= n_dst <= n_src)", l, t, (long long)in.n_dst[t], (long long)in.n_src[t]);
+        return bad(HGNN_EINVAL);
+      }
+      L.n_src[t] = in.n_src[t];
+      L.n_dst[t] = in.n_dst[t];
+      src_rows += in.n_src[t];
+    }
+    for (int r = 0; r < R; ++r) rows += in.n_dst[ctx->rel_dst[r]];
+    if (src_rows > INT32_MAX - 1 || rows > INT32_MAX - 1) { set_error("layer %d: more than 2^31-2 rows", l); return bad(HGNN_EOVERFLOW); }
+    L.rows = rows;
+    L.src_rows = src_rows;
+    L.max_long = (int32_t)(L.edges / kLongRow + 1);
+    L.max_chunks = (int32_t)(L.edges / kChunk + L.max_long + 1);
+    L.o_rel_row_off = take(R + 1);
+    L.o_rel_edge_off = take(R + 1);
+    L.o_rowptr = take(rows + 1);
+    L.o_colidx = take(L.edges);
+    L.o_cptr = take(src_rows + 1);
+    L.o_crow = take(L.edges);
+    L.o_chunk_row = take(L.max_chunks);
+    L.o_chunk_beg = take(L.max_chunks);
+    L.o_long_row = take(L.max_long);
+    L.o_long_chunk0 = take(L.max_long + 1);
+  }
+  const size_t dev_used = o;  // arrays below stay on the host (views only)
+  for (int l = 0; l < num_layers; ++l) {
+    g->L[l].o_perm = take(g->L[l].edges);
+    g->L[l].o_cperm = take(g->L[l].edges);
+  }
+  g->used = dev_used;
+  const size_t need = std::max<size_t>(o, 64);
+  // a pooled slab (with its two events) or a new one
+  {
+    std::lock_guard<std::mutex> lk(ctx->pm);
+    for (size_t i = 0; i < ctx->free_slabs.size(); ++i)
+      if (ctx->free_slabs[i].cap >= need) {
+        g->slab = ctx->free_slabs[i];
+        ctx->free_slabs.erase(ctx->free_slabs.begin() + i);
+        break;
+      }
+    if (!g->slab.host && !ctx->free_slabs.empty()) {  // too small: drop one so the pool does not grow forever
+      free_slab(ctx, ctx->free_slabs.back());
+      ctx->free_slabs.pop_back();
+    }
+    if (!ctx->free_events.empty()) {
+      g->ready = ctx->free_events.back();
+      ctx->free_events.pop_back();
+    }
+  }
+  if (!g->slab.host) {
+    const size_t cap = need + need / 4;
+    if (ctx->device >= 0) {
+      (void)hipSetDevice(ctx->device);
+      hipError_t e = hipHostMalloc((void **)&g->slab.host, cap * sizeof(int32_t), hipHostMallocDefault);
+      if (e == hipSuccess) e = hipMalloc((void **)&g->slab.dev, cap * sizeof(int32_t));
+      if (e != hipSuccess) {
+        free_slab(ctx, g->slab);
+        delete g;
+        HGNN_FAIL(HGNN_ENOMEM, "graph buffers (%zu bytes): %s", cap * sizeof(int32_t), hipGetErrorString(e));
+      }
+    } else {
+      g->slab.host = (int32_t *)malloc(cap * sizeof(int32_t));
+      if (!g->slab.host) {
+        delete g;
+        HGNN_FAIL(HGNN_ENOMEM, "out of host memory");
+      }
+    }
+    g->slab.cap = cap;
+  }
+  if (ctx->device >= 0 && !g->ready) {
+    hipError_t e = hipEventCreateWithFlags(&g->ready, hipEventDisableTiming);
+    if (e != hipSuccess) {
+      free_slab(ctx, g->slab);
+      delete g;
+      HGNN_FAIL(HGNN_EHIP, "hipEventCreate: %s", hipGetErrorString(e));
+    }
+  }
+  {
+    std::lock_guard<std::mutex> lk(ctx->qm);
+    ctx->queue.push_back(g);
+  }
+  ctx->qcv.notify_one();
+  *out = g;
+  return HGNN_OK;
+}
+
+hgnn_status hgnn_graph_wait(hgnn_ctx *ctx, hgnn_graph *g) {
+  if (!ctx || !g) HGNN_FAIL(HGNN_EINVAL, "NULL argument");
+  hgnn_status st = wait_built(g);
+  if (st != HGNN_OK) return st;
+  if (ctx->device >= 0) HGNN_HIP(hipEventSynchronize(g->ready));
+  return HGNN_OK;
+}
+
+hgnn_status hgnn_graph_host_view(hgnn_ctx *ctx, hgnn_graph *g, int32_t layer, hgnn_csr_view *v) {
+  if (!ctx || !g || !v) HGNN_FAIL(HGNN_EINVAL, "NULL argument");
+  if (layer < 0 || layer >= g->num_layers) HGNN_FAIL(HGNN_EINVAL, "layer %d outside [0,%d)", layer, g->num_layers);
+  hgnn_status st = wait_built(g);
+  if (st != HGNN_OK) return st;
+  const LayerHost &L = g->L[layer];
+  const int32_t *b = g->slab.host;
+  v->rows = L.rows; v->edges = L.edges; v->src_rows = L.src_rows;
+  v->rel_row_off = b + L.o_rel_row_off; v->rel_edge_off = b + L.o_rel_edge_off;
+  v->rowptr = b + L.o_rowptr; v->colidx = b + L.o_colidx; v->perm = b + L.o_perm;
+  v->cptr = b + L.o_cptr; v->crow = b + L.o_crow; v->cperm = b + L.o_cperm;
+  return HGNN_OK;
+}
+
+void hgnn_graph_release(hgnn_ctx *ctx, hgnn_graph *g) {
+  if (!ctx || !g) return;
+  {
+    std::unique_lock<std::mutex> lk(g->m);
+    g->cv.wait(lk, [&] { return g->state != 0; });
+  }
+  // the pinned block is rewritten by the next build: its upload must have left it
+  if (ctx->device >= 0 && g->state == 1) (void)hipEventSynchronize(g->ready);
+  {
+    std::lock_guard<std::mutex> lk(ctx->pm);
+    if (g->slab.host) ctx->free_slabs.push_back(g->slab);
+    if (g->ready) ctx->free_events.push_back(g->ready);
+  }
+  delete g;
+}
+
+hgnn_status hgnn_layer_workspace_bytes(hgnn_ctx *ctx, hgnn_graph *g, int32_t layer, const hgnn_layer_params *p,
+                                       size_t *saved_bytes, size_t *scratch_bytes) {
+  Plan pl;
+  hgnn_status st = make_plan(ctx, g, layer, p, pl, false);
+  if (st != HGNN_OK) return st;
+  if (saved_bytes) *saved_bytes = pl.saved_bytes;
+  if (scratch_bytes) *scratch_bytes = pl.scratch_bytes;
+  return HGNN_OK;
+}
+
+static hgnn_status fwd_common(hgnn_ctx *ctx, void *stream, hgnn_graph *g, int32_t layer, const hgnn_layer_params *p,
+                              const void *x, void *h, void *saved, size_t saved_bytes, void *scratch, size_t scratch_bytes,
+                              bool naive, int32_t *launches) {
+  Plan pl;
+  hgnn_status st = make_plan(ctx, g, layer, p, pl, true);
+  if (st != HGNN_OK) return st;
+  if (pl.total_dst > 0 && (!x || !h)) HGNN_FAIL(HGNN_EINVAL, "x_merged or h_out is NULL");
+  if (!saved || !scratch) HGNN_FAIL(HGNN_EINVAL, "NULL work area");
+  if (saved_bytes < pl.saved_bytes || scratch_bytes < pl.scratch_bytes)
+    HGNN_FAIL(HGNN_EINVAL, "work areas too small: need %zu saved, %zu scratch bytes", pl.saved_bytes, pl.scratch_bytes);
+  if (((uintptr_t)saved | (uintptr_t)scratch | (uintptr_t)x | (uintptr_t)h) & 15)
+    HGNN_FAIL(HGNN_EINVAL, "device buffers must be 16-byte aligned");
+  hipStream_t s = (hipStream_t)stream;
+  HGNN_HIP(hipStreamWaitEvent(s, g->ready, 0));
+  char *sc = (char *)scratch;
+  void *wtb = sc + pl.off_wt;
+  int n = 0;
+  SegTab tl;
+  fwd_tiles(pl, tl);
+  const int R = ctx->R, T = ctx->T;
+  if ((st = launch_transpose_weights(s, ctx->dtype, pl.tt, pl.rt, pl.pt, pl.wt, pl.H, wtb)) != HGNN_OK) return st;
+  ++n;
+  if (!naive) {
+    if ((st = launch_spmm_fwd(s, ctx->dtype, pl.dev, pl.tt, pl.rt, pl.max_dim, x, saved, 0, pl.dev.rows)) != HGNN_OK) return st;
+    if (pl.dev.rows > 0) ++n;
+    if ((st = launch_gemm_fwd(s, ctx->dtype, pl.dev, pl.tt, pl.rt, pl.pt, pl.wt, tl, pl.H, p->relu, x, saved, wtb, h, -1, nullptr)) != HGNN_OK) return st;
+    if (tl.tile_off[T] > 0) ++n;
+  } else {
+    // the un-merged launch structure: one aggregation and one projection launch per relation, one root
+    // projection and one bias/activation launch per vertex type
+    float *acc32 = (float *)(sc + pl.off_acc32);
+    if ((st = launch_fill_zero(s, acc32, (size_t)pl.total_dst * pl.H * 4)) != HGNN_OK) return st;
+    ++n;
+    const LayerHost &L = g->L[layer];
+    const int32_t *rro = g->slab.host + L.o_rel_row_off;
+    for (int r = 0; r < R; ++r) {
+      if (rro[r + 1] == rro[r]) continue;
+      if ((st = launch_spmm_fwd(s, ctx->dtype, pl.dev, pl.tt, pl.rt, pl.max_dim, x, saved, rro[r], rro[r + 1])) != HGNN_OK) return st;
+      ++n;
+      SegTab one;
+      std::memset(&one, 0, sizeof(one));
+      one.num_segs = T;
+      const int d = ctx->rel_dst[r];
+      for (int t = 0; t < T; ++t)
+        one.tile_off[t + 1] = one.tile_off[t] + (t == d ? tl.tile_off[t + 1] - tl.tile_off[t] : 0);
+      if ((st = launch_gemm_fwd(s, ctx->dtype, pl.dev, pl.tt, pl.rt, pl.pt, pl.wt, one, pl.H, 0, x, saved, wtb, h, r, acc32)) != HGNN_OK) return st;
+      ++n;
+    }
+    for (int t = 0; t < T; ++t) {
+      if (pl.tt.n_dst[t] == 0) continue;
+      if (p->w_root[t]) {
+        SegTab one;
+        std::memset(&one, 0, sizeof(one));
+        one.num_segs = T;
+        for (int u = 0; u < T; ++u)
+          one.tile_off[u + 1] = one.tile_off[u] + (u == t ? tl.tile_off[u + 1] - tl.tile_off[u] : 0);
+        if ((st = launch_gemm_fwd(s, ctx->dtype, pl.dev, pl.tt, pl.rt, pl.pt, pl.wt, one, pl.H, 0, x, saved, wtb, h, R + t, acc32)) != HGNN_OK) return st;
+        ++n;
+      }
+      if ((st = launch_bias_act(s, ctx->dtype, pl.tt, pl.pt, pl.H, p->relu, t, acc32, h)) != HGNN_OK) return st;
+      ++n;
+    }
+  }
+  if (launches) *launches = n;
+  return HGNN_OK;
+}
+
+hgnn_status hgnn_layer_fwd(hgnn_ctx *ctx, void *stream, hgnn_graph *g, int32_t layer, const hgnn_layer_params *p,
+                           const void *x_merged, void *h_out, void *saved, size_t saved_bytes, void *scratch,
+                           size_t scratch_bytes) {
+  return fwd_common(ctx, stream, g, layer, p, x_merged, h_out, saved, saved_bytes, scratch, scratch_bytes, false, nullptr);
+}
+
+hgnn_status hgnn_layer_fwd_naive(hgnn_ctx *ctx, void *stream, hgnn_graph *g, int32_t layer, const hgnn_layer_params *p,
+                                 const void *x_merged, void *h_out, void *saved, size_t saved_bytes, void *scratch,
+                                 size_t scratch_bytes, int32_t *launches) {
+  return fwd_common(ctx, stream, g, layer, p, x_merged, h_out, saved, saved_bytes, scratch, scratch_bytes, true, launches);
+}
+
+static void seg_tiles_da(hgnn_ctx *ctx, const Plan &pl, const hgnn_layer_params *p, const int32_t *rel_edge_off, SegTab &tl) {
+  std::memset(&tl, 0, sizeof(tl));
+  const int R = ctx->R, T = ctx->T;
+  tl.num_segs = R + T;
+  for (int sgi = 0; sgi < R + T; ++sgi) {
+    int cnt = 0;
+    const bool is_rel = sgi < R;
+    const int d = is_rel ? ctx->rel_dst[sgi] : sgi - R;
+    const int F = pl.tt.in_dim[is_rel ? ctx->rel_src[sgi] : d];
+    const bool live = is_rel ? rel_edge_off[sgi + 1] > rel_edge_off[sgi] : p->w_root[d] != nullptr;
+    if (live && pl.tt.n_dst[d] > 0) cnt = ((pl.tt.n_dst[d] + 127) / 128) * ((F + 127) / 128);
+    tl.tile_off[sgi + 1] = tl.tile_off[sgi] + cnt;
+  }
+}
+
+hgnn_status hgnn_layer_bwd(hgnn_ctx *ctx, void *stream, hgnn_graph *g, int32_t layer, const hgnn_layer_params *p,
+                           const void *x_merged, const void *h_out, const void *saved, const void *grad_h,
+                           void *grad_x_merged, const hgnn_layer_grads *go, void *scratch, size_t scratch_bytes) {
+  Plan pl;
+  hgnn_status st = make_plan(ctx, g, layer, p, pl, true);
+  if (st != HGNN_OK) return st;
+  if (!saved || !scratch || !go) HGNN_FAIL(HGNN_EINVAL, "NULL work area or gradient table");
+  if (pl.total_dst > 0 && (!x_merged || !grad_h || (p->relu && !h_out))) HGNN_FAIL(HGNN_EINVAL, "NULL input");
+  if (scratch_bytes < pl.scratch_bytes) HGNN_FAIL(HGNN_EINVAL, "scratch too small: need %zu bytes", pl.scratch_bytes);
+  if (((uintptr_t)saved | (uintptr_t)scratch | (uintptr_t)x_merged | (uintptr_t)grad_h | (uintptr_t)grad_x_merged) & 15)
+    HGNN_FAIL(HGNN_EINVAL, "device buffers must be 16-byte aligned");
+  const int R = ctx->R, T = ctx->T;
+  GradPtrTab gt;
+  std::memset(&gt, 0, sizeof(gt));
+  bool any_dw = false, any_db = false;
+  for (int r = 0; r < R; ++r) {
+    gt.dw_rel[r] = go->dw_rel ? go->dw_rel[r] : nullptr;
+    any_dw |= gt.dw_rel[r] != nullptr;
+  }
+  for (int t = 0; t < T; ++t) {
+    gt.dw_root[t] = (go->dw_root && p->w_root[t]) ? go->dw_root[t] : nullptr;
+    gt.dbias[t] = (go->dbias && p->bias && p->bias[t]) ? go->dbias[t] : nullptr;
+    any_dw |= gt.dw_root[t] != nullptr;
+    any_db |= gt.dbias[t] != nullptr;
+  }
+  hipStream_t s = (hipStream_t)stream;
+  HGNN_HIP(hipStreamWaitEvent(s, g->ready, 0));
+  char *sc = (char *)scratch;
+  const LayerHost &L = g->L[layer];
+  const int32_t *reo = g->slab.host + L.o_rel_edge_off;
+  if (any_dw || any_db)
+    if ((st = launch_zero_grads(s, pl.tt, pl.rt, gt, pl.H)) != HGNN_OK) return st;
+  const void *gp = grad_h;
+  if (pl.total_dst > 0 && (p->relu || any_db)) {
+    void *gpw = sc + pl.off_gp;
+    if ((st = launch_relu_bias_bwd(s, ctx->dtype, pl.tt, pl.H, p->relu, grad_h, h_out, gpw, gt)) != HGNN_OK) return st;
+    if (p->relu) gp = gpw;
+  }
+  if (any_dw && pl.total_dst > 0) {
+    // split the reduction over destination rows so that the launch has a few blocks per CU
+    SegTab tl;
+    std::memset(&tl, 0, sizeof(tl));
+    tl.num_segs = R + T;
+    int64_t base_tiles = 0;
+    for (int sgi = 0; sgi < R + T; ++sgi) {
+      const bool is_rel = sgi < R;
+      const int d = is_rel ? ctx->rel_dst[sgi] : sgi - R;
+      const int F = pl.tt.in_dim[is_rel ? ctx->rel_src[sgi] : d];
+      const bool live = (is_rel ? (reo[sgi + 1] > reo[sgi] && gt.dw_rel[sgi]) : gt.dw_root[d] != nullptr) && pl.tt.n_dst[d] > 0;
+      if (live) base_tiles += (int64_t)((F + 127) / 128) * ((pl.H + 127) / 128) * ((pl.tt.n_dst[d] + 1023) / 1024);
+    }
+    // every split covers `split_rows` destination rows (a multiple of the K tile)
+    int split_rows = 1024;
+    while (base_tiles > 0 && base_tiles < 1024 && split_rows > 128) {
+      split_rows /= 2;
+      base_tiles *= 2;
+    }
+    for (int sgi = 0; sgi < R + T; ++sgi) {
+      const bool is_rel = sgi < R;
+      const int d = is_rel ? ctx->rel_dst[sgi] : sgi - R;
+      const int F = pl.tt.in_dim[is_rel ? ctx->rel_src[sgi] : d];
+      const bool live = (is_rel ? (reo[sgi + 1] > reo[sgi] && gt.dw_rel[sgi]) : gt.dw_root[d] != nullptr) && pl.tt.n_dst[d] > 0;
+      int cnt = 0;
+      if (live) cnt = ((F + 127) / 128) * ((pl.H + 127) / 128) * ((pl.tt.n_dst[d] + split_rows - 1) / split_rows);
+      tl.tile_off[sgi + 1] = tl.tile_off[sgi] + cnt;
+    }
+    if ((st = launch_gemm_dw(s, ctx->dtype, pl.dev, pl.tt, pl.rt, gt, tl, split_rows, pl.H, x_merged, saved, gp)) != HGNN_OK) return st;
+  }
+  if (grad_x_merged && pl.dev.src_rows > 0) {
+    SegTab tl;
+    seg_tiles_da(ctx, pl, p, reo, tl);
+    void *dz = sc + pl.off_dz;
+    if ((st = launch_gemm_da(s, ctx->dtype, pl.dev, pl.tt, pl.rt, pl.pt, tl, pl.H, gp, dz)) != HGNN_OK) return st;
+    if ((st = launch_spmm_bwd(s, ctx->dtype, pl.dev, pl.tt, pl.rt, pl.pt, pl.max_dim, dz, grad_x_merged, (float *)(sc + pl.off_partial))) != HGNN_OK) return st;
+  }
+  return HGNN_OK;
+}
+
+hgnn_status hgnn_layer_launch_count(hgnn_ctx *ctx, hgnn_graph *g, int32_t layer, const hgnn_layer_params *p,
+                                    int32_t *fwd_launches, int32_t *bwd_launches) {
+  Plan pl;
+  hgnn_status st = make_plan(ctx, g, layer, p, pl, true);
+  if (st != HGNN_OK) return st;
+  if (fwd_launches) *fwd_launches = 1 + (pl.dev.rows > 0) + (pl.total_dst > 0);
+  if (bwd_launches) {
+    // zero grads, ReLU mask + bias grad, dW GEMM, dA GEMM, transposed aggregation (+ long-row pass)
+    *bwd_launches = 1 + (pl.total_dst > 0) + (pl.total_dst > 0) + (pl.dev.src_rows > 0 ? 2 + (pl.dev.n_long > 0) : 0);
+  }
+  return HGNN_OK;
+}
+
+hgnn_status hgnn_softmax_xent(hgnn_ctx *ctx, void *stream, const void *logits, const int64_t *labels, int64_t rows,
+                              int32_t classes, float *loss, void *grad_logits) {
+  if (!ctx || !loss) HGNN_FAIL(HGNN_EINVAL, "NULL argument");
+  if (rows < 0 || classes < 1) HGNN_FAIL(HGNN_EINVAL, "bad shape %lld x %d", (long long)rows, classes);
+  if (rows > 0 && (!logits || !labels || !grad_logits)) HGNN_FAIL(HGNN_EINVAL, "NULL argument");
+  if (ctx->device < 0) HGNN_FAIL(HGNN_EUNSUPPORTED, "host-only context cannot run device work");
+  return launch_xent((hipStream_t)stream, ctx->dtype, logits, labels, rows, classes, loss, grad_logits);
+}
+
+}  // extern "C"

@@ -1,0 +1,192 @@
+// Internal declarations shared by the host runtime and the kernel launchers.
+#pragma once
+#include <hip/hip_runtime.h>
+
+#include <atomic>
+#include <condition_variable>
+#include <cstdint>
+#include <cstdio>
+#include <deque>
+#include <functional>
+#include <mutex>
+#include <string>
+#include <thread>
+#include <vector>
+
+#include "../../include/hgnn.h"
+
+namespace hgnn {
+
+constexpr int kMaxT = HGNN_MAX_TYPES;
+constexpr int kMaxR = HGNN_MAX_RELS;
+constexpr int kMaxSeg = kMaxR + kMaxT;  // GEMM K-segments: one per relation, one root per type
+constexpr int kMaxLayers = 8;
+
+void set_error(const char *fmt, ...);
+#define HGNN_FAIL(code, ...)        \
+  do {                              \
+    ::hgnn::set_error(__VA_ARGS__); \
+    return (code);                  \
+  } while (0)
+#define HGNN_HIP(expr)                                                                  \
+  do {                                                                                  \
+    hipError_t e_ = (expr);                                                             \
+    if (e_ != hipSuccess) HGNN_FAIL(HGNN_EHIP, "%s: %s", #expr, hipGetErrorString(e_)); \
+  } while (0)
+
+// ---------------------------------------------------------------------------------------------
+// By-value kernel argument tables (each launch stays under the 4 KiB kernel-argument limit).
+// ---------------------------------------------------------------------------------------------
+struct TypeTab {
+  int64_t elem_off[kMaxT + 1];     // scalars of x_merged before type t (source rows)
+  int32_t in_dim[kMaxT];
+  int32_t n_dst[kMaxT];
+  int32_t row_off[kMaxT + 1];      // source rows before type t
+  int32_t out_row_off[kMaxT + 1];  // destination rows before type t
+  int32_t num_types;
+};
+struct RelTab {
+  uint32_t z_off4[kMaxR + 1];      // scalars/4 of the per-relation aggregate buffer before relation r
+  uint32_t zroot_off4[kMaxT + 1];  // scalars/4 of the root part of the dZ buffer before type t (bwd only)
+  uint8_t src[kMaxR], dst[kMaxR];
+  int32_t num_rels;
+};
+struct PtrTab {
+  const void *w_rel[kMaxR];
+  const void *w_root[kMaxT];
+  const void *bias[kMaxT];
+};
+struct GradPtrTab {
+  float *dw_rel[kMaxR];
+  float *dw_root[kMaxT];
+  float *dbias[kMaxT];
+};
+// Work list over GEMM segments (relation r -> segment r, root of type t -> segment R + t).
+struct SegTab {
+  int32_t tile_off[kMaxSeg + 1];
+  int32_t num_segs;
+};
+struct WtTab {                      // where each transposed weight lives in the scratch area
+  uint32_t rel4[kMaxR];
+  uint32_t root4[kMaxT];
+};
+
+// Device-side index arrays of one layer (all int32, inside the graph's device block).
+struct LayerDev {
+  const int32_t *rel_row_off, *rel_edge_off, *rowptr, *colidx, *cptr, *crow;
+  const int32_t *chunk_row, *chunk_beg;  // transpose rows longer than kLongRow, split in chunks of kChunk edges
+  const int32_t *long_row, *long_chunk0; // the long rows and the first chunk of each (n_long + 1 entries)
+  int32_t rows, edges, src_rows, n_long, n_chunks;
+};
+
+constexpr int kLongRow = 256;  // transpose rows above this length are reduced chunk-wise
+constexpr int kChunk = 128;
+
+struct LayerHost {
+  int64_t rows = 0, edges = 0, src_rows = 0;
+  int64_t n_src[kMaxT], n_dst[kMaxT];
+  // offsets in int32 units into the slab
+  size_t o_rel_row_off = 0, o_rel_edge_off = 0, o_rowptr = 0, o_colidx = 0, o_perm = 0, o_cptr = 0,
+         o_crow = 0, o_cperm = 0, o_chunk_row = 0, o_chunk_beg = 0, o_long_row = 0, o_long_chunk0 = 0;
+  int32_t n_long = 0, n_chunks = 0;
+  int32_t max_chunks = 0, max_long = 0;
+  hgnn_coo_layer in;  // caller's arrays (valid until the build finishes)
+};
+
+struct Slab {  // pinned host block + device block of equal capacity
+  int32_t *host = nullptr;
+  int32_t *dev = nullptr;
+  size_t cap = 0;  // in int32 units
+};
+
+class ThreadPool {
+ public:
+  explicit ThreadPool(int n);
+  ~ThreadPool();
+  int size() const { return nthreads_; }
+  // Runs fn(chunk) for chunk in [0, nchunks) on the workers plus the caller; returns when all are done.
+  void parallel_for(int nchunks, const std::function<void(int)> &fn);
+
+ private:
+  void worker();
+  void drain();
+  int nthreads_;
+  std::vector<std::thread> th_;
+  std::mutex m_;
+  std::condition_variable cv_, done_cv_;
+  const std::function<void(int)> *fn_ = nullptr;
+  int nchunks_ = 0;
+  std::atomic<int> next_{0};
+  int active_ = 0;
+  uint64_t epoch_ = 0;
+  bool stop_ = false;
+};
+
+}  // namespace hgnn
+
+struct hgnn_graph {
+  int32_t num_layers = 0;
+  hgnn::LayerHost L[hgnn::kMaxLayers];
+  hgnn::Slab slab;
+  size_t used = 0;
+  std::mutex m;
+  std::condition_variable cv;
+  int state = 0;  // 0 building, 1 uploaded (event recorded), 2 failed
+  int status = HGNN_OK;
+  std::string err;
+  hipEvent_t ready = nullptr;
+};
+
+struct hgnn_ctx {
+  int device = 0;  // < 0: host-only context (index build and views only)
+  int32_t T = 0, R = 0;
+  int32_t rel_src[hgnn::kMaxR], rel_dst[hgnn::kMaxR];
+  int32_t heads = 1, agg = 0, fuse = 0, dtype = 0;
+  hgnn::ThreadPool *pool = nullptr;
+  hipStream_t side = nullptr;
+  std::thread builder;  // processes graphs in submission order
+  std::mutex qm;
+  std::condition_variable qcv;
+  std::deque<hgnn_graph *> queue;
+  bool stop = false;
+  std::mutex pm;  // slab / event pool
+  std::vector<hgnn::Slab> free_slabs;
+  std::vector<hipEvent_t> free_events;
+  // builder-thread scratch
+  std::vector<int32_t> key, col, rowid, hist;
+};
+
+namespace hgnn {
+void build_graph_job(hgnn_ctx *ctx, hgnn_graph *g);  // host_build.cpp
+
+// ---- kernel launchers (kernels_*.hip); all enqueue on `s` and return ----
+hgnn_status launch_merge(hipStream_t s, int dtype, int T, const void *const *store, const int32_t *feat_dim,
+                         const int64_t *const *ids, const int64_t *n_rows, const int64_t *elem_off, void *out);
+// rows [row_begin,row_end) of the merged CSR: z[row] = mean of the x rows in colidx
+hgnn_status launch_spmm_fwd(hipStream_t s, int dtype, const LayerDev &L, const TypeTab &tt, const RelTab &rt,
+                            int max_dim, const void *x, void *z, int row_begin, int row_end);
+// dx[c] = sum over transpose row c of dz[crow] (+ root part for destination rows)
+hgnn_status launch_spmm_bwd(hipStream_t s, int dtype, const LayerDev &L, const TypeTab &tt, const RelTab &rt,
+                            const PtrTab &pt, int max_dim, const void *dz, void *dx, float *partial);
+hgnn_status launch_transpose_weights(hipStream_t s, int dtype, const TypeTab &tt, const RelTab &rt,
+                                     const PtrTab &pt, const WtTab &wt, int H, void *wt_buf);
+// mode 0: all segments of every type fused (bias/activation epilogue, writes h)
+// mode 1: one segment `only_seg`, accumulated into the fp32 buffer acc32 (naive launch structure)
+hgnn_status launch_gemm_fwd(hipStream_t s, int dtype, const LayerDev &L, const TypeTab &tt, const RelTab &rt,
+                            const PtrTab &pt, const WtTab &wt, const SegTab &tiles, int H, int relu,
+                            const void *x, const void *z, const void *wt_buf, void *h, int only_seg,
+                            float *acc32);
+hgnn_status launch_bias_act(hipStream_t s, int dtype, const TypeTab &tt, const PtrTab &pt, int H, int relu,
+                            int type, const float *acc32, void *h);
+hgnn_status launch_gemm_da(hipStream_t s, int dtype, const LayerDev &L, const TypeTab &tt, const RelTab &rt,
+                           const PtrTab &pt, const SegTab &tiles, int H, const void *gp, void *dz);
+hgnn_status launch_gemm_dw(hipStream_t s, int dtype, const LayerDev &L, const TypeTab &tt, const RelTab &rt,
+                           const GradPtrTab &gt, const SegTab &tiles, int split_rows, int H, const void *x,
+                           const void *z, const void *gp);
+hgnn_status launch_relu_bias_bwd(hipStream_t s, int dtype, const TypeTab &tt, int H, int relu,
+                                 const void *grad_h, const void *h, void *gp, const GradPtrTab &gt);
+hgnn_status launch_zero_grads(hipStream_t s, const TypeTab &tt, const RelTab &rt, const GradPtrTab &gt, int H);
+hgnn_status launch_fill_zero(hipStream_t s, void *p, size_t bytes);
+hgnn_status launch_xent(hipStream_t s, int dtype, const void *logits, const int64_t *labels, int64_t rows,
+                        int classes, float *loss, void *grad);
+}  // namespace hgnn

@@ -1,0 +1,68 @@
+// Storage types and 16-byte vector helpers for the device code.
+#pragma once
+#include <hip/hip_runtime.h>
+
+#include <cstdint>
+
+namespace hgnn {
+
+struct bf16 {
+  uint16_t bits;
+};
+
+__device__ __forceinline__ float bf16_bits_to_float(uint32_t b) { return __uint_as_float(b << 16); }
+// round to nearest, ties to even; NaN stays NaN
+__device__ __forceinline__ uint32_t float_to_bf16_bits(float f) {
+  uint32_t u = __float_as_uint(f);
+  if ((u & 0x7fffffffu) > 0x7f800000u) return (u >> 16) | 0x40u;
+  u += 0x7fffu + ((u >> 16) & 1u);
+  return u >> 16;
+}
+
+__device__ __forceinline__ float to_float(float v) { return v; }
+__device__ __forceinline__ float to_float(bf16 v) { return bf16_bits_to_float(v.bits); }
+template <typename T> __device__ __forceinline__ T from_float(float v);
+template <> __device__ __forceinline__ float from_float<float>(float v) { return v; }
+template <> __device__ __forceinline__ bf16 from_float<bf16>(float v) {
+  bf16 r;
+  r.bits = (uint16_t)float_to_bf16_bits(v);
+  return r;
+}
+
+// A 16-byte piece of a feature row: N scalars of T.
+template <typename T> struct Vec16;
+template <> struct Vec16<float> {
+  static constexpr int N = 4;
+  static __device__ __forceinline__ void add(float *acc, const uint4 &v) {
+    acc[0] += __uint_as_float(v.x);
+    acc[1] += __uint_as_float(v.y);
+    acc[2] += __uint_as_float(v.z);
+    acc[3] += __uint_as_float(v.w);
+  }
+  static __device__ __forceinline__ uint4 pack(const float *a) {
+    return make_uint4(__float_as_uint(a[0]), __float_as_uint(a[1]), __float_as_uint(a[2]), __float_as_uint(a[3]));
+  }
+};
+template <> struct Vec16<bf16> {
+  static constexpr int N = 8;
+  static __device__ __forceinline__ void add(float *acc, const uint4 &v) {
+    acc[0] += __uint_as_float(v.x << 16);
+    acc[1] += __uint_as_float(v.x & 0xffff0000u);
+    acc[2] += __uint_as_float(v.y << 16);
+    acc[3] += __uint_as_float(v.y & 0xffff0000u);
+    acc[4] += __uint_as_float(v.z << 16);
+    acc[5] += __uint_as_float(v.z & 0xffff0000u);
+    acc[6] += __uint_as_float(v.w << 16);
+    acc[7] += __uint_as_float(v.w & 0xffff0000u);
+  }
+  static __device__ __forceinline__ uint4 pack(const float *a) {
+    uint4 r;
+    r.x = float_to_bf16_bits(a[0]) | (float_to_bf16_bits(a[1]) << 16);
+    r.y = float_to_bf16_bits(a[2]) | (float_to_bf16_bits(a[3]) << 16);
+    r.z = float_to_bf16_bits(a[4]) | (float_to_bf16_bits(a[5]) << 16);
+    r.w = float_to_bf16_bits(a[6]) | (float_to_bf16_bits(a[7]) << 16);
+    return r;
+  }
+};
+
+}  // namespace hgnn

@@ -1,0 +1,476 @@
+// Memory-bound kernels of the layer path (gfx950): type-first feature gather, the relation-
+// segmented gather-mean over the merged CSR (paper Algorithm 1, evaluated without materialising
+// the per-edge feature copies), its transpose for the backward pass, and small element-wise
+// helpers.  Every feature row is moved in 16-byte pieces by a power-of-two group of lanes.
+#include "common.h"
+#include "device_types.h"
+
+namespace hgnn {
+
+static inline int lanes_log2_for(int max_dim, int esize) {
+  int nvec = (max_dim * esize + 15) / 16;
+  int l = 0;
+  while ((1 << l) < nvec && l < 6) ++l;
+  return l;
+}
+
+// ------------------------------------------------------------------------------------------
+// Stage 0: gather mini-batch rows from the per-type stores into the type-first buffer.
+// ------------------------------------------------------------------------------------------
+struct MergeTab {
+  const void *store[kMaxT];
+  const int64_t *ids[kMaxT];
+  int64_t elem_off[kMaxT + 1];
+  int32_t row_off[kMaxT + 1];
+  int32_t dim[kMaxT];
+  int32_t num_types;
+};
+
+__global__ void __launch_bounds__(256) merge_kernel(MergeTab mt, char *out, int esize, int lpr_log2) {
+  const int lpr = 1 << lpr_log2;
+  const int row = blockIdx.x * (256 >> lpr_log2) + (threadIdx.x >> lpr_log2);
+  const int lane = threadIdx.x & (lpr - 1);
+  if (row >= mt.row_off[mt.num_types]) return;
+  int t = 0;
+  while (row >= mt.row_off[t + 1]) ++t;
+  const int i = row - mt.row_off[t];
+  const int64_t id = mt.ids[t][i];
+  const int nvec = (mt.dim[t] * esize) >> 4;
+  const uint4 *src = reinterpret_cast<const uint4 *>(mt.store[t]) + id * nvec;
+  uint4 *dst = reinterpret_cast<uint4 *>(out + mt.elem_off[t] * esize) + (int64_t)i * nvec;
+  for (int c = lane; c < nvec; c += lpr) dst[c] = src[c];
+}
+
+hgnn_status launch_merge(hipStream_t s, int dtype, int T, const void *const *store, const int32_t *feat_dim,
+                         const int64_t *const *ids, const int64_t *n_rows, const int64_t *elem_off, void *out) {
+  MergeTab mt;
+  const int es = dtype == HGNN_BF16 ? 2 : 4;
+  int maxd = 0;
+  mt.row_off[0] = 0;
+  for (int t = 0; t < T; ++t) {
+    mt.store[t] = store[t];
+    mt.ids[t] = ids[t];
+    mt.elem_off[t] = elem_off[t];
+    mt.row_off[t + 1] = mt.row_off[t] + (int32_t)n_rows[t];
+    mt.dim[t] = feat_dim[t];
+    if (n_rows[t] > 0) maxd = std::max(maxd, feat_dim[t]);
+  }
+  mt.elem_off[T] = elem_off[T];
+  mt.num_types = T;
+  const int total = mt.row_off[T];
+  if (total == 0) return HGNN_OK;
+  const int l2 = lanes_log2_for(maxd, es);
+  const int rpb = 256 >> l2;
+  hipLaunchKernelGGL(merge_kernel, dim3((total + rpb - 1) / rpb), dim3(256), 0, s, mt, (char *)out, es, l2);
+  HGNN_HIP(hipGetLastError());
+  return HGNN_OK;
+}
+
+// ------------------------------------------------------------------------------------------
+// Stage 3: z[rho] = mean over the merged CSR row rho of the source rows of x.
+// One group of 2^lpr_log2 lanes owns one row; a lane owns 16-byte pieces of the feature row.
+// ------------------------------------------------------------------------------------------
+__device__ __forceinline__ int rel_of_row(const int32_t *rel_row_off, int R, int row) {
+  int lo = 0, hi = R;  // find r with rel_row_off[r] <= row < rel_row_off[r+1]
+  while (hi - lo > 1) {
+    const int mid = (lo + hi) >> 1;
+    if (rel_row_off[mid] <= row) lo = mid; else hi = mid;
+  }
+  return lo;
+}
+
+template <typename T>
+__global__ void __launch_bounds__(256) spmm_fwd_kernel(LayerDev L, TypeTab tt, RelTab rt, const T *__restrict__ x,
+                                                        T *__restrict__ z, int row_begin, int row_end, int lpr_log2) {
+  using V = Vec16<T>;
+  const int lpr = 1 << lpr_log2;
+  const int row = row_begin + blockIdx.x * (256 >> lpr_log2) + (threadIdx.x >> lpr_log2);
+  const int lane = threadIdx.x & (lpr - 1);
+  if (row >= row_end) return;
+  const int r = rel_of_row(L.rel_row_off, rt.num_rels, row);
+  const int st = rt.src[r];
+  const int F = tt.in_dim[st];
+  const int nvec = F / V::N;
+  const uint4 *xb = reinterpret_cast<const uint4 *>(x + tt.elem_off[st]);
+  const int rowbase = tt.row_off[st];
+  uint4 *zr = reinterpret_cast<uint4 *>(z + (int64_t)rt.z_off4[r] * 4 + (int64_t)(row - L.rel_row_off[r]) * F);
+  const int beg = L.rowptr[row], end = L.rowptr[row + 1];
+  const float inv = end > beg ? 1.0f / (float)(end - beg) : 0.0f;
+  for (int c = lane; c < nvec; c += lpr) {
+    float acc[V::N];
+#pragma unroll
+    for (int i = 0; i < V::N; ++i) acc[i] = 0.f;
+    int e = beg;
+    for (; e + 4 <= end; e += 4) {
+      const int c0 = L.colidx[e] - rowbase, c1 = L.colidx[e + 1] - rowbase;
+      const int c2 = L.colidx[e + 2] - rowbase, c3 = L.colidx[e + 3] - rowbase;
+      const uint4 v0 = xb[(int64_t)c0 * nvec + c], v1 = xb[(int64_t)c1 * nvec + c];
+      const uint4 v2 = xb[(int64_t)c2 * nvec + c], v3 = xb[(int64_t)c3 * nvec + c];
+      V::add(acc, v0); V::add(acc, v1); V::add(acc, v2); V::add(acc, v3);
+    }
+    for (; e < end; ++e) {
+      const int c0 = L.colidx[e] - rowbase;
+      V::add(acc, xb[(int64_t)c0 * nvec + c]);
+    }
+#pragma unroll
+    for (int i = 0; i < V::N; ++i) acc[i] *= inv;
+    zr[c] = V::pack(acc);
+  }
+}
+
+hgnn_status launch_spmm_fwd(hipStream_t s, int dtype, const LayerDev &L, const TypeTab &tt, const RelTab &rt,
+                            int max_dim, const void *x, void *z, int row_begin, int row_end) {
+  if (row_end <= row_begin) return HGNN_OK;
+  const int es = dtype == HGNN_BF16 ? 2 : 4;
+  const int l2 = lanes_log2_for(max_dim, es);
+  const int rpb = 256 >> l2;
+  dim3 grid((row_end - row_begin + rpb - 1) / rpb);
+  if (dtype == HGNN_BF16)
+    hipLaunchKernelGGL(spmm_fwd_kernel<bf16>, grid, dim3(256), 0, s, L, tt, rt, (const bf16 *)x, (bf16 *)z, row_begin, row_end, l2);
+  else
+    hipLaunchKernelGGL(spmm_fwd_kernel<float>, grid, dim3(256), 0, s, L, tt, rt, (const float *)x, (float *)z, row_begin, row_end, l2);
+  HGNN_HIP(hipGetLastError());
+  return HGNN_OK;
+}
+
+// ------------------------------------------------------------------------------------------
+// Backward of the aggregation: dx[c] = sum over the transpose row c of dz[crow] (dz rows arrive
+// already scaled by 1/|N_r(v)|) plus, for destination rows, the root-term gradient.
+// Rows longer than kLongRow are cut into chunks of kChunk edges: phase 0 handles the short rows
+// and writes fp32 partial sums for the chunks, phase 1 adds up the partials of each long row.
+// ------------------------------------------------------------------------------------------
+template <typename T>
+__device__ __forceinline__ const uint4 *dz_row(const T *dz, const LayerDev &L, const RelTab &rt, int F, int rho, bool uniform) {
+  if (uniform) return reinterpret_cast<const uint4 *>(dz + (int64_t)rho * F);
+  const int r = rel_of_row(L.rel_row_off, rt.num_rels, rho);
+  return reinterpret_cast<const uint4 *>(dz + (int64_t)rt.z_off4[r] * 4 + (int64_t)(rho - L.rel_row_off[r]) * F);
+}
+
+template <typename T>
+__global__ void __launch_bounds__(256) spmm_bwd_kernel(LayerDev L, TypeTab tt, RelTab rt, uint32_t root_mask,
+                                                        const T *__restrict__ dz, T *__restrict__ dx,
+                                                        float *__restrict__ partial, int max_dim, int row_blocks,
+                                                        int lpr_log2, int uniform) {
+  using V = Vec16<T>;
+  const int lpr = 1 << lpr_log2;
+  const int gpb = 256 >> lpr_log2;
+  const int lane = threadIdx.x & (lpr - 1);
+  const bool chunk_part = (int)blockIdx.x >= row_blocks;
+  const int item = (chunk_part ? (int)blockIdx.x - row_blocks : (int)blockIdx.x) * gpb + (threadIdx.x >> lpr_log2);
+  int c, beg, end;
+  if (!chunk_part) {
+    if (item >= L.src_rows) return;
+    c = item;
+    beg = L.cptr[c];
+    end = L.cptr[c + 1];
+    if (end - beg > kLongRow) return;
+  } else {
+    if (item >= L.n_chunks) return;
+    c = L.chunk_row[item];
+    beg = L.chunk_beg[item];
+    end = min(beg + kChunk, L.cptr[c + 1]);
+  }
+  int t = 0;
+  while (c >= tt.row_off[t + 1]) ++t;
+  const int F = tt.in_dim[t];
+  const int nvec = F / V::N;
+  const int cl = c - tt.row_off[t];
+  for (int q = lane; q < nvec; q += lpr) {
+    float acc[V::N];
+#pragma unroll
+    for (int i = 0; i < V::N; ++i) acc[i] = 0.f;
+    int e = beg;
+    for (; e + 4 <= end; e += 4) {
+      const uint4 *p0 = dz_row(dz, L, rt, F, L.crow[e], uniform), *p1 = dz_row(dz, L, rt, F, L.crow[e + 1], uniform);
+      const uint4 *p2 = dz_row(dz, L, rt, F, L.crow[e + 2], uniform), *p3 = dz_row(dz, L, rt, F, L.crow[e + 3], uniform);
+      const uint4 v0 = p0[q], v1 = p1[q], v2 = p2[q], v3 = p3[q];
+      V::add(acc, v0); V::add(acc, v1); V::add(acc, v2); V::add(acc, v3);
+    }
+    for (; e < end; ++e) V::add(acc, dz_row(dz, L, rt, F, L.crow[e], uniform)[q]);
+    if (!chunk_part) {
+      if (cl < tt.n_dst[t] && ((root_mask >> t) & 1u)) {
+        const T *zr = dz + (int64_t)rt.zroot_off4[t] * 4 + (int64_t)cl * F;
+        V::add(acc, reinterpret_cast<const uint4 *>(zr)[q]);
+      }
+      reinterpret_cast<uint4 *>(dx + tt.elem_off[t] + (int64_t)cl * F)[q] = V::pack(acc);
+    } else {
+      float *pp = partial + (int64_t)item * max_dim + q * V::N;
+#pragma unroll
+      for (int i = 0; i < V::N; ++i) pp[i] = acc[i];
+    }
+  }
+}
+
+template <typename T>
+__global__ void __launch_bounds__(256) spmm_bwd_long_kernel(LayerDev L, TypeTab tt, RelTab rt, uint32_t root_mask,
+                                                             const T *__restrict__ dz, T *__restrict__ dx,
+                                                             const float *__restrict__ partial, int max_dim) {
+  const int i = blockIdx.x;  // one block per long row
+  const int c = L.long_row[i];
+  int t = 0;
+  while (c >= tt.row_off[t + 1]) ++t;
+  const int F = tt.in_dim[t];
+  const int cl = c - tt.row_off[t];
+  const int j0 = L.long_chunk0[i], j1 = L.long_chunk0[i + 1];
+  const bool root = cl < tt.n_dst[t] && ((root_mask >> t) & 1u);
+  for (int f = threadIdx.x; f < F; f += blockDim.x) {
+    float acc = 0.f;
+    for (int j = j0; j < j1; ++j) acc += partial[(int64_t)j * max_dim + f];
+    if (root) acc += to_float(dz[(int64_t)rt.zroot_off4[t] * 4 + (int64_t)cl * F + f]);
+    dx[tt.elem_off[t] + (int64_t)cl * F + f] = from_float<T>(acc);
+  }
+}
+
+hgnn_status launch_spmm_bwd(hipStream_t s, int dtype, const LayerDev &L, const TypeTab &tt, const RelTab &rt,
+                            const PtrTab &pt, int max_dim, const void *dz, void *dx, float *partial) {
+  if (L.src_rows == 0) return HGNN_OK;
+  const int es = dtype == HGNN_BF16 ? 2 : 4;
+  const int l2 = lanes_log2_for(max_dim, es);
+  const int gpb = 256 >> l2;
+  const int row_blocks = (L.src_rows + gpb - 1) / gpb;
+  const int chunk_blocks = (L.n_chunks + gpb - 1) / gpb;
+  uint32_t root_mask = 0;
+  bool uniform = true;  // every relation's aggregate rows have the same width: dz row rho starts at rho * F
+  for (int t = 0; t < tt.num_types; ++t) {
+    if (pt.w_root[t]) root_mask |= 1u << t;
+    if (tt.in_dim[t] != tt.in_dim[0]) uniform = false;
+  }
+  dim3 grid(row_blocks + chunk_blocks);
+  if (dtype == HGNN_BF16)
+    hipLaunchKernelGGL(spmm_bwd_kernel<bf16>, grid, dim3(256), 0, s, L, tt, rt, root_mask, (const bf16 *)dz, (bf16 *)dx,
+                       partial, max_dim, row_blocks, l2, (int)uniform);
+  else
+    hipLaunchKernelGGL(spmm_bwd_kernel<float>, grid, dim3(256), 0, s, L, tt, rt, root_mask, (const float *)dz, (float *)dx,
+                       partial, max_dim, row_blocks, l2, (int)uniform);
+  HGNN_HIP(hipGetLastError());
+  if (L.n_long > 0) {
+    if (dtype == HGNN_BF16)
+      hipLaunchKernelGGL(spmm_bwd_long_kernel<bf16>, dim3(L.n_long), dim3(128), 0, s, L, tt, rt, root_mask, (const bf16 *)dz,
+                         (bf16 *)dx, partial, max_dim);
+    else
+      hipLaunchKernelGGL(spmm_bwd_long_kernel<float>, dim3(L.n_long), dim3(128), 0, s, L, tt, rt, root_mask, (const float *)dz,
+                         (float *)dx, partial, max_dim);
+    HGNN_HIP(hipGetLastError());
+  }
+  return HGNN_OK;
+}
+
+// ------------------------------------------------------------------------------------------
+// Weight transposes: Wt[h][f] = W[f][h] for every relation and root weight (segment = blockIdx.y).
+// ------------------------------------------------------------------------------------------
+template <typename T>
+__global__ void __launch_bounds__(256) transpose_weights_kernel(TypeTab tt, RelTab rt, PtrTab pt, WtTab wt, int H, T *out) {
+  const int seg = blockIdx.y;
+  const int R = rt.num_rels;
+  const T *w;
+  int F;
+  int64_t off;
+  if (seg < R) {
+    w = (const T *)pt.w_rel[seg];
+    F = tt.in_dim[rt.src[seg]];
+    off = (int64_t)wt.rel4[seg] * 4;
+  } else {
+    w = (const T *)pt.w_root[seg - R];
+    F = tt.in_dim[seg - R];
+    off = (int64_t)wt.root4[seg - R] * 4;
+  }
+  if (!w) return;
+  __shared__ T tile[32][33];
+  const int tiles_f = (F + 31) / 32, tiles_h = (H + 31) / 32;
+  const int tx = threadIdx.x & 31, ty = threadIdx.x >> 5;  // 32 x 8
+  for (int tl = blockIdx.x; tl < tiles_f * tiles_h; tl += gridDim.x) {
+    const int f0 = (tl / tiles_h) * 32, h0 = (tl % tiles_h) * 32;
+    for (int i = ty; i < 32; i += 8) {
+      const int f = f0 + i, h = h0 + tx;
+      if (f < F && h < H) tile[i][tx] = w[(int64_t)f * H + h];
+    }
+    __syncthreads();
+    for (int i = ty; i < 32; i += 8) {
+      const int h = h0 + i, f = f0 + tx;
+      if (f < F && h < H) out[off + (int64_t)h * F + f] = tile[tx][i];
+    }
+    __syncthreads();
+  }
+}
+
+hgnn_status launch_transpose_weights(hipStream_t s, int dtype, const TypeTab &tt, const RelTab &rt,
+                                     const PtrTab &pt, const WtTab &wt, int H, void *wt_buf) {
+  dim3 grid(16, rt.num_rels + tt.num_types);
+  if (dtype == HGNN_BF16)
+    hipLaunchKernelGGL(transpose_weights_kernel<bf16>, grid, dim3(256), 0, s, tt, rt, pt, wt, H, (bf16 *)wt_buf);
+  else
+    hipLaunchKernelGGL(transpose_weights_kernel<float>, grid, dim3(256), 0, s, tt, rt, pt, wt, H, (float *)wt_buf);
+  HGNN_HIP(hipGetLastError());
+  return HGNN_OK;
+}
+
+// ------------------------------------------------------------------------------------------
+// Backward epilogue: gp = grad_h * [h > 0] (when the layer has a ReLU) and dbias_t = column sums.
+// One block = 64 rows of one type; a thread owns columns tid, tid+256, ...
+// ------------------------------------------------------------------------------------------
+template <typename T>
+__global__ void __launch_bounds__(256) relu_bias_bwd_kernel(TypeTab tt, int H, int relu, const T *__restrict__ g,
+                                                             const T *__restrict__ h, T *__restrict__ gp, GradPtrTab gt) {
+  int b = blockIdx.x, t = 0;
+  for (;; ++t) {
+    const int nb = (tt.n_dst[t] + 63) / 64;
+    if (b < nb) break;
+    b -= nb;
+  }
+  const int r0 = tt.out_row_off[t] + b * 64;
+  const int r1 = min(r0 + 64, tt.out_row_off[t] + tt.n_dst[t]);
+  float *db = gt.dbias[t];
+  for (int c = threadIdx.x; c < H; c += 256) {
+    float sum = 0.f;
+    for (int r = r0; r < r1; ++r) {
+      const int64_t i = (int64_t)r * H + c;
+      float v = to_float(g[i]);
+      if (relu) {
+        if (!(to_float(h[i]) > 0.f)) v = 0.f;
+        gp[i] = from_float<T>(v);
+      }
+      sum += v;
+    }
+    if (db) atomicAdd(db + c, sum);
+  }
+}
+
+hgnn_status launch_relu_bias_bwd(hipStream_t s, int dtype, const TypeTab &tt, int H, int relu,
+                                 const void *grad_h, const void *h, void *gp, const GradPtrTab &gt) {
+  int blocks = 0;
+  for (int t = 0; t < tt.num_types; ++t) blocks += (tt.n_dst[t] + 63) / 64;
+  if (blocks == 0) return HGNN_OK;
+  if (dtype == HGNN_BF16)
+    hipLaunchKernelGGL(relu_bias_bwd_kernel<bf16>, dim3(blocks), dim3(256), 0, s, tt, H, relu, (const bf16 *)grad_h,
+                       (const bf16 *)h, (bf16 *)gp, gt);
+  else
+    hipLaunchKernelGGL(relu_bias_bwd_kernel<float>, dim3(blocks), dim3(256), 0, s, tt, H, relu, (const float *)grad_h,
+                       (const float *)h, (float *)gp, gt);
+  HGNN_HIP(hipGetLastError());
+  return HGNN_OK;
+}
+
+// ------------------------------------------------------------------------------------------
+__global__ void __launch_bounds__(256) zero_grads_kernel(TypeTab tt, RelTab rt, GradPtrTab gt, int H) {
+  const int seg = blockIdx.y, R = rt.num_rels;
+  float *w;
+  int64_t n;
+  if (seg < R) {
+    w = gt.dw_rel[seg];
+    n = (int64_t)tt.in_dim[rt.src[seg]] * H;
+  } else {
+    const int t = seg - R;
+    w = gt.dw_root[t];
+    n = (int64_t)tt.in_dim[t] * H;
+    float *b = gt.dbias[t];
+    if (b)
+      for (int i = blockIdx.x * 256 + threadIdx.x; i < H; i += gridDim.x * 256) b[i] = 0.f;
+  }
+  if (!w) return;
+  for (int64_t i = blockIdx.x * 256 + threadIdx.x; i < n; i += (int64_t)gridDim.x * 256) w[i] = 0.f;
+}
+
+hgnn_status launch_zero_grads(hipStream_t s, const TypeTab &tt, const RelTab &rt, const GradPtrTab &gt, int H) {
+  hipLaunchKernelGGL(zero_grads_kernel, dim3(32, rt.num_rels + tt.num_types), dim3(256), 0, s, tt, rt, gt, H);
+  HGNN_HIP(hipGetLastError());
+  return HGNN_OK;
+}
+
+__global__ void __launch_bounds__(256) fill_zero_kernel(uint4 *p, size_t n16, char *tail, size_t ntail) {
+  const uint4 z = make_uint4(0, 0, 0, 0);
+  for (size_t i = (size_t)blockIdx.x * 256 + threadIdx.x; i < n16; i += (size_t)gridDim.x * 256) p[i] = z;
+  if (blockIdx.x == 0 && threadIdx.x < ntail) tail[threadIdx.x] = 0;
+}
+
+hgnn_status launch_fill_zero(hipStream_t s, void *p, size_t bytes) {
+  if (bytes == 0) return HGNN_OK;
+  const size_t n16 = bytes / 16;
+  const int blocks = (int)std::min<size_t>(2048, (n16 + 255) / 256 + 1);
+  hipLaunchKernelGGL(fill_zero_kernel, dim3(blocks), dim3(256), 0, s, (uint4 *)p, n16, (char *)p + n16 * 16, bytes - n16 * 16);
+  HGNN_HIP(hipGetLastError());
+  return HGNN_OK;
+}
+
+// ------------------------------------------------------------------------------------------
+// Naive-structure helper: h = act(acc32 + bias) for one vertex type.
+// ------------------------------------------------------------------------------------------
+template <typename T>
+__global__ void __launch_bounds__(256) bias_act_kernel(int64_t row0, int64_t n_rows, int H, int relu, const float *bias,
+                                                        const float *__restrict__ acc, T *__restrict__ h) {
+  const int64_t n = n_rows * H;
+  for (int64_t i = (int64_t)blockIdx.x * 256 + threadIdx.x; i < n; i += (int64_t)gridDim.x * 256) {
+    float v = acc[row0 * H + i];
+    if (bias) v += bias[i % H];
+    if (relu) v = fmaxf(v, 0.f);
+    h[row0 * H + i] = from_float<T>(v);
+  }
+}
+
+template <typename T>
+__global__ void __launch_bounds__(256) bias_act_typed_kernel(int64_t row0, int64_t n_rows, int H, int relu, const T *bias,
+                                                              const float *__restrict__ acc, T *__restrict__ h) {
+  const int64_t n = n_rows * H;
+  for (int64_t i = (int64_t)blockIdx.x * 256 + threadIdx.x; i < n; i += (int64_t)gridDim.x * 256) {
+    float v = acc[row0 * H + i];
+    if (bias) v += to_float(bias[i % H]);
+    if (relu) v = fmaxf(v, 0.f);
+    h[row0 * H + i] = from_float<T>(v);
+  }
+}
+
+hgnn_status launch_bias_act(hipStream_t s, int dtype, const TypeTab &tt, const PtrTab &pt, int H, int relu,
+                            int type, const float *acc32, void *h) {
+  const int64_t n_rows = tt.n_dst[type];
+  if (n_rows == 0) return HGNN_OK;
+  const int blocks = (int)std::min<int64_t>(4096, (n_rows * H + 255) / 256);
+  if (dtype == HGNN_BF16)
+    hipLaunchKernelGGL(bias_act_typed_kernel<bf16>, dim3(blocks), dim3(256), 0, s, (int64_t)tt.out_row_off[type], n_rows, H,
+                       relu, (const bf16 *)pt.bias[type], acc32, (bf16 *)h);
+  else
+    hipLaunchKernelGGL(bias_act_typed_kernel<float>, dim3(blocks), dim3(256), 0, s, (int64_t)tt.out_row_off[type], n_rows, H,
+                       relu, (const float *)pt.bias[type], acc32, (float *)h);
+  HGNN_HIP(hipGetLastError());
+  return HGNN_OK;
+}
+
+// ------------------------------------------------------------------------------------------
+// Mean softmax cross-entropy and its gradient; one wavefront per row.
+// ------------------------------------------------------------------------------------------
+template <typename T>
+__global__ void __launch_bounds__(256) xent_kernel(const T *__restrict__ logits, const int64_t *__restrict__ labels,
+                                                    int64_t rows, int C, float *loss, T *__restrict__ grad) {
+  const int64_t row = (int64_t)blockIdx.x * 4 + (threadIdx.x >> 6);
+  const int lane = threadIdx.x & 63;
+  if (row >= rows) return;
+  const T *z = logits + row * C;
+  float m = -INFINITY;
+  for (int c = lane; c < C; c += 64) m = fmaxf(m, to_float(z[c]));
+  for (int o = 32; o > 0; o >>= 1) m = fmaxf(m, __shfl_xor(m, o));
+  float sum = 0.f;
+  for (int c = lane; c < C; c += 64) sum += __expf(to_float(z[c]) - m);
+  for (int o = 32; o > 0; o >>= 1) sum += __shfl_xor(sum, o);
+  const int lab = (int)labels[row];
+  const float inv_rows = 1.0f / (float)rows, inv_sum = 1.0f / sum;
+  for (int c = lane; c < C; c += 64) {
+    float p = __expf(to_float(z[c]) - m) * inv_sum;
+    if (c == lab) p -= 1.0f;
+    grad[row * C + c] = from_float<T>(p * inv_rows);
+  }
+  if (lane == 0) atomicAdd(loss, (logf(sum) + m - to_float(z[lab])) * inv_rows);
+}
+
+hgnn_status launch_xent(hipStream_t s, int dtype, const void *logits, const int64_t *labels, int64_t rows,
+                        int classes, float *loss, void *grad) {
+  hgnn_status st = launch_fill_zero(s, loss, sizeof(float));
+  if (st != HGNN_OK) return st;
+  if (rows == 0) return HGNN_OK;
+  dim3 grid((unsigned)((rows + 3) / 4));
+  if (dtype == HGNN_BF16)
+    hipLaunchKernelGGL(xent_kernel<bf16>, grid, dim3(256), 0, s, (const bf16 *)logits, labels, rows, classes, loss, (bf16 *)grad);
+  else
+    hipLaunchKernelGGL(xent_kernel<float>, grid, dim3(256), 0, s, (const float *)logits, labels, rows, classes, loss, (float *)grad);
+  HGNN_HIP(hipGetLastError());
+  return HGNN_OK;
+}
+
+}  // namespace hgnn

@@ -1,0 +1,139 @@
+"""Drives the C-ABI entry points over one mini-batch: buffers and call order only.
+
+Used by the GPU tests, the smoke check and bench.py.  All arithmetic happens in
+libhgnn.so; PyTorch provides device memory and the stream.
+"""
+from __future__ import annotations
+
+from typing import List, Optional
+
+import numpy as np
+import torch
+
+from . import binding as B
+
+
+def _tdtype(name):
+    return torch.bfloat16 if name == "bf16" else torch.float32
+
+
+def to_device(a: np.ndarray, dtype: str, dev) -> torch.Tensor:
+    """float32 host array -> device tensor of the path's storage type (values must already be
+    representable when dtype is bf16, so the conversion is exact)."""
+    return torch.from_numpy(np.ascontiguousarray(a, dtype=np.float32)).to(dev).to(_tdtype(dtype)).contiguous()
+
+
+class Batch:
+    def __init__(self):
+        self.ids_dev = None
+        self.graph = None
+        self.labels_dev = None
+        self.grad_out_dev = None
+        self.blocks = None
+        self.n_rows = None
+
+
+class Model:
+    """Weights, feature stores and work buffers of one configuration on one GPU."""
+
+    def __init__(self, schema, feat_dim, stores, layers, dtype="f32", loss="xent", target_type=0, device=0,
+                 host_threads=0):
+        self.dev = torch.device("cuda", device)
+        torch.cuda.set_device(self.dev)
+        self.dtype, self.loss, self.target_type = dtype, loss, target_type
+        self.T, self.R = schema.num_types, schema.num_rels
+        self.ctx = B.Context(schema.rel_src, schema.rel_dst, schema.num_types, dtype, device, host_threads)
+        self.feat_dim = list(feat_dim)
+        self.stores = [to_device(s, dtype, self.dev) for s in stores]
+        self.layers: List[B.Layer] = []
+        self.weights = []
+        for lw in layers:
+            w_rel = [to_device(w, dtype, self.dev) for w in lw.w_rel]
+            w_root = [None if w is None else to_device(w, dtype, self.dev) for w in lw.w_root]
+            bias = [None if b is None else to_device(b, dtype, self.dev) for b in lw.bias]
+            f32 = dict(device=self.dev, dtype=torch.float32)
+            dw_rel = [torch.empty(w.shape, **f32) for w in w_rel]
+            dw_root = [None if w is None else torch.empty(w.shape, **f32) for w in w_root]
+            dbias = [None if b is None else torch.empty(b.shape, **f32) for b in bias]
+            self.weights.append(dict(w_rel=w_rel, w_root=w_root, bias=bias, dw_rel=dw_rel, dw_root=dw_root, dbias=dbias))
+            self.layers.append(B.Layer(self.ctx, lw.in_dim, lw.out_dim, lw.relu, w_rel, w_root, bias, dw_rel, dw_root, dbias))
+        self.loss_dev = torch.zeros(1, device=self.dev, dtype=torch.float32)
+        self._buf = {}
+
+    def close(self):
+        self.ctx.close()
+
+    def _get(self, name, nbytes):
+        t = self._buf.get(name)
+        if t is None or t.numel() < nbytes:
+            t = torch.empty(max(nbytes, 256), device=self.dev, dtype=torch.uint8)
+            self._buf[name] = t
+        return t
+
+    def _typed(self, name, numel):
+        es = 2 if self.dtype == "bf16" else 4
+        raw = self._get(name, numel * es)
+        return raw[: numel * es].view(_tdtype(self.dtype))
+
+    # ---- host side of a step: upload ids / labels, start the semantic graph build ----
+    def prepare(self, mb, global_edge_type=None, use_edge_id=False) -> Batch:
+        b = Batch()
+        b.ids_dev = [torch.from_numpy(np.ascontiguousarray(i, dtype=np.int64)).to(self.dev) for i in mb.ids]
+        b.n_rows = [len(i) for i in mb.ids]
+        b.blocks = mb.blocks
+        b.graph = self.ctx.hgnn_build_semantic_csr(mb.blocks, global_edge_type, use_edge_id)
+        if mb.labels is not None:
+            b.labels_dev = torch.from_numpy(mb.labels.astype(np.int64)).to(self.dev)
+        if mb.grad_out is not None:
+            b.grad_out_dev = to_device(np.concatenate([g.reshape(-1) for g in mb.grad_out]), self.dtype, self.dev)
+        return b
+
+    # ---- device side of a step ----
+    def run(self, b: Batch, backward=True, naive=False, need_input_grad=True):
+        ctx, L = self.ctx, len(self.layers)
+        n0 = sum(n * f for n, f in zip(b.n_rows, self.feat_dim))
+        x = self._typed("x0", n0)
+        row_off, elem_off = ctx.hgnn_merge_features(self.stores, b.ids_dev, x, self.feat_dim)
+        xs, hs, saved = [x], [], []
+        launches = []
+        for l, lp in enumerate(self.layers):
+            blk = b.blocks[l]
+            sb, cb = ctx.hgnn_layer_workspace_bytes(b.graph, l, lp)
+            sv = self._get(f"saved{l}", sb)
+            sc = self._get("scratch", cb)
+            h = self._typed(f"h{l}", sum(blk.n_dst) * lp.out_dim)
+            if naive:
+                launches.append(ctx.hgnn_layer_fwd_naive(b.graph, l, lp, xs[-1], h, sv, sc))
+            else:
+                ctx.hgnn_layer_fwd(b.graph, l, lp, xs[-1], h, sv, sc)
+            hs.append(h); saved.append(sv); xs.append(h)
+        out = dict(x0=x, h=hs, row_off=row_off, elem_off=elem_off, launches=launches)
+        blk = b.blocks[-1]
+        H = self.layers[-1].out_dim
+        if self.loss == "xent":
+            t = self.target_type
+            r0 = sum(blk.n_dst[:t])
+            logits = hs[-1].view(-1, H)[r0: r0 + blk.n_dst[t]]
+            g = self._typed("g_last", sum(blk.n_dst) * H)
+            g.zero_()
+            gv = g.view(-1, H)[r0: r0 + blk.n_dst[t]]
+            ctx.hgnn_softmax_xent(logits, b.labels_dev, self.loss_dev, gv)
+            out["loss"] = self.loss_dev
+        else:
+            g = b.grad_out_dev
+        out["g_last"] = g
+        if not backward:
+            return out
+        dxs = [None] * L
+        for l in reversed(range(L)):
+            lp = self.layers[l]
+            blk = b.blocks[l]
+            sb, cb = ctx.hgnn_layer_workspace_bytes(b.graph, l, lp)
+            sc = self._get("scratch", cb)
+            want_dx = need_input_grad or l > 0
+            dx = self._typed(f"dx{l}", sum(n * f for n, f in zip(blk.n_src, lp.in_dim))) if want_dx else None
+            ctx.hgnn_layer_bwd(b.graph, l, lp, xs[l], hs[l], saved[l], g, dx, sc)
+            dxs[l] = dx
+            g = dx
+        out["dx"] = dxs
+        return out

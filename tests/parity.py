@@ -1,0 +1,133 @@
+"""Shared driver of the GPU parity tests: runs one configuration through the C-ABI path and
+through the CPU oracle on the same seeded inputs and compares every output."""
+import time
+
+import numpy as np
+
+from oracle import hgnn_oracle as O
+from workloads import make_config, build_graph, sample_minibatch, init_weights, bf16_round
+from workloads.synth import default_target_type
+
+TOL = {"f32": 1e-4, "bf16": 2e-2}   # relative, per tensor: max-abs over max|ref| and L2 over ||ref||
+
+
+def rel_errors(got, ref):
+    got = np.asarray(got, dtype=np.float64).ravel()
+    ref = np.asarray(ref, dtype=np.float64).ravel()
+    if ref.size == 0:
+        return 0.0, 0.0
+    d = got - ref
+    return (float(np.abs(d).max() / max(np.abs(ref).max(), 1e-30)),
+            float(np.linalg.norm(d) / max(np.linalg.norm(ref), 1e-30)))
+
+
+def prepare_inputs(index, scale=1.0, batch=None, graph=None):
+    cfg = make_config(index, scale=scale, batch=batch)
+    g = build_graph(cfg) if graph is None else graph
+    mb = sample_minibatch(cfg, g)
+    ws = init_weights(cfg, g)
+    if cfg.dtype == "bf16":                       # both sides start from the same bf16-representable values
+        g.stores = [bf16_round(s) for s in g.stores]
+        for lw in ws:
+            lw.w_rel = [bf16_round(w) for w in lw.w_rel]
+            lw.w_root = [None if w is None else bf16_round(w) for w in lw.w_root]
+            lw.bias = [None if b is None else bf16_round(b) for b in lw.bias]
+        if mb.grad_out is not None:
+            mb.grad_out = [bf16_round(x) for x in mb.grad_out]
+    return cfg, g, mb, ws
+
+
+def oracle_run(cfg, g, mb, ws):
+    sch = g.schema
+    blocks_x, _, _, flat = O.merge_features(g.stores, mb.ids)
+    sels, csrs = [], []
+    for b in mb.blocks:
+        sel = O.edge_index_select(b.edge_index, sch.num_rels, edge_id=b.edge_id, global_edge_type=g.edge_type)
+        sels.append(sel)
+        csrs.append(O.semantic_csr(sel, sch.rel_src, sch.rel_dst, b.n_src, b.n_dst))
+    layers = [dict(w_rel=lw.w_rel, w_root=lw.w_root, bias=lw.bias, relu=lw.relu) for lw in ws]
+    loss = "xent" if cfg.loss == "xent" else "dot"
+    res = O.rgcn_model_forward_backward(blocks_x, sels, sch.rel_src, sch.rel_dst, [b.n_dst for b in mb.blocks],
+                                        layers, loss, labels=mb.labels, grad_out=mb.grad_out,
+                                        target_type=mb.target_type)
+    res["csr"] = csrs
+    res["x0_flat"] = flat
+    return res
+
+
+def run_case(index, scale=1.0, batch=None, verbose=False, use_edge_id=True, check_naive=False, graph=None):
+    import torch
+    from paper_2408_08490_amd.runner import Model
+    cfg, g, mb, ws = prepare_inputs(index, scale, batch, graph)
+    sch = g.schema
+    t0 = time.time()
+    ref = oracle_run(cfg, g, mb, ws)
+    t_oracle = time.time() - t0
+    model = Model(sch, g.feat_dim, g.stores, ws, dtype=cfg.dtype, loss=("xent" if cfg.loss == "xent" else "dot"),
+                  target_type=mb.target_type)
+    bt = model.prepare(mb, g.edge_type, use_edge_id=use_edge_id)
+    out = model.run(bt)
+    torch.cuda.synchronize()
+    tol = TOL[cfg.dtype]
+    report, ok = {}, True
+
+    def chk(name, got, want, exact=False):
+        nonlocal ok
+        if exact:
+            good = np.array_equal(np.asarray(got), np.asarray(want))
+            report[name] = "exact" if good else "MISMATCH"
+        else:
+            e = rel_errors(got, want)
+            good = e[0] <= tol and e[1] <= tol
+            report[name] = (round(e[0], 7), round(e[1], 7))
+        if not good:
+            ok = False
+            if verbose:
+                print("FAIL", name, report[name], flush=True)
+
+    # integer outputs: bit-exact
+    for l in range(len(mb.blocks)):
+        view = bt.graph.host_view(l)
+        for k in ("rel_row_off", "rel_edge_off", "rowptr", "colidx", "perm", "cptr", "crow", "cperm"):
+            chk(f"L{l}.{k}", view[k], ref["csr"][l][k], exact=True)
+    want_ro = np.concatenate([[0], np.cumsum([len(i) for i in mb.ids])]).astype(np.int32)
+    want_eo = np.concatenate([[0], np.cumsum([len(i) * f for i, f in zip(mb.ids, g.feat_dim)])]).astype(np.int64)
+    chk("row_off", out["row_off"], want_ro, exact=True)
+    chk("elem_off", out["elem_off"], want_eo, exact=True)
+    chk("x_merged", out["x0"].float().cpu().numpy(), ref["x0_flat"].astype(np.float32), exact=True)
+    # floating point outputs
+    for l in range(len(ws)):
+        want = np.concatenate([h.ravel() for h in ref["h"][l]])
+        chk(f"L{l}.h", out["h"][l].float().cpu().numpy(), want)
+        gr, w = ref["grads"][l], model.weights[l]
+        for r in range(sch.num_rels):
+            chk(f"L{l}.dw_rel{r}", w["dw_rel"][r].cpu().numpy(), gr["dw_rel"][r])
+        for t in range(sch.num_types):
+            if gr["dw_root"][t] is not None:
+                chk(f"L{l}.dw_root{t}", w["dw_root"][t].cpu().numpy(), gr["dw_root"][t])
+            if gr["dbias"][t] is not None:
+                chk(f"L{l}.dbias{t}", w["dbias"][t].cpu().numpy(), gr["dbias"][t])
+        want_dx = np.concatenate([d.ravel() for d in gr["dx"]])
+        chk(f"L{l}.dx", out["dx"][l].float().cpu().numpy(), want_dx)
+    if cfg.loss == "xent":
+        chk("loss", out["loss"].cpu().numpy(), np.array([ref["loss"]]))
+    if check_naive:
+        out2 = model.run(bt, backward=False, naive=True)
+        torch.cuda.synchronize()
+        for l in range(len(ws)):
+            want = np.concatenate([h.ravel() for h in ref["h"][l]])
+            chk(f"L{l}.h_naive", out2["h"][l].float().cpu().numpy(), want)
+        report["naive_launches"] = out2["launches"]
+        report["merged_launches"] = [model.ctx.hgnn_layer_launch_count(bt.graph, l, model.layers[l])
+                                     for l in range(len(ws))]
+    bt.graph.release()
+    model.close()
+    report["ok"] = ok
+    report["oracle_s"] = round(t_oracle, 3)
+    report["sizes"] = [(sum(b.n_src), sum(b.n_dst), int(b.edge_index.shape[1])) for b in mb.blocks]
+    if verbose:
+        print({k: v for k, v in report.items() if not k.startswith("L")}, flush=True)
+        worst = sorted(((v[0], k) for k, v in report.items() if isinstance(v, tuple) and len(v) == 2
+                        and isinstance(v[0], float)), reverse=True)[:6]
+        print("worst:", worst, flush=True)
+    return report
