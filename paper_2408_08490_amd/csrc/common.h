@@ -164,7 +164,7 @@ hgnn_status launch_merge(hipStream_t s, int dtype, int T, const void *const *sto
                          const int64_t *const *ids, const int64_t *n_rows, const int64_t *elem_off, void *out);
 // rows [row_begin,row_end) of the merged CSR: z[row] = mean of the x rows in colidx
 hgnn_status launch_spmm_fwd(hipStream_t s, int dtype, const LayerDev &L, const TypeTab &tt, const RelTab &rt,
-                            int max_dim, const void *x, void *z, int row_begin, int row_end);
+                            int max_dim, const void *x, void *z, void *zlo, int row_begin, int row_end);
 // dx[c] = sum over transpose row c of dz[crow] (+ root part for destination rows)
 hgnn_status launch_spmm_bwd(hipStream_t s, int dtype, const LayerDev &L, const TypeTab &tt, const RelTab &rt,
                             const PtrTab &pt, int max_dim, const void *dz, void *dx, float *partial);
@@ -174,8 +174,8 @@ hgnn_status launch_transpose_weights(hipStream_t s, int dtype, const TypeTab &tt
 // mode 1: one segment `only_seg`, accumulated into the fp32 buffer acc32 (naive launch structure)
 hgnn_status launch_gemm_fwd(hipStream_t s, int dtype, const LayerDev &L, const TypeTab &tt, const RelTab &rt,
                             const PtrTab &pt, const WtTab &wt, const SegTab &tiles, int H, int relu,
-                            const void *x, const void *z, const void *wt_buf, void *h, int only_seg,
-                            float *acc32);
+                            const void *x, const void *z, const void *zlo, const void *wt_buf, void *h,
+                            int only_seg, float *acc32);
 hgnn_status launch_bias_act(hipStream_t s, int dtype, const TypeTab &tt, const PtrTab &pt, int H, int relu,
                             int type, const float *acc32, void *h);
 hgnn_status launch_gemm_da(hipStream_t s, int dtype, const LayerDev &L, const TypeTab &tt, const RelTab &rt,

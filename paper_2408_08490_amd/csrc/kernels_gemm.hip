@@ -188,7 +188,8 @@ __device__ __forceinline__ bool aligned16(const void *p) { return (reinterpret_c
 template <typename T>
 __global__ void __launch_bounds__(kThreads) gemm_fwd_kernel(LayerDev L, TypeTab tt, RelTab rt, PtrTab pt, WtTab wt, SegTab tiles,
                                                             int H, int relu, const T *__restrict__ x, const T *__restrict__ z,
-                                                            const T *__restrict__ wtb, T *__restrict__ h, int only_seg,
+                                                            const T *__restrict__ zlo, const T *__restrict__ wtb,
+                                                            T *__restrict__ h, int only_seg,
                                                             float *__restrict__ acc32) {
   __shared__ __attribute__((aligned(16))) T As[lds_elems<T>()];
   __shared__ __attribute__((aligned(16))) T Bs[lds_elems<T>()];
@@ -209,6 +210,9 @@ __global__ void __launch_bounds__(kThreads) gemm_fwd_kernel(LayerDev L, TypeTab 
     const int F = tt.in_dim[rt.src[r]];
     gemm_segment<T, true, true>(acc, As, Bs, z + (int64_t)rt.z_off4[r] * 4, F, M, m0, true,
                                 wtb + (int64_t)wt.rel4[r] * 4, F, H, n0, true, 0, F);
+    if (zlo)  // low-order part of the aggregate (bf16 storage): same weights, accumulated on top
+      gemm_segment<T, true, true>(acc, As, Bs, zlo + (int64_t)rt.z_off4[r] * 4, F, M, m0, true,
+                                  wtb + (int64_t)wt.rel4[r] * 4, F, H, n0, true, 0, F);
   }
   if (pt.w_root[d] && (only_seg < 0 || only_seg == R + d)) {
     const int F = tt.in_dim[d];
@@ -234,16 +238,17 @@ __global__ void __launch_bounds__(kThreads) gemm_fwd_kernel(LayerDev L, TypeTab 
 
 hgnn_status launch_gemm_fwd(hipStream_t s, int dtype, const LayerDev &L, const TypeTab &tt, const RelTab &rt,
                             const PtrTab &pt, const WtTab &wt, const SegTab &tiles, int H, int relu,
-                            const void *x, const void *z, const void *wt_buf, void *h, int only_seg, float *acc32) {
+                            const void *x, const void *z, const void *zlo, const void *wt_buf, void *h, int only_seg,
+                            float *acc32) {
   const int n = tiles.tile_off[tt.num_types];
   if (n == 0) return HGNN_OK;
   dim3 grid(round_up8(n));
   if (dtype == HGNN_BF16)
     hipLaunchKernelGGL(gemm_fwd_kernel<bf16>, grid, dim3(kThreads), 0, s, L, tt, rt, pt, wt, tiles, H, relu, (const bf16 *)x,
-                       (const bf16 *)z, (const bf16 *)wt_buf, (bf16 *)h, only_seg, acc32);
+                       (const bf16 *)z, (const bf16 *)zlo, (const bf16 *)wt_buf, (bf16 *)h, only_seg, acc32);
   else
     hipLaunchKernelGGL(gemm_fwd_kernel<float>, grid, dim3(kThreads), 0, s, L, tt, rt, pt, wt, tiles, H, relu, (const float *)x,
-                       (const float *)z, (const float *)wt_buf, (float *)h, only_seg, acc32);
+                       (const float *)z, (const float *)nullptr, (const float *)wt_buf, (float *)h, only_seg, acc32);
   HGNN_HIP(hipGetLastError());
   return HGNN_OK;
 }

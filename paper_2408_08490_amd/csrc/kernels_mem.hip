@@ -81,7 +81,8 @@ __device__ __forceinline__ int rel_of_row(const int32_t *rel_row_off, int R, int
 
 template <typename T>
 __global__ void __launch_bounds__(256) spmm_fwd_kernel(LayerDev L, TypeTab tt, RelTab rt, const T *__restrict__ x,
-                                                        T *__restrict__ z, int row_begin, int row_end, int lpr_log2) {
+                                                        T *__restrict__ z, T *__restrict__ zlo, int row_begin, int row_end,
+                                                        int lpr_log2) {
   using V = Vec16<T>;
   const int lpr = 1 << lpr_log2;
   const int row = row_begin + blockIdx.x * (256 >> lpr_log2) + (threadIdx.x >> lpr_log2);
@@ -93,7 +94,8 @@ __global__ void __launch_bounds__(256) spmm_fwd_kernel(LayerDev L, TypeTab tt, R
   const int nvec = F / V::N;
   const uint4 *xb = reinterpret_cast<const uint4 *>(x + tt.elem_off[st]);
   const int rowbase = tt.row_off[st];
-  uint4 *zr = reinterpret_cast<uint4 *>(z + (int64_t)rt.z_off4[r] * 4 + (int64_t)(row - L.rel_row_off[r]) * F);
+  const int64_t zoff = (int64_t)rt.z_off4[r] * 4 + (int64_t)(row - L.rel_row_off[r]) * F;
+  uint4 *zr = reinterpret_cast<uint4 *>(z + zoff);
   const int beg = L.rowptr[row], end = L.rowptr[row + 1];
   const float inv = end > beg ? 1.0f / (float)(end - beg) : 0.0f;
   for (int c = lane; c < nvec; c += lpr) {
@@ -114,21 +116,31 @@ __global__ void __launch_bounds__(256) spmm_fwd_kernel(LayerDev L, TypeTab tt, R
     }
 #pragma unroll
     for (int i = 0; i < V::N; ++i) acc[i] *= inv;
-    zr[c] = V::pack(acc);
+    const uint4 hi = V::pack(acc);
+    zr[c] = hi;
+    if (zlo) {  // what the storage type dropped, so that the projection can add it back
+      float back[V::N];
+#pragma unroll
+      for (int i = 0; i < V::N; ++i) back[i] = 0.f;
+      V::add(back, hi);
+#pragma unroll
+      for (int i = 0; i < V::N; ++i) back[i] = acc[i] - back[i];
+      reinterpret_cast<uint4 *>(zlo + zoff)[c] = V::pack(back);
+    }
   }
 }
 
 hgnn_status launch_spmm_fwd(hipStream_t s, int dtype, const LayerDev &L, const TypeTab &tt, const RelTab &rt,
-                            int max_dim, const void *x, void *z, int row_begin, int row_end) {
+                            int max_dim, const void *x, void *z, void *zlo, int row_begin, int row_end) {
   if (row_end <= row_begin) return HGNN_OK;
   const int es = dtype == HGNN_BF16 ? 2 : 4;
   const int l2 = lanes_log2_for(max_dim, es);
   const int rpb = 256 >> l2;
   dim3 grid((row_end - row_begin + rpb - 1) / rpb);
   if (dtype == HGNN_BF16)
-    hipLaunchKernelGGL(spmm_fwd_kernel<bf16>, grid, dim3(256), 0, s, L, tt, rt, (const bf16 *)x, (bf16 *)z, row_begin, row_end, l2);
+    hipLaunchKernelGGL(spmm_fwd_kernel<bf16>, grid, dim3(256), 0, s, L, tt, rt, (const bf16 *)x, (bf16 *)z, (bf16 *)zlo, row_begin, row_end, l2);
   else
-    hipLaunchKernelGGL(spmm_fwd_kernel<float>, grid, dim3(256), 0, s, L, tt, rt, (const float *)x, (float *)z, row_begin, row_end, l2);
+    hipLaunchKernelGGL(spmm_fwd_kernel<float>, grid, dim3(256), 0, s, L, tt, rt, (const float *)x, (float *)z, (float *)nullptr, row_begin, row_end, l2);
   HGNN_HIP(hipGetLastError());
   return HGNN_OK;
 }

@@ -130,4 +130,5 @@ def run_case(index, scale=1.0, batch=None, verbose=False, use_edge_id=True, chec
         worst = sorted(((v[0], k) for k, v in report.items() if isinstance(v, tuple) and len(v) == 2
                         and isinstance(v[0], float)), reverse=True)[:6]
         print("worst:", worst, flush=True)
+        print("all:", {k: v for k, v in report.items() if isinstance(v, tuple) and len(v) == 2}, flush=True)
     return report
