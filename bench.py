@@ -1,0 +1,247 @@
+#!/usr/bin/env python3
+"""Benchmark of the merged HGNN layer path on one MI355X.
+
+A "step" is one pass of the whole hot path over one pre-sampled synthetic mini-batch of the
+headline workload (4-type / 8-relation academic-shaped graph, bf16, hidden 512, 4096 targets,
+fanout [25, 20], 2 R-GCN layers 128 -> 512 -> 349, cross-entropy): type-first feature merge,
+host semantic-CSR build (running on host threads and uploaded on a side stream while the GPU
+works on the previous mini-batch), both layers forward, loss, both layers backward.
+
+Prints ONE JSON line.  `value` is mini-batches/s of the pipelined loop; `gpu_only_mb_per_s` is
+the same loop with the index arrays built beforehand.  `roofline` is for the dominant kernel,
+timed with HIP event pairs inside the timed loop; `cpu_baseline` is the CPU oracle on a bounded
+sample of the same workload.
+"""
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+HBM_PEAK_GBS = 8000.0
+MFMA_BF16_PEAK_TFLOPS = 2500.0
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=200)
+    ap.add_argument("--warmup", type=int, default=20)
+    ap.add_argument("--config", type=int, default=2)
+    ap.add_argument("--scale", type=float, default=1.0)
+    ap.add_argument("--batches", type=int, default=4, help="distinct pre-sampled mini-batches cycled through")
+    ap.add_argument("--probe", default="spmm_fwd", help="kernel bracketed with HIP events for the roofline object")
+    ap.add_argument("--probe-layer", type=int, default=0)
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--cpu-sample-batch", type=int, default=512)
+    ap.add_argument("--host-threads", type=int, default=0)
+    args = ap.parse_args()
+    if args.gpus != 1:
+        print("bench.py: this build runs on one GPU only (no collectives); use --gpus 1", file=sys.stderr)
+        sys.exit(2)
+
+    import numpy as np
+    import torch
+    from workloads import make_config, build_graph, sample_minibatch, init_weights, bf16_round
+    from workloads.synth import MASTER_SEED
+    from paper_2408_08490_amd.runner import Model
+    from paper_2408_08490_amd import binding as B
+
+    t0 = time.time()
+    cfg = make_config(args.config, scale=args.scale)
+    g = build_graph(cfg)
+    ws = init_weights(cfg, g)
+    if cfg.dtype == "bf16":
+        g.stores = [bf16_round(s) for s in g.stores]
+        for lw in ws:
+            lw.w_rel = [bf16_round(w) for w in lw.w_rel]
+            lw.w_root = [None if w is None else bf16_round(w) for w in lw.w_root]
+            lw.bias = [None if b is None else bf16_round(b) for b in lw.bias]
+    mbs = [sample_minibatch(cfg, g, rng=np.random.default_rng([MASTER_SEED + cfg.index, 1000 + i]))
+           for i in range(args.batches)]
+    for mb in mbs:
+        if mb.grad_out is not None and cfg.dtype == "bf16":
+            mb.grad_out = [bf16_round(x) for x in mb.grad_out]
+    t_setup = time.time() - t0
+
+    model = Model(g.schema, g.feat_dim, g.stores, ws, dtype=cfg.dtype,
+                  loss=("xent" if cfg.loss == "xent" else "dot"), target_type=mbs[0].target_type,
+                  host_threads=args.host_threads)
+    ctx = model.ctx
+
+    # inputs resident in HBM before the timed region: stores, weights, per-mini-batch id lists and labels
+    class Slot:
+        pass
+    slots = []
+    for mb in mbs:
+        s = Slot()
+        s.mb = mb
+        s.ids_dev = [torch.from_numpy(np.ascontiguousarray(i, dtype=np.int64)).to(model.dev) for i in mb.ids]
+        s.labels_dev = None if mb.labels is None else torch.from_numpy(mb.labels.astype(np.int64)).to(model.dev)
+        s.grad_out_dev = None
+        if mb.grad_out is not None:
+            from paper_2408_08490_amd.runner import to_device
+            s.grad_out_dev = to_device(np.concatenate([x.reshape(-1) for x in mb.grad_out]), cfg.dtype, model.dev)
+        slots.append(s)
+
+    from paper_2408_08490_amd.runner import Batch
+
+    def start_build(slot):
+        return ctx.hgnn_build_semantic_csr(slot.mb.blocks, g.edge_type, use_edge_id=True)
+
+    def batch_of(slot, graph):
+        b = Batch()
+        b.ids_dev, b.n_rows, b.blocks = slot.ids_dev, [len(i) for i in slot.mb.ids], slot.mb.blocks
+        b.graph, b.labels_dev, b.grad_out_dev = graph, slot.labels_dev, slot.grad_out_dev
+        return b
+
+    def pipelined(nsteps, first):
+        """Step i runs on the GPU while the host threads build the index arrays of step i+1."""
+        nxt = start_build(slots[first % len(slots)])
+        pending = []
+        for i in range(nsteps):
+            cur = nxt
+            nxt = start_build(slots[(first + i + 1) % len(slots)])
+            model.run(batch_of(slots[(first + i) % len(slots)], cur))
+            ev = torch.cuda.Event()
+            ev.record()
+            pending.append((ev, cur))
+            while len(pending) > 2:              # keep at most two finished-or-running steps alive
+                e, gr = pending.pop(0)
+                e.synchronize()
+                gr.release()
+        for e, gr in pending:
+            e.synchronize()
+            gr.release()
+        nxt.wait()
+        nxt.release()
+
+    W, K = args.warmup, args.steps
+    kid = B.KERNEL_IDS[args.probe]
+    pipelined(W, 0)
+    torch.cuda.synchronize()
+    ctx.hgnn_probe_select(kid, args.probe_layer)
+    t1 = time.perf_counter()
+    pipelined(K, W)
+    torch.cuda.synchronize()
+    t_pipe = time.perf_counter() - t1
+    probe_ms, probe_n = ctx.hgnn_probe_read()
+    ctx.hgnn_probe_select(-1, -1)
+
+    # same loop with the index arrays built beforehand (GPU work only)
+    graphs = [start_build(s) for s in slots]
+    for gr in graphs:
+        gr.wait()
+    for i in range(W):
+        model.run(batch_of(slots[i % len(slots)], graphs[i % len(slots)]))
+    torch.cuda.synchronize()
+    t2 = time.perf_counter()
+    for i in range(K):
+        model.run(batch_of(slots[i % len(slots)], graphs[i % len(slots)]))
+    torch.cuda.synchronize()
+    t_gpu = time.perf_counter() - t2
+
+    # host build alone
+    t3 = time.perf_counter()
+    nb = 20
+    for i in range(nb):
+        gr = start_build(slots[i % len(slots)])
+        gr.wait()
+        gr.release()
+    t_build = (time.perf_counter() - t3) / nb
+
+    # launches per layer: merged vs per-relation / per-type launch loop
+    launches = []
+    b0 = batch_of(slots[0], graphs[0])
+    out_naive = model.run(b0, backward=False, naive=True)
+    torch.cuda.synchronize()
+    for l in range(len(model.layers)):
+        f, bw = ctx.hgnn_layer_launch_count(graphs[0], l, model.layers[l])
+        launches.append(dict(layer=l, merged_fwd=f, merged_bwd=bw, naive_fwd=out_naive["launches"][l]))
+
+    # algorithmic traffic / flops of the probed kernel, from the first mini-batch's shapes
+    es = 2 if cfg.dtype == "bf16" else 4
+    mb = slots[0].mb
+    blk = mb.blocks[args.probe_layer]
+    sch = g.schema
+    lw = ws[args.probe_layer]
+    view = graphs[0].host_view(args.probe_layer)
+    rows, E = int(view["rows"]), int(view["edges"])
+    roof = None
+    if args.probe == "spmm_fwd":
+        # each referenced source row once per relation segment + index arrays + both output planes
+        uniq = 0
+        for r in range(sch.num_rels):
+            a, b_ = view["rel_edge_off"][r], view["rel_edge_off"][r + 1]
+            uniq += len(np.unique(view["colidx"][a:b_])) * lw.in_dim[sch.rel_src[r]]
+        zel = sum(blk.n_dst[sch.rel_dst[r]] * lw.in_dim[sch.rel_src[r]] for r in range(sch.num_rels))
+        nplanes = 2 if cfg.dtype == "bf16" else 1
+        alg_bytes = uniq * es + 4 * E + 4 * (rows + 1) + zel * es * nplanes
+        req_bytes = alg_bytes + (sum(lw.in_dim[sch.rel_src[r]] * (view["rel_edge_off"][r + 1] - view["rel_edge_off"][r])
+                                     for r in range(sch.num_rels)) - uniq) * es
+        avg_ms = probe_ms / max(probe_n, 1)
+        ach = alg_bytes / (avg_ms * 1e-3) / 1e9 if avg_ms > 0 else 0.0
+        roof = dict(kernel="spmm_fwd_kernel (layer %d)" % args.probe_layer, bound="hbm", achieved=round(ach, 1),
+                    peak=HBM_PEAK_GBS, unit="GB/s", frac=round(ach / HBM_PEAK_GBS, 4), traffic=None,
+                    algorithmic_bytes=int(alg_bytes), requested_bytes=int(req_bytes),
+                    avg_kernel_us=round(avg_ms * 1e3, 2), launches_timed=probe_n)
+    elif args.probe in ("gemm_fwd", "gemm_dw", "gemm_da"):
+        flops = 0
+        for t in range(sch.num_types):
+            k = sum(lw.in_dim[sch.rel_src[r]] for r in range(sch.num_rels)
+                    if sch.rel_dst[r] == t and view["rel_edge_off"][r + 1] > view["rel_edge_off"][r])
+            k += lw.in_dim[t] if lw.w_root[t] is not None else 0
+            flops += 2 * blk.n_dst[t] * k * lw.out_dim
+        avg_ms = probe_ms / max(probe_n, 1)
+        ach = flops / (avg_ms * 1e-3) / 1e12 if avg_ms > 0 else 0.0
+        peak = MFMA_BF16_PEAK_TFLOPS if cfg.dtype == "bf16" else 157.3
+        roof = dict(kernel="%s_kernel (layer %d)" % (args.probe, args.probe_layer), bound="mfma", achieved=round(ach, 1),
+                    peak=peak, unit="TFLOP/s", frac=round(ach / peak, 4), traffic=None, algorithmic_flops=int(flops),
+                    avg_kernel_us=round(avg_ms * 1e3, 2), launches_timed=probe_n)
+    else:
+        avg_ms = probe_ms / max(probe_n, 1)
+        roof = dict(kernel=args.probe, bound="hbm", achieved=None, peak=HBM_PEAK_GBS, unit="GB/s", frac=None, traffic=None,
+                    avg_kernel_us=round(avg_ms * 1e3, 2), launches_timed=probe_n)
+
+    for gr in graphs:
+        gr.release()
+
+    cpu = None
+    if not args.no_cpu_baseline:
+        from tests.parity import oracle_run
+        import copy
+        cfg_s = make_config(args.config, scale=args.scale, batch=args.cpu_sample_batch)
+        mb_s = sample_minibatch(cfg_s, g, rng=np.random.default_rng([MASTER_SEED + cfg.index, 999]))
+        if mb_s.grad_out is not None and cfg.dtype == "bf16":
+            mb_s.grad_out = [bf16_round(x) for x in mb_s.grad_out]
+        tc = time.perf_counter()
+        oracle_run(cfg_s, g, mb_s, ws)
+        t_cpu = time.perf_counter() - tc
+        frac = args.cpu_sample_batch / cfg.batch
+        cpu = dict(value=round(frac / t_cpu, 5), unit="mini-batches/s", cores=os.cpu_count() if False else len(os.sched_getaffinity(0)),
+                   kind="oracle",
+                   sample="one mini-batch of %d targets (1/%d of the workload's %d), full fwd+bwd incl. index build, "
+                          "%.1f s of numpy fp64; rate scaled by the target fraction" %
+                          (args.cpu_sample_batch, round(1 / frac), cfg.batch, t_cpu))
+
+    sizes = [dict(src_rows=sum(b.n_src), dst_rows=sum(b.n_dst), edges=int(b.edge_index.shape[1])) for b in mb.blocks]
+    line = dict(
+        metric="HGNN layer fwd+bwd mini-batches/s (1 GPU)", value=round(K / t_pipe, 2), unit="mini-batches/s",
+        n_gpus=1, steps=K, warmup=W, ms_per_step=round(1e3 * t_pipe / K, 4), higher_is_better=True, scaling="weak",
+        vs_baseline=None, dtype=cfg.dtype, data="synthetic",
+        config=dict(workload="configs[%d] %s: 4 types / 8 relations, %d targets, fanout %s, layers %s, scale %.3g" %
+                    (cfg.index, cfg.name, cfg.batch, cfg.fanouts[::-1], [g.feat_dim[0]] + cfg.layer_out, cfg.scale),
+                    minibatch_sizes=sizes, distinct_minibatches=len(slots)),
+        gpu_only_mb_per_s=round(K / t_gpu, 2), gpu_only_ms_per_step=round(1e3 * t_gpu / K, 4),
+        host_build_ms=round(1e3 * t_build, 3), launches_per_layer=launches,
+        roofline=roof, cpu_baseline=cpu, setup_s=round(t_setup, 1))
+    print(json.dumps(line))
+    model.close()
+
+
+if __name__ == "__main__":
+    main()

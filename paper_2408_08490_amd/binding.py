@@ -79,6 +79,8 @@ def _load():
                            vp, C.c_size_t],
         "hgnn_layer_launch_count": [vp, vp, i32, C.POINTER(LayerParams), C.POINTER(i32), C.POINTER(i32)],
         "hgnn_softmax_xent": [vp, vp, vp, vp, i64, i32, vp, vp],
+        "hgnn_probe_select": [vp, i32, i32],
+        "hgnn_probe_read": [vp, C.POINTER(C.c_double), C.POINTER(i64)],
     }
     for name, args in sig.items():
         f = getattr(lib, name)
@@ -95,7 +97,10 @@ lib = _load()
 EXPORTS = ["hgnn_create", "hgnn_destroy", "hgnn_last_error", "hgnn_merge_features", "hgnn_build_semantic_csr",
            "hgnn_graph_wait", "hgnn_graph_host_view", "hgnn_graph_release", "hgnn_layer_workspace_bytes",
            "hgnn_layer_fwd", "hgnn_layer_bwd", "hgnn_layer_fwd_naive", "hgnn_layer_launch_count",
-           "hgnn_softmax_xent"]
+           "hgnn_softmax_xent", "hgnn_probe_select", "hgnn_probe_read"]
+
+KERNEL_IDS = dict(merge=0, transpose_w=1, spmm_fwd=2, gemm_fwd=3, zero_grads=4, relu_bias_bwd=5, gemm_dw=6,
+                  gemm_da=7, spmm_bwd=8, xent=9)
 
 
 def _check(st):
@@ -263,6 +268,14 @@ class Context:
         a, b = C.c_int32(), C.c_int32()
         _check(lib.hgnn_layer_launch_count(self.handle, graph.handle, layer, C.byref(lp.params), C.byref(a), C.byref(b)))
         return a.value, b.value
+
+    def hgnn_probe_select(self, kernel: int, layer: int = -1):
+        _check(lib.hgnn_probe_select(self.handle, kernel, layer))
+
+    def hgnn_probe_read(self):
+        ms, n = C.c_double(), C.c_int64()
+        _check(lib.hgnn_probe_read(self.handle, C.byref(ms), C.byref(n)))
+        return ms.value, n.value
 
     def hgnn_softmax_xent(self, logits, labels, loss, grad_logits):
         rows, classes = logits.shape

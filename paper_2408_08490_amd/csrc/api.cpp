@@ -142,6 +142,28 @@ static hgnn_status make_plan(hgnn_ctx *ctx, hgnn_graph *g, int32_t layer, const 
   return HGNN_OK;
 }
 
+// Records an event pair around the launches made while it is alive, if the probe selects them.
+struct Probe {
+  hgnn_ctx *c;
+  hipStream_t s;
+  hipEvent_t stop = nullptr;
+  Probe(hgnn_ctx *ctx, hipStream_t st, int kernel, int layer) : c(ctx), s(st) {
+    if (c->probe_kernel != kernel || (c->probe_layer >= 0 && c->probe_layer != layer)) return;
+    if (c->probe_used == c->probe_events.size()) {
+      hipEvent_t a, b;
+      if (hipEventCreate(&a) != hipSuccess) return;
+      if (hipEventCreate(&b) != hipSuccess) { (void)hipEventDestroy(a); return; }
+      c->probe_events.emplace_back(a, b);
+    }
+    auto &pr = c->probe_events[c->probe_used++];
+    (void)hipEventRecord(pr.first, s);
+    stop = pr.second;
+  }
+  ~Probe() {
+    if (stop) (void)hipEventRecord(stop, s);
+  }
+};
+
 static void fwd_tiles(const Plan &pl, SegTab &tl) {
   std::memset(&tl, 0, sizeof(tl));
   const int T = pl.tt.num_types, tn = (pl.H + 127) / 128;
@@ -214,6 +236,10 @@ void hgnn_destroy(hgnn_ctx *c) {
   }
   for (auto &s : c->free_slabs) free_slab(c, s);
   for (auto e : c->free_events) (void)hipEventDestroy(e);
+  for (auto &pr : c->probe_events) {
+    (void)hipEventDestroy(pr.first);
+    (void)hipEventDestroy(pr.second);
+  }
   if (c->side) (void)hipStreamDestroy(c->side);
   delete c;
 }
@@ -241,7 +267,11 @@ hgnn_status hgnn_merge_features(hgnn_ctx *ctx, void *stream, const void *const *
   tmp_eo[T] = eo;
   if (ro > 0 && !x_merged) HGNN_FAIL(HGNN_EINVAL, "x_merged is NULL");
   if (ctx->device < 0) HGNN_FAIL(HGNN_EUNSUPPORTED, "host-only context cannot run device work");
-  hgnn_status st = launch_merge((hipStream_t)stream, ctx->dtype, T, store, feat_dim, ids, n_rows, tmp_eo, x_merged);
+  hgnn_status st;
+  {
+    Probe pb(ctx, (hipStream_t)stream, HGNN_K_MERGE, -1);
+    st = launch_merge((hipStream_t)stream, ctx->dtype, T, store, feat_dim, ids, n_rows, tmp_eo, x_merged);
+  }
   if (st != HGNN_OK) return st;
   std::memcpy(row_off, tmp_ro, sizeof(int32_t) * (T + 1));
   std::memcpy(elem_off, tmp_eo, sizeof(int64_t) * (T + 1));
@@ -434,12 +464,21 @@ static hgnn_status fwd_common(hgnn_ctx *ctx, void *stream, hgnn_graph *g, int32_
   SegTab tl;
   fwd_tiles(pl, tl);
   const int R = ctx->R, T = ctx->T;
-  if ((st = launch_transpose_weights(s, ctx->dtype, pl.tt, pl.rt, pl.pt, pl.wt, pl.H, wtb)) != HGNN_OK) return st;
+  {
+    Probe pb(ctx, s, HGNN_K_TRANSPOSE_W, layer);
+    if ((st = launch_transpose_weights(s, ctx->dtype, pl.tt, pl.rt, pl.pt, pl.wt, pl.H, wtb)) != HGNN_OK) return st;
+  }
   ++n;
   if (!naive) {
-    if ((st = launch_spmm_fwd(s, ctx->dtype, pl.dev, pl.tt, pl.rt, pl.max_dim, x, saved, zlo, 0, pl.dev.rows)) != HGNN_OK) return st;
+    {
+      Probe pb(ctx, s, HGNN_K_SPMM_FWD, layer);
+      if ((st = launch_spmm_fwd(s, ctx->dtype, pl.dev, pl.tt, pl.rt, pl.max_dim, x, saved, zlo, 0, pl.dev.rows)) != HGNN_OK) return st;
+    }
     if (pl.dev.rows > 0) ++n;
-    if ((st = launch_gemm_fwd(s, ctx->dtype, pl.dev, pl.tt, pl.rt, pl.pt, pl.wt, tl, pl.H, p->relu, x, saved, zlo, wtb, h, -1, nullptr)) != HGNN_OK) return st;
+    {
+      Probe pb(ctx, s, HGNN_K_GEMM_FWD, layer);
+      if ((st = launch_gemm_fwd(s, ctx->dtype, pl.dev, pl.tt, pl.rt, pl.pt, pl.wt, tl, pl.H, p->relu, x, saved, zlo, wtb, h, -1, nullptr)) != HGNN_OK) return st;
+    }
     if (tl.tile_off[T] > 0) ++n;
   } else {
     // the un-merged launch structure: one aggregation and one projection launch per relation, one root
@@ -538,11 +577,14 @@ hgnn_status hgnn_layer_bwd(hgnn_ctx *ctx, void *stream, hgnn_graph *g, int32_t l
   char *sc = (char *)scratch;
   const LayerHost &L = g->L[layer];
   const int32_t *reo = g->slab.host + L.o_rel_edge_off;
-  if (any_dw || any_db)
+  if (any_dw || any_db) {
+    Probe pb(ctx, s, HGNN_K_ZERO_GRADS, layer);
     if ((st = launch_zero_grads(s, pl.tt, pl.rt, gt, pl.H)) != HGNN_OK) return st;
+  }
   const void *gp = grad_h;
   if (pl.total_dst > 0 && (p->relu || any_db)) {
     void *gpw = sc + pl.off_gp;
+    Probe pb(ctx, s, HGNN_K_RELU_BIAS_BWD, layer);
     if ((st = launch_relu_bias_bwd(s, ctx->dtype, pl.tt, pl.H, p->relu, grad_h, h_out, gpw, gt)) != HGNN_OK) return st;
     if (p->relu) gp = gpw;
   }
@@ -574,13 +616,18 @@ hgnn_status hgnn_layer_bwd(hgnn_ctx *ctx, void *stream, hgnn_graph *g, int32_t l
       if (live) cnt = ((F + 127) / 128) * ((pl.H + 127) / 128) * ((pl.tt.n_dst[d] + split_rows - 1) / split_rows);
       tl.tile_off[sgi + 1] = tl.tile_off[sgi] + cnt;
     }
+    Probe pb(ctx, s, HGNN_K_GEMM_DW, layer);
     if ((st = launch_gemm_dw(s, ctx->dtype, pl.dev, pl.tt, pl.rt, gt, tl, split_rows, pl.H, x_merged, saved, gp)) != HGNN_OK) return st;
   }
   if (grad_x_merged && pl.dev.src_rows > 0) {
     SegTab tl;
     seg_tiles_da(ctx, pl, p, reo, tl);
     void *dz = sc + pl.off_dz;
-    if ((st = launch_gemm_da(s, ctx->dtype, pl.dev, pl.tt, pl.rt, pl.pt, tl, pl.H, gp, dz)) != HGNN_OK) return st;
+    {
+      Probe pb(ctx, s, HGNN_K_GEMM_DA, layer);
+      if ((st = launch_gemm_da(s, ctx->dtype, pl.dev, pl.tt, pl.rt, pl.pt, tl, pl.H, gp, dz)) != HGNN_OK) return st;
+    }
+    Probe pb(ctx, s, HGNN_K_SPMM_BWD, layer);
     if ((st = launch_spmm_bwd(s, ctx->dtype, pl.dev, pl.tt, pl.rt, pl.pt, pl.max_dim, dz, grad_x_merged, (float *)(sc + pl.off_partial))) != HGNN_OK) return st;
   }
   return HGNN_OK;
@@ -605,7 +652,31 @@ hgnn_status hgnn_softmax_xent(hgnn_ctx *ctx, void *stream, const void *logits, c
   if (rows < 0 || classes < 1) HGNN_FAIL(HGNN_EINVAL, "bad shape %lld x %d", (long long)rows, classes);
   if (rows > 0 && (!logits || !labels || !grad_logits)) HGNN_FAIL(HGNN_EINVAL, "NULL argument");
   if (ctx->device < 0) HGNN_FAIL(HGNN_EUNSUPPORTED, "host-only context cannot run device work");
+  Probe pb(ctx, (hipStream_t)stream, HGNN_K_XENT, -1);
   return launch_xent((hipStream_t)stream, ctx->dtype, logits, labels, rows, classes, loss, grad_logits);
+}
+
+hgnn_status hgnn_probe_select(hgnn_ctx *ctx, int32_t kernel, int32_t layer) {
+  if (!ctx) HGNN_FAIL(HGNN_EINVAL, "NULL context");
+  if (kernel > HGNN_K_XENT) HGNN_FAIL(HGNN_EINVAL, "unknown kernel id %d", kernel);
+  ctx->probe_kernel = kernel < 0 ? -1 : kernel;
+  ctx->probe_layer = layer;
+  ctx->probe_used = 0;
+  return HGNN_OK;
+}
+
+hgnn_status hgnn_probe_read(hgnn_ctx *ctx, double *total_ms, int64_t *launches) {
+  if (!ctx || !total_ms || !launches) HGNN_FAIL(HGNN_EINVAL, "NULL argument");
+  double sum = 0;
+  for (size_t i = 0; i < ctx->probe_used; ++i) {
+    float ms = 0;
+    HGNN_HIP(hipEventSynchronize(ctx->probe_events[i].second));
+    HGNN_HIP(hipEventElapsedTime(&ms, ctx->probe_events[i].first, ctx->probe_events[i].second));
+    sum += ms;
+  }
+  *total_ms = sum;
+  *launches = (int64_t)ctx->probe_used;
+  return HGNN_OK;
 }
 
 }  // extern "C"

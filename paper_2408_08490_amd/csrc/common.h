@@ -154,6 +154,10 @@ struct hgnn_ctx {
   std::vector<hipEvent_t> free_events;
   // builder-thread scratch
   std::vector<int32_t> key, col, rowid, hist;
+  // kernel probe (measurement aid)
+  int probe_kernel = -1, probe_layer = -1;
+  std::vector<std::pair<hipEvent_t, hipEvent_t>> probe_events;
+  size_t probe_used = 0;
 };
 
 namespace hgnn {

@@ -1,0 +1,185 @@
+"""CPU-only checks of the C-ABI library: it loads, exports every symbol the header declares,
+validates arguments, and its multi-threaded host semantic-graph build (which needs no GPU when
+the context is created with device < 0) is bit-exact against the oracle."""
+import ctypes as C
+import os
+import re
+
+import numpy as np
+import pytest
+
+from oracle import hgnn_oracle as O
+from workloads import make_config, build_graph, sample_minibatch
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+@pytest.fixture(scope="module")
+def B():
+    lib = os.path.join(ROOT, "paper_2408_08490_amd", "libhgnn.so")
+    if not os.path.exists(lib):                      # build only when nothing has been built
+        from paper_2408_08490_amd.build import build_library
+        build_library(verbose=False)
+    from paper_2408_08490_amd import binding
+    return binding
+
+
+def test_exports_match_header(B):
+    hdr = open(os.path.join(ROOT, "include", "hgnn.h")).read()
+    declared = set(re.findall(r"^(?:hgnn_status|void|const char \*)\s*(hgnn_[a-z_0-9]+)\s*\(", hdr, flags=re.M))
+    assert declared, "no declarations found"
+    for name in declared:
+        assert hasattr(B.lib, name), f"{name} declared in include/hgnn.h but not exported"
+    assert set(B.EXPORTS) == declared
+
+
+def _host_ctx(B, sch, dtype="f32", threads=4):
+    return B.Context(sch.rel_src, sch.rel_dst, sch.num_types, dtype, device=-1, host_threads=threads)
+
+
+@pytest.mark.parametrize("index,scale,threads", [(0, 1.0, 1), (0, 1.0, 4), (2, 0.02, 8), (3, 0.003, 3)])
+@pytest.mark.parametrize("use_edge_id", [False, True])
+def test_host_build_bit_exact(B, index, scale, threads, use_edge_id):
+    cfg = make_config(index, scale=scale, batch=96)
+    g = build_graph(cfg)
+    mb = sample_minibatch(cfg, g)
+    ctx = _host_ctx(B, g.schema, threads=threads)
+    gr = ctx.hgnn_build_semantic_csr(mb.blocks, g.edge_type, use_edge_id=use_edge_id)
+    gr.wait()
+    for l, b in enumerate(mb.blocks):
+        sel = O.edge_index_select(b.edge_index, g.schema.num_rels, edge_type=b.edge_type)
+        ref = O.semantic_csr(sel, g.schema.rel_src, g.schema.rel_dst, b.n_src, b.n_dst)
+        v = gr.host_view(l)
+        assert v["rows"] == ref["rowptr"].size - 1 and v["edges"] == ref["colidx"].size
+        for k in ("rel_row_off", "rel_edge_off", "rowptr", "colidx", "perm", "cptr", "crow", "cperm"):
+            assert np.array_equal(v[k], ref[k]), (l, k)
+    gr.release()
+    ctx.close()
+
+
+def test_host_build_int32_indices_and_repeat(B):
+    cfg = make_config(0)
+    g = build_graph(cfg)
+    mb = sample_minibatch(cfg, g)
+    ctx = _host_ctx(B, g.schema)
+    b = mb.blocks[0]
+
+    class Blk:
+        pass
+    b32 = Blk()
+    b32.n_src, b32.n_dst, b32.edge_type = b.n_src, b.n_dst, b.edge_type
+    b32.edge_index = b.edge_index.astype(np.int32)
+    views = []
+    for _ in range(3):                              # pooled buffers are reused: results must not change
+        gr = ctx.hgnn_build_semantic_csr([b32])
+        views.append(gr.host_view(0))
+        gr.release()
+    gr = ctx.hgnn_build_semantic_csr([b])
+    v64 = gr.host_view(0)
+    gr.release()
+    for v in views:
+        for k in ("rowptr", "colidx", "perm", "cptr", "crow", "cperm"):
+            assert np.array_equal(v[k], v64[k])
+    ctx.close()
+
+
+def test_empty_layer_and_empty_relation(B):
+    from workloads import Schema
+
+    class Blk:
+        pass
+    sch = Schema(2, [0, 1], [1, 1])
+    ctx = _host_ctx(B, sch)
+    b = Blk()
+    b.n_src, b.n_dst = [3, 2], [0, 2]
+    b.edge_index = np.zeros((2, 0), dtype=np.int64)
+    b.edge_type = np.zeros(0, dtype=np.int32)
+    gr = ctx.hgnn_build_semantic_csr([b])
+    v = gr.host_view(0)
+    assert v["rows"] == 4 and v["edges"] == 0
+    assert v["rowptr"].tolist() == [0] * 5 and v["cptr"].tolist() == [0] * 6
+    assert v["rel_row_off"].tolist() == [0, 2, 4]
+    gr.release()
+    ctx.close()
+
+
+def _bad_block(mb, **kw):
+    class Blk:
+        pass
+    b = Blk()
+    src = mb.blocks[0]
+    b.n_src, b.n_dst = list(src.n_src), list(src.n_dst)
+    b.edge_index, b.edge_type = src.edge_index.copy(), src.edge_type.copy()
+    for k, v in kw.items():
+        setattr(b, k, v)
+    return b
+
+
+def test_validation_errors(B):
+    cfg = make_config(0)
+    g = build_graph(cfg)
+    mb = sample_minibatch(cfg, g)
+    ctx = _host_ctx(B, g.schema)
+    # edge type out of range
+    et = mb.blocks[0].edge_type.copy(); et[5] = 7
+    gr = ctx.hgnn_build_semantic_csr([_bad_block(mb, edge_type=et)])
+    with pytest.raises(B.HgnnError) as e:
+        gr.wait()
+    assert e.value.status == -1 and "type" in str(e.value)
+    gr.release()
+    # source index out of range
+    ei = mb.blocks[0].edge_index.copy(); ei[0, 3] = 10 ** 6
+    gr = ctx.hgnn_build_semantic_csr([_bad_block(mb, edge_index=ei)])
+    with pytest.raises(B.HgnnError):
+        gr.host_view(0)
+    gr.release()
+    # negative destination
+    ei = mb.blocks[0].edge_index.copy(); ei[1, 0] = -1
+    gr = ctx.hgnn_build_semantic_csr([_bad_block(mb, edge_index=ei)])
+    with pytest.raises(B.HgnnError):
+        gr.wait()
+    gr.release()
+    # n_dst > n_src is an argument error reported at once
+    nd = list(mb.blocks[0].n_dst); nd[0] = mb.blocks[0].n_src[0] + 1
+    with pytest.raises(B.HgnnError) as e:
+        ctx.hgnn_build_semantic_csr([_bad_block(mb, n_dst=nd)])
+    assert e.value.status == -1
+    # a good build still works afterwards
+    gr = ctx.hgnn_build_semantic_csr(mb.blocks)
+    gr.wait(); gr.release()
+    ctx.close()
+
+
+def test_create_rejects_bad_schema(B):
+    with pytest.raises(B.HgnnError):
+        B.Context([0, 5], [0, 0], 2, "f32", device=-1)
+    with pytest.raises(B.HgnnError):
+        B.Context(list(range(200)), list(range(200)), 200, "f32", device=-1)
+
+
+def test_device_entry_points_refuse_host_only_context(B):
+    cfg = make_config(0)
+    g = build_graph(cfg)
+    ctx = _host_ctx(B, g.schema)
+    loss = C.c_float()
+    st = B.lib.hgnn_softmax_xent(ctx.handle, None, None, None, 0, 4, C.byref(loss), None)
+    assert st == -6
+    assert b"host-only" in B.lib.hgnn_last_error()
+    ctx.close()
+
+
+def test_overlapping_builds_from_one_context(B):
+    cfg = make_config(2, scale=0.02, batch=64)
+    g = build_graph(cfg)
+    mbs = [sample_minibatch(cfg, g, rng=np.random.default_rng(i)) for i in range(4)]
+    ctx = _host_ctx(B, g.schema, threads=4)
+    graphs = [ctx.hgnn_build_semantic_csr(mb.blocks) for mb in mbs]       # all queued before any wait
+    for mb, gr in zip(mbs, graphs):
+        for l, b in enumerate(mb.blocks):
+            sel = O.edge_index_select(b.edge_index, g.schema.num_rels, edge_type=b.edge_type)
+            ref = O.semantic_csr(sel, g.schema.rel_src, g.schema.rel_dst, b.n_src, b.n_dst)
+            v = gr.host_view(l)
+            for k in ("rowptr", "colidx", "cptr", "crow"):
+                assert np.array_equal(v[k], ref[k])
+        gr.release()
+    ctx.close()

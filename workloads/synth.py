@@ -115,10 +115,28 @@ def bf16_round(x: np.ndarray) -> np.ndarray:
     Storage-format conversion only, so that both sides start from bit-identical
     bf16-representable inputs."""
     x = np.ascontiguousarray(x, dtype=np.float32)
-    u = x.view(np.uint32).astype(np.uint64)
-    r = ((u + 0x7FFF + ((u >> 16) & 1)) >> 16) << 16
-    out = (r & 0xFFFFFFFF).astype(np.uint32).view(np.float32)
-    return np.where(np.isfinite(x), out, x).astype(np.float32).reshape(x.shape)
+    out = np.empty_like(x)
+    xf, of = x.reshape(-1), out.reshape(-1)
+    step = 1 << 22
+
+    def work(a):
+        u = xf[a: a + step].view(np.uint32)
+        r = u + (np.uint32(0x7FFF) + ((u >> np.uint32(16)) & np.uint32(1)))
+        r &= np.uint32(0xFFFF0000)
+        o = r.view(np.float32)
+        bad = ~np.isfinite(xf[a: a + step])
+        if bad.any():
+            o[bad] = xf[a: a + step][bad]
+        of[a: a + step] = o
+    starts = range(0, xf.size, step)
+    if xf.size > step:
+        from concurrent.futures import ThreadPoolExecutor
+        with ThreadPoolExecutor(max_workers=8) as ex:
+            list(ex.map(work, starts))
+    else:
+        for a in starts:
+            work(a)
+    return out
 
 
 def _streams(index: int):
