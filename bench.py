@@ -39,6 +39,7 @@ def main():
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--cpu-sample-batch", type=int, default=512)
     ap.add_argument("--host-threads", type=int, default=0)
+    ap.add_argument("--lookahead", type=int, default=4, help="mini-batches whose index build is started ahead of the GPU")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build runs on one GPU only (no collectives); use --gpus 1", file=sys.stderr)
@@ -100,12 +101,16 @@ def main():
         return b
 
     def pipelined(nsteps, first):
-        """Step i runs on the GPU while the host threads build the index arrays of step i+1."""
-        nxt = start_build(slots[first % len(slots)])
+        """Step i runs on the GPU while the host threads build the index arrays of the next
+        `lookahead` steps (the sampler of a training loop runs that far ahead)."""
+        ahead = [start_build(slots[(first + j) % len(slots)]) for j in range(min(args.lookahead, nsteps))]
+        started = len(ahead)
         pending = []
         for i in range(nsteps):
-            cur = nxt
-            nxt = start_build(slots[(first + i + 1) % len(slots)])
+            cur = ahead.pop(0)
+            if started < nsteps:
+                ahead.append(start_build(slots[(first + started) % len(slots)]))
+                started += 1
             model.run(batch_of(slots[(first + i) % len(slots)], cur))
             ev = torch.cuda.Event()
             ev.record()
@@ -117,8 +122,6 @@ def main():
         for e, gr in pending:
             e.synchronize()
             gr.release()
-        nxt.wait()
-        nxt.release()
 
     W, K = args.warmup, args.steps
     kid = B.KERNEL_IDS[args.probe]

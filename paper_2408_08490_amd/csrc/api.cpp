@@ -11,7 +11,7 @@ const char *get_error();
 static inline size_t align_up(size_t v, size_t a) { return (v + a - 1) / a * a; }
 static inline int esize(int dtype) { return dtype == HGNN_BF16 ? 2 : 4; }
 
-static void builder_main(hgnn_ctx *ctx) {
+static void builder_main(hgnn_ctx *ctx, Builder *bd) {
   if (ctx->device >= 0) (void)hipSetDevice(ctx->device);
   for (;;) {
     hgnn_graph *g = nullptr;
@@ -22,7 +22,7 @@ static void builder_main(hgnn_ctx *ctx) {
       g = ctx->queue.front();
       ctx->queue.pop_front();
     }
-    build_graph_job(ctx, g);
+    build_graph_job(ctx, *bd, g);
   }
 }
 
@@ -215,8 +215,14 @@ hgnn_status hgnn_create(hgnn_ctx **out, const hgnn_schema *s, int device, int ho
     long on = sysconf(_SC_NPROCESSORS_ONLN);
     n = (int)std::min<long>(16, std::max<long>(1, on));
   }
-  c->pool = new ThreadPool(n);
-  c->builder = std::thread(builder_main, c);
+  // graphs are independent, so several are built at once: up to 4 builders share the host threads
+  const int nb = std::max(1, std::min(4, n / 4));
+  for (int i = 0; i < nb; ++i) {
+    Builder *b = new Builder();
+    b->pool = new ThreadPool(n / nb + (i < n % nb ? 1 : 0));
+    c->builders.push_back(b);
+  }
+  for (Builder *b : c->builders) b->th = std::thread(builder_main, c, b);
   *out = c;
   return HGNN_OK;
 }
@@ -228,8 +234,11 @@ void hgnn_destroy(hgnn_ctx *c) {
     c->stop = true;
   }
   c->qcv.notify_all();
-  if (c->builder.joinable()) c->builder.join();
-  delete c->pool;
+  for (Builder *b : c->builders) {
+    if (b->th.joinable()) b->th.join();
+    delete b->pool;
+    delete b;
+  }
   if (c->device >= 0) {
     (void)hipSetDevice(c->device);
     (void)hipStreamSynchronize(c->side);

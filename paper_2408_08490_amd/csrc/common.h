@@ -122,6 +122,14 @@ class ThreadPool {
   bool stop_ = false;
 };
 
+// One builder: a host thread that takes whole graphs off the context's queue, its worker pool and its scratch.
+struct Builder {
+  ThreadPool *pool = nullptr;
+  std::thread th;
+  std::vector<int32_t> key, col, rowid, hist, tkey;
+  std::vector<std::vector<int32_t>> long_lists;
+};
+
 }  // namespace hgnn
 
 struct hgnn_graph {
@@ -142,9 +150,8 @@ struct hgnn_ctx {
   int32_t T = 0, R = 0;
   int32_t rel_src[hgnn::kMaxR], rel_dst[hgnn::kMaxR];
   int32_t heads = 1, agg = 0, fuse = 0, dtype = 0;
-  hgnn::ThreadPool *pool = nullptr;
+  std::vector<hgnn::Builder *> builders;  // each takes whole graphs off the queue and owns a slice of the host threads
   hipStream_t side = nullptr;
-  std::thread builder;  // processes graphs in submission order
   std::mutex qm;
   std::condition_variable qcv;
   std::deque<hgnn_graph *> queue;
@@ -152,8 +159,6 @@ struct hgnn_ctx {
   std::mutex pm;  // slab / event pool
   std::vector<hgnn::Slab> free_slabs;
   std::vector<hipEvent_t> free_events;
-  // builder-thread scratch
-  std::vector<int32_t> key, col, rowid, hist;
   // kernel probe (measurement aid)
   int probe_kernel = -1, probe_layer = -1;
   std::vector<std::pair<hipEvent_t, hipEvent_t>> probe_events;
@@ -161,7 +166,7 @@ struct hgnn_ctx {
 };
 
 namespace hgnn {
-void build_graph_job(hgnn_ctx *ctx, hgnn_graph *g);  // host_build.cpp
+void build_graph_job(hgnn_ctx *ctx, Builder &b, hgnn_graph *g);  // host_build.cpp
 
 // ---- kernel launchers (kernels_*.hip); all enqueue on `s` and return ----
 hgnn_status launch_merge(hipStream_t s, int dtype, int T, const void *const *store, const int32_t *feat_dim,

@@ -4,6 +4,8 @@
 // the selection with one OpenMP thread per relation; here the threads split the edge list
 // instead (relations are very uneven in size), which yields the same arrays.
 #include <algorithm>
+#include <chrono>
+#include <cstdlib>
 #include <cstdarg>
 #include <cstring>
 
@@ -94,49 +96,28 @@ struct BuildError {
   }
 };
 
-// Stable counting sort of items 0..n-1 by key[i] in [0,nkeys): pos[i] receives the output slot.
-// ptr (nkeys+1) receives the exclusive prefix of the key counts.  `hist` is P*nkeys scratch.
-template <class Emit>
-void counting_sort_positions(ThreadPool &pool, int P, int64_t n, const int32_t *key, int64_t nkeys,
-                             int32_t *ptr, std::vector<int32_t> &hist, Emit emit) {
-  hist.resize((size_t)P * (size_t)nkeys);
-  const int64_t slice = (n + P - 1) / P;
-  pool.parallel_for(P, [&](int p) {
-    int32_t *h = hist.data() + (size_t)p * nkeys;
-    std::memset(h, 0, sizeof(int32_t) * (size_t)nkeys);
-    const int64_t a = std::min<int64_t>(n, p * slice), b = std::min<int64_t>(n, a + slice);
-    for (int64_t i = a; i < b; ++i) ++h[key[i]];
-  });
-  const int KC = std::max(1, P * 4);
-  const int64_t kslice = (nkeys + KC - 1) / KC;
-  pool.parallel_for(KC, [&](int c) {
-    const int64_t a = std::min<int64_t>(nkeys, c * kslice), b = std::min<int64_t>(nkeys, a + kslice);
-    for (int64_t k = a; k < b; ++k) {
-      int32_t run = 0;
-      for (int p = 0; p < P; ++p) {
-        int32_t *h = hist.data() + (size_t)p * nkeys + k;
-        const int32_t t = *h;
-        *h = run;
-        run += t;
-      }
-      ptr[k + 1] = run;
-    }
-  });
-  ptr[0] = 0;
-  for (int64_t k = 0; k < nkeys; ++k) ptr[k + 1] += ptr[k];
-  pool.parallel_for(P, [&](int p) {
-    int32_t *h = hist.data() + (size_t)p * nkeys;
-    const int64_t a = std::min<int64_t>(n, p * slice), b = std::min<int64_t>(n, a + slice);
-    for (int64_t i = a; i < b; ++i) {
-      const int32_t k = key[i];
-      emit(i, ptr[k] + h[k]++);
-    }
-  });
-}
+constexpr int kBucketShift = 12;  // 4096 consecutive keys form one bucket (its counters stay in L1)
 
 }  // namespace
 
-static bool build_layer(hgnn_ctx *ctx, hgnn_graph *g, int l, BuildError &err) {
+// Two-level stable counting sort, used twice per layer (edges by merged row; CSR positions by source
+// row).  Level 1 splits the items into key-range buckets (threads own contiguous item slices, so the
+// order inside a bucket is the input order); level 2 sorts every bucket on its own with a local
+// histogram and writes the final arrays and the bucket's part of the row pointer.
+struct PhaseTimer {
+  bool on;
+  std::chrono::steady_clock::time_point t0;
+  PhaseTimer() : on(getenv("HGNN_BUILD_TIMING") != nullptr), t0(std::chrono::steady_clock::now()) {}
+  void lap(const char *what) {
+    if (!on) return;
+    auto t1 = std::chrono::steady_clock::now();
+    fprintf(stderr, "  [build] %-28s %8.3f ms\n", what, std::chrono::duration<double, std::milli>(t1 - t0).count());
+    t0 = t1;
+  }
+};
+
+static bool build_layer(hgnn_ctx *ctx, Builder &bd, hgnn_graph *g, int l, BuildError &err) {
+  PhaseTimer tm;
   LayerHost &L = g->L[l];
   const hgnn_coo_layer &in = L.in;
   const int T = ctx->T, R = ctx->R;
@@ -150,25 +131,47 @@ static bool build_layer(hgnn_ctx *ctx, hgnn_graph *g, int l, BuildError &err) {
   rel_row_off[0] = 0;
   for (int r = 0; r < R; ++r) rel_row_off[r + 1] = rel_row_off[r] + (int32_t)L.n_dst[ctx->rel_dst[r]];
   const int64_t E = L.edges, rows = L.rows, src_rows = L.src_rows;
-  ThreadPool &pool = *ctx->pool;
-  const int P = (int)std::max<int64_t>(1, std::min<int64_t>(pool.size(), (E + 8191) / 8192));
-  ctx->key.resize((size_t)E);
-  ctx->col.resize((size_t)E);
-  ctx->rowid.resize((size_t)E);
-  int32_t *key = ctx->key.data(), *col = ctx->col.data(), *rowid = ctx->rowid.data();
+  ThreadPool &pool = *bd.pool;
+  const int P = (int)std::max<int64_t>(1, std::min<int64_t>(pool.size(), (E + 16383) / 16384));
+  const int B1 = (int)((rows + (1 << kBucketShift) - 1) >> kBucketShift);
+  const int B2 = (int)((src_rows + (1 << kBucketShift) - 1) >> kBucketShift);
+  auto grow = [](std::vector<int32_t> &v, size_t n) {
+    if (v.size() < n) v.resize(n + n / 4);
+  };
+  grow(bd.key, (size_t)E);
+  grow(bd.col, (size_t)E);
+  grow(bd.rowid, (size_t)E);
+  grow(bd.tkey, (size_t)E * 3);  // level-1 records: (key, item, payload)
+  // counter rows are padded to whole 128-byte lines: neighbouring threads must not share a line
+  const size_t S1 = ((size_t)B1 + 63) / 32 * 32, S2 = ((size_t)B2 + 63) / 32 * 32;
+  grow(bd.hist, (size_t)P * S1 + (size_t)std::max(B1, 1) * S2 + B1 + B2 + 2 + 64);
+  int32_t *key = bd.key.data(), *col = bd.col.data(), *rowid = bd.rowid.data();
+  int32_t *trec = bd.tkey.data();
+  int32_t *cnt1 = reinterpret_cast<int32_t *>((reinterpret_cast<uintptr_t>(bd.hist.data()) + 127) & ~(uintptr_t)127);  // [P][S1]
+  int32_t *cnt2 = cnt1 + (size_t)P * S1;                     // [B1][S2]
+  int32_t *base1 = cnt2 + (size_t)std::max(B1, 1) * S2;      // [B1+1]
+  int32_t *base2 = base1 + B1 + 1;                           // [B2+1]
+  std::memset(cnt1, 0, sizeof(int32_t) * (size_t)P * S1);
+  std::memset(cnt2, 0, sizeof(int32_t) * (size_t)std::max(B1, 1) * S2);
+  tm.lap("setup");
 
-  // Algorithm 2, line "EdgeTypeLayer <- IndexSelect(EdgeType, EdgeID[i])" and the per-relation
-  // compare, done for all relations in one pass: each edge gets its merged row and source row.
+  // Algorithm 2: the layer's edge types are looked up through the edge ids (or taken as given) and matched
+  // against the relations -- for all relations in one pass: each edge gets its merged row and source row.
   const int64_t slice = (E + P - 1) / P;
   pool.parallel_for(P, [&](int p) {
     const int64_t a = std::min<int64_t>(E, p * slice), b = std::min<int64_t>(E, a + slice);
     const int64_t *ei64 = in.index_is_i64 ? (const int64_t *)in.edge_index : nullptr;
     const int32_t *ei32 = in.index_is_i64 ? nullptr : (const int32_t *)in.edge_index;
+    int32_t *cnt = cnt1 + (size_t)p * S1;
     for (int64_t e = a; e < b; ++e) {
       int64_t r;
       if (in.edge_type) {
         r = in.edge_type[e];
       } else {
+        if (e + 16 < b) {
+          const int64_t nid = in.edge_id[e + 16];
+          if (nid >= 0 && nid < in.num_global_edges) __builtin_prefetch(in.global_edge_type + nid);
+        }
         const int64_t id = in.edge_id[e];
         if (id < 0 || id >= in.num_global_edges) {
           err.set(HGNN_EINVAL, "layer " + std::to_string(l) + ": edge_id[" + std::to_string(e) + "]=" +
@@ -191,53 +194,148 @@ static bool build_layer(hgnn_ctx *ctx, hgnn_graph *g, int l, BuildError &err) {
                                  std::to_string(r) + ") outside its source/destination row range");
         return;
       }
-      key[e] = rel_row_off[r] + (int32_t)d;
+      const int32_t k = rel_row_off[r] + (int32_t)d;
+      key[e] = k;
       col[e] = row_off[ts] + (int32_t)s;
+      ++cnt[k >> kBucketShift];
     }
   });
   if (err.failed.load()) return false;
+  tm.lap("select (Alg.2) + count");
 
-  // merged CSR: stable by (relation, destination)
-  counting_sort_positions(pool, P, E, key, rows, rowptr, ctx->hist, [&](int64_t e, int32_t pos) {
-    colidx[pos] = col[e];
-    perm[pos] = (int32_t)e;
-    rowid[pos] = key[e];
+  // ---- merged CSR: stable by (relation, destination) ----
+  {
+    int32_t run = 0;
+    for (int b = 0; b < B1; ++b) {
+      base1[b] = run;
+      for (int p = 0; p < P; ++p) {
+        const int32_t t = cnt1[(size_t)p * S1 + b];
+        cnt1[(size_t)p * S1 + b] = run;
+        run += t;
+      }
+    }
+    base1[B1] = run;
+  }
+  pool.parallel_for(P, [&](int p) {
+    const int64_t a = std::min<int64_t>(E, p * slice), b = std::min<int64_t>(E, a + slice);
+    int32_t *off = cnt1 + (size_t)p * S1;
+    for (int64_t e = a; e < b; ++e) {
+      const int32_t q = off[key[e] >> kBucketShift]++;
+      int32_t *rec = trec + (size_t)q * 3;
+      rec[0] = key[e];
+      rec[1] = (int32_t)e;
+      rec[2] = col[e];
+    }
   });
+  tm.lap("csr level-1 scatter");
+  pool.parallel_for(B1, [&](int b) {
+    int32_t h[(1 << kBucketShift) + 1];
+    const int32_t k0 = b << kBucketShift;
+    const int32_t nk = (int32_t)std::min<int64_t>(1 << kBucketShift, rows - k0);
+    std::memset(h, 0, sizeof(int32_t) * (nk + 1));
+    const int32_t ja = base1[b], jb = base1[b + 1];
+    for (int32_t j = ja; j < jb; ++j) ++h[trec[(size_t)j * 3] - k0];
+    int32_t run = ja;
+    for (int32_t i = 0; i < nk; ++i) {
+      const int32_t t = h[i];
+      h[i] = run;
+      rowptr[k0 + i] = run;
+      run += t;
+    }
+    int32_t *c2 = cnt2 + (size_t)b * S2;
+    for (int32_t j = ja; j < jb; ++j) {
+      const int32_t *rec = trec + (size_t)j * 3;
+      const int32_t k = rec[0], e = rec[1], c = rec[2];
+      const int32_t pos = h[k - k0]++;
+      colidx[pos] = c;
+      perm[pos] = e;
+      rowid[pos] = k;
+      ++c2[c >> kBucketShift];
+    }
+  });
+  tm.lap("csr level-2 buckets");
+  rowptr[rows] = (int32_t)E;
   for (int r = 0; r <= R; ++r) rel_edge_off[r] = rowptr[rel_row_off[r]];
 
-  // transpose: CSR positions grouped by source row, ascending position inside a group
-  counting_sort_positions(pool, P, E, colidx, src_rows, cptr, ctx->hist, [&](int64_t k, int32_t pos) {
-    crow[pos] = rowid[k];
-    cperm[pos] = (int32_t)k;
+  // ---- transpose: CSR positions grouped by source row, ascending position inside a group ----
+  // the level-1 slices are the CSR position ranges of the buckets above (already in CSR order)
+  {
+    int32_t run = 0;
+    for (int b2 = 0; b2 < B2; ++b2) {
+      base2[b2] = run;
+      for (int b1 = 0; b1 < B1; ++b1) {
+        const int32_t t = cnt2[(size_t)b1 * S2 + b2];
+        cnt2[(size_t)b1 * S2 + b2] = run;
+        run += t;
+      }
+    }
+    base2[B2] = run;
+  }
+  pool.parallel_for(B1, [&](int b1) {
+    int32_t *off = cnt2 + (size_t)b1 * S2;
+    for (int32_t k = base1[b1]; k < base1[b1 + 1]; ++k) {
+      const int32_t q = off[colidx[k] >> kBucketShift]++;
+      int32_t *rec = trec + (size_t)q * 3;
+      rec[0] = colidx[k];
+      rec[1] = k;
+      rec[2] = rowid[k];
+    }
   });
+  tm.lap("csc level-1 scatter");
+  std::vector<std::vector<int32_t>> &longs = bd.long_lists;
+  if ((int)longs.size() < B2) longs.resize(B2);
+  pool.parallel_for(B2, [&](int b) {
+    int32_t h[(1 << kBucketShift) + 1];
+    const int32_t k0 = b << kBucketShift;
+    const int32_t nk = (int32_t)std::min<int64_t>(1 << kBucketShift, src_rows - k0);
+    std::memset(h, 0, sizeof(int32_t) * (nk + 1));
+    const int32_t ja = base2[b], jb = base2[b + 1];
+    for (int32_t j = ja; j < jb; ++j) ++h[trec[(size_t)j * 3] - k0];
+    int32_t run = ja;
+    longs[b].clear();
+    for (int32_t i = 0; i < nk; ++i) {
+      const int32_t t = h[i];
+      if (t > kLongRow) longs[b].push_back(k0 + i);
+      h[i] = run;
+      cptr[k0 + i] = run;
+      run += t;
+    }
+    for (int32_t j = ja; j < jb; ++j) {
+      const int32_t *rec = trec + (size_t)j * 3;
+      const int32_t pos = h[rec[0] - k0]++;
+      crow[pos] = rec[2];
+      cperm[pos] = rec[1];
+    }
+  });
+  cptr[src_rows] = (int32_t)E;
+  tm.lap("csc level-2 buckets");
 
   // long transpose rows are cut into chunks so that no single wave walks thousands of edges
   int32_t *chunk_row = base + L.o_chunk_row, *chunk_beg = base + L.o_chunk_beg;
   int32_t *long_row = base + L.o_long_row, *long_chunk0 = base + L.o_long_chunk0;
   int32_t nl = 0, nc = 0;
-  for (int64_t c = 0; c < src_rows; ++c) {
-    const int32_t len = cptr[c + 1] - cptr[c];
-    if (len > kLongRow) {
-      long_row[nl] = (int32_t)c;
+  for (int b = 0; b < B2; ++b)
+    for (int32_t c : longs[b]) {
+      long_row[nl] = c;
       long_chunk0[nl] = nc;
       ++nl;
-      for (int32_t b = cptr[c]; b < cptr[c + 1]; b += kChunk) {
-        chunk_row[nc] = (int32_t)c;
-        chunk_beg[nc] = b;
+      for (int32_t q = cptr[c]; q < cptr[c + 1]; q += kChunk) {
+        chunk_row[nc] = c;
+        chunk_beg[nc] = q;
         ++nc;
       }
     }
-  }
   long_chunk0[nl] = nc;
   L.n_long = nl;
   L.n_chunks = nc;
+  tm.lap("long-row chunks");
   return true;
 }
 
-void build_graph_job(hgnn_ctx *ctx, hgnn_graph *g) {
+void build_graph_job(hgnn_ctx *ctx, Builder &bd, hgnn_graph *g) {
   BuildError err;
   bool ok = true;
-  for (int l = 0; l < g->num_layers && ok; ++l) ok = build_layer(ctx, g, l, err);
+  for (int l = 0; l < g->num_layers && ok; ++l) ok = build_layer(ctx, bd, g, l, err);
   int status = ok ? HGNN_OK : err.status;
   std::string msg = err.msg;
   if (ok && ctx->device >= 0) {

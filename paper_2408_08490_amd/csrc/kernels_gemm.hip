@@ -5,9 +5,11 @@
 //   dA      : dZ_s = (G' W_s^T) scaled per row by 1/|N_r(v)|                          per K-segment s
 //   dW      : dW_s = A_s^T G'  (reduction over the destination rows, split and added atomically)
 // One 256-thread block (2x2 wavefronts) computes a 128x128 tile; every wavefront owns 64x64 of it as
-// 2x2 MFMA 32x32 accumulators.  Operands go global -> registers -> LDS (next tile's global loads are in
-// flight while the current one is multiplied).  An operand is kept in LDS the way it lies in memory:
-// "KC" = the reduction index is contiguous (rows = output index), "KS" = the output index is contiguous.
+// 2x2 MFMA 32x32 accumulators.  The reduction runs as ONE flat sequence of K-steps over all segments of
+// the tile, software-pipelined: operands go global -> registers -> LDS, the global loads of the next
+// two K-steps are in flight while the current one is multiplied, and LDS is double-buffered so that a
+// step costs one barrier.  An operand is kept in LDS the way it lies in memory: "KC" = the reduction
+// index is contiguous (rows = output index), "KS" = the output index is contiguous.
 #include "common.h"
 #include "device_types.h"
 
@@ -15,19 +17,29 @@ namespace hgnn {
 
 typedef float f32x16 __attribute__((ext_vector_type(16)));
 typedef __bf16 bf16x8_t __attribute__((ext_vector_type(8)));
+typedef unsigned int u32x4 __attribute__((ext_vector_type(4)));
+typedef unsigned int u32x2 __attribute__((ext_vector_type(2)));
 
 constexpr int BM = 128, BN = 128, kThreads = 256;
+constexpr int kSegCap = 96;  // K-segments staged in LDS at a time
 
 template <typename T> struct Mma;
 template <> struct Mma<bf16> {
-  static constexpr int BK = 32, KSTEP = 16, VEC = 8, PKC = BK + 8, PKS = 128 + 4;
+  static constexpr int BK = 64, KSTEP = 16, VEC = 8, PKC = BK + 8, PKS = 128 + 4;
 };
 template <> struct Mma<float> {
-  static constexpr int BK = 16, KSTEP = 2, VEC = 4, PKC = BK + 4, PKS = 128 + 4;
+  static constexpr int BK = 32, KSTEP = 2, VEC = 4, PKC = BK + 4, PKS = 128 + 4;
 };
 template <typename T> constexpr int lds_elems() {
   return (BM * Mma<T>::PKC > Mma<T>::BK * Mma<T>::PKS) ? BM * Mma<T>::PKC : Mma<T>::BK * Mma<T>::PKS;
 }
+
+// One K-segment of a tile's reduction: sum over k in [kb, ke) of Aop[.][k] * Bop[.][k].
+template <typename T> struct Seg {
+  const T *A, *B;
+  int lda, ldb, kb, ke;
+  int a_vec, b_vec;  // 16-byte loads allowed (base and leading dimension aligned)
+};
 
 // One operand tile on its way global -> registers -> LDS.  The tile is ROWS x COLS in the operand's own
 // row-major orientation (COLS contiguous); out-of-range parts are zero-filled.
@@ -35,27 +47,45 @@ template <typename T, int ROWS, int COLS, int PITCH>
 struct TileMover {
   static constexpr int VEC = 16 / sizeof(T), VPR = COLS / VEC, NV = ROWS * VPR / kThreads;
   static_assert(ROWS * VPR % kThreads == 0, "tile must split evenly over the block");
-  uint4 reg[NV];
+  u32x4 reg[NV];
+  unsigned okmask = 0;
+  // Branch-free inside either path (out-of-range pieces read a clamped address and are zeroed afterwards),
+  // so that all loads of a K-step are issued back to back and waited for once, when they are stored to LDS.
+  // vec_ok promises 16-byte aligned rows and ncols % VEC == 0.
   __device__ __forceinline__ void load(const T *base, int64_t ld, int nrows, int ncols, int r0, int c0, bool vec_ok) {
+    typedef const u32x4 __attribute__((address_space(1))) *gvec_t;
+    typedef const unsigned short __attribute__((address_space(1))) *g16_t;
+    typedef const unsigned int __attribute__((address_space(1))) *g32_t;
+    if (vec_ok) {
 #pragma unroll
-    for (int i = 0; i < NV; ++i) {
-      const int v = threadIdx.x + i * kThreads;
-      const int gr = r0 + v / VPR, gc = c0 + (v % VPR) * VEC;
-      uint4 val = make_uint4(0, 0, 0, 0);
-      if (gr < nrows && gc < ncols) {
-        const T *p = base + (int64_t)gr * ld + gc;
-        if (vec_ok && gc + VEC <= ncols) {
-          val = *reinterpret_cast<const uint4 *>(p);
-        } else {
-          union { uint4 u; T e[VEC]; } tmp;
-          tmp.u = make_uint4(0, 0, 0, 0);
-#pragma unroll
-          for (int j = 0; j < VEC; ++j)
-            if (gc + j < ncols) tmp.e[j] = p[j];
-          val = tmp.u;
-        }
+      for (int i = 0; i < NV; ++i) {
+        const int v = threadIdx.x + i * kThreads;
+        const int gr = r0 + v / VPR, gc = c0 + (v % VPR) * VEC;
+        const bool ok = gr < nrows && gc < ncols;
+        const int64_t off = ok ? (int64_t)gr * ld + gc : 0;
+        reg[i] = *(gvec_t)(base + off);
+        okmask = ok ? (okmask | (1u << i)) : (okmask & ~(1u << i));  // zeroing waits until the LDS store
       }
-      reg[i] = val;
+    } else {
+#pragma unroll
+      for (int i = 0; i < NV; ++i) {
+        const int v = threadIdx.x + i * kThreads;
+        const int gr = r0 + v / VPR, gc = c0 + (v % VPR) * VEC;
+        unsigned int e[VEC];
+#pragma unroll
+        for (int j = 0; j < VEC; ++j) {
+          const bool ok = gr < nrows && gc + j < ncols;
+          const T *p = ok ? base + (int64_t)gr * ld + gc + j : base;
+          unsigned int x;
+          if constexpr (sizeof(T) == 2) x = *(g16_t)p; else x = *(g32_t)p;
+          e[j] = ok ? x : 0u;
+        }
+        if constexpr (sizeof(T) == 2)
+          reg[i] = u32x4{e[0] | (e[1] << 16), e[2] | (e[3] << 16), e[4] | (e[5] << 16), e[6] | (e[7] << 16)};
+        else
+          reg[i] = u32x4{e[0], e[1], e[2], e[3]};
+        okmask |= 1u << i;
+      }
     }
   }
   __device__ __forceinline__ void store(T *lds) const {
@@ -63,12 +93,13 @@ struct TileMover {
     for (int i = 0; i < NV; ++i) {
       const int v = threadIdx.x + i * kThreads;
       T *q = lds + (v / VPR) * PITCH + (v % VPR) * VEC;
+      const u32x4 val = ((okmask >> i) & 1u) ? reg[i] : u32x4{0u, 0u, 0u, 0u};
       if constexpr ((PITCH * sizeof(T)) % 16 == 0) {
-        *reinterpret_cast<uint4 *>(q) = reg[i];
+        *reinterpret_cast<u32x4 *>(q) = val;
       } else {
         static_assert((PITCH * sizeof(T)) % 8 == 0, "LDS pitch must keep 8-byte alignment");
-        reinterpret_cast<uint2 *>(q)[0] = make_uint2(reg[i].x, reg[i].y);
-        reinterpret_cast<uint2 *>(q)[1] = make_uint2(reg[i].z, reg[i].w);
+        reinterpret_cast<u32x2 *>(q)[0] = u32x2{val.x, val.y};
+        reinterpret_cast<u32x2 *>(q)[1] = u32x2{val.z, val.w};
       }
     }
   }
@@ -122,33 +153,58 @@ __device__ __forceinline__ void mma_tile(f32x16 (&acc)[2][2], const T *As, const
   }
 }
 
-// Accumulates  sum_{k in [k_begin,k_end)} Aop[a0+i][k] * Bop[b0+j][k]  into the block's accumulators.
+// LDS of one block: two stages of (A tile, B tile) and the K-segment table.
+template <typename T> struct GemmLds {
+  __attribute__((aligned(16))) T a[2][lds_elems<T>()];
+  __attribute__((aligned(16))) T b[2][lds_elems<T>()];
+  Seg<T> seg[kSegCap];
+};
+
+// Runs the K-steps of segs[0..nseg) (read from LDS; must be visible to the whole block) into `acc`.
 // KC operand: matrix [extent x K] row-major (ld); KS operand: matrix [K x extent] row-major (ld).
 template <typename T, bool AKC, bool BKC>
-__device__ __forceinline__ void gemm_segment(f32x16 (&acc)[2][2], T *As, T *Bs, const T *A, int64_t lda, int a_extent,
-                                             int a0, bool a_vec, const T *B, int64_t ldb, int b_extent, int b0,
-                                             bool b_vec, int k_begin, int k_end) {
+__device__ __forceinline__ void gemm_run(f32x16 (&acc)[2][2], GemmLds<T> &sm, int nseg, int a_extent, int a0,
+                                         int b_extent, int b0) {
   using M = Mma<T>;
   const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
   const int wm = (wave >> 1) * 64, wn = (wave & 1) * 64;
-  TileMover<T, AKC ? BM : M::BK, AKC ? M::BK : BM, AKC ? M::PKC : M::PKS> ta;
-  TileMover<T, BKC ? BN : M::BK, BKC ? M::BK : BN, BKC ? M::PKC : M::PKS> tb;
-  auto load = [&](int k0) {
-    if constexpr (AKC) ta.load(A, lda, a_extent, k_end, a0, k0, a_vec);
-    else ta.load(A, lda, k_end, a_extent, k0, a0, a_vec);
-    if constexpr (BKC) tb.load(B, ldb, b_extent, k_end, b0, k0, b_vec);
-    else tb.load(B, ldb, k_end, b_extent, k0, b0, b_vec);
+  using MoverA = TileMover<T, AKC ? BM : M::BK, AKC ? M::BK : BM, AKC ? M::PKC : M::PKS>;
+  using MoverB = TileMover<T, BKC ? BN : M::BK, BKC ? M::BK : BN, BKC ? M::PKC : M::PKS>;
+  MoverA ta0, ta1;
+  MoverB tb0, tb1;
+  int total = 0;
+  for (int s = 0; s < nseg; ++s) total += (sm.seg[s].ke - sm.seg[s].kb + M::BK - 1) / M::BK;
+  int s_ld = 0, k_ld = nseg > 0 ? sm.seg[0].kb : 0;  // cursor of the loader, two K-steps ahead of the multiplier
+  auto issue = [&](MoverA &ta, MoverB &tb) {
+    if (s_ld >= nseg) return;
+    const Seg<T> g = sm.seg[s_ld];
+    if constexpr (AKC) ta.load(g.A, g.lda, a_extent, g.ke, a0, k_ld, g.a_vec);
+    else ta.load(g.A, g.lda, g.ke, a_extent, k_ld, a0, g.a_vec);
+    if constexpr (BKC) tb.load(g.B, g.ldb, b_extent, g.ke, b0, k_ld, g.b_vec);
+    else tb.load(g.B, g.ldb, g.ke, b_extent, k_ld, b0, g.b_vec);
+    k_ld += M::BK;
+    if (k_ld >= g.ke) {
+      ++s_ld;
+      if (s_ld < nseg) k_ld = sm.seg[s_ld].kb;
+    }
   };
-  if (k_begin >= k_end) return;
-  load(k_begin);
-  for (int k0 = k_begin; k0 < k_end; k0 += M::BK) {
-    ta.store(As);
-    tb.store(Bs);
+  issue(ta0, tb0);
+  issue(ta1, tb1);
+  for (int step = 0; step < total; step += 2) {
+    ta0.store(sm.a[0]);
+    tb0.store(sm.b[0]);
     __syncthreads();
-    if (k0 + M::BK < k_end) load(k0 + M::BK);
-    mma_tile<T, AKC, BKC>(acc, As, Bs, wm, wn, lane);
-    __syncthreads();
+    issue(ta0, tb0);
+    mma_tile<T, AKC, BKC>(acc, sm.a[0], sm.b[0], wm, wn, lane);
+    if (step + 1 < total) {
+      ta1.store(sm.a[1]);
+      tb1.store(sm.b[1]);
+      __syncthreads();
+      issue(ta1, tb1);
+      mma_tile<T, AKC, BKC>(acc, sm.a[1], sm.b[1], wm, wn, lane);
+    }
   }
+  __syncthreads();  // the segment table and the stages may be rewritten by the caller
 }
 
 __device__ __forceinline__ void zero_acc(f32x16 (&acc)[2][2]) {
@@ -184,6 +240,17 @@ static inline int round_up8(int n) { return (n + 7) & ~7; }
 
 __device__ __forceinline__ bool aligned16(const void *p) { return (reinterpret_cast<uintptr_t>(p) & 15) == 0; }
 
+// a_cols / b_cols: length of the contiguous dimension of each operand (K for a KC operand, the output
+// extent for a KS operand); vector loads need it, the leading dimension and the base to be 16-byte multiples.
+template <typename T>
+__device__ __forceinline__ void put_seg(Seg<T> &g, const T *A, int lda, int a_cols, const T *B, int ldb, int b_cols,
+                                        int kb, int ke) {
+  constexpr int V = Mma<T>::VEC;
+  g.A = A; g.B = B; g.lda = lda; g.ldb = ldb; g.kb = kb; g.ke = ke;
+  g.a_vec = (lda % V) == 0 && (a_cols % V) == 0 && aligned16(A);
+  g.b_vec = (ldb % V) == 0 && (b_cols % V) == 0 && aligned16(B);
+}
+
 // ------------------------------------------------------------------------------------------
 template <typename T>
 __global__ void __launch_bounds__(kThreads) gemm_fwd_kernel(LayerDev L, TypeTab tt, RelTab rt, PtrTab pt, WtTab wt, SegTab tiles,
@@ -191,8 +258,8 @@ __global__ void __launch_bounds__(kThreads) gemm_fwd_kernel(LayerDev L, TypeTab 
                                                             const T *__restrict__ zlo, const T *__restrict__ wtb,
                                                             T *__restrict__ h, int only_seg,
                                                             float *__restrict__ acc32) {
-  __shared__ __attribute__((aligned(16))) T As[lds_elems<T>()];
-  __shared__ __attribute__((aligned(16))) T Bs[lds_elems<T>()];
+  __shared__ GemmLds<T> sm;
+  __shared__ int s_nseg, s_next;
   const int tile = xcd_tile(blockIdx.x, gridDim.x);
   const int T_ = tt.num_types, R = rt.num_rels;
   if (tile >= tiles.tile_off[T_]) return;
@@ -204,20 +271,34 @@ __global__ void __launch_bounds__(kThreads) gemm_fwd_kernel(LayerDev L, TypeTab 
   const int M = tt.n_dst[d];
   f32x16 acc[2][2];
   zero_acc(acc);
-  for (int r = 0; r < R; ++r) {
-    if (rt.dst[r] != d || (only_seg >= 0 && only_seg != r)) continue;
-    if (L.rel_edge_off[r + 1] == L.rel_edge_off[r]) continue;  // no edge: the aggregate is all zero
-    const int F = tt.in_dim[rt.src[r]];
-    gemm_segment<T, true, true>(acc, As, Bs, z + (int64_t)rt.z_off4[r] * 4, F, M, m0, true,
-                                wtb + (int64_t)wt.rel4[r] * 4, F, H, n0, true, 0, F);
-    if (zlo)  // low-order part of the aggregate (bf16 storage): same weights, accumulated on top
-      gemm_segment<T, true, true>(acc, As, Bs, zlo + (int64_t)rt.z_off4[r] * 4, F, M, m0, true,
-                                  wtb + (int64_t)wt.rel4[r] * 4, F, H, n0, true, 0, F);
-  }
-  if (pt.w_root[d] && (only_seg < 0 || only_seg == R + d)) {
-    const int F = tt.in_dim[d];
-    gemm_segment<T, true, true>(acc, As, Bs, x + tt.elem_off[d], F, M, m0, true, wtb + (int64_t)wt.root4[d] * 4, F, H,
-                                n0, true, 0, F);
+  // K-segments of this destination type: every relation ending in d (aggregate, and for bf16 storage its
+  // low-order remainder against the same weights), then the root term.  Staged kSegCap at a time.
+  int cursor = 0;  // next relation to look at; R = root; R + 1 = done
+  while (cursor <= R) {
+    if (threadIdx.x == 0) {
+      int n = 0, r = cursor;
+      for (; r < R && n + 2 <= kSegCap; ++r) {
+        if (rt.dst[r] != d || (only_seg >= 0 && only_seg != r)) continue;
+        if (L.rel_edge_off[r + 1] == L.rel_edge_off[r]) continue;  // no edge: the aggregate is all zero
+        const int F = tt.in_dim[rt.src[r]];
+        const T *B = wtb + (int64_t)wt.rel4[r] * 4;
+        put_seg(sm.seg[n++], z + (int64_t)rt.z_off4[r] * 4, F, F, B, F, F, 0, F);
+        if (zlo) put_seg(sm.seg[n++], zlo + (int64_t)rt.z_off4[r] * 4, F, F, B, F, F, 0, F);
+      }
+      if (r == R && n + 1 <= kSegCap) {
+        if (pt.w_root[d] && (only_seg < 0 || only_seg == R + d)) {
+          const int F = tt.in_dim[d];
+          put_seg(sm.seg[n++], x + tt.elem_off[d], F, F, wtb + (int64_t)wt.root4[d] * 4, F, F, 0, F);
+        }
+        r = R + 1;
+      }
+      s_nseg = n;
+      s_next = r;
+    }
+    __syncthreads();
+    const int nseg = s_nseg;
+    cursor = s_next;
+    gemm_run<T, true, true>(acc, sm, nseg, M, m0, H, n0);
   }
   const T *bias = reinterpret_cast<const T *>(pt.bias[d]);
   const int64_t orow = tt.out_row_off[d];
@@ -266,8 +347,7 @@ __device__ __forceinline__ int find_seg(const SegTab &tiles, int tile) {
 template <typename T>
 __global__ void __launch_bounds__(kThreads) gemm_da_kernel(LayerDev L, TypeTab tt, RelTab rt, PtrTab pt, SegTab tiles, int H,
                                                            const T *__restrict__ gp, T *__restrict__ dz) {
-  __shared__ __attribute__((aligned(16))) T As[lds_elems<T>()];
-  __shared__ __attribute__((aligned(16))) T Bs[lds_elems<T>()];
+  __shared__ GemmLds<T> sm;
   const int tile = xcd_tile(blockIdx.x, gridDim.x);
   const int R = rt.num_rels;
   if (tile >= tiles.tile_off[tiles.num_segs]) return;
@@ -282,9 +362,9 @@ __global__ void __launch_bounds__(kThreads) gemm_da_kernel(LayerDev L, TypeTab t
   const int m0 = (local / tiles_n) * BM, n0 = (local % tiles_n) * BN;
   f32x16 acc[2][2];
   zero_acc(acc);
-  const T *A = gp + (int64_t)tt.out_row_off[d] * H;
-  const bool vec = (H % Mma<T>::VEC) == 0;
-  gemm_segment<T, true, true>(acc, As, Bs, A, H, M, m0, vec && aligned16(A), W, H, F, n0, vec && aligned16(W), 0, H);
+  if (threadIdx.x == 0) put_seg(sm.seg[0], gp + (int64_t)tt.out_row_off[d] * H, H, H, W, H, H, 0, H);
+  __syncthreads();
+  gemm_run<T, true, true>(acc, sm, 1, M, m0, F, n0);
   T *out = dz + (int64_t)(is_rel ? rt.z_off4[seg] : rt.zroot_off4[d]) * 4;
   const int rho0 = is_rel ? L.rel_row_off[seg] : 0;
   HGNN_FOR_EACH_ACC({
@@ -317,8 +397,7 @@ template <typename T>
 __global__ void __launch_bounds__(kThreads) gemm_dw_kernel(LayerDev L, TypeTab tt, RelTab rt, GradPtrTab gt, SegTab tiles,
                                                            int split_rows, int H, const T *__restrict__ x,
                                                            const T *__restrict__ z, const T *__restrict__ gp) {
-  __shared__ __attribute__((aligned(16))) T As[lds_elems<T>()];
-  __shared__ __attribute__((aligned(16))) T Bs[lds_elems<T>()];
+  __shared__ GemmLds<T> sm;
   const int tile = xcd_tile(blockIdx.x, gridDim.x);
   const int R = rt.num_rels;
   if (tile >= tiles.tile_off[tiles.num_segs]) return;
@@ -338,10 +417,11 @@ __global__ void __launch_bounds__(kThreads) gemm_dw_kernel(LayerDev L, TypeTab t
   const int k_begin = sp * split_rows, k_end = min(M, k_begin + split_rows);
   f32x16 acc[2][2];
   zero_acc(acc);
-  const T *A = is_rel ? z + (int64_t)rt.z_off4[seg] * 4 : x + tt.elem_off[d];
-  const T *B = gp + (int64_t)tt.out_row_off[d] * H;
-  gemm_segment<T, false, false>(acc, As, Bs, A, F, F, f0, true, B, H, H, h0, (H % Mma<T>::VEC) == 0 && aligned16(B),
-                                k_begin, k_end);
+  if (threadIdx.x == 0)
+    put_seg(sm.seg[0], is_rel ? z + (int64_t)rt.z_off4[seg] * 4 : x + tt.elem_off[d], F, F,
+            gp + (int64_t)tt.out_row_off[d] * H, H, H, k_begin, k_end);
+  __syncthreads();
+  gemm_run<T, false, false>(acc, sm, 1, F, f0, H, h0);
   HGNN_FOR_EACH_ACC({
     if (f0 + row < F && h0 + col < H) atomicAdd(dW + (int64_t)(f0 + row) * H + h0 + col, val);
   })
