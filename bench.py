@@ -39,6 +39,7 @@ def main():
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--cpu-sample-batch", type=int, default=512)
     ap.add_argument("--host-threads", type=int, default=0)
+    ap.add_argument("--all-input-grads", action="store_true", help="also compute gradients w.r.t. the fixed T0 features")
     ap.add_argument("--lookahead", type=int, default=4, help="mini-batches whose index build is started ahead of the GPU")
     args = ap.parse_args()
     if args.gpus != 1:
@@ -71,7 +72,9 @@ def main():
 
     model = Model(g.schema, g.feat_dim, g.stores, ws, dtype=cfg.dtype,
                   loss=("xent" if cfg.loss == "xent" else "dot"), target_type=mbs[0].target_type,
-                  host_threads=args.host_threads)
+                  host_threads=args.host_threads,
+                  # T0 carries fixed input features; only the learnable embeddings of T1-T3 need input gradients
+                  first_layer_input_grad=([0, 1, 1, 1] if cfg.index in (1, 2, 4) and not args.all_input_grads else None))
     ctx = model.ctx
 
     # inputs resident in HBM before the timed region: stores, weights, per-mini-batch id lists and labels

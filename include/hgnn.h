@@ -150,6 +150,8 @@ typedef struct {
   const void *const *w_rel;    /* [R] W_r  [in_dim[src(r)] x H]            (mean aggregation) */
   const void *const *w_root;   /* [T] W_0^t [in_dim[t] x H] or NULL entry  (mean aggregation) */
   const void *const *bias;     /* [T] b_t [H] or NULL entry; the array itself may be NULL      */
+  const int32_t *input_grad;   /* host [T] or NULL (= all 1): 0 = hgnn_layer_bwd leaves the grad_x_merged rows
+                                  of type t unwritten and skips their work (fixed, non-learnable input features) */
 } hgnn_layer_params;
 
 /* fp32 gradient buffers mirroring hgnn_layer_params (device, caller-owned, OVERWRITTEN).

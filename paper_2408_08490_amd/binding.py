@@ -49,7 +49,7 @@ class CsrView(C.Structure):
 class LayerParams(C.Structure):
     _fields_ = [("in_dim", C.POINTER(C.c_int32)), ("out_dim", C.c_int32), ("relu", C.c_int32),
                 ("w_rel", C.POINTER(C.c_void_p)), ("w_root", C.POINTER(C.c_void_p)),
-                ("bias", C.POINTER(C.c_void_p))]
+                ("bias", C.POINTER(C.c_void_p)), ("input_grad", C.POINTER(C.c_int32))]
 
 
 class LayerGrads(C.Structure):
@@ -153,15 +153,18 @@ class Graph:
 class Layer:
     """Marshalled hgnn_layer_params (+ optional gradient table) for one layer; holds the tensors."""
 
-    def __init__(self, ctx, in_dim, out_dim, relu, w_rel, w_root, bias, dw_rel=None, dw_root=None, dbias=None):
+    def __init__(self, ctx, in_dim, out_dim, relu, w_rel, w_root, bias, dw_rel=None, dw_root=None, dbias=None,
+                 input_grad=None):
         T, R = ctx.num_types, ctx.num_rels
         self.tensors = (w_rel, w_root, bias, dw_rel, dw_root, dbias)
         self._in_dim = (C.c_int32 * T)(*in_dim)
         self._w_rel = (C.c_void_p * R)(*[_ptr(w) for w in w_rel])
         self._w_root = (C.c_void_p * T)(*[_ptr(w) for w in w_root])
         self._bias = (C.c_void_p * T)(*[_ptr(b) for b in bias]) if bias is not None else None
+        self._input_grad = (C.c_int32 * T)(*[int(x) for x in input_grad]) if input_grad is not None else None
         self.params = LayerParams(self._in_dim, out_dim, int(relu), self._w_rel, self._w_root,
-                                  self._bias if self._bias is not None else C.POINTER(C.c_void_p)())
+                                  self._bias if self._bias is not None else C.POINTER(C.c_void_p)(),
+                                  self._input_grad if self._input_grad is not None else C.POINTER(C.c_int32)())
         self.in_dim, self.out_dim, self.relu = list(in_dim), out_dim, bool(relu)
         self.grads = None
         if dw_rel is not None:

@@ -468,7 +468,7 @@ static hgnn_status fwd_common(hgnn_ctx *ctx, void *stream, hgnn_graph *g, int32_
   void *wtb = sc + pl.off_wt;
   // bf16 storage: the aggregate is kept as a pair (rounded value, remainder) so that the pre-activation,
   // and with it the ReLU mask the backward pass uses, does not inherit the rounding of the aggregate
-  void *zlo = ctx->dtype == HGNN_BF16 ? sc + pl.off_zlo : nullptr;
+  void *zlo = (ctx->dtype == HGNN_BF16 && p->relu) ? sc + pl.off_zlo : nullptr;
   int n = 0;
   SegTab tl;
   fwd_tiles(pl, tl);
@@ -550,7 +550,8 @@ static void seg_tiles_da(hgnn_ctx *ctx, const Plan &pl, const hgnn_layer_params 
     const bool is_rel = sgi < R;
     const int d = is_rel ? ctx->rel_dst[sgi] : sgi - R;
     const int F = pl.tt.in_dim[is_rel ? ctx->rel_src[sgi] : d];
-    const bool live = is_rel ? rel_edge_off[sgi + 1] > rel_edge_off[sgi] : p->w_root[d] != nullptr;
+    bool live = is_rel ? rel_edge_off[sgi + 1] > rel_edge_off[sgi] : p->w_root[d] != nullptr;
+    if (p->input_grad && !p->input_grad[is_rel ? ctx->rel_src[sgi] : d]) live = false;  // nobody reads this dZ
     if (live && pl.tt.n_dst[d] > 0) cnt = ((pl.tt.n_dst[d] + 127) / 128) * ((F + 127) / 128);
     tl.tile_off[sgi + 1] = tl.tile_off[sgi] + cnt;
   }
@@ -637,7 +638,10 @@ hgnn_status hgnn_layer_bwd(hgnn_ctx *ctx, void *stream, hgnn_graph *g, int32_t l
       if ((st = launch_gemm_da(s, ctx->dtype, pl.dev, pl.tt, pl.rt, pl.pt, tl, pl.H, gp, dz)) != HGNN_OK) return st;
     }
     Probe pb(ctx, s, HGNN_K_SPMM_BWD, layer);
-    if ((st = launch_spmm_bwd(s, ctx->dtype, pl.dev, pl.tt, pl.rt, pl.pt, pl.max_dim, dz, grad_x_merged, (float *)(sc + pl.off_partial))) != HGNN_OK) return st;
+    uint32_t want = 0;
+    for (int t = 0; t < T; ++t)
+      if (!p->input_grad || p->input_grad[t]) want |= 1u << t;
+    if ((st = launch_spmm_bwd(s, ctx->dtype, pl.dev, pl.tt, pl.rt, pl.pt, pl.max_dim, want, dz, grad_x_merged, (float *)(sc + pl.off_partial))) != HGNN_OK) return st;
   }
   return HGNN_OK;
 }

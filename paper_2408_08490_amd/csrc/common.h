@@ -176,7 +176,7 @@ hgnn_status launch_spmm_fwd(hipStream_t s, int dtype, const LayerDev &L, const T
                             int max_dim, const void *x, void *z, void *zlo, int row_begin, int row_end);
 // dx[c] = sum over transpose row c of dz[crow] (+ root part for destination rows)
 hgnn_status launch_spmm_bwd(hipStream_t s, int dtype, const LayerDev &L, const TypeTab &tt, const RelTab &rt,
-                            const PtrTab &pt, int max_dim, const void *dz, void *dx, float *partial);
+                            const PtrTab &pt, int max_dim, uint32_t want_types, const void *dz, void *dx, float *partial);
 hgnn_status launch_transpose_weights(hipStream_t s, int dtype, const TypeTab &tt, const RelTab &rt,
                                      const PtrTab &pt, const WtTab &wt, int H, void *wt_buf);
 // mode 0: all segments of every type fused (bias/activation epilogue, writes h)

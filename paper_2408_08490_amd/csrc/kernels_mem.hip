@@ -159,7 +159,7 @@ __device__ __forceinline__ const uint4 *dz_row(const T *dz, const LayerDev &L, c
 }
 
 template <typename T>
-__global__ void __launch_bounds__(256) spmm_bwd_kernel(LayerDev L, TypeTab tt, RelTab rt, uint32_t root_mask,
+__global__ void __launch_bounds__(256) spmm_bwd_kernel(LayerDev L, TypeTab tt, RelTab rt, uint32_t root_mask, uint32_t want,
                                                         const T *__restrict__ dz, T *__restrict__ dx,
                                                         float *__restrict__ partial, int max_dim, int row_blocks,
                                                         int lpr_log2, int uniform) {
@@ -184,6 +184,7 @@ __global__ void __launch_bounds__(256) spmm_bwd_kernel(LayerDev L, TypeTab tt, R
   }
   int t = 0;
   while (c >= tt.row_off[t + 1]) ++t;
+  if (!((want >> t) & 1u)) return;  // the caller does not want input gradients of this vertex type
   const int F = tt.in_dim[t];
   const int nvec = F / V::N;
   const int cl = c - tt.row_off[t];
@@ -214,13 +215,14 @@ __global__ void __launch_bounds__(256) spmm_bwd_kernel(LayerDev L, TypeTab tt, R
 }
 
 template <typename T>
-__global__ void __launch_bounds__(256) spmm_bwd_long_kernel(LayerDev L, TypeTab tt, RelTab rt, uint32_t root_mask,
+__global__ void __launch_bounds__(256) spmm_bwd_long_kernel(LayerDev L, TypeTab tt, RelTab rt, uint32_t root_mask, uint32_t want,
                                                              const T *__restrict__ dz, T *__restrict__ dx,
                                                              const float *__restrict__ partial, int max_dim) {
   const int i = blockIdx.x;  // one block per long row
   const int c = L.long_row[i];
   int t = 0;
   while (c >= tt.row_off[t + 1]) ++t;
+  if (!((want >> t) & 1u)) return;
   const int F = tt.in_dim[t];
   const int cl = c - tt.row_off[t];
   const int j0 = L.long_chunk0[i], j1 = L.long_chunk0[i + 1];
@@ -234,7 +236,7 @@ __global__ void __launch_bounds__(256) spmm_bwd_long_kernel(LayerDev L, TypeTab 
 }
 
 hgnn_status launch_spmm_bwd(hipStream_t s, int dtype, const LayerDev &L, const TypeTab &tt, const RelTab &rt,
-                            const PtrTab &pt, int max_dim, const void *dz, void *dx, float *partial) {
+                            const PtrTab &pt, int max_dim, uint32_t want, const void *dz, void *dx, float *partial) {
   if (L.src_rows == 0) return HGNN_OK;
   const int es = dtype == HGNN_BF16 ? 2 : 4;
   const int l2 = lanes_log2_for(max_dim, es);
@@ -249,18 +251,18 @@ hgnn_status launch_spmm_bwd(hipStream_t s, int dtype, const LayerDev &L, const T
   }
   dim3 grid(row_blocks + chunk_blocks);
   if (dtype == HGNN_BF16)
-    hipLaunchKernelGGL(spmm_bwd_kernel<bf16>, grid, dim3(256), 0, s, L, tt, rt, root_mask, (const bf16 *)dz, (bf16 *)dx,
+    hipLaunchKernelGGL(spmm_bwd_kernel<bf16>, grid, dim3(256), 0, s, L, tt, rt, root_mask, want, (const bf16 *)dz, (bf16 *)dx,
                        partial, max_dim, row_blocks, l2, (int)uniform);
   else
-    hipLaunchKernelGGL(spmm_bwd_kernel<float>, grid, dim3(256), 0, s, L, tt, rt, root_mask, (const float *)dz, (float *)dx,
+    hipLaunchKernelGGL(spmm_bwd_kernel<float>, grid, dim3(256), 0, s, L, tt, rt, root_mask, want, (const float *)dz, (float *)dx,
                        partial, max_dim, row_blocks, l2, (int)uniform);
   HGNN_HIP(hipGetLastError());
   if (L.n_long > 0) {
     if (dtype == HGNN_BF16)
-      hipLaunchKernelGGL(spmm_bwd_long_kernel<bf16>, dim3(L.n_long), dim3(128), 0, s, L, tt, rt, root_mask, (const bf16 *)dz,
+      hipLaunchKernelGGL(spmm_bwd_long_kernel<bf16>, dim3(L.n_long), dim3(128), 0, s, L, tt, rt, root_mask, want, (const bf16 *)dz,
                          (bf16 *)dx, partial, max_dim);
     else
-      hipLaunchKernelGGL(spmm_bwd_long_kernel<float>, dim3(L.n_long), dim3(128), 0, s, L, tt, rt, root_mask, (const float *)dz,
+      hipLaunchKernelGGL(spmm_bwd_long_kernel<float>, dim3(L.n_long), dim3(128), 0, s, L, tt, rt, root_mask, want, (const float *)dz,
                          (float *)dx, partial, max_dim);
     HGNN_HIP(hipGetLastError());
   }
@@ -347,17 +349,82 @@ __global__ void __launch_bounds__(256) relu_bias_bwd_kernel(TypeTab tt, int H, i
   }
 }
 
+// Same, 16 bytes per lane: a block owns 128 rows of one type, 256/(H/VEC) rows are in flight at a time.
+template <typename T>
+__global__ void __launch_bounds__(256) relu_bias_bwd_vec_kernel(TypeTab tt, int H, int relu, const T *__restrict__ g,
+                                                                 const T *__restrict__ h, T *__restrict__ gp, GradPtrTab gt) {
+  using V = Vec16<T>;
+  __shared__ float red[256 * V::N];
+  int b = blockIdx.x, t = 0;
+  for (;; ++t) {
+    const int nb = (tt.n_dst[t] + 127) / 128;
+    if (b < nb) break;
+    b -= nb;
+  }
+  const int chunks = H / V::N;          // <= 256
+  const int rif = 256 / chunks;         // rows in flight
+  const int c = threadIdx.x % chunks, rg = threadIdx.x / chunks;
+  const int r0 = tt.out_row_off[t] + b * 128;
+  const int r1 = min(r0 + 128, tt.out_row_off[t] + tt.n_dst[t]);
+  float sum[V::N];
+#pragma unroll
+  for (int i = 0; i < V::N; ++i) sum[i] = 0.f;
+  if (rg < rif) {
+    for (int r = r0 + rg; r < r1; r += rif) {
+      const int64_t i = ((int64_t)r * H) / V::N + c;
+      float v[V::N];
+#pragma unroll
+      for (int k = 0; k < V::N; ++k) v[k] = 0.f;
+      V::add(v, reinterpret_cast<const uint4 *>(g)[i]);
+      if (relu) {
+        float hv[V::N];
+#pragma unroll
+        for (int k = 0; k < V::N; ++k) hv[k] = 0.f;
+        V::add(hv, reinterpret_cast<const uint4 *>(h)[i]);
+#pragma unroll
+        for (int k = 0; k < V::N; ++k)
+          if (!(hv[k] > 0.f)) v[k] = 0.f;
+        reinterpret_cast<uint4 *>(gp)[i] = V::pack(v);
+      }
+#pragma unroll
+      for (int k = 0; k < V::N; ++k) sum[k] += v[k];
+    }
+  }
+  float *db = gt.dbias[t];
+  if (!db) return;
+#pragma unroll
+  for (int k = 0; k < V::N; ++k) red[threadIdx.x * V::N + k] = sum[k];
+  __syncthreads();
+  for (int col = threadIdx.x; col < H; col += 256) {
+    const int cc = col / V::N, k = col % V::N;
+    float a = 0.f;
+    for (int q = 0; q < rif; ++q) a += red[(q * chunks + cc) * V::N + k];
+    atomicAdd(db + col, a);
+  }
+}
+
 hgnn_status launch_relu_bias_bwd(hipStream_t s, int dtype, const TypeTab &tt, int H, int relu,
                                  const void *grad_h, const void *h, void *gp, const GradPtrTab &gt) {
+  const int vec = dtype == HGNN_BF16 ? 8 : 4;
+  const bool fast = H % vec == 0 && H / vec <= 256 && (((uintptr_t)grad_h | (uintptr_t)h | (uintptr_t)gp) & 15) == 0;
+  const int rpb = fast ? 128 : 64;
   int blocks = 0;
-  for (int t = 0; t < tt.num_types; ++t) blocks += (tt.n_dst[t] + 63) / 64;
+  for (int t = 0; t < tt.num_types; ++t) blocks += (tt.n_dst[t] + rpb - 1) / rpb;
   if (blocks == 0) return HGNN_OK;
-  if (dtype == HGNN_BF16)
+  if (fast) {
+    if (dtype == HGNN_BF16)
+      hipLaunchKernelGGL(relu_bias_bwd_vec_kernel<bf16>, dim3(blocks), dim3(256), 0, s, tt, H, relu, (const bf16 *)grad_h,
+                         (const bf16 *)h, (bf16 *)gp, gt);
+    else
+      hipLaunchKernelGGL(relu_bias_bwd_vec_kernel<float>, dim3(blocks), dim3(256), 0, s, tt, H, relu, (const float *)grad_h,
+                         (const float *)h, (float *)gp, gt);
+  } else if (dtype == HGNN_BF16) {
     hipLaunchKernelGGL(relu_bias_bwd_kernel<bf16>, dim3(blocks), dim3(256), 0, s, tt, H, relu, (const bf16 *)grad_h,
                        (const bf16 *)h, (bf16 *)gp, gt);
-  else
+  } else {
     hipLaunchKernelGGL(relu_bias_bwd_kernel<float>, dim3(blocks), dim3(256), 0, s, tt, H, relu, (const float *)grad_h,
                        (const float *)h, (float *)gp, gt);
+  }
   HGNN_HIP(hipGetLastError());
   return HGNN_OK;
 }
@@ -451,24 +518,30 @@ hgnn_status launch_bias_act(hipStream_t s, int dtype, const TypeTab &tt, const P
 template <typename T>
 __global__ void __launch_bounds__(256) xent_kernel(const T *__restrict__ logits, const int64_t *__restrict__ labels,
                                                     int64_t rows, int C, float *loss, T *__restrict__ grad) {
-  const int64_t row = (int64_t)blockIdx.x * 4 + (threadIdx.x >> 6);
-  const int lane = threadIdx.x & 63;
-  if (row >= rows) return;
-  const T *z = logits + row * C;
-  float m = -INFINITY;
-  for (int c = lane; c < C; c += 64) m = fmaxf(m, to_float(z[c]));
-  for (int o = 32; o > 0; o >>= 1) m = fmaxf(m, __shfl_xor(m, o));
-  float sum = 0.f;
-  for (int c = lane; c < C; c += 64) sum += __expf(to_float(z[c]) - m);
-  for (int o = 32; o > 0; o >>= 1) sum += __shfl_xor(sum, o);
-  const int lab = (int)labels[row];
-  const float inv_rows = 1.0f / (float)rows, inv_sum = 1.0f / sum;
-  for (int c = lane; c < C; c += 64) {
-    float p = __expf(to_float(z[c]) - m) * inv_sum;
-    if (c == lab) p -= 1.0f;
-    grad[row * C + c] = from_float<T>(p * inv_rows);
+  __shared__ float part[4];
+  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+  const float inv_rows = 1.0f / (float)rows;
+  float my_loss = 0.f;
+  for (int64_t row = (int64_t)blockIdx.x * 4 + wave; row < rows; row += (int64_t)gridDim.x * 4) {
+    const T *z = logits + row * C;
+    float m = -INFINITY;
+    for (int c = lane; c < C; c += 64) m = fmaxf(m, to_float(z[c]));
+    for (int o = 32; o > 0; o >>= 1) m = fmaxf(m, __shfl_xor(m, o));
+    float sum = 0.f;
+    for (int c = lane; c < C; c += 64) sum += __expf(to_float(z[c]) - m);
+    for (int o = 32; o > 0; o >>= 1) sum += __shfl_xor(sum, o);
+    const int lab = (int)labels[row];
+    const float inv_sum = 1.0f / sum;
+    for (int c = lane; c < C; c += 64) {
+      float p = __expf(to_float(z[c]) - m) * inv_sum;
+      if (c == lab) p -= 1.0f;
+      grad[row * C + c] = from_float<T>(p * inv_rows);
+    }
+    my_loss += (logf(sum) + m - to_float(z[lab])) * inv_rows;
   }
-  if (lane == 0) atomicAdd(loss, (logf(sum) + m - to_float(z[lab])) * inv_rows);
+  if (lane == 0) part[wave] = my_loss;
+  __syncthreads();
+  if (threadIdx.x == 0) atomicAdd(loss, part[0] + part[1] + part[2] + part[3]);
 }
 
 hgnn_status launch_xent(hipStream_t s, int dtype, const void *logits, const int64_t *labels, int64_t rows,
@@ -476,7 +549,7 @@ hgnn_status launch_xent(hipStream_t s, int dtype, const void *logits, const int6
   hgnn_status st = launch_fill_zero(s, loss, sizeof(float));
   if (st != HGNN_OK) return st;
   if (rows == 0) return HGNN_OK;
-  dim3 grid((unsigned)((rows + 3) / 4));
+  dim3 grid((unsigned)std::min<int64_t>(512, (rows + 3) / 4));
   if (dtype == HGNN_BF16)
     hipLaunchKernelGGL(xent_kernel<bf16>, grid, dim3(256), 0, s, (const bf16 *)logits, labels, rows, classes, loss, (bf16 *)grad);
   else

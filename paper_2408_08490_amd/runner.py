@@ -37,7 +37,9 @@ class Model:
     """Weights, feature stores and work buffers of one configuration on one GPU."""
 
     def __init__(self, schema, feat_dim, stores, layers, dtype="f32", loss="xent", target_type=0, device=0,
-                 host_threads=0):
+                 host_threads=0, first_layer_input_grad=None):
+        """first_layer_input_grad: per type 0/1, which vertex types need gradients w.r.t. their input
+        features in the first layer (learnable embeddings); None = all."""
         self.dev = torch.device("cuda", device)
         torch.cuda.set_device(self.dev)
         self.dtype, self.loss, self.target_type = dtype, loss, target_type
@@ -56,7 +58,8 @@ class Model:
             dw_root = [None if w is None else torch.empty(w.shape, **f32) for w in w_root]
             dbias = [None if b is None else torch.empty(b.shape, **f32) for b in bias]
             self.weights.append(dict(w_rel=w_rel, w_root=w_root, bias=bias, dw_rel=dw_rel, dw_root=dw_root, dbias=dbias))
-            self.layers.append(B.Layer(self.ctx, lw.in_dim, lw.out_dim, lw.relu, w_rel, w_root, bias, dw_rel, dw_root, dbias))
+            self.layers.append(B.Layer(self.ctx, lw.in_dim, lw.out_dim, lw.relu, w_rel, w_root, bias, dw_rel, dw_root, dbias,
+                                       input_grad=first_layer_input_grad if not self.layers else None))
         self.loss_dev = torch.zeros(1, device=self.dev, dtype=torch.float32)
         self._buf = {}
 

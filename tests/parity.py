@@ -55,7 +55,8 @@ def oracle_run(cfg, g, mb, ws):
     return res
 
 
-def run_case(index, scale=1.0, batch=None, verbose=False, use_edge_id=True, check_naive=False, graph=None):
+def run_case(index, scale=1.0, batch=None, verbose=False, use_edge_id=True, check_naive=False, graph=None,
+             input_grad=None):
     import torch
     from paper_2408_08490_amd.runner import Model
     cfg, g, mb, ws = prepare_inputs(index, scale, batch, graph)
@@ -64,7 +65,7 @@ def run_case(index, scale=1.0, batch=None, verbose=False, use_edge_id=True, chec
     ref = oracle_run(cfg, g, mb, ws)
     t_oracle = time.time() - t0
     model = Model(sch, g.feat_dim, g.stores, ws, dtype=cfg.dtype, loss=("xent" if cfg.loss == "xent" else "dot"),
-                  target_type=mb.target_type)
+                  target_type=mb.target_type, first_layer_input_grad=input_grad)
     bt = model.prepare(mb, g.edge_type, use_edge_id=use_edge_id)
     out = model.run(bt)
     torch.cuda.synchronize()
@@ -107,8 +108,14 @@ def run_case(index, scale=1.0, batch=None, verbose=False, use_edge_id=True, chec
                 chk(f"L{l}.dw_root{t}", w["dw_root"][t].cpu().numpy(), gr["dw_root"][t])
             if gr["dbias"][t] is not None:
                 chk(f"L{l}.dbias{t}", w["dbias"][t].cpu().numpy(), gr["dbias"][t])
-        want_dx = np.concatenate([d.ravel() for d in gr["dx"]])
-        chk(f"L{l}.dx", out["dx"][l].float().cpu().numpy(), want_dx)
+        got_dx = out["dx"][l].float().cpu().numpy()
+        if l == 0 and input_grad is not None:          # rows of types without input gradients are left unwritten
+            eo = np.concatenate([[0], np.cumsum([d.size for d in gr["dx"]])])
+            keep = [t for t in range(sch.num_types) if input_grad[t]]
+            chk(f"L{l}.dx", np.concatenate([got_dx[eo[t]: eo[t + 1]] for t in keep]),
+                np.concatenate([gr["dx"][t].ravel() for t in keep]))
+        else:
+            chk(f"L{l}.dx", got_dx, np.concatenate([d.ravel() for d in gr["dx"]]))
     if cfg.loss == "xent":
         chk("loss", out["loss"].cpu().numpy(), np.array([ref["loss"]]))
     if check_naive:

@@ -27,5 +27,10 @@ def test_config2_bf16_scaled():
     _assert_ok(run_case(2, scale=0.05, batch=512, verbose=True, check_naive=True))
 
 
+def test_config2_bf16_scaled_without_input_grads_of_fixed_features():
+    # T0 carries fixed features, T1-T3 learnable embeddings: only those need input gradients in layer 1
+    _assert_ok(run_case(2, scale=0.05, batch=512, verbose=True, input_grad=[0, 1, 1, 1]))
+
+
 def test_config3_many_types_fp32_scaled():
     _assert_ok(run_case(3, scale=0.02, batch=128, verbose=True, check_naive=True))
