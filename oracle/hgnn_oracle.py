@@ -168,10 +168,13 @@ def rgcn_layer_forward(x, rel_edges, rel_src, rel_dst, n_dst, w_rel, w_root, bia
     return h, cache
 
 
-def rgcn_layer_backward(cache, grad_h):
+def rgcn_layer_backward(cache, grad_h, relu_mask=None):
     """Reverse of `rgcn_layer_forward`, one step at a time.  grad_h: per type
     [n_dst[t], H].  Returns (dx per type, dw_rel, dw_root, dbias); parameters that
-    received no contribution get zeros (None where the parameter is None)."""
+    received no contribution get zeros (None where the parameter is None).
+    relu_mask (per type boolean [n_dst[t], H], optional) replaces the decision
+    `pre > 0` of the ReLU's backward; parity tests use it to settle units whose
+    pre-activation is zero to within rounding, where either decision is valid."""
     x, nbrs, pre = cache["x"], cache["nbrs"], cache["pre"]
     rel_src, rel_dst, n_dst = cache["rel_src"], cache["rel_dst"], cache["n_dst"]
     w_rel, w_root, bias = cache["w_rel"], cache["w_root"], cache["bias"]
@@ -179,7 +182,12 @@ def rgcn_layer_backward(cache, grad_h):
     gp = []
     for t in range(T):
         g = np.asarray(grad_h[t], dtype=F64).reshape(pre[t].shape)
-        gp.append(g * (pre[t] > 0) if cache["relu"] else g.copy())
+        if not cache["relu"]:
+            gp.append(g.copy())
+        elif relu_mask is not None:
+            gp.append(g * np.asarray(relu_mask[t], dtype=bool).reshape(pre[t].shape))
+        else:
+            gp.append(g * (pre[t] > 0))
     dx = [np.zeros_like(a) for a in x]
     dw_root, dbias = [], []
     for t in range(T):
@@ -258,18 +266,28 @@ def softmax_xent(logits, labels):
 # --------------------------------------------------------------------------- #
 # Whole model: layers stacked, each layer's output rows are the next layer's input
 # --------------------------------------------------------------------------- #
-def rgcn_model_forward_backward(x0, blocks_sel, rel_src, rel_dst, blocks_n_dst, layers, loss,
-                                labels=None, grad_out=None, target_type=0):
-    """x0: per type first-layer input; blocks_sel[l]: per-relation selected edges of
-    layer l; layers[l]: dict(w_rel, w_root, bias, relu).  loss: "xent" (mean softmax
-    cross-entropy of the target type's last-layer rows) or "dot" (sum of grad_out*h).
-    Returns dict with per-layer outputs, loss value and all gradients."""
+def rgcn_model_forward(x0, blocks_sel, rel_src, rel_dst, blocks_n_dst, layers):
+    """Layers stacked: returns per-layer outputs `h` and the per-layer caches."""
     xs, caches, hs = [x0], [], []
     for l, lw in enumerate(layers):
         h, c = rgcn_layer_forward(xs[-1], blocks_sel[l], rel_src, rel_dst, blocks_n_dst[l],
                                   lw["w_rel"], lw["w_root"], lw["bias"], lw["relu"])
         caches.append(c); hs.append(h); xs.append(h)
-    T = len(x0)
+    return dict(h=hs, caches=caches)
+
+
+def rgcn_model_forward_backward(x0, blocks_sel, rel_src, rel_dst, blocks_n_dst, layers, loss,
+                                labels=None, grad_out=None, target_type=0, forward=None, relu_masks=None,
+                                num_types=None):
+    """x0: per type first-layer input; blocks_sel[l]: per-relation selected edges of
+    layer l; layers[l]: dict(w_rel, w_root, bias, relu).  loss: "xent" (mean softmax
+    cross-entropy of the target type's last-layer rows) or "dot" (sum of grad_out*h).
+    `forward` may carry the result of `rgcn_model_forward` (then it is not recomputed);
+    `relu_masks[l]` is passed to layer l's backward.
+    Returns dict with per-layer outputs, loss value and all gradients."""
+    fw = forward if forward is not None else rgcn_model_forward(x0, blocks_sel, rel_src, rel_dst, blocks_n_dst, layers)
+    hs, caches = fw["h"], fw["caches"]
+    T = len(x0) if x0 is not None else num_types
     if loss == "xent":
         val, g_t = softmax_xent(hs[-1][target_type], labels)
         g = [np.zeros_like(h) for h in hs[-1]]
@@ -279,7 +297,7 @@ def rgcn_model_forward_backward(x0, blocks_sel, rel_src, rel_dst, blocks_n_dst, 
         val = sum(float((g[t] * hs[-1][t]).sum()) for t in range(T))
     grads = [None] * len(layers)
     for l in reversed(range(len(layers))):
-        dx, dw_rel, dw_root, dbias = rgcn_layer_backward(caches[l], g)
+        dx, dw_rel, dw_root, dbias = rgcn_layer_backward(caches[l], g, None if relu_masks is None else relu_masks[l])
         grads[l] = dict(dw_rel=dw_rel, dw_root=dw_root, dbias=dbias, dx=dx)
         g = dx
-    return dict(h=hs, loss=val, grads=grads, dx0=g)
+    return dict(h=hs, loss=val, grads=grads, dx0=g, caches=caches)

@@ -96,26 +96,76 @@ def run_case(index, scale=1.0, batch=None, verbose=False, use_edge_id=True, chec
     chk("row_off", out["row_off"], want_ro, exact=True)
     chk("elem_off", out["elem_off"], want_eo, exact=True)
     chk("x_merged", out["x0"].float().cpu().numpy(), ref["x0_flat"].astype(np.float32), exact=True)
-    # floating point outputs
+    # floating point outputs.  Every tensor must meet the L2 criterion against the plain oracle.  For the
+    # max-norm criterion the gradients are compared against the oracle evaluated with the SAME ReLU decisions
+    # as the kernel on the units whose exact pre-activation is zero to within the kernel's rounding
+    # (|pre| < AMBIG * rms(pre)): there either decision is valid, a flipped decision moves a whole column of a
+    # weight gradient, and the kernel takes it in fp32.  The kernel's decisions are first checked to be valid
+    # (equal to the oracle's wherever the pre-activation is not ambiguous).
+    AMBIG = {"f32": 1e-5, "bf16": 1e-4}[cfg.dtype]
+    masks, n_amb, n_units = [], 0, 0
+    for l in range(len(ws)):
+        if not ws[l].relu:
+            masks.append(None)
+            continue
+        hg = out["h"][l].float().cpu().numpy().reshape(-1, ws[l].out_dim)
+        ml, r0 = [], 0
+        for t in range(sch.num_types):
+            pre = ref["caches"][l]["pre"][t]
+            hgt = hg[r0: r0 + pre.shape[0]]
+            r0 += pre.shape[0]
+            if pre.size == 0:
+                ml.append(np.zeros(pre.shape, bool))
+                continue
+            amb = np.abs(pre) < AMBIG * np.sqrt(np.mean(pre * pre))
+            if not np.array_equal((hgt > 0)[~amb], (pre > 0)[~amb]):
+                ok = False
+                report[f"L{l}.relu_decisions_type{t}"] = "MISMATCH"
+            ml.append(np.where(amb, hgt > 0, pre > 0))
+            n_amb += int(amb.sum()); n_units += amb.size
+        masks.append(ml)
+    report["ambiguous_relu_units"] = (n_amb, n_units)
+    if n_units and n_amb > 1e-3 * n_units:
+        ok = False
+    ref_tb = ref
+    if n_amb:
+        layers = [dict(w_rel=lw.w_rel, w_root=lw.w_root, bias=lw.bias, relu=lw.relu) for lw in ws]
+        ref_tb = O.rgcn_model_forward_backward(None, None, sch.rel_src, sch.rel_dst, None, layers,
+                                               "xent" if cfg.loss == "xent" else "dot", labels=mb.labels,
+                                               grad_out=mb.grad_out, target_type=mb.target_type,
+                                               forward=dict(h=ref["h"], caches=ref["caches"]), relu_masks=masks,
+                                               num_types=sch.num_types)
+
+    def chk2(name, got, want_plain, want_tb):
+        nonlocal ok
+        e_plain, e_tb = rel_errors(got, want_plain), rel_errors(got, want_tb)
+        good = e_plain[1] <= tol and e_tb[0] <= tol and e_tb[1] <= tol
+        report[name] = (round(e_tb[0], 7), round(e_plain[1], 7))
+        if not good:
+            ok = False
+            if verbose:
+                print("FAIL", name, "plain", e_plain, "tie-broken", e_tb, flush=True)
+
     for l in range(len(ws)):
         want = np.concatenate([h.ravel() for h in ref["h"][l]])
         chk(f"L{l}.h", out["h"][l].float().cpu().numpy(), want)
-        gr, w = ref["grads"][l], model.weights[l]
+        gr, gt, w = ref["grads"][l], ref_tb["grads"][l], model.weights[l]
         for r in range(sch.num_rels):
-            chk(f"L{l}.dw_rel{r}", w["dw_rel"][r].cpu().numpy(), gr["dw_rel"][r])
+            chk2(f"L{l}.dw_rel{r}", w["dw_rel"][r].cpu().numpy(), gr["dw_rel"][r], gt["dw_rel"][r])
         for t in range(sch.num_types):
             if gr["dw_root"][t] is not None:
-                chk(f"L{l}.dw_root{t}", w["dw_root"][t].cpu().numpy(), gr["dw_root"][t])
+                chk2(f"L{l}.dw_root{t}", w["dw_root"][t].cpu().numpy(), gr["dw_root"][t], gt["dw_root"][t])
             if gr["dbias"][t] is not None:
-                chk(f"L{l}.dbias{t}", w["dbias"][t].cpu().numpy(), gr["dbias"][t])
+                chk2(f"L{l}.dbias{t}", w["dbias"][t].cpu().numpy(), gr["dbias"][t], gt["dbias"][t])
         got_dx = out["dx"][l].float().cpu().numpy()
         if l == 0 and input_grad is not None:          # rows of types without input gradients are left unwritten
             eo = np.concatenate([[0], np.cumsum([d.size for d in gr["dx"]])])
             keep = [t for t in range(sch.num_types) if input_grad[t]]
-            chk(f"L{l}.dx", np.concatenate([got_dx[eo[t]: eo[t + 1]] for t in keep]),
-                np.concatenate([gr["dx"][t].ravel() for t in keep]))
+            chk2(f"L{l}.dx", np.concatenate([got_dx[eo[t]: eo[t + 1]] for t in keep]),
+                 np.concatenate([gr["dx"][t].ravel() for t in keep]), np.concatenate([gt["dx"][t].ravel() for t in keep]))
         else:
-            chk(f"L{l}.dx", got_dx, np.concatenate([d.ravel() for d in gr["dx"]]))
+            chk2(f"L{l}.dx", got_dx, np.concatenate([d.ravel() for d in gr["dx"]]),
+                 np.concatenate([d.ravel() for d in gt["dx"]]))
     if cfg.loss == "xent":
         chk("loss", out["loss"].cpu().numpy(), np.array([ref["loss"]]))
     if check_naive:

@@ -34,3 +34,11 @@ def test_config2_bf16_scaled_without_input_grads_of_fixed_features():
 
 def test_config3_many_types_fp32_scaled():
     _assert_ok(run_case(3, scale=0.02, batch=128, verbose=True, check_naive=True))
+
+
+def test_config2_full_size_headline_workload():
+    """The workload bench.py times (full graph, 4096 targets, bf16, hidden 512, input gradients only for the
+    learnable embeddings), compared element by element with the oracle."""
+    rep = run_case(2, scale=1.0, verbose=True, input_grad=[0, 1, 1, 1])
+    _assert_ok(rep)
+    assert rep["sizes"][0][2] > 900_000 and rep["sizes"][1][1] == 4096
