@@ -119,8 +119,9 @@ static hgnn_status make_plan(hgnn_ctx *ctx, hgnn_graph *g, int32_t layer, const 
   if (zr / 4 >= ((size_t)1 << 32) || w / 4 >= ((size_t)1 << 32)) HGNN_FAIL(HGNN_EOVERFLOW, "work area too large");
   pl.saved_bytes = align_up(std::max<size_t>(z, 1) * pl.es, 256);
   size_t o = 0;
-  pl.off_wt = o;      o += align_up(std::max<size_t>(w, 1) * pl.es, 256);
-  pl.off_gp = o;      o += align_up(std::max<size_t>((size_t)pl.total_dst * pl.H, 1) * pl.es, 256);
+  const size_t Hpad = ((size_t)pl.H + vec - 1) / vec * vec;  // the backward pads H to whole 16-byte pieces when needed
+  pl.off_wt = o;      o += align_up(std::max<size_t>(w / pl.H * Hpad, 1) * pl.es, 256);
+  pl.off_gp = o;      o += align_up(std::max<size_t>((size_t)pl.total_dst * Hpad, 1) * pl.es, 256);
   pl.off_dz = o;      o += align_up(std::max<size_t>(zr, 1) * pl.es, 256);
   pl.off_partial = o; o += align_up(std::max<size_t>((size_t)L.max_chunks * std::max(pl.max_dim, 1), 1) * 4, 256);
   pl.off_acc32 = o;   o += align_up(std::max<size_t>((size_t)pl.total_dst * pl.H, 1) * 4, 256);
@@ -473,6 +474,12 @@ static hgnn_status fwd_common(hgnn_ctx *ctx, void *stream, hgnn_graph *g, int32_
   SegTab tl;
   fwd_tiles(pl, tl);
   const int R = ctx->R, T = ctx->T;
+  uint32_t live[kMaxR / 32] = {0};
+  {
+    const int32_t *reo = g->slab.host + g->L[layer].o_rel_edge_off;
+    for (int r = 0; r < R; ++r)
+      if (reo[r + 1] > reo[r]) live[r >> 5] |= 1u << (r & 31);
+  }
   {
     Probe pb(ctx, s, HGNN_K_TRANSPOSE_W, layer);
     if ((st = launch_transpose_weights(s, ctx->dtype, pl.tt, pl.rt, pl.pt, pl.wt, pl.H, wtb)) != HGNN_OK) return st;
@@ -486,7 +493,7 @@ static hgnn_status fwd_common(hgnn_ctx *ctx, void *stream, hgnn_graph *g, int32_
     if (pl.dev.rows > 0) ++n;
     {
       Probe pb(ctx, s, HGNN_K_GEMM_FWD, layer);
-      if ((st = launch_gemm_fwd(s, ctx->dtype, pl.dev, pl.tt, pl.rt, pl.pt, pl.wt, tl, pl.H, p->relu, x, saved, zlo, wtb, h, -1, nullptr)) != HGNN_OK) return st;
+      if ((st = launch_gemm_fwd(s, ctx->dtype, pl.dev, pl.tt, pl.rt, pl.pt, pl.wt, tl, live, pl.H, p->relu, x, saved, zlo, wtb, h, -1, nullptr)) != HGNN_OK) return st;
     }
     if (tl.tile_off[T] > 0) ++n;
   } else {
@@ -507,7 +514,7 @@ static hgnn_status fwd_common(hgnn_ctx *ctx, void *stream, hgnn_graph *g, int32_
       const int d = ctx->rel_dst[r];
       for (int t = 0; t < T; ++t)
         one.tile_off[t + 1] = one.tile_off[t] + (t == d ? tl.tile_off[t + 1] - tl.tile_off[t] : 0);
-      if ((st = launch_gemm_fwd(s, ctx->dtype, pl.dev, pl.tt, pl.rt, pl.pt, pl.wt, one, pl.H, 0, x, saved, zlo, wtb, h, r, acc32)) != HGNN_OK) return st;
+      if ((st = launch_gemm_fwd(s, ctx->dtype, pl.dev, pl.tt, pl.rt, pl.pt, pl.wt, one, live, pl.H, 0, x, saved, zlo, wtb, h, r, acc32)) != HGNN_OK) return st;
       ++n;
     }
     for (int t = 0; t < T; ++t) {
@@ -518,7 +525,7 @@ static hgnn_status fwd_common(hgnn_ctx *ctx, void *stream, hgnn_graph *g, int32_
         one.num_segs = T;
         for (int u = 0; u < T; ++u)
           one.tile_off[u + 1] = one.tile_off[u] + (u == t ? tl.tile_off[u + 1] - tl.tile_off[u] : 0);
-        if ((st = launch_gemm_fwd(s, ctx->dtype, pl.dev, pl.tt, pl.rt, pl.pt, pl.wt, one, pl.H, 0, x, saved, zlo, wtb, h, R + t, acc32)) != HGNN_OK) return st;
+        if ((st = launch_gemm_fwd(s, ctx->dtype, pl.dev, pl.tt, pl.rt, pl.pt, pl.wt, one, live, pl.H, 0, x, saved, zlo, wtb, h, R + t, acc32)) != HGNN_OK) return st;
         ++n;
       }
       if ((st = launch_bias_act(s, ctx->dtype, pl.tt, pl.pt, pl.H, p->relu, t, acc32, h)) != HGNN_OK) return st;
@@ -591,43 +598,76 @@ hgnn_status hgnn_layer_bwd(hgnn_ctx *ctx, void *stream, hgnn_graph *g, int32_t l
     Probe pb(ctx, s, HGNN_K_ZERO_GRADS, layer);
     if ((st = launch_zero_grads(s, pl.tt, pl.rt, gt, pl.H)) != HGNN_OK) return st;
   }
+  // The GEMMs want 16-byte aligned rows.  When H is not a multiple of 16 bytes (or a weight pointer is not
+  // aligned) they run on zero-padded copies: G' gets leading dimension Hp in the scratch area (written by the
+  // ReLU/bias pass, which then always runs) and so do the weights.
+  const int vec = 16 / pl.es;
+  const int Hp = (pl.H + vec - 1) / vec * vec;
+  bool pad = Hp != pl.H;
+  for (int r = 0; r < R; ++r) pad |= ((uintptr_t)p->w_rel[r] & 15) != 0;
+  for (int t = 0; t < T; ++t) pad |= p->w_root[t] && ((uintptr_t)p->w_root[t] & 15) != 0;
+  int ldg = pl.H;
+  PtrTab wpt = pl.pt;
+  if (pad && pl.total_dst > 0) {
+    ldg = Hp;
+    WtTab wo;
+    std::memset(&wo, 0, sizeof(wo));
+    size_t w = 0;
+    char *wp = sc + pl.off_wt;
+    for (int r = 0; r < R; ++r) {
+      wo.rel4[r] = (uint32_t)(w / 4);
+      wpt.w_rel[r] = wp + w * pl.es;
+      w += (size_t)p->in_dim[ctx->rel_src[r]] * Hp;
+    }
+    for (int t = 0; t < T; ++t) {
+      wo.root4[t] = (uint32_t)(w / 4);
+      if (p->w_root[t]) {
+        wpt.w_root[t] = wp + w * pl.es;
+        w += (size_t)p->in_dim[t] * Hp;
+      }
+    }
+    if (grad_x_merged)
+      if ((st = launch_pad_weights(s, ctx->dtype, pl.tt, pl.rt, pl.pt, wo, pl.H, Hp, wp)) != HGNN_OK) return st;
+  }
   const void *gp = grad_h;
-  if (pl.total_dst > 0 && (p->relu || any_db)) {
+  if (pl.total_dst > 0 && (p->relu || any_db || ldg != pl.H)) {
     void *gpw = sc + pl.off_gp;
     Probe pb(ctx, s, HGNN_K_RELU_BIAS_BWD, layer);
-    if ((st = launch_relu_bias_bwd(s, ctx->dtype, pl.tt, pl.H, p->relu, grad_h, h_out, gpw, gt)) != HGNN_OK) return st;
-    if (p->relu) gp = gpw;
+    if ((st = launch_relu_bias_bwd(s, ctx->dtype, pl.tt, pl.H, ldg, p->relu, grad_h, h_out, gpw, gt)) != HGNN_OK) return st;
+    if (p->relu || ldg != pl.H) gp = gpw;
   }
+  const bool fast = (ldg % vec) == 0;
   if (any_dw && pl.total_dst > 0) {
-    // split the reduction over destination rows so that the launch has a few blocks per CU
+    // split the reduction over destination rows so that the launch has about two blocks per CU; every extra
+    // split costs a tile's worth of atomic adds
     SegTab tl;
     std::memset(&tl, 0, sizeof(tl));
     tl.num_segs = R + T;
-    int64_t base_tiles = 0;
-    for (int sgi = 0; sgi < R + T; ++sgi) {
+    auto live_seg = [&](int sgi, int &d, int &F) {
       const bool is_rel = sgi < R;
-      const int d = is_rel ? ctx->rel_dst[sgi] : sgi - R;
-      const int F = pl.tt.in_dim[is_rel ? ctx->rel_src[sgi] : d];
-      const bool live = (is_rel ? (reo[sgi + 1] > reo[sgi] && gt.dw_rel[sgi]) : gt.dw_root[d] != nullptr) && pl.tt.n_dst[d] > 0;
-      if (live) base_tiles += (int64_t)((F + 127) / 128) * ((pl.H + 127) / 128) * ((pl.tt.n_dst[d] + 1023) / 1024);
-    }
-    // every split covers `split_rows` destination rows (a multiple of the K tile)
-    int split_rows = 1024;
-    while (base_tiles > 0 && base_tiles < 1024 && split_rows > 128) {
+      d = is_rel ? ctx->rel_dst[sgi] : sgi - R;
+      F = pl.tt.in_dim[is_rel ? ctx->rel_src[sgi] : d];
+      return (is_rel ? (reo[sgi + 1] > reo[sgi] && gt.dw_rel[sgi]) : gt.dw_root[d] != nullptr) && pl.tt.n_dst[d] > 0;
+    };
+    int split_rows = 4096;
+    for (;;) {
+      int64_t tiles = 0;
+      for (int sgi = 0; sgi < R + T; ++sgi) {
+        int d, F;
+        if (live_seg(sgi, d, F))
+          tiles += (int64_t)((F + 127) / 128) * ((pl.H + 127) / 128) * ((pl.tt.n_dst[d] + split_rows - 1) / split_rows);
+      }
+      if (tiles >= 512 || split_rows <= 128) break;
       split_rows /= 2;
-      base_tiles *= 2;
     }
     for (int sgi = 0; sgi < R + T; ++sgi) {
-      const bool is_rel = sgi < R;
-      const int d = is_rel ? ctx->rel_dst[sgi] : sgi - R;
-      const int F = pl.tt.in_dim[is_rel ? ctx->rel_src[sgi] : d];
-      const bool live = (is_rel ? (reo[sgi + 1] > reo[sgi] && gt.dw_rel[sgi]) : gt.dw_root[d] != nullptr) && pl.tt.n_dst[d] > 0;
-      int cnt = 0;
-      if (live) cnt = ((F + 127) / 128) * ((pl.H + 127) / 128) * ((pl.tt.n_dst[d] + split_rows - 1) / split_rows);
+      int d, F, cnt = 0;
+      if (live_seg(sgi, d, F))
+        cnt = ((F + 127) / 128) * ((pl.H + 127) / 128) * ((pl.tt.n_dst[d] + split_rows - 1) / split_rows);
       tl.tile_off[sgi + 1] = tl.tile_off[sgi] + cnt;
     }
     Probe pb(ctx, s, HGNN_K_GEMM_DW, layer);
-    if ((st = launch_gemm_dw(s, ctx->dtype, pl.dev, pl.tt, pl.rt, gt, tl, split_rows, pl.H, x_merged, saved, gp)) != HGNN_OK) return st;
+    if ((st = launch_gemm_dw(s, ctx->dtype, pl.dev, pl.tt, pl.rt, gt, tl, split_rows, pl.H, ldg, fast, x_merged, saved, gp)) != HGNN_OK) return st;
   }
   if (grad_x_merged && pl.dev.src_rows > 0) {
     SegTab tl;
@@ -635,7 +675,7 @@ hgnn_status hgnn_layer_bwd(hgnn_ctx *ctx, void *stream, hgnn_graph *g, int32_t l
     void *dz = sc + pl.off_dz;
     {
       Probe pb(ctx, s, HGNN_K_GEMM_DA, layer);
-      if ((st = launch_gemm_da(s, ctx->dtype, pl.dev, pl.tt, pl.rt, pl.pt, tl, pl.H, gp, dz)) != HGNN_OK) return st;
+      if ((st = launch_gemm_da(s, ctx->dtype, pl.dev, pl.tt, pl.rt, wpt, tl, ldg, fast, gp, dz)) != HGNN_OK) return st;
     }
     Probe pb(ctx, s, HGNN_K_SPMM_BWD, layer);
     uint32_t want = 0;

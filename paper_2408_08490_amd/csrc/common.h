@@ -182,18 +182,23 @@ hgnn_status launch_transpose_weights(hipStream_t s, int dtype, const TypeTab &tt
 // mode 0: all segments of every type fused (bias/activation epilogue, writes h)
 // mode 1: one segment `only_seg`, accumulated into the fp32 buffer acc32 (naive launch structure)
 hgnn_status launch_gemm_fwd(hipStream_t s, int dtype, const LayerDev &L, const TypeTab &tt, const RelTab &rt,
-                            const PtrTab &pt, const WtTab &wt, const SegTab &tiles, int H, int relu,
-                            const void *x, const void *z, const void *zlo, const void *wt_buf, void *h,
+                            const PtrTab &pt, const WtTab &wt, const SegTab &tiles, const uint32_t *live_mask, int H,
+                            int relu, const void *x, const void *z, const void *zlo, const void *wt_buf, void *h,
                             int only_seg, float *acc32);
 hgnn_status launch_bias_act(hipStream_t s, int dtype, const TypeTab &tt, const PtrTab &pt, int H, int relu,
                             int type, const float *acc32, void *h);
+// gp has leading dimension ldg >= H (zero beyond H), and so have the weights in `pt`
 hgnn_status launch_gemm_da(hipStream_t s, int dtype, const LayerDev &L, const TypeTab &tt, const RelTab &rt,
-                           const PtrTab &pt, const SegTab &tiles, int H, const void *gp, void *dz);
+                           const PtrTab &pt, const SegTab &tiles, int ldg, bool fast, const void *gp, void *dz);
 hgnn_status launch_gemm_dw(hipStream_t s, int dtype, const LayerDev &L, const TypeTab &tt, const RelTab &rt,
-                           const GradPtrTab &gt, const SegTab &tiles, int split_rows, int H, const void *x,
-                           const void *z, const void *gp);
-hgnn_status launch_relu_bias_bwd(hipStream_t s, int dtype, const TypeTab &tt, int H, int relu,
+                           const GradPtrTab &gt, const SegTab &tiles, int split_rows, int H, int ldg, bool fast,
+                           const void *x, const void *z, const void *gp);
+// gp (leading dimension ldo >= H, zero beyond H) = grad_h * [h > 0] (or a plain copy without ReLU); dbias = column sums
+hgnn_status launch_relu_bias_bwd(hipStream_t s, int dtype, const TypeTab &tt, int H, int ldo, int relu,
                                  const void *grad_h, const void *h, void *gp, const GradPtrTab &gt);
+// zero-padded copies [F x Hp] of every weight
+hgnn_status launch_pad_weights(hipStream_t s, int dtype, const TypeTab &tt, const RelTab &rt, const PtrTab &pt,
+                               const WtTab &wo, int H, int Hp, void *out);
 hgnn_status launch_zero_grads(hipStream_t s, const TypeTab &tt, const RelTab &rt, const GradPtrTab &gt, int H);
 hgnn_status launch_fill_zero(hipStream_t s, void *p, size_t bytes);
 hgnn_status launch_xent(hipStream_t s, int dtype, const void *logits, const int64_t *labels, int64_t rows,

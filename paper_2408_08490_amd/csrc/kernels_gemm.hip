@@ -10,6 +10,9 @@
 // two K-steps are in flight while the current one is multiplied, and LDS is double-buffered so that a
 // step costs one barrier.  An operand is kept in LDS the way it lies in memory: "KC" = the reduction
 // index is contiguous (rows = output index), "KS" = the output index is contiguous.
+// Every kernel exists in a FAST form (all operands 16-byte aligned: per-thread offsets are computed once
+// per segment, a K-step is 8 vector loads from wave-uniform bases) and a generic form (element-wise,
+// zero-filled loads) for unaligned shapes.
 #include "common.h"
 #include "device_types.h"
 
@@ -38,68 +41,99 @@ template <typename T> constexpr int lds_elems() {
 template <typename T> struct Seg {
   const T *A, *B;
   int lda, ldb, kb, ke;
-  int a_vec, b_vec;  // 16-byte loads allowed (base and leading dimension aligned)
 };
 
 // One operand tile on its way global -> registers -> LDS.  The tile is ROWS x COLS in the operand's own
-// row-major orientation (COLS contiguous); out-of-range parts are zero-filled.
-template <typename T, int ROWS, int COLS, int PITCH>
+// row-major orientation (COLS contiguous).
+//  * FAST: per-thread byte offsets are computed once per segment (`setup`); a full K-step is NV 16-byte
+//    loads from a wave-uniform base plus those offsets and nothing else.  Pieces whose OUTPUT index is out of
+//    range read a clamped address and are stored as they are: they only feed output rows / columns that the
+//    epilogue never writes.  Only the last, partial K-step of a segment masks (and zero-fills) pieces.
+//  * generic: element-wise, zero-filled loads.
+template <typename T, int ROWS, int COLS, int PITCH, bool KC>
 struct TileMover {
   static constexpr int VEC = 16 / sizeof(T), VPR = COLS / VEC, NV = ROWS * VPR / kThreads;
   static_assert(ROWS * VPR % kThreads == 0, "tile must split evenly over the block");
+  typedef const u32x4 __attribute__((address_space(1))) *gvec_t;
+  typedef const unsigned short __attribute__((address_space(1))) *g16_t;
+  typedef const unsigned int __attribute__((address_space(1))) *g32_t;
+  typedef const char __attribute__((address_space(1))) *gbyte_t;
   u32x4 reg[NV];
-  unsigned okmask = 0;
-  // Branch-free inside either path (out-of-range pieces read a clamped address and are zeroed afterwards),
-  // so that all loads of a K-step are issued back to back and waited for once, when they are stored to LDS.
-  // vec_ok promises 16-byte aligned rows and ncols % VEC == 0.
-  __device__ __forceinline__ void load(const T *base, int64_t ld, int nrows, int ncols, int r0, int c0, bool vec_ok) {
-    typedef const u32x4 __attribute__((address_space(1))) *gvec_t;
-    typedef const unsigned short __attribute__((address_space(1))) *g16_t;
-    typedef const unsigned int __attribute__((address_space(1))) *g32_t;
-    if (vec_ok) {
+  unsigned voff[NV];    // byte offset of this thread's pieces from the K-step's base (FAST)
+  unsigned okmask = ~0u;  // pieces to keep; the others are stored as zero
+
+  // `o0` = first output index of the tile, `extent` = number of valid output indices, ld in elements.
+  __device__ __forceinline__ void setup(int ld, int extent, int o0) {
 #pragma unroll
-      for (int i = 0; i < NV; ++i) {
-        const int v = threadIdx.x + i * kThreads;
-        const int gr = r0 + v / VPR, gc = c0 + (v % VPR) * VEC;
-        const bool ok = gr < nrows && gc < ncols;
-        const int64_t off = ok ? (int64_t)gr * ld + gc : 0;
-        reg[i] = *(gvec_t)(base + off);
-        okmask = ok ? (okmask | (1u << i)) : (okmask & ~(1u << i));  // zeroing waits until the LDS store
-      }
-    } else {
-#pragma unroll
-      for (int i = 0; i < NV; ++i) {
-        const int v = threadIdx.x + i * kThreads;
-        const int gr = r0 + v / VPR, gc = c0 + (v % VPR) * VEC;
-        unsigned int e[VEC];
-#pragma unroll
-        for (int j = 0; j < VEC; ++j) {
-          const bool ok = gr < nrows && gc + j < ncols;
-          const T *p = ok ? base + (int64_t)gr * ld + gc + j : base;
-          unsigned int x;
-          if constexpr (sizeof(T) == 2) x = *(g16_t)p; else x = *(g32_t)p;
-          e[j] = ok ? x : 0u;
-        }
-        if constexpr (sizeof(T) == 2)
-          reg[i] = u32x4{e[0] | (e[1] << 16), e[2] | (e[3] << 16), e[4] | (e[5] << 16), e[6] | (e[7] << 16)};
-        else
-          reg[i] = u32x4{e[0], e[1], e[2], e[3]};
-        okmask |= 1u << i;
+    for (int i = 0; i < NV; ++i) {
+      const int v = threadIdx.x + i * kThreads;
+      const int r = v / VPR, c = (v % VPR) * VEC;
+      if constexpr (KC) {  // rows = output index, cols = k
+        const int o = o0 + r < extent ? o0 + r : 0;
+        voff[i] = (unsigned)((o * ld + c) * (int)sizeof(T));
+      } else {             // rows = k, cols = output index
+        const int o = o0 + c < extent ? o0 + c : 0;
+        voff[i] = (unsigned)((r * ld + o) * (int)sizeof(T));
       }
     }
   }
-  __device__ __forceinline__ void store(T *lds) const {
+  // base = operand base advanced to the K-step (KC: + k0 elements, KS: + k0 rows); krem = ke - k0 > 0
+  __device__ __forceinline__ void load_fast(const T *base, int krem) {
+    gbyte_t b = (gbyte_t)base;
+    if (krem >= (KC ? COLS : ROWS)) {
+#pragma unroll
+      for (int i = 0; i < NV; ++i) reg[i] = *(gvec_t)(b + voff[i]);
+      okmask = ~0u;
+    } else {
+      unsigned m = 0;
+#pragma unroll
+      for (int i = 0; i < NV; ++i) {
+        const int v = threadIdx.x + i * kThreads;
+        const int kk = KC ? (v % VPR) * VEC : v / VPR;   // first k index of the piece within the step
+        const bool ok = kk < krem;                        // K extents are multiples of VEC here
+        reg[i] = *(gvec_t)(b + (ok ? voff[i] : 0u));
+        m |= ok ? (1u << i) : 0u;
+      }
+      okmask = m;
+    }
+  }
+  __device__ __forceinline__ void load_slow(const T *base, int64_t ld, int nrows, int ncols, int r0, int c0) {
+#pragma unroll
+    for (int i = 0; i < NV; ++i) {
+      const int v = threadIdx.x + i * kThreads;
+      const int gr = r0 + v / VPR, gc = c0 + (v % VPR) * VEC;
+      unsigned int e[VEC];
+#pragma unroll
+      for (int j = 0; j < VEC; ++j) {
+        const bool ok = gr < nrows && gc + j < ncols;
+        const T *p = ok ? base + (int64_t)gr * ld + gc + j : base;
+        unsigned int x;
+        if constexpr (sizeof(T) == 2) x = *(g16_t)p; else x = *(g32_t)p;
+        e[j] = ok ? x : 0u;
+      }
+      if constexpr (sizeof(T) == 2)
+        reg[i] = u32x4{e[0] | (e[1] << 16), e[2] | (e[3] << 16), e[4] | (e[5] << 16), e[6] | (e[7] << 16)};
+      else
+        reg[i] = u32x4{e[0], e[1], e[2], e[3]};
+    }
+    okmask = ~0u;
+  }
+  __device__ __forceinline__ void store(T *lds) {
+    if (okmask != ~0u) {
+#pragma unroll
+      for (int i = 0; i < NV; ++i)
+        if (!((okmask >> i) & 1u)) reg[i] = u32x4{0u, 0u, 0u, 0u};
+    }
 #pragma unroll
     for (int i = 0; i < NV; ++i) {
       const int v = threadIdx.x + i * kThreads;
       T *q = lds + (v / VPR) * PITCH + (v % VPR) * VEC;
-      const u32x4 val = ((okmask >> i) & 1u) ? reg[i] : u32x4{0u, 0u, 0u, 0u};
       if constexpr ((PITCH * sizeof(T)) % 16 == 0) {
-        *reinterpret_cast<u32x4 *>(q) = val;
+        *reinterpret_cast<u32x4 *>(q) = reg[i];
       } else {
         static_assert((PITCH * sizeof(T)) % 8 == 0, "LDS pitch must keep 8-byte alignment");
-        reinterpret_cast<u32x2 *>(q)[0] = u32x2{val.x, val.y};
-        reinterpret_cast<u32x2 *>(q)[1] = u32x2{val.z, val.w};
+        reinterpret_cast<u32x2 *>(q)[0] = u32x2{reg[i].x, reg[i].y};
+        reinterpret_cast<u32x2 *>(q)[1] = u32x2{reg[i].z, reg[i].w};
       }
     }
   }
@@ -153,54 +187,69 @@ __device__ __forceinline__ void mma_tile(f32x16 (&acc)[2][2], const T *As, const
   }
 }
 
-// LDS of one block: two stages of (A tile, B tile) and the K-segment table.
+// LDS of one block: two stages of (A tile, B tile) -- reused as the output staging tile by the epilogues --
+// and the K-segment table.
 template <typename T> struct GemmLds {
   __attribute__((aligned(16))) T a[2][lds_elems<T>()];
   __attribute__((aligned(16))) T b[2][lds_elems<T>()];
   Seg<T> seg[kSegCap];
+  float rowscale[BM];
 };
+constexpr int kOutPitchPad = 8;  // elements; keeps 16-byte alignment of the staged rows for both types
+static_assert((BN + kOutPitchPad) * BM * 4 <= 4 * lds_elems<float>() * 4, "fp32 output tile must fit the stages");
 
-// Runs the K-steps of segs[0..nseg) (read from LDS; must be visible to the whole block) into `acc`.
+// Runs the K-steps of sm.seg[0..nseg) (must be visible to the whole block) into `acc`.
 // KC operand: matrix [extent x K] row-major (ld); KS operand: matrix [K x extent] row-major (ld).
-template <typename T, bool AKC, bool BKC>
+template <typename T, bool FAST, bool AKC, bool BKC>
 __device__ __forceinline__ void gemm_run(f32x16 (&acc)[2][2], GemmLds<T> &sm, int nseg, int a_extent, int a0,
                                          int b_extent, int b0) {
   using M = Mma<T>;
   const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
   const int wm = (wave >> 1) * 64, wn = (wave & 1) * 64;
-  using MoverA = TileMover<T, AKC ? BM : M::BK, AKC ? M::BK : BM, AKC ? M::PKC : M::PKS>;
-  using MoverB = TileMover<T, BKC ? BN : M::BK, BKC ? M::BK : BN, BKC ? M::PKC : M::PKS>;
+  using MoverA = TileMover<T, AKC ? BM : M::BK, AKC ? M::BK : BM, AKC ? M::PKC : M::PKS, AKC>;
+  using MoverB = TileMover<T, BKC ? BN : M::BK, BKC ? M::BK : BN, BKC ? M::PKC : M::PKS, BKC>;
   MoverA ta0, ta1;
   MoverB tb0, tb1;
   int total = 0;
   for (int s = 0; s < nseg; ++s) total += (sm.seg[s].ke - sm.seg[s].kb + M::BK - 1) / M::BK;
   int s_ld = 0, k_ld = nseg > 0 ? sm.seg[0].kb : 0;  // cursor of the loader, two K-steps ahead of the multiplier
-  auto issue = [&](MoverA &ta, MoverB &tb) {
+  int s_set0 = -1, s_set1 = -1;                      // segment each register set's offsets were computed for
+  auto issue = [&](MoverA &ta, MoverB &tb, int &s_set) {
     if (s_ld >= nseg) return;
     const Seg<T> g = sm.seg[s_ld];
-    if constexpr (AKC) ta.load(g.A, g.lda, a_extent, g.ke, a0, k_ld, g.a_vec);
-    else ta.load(g.A, g.lda, g.ke, a_extent, k_ld, a0, g.a_vec);
-    if constexpr (BKC) tb.load(g.B, g.ldb, b_extent, g.ke, b0, k_ld, g.b_vec);
-    else tb.load(g.B, g.ldb, g.ke, b_extent, k_ld, b0, g.b_vec);
+    if constexpr (FAST) {
+      if (s_set != s_ld) {
+        ta.setup(g.lda, a_extent, a0);
+        tb.setup(g.ldb, b_extent, b0);
+        s_set = s_ld;
+      }
+      ta.load_fast(AKC ? g.A + k_ld : g.A + (int64_t)k_ld * g.lda, g.ke - k_ld);
+      tb.load_fast(BKC ? g.B + k_ld : g.B + (int64_t)k_ld * g.ldb, g.ke - k_ld);
+    } else {
+      if constexpr (AKC) ta.load_slow(g.A, g.lda, a_extent, g.ke, a0, k_ld);
+      else ta.load_slow(g.A, g.lda, g.ke, a_extent, k_ld, a0);
+      if constexpr (BKC) tb.load_slow(g.B, g.ldb, b_extent, g.ke, b0, k_ld);
+      else tb.load_slow(g.B, g.ldb, g.ke, b_extent, k_ld, b0);
+    }
     k_ld += M::BK;
     if (k_ld >= g.ke) {
       ++s_ld;
       if (s_ld < nseg) k_ld = sm.seg[s_ld].kb;
     }
   };
-  issue(ta0, tb0);
-  issue(ta1, tb1);
+  issue(ta0, tb0, s_set0);
+  issue(ta1, tb1, s_set1);
   for (int step = 0; step < total; step += 2) {
     ta0.store(sm.a[0]);
     tb0.store(sm.b[0]);
     __syncthreads();
-    issue(ta0, tb0);
+    issue(ta0, tb0, s_set0);
     mma_tile<T, AKC, BKC>(acc, sm.a[0], sm.b[0], wm, wn, lane);
     if (step + 1 < total) {
       ta1.store(sm.a[1]);
       tb1.store(sm.b[1]);
       __syncthreads();
-      issue(ta1, tb1);
+      issue(ta1, tb1, s_set1);
       mma_tile<T, AKC, BKC>(acc, sm.a[1], sm.b[1], wm, wn, lane);
     }
   }
@@ -230,6 +279,39 @@ __device__ __forceinline__ void zero_acc(f32x16 (&acc)[2][2]) {
     }                                                                               \
   }
 
+// Writes the block's 128x128 tile `out[(row0 + r) * ld + col0 + c] = f(acc, r, c)` for r < rows, c < cols.
+// When rows of `out` are 16-byte aligned the tile goes through LDS (the K loop's stages are free by then)
+// and leaves as whole 16-byte pieces; otherwise element by element.  `f(val, row, col)` returns the value.
+template <typename T, typename F>
+__device__ __forceinline__ void write_tile(f32x16 (&acc)[2][2], GemmLds<T> &sm, T *out, int64_t ld, int rows, int cols, F f) {
+  constexpr int V = 16 / sizeof(T), P = BN + kOutPitchPad;
+  const bool vec = (ld % V) == 0 && (reinterpret_cast<uintptr_t>(out) & 15) == 0;
+  if (vec) {
+    T *stage = &sm.a[0][0];
+    HGNN_FOR_EACH_ACC({ stage[row * P + col] = from_float<T>(f(val, row, col)); })
+    __syncthreads();
+    constexpr int VPR = BN / V;
+#pragma unroll
+    for (int i = 0; i < BM * VPR / kThreads; ++i) {
+      const int v = threadIdx.x + i * kThreads;
+      const int r = v / VPR, c = (v % VPR) * V;
+      if (r < rows && c < cols) {
+        const u32x4 piece = *reinterpret_cast<const u32x4 *>(stage + r * P + c);
+        if (c + V <= cols) {
+          *reinterpret_cast<u32x4 *>(out + (int64_t)r * ld + c) = piece;
+        } else {
+          const T *e = reinterpret_cast<const T *>(&piece);
+          for (int j = 0; c + j < cols; ++j) out[(int64_t)r * ld + c + j] = e[j];
+        }
+      }
+    }
+  } else {
+    HGNN_FOR_EACH_ACC({
+      if (row < rows && col < cols) out[(int64_t)row * ld + col] = from_float<T>(f(val, row, col));
+    })
+  }
+}
+
 // Blocks are spread round-robin over the 8 XCDs by the hardware; give each XCD a contiguous range of tiles
 // so that tiles sharing operand rows meet in the same L2.
 __device__ __forceinline__ int xcd_tile(int bid, int nblocks) {
@@ -238,22 +320,19 @@ __device__ __forceinline__ int xcd_tile(int bid, int nblocks) {
 }
 static inline int round_up8(int n) { return (n + 7) & ~7; }
 
-__device__ __forceinline__ bool aligned16(const void *p) { return (reinterpret_cast<uintptr_t>(p) & 15) == 0; }
-
-// a_cols / b_cols: length of the contiguous dimension of each operand (K for a KC operand, the output
-// extent for a KS operand); vector loads need it, the leading dimension and the base to be 16-byte multiples.
 template <typename T>
-__device__ __forceinline__ void put_seg(Seg<T> &g, const T *A, int lda, int a_cols, const T *B, int ldb, int b_cols,
-                                        int kb, int ke) {
-  constexpr int V = Mma<T>::VEC;
+__device__ __forceinline__ void put_seg(Seg<T> &g, const T *A, int lda, const T *B, int ldb, int kb, int ke) {
   g.A = A; g.B = B; g.lda = lda; g.ldb = ldb; g.kb = kb; g.ke = ke;
-  g.a_vec = (lda % V) == 0 && (a_cols % V) == 0 && aligned16(A);
-  g.b_vec = (ldb % V) == 0 && (b_cols % V) == 0 && aligned16(B);
 }
 
 // ------------------------------------------------------------------------------------------
-template <typename T>
-__global__ void __launch_bounds__(kThreads) gemm_fwd_kernel(LayerDev L, TypeTab tt, RelTab rt, PtrTab pt, WtTab wt, SegTab tiles,
+// Forward.  `live` has bit r set when relation r has at least one edge in this layer.
+struct LiveMask {
+  uint32_t w[kMaxR / 32];
+};
+
+template <typename T, bool FAST>
+__global__ void __launch_bounds__(kThreads, 2) gemm_fwd_kernel(TypeTab tt, RelTab rt, PtrTab pt, WtTab wt, SegTab tiles, LiveMask live,
                                                             int H, int relu, const T *__restrict__ x, const T *__restrict__ z,
                                                             const T *__restrict__ zlo, const T *__restrict__ wtb,
                                                             T *__restrict__ h, int only_seg,
@@ -279,16 +358,16 @@ __global__ void __launch_bounds__(kThreads) gemm_fwd_kernel(LayerDev L, TypeTab 
       int n = 0, r = cursor;
       for (; r < R && n + 2 <= kSegCap; ++r) {
         if (rt.dst[r] != d || (only_seg >= 0 && only_seg != r)) continue;
-        if (L.rel_edge_off[r + 1] == L.rel_edge_off[r]) continue;  // no edge: the aggregate is all zero
+        if (!((live.w[r >> 5] >> (r & 31)) & 1u)) continue;  // no edge: the aggregate is all zero
         const int F = tt.in_dim[rt.src[r]];
         const T *B = wtb + (int64_t)wt.rel4[r] * 4;
-        put_seg(sm.seg[n++], z + (int64_t)rt.z_off4[r] * 4, F, F, B, F, F, 0, F);
-        if (zlo) put_seg(sm.seg[n++], zlo + (int64_t)rt.z_off4[r] * 4, F, F, B, F, F, 0, F);
+        put_seg(sm.seg[n++], z + (int64_t)rt.z_off4[r] * 4, F, B, F, 0, F);
+        if (zlo) put_seg(sm.seg[n++], zlo + (int64_t)rt.z_off4[r] * 4, F, B, F, 0, F);
       }
       if (r == R && n + 1 <= kSegCap) {
         if (pt.w_root[d] && (only_seg < 0 || only_seg == R + d)) {
           const int F = tt.in_dim[d];
-          put_seg(sm.seg[n++], x + tt.elem_off[d], F, F, wtb + (int64_t)wt.root4[d] * 4, F, F, 0, F);
+          put_seg(sm.seg[n++], x + tt.elem_off[d], F, wtb + (int64_t)wt.root4[d] * 4, F, 0, F);
         }
         r = R + 1;
       }
@@ -298,38 +377,48 @@ __global__ void __launch_bounds__(kThreads) gemm_fwd_kernel(LayerDev L, TypeTab 
     __syncthreads();
     const int nseg = s_nseg;
     cursor = s_next;
-    gemm_run<T, true, true>(acc, sm, nseg, M, m0, H, n0);
+    gemm_run<T, FAST, true, true>(acc, sm, nseg, M, m0, H, n0);
   }
-  const T *bias = reinterpret_cast<const T *>(pt.bias[d]);
   const int64_t orow = tt.out_row_off[d];
   if (acc32) {
     HGNN_FOR_EACH_ACC({
       if (m0 + row < M && n0 + col < H) acc32[(orow + m0 + row) * H + n0 + col] += val;
     })
-  } else {
-    HGNN_FOR_EACH_ACC({
-      if (m0 + row < M && n0 + col < H) {
-        float o = val + (bias ? to_float(bias[n0 + col]) : 0.f);
-        if (relu) o = fmaxf(o, 0.f);
-        h[(orow + m0 + row) * H + n0 + col] = from_float<T>(o);
-      }
-    })
+    return;
   }
+  const T *bias = reinterpret_cast<const T *>(pt.bias[d]);
+  float bv[2];
+#pragma unroll
+  for (int j = 0; j < 2; ++j) {
+    const int c = n0 + ((threadIdx.x >> 6) & 1) * 64 + j * 32 + (threadIdx.x & 31);
+    bv[j] = (bias && c < H) ? to_float(bias[c]) : 0.f;
+  }
+  const int wn0 = ((threadIdx.x >> 6) & 1) * 64;
+  write_tile(acc, sm, h + (orow + m0) * H + n0, H, M - m0, H - n0, [&](float v, int, int col) {
+    const float o = v + bv[(col - wn0) >> 5];
+    return relu ? fmaxf(o, 0.f) : o;
+  });
 }
 
 hgnn_status launch_gemm_fwd(hipStream_t s, int dtype, const LayerDev &L, const TypeTab &tt, const RelTab &rt,
-                            const PtrTab &pt, const WtTab &wt, const SegTab &tiles, int H, int relu,
-                            const void *x, const void *z, const void *zlo, const void *wt_buf, void *h, int only_seg,
-                            float *acc32) {
+                            const PtrTab &pt, const WtTab &wt, const SegTab &tiles, const uint32_t *live_mask, int H,
+                            int relu, const void *x, const void *z, const void *zlo, const void *wt_buf, void *h,
+                            int only_seg, float *acc32) {
   const int n = tiles.tile_off[tt.num_types];
   if (n == 0) return HGNN_OK;
+  (void)L;
+  LiveMask live;
+  for (int i = 0; i < kMaxR / 32; ++i) live.w[i] = live_mask[i];
   dim3 grid(round_up8(n));
+  // operands of the forward are the library's own aligned buffers (aggregates, transposed weights) and
+  // x_merged, whose row widths are multiples of 16 bytes: always the FAST form
   if (dtype == HGNN_BF16)
-    hipLaunchKernelGGL(gemm_fwd_kernel<bf16>, grid, dim3(kThreads), 0, s, L, tt, rt, pt, wt, tiles, H, relu, (const bf16 *)x,
-                       (const bf16 *)z, (const bf16 *)zlo, (const bf16 *)wt_buf, (bf16 *)h, only_seg, acc32);
+    hipLaunchKernelGGL((gemm_fwd_kernel<bf16, true>), grid, dim3(kThreads), 0, s, tt, rt, pt, wt, tiles, live, H, relu,
+                       (const bf16 *)x, (const bf16 *)z, (const bf16 *)zlo, (const bf16 *)wt_buf, (bf16 *)h, only_seg, acc32);
   else
-    hipLaunchKernelGGL(gemm_fwd_kernel<float>, grid, dim3(kThreads), 0, s, L, tt, rt, pt, wt, tiles, H, relu, (const float *)x,
-                       (const float *)z, (const float *)nullptr, (const float *)wt_buf, (float *)h, only_seg, acc32);
+    hipLaunchKernelGGL((gemm_fwd_kernel<float, true>), grid, dim3(kThreads), 0, s, tt, rt, pt, wt, tiles, live, H, relu,
+                       (const float *)x, (const float *)z, (const float *)nullptr, (const float *)wt_buf, (float *)h,
+                       only_seg, acc32);
   HGNN_HIP(hipGetLastError());
   return HGNN_OK;
 }
@@ -344,8 +433,11 @@ __device__ __forceinline__ int find_seg(const SegTab &tiles, int tile) {
   return lo;
 }
 
-template <typename T>
-__global__ void __launch_bounds__(kThreads) gemm_da_kernel(LayerDev L, TypeTab tt, RelTab rt, PtrTab pt, SegTab tiles, int H,
+// dZ_s = (G' W_s^T) / deg.  G' has leading dimension ldg (>= H; the columns H..ldg-1 are zero), and so have
+// the weights handed in through `pt` (the caller's own when H is a multiple of 16 bytes, zero-padded copies
+// otherwise), so that the reduction simply runs over ldg.
+template <typename T, bool FAST>
+__global__ void __launch_bounds__(kThreads, 2) gemm_da_kernel(LayerDev L, TypeTab tt, RelTab rt, PtrTab pt, SegTab tiles, int ldg,
                                                            const T *__restrict__ gp, T *__restrict__ dz) {
   __shared__ GemmLds<T> sm;
   const int tile = xcd_tile(blockIdx.x, gridDim.x);
@@ -362,41 +454,46 @@ __global__ void __launch_bounds__(kThreads) gemm_da_kernel(LayerDev L, TypeTab t
   const int m0 = (local / tiles_n) * BM, n0 = (local % tiles_n) * BN;
   f32x16 acc[2][2];
   zero_acc(acc);
-  if (threadIdx.x == 0) put_seg(sm.seg[0], gp + (int64_t)tt.out_row_off[d] * H, H, H, W, H, H, 0, H);
-  __syncthreads();
-  gemm_run<T, true, true>(acc, sm, 1, M, m0, F, n0);
-  T *out = dz + (int64_t)(is_rel ? rt.z_off4[seg] : rt.zroot_off4[d]) * 4;
-  const int rho0 = is_rel ? L.rel_row_off[seg] : 0;
-  HGNN_FOR_EACH_ACC({
-    if (m0 + row < M && n0 + col < F) {
-      float sc = 1.f;
-      if (is_rel) {
-        const int deg = L.rowptr[rho0 + m0 + row + 1] - L.rowptr[rho0 + m0 + row];
-        sc = deg > 0 ? 1.f / (float)deg : 0.f;
-      }
-      out[(int64_t)(m0 + row) * F + n0 + col] = from_float<T>(val * sc);
+  if (threadIdx.x == 0) put_seg(sm.seg[0], gp + (int64_t)tt.out_row_off[d] * ldg, ldg, W, ldg, 0, ldg);
+  if (threadIdx.x < BM) {  // 1/|N_r(v)| of the tile's rows (1 for the root term)
+    float sc = 1.f;
+    const int row = m0 + threadIdx.x;
+    if (is_rel && row < M) {
+      const int rho = L.rel_row_off[seg] + row;
+      const int deg = L.rowptr[rho + 1] - L.rowptr[rho];
+      sc = deg > 0 ? 1.f / (float)deg : 0.f;
     }
-  })
+    sm.rowscale[threadIdx.x] = sc;
+  }
+  __syncthreads();
+  gemm_run<T, FAST, true, true>(acc, sm, 1, M, m0, F, n0);
+  T *out = dz + (int64_t)(is_rel ? rt.z_off4[seg] : rt.zroot_off4[d]) * 4;
+  write_tile(acc, sm, out + (int64_t)m0 * F + n0, F, M - m0, F - n0,
+             [&](float v, int row, int) { return v * sm.rowscale[row]; });
 }
 
 hgnn_status launch_gemm_da(hipStream_t s, int dtype, const LayerDev &L, const TypeTab &tt, const RelTab &rt,
-                           const PtrTab &pt, const SegTab &tiles, int H, const void *gp, void *dz) {
+                           const PtrTab &pt, const SegTab &tiles, int ldg, bool fast, const void *gp, void *dz) {
   const int n = tiles.tile_off[tiles.num_segs];
   if (n == 0) return HGNN_OK;
-  dim3 grid(round_up8(n));
-  if (dtype == HGNN_BF16)
-    hipLaunchKernelGGL(gemm_da_kernel<bf16>, grid, dim3(kThreads), 0, s, L, tt, rt, pt, tiles, H, (const bf16 *)gp, (bf16 *)dz);
-  else
-    hipLaunchKernelGGL(gemm_da_kernel<float>, grid, dim3(kThreads), 0, s, L, tt, rt, pt, tiles, H, (const float *)gp, (float *)dz);
+  dim3 grid(round_up8(n)), blk(kThreads);
+  if (dtype == HGNN_BF16) {
+    if (fast) hipLaunchKernelGGL((gemm_da_kernel<bf16, true>), grid, blk, 0, s, L, tt, rt, pt, tiles, ldg, (const bf16 *)gp, (bf16 *)dz);
+    else hipLaunchKernelGGL((gemm_da_kernel<bf16, false>), grid, blk, 0, s, L, tt, rt, pt, tiles, ldg, (const bf16 *)gp, (bf16 *)dz);
+  } else {
+    if (fast) hipLaunchKernelGGL((gemm_da_kernel<float, true>), grid, blk, 0, s, L, tt, rt, pt, tiles, ldg, (const float *)gp, (float *)dz);
+    else hipLaunchKernelGGL((gemm_da_kernel<float, false>), grid, blk, 0, s, L, tt, rt, pt, tiles, ldg, (const float *)gp, (float *)dz);
+  }
   HGNN_HIP(hipGetLastError());
   return HGNN_OK;
 }
 
 // ------------------------------------------------------------------------------------------
-template <typename T>
-__global__ void __launch_bounds__(kThreads) gemm_dw_kernel(LayerDev L, TypeTab tt, RelTab rt, GradPtrTab gt, SegTab tiles,
-                                                           int split_rows, int H, const T *__restrict__ x,
-                                                           const T *__restrict__ z, const T *__restrict__ gp) {
+// dW_s += A_s^T G' over the destination-row slice [k_begin, k_end) of this block.
+template <typename T, bool FAST>
+__global__ void __launch_bounds__(kThreads, 2) gemm_dw_kernel(TypeTab tt, RelTab rt, GradPtrTab gt, SegTab tiles, int split_rows, int H,
+                                                           int ldg, const T *__restrict__ x, const T *__restrict__ z,
+                                                           const T *__restrict__ gp) {
   __shared__ GemmLds<T> sm;
   const int tile = xcd_tile(blockIdx.x, gridDim.x);
   const int R = rt.num_rels;
@@ -418,27 +515,29 @@ __global__ void __launch_bounds__(kThreads) gemm_dw_kernel(LayerDev L, TypeTab t
   f32x16 acc[2][2];
   zero_acc(acc);
   if (threadIdx.x == 0)
-    put_seg(sm.seg[0], is_rel ? z + (int64_t)rt.z_off4[seg] * 4 : x + tt.elem_off[d], F, F,
-            gp + (int64_t)tt.out_row_off[d] * H, H, H, k_begin, k_end);
+    put_seg(sm.seg[0], is_rel ? z + (int64_t)rt.z_off4[seg] * 4 : x + tt.elem_off[d], F,
+            gp + (int64_t)tt.out_row_off[d] * ldg, ldg, k_begin, k_end);
   __syncthreads();
-  gemm_run<T, false, false>(acc, sm, 1, F, f0, H, h0);
+  gemm_run<T, FAST, false, false>(acc, sm, 1, F, f0, ldg, h0);
   HGNN_FOR_EACH_ACC({
     if (f0 + row < F && h0 + col < H) atomicAdd(dW + (int64_t)(f0 + row) * H + h0 + col, val);
   })
 }
 
 hgnn_status launch_gemm_dw(hipStream_t s, int dtype, const LayerDev &L, const TypeTab &tt, const RelTab &rt,
-                           const GradPtrTab &gt, const SegTab &tiles, int split_rows, int H, const void *x,
-                           const void *z, const void *gp) {
+                           const GradPtrTab &gt, const SegTab &tiles, int split_rows, int H, int ldg, bool fast,
+                           const void *x, const void *z, const void *gp) {
   const int n = tiles.tile_off[tiles.num_segs];
   if (n == 0) return HGNN_OK;
-  dim3 grid(round_up8(n));
-  if (dtype == HGNN_BF16)
-    hipLaunchKernelGGL(gemm_dw_kernel<bf16>, grid, dim3(kThreads), 0, s, L, tt, rt, gt, tiles, split_rows, H, (const bf16 *)x,
-                       (const bf16 *)z, (const bf16 *)gp);
-  else
-    hipLaunchKernelGGL(gemm_dw_kernel<float>, grid, dim3(kThreads), 0, s, L, tt, rt, gt, tiles, split_rows, H, (const float *)x,
-                       (const float *)z, (const float *)gp);
+  (void)L;
+  dim3 grid(round_up8(n)), blk(kThreads);
+  if (dtype == HGNN_BF16) {
+    if (fast) hipLaunchKernelGGL((gemm_dw_kernel<bf16, true>), grid, blk, 0, s, tt, rt, gt, tiles, split_rows, H, ldg, (const bf16 *)x, (const bf16 *)z, (const bf16 *)gp);
+    else hipLaunchKernelGGL((gemm_dw_kernel<bf16, false>), grid, blk, 0, s, tt, rt, gt, tiles, split_rows, H, ldg, (const bf16 *)x, (const bf16 *)z, (const bf16 *)gp);
+  } else {
+    if (fast) hipLaunchKernelGGL((gemm_dw_kernel<float, true>), grid, blk, 0, s, tt, rt, gt, tiles, split_rows, H, ldg, (const float *)x, (const float *)z, (const float *)gp);
+    else hipLaunchKernelGGL((gemm_dw_kernel<float, false>), grid, blk, 0, s, tt, rt, gt, tiles, split_rows, H, ldg, (const float *)x, (const float *)z, (const float *)gp);
+  }
   HGNN_HIP(hipGetLastError());
   return HGNN_OK;
 }

@@ -318,34 +318,61 @@ hgnn_status launch_transpose_weights(hipStream_t s, int dtype, const TypeTab &tt
   return HGNN_OK;
 }
 
+// Zero-padded copies: out[off + f*Hp + c] = c < H ? W[f*H + c] : 0  (segment = blockIdx.y).
+template <typename T>
+__global__ void __launch_bounds__(256) pad_weights_kernel(TypeTab tt, RelTab rt, PtrTab pt, WtTab wo, int H, int Hp, T *out) {
+  const int seg = blockIdx.y, R = rt.num_rels;
+  const T *w = (const T *)(seg < R ? pt.w_rel[seg] : pt.w_root[seg - R]);
+  if (!w) return;
+  const int F = tt.in_dim[seg < R ? rt.src[seg] : seg - R];
+  T *o = out + (int64_t)(seg < R ? wo.rel4[seg] : wo.root4[seg - R]) * 4;
+  const int64_t n = (int64_t)F * Hp;
+  for (int64_t i = (int64_t)blockIdx.x * 256 + threadIdx.x; i < n; i += (int64_t)gridDim.x * 256) {
+    const int f = (int)(i / Hp), c = (int)(i % Hp);
+    o[i] = c < H ? w[(int64_t)f * H + c] : from_float<T>(0.f);
+  }
+}
+
+hgnn_status launch_pad_weights(hipStream_t s, int dtype, const TypeTab &tt, const RelTab &rt, const PtrTab &pt,
+                               const WtTab &wo, int H, int Hp, void *out) {
+  dim3 grid(32, rt.num_rels + tt.num_types);
+  if (dtype == HGNN_BF16)
+    hipLaunchKernelGGL(pad_weights_kernel<bf16>, grid, dim3(256), 0, s, tt, rt, pt, wo, H, Hp, (bf16 *)out);
+  else
+    hipLaunchKernelGGL(pad_weights_kernel<float>, grid, dim3(256), 0, s, tt, rt, pt, wo, H, Hp, (float *)out);
+  HGNN_HIP(hipGetLastError());
+  return HGNN_OK;
+}
+
 // ------------------------------------------------------------------------------------------
 // Backward epilogue: gp = grad_h * [h > 0] (when the layer has a ReLU) and dbias_t = column sums.
 // One block = 64 rows of one type; a thread owns columns tid, tid+256, ...
 // ------------------------------------------------------------------------------------------
 template <typename T>
-__global__ void __launch_bounds__(256) relu_bias_bwd_kernel(TypeTab tt, int H, int relu, const T *__restrict__ g,
+__global__ void __launch_bounds__(256) relu_bias_bwd_kernel(TypeTab tt, int H, int ldo, int relu, int write, const T *__restrict__ g,
                                                              const T *__restrict__ h, T *__restrict__ gp, GradPtrTab gt) {
   int b = blockIdx.x, t = 0;
   for (;; ++t) {
-    const int nb = (tt.n_dst[t] + 63) / 64;
+    const int nb = (tt.n_dst[t] + 15) / 16;
     if (b < nb) break;
     b -= nb;
   }
-  const int r0 = tt.out_row_off[t] + b * 64;
-  const int r1 = min(r0 + 64, tt.out_row_off[t] + tt.n_dst[t]);
+  const int r0 = tt.out_row_off[t] + b * 16;
+  const int r1 = min(r0 + 16, tt.out_row_off[t] + tt.n_dst[t]);
   float *db = gt.dbias[t];
-  for (int c = threadIdx.x; c < H; c += 256) {
+  for (int c = threadIdx.x; c < ldo; c += 256) {
     float sum = 0.f;
     for (int r = r0; r < r1; ++r) {
-      const int64_t i = (int64_t)r * H + c;
-      float v = to_float(g[i]);
-      if (relu) {
-        if (!(to_float(h[i]) > 0.f)) v = 0.f;
-        gp[i] = from_float<T>(v);
+      float v = 0.f;
+      if (c < H) {
+        const int64_t i = (int64_t)r * H + c;
+        v = to_float(g[i]);
+        if (relu && !(to_float(h[i]) > 0.f)) v = 0.f;
       }
+      if (write) gp[(int64_t)r * ldo + c] = from_float<T>(v);
       sum += v;
     }
-    if (db) atomicAdd(db + c, sum);
+    if (db && c < H) atomicAdd(db + c, sum);
   }
 }
 
@@ -403,11 +430,12 @@ __global__ void __launch_bounds__(256) relu_bias_bwd_vec_kernel(TypeTab tt, int 
   }
 }
 
-hgnn_status launch_relu_bias_bwd(hipStream_t s, int dtype, const TypeTab &tt, int H, int relu,
+hgnn_status launch_relu_bias_bwd(hipStream_t s, int dtype, const TypeTab &tt, int H, int ldo, int relu,
                                  const void *grad_h, const void *h, void *gp, const GradPtrTab &gt) {
   const int vec = dtype == HGNN_BF16 ? 8 : 4;
-  const bool fast = H % vec == 0 && H / vec <= 256 && (((uintptr_t)grad_h | (uintptr_t)h | (uintptr_t)gp) & 15) == 0;
-  const int rpb = fast ? 128 : 64;
+  const bool fast = ldo == H && H % vec == 0 && H / vec <= 256 && (((uintptr_t)grad_h | (uintptr_t)h | (uintptr_t)gp) & 15) == 0;
+  const int rpb = fast ? 128 : 16;
+  const int write = relu || ldo != H;
   int blocks = 0;
   for (int t = 0; t < tt.num_types; ++t) blocks += (tt.n_dst[t] + rpb - 1) / rpb;
   if (blocks == 0) return HGNN_OK;
@@ -419,10 +447,10 @@ hgnn_status launch_relu_bias_bwd(hipStream_t s, int dtype, const TypeTab &tt, in
       hipLaunchKernelGGL(relu_bias_bwd_vec_kernel<float>, dim3(blocks), dim3(256), 0, s, tt, H, relu, (const float *)grad_h,
                          (const float *)h, (float *)gp, gt);
   } else if (dtype == HGNN_BF16) {
-    hipLaunchKernelGGL(relu_bias_bwd_kernel<bf16>, dim3(blocks), dim3(256), 0, s, tt, H, relu, (const bf16 *)grad_h,
+    hipLaunchKernelGGL(relu_bias_bwd_kernel<bf16>, dim3(blocks), dim3(256), 0, s, tt, H, ldo, relu, write, (const bf16 *)grad_h,
                        (const bf16 *)h, (bf16 *)gp, gt);
   } else {
-    hipLaunchKernelGGL(relu_bias_bwd_kernel<float>, dim3(blocks), dim3(256), 0, s, tt, H, relu, (const float *)grad_h,
+    hipLaunchKernelGGL(relu_bias_bwd_kernel<float>, dim3(blocks), dim3(256), 0, s, tt, H, ldo, relu, write, (const float *)grad_h,
                        (const float *)h, (float *)gp, gt);
   }
   HGNN_HIP(hipGetLastError());
