@@ -95,7 +95,8 @@ def main():
     from paper_2408_08490_amd.runner import Batch
 
     def start_build(slot):
-        return ctx.hgnn_build_semantic_csr(slot.mb.blocks, g.edge_type, use_edge_id=True)
+        return ctx.hgnn_build_semantic_csr(slot.mb.blocks, g.edge_type, use_edge_id=True,
+                                           transpose_types=model.transpose_types(len(slot.mb.blocks)))
 
     def batch_of(slot, graph):
         b = Batch()

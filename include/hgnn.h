@@ -104,6 +104,9 @@ typedef struct {
   const int64_t *n_src;            /* host [T] source-side rows per type (rows of this layer's x_merged) */
   const int64_t *n_dst;            /* host [T] destination rows per type; the destinations of type t are
                                       the FIRST n_dst[t] of its n_src[t] source rows */
+  const int32_t *transpose_types;  /* host [T] or NULL (= all 1): 0 = source rows of type t get no transpose
+                                      entries (their input gradient will not be asked for; see
+                                      hgnn_layer_params.input_grad, which must then be 0 for t as well) */
 } hgnn_coo_layer;
 
 /* Starts the build of all `num_layers` layers (execution order) on the context's host threads
@@ -133,6 +136,7 @@ hgnn_status hgnn_graph_wait(hgnn_ctx *ctx, hgnn_graph *g);
  * Any output pointer may be NULL. */
 typedef struct {
   int64_t rows, edges, src_rows;
+  int64_t transpose_edges; /* entries of crow/cperm (= edges unless transpose_types masks some types) */
   const int32_t *rel_row_off, *rel_edge_off, *rowptr, *colidx, *perm, *cptr, *crow, *cperm;
 } hgnn_csr_view;
 hgnn_status hgnn_graph_host_view(hgnn_ctx *ctx, hgnn_graph *g, int32_t layer, hgnn_csr_view *view);

@@ -81,13 +81,15 @@ def edge_index_select(edge_index, num_rels, edge_type=None, edge_id=None, global
     return out
 
 
-def semantic_csr(selected, rel_src, rel_dst, n_src, n_dst):
+def semantic_csr(selected, rel_src, rel_dst, n_src, n_dst, transpose_types=None):
     """One CSR over all relations.  Relation r owns rows
     rel_row_off[r] .. rel_row_off[r+1]-1, one per destination vertex of type dst(r)
     (also when r has no edge).  A row lists its edges in input order; `colidx` is the
     source's row in the type-first feature matrix; `perm` the edge's input position.
     The transpose groups the same edges by `colidx`, ascending CSR position inside a
-    group: `crow` is the edge's CSR row, `cperm` its CSR position."""
+    group: `crow` is the edge's CSR row, `cperm` its CSR position.  With
+    `transpose_types` (0/1 per vertex type) the transpose lists only the edges whose
+    source vertex is of a type flagged 1 (rows of the other types stay empty)."""
     R, T = len(rel_src), len(n_src)
     row_off = [0]
     for t in range(T):
@@ -111,9 +113,13 @@ def semantic_csr(selected, rel_src, rel_dst, n_src, n_dst):
             colidx.append(c); perm.append(p)
         rowptr.append(len(colidx))
     cols = [[] for _ in range(row_off[-1])]
+    type_of_row = []
+    for t in range(T):
+        type_of_row += [t] * int(n_src[t])
     for rho in range(len(rows)):
         for k in range(rowptr[rho], rowptr[rho + 1]):
-            cols[colidx[k]].append((rho, k))
+            if transpose_types is None or transpose_types[type_of_row[colidx[k]]]:
+                cols[colidx[k]].append((rho, k))
     cptr, crow, cperm = [0], [], []
     for lst in cols:
         for (rho, k) in lst:

@@ -37,11 +37,12 @@ class Schema(C.Structure):
 class CooLayer(C.Structure):
     _fields_ = [("num_edges", C.c_int64), ("edge_index", C.c_void_p), ("index_is_i64", C.c_int32),
                 ("edge_type", C.c_void_p), ("edge_id", C.c_void_p), ("global_edge_type", C.c_void_p),
-                ("num_global_edges", C.c_int64), ("n_src", C.c_void_p), ("n_dst", C.c_void_p)]
+                ("num_global_edges", C.c_int64), ("n_src", C.c_void_p), ("n_dst", C.c_void_p),
+                ("transpose_types", C.c_void_p)]
 
 
 class CsrView(C.Structure):
-    _fields_ = [("rows", C.c_int64), ("edges", C.c_int64), ("src_rows", C.c_int64)] + \
+    _fields_ = [("rows", C.c_int64), ("edges", C.c_int64), ("src_rows", C.c_int64), ("transpose_edges", C.c_int64)] + \
                [(k, C.POINTER(C.c_int32)) for k in
                 ("rel_row_off", "rel_edge_off", "rowptr", "colidx", "perm", "cptr", "crow", "cperm")]
 
@@ -132,9 +133,9 @@ class Graph:
         v = CsrView()
         _check(lib.hgnn_graph_host_view(self.ctx.handle, self.handle, layer, C.byref(v)))
         R = self.ctx.num_rels
-        out = dict(rows=v.rows, edges=v.edges, src_rows=v.src_rows)
+        out = dict(rows=v.rows, edges=v.edges, src_rows=v.src_rows, transpose_edges=v.transpose_edges)
         for k, n in (("rel_row_off", R + 1), ("rel_edge_off", R + 1), ("rowptr", v.rows + 1), ("colidx", v.edges),
-                     ("perm", v.edges), ("cptr", v.src_rows + 1), ("crow", v.edges), ("cperm", v.edges)):
+                     ("perm", v.edges), ("cptr", v.src_rows + 1), ("crow", v.transpose_edges), ("cperm", v.transpose_edges)):
             out[k] = np.ctypeslib.as_array(getattr(v, k), shape=(n,)).copy() if n > 0 else np.zeros(0, np.int32)
         return out
 
@@ -212,8 +213,9 @@ class Context:
         return np.array(row_off[:], dtype=np.int32), np.array(elem_off[:], dtype=np.int64)
 
     # ---- hgnn_build_semantic_csr ----
-    def hgnn_build_semantic_csr(self, blocks, global_edge_type=None, use_edge_id=False) -> Graph:
-        """blocks: objects with n_src, n_dst, edge_index (2 x E, int64 or int32), edge_type / edge_id."""
+    def hgnn_build_semantic_csr(self, blocks, global_edge_type=None, use_edge_id=False, transpose_types=None) -> Graph:
+        """blocks: objects with n_src, n_dst, edge_index (2 x E, int64 or int32), edge_type / edge_id.
+        transpose_types: per layer, None or a 0/1 list per vertex type (hgnn_coo_layer.transpose_types)."""
         n = len(blocks)
         arr = (CooLayer * n)()
         keep = []
@@ -240,6 +242,11 @@ class Context:
                 arr[i].edge_type = et.ctypes.data
             arr[i].n_src = ns.ctypes.data
             arr[i].n_dst = nd.ctypes.data
+            tt = None if transpose_types is None else transpose_types[i]
+            if tt is not None:
+                tta = np.ascontiguousarray(tt, dtype=np.int32)
+                keep.append(tta)
+                arr[i].transpose_types = tta.ctypes.data
         h = C.c_void_p()
         _check(lib.hgnn_build_semantic_csr(self.handle, n, arr, C.byref(h)))
         return Graph(self, h, keep)

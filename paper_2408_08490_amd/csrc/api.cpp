@@ -322,6 +322,7 @@ hgnn_status hgnn_build_semantic_csr(hgnn_ctx *ctx, int32_t num_layers, const hgn
       }
       L.n_src[t] = in.n_src[t];
       L.n_dst[t] = in.n_dst[t];
+      if (in.transpose_types && !in.transpose_types[t]) L.tmask &= ~(1u << t);
       src_rows += in.n_src[t];
     }
     for (int r = 0; r < R; ++r) rows += in.n_dst[ctx->rel_dst[r]];
@@ -418,7 +419,7 @@ hgnn_status hgnn_graph_host_view(hgnn_ctx *ctx, hgnn_graph *g, int32_t layer, hg
   if (st != HGNN_OK) return st;
   const LayerHost &L = g->L[layer];
   const int32_t *b = g->slab.host;
-  v->rows = L.rows; v->edges = L.edges; v->src_rows = L.src_rows;
+  v->rows = L.rows; v->edges = L.edges; v->src_rows = L.src_rows; v->transpose_edges = L.tedges;
   v->rel_row_off = b + L.o_rel_row_off; v->rel_edge_off = b + L.o_rel_edge_off;
   v->rowptr = b + L.o_rowptr; v->colidx = b + L.o_colidx; v->perm = b + L.o_perm;
   v->cptr = b + L.o_cptr; v->crow = b + L.o_crow; v->cperm = b + L.o_cperm;
@@ -657,7 +658,7 @@ hgnn_status hgnn_layer_bwd(hgnn_ctx *ctx, void *stream, hgnn_graph *g, int32_t l
         if (live_seg(sgi, d, F))
           tiles += (int64_t)((F + 127) / 128) * ((pl.H + 127) / 128) * ((pl.tt.n_dst[d] + split_rows - 1) / split_rows);
       }
-      if (tiles >= 512 || split_rows <= 128) break;
+      if (tiles >= 320 || split_rows <= 128) break;
       split_rows /= 2;
     }
     for (int sgi = 0; sgi < R + T; ++sgi) {
@@ -670,6 +671,9 @@ hgnn_status hgnn_layer_bwd(hgnn_ctx *ctx, void *stream, hgnn_graph *g, int32_t l
     if ((st = launch_gemm_dw(s, ctx->dtype, pl.dev, pl.tt, pl.rt, gt, tl, split_rows, pl.H, ldg, fast, x_merged, saved, gp)) != HGNN_OK) return st;
   }
   if (grad_x_merged && pl.dev.src_rows > 0) {
+    for (int t = 0; t < T; ++t)
+      if ((!p->input_grad || p->input_grad[t]) && !((L.tmask >> t) & 1u) && L.n_src[t] > 0)
+        HGNN_FAIL(HGNN_EINVAL, "input gradient of type %d asked for, but the graph was built without its transpose entries", t);
     SegTab tl;
     seg_tiles_da(ctx, pl, p, reo, tl);
     void *dz = sc + pl.off_dz;

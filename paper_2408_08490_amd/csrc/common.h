@@ -83,13 +83,14 @@ constexpr int kLongRow = 256;  // transpose rows above this length are reduced c
 constexpr int kChunk = 128;
 
 struct LayerHost {
-  int64_t rows = 0, edges = 0, src_rows = 0;
+  int64_t rows = 0, edges = 0, src_rows = 0, tedges = 0;
   int64_t n_src[kMaxT], n_dst[kMaxT];
   // offsets in int32 units into the slab
   size_t o_rel_row_off = 0, o_rel_edge_off = 0, o_rowptr = 0, o_colidx = 0, o_perm = 0, o_cptr = 0,
          o_crow = 0, o_cperm = 0, o_chunk_row = 0, o_chunk_beg = 0, o_long_row = 0, o_long_chunk0 = 0;
   int32_t n_long = 0, n_chunks = 0;
   int32_t max_chunks = 0, max_long = 0;
+  uint32_t tmask = ~0u;  // vertex types whose source rows get transpose entries
   hgnn_coo_layer in;  // caller's arrays (valid until the build finishes)
 };
 

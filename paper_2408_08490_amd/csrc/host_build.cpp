@@ -203,6 +203,20 @@ static bool build_layer(hgnn_ctx *ctx, Builder &bd, hgnn_graph *g, int l, BuildE
   if (err.failed.load()) return false;
   tm.lap("select (Alg.2) + count");
 
+  // source rows whose transpose entries are wanted (input gradients), as at most T row ranges
+  int n_want = 0;
+  int32_t want_lo[kMaxT], want_hi[kMaxT];
+  for (int t = 0; t < T; ++t) {
+    if (!((L.tmask >> t) & 1u)) continue;
+    if (n_want > 0 && want_hi[n_want - 1] == row_off[t]) want_hi[n_want - 1] = row_off[t + 1];
+    else { want_lo[n_want] = row_off[t]; want_hi[n_want] = row_off[t + 1]; ++n_want; }
+  }
+  auto wanted = [&](int32_t c) {
+    for (int i = 0; i < n_want; ++i)
+      if (c >= want_lo[i] && c < want_hi[i]) return true;
+    return false;
+  };
+
   // ---- merged CSR: stable by (relation, destination) ----
   {
     int32_t run = 0;
@@ -250,7 +264,7 @@ static bool build_layer(hgnn_ctx *ctx, Builder &bd, hgnn_graph *g, int l, BuildE
       colidx[pos] = c;
       perm[pos] = e;
       rowid[pos] = k;
-      ++c2[c >> kBucketShift];
+      if (wanted(c)) ++c2[c >> kBucketShift];
     }
   });
   tm.lap("csr level-2 buckets");
@@ -274,6 +288,7 @@ static bool build_layer(hgnn_ctx *ctx, Builder &bd, hgnn_graph *g, int l, BuildE
   pool.parallel_for(B1, [&](int b1) {
     int32_t *off = cnt2 + (size_t)b1 * S2;
     for (int32_t k = base1[b1]; k < base1[b1 + 1]; ++k) {
+      if (!wanted(colidx[k])) continue;
       const int32_t q = off[colidx[k] >> kBucketShift]++;
       int32_t *rec = trec + (size_t)q * 3;
       rec[0] = colidx[k];
@@ -307,7 +322,8 @@ static bool build_layer(hgnn_ctx *ctx, Builder &bd, hgnn_graph *g, int l, BuildE
       cperm[pos] = rec[1];
     }
   });
-  cptr[src_rows] = (int32_t)E;
+  cptr[src_rows] = base2[B2];
+  L.tedges = base2[B2];
   tm.lap("csc level-2 buckets");
 
   // long transpose rows are cut into chunks so that no single wave walks thousands of edges

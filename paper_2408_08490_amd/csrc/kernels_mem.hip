@@ -309,7 +309,7 @@ __global__ void __launch_bounds__(256) transpose_weights_kernel(TypeTab tt, RelT
 
 hgnn_status launch_transpose_weights(hipStream_t s, int dtype, const TypeTab &tt, const RelTab &rt,
                                      const PtrTab &pt, const WtTab &wt, int H, void *wt_buf) {
-  dim3 grid(16, rt.num_rels + tt.num_types);
+  dim3 grid(128, rt.num_rels + tt.num_types);
   if (dtype == HGNN_BF16)
     hipLaunchKernelGGL(transpose_weights_kernel<bf16>, grid, dim3(256), 0, s, tt, rt, pt, wt, H, (bf16 *)wt_buf);
   else

@@ -43,6 +43,7 @@ class Model:
         self.dev = torch.device("cuda", device)
         torch.cuda.set_device(self.dev)
         self.dtype, self.loss, self.target_type = dtype, loss, target_type
+        self.first_layer_input_grad = first_layer_input_grad
         self.T, self.R = schema.num_types, schema.num_rels
         self.ctx = B.Context(schema.rel_src, schema.rel_dst, schema.num_types, dtype, device, host_threads)
         self.feat_dim = list(feat_dim)
@@ -62,6 +63,13 @@ class Model:
                                        input_grad=first_layer_input_grad if not self.layers else None))
         self.loss_dev = torch.zeros(1, device=self.dev, dtype=torch.float32)
         self._buf = {}
+
+    def transpose_types(self, num_layers):
+        """Per layer: which vertex types need transpose entries (the first layer skips the types whose input
+        gradient is not wanted)."""
+        if self.first_layer_input_grad is None:
+            return None
+        return [list(self.first_layer_input_grad)] + [None] * (num_layers - 1)
 
     def close(self):
         self.ctx.close()
@@ -84,7 +92,7 @@ class Model:
         b.ids_dev = [torch.from_numpy(np.ascontiguousarray(i, dtype=np.int64)).to(self.dev) for i in mb.ids]
         b.n_rows = [len(i) for i in mb.ids]
         b.blocks = mb.blocks
-        b.graph = self.ctx.hgnn_build_semantic_csr(mb.blocks, global_edge_type, use_edge_id)
+        b.graph = self.ctx.hgnn_build_semantic_csr(mb.blocks, global_edge_type, use_edge_id, self.transpose_types(len(mb.blocks)))
         if mb.labels is not None:
             b.labels_dev = torch.from_numpy(mb.labels.astype(np.int64)).to(self.dev)
         if mb.grad_out is not None:

@@ -37,14 +37,15 @@ def prepare_inputs(index, scale=1.0, batch=None, graph=None):
     return cfg, g, mb, ws
 
 
-def oracle_run(cfg, g, mb, ws):
+def oracle_run(cfg, g, mb, ws, input_grad=None):
     sch = g.schema
     blocks_x, _, _, flat = O.merge_features(g.stores, mb.ids)
     sels, csrs = [], []
     for b in mb.blocks:
         sel = O.edge_index_select(b.edge_index, sch.num_rels, edge_id=b.edge_id, global_edge_type=g.edge_type)
         sels.append(sel)
-        csrs.append(O.semantic_csr(sel, sch.rel_src, sch.rel_dst, b.n_src, b.n_dst))
+        csrs.append(O.semantic_csr(sel, sch.rel_src, sch.rel_dst, b.n_src, b.n_dst,
+                                   transpose_types=input_grad if len(csrs) == 0 else None))
     layers = [dict(w_rel=lw.w_rel, w_root=lw.w_root, bias=lw.bias, relu=lw.relu) for lw in ws]
     loss = "xent" if cfg.loss == "xent" else "dot"
     res = O.rgcn_model_forward_backward(blocks_x, sels, sch.rel_src, sch.rel_dst, [b.n_dst for b in mb.blocks],
@@ -62,7 +63,7 @@ def run_case(index, scale=1.0, batch=None, verbose=False, use_edge_id=True, chec
     cfg, g, mb, ws = prepare_inputs(index, scale, batch, graph)
     sch = g.schema
     t0 = time.time()
-    ref = oracle_run(cfg, g, mb, ws)
+    ref = oracle_run(cfg, g, mb, ws, input_grad)
     t_oracle = time.time() - t0
     model = Model(sch, g.feat_dim, g.stores, ws, dtype=cfg.dtype, loss=("xent" if cfg.loss == "xent" else "dot"),
                   target_type=mb.target_type, first_layer_input_grad=input_grad)

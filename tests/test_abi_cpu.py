@@ -183,3 +183,24 @@ def test_overlapping_builds_from_one_context(B):
                 assert np.array_equal(v[k], ref[k])
         gr.release()
     ctx.close()
+
+
+def test_transpose_restricted_to_wanted_types(B):
+    cfg = make_config(2, scale=0.02, batch=96)
+    g = build_graph(cfg)
+    mb = sample_minibatch(cfg, g)
+    ctx = _host_ctx(B, g.schema, threads=4)
+    want = [0, 1, 1, 1]
+    gr = ctx.hgnn_build_semantic_csr(mb.blocks, g.edge_type, use_edge_id=True,
+                                     transpose_types=[want] + [None] * (len(mb.blocks) - 1))
+    for l, b in enumerate(mb.blocks):
+        sel = O.edge_index_select(b.edge_index, g.schema.num_rels, edge_type=b.edge_type)
+        ref = O.semantic_csr(sel, g.schema.rel_src, g.schema.rel_dst, b.n_src, b.n_dst,
+                             transpose_types=want if l == 0 else None)
+        v = gr.host_view(l)
+        for k in ("rowptr", "colidx", "perm", "cptr", "crow", "cperm"):
+            assert np.array_equal(v[k], ref[k]), (l, k)
+        if l == 0:
+            assert v["transpose_edges"] < v["edges"] and v["cptr"][b.n_src[0]] == 0
+    gr.release()
+    ctx.close()
