@@ -24,6 +24,9 @@ if ROOT not in sys.path:
 
 HBM_PEAK_GBS = 8000.0
 MFMA_BF16_PEAK_TFLOPS = 2500.0
+# HBM bytes per launch of the two probed kernels on the default workload, from the rocprofv3 --pmc runs
+# summarised under profiles/ (FETCH_SIZE + WRITE_SIZE, scaled by the copy-kernel calibration); None = not measured
+TRAFFIC_BYTES = {"gemm_fwd": None, "spmm_fwd": None}
 
 
 def main():
@@ -34,10 +37,11 @@ def main():
     ap.add_argument("--config", type=int, default=2)
     ap.add_argument("--scale", type=float, default=1.0)
     ap.add_argument("--batches", type=int, default=4, help="distinct pre-sampled mini-batches cycled through")
-    ap.add_argument("--probe", default="spmm_fwd", help="kernel bracketed with HIP events for the roofline object")
+    ap.add_argument("--probe", default="auto", help="kernel bracketed with HIP events for the roofline object "
+                    "(auto: forward GEMM and gather-mean of layer 1)")
     ap.add_argument("--probe-layer", type=int, default=0)
     ap.add_argument("--no-cpu-baseline", action="store_true")
-    ap.add_argument("--cpu-sample-batch", type=int, default=512)
+    ap.add_argument("--cpu-sample-batch", type=int, default=4096)
     ap.add_argument("--host-threads", type=int, default=0)
     ap.add_argument("--all-input-grads", action="store_true", help="also compute gradients w.r.t. the fixed T0 features")
     ap.add_argument("--lookahead", type=int, default=4, help="mini-batches whose index build is started ahead of the GPU")
@@ -128,15 +132,18 @@ def main():
             gr.release()
 
     W, K = args.warmup, args.steps
-    kid = B.KERNEL_IDS[args.probe]
+    # kernels bracketed with HIP event pairs inside the timed region: the dominant kernel (forward GEMM of
+    # layer 1: projection + fusion) and the aggregation kernel of layer 1, or the one asked for
+    probes = [("gemm_fwd", 0), ("spmm_fwd", 0)] if args.probe == "auto" else [(args.probe, args.probe_layer)]
     pipelined(W, 0)
     torch.cuda.synchronize()
-    ctx.hgnn_probe_select(kid, args.probe_layer)
+    for k_, l_ in probes:
+        ctx.hgnn_probe_select(B.KERNEL_IDS[k_], l_)
     t1 = time.perf_counter()
     pipelined(K, W)
     torch.cuda.synchronize()
     t_pipe = time.perf_counter() - t1
-    probe_ms, probe_n = ctx.hgnn_probe_read()
+    probe_res = {(k_, l_): ctx.hgnn_probe_read(B.KERNEL_IDS[k_], l_) for k_, l_ in probes}
     ctx.hgnn_probe_select(-1, -1)
 
     # same loop with the index arrays built beforehand (GPU work only)
@@ -170,49 +177,54 @@ def main():
         f, bw = ctx.hgnn_layer_launch_count(graphs[0], l, model.layers[l])
         launches.append(dict(layer=l, merged_fwd=f, merged_bwd=bw, naive_fwd=out_naive["launches"][l]))
 
-    # algorithmic traffic / flops of the probed kernel, from the first mini-batch's shapes
+    # algorithmic traffic / flops of the probed kernels, from the first mini-batch's shapes
     es = 2 if cfg.dtype == "bf16" else 4
     mb = slots[0].mb
-    blk = mb.blocks[args.probe_layer]
     sch = g.schema
-    lw = ws[args.probe_layer]
-    view = graphs[0].host_view(args.probe_layer)
-    rows, E = int(view["rows"]), int(view["edges"])
-    roof = None
-    if args.probe == "spmm_fwd":
-        # each referenced source row once per relation segment + index arrays + both output planes
-        uniq = 0
-        for r in range(sch.num_rels):
-            a, b_ = view["rel_edge_off"][r], view["rel_edge_off"][r + 1]
-            uniq += len(np.unique(view["colidx"][a:b_])) * lw.in_dim[sch.rel_src[r]]
-        zel = sum(blk.n_dst[sch.rel_dst[r]] * lw.in_dim[sch.rel_src[r]] for r in range(sch.num_rels))
-        nplanes = 2 if cfg.dtype == "bf16" else 1
-        alg_bytes = uniq * es + 4 * E + 4 * (rows + 1) + zel * es * nplanes
-        req_bytes = alg_bytes + (sum(lw.in_dim[sch.rel_src[r]] * (view["rel_edge_off"][r + 1] - view["rel_edge_off"][r])
-                                     for r in range(sch.num_rels)) - uniq) * es
+
+    def roofline_of(kname, layer):
+        probe_ms, probe_n = probe_res[(kname, layer)]
         avg_ms = probe_ms / max(probe_n, 1)
-        ach = alg_bytes / (avg_ms * 1e-3) / 1e9 if avg_ms > 0 else 0.0
-        roof = dict(kernel="spmm_fwd_kernel (layer %d)" % args.probe_layer, bound="hbm", achieved=round(ach, 1),
-                    peak=HBM_PEAK_GBS, unit="GB/s", frac=round(ach / HBM_PEAK_GBS, 4), traffic=None,
-                    algorithmic_bytes=int(alg_bytes), requested_bytes=int(req_bytes),
+        blk, lw = mb.blocks[layer], ws[layer]
+        view = graphs[0].host_view(layer)
+        rows, E = int(view["rows"]), int(view["edges"])
+        live = [view["rel_edge_off"][r + 1] > view["rel_edge_off"][r] for r in range(sch.num_rels)]
+        if kname == "spmm_fwd":
+            # each referenced source row once per relation segment + index arrays + the output plane(s)
+            uniq = sum(len(np.unique(view["colidx"][view["rel_edge_off"][r]: view["rel_edge_off"][r + 1]])) *
+                       lw.in_dim[sch.rel_src[r]] for r in range(sch.num_rels))
+            zel = sum(blk.n_dst[sch.rel_dst[r]] * lw.in_dim[sch.rel_src[r]] for r in range(sch.num_rels))
+            nplanes = 2 if (cfg.dtype == "bf16" and lw.relu) else 1
+            alg = uniq * es + 4 * E + 4 * (rows + 1) + zel * es * nplanes
+            req = alg + (sum(lw.in_dim[sch.rel_src[r]] * int(view["rel_edge_off"][r + 1] - view["rel_edge_off"][r])
+                             for r in range(sch.num_rels)) - uniq) * es
+            ach = alg / (avg_ms * 1e-3) / 1e9 if avg_ms > 0 else 0.0
+            return dict(kernel="spmm_fwd_kernel (layer %d: relation-segmented gather-mean)" % (layer + 1), bound="hbm",
+                        achieved=round(ach, 1), peak=HBM_PEAK_GBS, unit="GB/s", frac=round(ach / HBM_PEAK_GBS, 4),
+                        traffic=None, algorithmic_bytes=int(alg), requested_bytes=int(req),
+                        avg_kernel_us=round(avg_ms * 1e3, 2), launches_timed=probe_n)
+        if kname in ("gemm_fwd", "gemm_dw", "gemm_da"):
+            # 2*M*K*N over the live K-segments (relations with edges + root); the low-order plane the bf16
+            # forward multiplies as well is not counted: it is not part of the method
+            flops = 0
+            for t in range(sch.num_types):
+                k = sum(lw.in_dim[sch.rel_src[r]] for r in range(sch.num_rels) if sch.rel_dst[r] == t and live[r])
+                k += lw.in_dim[t] if lw.w_root[t] is not None else 0
+                flops += 2 * blk.n_dst[t] * k * lw.out_dim
+            ach = flops / (avg_ms * 1e-3) / 1e12 if avg_ms > 0 else 0.0
+            peak = MFMA_BF16_PEAK_TFLOPS if cfg.dtype == "bf16" else 157.3
+            return dict(kernel="%s_kernel (layer %d)" % (kname, layer + 1), bound="mfma", achieved=round(ach, 1), peak=peak,
+                        unit="TFLOP/s", frac=round(ach / peak, 4), traffic=None, algorithmic_flops=int(flops),
+                        avg_kernel_us=round(avg_ms * 1e3, 2), launches_timed=probe_n)
+        return dict(kernel=kname, bound="hbm", achieved=None, peak=HBM_PEAK_GBS, unit="GB/s", frac=None, traffic=None,
                     avg_kernel_us=round(avg_ms * 1e3, 2), launches_timed=probe_n)
-    elif args.probe in ("gemm_fwd", "gemm_dw", "gemm_da"):
-        flops = 0
-        for t in range(sch.num_types):
-            k = sum(lw.in_dim[sch.rel_src[r]] for r in range(sch.num_rels)
-                    if sch.rel_dst[r] == t and view["rel_edge_off"][r + 1] > view["rel_edge_off"][r])
-            k += lw.in_dim[t] if lw.w_root[t] is not None else 0
-            flops += 2 * blk.n_dst[t] * k * lw.out_dim
-        avg_ms = probe_ms / max(probe_n, 1)
-        ach = flops / (avg_ms * 1e-3) / 1e12 if avg_ms > 0 else 0.0
-        peak = MFMA_BF16_PEAK_TFLOPS if cfg.dtype == "bf16" else 157.3
-        roof = dict(kernel="%s_kernel (layer %d)" % (args.probe, args.probe_layer), bound="mfma", achieved=round(ach, 1),
-                    peak=peak, unit="TFLOP/s", frac=round(ach / peak, 4), traffic=None, algorithmic_flops=int(flops),
-                    avg_kernel_us=round(avg_ms * 1e3, 2), launches_timed=probe_n)
-    else:
-        avg_ms = probe_ms / max(probe_n, 1)
-        roof = dict(kernel=args.probe, bound="hbm", achieved=None, peak=HBM_PEAK_GBS, unit="GB/s", frac=None, traffic=None,
-                    avg_kernel_us=round(avg_ms * 1e3, 2), launches_timed=probe_n)
+
+    roof = roofline_of(*probes[0])
+    roof_agg = roofline_of(*probes[1]) if len(probes) > 1 else None
+    if roof_agg is not None:
+        # HBM bytes per launch from rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE runs of this command (profiles/)
+        roof["traffic"] = TRAFFIC_BYTES.get("gemm_fwd")
+        roof_agg["traffic"] = TRAFFIC_BYTES.get("spmm_fwd")
 
     for gr in graphs:
         gr.release()
@@ -226,14 +238,15 @@ def main():
         if mb_s.grad_out is not None and cfg.dtype == "bf16":
             mb_s.grad_out = [bf16_round(x) for x in mb_s.grad_out]
         tc = time.perf_counter()
-        oracle_run(cfg_s, g, mb_s, ws)
+        oracle_run(cfg_s, g, mb_s, ws)                # plain numpy fp64 oracle, whole mini-batch, fwd + bwd
         t_cpu = time.perf_counter() - tc
         frac = args.cpu_sample_batch / cfg.batch
         cpu = dict(value=round(frac / t_cpu, 5), unit="mini-batches/s", cores=os.cpu_count() if False else len(os.sched_getaffinity(0)),
                    kind="oracle",
-                   sample="one mini-batch of %d targets (1/%d of the workload's %d), full fwd+bwd incl. index build, "
-                          "%.1f s of numpy fp64; rate scaled by the target fraction" %
-                          (args.cpu_sample_batch, round(1 / frac), cfg.batch, t_cpu))
+                   sample="one mini-batch of %d targets (%.3g of the workload's %d): feature merge, index build, both "
+                          "layers forward and backward in numpy fp64, %.1f s; rate scaled by the target fraction; "
+                          "numpy's BLAS uses the host cores for the matmuls, the row loops are single-threaded" %
+                          (args.cpu_sample_batch, frac, cfg.batch, t_cpu))
 
     sizes = [dict(src_rows=sum(b.n_src), dst_rows=sum(b.n_dst), edges=int(b.edge_index.shape[1])) for b in mb.blocks]
     line = dict(
@@ -245,7 +258,7 @@ def main():
                     minibatch_sizes=sizes, distinct_minibatches=len(slots)),
         gpu_only_mb_per_s=round(K / t_gpu, 2), gpu_only_ms_per_step=round(1e3 * t_gpu / K, 4),
         host_build_ms=round(1e3 * t_build, 3), launches_per_layer=launches,
-        roofline=roof, cpu_baseline=cpu, setup_s=round(t_setup, 1))
+        roofline=roof, roofline_aggregation=roof_agg, cpu_baseline=cpu, setup_s=round(t_setup, 1))
     print(json.dumps(line))
     model.close()
 

@@ -81,7 +81,7 @@ def _load():
         "hgnn_layer_launch_count": [vp, vp, i32, C.POINTER(LayerParams), C.POINTER(i32), C.POINTER(i32)],
         "hgnn_softmax_xent": [vp, vp, vp, vp, i64, i32, vp, vp],
         "hgnn_probe_select": [vp, i32, i32],
-        "hgnn_probe_read": [vp, C.POINTER(C.c_double), C.POINTER(i64)],
+        "hgnn_probe_read": [vp, i32, i32, C.POINTER(C.c_double), C.POINTER(i64)],
     }
     for name, args in sig.items():
         f = getattr(lib, name)
@@ -282,9 +282,9 @@ class Context:
     def hgnn_probe_select(self, kernel: int, layer: int = -1):
         _check(lib.hgnn_probe_select(self.handle, kernel, layer))
 
-    def hgnn_probe_read(self):
+    def hgnn_probe_read(self, kernel: int, layer: int = -1):
         ms, n = C.c_double(), C.c_int64()
-        _check(lib.hgnn_probe_read(self.handle, C.byref(ms), C.byref(n)))
+        _check(lib.hgnn_probe_read(self.handle, kernel, layer, C.byref(ms), C.byref(n)))
         return ms.value, n.value
 
     def hgnn_softmax_xent(self, logits, labels, loss, grad_logits):

@@ -149,13 +149,18 @@ struct Probe {
   hipStream_t s;
   hipEvent_t stop = nullptr;
   Probe(hgnn_ctx *ctx, hipStream_t st, int kernel, int layer) : c(ctx), s(st) {
-    if (c->probe_kernel != kernel || (c->probe_layer >= 0 && c->probe_layer != layer)) return;
+    int slot = -1;
+    for (int i = 0; i < c->probe_n; ++i)
+      if (c->probe_sel[i][0] == kernel && (c->probe_sel[i][1] < 0 || c->probe_sel[i][1] == layer)) slot = i;
+    if (slot < 0) return;
     if (c->probe_used == c->probe_events.size()) {
       hipEvent_t a, b;
       if (hipEventCreate(&a) != hipSuccess) return;
       if (hipEventCreate(&b) != hipSuccess) { (void)hipEventDestroy(a); return; }
       c->probe_events.emplace_back(a, b);
     }
+    c->probe_slot.resize(c->probe_events.size());
+    c->probe_slot[c->probe_used] = slot;
     auto &pr = c->probe_events[c->probe_used++];
     (void)hipEventRecord(pr.first, s);
     stop = pr.second;
@@ -716,23 +721,33 @@ hgnn_status hgnn_softmax_xent(hgnn_ctx *ctx, void *stream, const void *logits, c
 hgnn_status hgnn_probe_select(hgnn_ctx *ctx, int32_t kernel, int32_t layer) {
   if (!ctx) HGNN_FAIL(HGNN_EINVAL, "NULL context");
   if (kernel > HGNN_K_XENT) HGNN_FAIL(HGNN_EINVAL, "unknown kernel id %d", kernel);
-  ctx->probe_kernel = kernel < 0 ? -1 : kernel;
-  ctx->probe_layer = layer;
-  ctx->probe_used = 0;
+  if (kernel < 0) {
+    ctx->probe_n = 0;
+    ctx->probe_used = 0;
+    return HGNN_OK;
+  }
+  if (ctx->probe_n >= 4) HGNN_FAIL(HGNN_EINVAL, "at most 4 kernels can be selected at a time");
+  ctx->probe_sel[ctx->probe_n][0] = kernel;
+  ctx->probe_sel[ctx->probe_n][1] = layer;
+  ++ctx->probe_n;
   return HGNN_OK;
 }
 
-hgnn_status hgnn_probe_read(hgnn_ctx *ctx, double *total_ms, int64_t *launches) {
+hgnn_status hgnn_probe_read(hgnn_ctx *ctx, int32_t kernel, int32_t layer, double *total_ms, int64_t *launches) {
   if (!ctx || !total_ms || !launches) HGNN_FAIL(HGNN_EINVAL, "NULL argument");
   double sum = 0;
+  int64_t n = 0;
   for (size_t i = 0; i < ctx->probe_used; ++i) {
+    const int sl = ctx->probe_slot[i];
+    if (ctx->probe_sel[sl][0] != kernel || ctx->probe_sel[sl][1] != layer) continue;
     float ms = 0;
     HGNN_HIP(hipEventSynchronize(ctx->probe_events[i].second));
     HGNN_HIP(hipEventElapsedTime(&ms, ctx->probe_events[i].first, ctx->probe_events[i].second));
     sum += ms;
+    ++n;
   }
   *total_ms = sum;
-  *launches = (int64_t)ctx->probe_used;
+  *launches = n;
   return HGNN_OK;
 }
 

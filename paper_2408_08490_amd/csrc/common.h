@@ -161,7 +161,9 @@ struct hgnn_ctx {
   std::vector<hgnn::Slab> free_slabs;
   std::vector<hipEvent_t> free_events;
   // kernel probe (measurement aid)
-  int probe_kernel = -1, probe_layer = -1;
+  int probe_sel[4][2];  // selected (kernel, layer) pairs
+  int probe_n = 0;
+  std::vector<int> probe_slot;  // selection each recorded event pair belongs to
   std::vector<std::pair<hipEvent_t, hipEvent_t>> probe_events;
   size_t probe_used = 0;
 };
