@@ -44,7 +44,13 @@ def main():
     ap.add_argument("--cpu-sample-batch", type=int, default=4096)
     ap.add_argument("--host-threads", type=int, default=0)
     ap.add_argument("--all-input-grads", action="store_true", help="also compute gradients w.r.t. the fixed T0 features")
-    ap.add_argument("--lookahead", type=int, default=4, help="mini-batches whose index build is started ahead of the GPU")
+    ap.add_argument("--calibrate", action="store_true",
+                    help="also launch the merge kernel as a plain copy of known size (2^20 rows x 128, identity ids) "
+                         "three times: reference for scaling rocprofv3 FETCH_SIZE / WRITE_SIZE readings")
+    ap.add_argument("--lookahead", type=int, default=24, help="mini-batches whose index build is started ahead of the GPU")
+    ap.add_argument("--concurrent-builds", type=int, default=16,
+                    help="host builders working on separate mini-batches at once (the host threads are split over them; "
+                         "0: the library's low-latency default)")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build runs on one GPU only (no collectives); use --gpus 1", file=sys.stderr)
@@ -76,7 +82,7 @@ def main():
 
     model = Model(g.schema, g.feat_dim, g.stores, ws, dtype=cfg.dtype,
                   loss=("xent" if cfg.loss == "xent" else "dot"), target_type=mbs[0].target_type,
-                  host_threads=args.host_threads,
+                  host_threads=args.host_threads, concurrent_builds=args.concurrent_builds,
                   # T0 carries fixed input features; only the learnable embeddings of T1-T3 need input gradients
                   first_layer_input_grad=([0, 1, 1, 1] if cfg.index in (1, 2, 4) and not args.all_input_grads else None))
     ctx = model.ctx
@@ -228,6 +234,17 @@ def main():
 
     for gr in graphs:
         gr.release()
+
+    if args.calibrate:
+        n_cal = 1 << 20
+        tdt = torch.bfloat16 if cfg.dtype == "bf16" else torch.float32
+        src = torch.ones((n_cal, 128), device=model.dev, dtype=tdt)
+        dst = torch.empty((n_cal, 128), device=model.dev, dtype=tdt)
+        ids = torch.arange(n_cal, device=model.dev, dtype=torch.int64)
+        T_ = sch.num_types
+        for _ in range(3):
+            ctx.hgnn_merge_features([src] + [None] * (T_ - 1), [ids] + [None] * (T_ - 1), dst, [128] * T_)
+        torch.cuda.synchronize()
 
     cpu = None
     if not args.no_cpu_baseline:

@@ -67,9 +67,14 @@ typedef struct {
   int32_t dtype;               /* hgnn_dtype */
 } hgnn_schema;
 
-/* Create a context bound to HIP device `device` with `host_threads` builder threads
- * (<= 0: one per online core, at most 16).  The schema is copied. */
-hgnn_status hgnn_create(hgnn_ctx **out, const hgnn_schema *schema, int device, int host_threads);
+/* Create a context bound to HIP device `device` (< 0: host-only, for the graph build alone)
+ * with `host_threads` builder threads (<= 0: one per online core, at most 16), split evenly
+ * over `concurrent_builds` builders that each work on one queued graph at a time (<= 0: a
+ * quarter of the threads, at most 4 builders: lowest latency for one build; == host_threads:
+ * single-threaded builds, the highest rate when many mini-batches are queued ahead).
+ * The schema is copied. */
+hgnn_status hgnn_create(hgnn_ctx **out, const hgnn_schema *schema, int device, int host_threads,
+                        int concurrent_builds);
 void hgnn_destroy(hgnn_ctx *ctx);
 /* Message of the calling thread's last failed call; never NULL. */
 const char *hgnn_last_error(void);

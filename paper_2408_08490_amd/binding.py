@@ -65,7 +65,7 @@ def _load():
     lib = C.CDLL(LIB_PATH)
     vp, i32, i64 = C.c_void_p, C.c_int32, C.c_int64
     sig = {
-        "hgnn_create": [C.POINTER(vp), C.POINTER(Schema), C.c_int, C.c_int],
+        "hgnn_create": [C.POINTER(vp), C.POINTER(Schema), C.c_int, C.c_int, C.c_int],
         "hgnn_merge_features": [vp, vp, C.POINTER(vp), C.POINTER(i32), C.POINTER(vp), C.POINTER(i64), vp,
                                 C.POINTER(i32), C.POINTER(i64)],
         "hgnn_build_semantic_csr": [vp, i32, C.POINTER(CooLayer), C.POINTER(vp)],
@@ -178,13 +178,13 @@ class Layer:
 
 class Context:
     def __init__(self, rel_src: Sequence[int], rel_dst: Sequence[int], num_types: int, dtype: str = "f32",
-                 device: int = 0, host_threads: int = 0):
+                 device: int = 0, host_threads: int = 0, concurrent_builds: int = 0):
         R = len(rel_src)
         self._rs = (C.c_int32 * R)(*rel_src)
         self._rd = (C.c_int32 * R)(*rel_dst)
         sch = Schema(num_types, R, self._rs, self._rd, 1, 0, 0, HGNN_BF16 if dtype == "bf16" else HGNN_F32)
         h = C.c_void_p()
-        _check(lib.hgnn_create(C.byref(h), C.byref(sch), device, host_threads))
+        _check(lib.hgnn_create(C.byref(h), C.byref(sch), device, host_threads, concurrent_builds))
         self.handle, self.num_types, self.num_rels, self.dtype = h, num_types, R, dtype
         self.rel_src, self.rel_dst = list(rel_src), list(rel_dst)
 

@@ -6,7 +6,7 @@ import subprocess
 HERE = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(HERE, "csrc")
 LIB = os.path.join(HERE, "libhgnn.so")
-SOURCES = ["api.cpp", "host_build.cpp", "kernels_mem.hip", "kernels_gemm.hip"]
+SOURCES = ["api.cpp", "host_build.cpp", "kernels_mem.hip", "kernels_spmm.hip", "kernels_gemm.hip"]
 
 
 def hipcc_path():
@@ -14,7 +14,7 @@ def hipcc_path():
 
 
 def build_library(verbose=True):
-    cmd = [hipcc_path(), "-O3", "-std=c++17", "--offload-arch=gfx950", "-fPIC", "-shared",
+    cmd = [hipcc_path(), "-O3", "-std=c++20", "--offload-arch=gfx950", "-fPIC", "-shared",
            "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",
            "-o", LIB + ".tmp"] + [os.path.join(CSRC, s) for s in SOURCES] + ["-lpthread"]
     if verbose:

@@ -185,7 +185,7 @@ extern "C" {
 
 const char *hgnn_last_error(void) { return hgnn::get_error(); }
 
-hgnn_status hgnn_create(hgnn_ctx **out, const hgnn_schema *s, int device, int host_threads) {
+hgnn_status hgnn_create(hgnn_ctx **out, const hgnn_schema *s, int device, int host_threads, int concurrent_builds) {
   if (!out || !s || !s->rel_src_type || !s->rel_dst_type) HGNN_FAIL(HGNN_EINVAL, "NULL argument");
   *out = nullptr;
   if (s->num_types < 1 || s->num_types > kMaxT) HGNN_FAIL(HGNN_EINVAL, "num_types %d outside [1,%d]", s->num_types, kMaxT);
@@ -221,8 +221,11 @@ hgnn_status hgnn_create(hgnn_ctx **out, const hgnn_schema *s, int device, int ho
     long on = sysconf(_SC_NPROCESSORS_ONLN);
     n = (int)std::min<long>(16, std::max<long>(1, on));
   }
-  // graphs are independent, so several are built at once: up to 4 builders share the host threads
-  const int nb = std::max(1, std::min(4, n / 4));
+  // Graphs are independent, so several are built at once, each by a builder with its own share
+  // of the host threads.  Few builders with several threads each finish one build soonest; one
+  // single-threaded builder per host thread gives the most builds per second (no barriers between
+  // the phases of a build), which is what a caller that queues many mini-batches ahead wants.
+  int nb = concurrent_builds > 0 ? std::min(n, concurrent_builds) : std::max(1, std::min(4, n / 4));
   for (int i = 0; i < nb; ++i) {
     Builder *b = new Builder();
     b->pool = new ThreadPool(n / nb + (i < n % nb ? 1 : 0));

@@ -79,8 +79,8 @@ struct LayerDev {
   int32_t rows, edges, src_rows, n_long, n_chunks;
 };
 
-constexpr int kLongRow = 256;  // transpose rows above this length are reduced chunk-wise
-constexpr int kChunk = 128;
+constexpr int kLongRow = 32;  // transpose rows above this length are reduced chunk-wise
+constexpr int kChunk = 32;
 
 struct LayerHost {
   int64_t rows = 0, edges = 0, src_rows = 0, tedges = 0;
@@ -180,6 +180,11 @@ hgnn_status launch_spmm_fwd(hipStream_t s, int dtype, const LayerDev &L, const T
 // dx[c] = sum over transpose row c of dz[crow] (+ root part for destination rows)
 hgnn_status launch_spmm_bwd(hipStream_t s, int dtype, const LayerDev &L, const TypeTab &tt, const RelTab &rt,
                             const PtrTab &pt, int max_dim, uint32_t want_types, const void *dz, void *dx, float *partial);
+// uniform feature width: return false when the width is outside what they cover (caller falls back)
+bool launch_spmm_fwd_uniform(hipStream_t s, int dtype, const LayerDev &L, int F, const void *x, void *z, void *zlo,
+                             int row_begin, int row_end);
+bool launch_spmm_bwd_uniform(hipStream_t s, int dtype, const LayerDev &L, const TypeTab &tt, const RelTab &rt, const PtrTab &pt,
+                             int F, uint32_t want, const void *dz, void *dx);
 hgnn_status launch_transpose_weights(hipStream_t s, int dtype, const TypeTab &tt, const RelTab &rt,
                                      const PtrTab &pt, const WtTab &wt, int H, void *wt_buf);
 // mode 0: all segments of every type fused (bias/activation epilogue, writes h)

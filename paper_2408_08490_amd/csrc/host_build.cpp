@@ -168,8 +168,8 @@ static bool build_layer(hgnn_ctx *ctx, Builder &bd, hgnn_graph *g, int l, BuildE
       if (in.edge_type) {
         r = in.edge_type[e];
       } else {
-        if (e + 16 < b) {
-          const int64_t nid = in.edge_id[e + 16];
+        if (e + 48 < b) {
+          const int64_t nid = in.edge_id[e + 48];
           if (nid >= 0 && nid < in.num_global_edges) __builtin_prefetch(in.global_edge_type + nid);
         }
         const int64_t id = in.edge_id[e];

@@ -134,6 +134,12 @@ hgnn_status launch_spmm_fwd(hipStream_t s, int dtype, const LayerDev &L, const T
                             int max_dim, const void *x, void *z, void *zlo, int row_begin, int row_end) {
   if (row_end <= row_begin) return HGNN_OK;
   const int es = dtype == HGNN_BF16 ? 2 : 4;
+  bool uniform = true;
+  for (int t = 0; t < tt.num_types; ++t) uniform &= tt.in_dim[t] == tt.in_dim[0];
+  if (uniform && launch_spmm_fwd_uniform(s, dtype, L, tt.in_dim[0], x, z, zlo, row_begin, row_end)) {
+    HGNN_HIP(hipGetLastError());
+    return HGNN_OK;
+  }
   const int l2 = lanes_log2_for(max_dim, es);
   const int rpb = 256 >> l2;
   dim3 grid((row_end - row_begin + rpb - 1) / rpb);
@@ -241,7 +247,7 @@ hgnn_status launch_spmm_bwd(hipStream_t s, int dtype, const LayerDev &L, const T
   const int es = dtype == HGNN_BF16 ? 2 : 4;
   const int l2 = lanes_log2_for(max_dim, es);
   const int gpb = 256 >> l2;
-  const int row_blocks = (L.src_rows + gpb - 1) / gpb;
+  int row_blocks = (L.src_rows + gpb - 1) / gpb;
   const int chunk_blocks = (L.n_chunks + gpb - 1) / gpb;
   uint32_t root_mask = 0;
   bool uniform = true;  // every relation's aggregate rows have the same width: dz row rho starts at rho * F
@@ -249,7 +255,13 @@ hgnn_status launch_spmm_bwd(hipStream_t s, int dtype, const LayerDev &L, const T
     if (pt.w_root[t]) root_mask |= 1u << t;
     if (tt.in_dim[t] != tt.in_dim[0]) uniform = false;
   }
+  // rows up to kLongRow edges: the uniform-width kernel when it applies, else the generic one below
+  if (uniform && launch_spmm_bwd_uniform(s, dtype, L, tt, rt, pt, tt.in_dim[0], want, dz, dx)) {
+    HGNN_HIP(hipGetLastError());
+    row_blocks = 0;
+  }
   dim3 grid(row_blocks + chunk_blocks);
+  if (grid.x > 0) {
   if (dtype == HGNN_BF16)
     hipLaunchKernelGGL(spmm_bwd_kernel<bf16>, grid, dim3(256), 0, s, L, tt, rt, root_mask, want, (const bf16 *)dz, (bf16 *)dx,
                        partial, max_dim, row_blocks, l2, (int)uniform);
@@ -257,6 +269,7 @@ hgnn_status launch_spmm_bwd(hipStream_t s, int dtype, const LayerDev &L, const T
     hipLaunchKernelGGL(spmm_bwd_kernel<float>, grid, dim3(256), 0, s, L, tt, rt, root_mask, want, (const float *)dz, (float *)dx,
                        partial, max_dim, row_blocks, l2, (int)uniform);
   HGNN_HIP(hipGetLastError());
+  }
   if (L.n_long > 0) {
     if (dtype == HGNN_BF16)
       hipLaunchKernelGGL(spmm_bwd_long_kernel<bf16>, dim3(L.n_long), dim3(128), 0, s, L, tt, rt, root_mask, want, (const bf16 *)dz,

@@ -1,0 +1,242 @@
+// Gather-mean over the merged CSR and its transpose for the common case that every vertex type has the
+// same feature width F (then row i of x_merged / of the aggregate starts at i * F and no per-row relation
+// lookup is needed).  These are the HBM-bound kernels of the path (the paper's merged aggregation,
+// Algorithm 1, evaluated without materialising per-edge feature copies).
+//
+// A wavefront owns 64/LPR consecutive rows (LPR = lanes per row, each lane moving C 16-byte pieces of a
+// feature row).  The rows of a wavefront are consecutive in the CSR, so their edges are one contiguous
+// range: the wave loads its row pointers with one load, its column indices with one or two coalesced
+// loads, and hands the indices to the lanes that need them through cross-lane reads.  All feature-row
+// loads of up to four edges are then in flight together.  Dependent round trips per wave: row pointers,
+// indices, features -- three, however many rows and edges it owns.
+#include "common.h"
+#include "device_types.h"
+
+namespace hgnn {
+
+// Column index of wave-relative edge `rel` (0 = first edge of the wave), from the two index registers.
+__device__ __forceinline__ int wave_col(int c0, int c1, int rel) {
+  const int r = min(max(rel, 0), 127);
+  const int a = __shfl(c0, r & 63), b = __shfl(c1, r & 63);
+  return r < 64 ? a : b;
+}
+
+template <typename T, int LPRL, int C>
+__global__ void __launch_bounds__(256) spmm_fwd_uniform_kernel(const int32_t *__restrict__ rowptr, const int32_t *__restrict__ colidx,
+                                                                const T *__restrict__ x, T *__restrict__ z, T *__restrict__ zlo,
+                                                                int F, int row_begin, int row_end) {
+  using V = Vec16<T>;
+  constexpr int LPR = 1 << LPRL, RPW = 64 / LPR;
+  const int lane = threadIdx.x & 63;
+  const int row0 = row_begin + (blockIdx.x * 4 + (threadIdx.x >> 6)) * RPW;
+  if (row0 >= row_end) return;  // whole wave
+  const int nrows = min(RPW, row_end - row0);
+  const int rp = rowptr[row0 + min(lane, nrows)];
+  const int e0 = __shfl(rp, 0), eN = __shfl(rp, nrows);
+  const int c0 = e0 + lane < eN ? colidx[e0 + lane] : 0;
+  const int c1 = e0 + 64 + lane < eN ? colidx[e0 + 64 + lane] : 0;
+  const int g = lane >> LPRL, sub = lane & (LPR - 1);
+  const int beg = __shfl(rp, min(g, nrows)), end = __shfl(rp, min(g + 1, nrows));
+  const int len = end - beg;
+  int maxlen = len;
+#pragma unroll
+  for (int o = 32; o >= LPR; o >>= 1) maxlen = max(maxlen, __shfl_xor(maxlen, o));
+  const int nvec = F / V::N;
+  const uint4 *xb = reinterpret_cast<const uint4 *>(x);
+  float acc[C][V::N];
+#pragma unroll
+  for (int p = 0; p < C; ++p)
+#pragma unroll
+    for (int i = 0; i < V::N; ++i) acc[p][i] = 0.f;
+  for (int i = 0; i < maxlen; i += 4) {  // same trip count for every lane: the cross-lane reads need all lanes
+    int col[4];
+#pragma unroll
+    for (int j = 0; j < 4; ++j) col[j] = wave_col(c0, c1, beg - e0 + i + j);
+    uint4 v[4][C];
+#pragma unroll
+    for (int j = 0; j < 4; ++j) {
+      const bool on = i + j < len;
+      int cj = col[j];
+      if (on && beg - e0 + i + j >= 128) cj = colidx[beg + i + j];  // beyond the two index registers
+#pragma unroll
+      for (int p = 0; p < C; ++p) {
+        const int q = sub + p * LPR;
+        v[j][p] = (on && q < nvec) ? xb[(int64_t)cj * nvec + q] : make_uint4(0, 0, 0, 0);
+      }
+    }
+#pragma unroll
+    for (int j = 0; j < 4; ++j)
+#pragma unroll
+      for (int p = 0; p < C; ++p) V::add(acc[p], v[j][p]);
+  }
+  if (g >= nrows) return;
+  const float inv = len > 0 ? 1.0f / (float)len : 0.0f;
+  const int64_t zoff = (int64_t)(row0 + g) * F;
+#pragma unroll
+  for (int p = 0; p < C; ++p) {
+    const int q = sub + p * LPR;
+    if (q >= nvec) continue;
+#pragma unroll
+    for (int i = 0; i < V::N; ++i) acc[p][i] *= inv;
+    const uint4 hi = V::pack(acc[p]);
+    reinterpret_cast<uint4 *>(z + zoff)[q] = hi;
+    if (zlo) {  // what the storage type dropped, so that the projection can add it back
+      float back[V::N];
+#pragma unroll
+      for (int i = 0; i < V::N; ++i) back[i] = 0.f;
+      V::add(back, hi);
+#pragma unroll
+      for (int i = 0; i < V::N; ++i) back[i] = acc[p][i] - back[i];
+      reinterpret_cast<uint4 *>(zlo + zoff)[q] = V::pack(back);
+    }
+  }
+}
+
+template <typename T, int LPRL, int C>
+static void launch_fwd_uniform(hipStream_t s, const LayerDev &L, const void *x, void *z, void *zlo, int F, int row_begin, int row_end) {
+  constexpr int RPB = 4 * (64 >> LPRL);
+  dim3 grid((row_end - row_begin + RPB - 1) / RPB);
+  hipLaunchKernelGGL((spmm_fwd_uniform_kernel<T, LPRL, C>), grid, dim3(256), 0, s, L.rowptr, L.colidx, (const T *)x, (T *)z,
+                     (T *)zlo, F, row_begin, row_end);
+}
+
+// Returns false when the shape is outside what the uniform kernels cover (the generic kernels then run).
+template <typename T, typename FN> static bool dispatch_width(int nvec, FN fn) {
+  // lanes per row: the largest power of two <= 64 that keeps the pieces per lane at 1, 2 or 4
+  if (nvec <= 1) fn.template operator()<0, 1>();
+  else if (nvec <= 2) fn.template operator()<1, 1>();
+  else if (nvec <= 4) fn.template operator()<2, 1>();
+  else if (nvec <= 8) fn.template operator()<3, 1>();
+  else if (nvec <= 16) fn.template operator()<4, 1>();
+  else if (nvec <= 32) fn.template operator()<4, 2>();
+  else if (nvec <= 64) fn.template operator()<5, 2>();
+  else if (nvec <= 128) fn.template operator()<6, 2>();
+  else if (nvec <= 256) fn.template operator()<6, 4>();
+  else return false;
+  return true;
+}
+
+bool launch_spmm_fwd_uniform(hipStream_t s, int dtype, const LayerDev &L, int F, const void *x, void *z, void *zlo,
+                             int row_begin, int row_end) {
+  const int es = dtype == HGNN_BF16 ? 2 : 4;
+  const int nvec = F * es / 16;
+  if (dtype == HGNN_BF16)
+    return dispatch_width<bf16>(nvec, [&]<int LPRL, int C>() { launch_fwd_uniform<bf16, LPRL, C>(s, L, x, z, zlo, F, row_begin, row_end); });
+  return dispatch_width<float>(nvec, [&]<int LPRL, int C>() { launch_fwd_uniform<float, LPRL, C>(s, L, x, z, nullptr, F, row_begin, row_end); });
+}
+
+// ------------------------------------------------------------------------------------------
+// Transpose: dx[c] = sum over transpose row c of dz[crow] (+ root-term gradient for destination rows).
+// Only the source rows of the vertex types listed in `ranges` are produced; rows longer than kLongRow are
+// left to the chunked path.
+struct RowRange {
+  int32_t lo, hi;        // merged source rows of one vertex type
+  int32_t n_dst;         // its destination rows (prefix)
+  int32_t wave0;         // first wave working on this range
+  int64_t root_off;      // scalars before its root-term gradient in dz, or -1 without a root term
+};
+struct RowRanges {
+  RowRange r[kMaxT];
+  int32_t n, total_waves;
+};
+
+template <typename T, int LPRL, int C>
+__global__ void __launch_bounds__(256) spmm_bwd_uniform_kernel(const int32_t *__restrict__ cptr, const int32_t *__restrict__ crow,
+                                                                RowRanges rr, const T *__restrict__ dz, T *__restrict__ dx, int F) {
+  using V = Vec16<T>;
+  constexpr int LPR = 1 << LPRL, RPW = 64 / LPR;
+  const int lane = threadIdx.x & 63;
+  const int wave = blockIdx.x * 4 + (threadIdx.x >> 6);
+  if (wave >= rr.total_waves) return;
+  int ri = 0;
+  while (ri + 1 < rr.n && wave >= rr.r[ri + 1].wave0) ++ri;
+  const RowRange R = rr.r[ri];
+  const int row0 = R.lo + (wave - R.wave0) * RPW;
+  const int nrows = min(RPW, R.hi - row0);
+  const int rp = cptr[row0 + min(lane, nrows)];
+  const int e0 = __shfl(rp, 0), eN = __shfl(rp, nrows);
+  const int c0 = e0 + lane < eN ? crow[e0 + lane] : 0;
+  const int c1 = e0 + 64 + lane < eN ? crow[e0 + 64 + lane] : 0;
+  const int g = lane >> LPRL, sub = lane & (LPR - 1);
+  const int beg = __shfl(rp, min(g, nrows)), end = __shfl(rp, min(g + 1, nrows));
+  const bool is_long = end - beg > kLongRow;
+  const int len = is_long ? 0 : end - beg;
+  int maxlen = len;
+#pragma unroll
+  for (int o = 32; o >= LPR; o >>= 1) maxlen = max(maxlen, __shfl_xor(maxlen, o));
+  const int nvec = F / V::N;
+  const uint4 *zb = reinterpret_cast<const uint4 *>(dz);
+  float acc[C][V::N];
+#pragma unroll
+  for (int p = 0; p < C; ++p)
+#pragma unroll
+    for (int i = 0; i < V::N; ++i) acc[p][i] = 0.f;
+  for (int i = 0; i < maxlen; i += 4) {
+    int col[4];
+#pragma unroll
+    for (int j = 0; j < 4; ++j) col[j] = wave_col(c0, c1, beg - e0 + i + j);
+    uint4 v[4][C];
+#pragma unroll
+    for (int j = 0; j < 4; ++j) {
+      const bool on = i + j < len;
+      int cj = col[j];
+      if (on && beg - e0 + i + j >= 128) cj = crow[beg + i + j];
+#pragma unroll
+      for (int p = 0; p < C; ++p) {
+        const int q = sub + p * LPR;
+        v[j][p] = (on && q < nvec) ? zb[(int64_t)cj * nvec + q] : make_uint4(0, 0, 0, 0);
+      }
+    }
+#pragma unroll
+    for (int j = 0; j < 4; ++j)
+#pragma unroll
+      for (int p = 0; p < C; ++p) V::add(acc[p], v[j][p]);
+  }
+  if (g >= nrows || is_long) return;
+  const int c = row0 + g, cl = c - R.lo;
+  const bool root = R.root_off >= 0 && cl < R.n_dst;
+#pragma unroll
+  for (int p = 0; p < C; ++p) {
+    const int q = sub + p * LPR;
+    if (q >= nvec) continue;
+    if (root) V::add(acc[p], reinterpret_cast<const uint4 *>(dz + R.root_off + (int64_t)cl * F)[q]);
+    reinterpret_cast<uint4 *>(dx + (int64_t)c * F)[q] = V::pack(acc[p]);
+  }
+}
+
+template <typename T, int LPRL, int C>
+static void launch_bwd_uniform(hipStream_t s, const LayerDev &L, RowRanges &rr, const void *dz, void *dx, int F) {
+  constexpr int RPW = 64 >> LPRL;
+  int w = 0;
+  for (int i = 0; i < rr.n; ++i) {
+    rr.r[i].wave0 = w;
+    w += (rr.r[i].hi - rr.r[i].lo + RPW - 1) / RPW;
+  }
+  rr.total_waves = w;
+  if (w == 0) return;
+  hipLaunchKernelGGL((spmm_bwd_uniform_kernel<T, LPRL, C>), dim3((w + 3) / 4), dim3(256), 0, s, L.cptr, L.crow, rr, (const T *)dz,
+                     (T *)dx, F);
+}
+
+bool launch_spmm_bwd_uniform(hipStream_t s, int dtype, const LayerDev &L, const TypeTab &tt, const RelTab &rt, const PtrTab &pt,
+                             int F, uint32_t want, const void *dz, void *dx) {
+  RowRanges rr;
+  rr.n = 0;
+  for (int t = 0; t < tt.num_types; ++t) {
+    if (!((want >> t) & 1u) || tt.row_off[t + 1] == tt.row_off[t]) continue;
+    RowRange &r = rr.r[rr.n++];
+    r.lo = tt.row_off[t];
+    r.hi = tt.row_off[t + 1];
+    r.n_dst = tt.n_dst[t];
+    r.root_off = pt.w_root[t] ? (int64_t)rt.zroot_off4[t] * 4 : -1;
+    r.wave0 = 0;
+  }
+  rr.total_waves = 0;
+  const int es = dtype == HGNN_BF16 ? 2 : 4;
+  const int nvec = F * es / 16;
+  if (dtype == HGNN_BF16)
+    return dispatch_width<bf16>(nvec, [&]<int LPRL, int C>() { launch_bwd_uniform<bf16, LPRL, C>(s, L, rr, dz, dx, F); });
+  return dispatch_width<float>(nvec, [&]<int LPRL, int C>() { launch_bwd_uniform<float, LPRL, C>(s, L, rr, dz, dx, F); });
+}
+
+}  // namespace hgnn

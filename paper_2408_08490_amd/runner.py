@@ -37,7 +37,7 @@ class Model:
     """Weights, feature stores and work buffers of one configuration on one GPU."""
 
     def __init__(self, schema, feat_dim, stores, layers, dtype="f32", loss="xent", target_type=0, device=0,
-                 host_threads=0, first_layer_input_grad=None):
+                 host_threads=0, first_layer_input_grad=None, concurrent_builds=0):
         """first_layer_input_grad: per type 0/1, which vertex types need gradients w.r.t. their input
         features in the first layer (learnable embeddings); None = all."""
         self.dev = torch.device("cuda", device)
@@ -45,7 +45,7 @@ class Model:
         self.dtype, self.loss, self.target_type = dtype, loss, target_type
         self.first_layer_input_grad = first_layer_input_grad
         self.T, self.R = schema.num_types, schema.num_rels
-        self.ctx = B.Context(schema.rel_src, schema.rel_dst, schema.num_types, dtype, device, host_threads)
+        self.ctx = B.Context(schema.rel_src, schema.rel_dst, schema.num_types, dtype, device, host_threads, concurrent_builds)
         self.feat_dim = list(feat_dim)
         self.stores = [to_device(s, dtype, self.dev) for s in stores]
         self.layers: List[B.Layer] = []

@@ -33,8 +33,9 @@ def test_exports_match_header(B):
     assert set(B.EXPORTS) == declared
 
 
-def _host_ctx(B, sch, dtype="f32", threads=4):
-    return B.Context(sch.rel_src, sch.rel_dst, sch.num_types, dtype, device=-1, host_threads=threads)
+def _host_ctx(B, sch, dtype="f32", threads=4, concurrent_builds=0):
+    return B.Context(sch.rel_src, sch.rel_dst, sch.num_types, dtype, device=-1, host_threads=threads,
+                     concurrent_builds=concurrent_builds)
 
 
 @pytest.mark.parametrize("index,scale,threads", [(0, 1.0, 1), (0, 1.0, 4), (2, 0.02, 8), (3, 0.003, 3)])
@@ -168,11 +169,13 @@ def test_device_entry_points_refuse_host_only_context(B):
     ctx.close()
 
 
-def test_overlapping_builds_from_one_context(B):
+@pytest.mark.parametrize("threads,builders", [(4, 0), (4, 4), (6, 4), (8, 2)])
+def test_overlapping_builds_from_one_context(B, threads, builders):
+    """Several builders (single- or multi-threaded) work on queued graphs at once."""
     cfg = make_config(2, scale=0.02, batch=64)
     g = build_graph(cfg)
-    mbs = [sample_minibatch(cfg, g, rng=np.random.default_rng(i)) for i in range(4)]
-    ctx = _host_ctx(B, g.schema, threads=4)
+    mbs = [sample_minibatch(cfg, g, rng=np.random.default_rng(i)) for i in range(6)]
+    ctx = _host_ctx(B, g.schema, threads=threads, concurrent_builds=builders)
     graphs = [ctx.hgnn_build_semantic_csr(mb.blocks) for mb in mbs]       # all queued before any wait
     for mb, gr in zip(mbs, graphs):
         for l, b in enumerate(mb.blocks):
