@@ -11,13 +11,14 @@ struct bf16 {
 };
 
 __device__ __forceinline__ float bf16_bits_to_float(uint32_t b) { return __uint_as_float(b << 16); }
-// round to nearest, ties to even; NaN stays NaN
-__device__ __forceinline__ uint32_t float_to_bf16_bits(float f) {
-  uint32_t u = __float_as_uint(f);
-  if ((u & 0x7fffffffu) > 0x7f800000u) return (u >> 16) | 0x40u;
-  u += 0x7fffu + ((u >> 16) & 1u);
-  return u >> 16;
+// Round to nearest, ties to even; NaN stays (quiet) NaN.  gfx950 converts in hardware, two values per
+// instruction; the result equals the integer recipe (add 0x7fff + lsb, shift) bit for bit.
+typedef __bf16 bf16x2_t __attribute__((ext_vector_type(2)));
+typedef float f32x2_t __attribute__((ext_vector_type(2)));
+__device__ __forceinline__ uint32_t pack2(float a, float b) {  // a in the low half
+  return __builtin_bit_cast(uint32_t, __builtin_convertvector(f32x2_t{a, b}, bf16x2_t));
 }
+__device__ __forceinline__ uint32_t float_to_bf16_bits(float f) { return pack2(f, 0.f) & 0xffffu; }
 
 __device__ __forceinline__ float to_float(float v) { return v; }
 __device__ __forceinline__ float to_float(bf16 v) { return bf16_bits_to_float(v.bits); }
@@ -57,10 +58,10 @@ template <> struct Vec16<bf16> {
   }
   static __device__ __forceinline__ uint4 pack(const float *a) {
     uint4 r;
-    r.x = float_to_bf16_bits(a[0]) | (float_to_bf16_bits(a[1]) << 16);
-    r.y = float_to_bf16_bits(a[2]) | (float_to_bf16_bits(a[3]) << 16);
-    r.z = float_to_bf16_bits(a[4]) | (float_to_bf16_bits(a[5]) << 16);
-    r.w = float_to_bf16_bits(a[6]) | (float_to_bf16_bits(a[7]) << 16);
+    r.x = pack2(a[0], a[1]);
+    r.y = pack2(a[2], a[3]);
+    r.z = pack2(a[4], a[5]);
+    r.w = pack2(a[6], a[7]);
     return r;
   }
 };

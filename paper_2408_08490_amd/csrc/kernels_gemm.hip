@@ -22,9 +22,11 @@ typedef float f32x16 __attribute__((ext_vector_type(16)));
 typedef __bf16 bf16x8_t __attribute__((ext_vector_type(8)));
 typedef unsigned int u32x4 __attribute__((ext_vector_type(4)));
 typedef unsigned int u32x2 __attribute__((ext_vector_type(2)));
+typedef float f32x4 __attribute__((ext_vector_type(4)));
 
 constexpr int BM = 128, BN = 128, kThreads = 256;
 constexpr int kSegCap = 96;  // K-segments staged in LDS at a time
+constexpr int kRelWindow = (kSegCap - 1) / 2;  // relations examined per pass of the forward kernel (two segments each + root)
 
 template <typename T> struct Mma;
 template <> struct Mma<bf16> {
@@ -195,8 +197,7 @@ template <typename T> struct GemmLds {
   Seg<T> seg[kSegCap];
   float rowscale[BM];
 };
-constexpr int kOutPitchPad = 8;  // elements; keeps 16-byte alignment of the staged rows for both types
-static_assert((BN + kOutPitchPad) * BM * 4 <= 4 * lds_elems<float>() * 4, "fp32 output tile must fit the stages");
+constexpr int kOutPitchPad = 8;  // floats: staged rows stay 16-byte aligned, rows r and r + 4 lie 32 banks apart
 
 // Runs the K-steps of sm.seg[0..nseg) (must be visible to the whole block) into `acc`.
 // KC operand: matrix [extent x K] row-major (ld); KS operand: matrix [K x extent] row-major (ld).
@@ -282,13 +283,17 @@ __device__ __forceinline__ void zero_acc(f32x16 (&acc)[2][2]) {
 // Writes the block's 128x128 tile `out[(row0 + r) * ld + col0 + c] = f(acc, r, c)` for r < rows, c < cols.
 // When rows of `out` are 16-byte aligned the tile goes through LDS (the K loop's stages are free by then)
 // and leaves as whole 16-byte pieces; otherwise element by element.  `f(val, row, col)` returns the value.
+// The staged tile is fp32 whatever T is: 32-bit LDS writes with a pitch that puts the two half-waves
+// (rows r and r + 4 of one store) on disjoint banks; two lanes writing the halves of one dword would be
+// serialised.  Conversion to T happens on the way out.
 template <typename T, typename F>
 __device__ __forceinline__ void write_tile(f32x16 (&acc)[2][2], GemmLds<T> &sm, T *out, int64_t ld, int rows, int cols, F f) {
   constexpr int V = 16 / sizeof(T), P = BN + kOutPitchPad;
+  static_assert(sizeof(sm.a) + sizeof(sm.b) >= sizeof(float) * P * BM, "fp32 output tile must fit the stages");
   const bool vec = (ld % V) == 0 && (reinterpret_cast<uintptr_t>(out) & 15) == 0;
   if (vec) {
-    T *stage = &sm.a[0][0];
-    HGNN_FOR_EACH_ACC({ stage[row * P + col] = from_float<T>(f(val, row, col)); })
+    float *stage = reinterpret_cast<float *>(&sm.a[0][0]);
+    HGNN_FOR_EACH_ACC({ stage[row * P + col] = f(val, row, col); })
     __syncthreads();
     constexpr int VPR = BN / V;
 #pragma unroll
@@ -296,12 +301,29 @@ __device__ __forceinline__ void write_tile(f32x16 (&acc)[2][2], GemmLds<T> &sm, 
       const int v = threadIdx.x + i * kThreads;
       const int r = v / VPR, c = (v % VPR) * V;
       if (r < rows && c < cols) {
-        const u32x4 piece = *reinterpret_cast<const u32x4 *>(stage + r * P + c);
-        if (c + V <= cols) {
-          *reinterpret_cast<u32x4 *>(out + (int64_t)r * ld + c) = piece;
+        const float *sp = stage + r * P + c;
+        u32x4 piece;
+        if constexpr (sizeof(T) == 4) {
+          piece = *reinterpret_cast<const u32x4 *>(sp);
         } else {
-          const T *e = reinterpret_cast<const T *>(&piece);
-          for (int j = 0; c + j < cols; ++j) out[(int64_t)r * ld + c + j] = e[j];
+          const f32x4 lo = *reinterpret_cast<const f32x4 *>(sp), hi = *reinterpret_cast<const f32x4 *>(sp + 4);
+          piece = u32x4{pack2(lo.x, lo.y), pack2(lo.z, lo.w), pack2(hi.x, hi.y), pack2(hi.z, hi.w)};
+        }
+        T *dst = out + (int64_t)r * ld + c;
+        if (c + V <= cols) {
+          *reinterpret_cast<u32x4 *>(dst) = piece;
+        } else {  // last, partial piece of a row: element by element out of the registers
+#pragma unroll
+          for (int j = 0; j < V; ++j) {
+            if (c + j < cols) {
+              if constexpr (sizeof(T) == 4) {
+                reinterpret_cast<unsigned *>(dst)[j] = piece[j];
+              } else {
+                const unsigned w = piece[j >> 1];
+                reinterpret_cast<unsigned short *>(dst)[j] = (unsigned short)((j & 1) ? (w >> 16) : (w & 0xffffu));
+              }
+            }
+          }
         }
       }
     }
@@ -325,6 +347,20 @@ __device__ __forceinline__ void put_seg(Seg<T> &g, const T *A, int lda, const T 
   g.A = A; g.B = B; g.lda = lda; g.ldb = ldb; g.kb = kb; g.ke = ke;
 }
 
+// All blocks of a launch's first resident set start together, reach their epilogues together and start their
+// successors together: the multiply phases leave HBM idle and the store phases leave the matrix cores idle,
+// round after round.  Delaying the first set by a quarter, a half and three quarters of a tile time spreads
+// the phases for the whole launch (later blocks start whenever an earlier one ends).  The two blocks that
+// share a compute unit (hardware placement: block j of an XCD and block j + 32) end up half a tile apart.
+// `units` = sleeps of about 6400 clocks per quarter phase; 0 = no stagger.
+constexpr int kResidentBlocks = 512;
+__device__ __forceinline__ void stagger_start(int units) {
+  if (units <= 0 || blockIdx.x >= kResidentBlocks) return;
+  const int j = blockIdx.x >> 3;
+  const int phase = ((j >> 5) & 1) * 2 + (j & 1);
+  for (int i = 0; i < phase * units; ++i) __builtin_amdgcn_s_sleep(100);
+}
+
 // ------------------------------------------------------------------------------------------
 // Forward.  `live` has bit r set when relation r has at least one edge in this layer.
 struct LiveMask {
@@ -336,12 +372,13 @@ __global__ void __launch_bounds__(kThreads, 2) gemm_fwd_kernel(TypeTab tt, RelTa
                                                             int H, int relu, const T *__restrict__ x, const T *__restrict__ z,
                                                             const T *__restrict__ zlo, const T *__restrict__ wtb,
                                                             T *__restrict__ h, int only_seg,
-                                                            float *__restrict__ acc32) {
+                                                            float *__restrict__ acc32, int stagger) {
   __shared__ GemmLds<T> sm;
-  __shared__ int s_nseg, s_next;
-  const int tile = xcd_tile(blockIdx.x, gridDim.x);
+  __shared__ int s_nseg;
   const int T_ = tt.num_types, R = rt.num_rels;
+  const int tile = xcd_tile(blockIdx.x, gridDim.x);
   if (tile >= tiles.tile_off[T_]) return;
+  stagger_start(stagger);
   int d = 0;
   while (tile >= tiles.tile_off[d + 1]) ++d;
   const int tiles_n = (H + BN - 1) / BN;
@@ -351,33 +388,33 @@ __global__ void __launch_bounds__(kThreads, 2) gemm_fwd_kernel(TypeTab tt, RelTa
   f32x16 acc[2][2];
   zero_acc(acc);
   // K-segments of this destination type: every relation ending in d (aggregate, and for bf16 storage its
-  // low-order remainder against the same weights), then the root term.  Staged kSegCap at a time.
-  int cursor = 0;  // next relation to look at; R = root; R + 1 = done
-  while (cursor <= R) {
-    if (threadIdx.x == 0) {
-      int n = 0, r = cursor;
-      for (; r < R && n + 2 <= kSegCap; ++r) {
-        if (rt.dst[r] != d || (only_seg >= 0 && only_seg != r)) continue;
-        if (!((live.w[r >> 5] >> (r & 31)) & 1u)) continue;  // no edge: the aggregate is all zero
+  // low-order remainder against the same weights), then the root term.  The first wavefront looks at a
+  // window of relations at once, one per lane, and packs the ones that take part with a ballot.
+  for (int cursor = 0; cursor < R; cursor += kRelWindow) {
+    if (threadIdx.x < 64) {
+      const int lane = threadIdx.x, r = cursor + lane;
+      bool use = lane < kRelWindow && r < R;
+      if (use) use = rt.dst[r] == d && (only_seg < 0 || only_seg == r) && ((live.w[r >> 5] >> (r & 31)) & 1u);  // no edge: all zero
+      const unsigned long long m = __ballot(use);
+      const int mult = zlo ? 2 : 1;
+      if (use) {
+        const int pos = __popcll(m & ((1ull << lane) - 1ull)) * mult;
         const int F = tt.in_dim[rt.src[r]];
         const T *B = wtb + (int64_t)wt.rel4[r] * 4;
-        put_seg(sm.seg[n++], z + (int64_t)rt.z_off4[r] * 4, F, B, F, 0, F);
-        if (zlo) put_seg(sm.seg[n++], zlo + (int64_t)rt.z_off4[r] * 4, F, B, F, 0, F);
+        put_seg(sm.seg[pos], z + (int64_t)rt.z_off4[r] * 4, F, B, F, 0, F);
+        if (zlo) put_seg(sm.seg[pos + 1], zlo + (int64_t)rt.z_off4[r] * 4, F, B, F, 0, F);
       }
-      if (r == R && n + 1 <= kSegCap) {
-        if (pt.w_root[d] && (only_seg < 0 || only_seg == R + d)) {
+      if (lane == 0) {
+        int n = __popcll(m) * mult;
+        if (cursor + kRelWindow >= R && pt.w_root[d] && (only_seg < 0 || only_seg == R + d)) {
           const int F = tt.in_dim[d];
           put_seg(sm.seg[n++], x + tt.elem_off[d], F, wtb + (int64_t)wt.root4[d] * 4, F, 0, F);
         }
-        r = R + 1;
+        s_nseg = n;
       }
-      s_nseg = n;
-      s_next = r;
     }
     __syncthreads();
-    const int nseg = s_nseg;
-    cursor = s_next;
-    gemm_run<T, FAST, true, true>(acc, sm, nseg, M, m0, H, n0);
+    gemm_run<T, FAST, true, true>(acc, sm, s_nseg, M, m0, H, n0);
   }
   const int64_t orow = tt.out_row_off[d];
   if (acc32) {
@@ -407,6 +444,8 @@ hgnn_status launch_gemm_fwd(hipStream_t s, int dtype, const LayerDev &L, const T
   const int n = tiles.tile_off[tt.num_types];
   if (n == 0) return HGNN_OK;
   (void)L;
+  static const int stagger_env = getenv("HGNN_STAGGER") ? atoi(getenv("HGNN_STAGGER")) : 1;
+  const int stagger = n > kResidentBlocks ? stagger_env : 0;
   LiveMask live;
   for (int i = 0; i < kMaxR / 32; ++i) live.w[i] = live_mask[i];
   dim3 grid(round_up8(n));
@@ -414,11 +453,11 @@ hgnn_status launch_gemm_fwd(hipStream_t s, int dtype, const LayerDev &L, const T
   // x_merged, whose row widths are multiples of 16 bytes: always the FAST form
   if (dtype == HGNN_BF16)
     hipLaunchKernelGGL((gemm_fwd_kernel<bf16, true>), grid, dim3(kThreads), 0, s, tt, rt, pt, wt, tiles, live, H, relu,
-                       (const bf16 *)x, (const bf16 *)z, (const bf16 *)zlo, (const bf16 *)wt_buf, (bf16 *)h, only_seg, acc32);
+                       (const bf16 *)x, (const bf16 *)z, (const bf16 *)zlo, (const bf16 *)wt_buf, (bf16 *)h, only_seg, acc32, stagger);
   else
     hipLaunchKernelGGL((gemm_fwd_kernel<float, true>), grid, dim3(kThreads), 0, s, tt, rt, pt, wt, tiles, live, H, relu,
                        (const float *)x, (const float *)z, (const float *)nullptr, (const float *)wt_buf, (float *)h,
-                       only_seg, acc32);
+                       only_seg, acc32, stagger);
   HGNN_HIP(hipGetLastError());
   return HGNN_OK;
 }
