@@ -30,7 +30,7 @@ constexpr int kRelWindow = (kSegCap - 1) / 2;  // relations examined per pass of
 
 template <typename T> struct Mma;
 template <> struct Mma<bf16> {
-  static constexpr int BK = 64, KSTEP = 16, VEC = 8, PKC = BK + 8, PKS = 128 + 4;
+  static constexpr int BK = 64, KSTEP = 16, VEC = 8, PKC = BK + 8, PKS = 128 + 16;  // PKS: four k-rows of a transposing read on disjoint banks
 };
 template <> struct Mma<float> {
   static constexpr int BK = 32, KSTEP = 2, VEC = 4, PKC = BK + 4, PKS = 128 + 4;
@@ -147,10 +147,17 @@ template <bool KC> __device__ __forceinline__ bf16x8_t frag_bf16(const bf16 *s, 
   if constexpr (KC) {
     return *reinterpret_cast<const bf16x8_t *>(s + (o + (lane & 31)) * M::PKC + ks * 16 + 8 * (lane >> 5));
   } else {
-    union { bf16x8_t v; uint16_t e[8]; } u;
-    const bf16 *p = s + (ks * 16 + 8 * (lane >> 5)) * M::PKS + o + (lane & 31);
-#pragma unroll
-    for (int j = 0; j < 8; ++j) u.e[j] = p[j * M::PKS].bits;
+    // The operand lies in LDS with the output index contiguous; the transposing LDS read hands every lane
+    // four consecutive k of one output index.  Within a group of 16 lanes, lane p passes the address of four
+    // contiguous 16-bit values ("row" p) and lane i receives rows (i / 4) + 4 j, j = 0..3, at position i % 4:
+    // with row p = (k0 + p / 4, outputs o16 + 4 (p % 4) ...) lane i ends up with k0..k0+3 of output o16 + i.
+    typedef short v4i16 __attribute__((ext_vector_type(4)));
+    typedef __attribute__((address_space(3))) v4i16 *lds_v4;
+    const int p = lane & 15;
+    const bf16 *q = s + (ks * 16 + 8 * (lane >> 5) + (p >> 2)) * M::PKS + o + 16 * ((lane >> 4) & 1) + 4 * (p & 3);
+    union { bf16x8_t v; v4i16 h[2]; } u;
+    u.h[0] = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_v4)q);
+    u.h[1] = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_v4)(q + 4 * M::PKS));
     return u.v;
   }
 }
@@ -347,20 +354,6 @@ __device__ __forceinline__ void put_seg(Seg<T> &g, const T *A, int lda, const T 
   g.A = A; g.B = B; g.lda = lda; g.ldb = ldb; g.kb = kb; g.ke = ke;
 }
 
-// All blocks of a launch's first resident set start together, reach their epilogues together and start their
-// successors together: the multiply phases leave HBM idle and the store phases leave the matrix cores idle,
-// round after round.  Delaying the first set by a quarter, a half and three quarters of a tile time spreads
-// the phases for the whole launch (later blocks start whenever an earlier one ends).  The two blocks that
-// share a compute unit (hardware placement: block j of an XCD and block j + 32) end up half a tile apart.
-// `units` = sleeps of about 6400 clocks per quarter phase; 0 = no stagger.
-constexpr int kResidentBlocks = 512;
-__device__ __forceinline__ void stagger_start(int units) {
-  if (units <= 0 || blockIdx.x >= kResidentBlocks) return;
-  const int j = blockIdx.x >> 3;
-  const int phase = ((j >> 5) & 1) * 2 + (j & 1);
-  for (int i = 0; i < phase * units; ++i) __builtin_amdgcn_s_sleep(100);
-}
-
 // ------------------------------------------------------------------------------------------
 // Forward.  `live` has bit r set when relation r has at least one edge in this layer.
 struct LiveMask {
@@ -372,13 +365,12 @@ __global__ void __launch_bounds__(kThreads, 2) gemm_fwd_kernel(TypeTab tt, RelTa
                                                             int H, int relu, const T *__restrict__ x, const T *__restrict__ z,
                                                             const T *__restrict__ zlo, const T *__restrict__ wtb,
                                                             T *__restrict__ h, int only_seg,
-                                                            float *__restrict__ acc32, int stagger) {
+                                                            float *__restrict__ acc32) {
   __shared__ GemmLds<T> sm;
   __shared__ int s_nseg;
   const int T_ = tt.num_types, R = rt.num_rels;
   const int tile = xcd_tile(blockIdx.x, gridDim.x);
   if (tile >= tiles.tile_off[T_]) return;
-  stagger_start(stagger);
   int d = 0;
   while (tile >= tiles.tile_off[d + 1]) ++d;
   const int tiles_n = (H + BN - 1) / BN;
@@ -444,8 +436,6 @@ hgnn_status launch_gemm_fwd(hipStream_t s, int dtype, const LayerDev &L, const T
   const int n = tiles.tile_off[tt.num_types];
   if (n == 0) return HGNN_OK;
   (void)L;
-  static const int stagger_env = getenv("HGNN_STAGGER") ? atoi(getenv("HGNN_STAGGER")) : 1;
-  const int stagger = n > kResidentBlocks ? stagger_env : 0;
   LiveMask live;
   for (int i = 0; i < kMaxR / 32; ++i) live.w[i] = live_mask[i];
   dim3 grid(round_up8(n));
@@ -453,11 +443,11 @@ hgnn_status launch_gemm_fwd(hipStream_t s, int dtype, const LayerDev &L, const T
   // x_merged, whose row widths are multiples of 16 bytes: always the FAST form
   if (dtype == HGNN_BF16)
     hipLaunchKernelGGL((gemm_fwd_kernel<bf16, true>), grid, dim3(kThreads), 0, s, tt, rt, pt, wt, tiles, live, H, relu,
-                       (const bf16 *)x, (const bf16 *)z, (const bf16 *)zlo, (const bf16 *)wt_buf, (bf16 *)h, only_seg, acc32, stagger);
+                       (const bf16 *)x, (const bf16 *)z, (const bf16 *)zlo, (const bf16 *)wt_buf, (bf16 *)h, only_seg, acc32);
   else
     hipLaunchKernelGGL((gemm_fwd_kernel<float, true>), grid, dim3(kThreads), 0, s, tt, rt, pt, wt, tiles, live, H, relu,
                        (const float *)x, (const float *)z, (const float *)nullptr, (const float *)wt_buf, (float *)h,
-                       only_seg, acc32, stagger);
+                       only_seg, acc32);
   HGNN_HIP(hipGetLastError());
   return HGNN_OK;
 }
