@@ -666,7 +666,8 @@ hgnn_status hgnn_layer_bwd(hgnn_ctx *ctx, void *stream, hgnn_graph *g, int32_t l
         if (live_seg(sgi, d, F))
           tiles += (int64_t)((F + 127) / 128) * ((pl.H + 127) / 128) * ((pl.tt.n_dst[d] + split_rows - 1) / split_rows);
       }
-      if (tiles >= 320 || split_rows <= 128) break;
+      static const int64_t want = getenv("HGNN_DW_TILES") ? atoi(getenv("HGNN_DW_TILES")) : 320;
+      if (tiles >= want || split_rows <= 128) break;
       split_rows /= 2;
     }
     for (int sgi = 0; sgi < R + T; ++sgi) {

@@ -220,10 +220,15 @@ __global__ void __launch_bounds__(256) spmm_bwd_kernel(LayerDev L, TypeTab tt, R
   }
 }
 
-template <typename T>
+// Long rows: sums the chunk partials of one source row (one block per row), adds the root part and writes
+// the row.  W = floats per load (4 when the row width allows).  The block's threads form `groups` groups of
+// `lanes` threads; group g sums chunks g, g + groups, ... four at a time, LDS adds the groups up.
+template <typename T, int W>
 __global__ void __launch_bounds__(256) spmm_bwd_long_kernel(LayerDev L, TypeTab tt, RelTab rt, uint32_t root_mask, uint32_t want,
                                                              const T *__restrict__ dz, T *__restrict__ dx,
                                                              const float *__restrict__ partial, int max_dim) {
+  typedef float fw __attribute__((ext_vector_type(W)));
+  __shared__ float red[256 * W];
   const int i = blockIdx.x;  // one block per long row
   const int c = L.long_row[i];
   int t = 0;
@@ -233,11 +238,41 @@ __global__ void __launch_bounds__(256) spmm_bwd_long_kernel(LayerDev L, TypeTab 
   const int cl = c - tt.row_off[t];
   const int j0 = L.long_chunk0[i], j1 = L.long_chunk0[i + 1];
   const bool root = cl < tt.n_dst[t] && ((root_mask >> t) & 1u);
-  for (int f = threadIdx.x; f < F; f += blockDim.x) {
-    float acc = 0.f;
-    for (int j = j0; j < j1; ++j) acc += partial[(int64_t)j * max_dim + f];
-    if (root) acc += to_float(dz[(int64_t)rt.zroot_off4[t] * 4 + (int64_t)cl * F + f]);
-    dx[tt.elem_off[t] + (int64_t)cl * F + f] = from_float<T>(acc);
+  const int nw = F / W;                       // loads per row (W divides F)
+  int lanes = 1;
+  while (lanes < nw && lanes < 256) lanes <<= 1;
+  const int groups = 256 / lanes, g = threadIdx.x / lanes, ln = threadIdx.x % lanes;
+  for (int q0 = 0; q0 < nw; q0 += lanes) {    // more than one pass only for rows wider than 256 loads
+    const int q = q0 + ln;
+    fw acc = {};
+    if (q < nw) {
+      int j = j0 + g;
+      for (; j + 3 * groups < j1; j += 4 * groups) {
+        const fw v0 = *reinterpret_cast<const fw *>(partial + (int64_t)j * max_dim + q * W);
+        const fw v1 = *reinterpret_cast<const fw *>(partial + (int64_t)(j + groups) * max_dim + q * W);
+        const fw v2 = *reinterpret_cast<const fw *>(partial + (int64_t)(j + 2 * groups) * max_dim + q * W);
+        const fw v3 = *reinterpret_cast<const fw *>(partial + (int64_t)(j + 3 * groups) * max_dim + q * W);
+        acc += (v0 + v1) + (v2 + v3);
+      }
+      for (; j < j1; j += groups) acc += *reinterpret_cast<const fw *>(partial + (int64_t)j * max_dim + q * W);
+    }
+    if (groups > 1) {
+      *reinterpret_cast<fw *>(red + threadIdx.x * W) = acc;
+      __syncthreads();
+      if (g == 0) {
+        for (int o = 1; o < groups; ++o) acc += *reinterpret_cast<const fw *>(red + (o * lanes + ln) * W);
+      }
+    }
+    if (g == 0 && q < nw) {
+#pragma unroll
+      for (int k = 0; k < W; ++k) {
+        const int f = q * W + k;
+        float v = acc[k];
+        if (root) v += to_float(dz[(int64_t)rt.zroot_off4[t] * 4 + (int64_t)cl * F + f]);
+        dx[tt.elem_off[t] + (int64_t)cl * F + f] = from_float<T>(v);
+      }
+    }
+    if (groups > 1) __syncthreads();
   }
 }
 
@@ -271,12 +306,17 @@ hgnn_status launch_spmm_bwd(hipStream_t s, int dtype, const LayerDev &L, const T
   HGNN_HIP(hipGetLastError());
   }
   if (L.n_long > 0) {
-    if (dtype == HGNN_BF16)
-      hipLaunchKernelGGL(spmm_bwd_long_kernel<bf16>, dim3(L.n_long), dim3(128), 0, s, L, tt, rt, root_mask, want, (const bf16 *)dz,
-                         (bf16 *)dx, partial, max_dim);
-    else
-      hipLaunchKernelGGL(spmm_bwd_long_kernel<float>, dim3(L.n_long), dim3(128), 0, s, L, tt, rt, root_mask, want, (const float *)dz,
-                         (float *)dx, partial, max_dim);
+    bool w4 = (max_dim % 4) == 0;   // every row of the partial buffer starts 16-byte aligned
+    for (int t = 0; t < tt.num_types; ++t)
+      if (tt.in_dim[t] % 4) w4 = false;
+    const dim3 g(L.n_long), b(256);
+    if (dtype == HGNN_BF16) {
+      if (w4) hipLaunchKernelGGL((spmm_bwd_long_kernel<bf16, 4>), g, b, 0, s, L, tt, rt, root_mask, want, (const bf16 *)dz, (bf16 *)dx, partial, max_dim);
+      else hipLaunchKernelGGL((spmm_bwd_long_kernel<bf16, 1>), g, b, 0, s, L, tt, rt, root_mask, want, (const bf16 *)dz, (bf16 *)dx, partial, max_dim);
+    } else {
+      if (w4) hipLaunchKernelGGL((spmm_bwd_long_kernel<float, 4>), g, b, 0, s, L, tt, rt, root_mask, want, (const float *)dz, (float *)dx, partial, max_dim);
+      else hipLaunchKernelGGL((spmm_bwd_long_kernel<float, 1>), g, b, 0, s, L, tt, rt, root_mask, want, (const float *)dz, (float *)dx, partial, max_dim);
+    }
     HGNN_HIP(hipGetLastError());
   }
   return HGNN_OK;
