@@ -222,13 +222,15 @@ hgnn_status hgnn_softmax_xent(hgnn_ctx *ctx, void *stream, const void *logits, c
                               int64_t rows, int32_t classes, float *loss, void *grad_logits);
 
 /* ---- Measurement aid --------------------------------------------------------------------
- * Brackets every later launch of the selected kernels (on the launching stream) with a pair of HIP
- * events so that a benchmark can report a kernel's average duration without a profiler attached.
+ * Attaches a pair of HIP events to every later dispatch of the selected kernels (the events carry the
+ * dispatch's own begin and end timestamps) so that a benchmark can report a kernel's average duration
+ * without a profiler attached.  A call that launches several kernels (transposed aggregation with
+ * long rows) adds their durations up.
  *   hgnn_probe_select(kernel, layer): adds (kernel, layer) to the selection (at most 4 entries);
  *     kernel = hgnn_kernel_id, layer = layer index or < 0 for every layer; kernel < 0 clears the
  *     selection and discards what was collected.
  *   hgnn_probe_read(kernel, layer, ...): waits for the recorded events of that entry and returns their
- *     summed duration in milliseconds and the number of bracketed launches. */
+ *     summed duration in milliseconds and the number of timed calls. */
 typedef enum {
   HGNN_K_MERGE = 0, HGNN_K_TRANSPOSE_W = 1, HGNN_K_SPMM_FWD = 2, HGNN_K_GEMM_FWD = 3, HGNN_K_ZERO_GRADS = 4,
   HGNN_K_RELU_BIAS_BWD = 5, HGNN_K_GEMM_DW = 6, HGNN_K_GEMM_DA = 7, HGNN_K_SPMM_BWD = 8, HGNN_K_XENT = 9

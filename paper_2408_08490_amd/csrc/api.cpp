@@ -143,32 +143,47 @@ static hgnn_status make_plan(hgnn_ctx *ctx, hgnn_graph *g, int32_t layer, const 
   return HGNN_OK;
 }
 
-// Records an event pair around the launches made while it is alive, if the probe selects them.
+// While alive, the launches made on this thread are timed if the probe selects (kernel, layer).
+static thread_local hgnn_ctx *tl_probe_ctx = nullptr;
+static thread_local int tl_probe_slot = -1;
+static thread_local bool tl_probe_first = false;
+
 struct Probe {
-  hgnn_ctx *c;
-  hipStream_t s;
-  hipEvent_t stop = nullptr;
-  Probe(hgnn_ctx *ctx, hipStream_t st, int kernel, int layer) : c(ctx), s(st) {
+  bool active = false;
+  Probe(hgnn_ctx *c, hipStream_t, int kernel, int layer) {
     int slot = -1;
     for (int i = 0; i < c->probe_n; ++i)
       if (c->probe_sel[i][0] == kernel && (c->probe_sel[i][1] < 0 || c->probe_sel[i][1] == layer)) slot = i;
     if (slot < 0) return;
-    if (c->probe_used == c->probe_events.size()) {
-      hipEvent_t a, b;
-      if (hipEventCreate(&a) != hipSuccess) return;
-      if (hipEventCreate(&b) != hipSuccess) { (void)hipEventDestroy(a); return; }
-      c->probe_events.emplace_back(a, b);
-    }
-    c->probe_slot.resize(c->probe_events.size());
-    c->probe_slot[c->probe_used] = slot;
-    auto &pr = c->probe_events[c->probe_used++];
-    (void)hipEventRecord(pr.first, s);
-    stop = pr.second;
+    tl_probe_ctx = c;
+    tl_probe_slot = slot;
+    tl_probe_first = true;
+    active = true;
   }
   ~Probe() {
-    if (stop) (void)hipEventRecord(stop, s);
+    if (active) tl_probe_ctx = nullptr;
   }
 };
+
+bool probe_take_events(hipEvent_t *start, hipEvent_t *stop) {
+  hgnn_ctx *c = tl_probe_ctx;
+  if (!c) return false;
+  if (c->probe_used == c->probe_events.size()) {
+    hipEvent_t a, b;
+    if (hipEventCreate(&a) != hipSuccess) return false;
+    if (hipEventCreate(&b) != hipSuccess) { (void)hipEventDestroy(a); return false; }
+    c->probe_events.emplace_back(a, b);
+  }
+  c->probe_slot.resize(c->probe_events.size());
+  c->probe_first.resize(c->probe_events.size());
+  c->probe_slot[c->probe_used] = tl_probe_slot;
+  c->probe_first[c->probe_used] = tl_probe_first ? 1 : 0;
+  tl_probe_first = false;
+  auto &pr = c->probe_events[c->probe_used++];
+  *start = pr.first;
+  *stop = pr.second;
+  return true;
+}
 
 static void fwd_tiles(const Plan &pl, SegTab &tl) {
   std::memset(&tl, 0, sizeof(tl));
@@ -748,7 +763,7 @@ hgnn_status hgnn_probe_read(hgnn_ctx *ctx, int32_t kernel, int32_t layer, double
     HGNN_HIP(hipEventSynchronize(ctx->probe_events[i].second));
     HGNN_HIP(hipEventElapsedTime(&ms, ctx->probe_events[i].first, ctx->probe_events[i].second));
     sum += ms;
-    ++n;
+    n += ctx->probe_first[i];
   }
   *total_ms = sum;
   *launches = n;

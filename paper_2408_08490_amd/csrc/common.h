@@ -1,6 +1,7 @@
 // Internal declarations shared by the host runtime and the kernel launchers.
 #pragma once
 #include <hip/hip_runtime.h>
+#include <hip/hip_ext.h>
 
 #include <atomic>
 #include <condition_variable>
@@ -32,6 +33,19 @@ void set_error(const char *fmt, ...);
   do {                                                                                  \
     hipError_t e_ = (expr);                                                             \
     if (e_ != hipSuccess) HGNN_FAIL(HGNN_EHIP, "%s: %s", #expr, hipGetErrorString(e_)); \
+  } while (0)
+
+// Every kernel launch of the library goes through HGNN_LAUNCH.  While a kernel probe is active on the calling
+// thread the launch carries its own start/stop events, whose timestamps are those of the dispatch itself (no
+// launch gap, no neighbouring work): `probe_take_events` hands out the pair.
+bool probe_take_events(hipEvent_t *start, hipEvent_t *stop);
+#define HGNN_LAUNCH(kernel, grid, block, shmem, stream, ...)                                          \
+  do {                                                                                                \
+    hipEvent_t pe0_, pe1_;                                                                            \
+    if (::hgnn::probe_take_events(&pe0_, &pe1_))                                                      \
+      hipExtLaunchKernelGGL(kernel, grid, block, shmem, stream, pe0_, pe1_, 0, __VA_ARGS__);          \
+    else                                                                                              \
+      hipLaunchKernelGGL(kernel, grid, block, shmem, stream, __VA_ARGS__);                            \
   } while (0)
 
 // ---------------------------------------------------------------------------------------------
@@ -164,6 +178,7 @@ struct hgnn_ctx {
   int probe_sel[4][2];  // selected (kernel, layer) pairs
   int probe_n = 0;
   std::vector<int> probe_slot;  // selection each recorded event pair belongs to
+  std::vector<uint8_t> probe_first;  // 1 for the first launch of a probed call (a call may launch several kernels)
   std::vector<std::pair<hipEvent_t, hipEvent_t>> probe_events;
   size_t probe_used = 0;
 };

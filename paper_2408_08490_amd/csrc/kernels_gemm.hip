@@ -442,10 +442,10 @@ hgnn_status launch_gemm_fwd(hipStream_t s, int dtype, const LayerDev &L, const T
   // operands of the forward are the library's own aligned buffers (aggregates, transposed weights) and
   // x_merged, whose row widths are multiples of 16 bytes: always the FAST form
   if (dtype == HGNN_BF16)
-    hipLaunchKernelGGL((gemm_fwd_kernel<bf16, true>), grid, dim3(kThreads), 0, s, tt, rt, pt, wt, tiles, live, H, relu,
+    HGNN_LAUNCH((gemm_fwd_kernel<bf16, true>), grid, dim3(kThreads), 0, s, tt, rt, pt, wt, tiles, live, H, relu,
                        (const bf16 *)x, (const bf16 *)z, (const bf16 *)zlo, (const bf16 *)wt_buf, (bf16 *)h, only_seg, acc32);
   else
-    hipLaunchKernelGGL((gemm_fwd_kernel<float, true>), grid, dim3(kThreads), 0, s, tt, rt, pt, wt, tiles, live, H, relu,
+    HGNN_LAUNCH((gemm_fwd_kernel<float, true>), grid, dim3(kThreads), 0, s, tt, rt, pt, wt, tiles, live, H, relu,
                        (const float *)x, (const float *)z, (const float *)nullptr, (const float *)wt_buf, (float *)h,
                        only_seg, acc32);
   HGNN_HIP(hipGetLastError());
@@ -507,11 +507,11 @@ hgnn_status launch_gemm_da(hipStream_t s, int dtype, const LayerDev &L, const Ty
   if (n == 0) return HGNN_OK;
   dim3 grid(round_up8(n)), blk(kThreads);
   if (dtype == HGNN_BF16) {
-    if (fast) hipLaunchKernelGGL((gemm_da_kernel<bf16, true>), grid, blk, 0, s, L, tt, rt, pt, tiles, ldg, (const bf16 *)gp, (bf16 *)dz);
-    else hipLaunchKernelGGL((gemm_da_kernel<bf16, false>), grid, blk, 0, s, L, tt, rt, pt, tiles, ldg, (const bf16 *)gp, (bf16 *)dz);
+    if (fast) HGNN_LAUNCH((gemm_da_kernel<bf16, true>), grid, blk, 0, s, L, tt, rt, pt, tiles, ldg, (const bf16 *)gp, (bf16 *)dz);
+    else HGNN_LAUNCH((gemm_da_kernel<bf16, false>), grid, blk, 0, s, L, tt, rt, pt, tiles, ldg, (const bf16 *)gp, (bf16 *)dz);
   } else {
-    if (fast) hipLaunchKernelGGL((gemm_da_kernel<float, true>), grid, blk, 0, s, L, tt, rt, pt, tiles, ldg, (const float *)gp, (float *)dz);
-    else hipLaunchKernelGGL((gemm_da_kernel<float, false>), grid, blk, 0, s, L, tt, rt, pt, tiles, ldg, (const float *)gp, (float *)dz);
+    if (fast) HGNN_LAUNCH((gemm_da_kernel<float, true>), grid, blk, 0, s, L, tt, rt, pt, tiles, ldg, (const float *)gp, (float *)dz);
+    else HGNN_LAUNCH((gemm_da_kernel<float, false>), grid, blk, 0, s, L, tt, rt, pt, tiles, ldg, (const float *)gp, (float *)dz);
   }
   HGNN_HIP(hipGetLastError());
   return HGNN_OK;
@@ -561,11 +561,11 @@ hgnn_status launch_gemm_dw(hipStream_t s, int dtype, const LayerDev &L, const Ty
   (void)L;
   dim3 grid(round_up8(n)), blk(kThreads);
   if (dtype == HGNN_BF16) {
-    if (fast) hipLaunchKernelGGL((gemm_dw_kernel<bf16, true>), grid, blk, 0, s, tt, rt, gt, tiles, split_rows, H, ldg, (const bf16 *)x, (const bf16 *)z, (const bf16 *)gp);
-    else hipLaunchKernelGGL((gemm_dw_kernel<bf16, false>), grid, blk, 0, s, tt, rt, gt, tiles, split_rows, H, ldg, (const bf16 *)x, (const bf16 *)z, (const bf16 *)gp);
+    if (fast) HGNN_LAUNCH((gemm_dw_kernel<bf16, true>), grid, blk, 0, s, tt, rt, gt, tiles, split_rows, H, ldg, (const bf16 *)x, (const bf16 *)z, (const bf16 *)gp);
+    else HGNN_LAUNCH((gemm_dw_kernel<bf16, false>), grid, blk, 0, s, tt, rt, gt, tiles, split_rows, H, ldg, (const bf16 *)x, (const bf16 *)z, (const bf16 *)gp);
   } else {
-    if (fast) hipLaunchKernelGGL((gemm_dw_kernel<float, true>), grid, blk, 0, s, tt, rt, gt, tiles, split_rows, H, ldg, (const float *)x, (const float *)z, (const float *)gp);
-    else hipLaunchKernelGGL((gemm_dw_kernel<float, false>), grid, blk, 0, s, tt, rt, gt, tiles, split_rows, H, ldg, (const float *)x, (const float *)z, (const float *)gp);
+    if (fast) HGNN_LAUNCH((gemm_dw_kernel<float, true>), grid, blk, 0, s, tt, rt, gt, tiles, split_rows, H, ldg, (const float *)x, (const float *)z, (const float *)gp);
+    else HGNN_LAUNCH((gemm_dw_kernel<float, false>), grid, blk, 0, s, tt, rt, gt, tiles, split_rows, H, ldg, (const float *)x, (const float *)z, (const float *)gp);
   }
   HGNN_HIP(hipGetLastError());
   return HGNN_OK;

@@ -61,7 +61,7 @@ hgnn_status launch_merge(hipStream_t s, int dtype, int T, const void *const *sto
   if (total == 0) return HGNN_OK;
   const int l2 = lanes_log2_for(maxd, es);
   const int rpb = 256 >> l2;
-  hipLaunchKernelGGL(merge_kernel, dim3((total + rpb - 1) / rpb), dim3(256), 0, s, mt, (char *)out, es, l2);
+  HGNN_LAUNCH(merge_kernel, dim3((total + rpb - 1) / rpb), dim3(256), 0, s, mt, (char *)out, es, l2);
   HGNN_HIP(hipGetLastError());
   return HGNN_OK;
 }
@@ -144,9 +144,9 @@ hgnn_status launch_spmm_fwd(hipStream_t s, int dtype, const LayerDev &L, const T
   const int rpb = 256 >> l2;
   dim3 grid((row_end - row_begin + rpb - 1) / rpb);
   if (dtype == HGNN_BF16)
-    hipLaunchKernelGGL(spmm_fwd_kernel<bf16>, grid, dim3(256), 0, s, L, tt, rt, (const bf16 *)x, (bf16 *)z, (bf16 *)zlo, row_begin, row_end, l2);
+    HGNN_LAUNCH(spmm_fwd_kernel<bf16>, grid, dim3(256), 0, s, L, tt, rt, (const bf16 *)x, (bf16 *)z, (bf16 *)zlo, row_begin, row_end, l2);
   else
-    hipLaunchKernelGGL(spmm_fwd_kernel<float>, grid, dim3(256), 0, s, L, tt, rt, (const float *)x, (float *)z, (float *)nullptr, row_begin, row_end, l2);
+    HGNN_LAUNCH(spmm_fwd_kernel<float>, grid, dim3(256), 0, s, L, tt, rt, (const float *)x, (float *)z, (float *)nullptr, row_begin, row_end, l2);
   HGNN_HIP(hipGetLastError());
   return HGNN_OK;
 }
@@ -298,10 +298,10 @@ hgnn_status launch_spmm_bwd(hipStream_t s, int dtype, const LayerDev &L, const T
   dim3 grid(row_blocks + chunk_blocks);
   if (grid.x > 0) {
   if (dtype == HGNN_BF16)
-    hipLaunchKernelGGL(spmm_bwd_kernel<bf16>, grid, dim3(256), 0, s, L, tt, rt, root_mask, want, (const bf16 *)dz, (bf16 *)dx,
+    HGNN_LAUNCH(spmm_bwd_kernel<bf16>, grid, dim3(256), 0, s, L, tt, rt, root_mask, want, (const bf16 *)dz, (bf16 *)dx,
                        partial, max_dim, row_blocks, l2, (int)uniform);
   else
-    hipLaunchKernelGGL(spmm_bwd_kernel<float>, grid, dim3(256), 0, s, L, tt, rt, root_mask, want, (const float *)dz, (float *)dx,
+    HGNN_LAUNCH(spmm_bwd_kernel<float>, grid, dim3(256), 0, s, L, tt, rt, root_mask, want, (const float *)dz, (float *)dx,
                        partial, max_dim, row_blocks, l2, (int)uniform);
   HGNN_HIP(hipGetLastError());
   }
@@ -311,11 +311,11 @@ hgnn_status launch_spmm_bwd(hipStream_t s, int dtype, const LayerDev &L, const T
       if (tt.in_dim[t] % 4) w4 = false;
     const dim3 g(L.n_long), b(256);
     if (dtype == HGNN_BF16) {
-      if (w4) hipLaunchKernelGGL((spmm_bwd_long_kernel<bf16, 4>), g, b, 0, s, L, tt, rt, root_mask, want, (const bf16 *)dz, (bf16 *)dx, partial, max_dim);
-      else hipLaunchKernelGGL((spmm_bwd_long_kernel<bf16, 1>), g, b, 0, s, L, tt, rt, root_mask, want, (const bf16 *)dz, (bf16 *)dx, partial, max_dim);
+      if (w4) HGNN_LAUNCH((spmm_bwd_long_kernel<bf16, 4>), g, b, 0, s, L, tt, rt, root_mask, want, (const bf16 *)dz, (bf16 *)dx, partial, max_dim);
+      else HGNN_LAUNCH((spmm_bwd_long_kernel<bf16, 1>), g, b, 0, s, L, tt, rt, root_mask, want, (const bf16 *)dz, (bf16 *)dx, partial, max_dim);
     } else {
-      if (w4) hipLaunchKernelGGL((spmm_bwd_long_kernel<float, 4>), g, b, 0, s, L, tt, rt, root_mask, want, (const float *)dz, (float *)dx, partial, max_dim);
-      else hipLaunchKernelGGL((spmm_bwd_long_kernel<float, 1>), g, b, 0, s, L, tt, rt, root_mask, want, (const float *)dz, (float *)dx, partial, max_dim);
+      if (w4) HGNN_LAUNCH((spmm_bwd_long_kernel<float, 4>), g, b, 0, s, L, tt, rt, root_mask, want, (const float *)dz, (float *)dx, partial, max_dim);
+      else HGNN_LAUNCH((spmm_bwd_long_kernel<float, 1>), g, b, 0, s, L, tt, rt, root_mask, want, (const float *)dz, (float *)dx, partial, max_dim);
     }
     HGNN_HIP(hipGetLastError());
   }
@@ -364,9 +364,9 @@ hgnn_status launch_transpose_weights(hipStream_t s, int dtype, const TypeTab &tt
                                      const PtrTab &pt, const WtTab &wt, int H, void *wt_buf) {
   dim3 grid(128, rt.num_rels + tt.num_types);
   if (dtype == HGNN_BF16)
-    hipLaunchKernelGGL(transpose_weights_kernel<bf16>, grid, dim3(256), 0, s, tt, rt, pt, wt, H, (bf16 *)wt_buf);
+    HGNN_LAUNCH(transpose_weights_kernel<bf16>, grid, dim3(256), 0, s, tt, rt, pt, wt, H, (bf16 *)wt_buf);
   else
-    hipLaunchKernelGGL(transpose_weights_kernel<float>, grid, dim3(256), 0, s, tt, rt, pt, wt, H, (float *)wt_buf);
+    HGNN_LAUNCH(transpose_weights_kernel<float>, grid, dim3(256), 0, s, tt, rt, pt, wt, H, (float *)wt_buf);
   HGNN_HIP(hipGetLastError());
   return HGNN_OK;
 }
@@ -390,9 +390,9 @@ hgnn_status launch_pad_weights(hipStream_t s, int dtype, const TypeTab &tt, cons
                                const WtTab &wo, int H, int Hp, void *out) {
   dim3 grid(32, rt.num_rels + tt.num_types);
   if (dtype == HGNN_BF16)
-    hipLaunchKernelGGL(pad_weights_kernel<bf16>, grid, dim3(256), 0, s, tt, rt, pt, wo, H, Hp, (bf16 *)out);
+    HGNN_LAUNCH(pad_weights_kernel<bf16>, grid, dim3(256), 0, s, tt, rt, pt, wo, H, Hp, (bf16 *)out);
   else
-    hipLaunchKernelGGL(pad_weights_kernel<float>, grid, dim3(256), 0, s, tt, rt, pt, wo, H, Hp, (float *)out);
+    HGNN_LAUNCH(pad_weights_kernel<float>, grid, dim3(256), 0, s, tt, rt, pt, wo, H, Hp, (float *)out);
   HGNN_HIP(hipGetLastError());
   return HGNN_OK;
 }
@@ -494,16 +494,16 @@ hgnn_status launch_relu_bias_bwd(hipStream_t s, int dtype, const TypeTab &tt, in
   if (blocks == 0) return HGNN_OK;
   if (fast) {
     if (dtype == HGNN_BF16)
-      hipLaunchKernelGGL(relu_bias_bwd_vec_kernel<bf16>, dim3(blocks), dim3(256), 0, s, tt, H, relu, (const bf16 *)grad_h,
+      HGNN_LAUNCH(relu_bias_bwd_vec_kernel<bf16>, dim3(blocks), dim3(256), 0, s, tt, H, relu, (const bf16 *)grad_h,
                          (const bf16 *)h, (bf16 *)gp, gt);
     else
-      hipLaunchKernelGGL(relu_bias_bwd_vec_kernel<float>, dim3(blocks), dim3(256), 0, s, tt, H, relu, (const float *)grad_h,
+      HGNN_LAUNCH(relu_bias_bwd_vec_kernel<float>, dim3(blocks), dim3(256), 0, s, tt, H, relu, (const float *)grad_h,
                          (const float *)h, (float *)gp, gt);
   } else if (dtype == HGNN_BF16) {
-    hipLaunchKernelGGL(relu_bias_bwd_kernel<bf16>, dim3(blocks), dim3(256), 0, s, tt, H, ldo, relu, write, (const bf16 *)grad_h,
+    HGNN_LAUNCH(relu_bias_bwd_kernel<bf16>, dim3(blocks), dim3(256), 0, s, tt, H, ldo, relu, write, (const bf16 *)grad_h,
                        (const bf16 *)h, (bf16 *)gp, gt);
   } else {
-    hipLaunchKernelGGL(relu_bias_bwd_kernel<float>, dim3(blocks), dim3(256), 0, s, tt, H, ldo, relu, write, (const float *)grad_h,
+    HGNN_LAUNCH(relu_bias_bwd_kernel<float>, dim3(blocks), dim3(256), 0, s, tt, H, ldo, relu, write, (const float *)grad_h,
                        (const float *)h, (float *)gp, gt);
   }
   HGNN_HIP(hipGetLastError());
@@ -531,7 +531,7 @@ __global__ void __launch_bounds__(256) zero_grads_kernel(TypeTab tt, RelTab rt, 
 }
 
 hgnn_status launch_zero_grads(hipStream_t s, const TypeTab &tt, const RelTab &rt, const GradPtrTab &gt, int H) {
-  hipLaunchKernelGGL(zero_grads_kernel, dim3(32, rt.num_rels + tt.num_types), dim3(256), 0, s, tt, rt, gt, H);
+  HGNN_LAUNCH(zero_grads_kernel, dim3(32, rt.num_rels + tt.num_types), dim3(256), 0, s, tt, rt, gt, H);
   HGNN_HIP(hipGetLastError());
   return HGNN_OK;
 }
@@ -546,7 +546,7 @@ hgnn_status launch_fill_zero(hipStream_t s, void *p, size_t bytes) {
   if (bytes == 0) return HGNN_OK;
   const size_t n16 = bytes / 16;
   const int blocks = (int)std::min<size_t>(2048, (n16 + 255) / 256 + 1);
-  hipLaunchKernelGGL(fill_zero_kernel, dim3(blocks), dim3(256), 0, s, (uint4 *)p, n16, (char *)p + n16 * 16, bytes - n16 * 16);
+  HGNN_LAUNCH(fill_zero_kernel, dim3(blocks), dim3(256), 0, s, (uint4 *)p, n16, (char *)p + n16 * 16, bytes - n16 * 16);
   HGNN_HIP(hipGetLastError());
   return HGNN_OK;
 }
@@ -584,10 +584,10 @@ hgnn_status launch_bias_act(hipStream_t s, int dtype, const TypeTab &tt, const P
   if (n_rows == 0) return HGNN_OK;
   const int blocks = (int)std::min<int64_t>(4096, (n_rows * H + 255) / 256);
   if (dtype == HGNN_BF16)
-    hipLaunchKernelGGL(bias_act_typed_kernel<bf16>, dim3(blocks), dim3(256), 0, s, (int64_t)tt.out_row_off[type], n_rows, H,
+    HGNN_LAUNCH(bias_act_typed_kernel<bf16>, dim3(blocks), dim3(256), 0, s, (int64_t)tt.out_row_off[type], n_rows, H,
                        relu, (const bf16 *)pt.bias[type], acc32, (bf16 *)h);
   else
-    hipLaunchKernelGGL(bias_act_typed_kernel<float>, dim3(blocks), dim3(256), 0, s, (int64_t)tt.out_row_off[type], n_rows, H,
+    HGNN_LAUNCH(bias_act_typed_kernel<float>, dim3(blocks), dim3(256), 0, s, (int64_t)tt.out_row_off[type], n_rows, H,
                        relu, (const float *)pt.bias[type], acc32, (float *)h);
   HGNN_HIP(hipGetLastError());
   return HGNN_OK;
@@ -632,9 +632,9 @@ hgnn_status launch_xent(hipStream_t s, int dtype, const void *logits, const int6
   if (rows == 0) return HGNN_OK;
   dim3 grid((unsigned)std::min<int64_t>(512, (rows + 3) / 4));
   if (dtype == HGNN_BF16)
-    hipLaunchKernelGGL(xent_kernel<bf16>, grid, dim3(256), 0, s, (const bf16 *)logits, labels, rows, classes, loss, (bf16 *)grad);
+    HGNN_LAUNCH(xent_kernel<bf16>, grid, dim3(256), 0, s, (const bf16 *)logits, labels, rows, classes, loss, (bf16 *)grad);
   else
-    hipLaunchKernelGGL(xent_kernel<float>, grid, dim3(256), 0, s, (const float *)logits, labels, rows, classes, loss, (float *)grad);
+    HGNN_LAUNCH(xent_kernel<float>, grid, dim3(256), 0, s, (const float *)logits, labels, rows, classes, loss, (float *)grad);
   HGNN_HIP(hipGetLastError());
   return HGNN_OK;
 }

@@ -96,7 +96,7 @@ template <typename T, int LPRL, int C>
 static void launch_fwd_uniform(hipStream_t s, const LayerDev &L, const void *x, void *z, void *zlo, int F, int row_begin, int row_end) {
   constexpr int RPB = 4 * (64 >> LPRL);
   dim3 grid((row_end - row_begin + RPB - 1) / RPB);
-  hipLaunchKernelGGL((spmm_fwd_uniform_kernel<T, LPRL, C>), grid, dim3(256), 0, s, L.rowptr, L.colidx, (const T *)x, (T *)z,
+  HGNN_LAUNCH((spmm_fwd_uniform_kernel<T, LPRL, C>), grid, dim3(256), 0, s, L.rowptr, L.colidx, (const T *)x, (T *)z,
                      (T *)zlo, F, row_begin, row_end);
 }
 
@@ -214,7 +214,7 @@ static void launch_bwd_uniform(hipStream_t s, const LayerDev &L, RowRanges &rr, 
   }
   rr.total_waves = w;
   if (w == 0) return;
-  hipLaunchKernelGGL((spmm_bwd_uniform_kernel<T, LPRL, C>), dim3((w + 3) / 4), dim3(256), 0, s, L.cptr, L.crow, rr, (const T *)dz,
+  HGNN_LAUNCH((spmm_bwd_uniform_kernel<T, LPRL, C>), dim3((w + 3) / 4), dim3(256), 0, s, L.cptr, L.crow, rr, (const T *)dz,
                      (T *)dx, F);
 }
 
