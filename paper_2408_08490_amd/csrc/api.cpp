@@ -662,35 +662,38 @@ hgnn_status hgnn_layer_bwd(hgnn_ctx *ctx, void *stream, hgnn_graph *g, int32_t l
   }
   const bool fast = (ldg % vec) == 0;
   if (any_dw && pl.total_dst > 0) {
-    // split the reduction over destination rows so that the launch has about two blocks per CU; every extra
-    // split costs a tile's worth of atomic adds
-    SegTab tl;
+    // Work list: per destination type its live segments (relations with edges, then the root) and the 128-row
+    // blocks of their weight gradients.  The reduction is split over destination rows so that the launch has
+    // about two blocks per CU, but not into slices under 1024 rows: every extra split costs a tile's worth of
+    // atomic adds, which outweigh the shorter reduction below that.
+    DwTab tl;
     std::memset(&tl, 0, sizeof(tl));
-    tl.num_segs = R + T;
-    auto live_seg = [&](int sgi, int &d, int &F) {
-      const bool is_rel = sgi < R;
-      d = is_rel ? ctx->rel_dst[sgi] : sgi - R;
-      F = pl.tt.in_dim[is_rel ? ctx->rel_src[sgi] : d];
-      return (is_rel ? (reo[sgi + 1] > reo[sgi] && gt.dw_rel[sgi]) : gt.dw_root[d] != nullptr) && pl.tt.n_dst[d] > 0;
-    };
+    int ne = 0;
+    for (int d = 0; d < T; ++d) {
+      tl.first[d] = (uint16_t)ne;
+      int u = 0;
+      if (pl.tt.n_dst[d] > 0)
+        for (int sgi = 0; sgi < R + T; ++sgi) {
+          const bool is_rel = sgi < R;
+          if (is_rel ? (ctx->rel_dst[sgi] != d || reo[sgi + 1] == reo[sgi] || !gt.dw_rel[sgi]) : (sgi - R != d || !gt.dw_root[d])) continue;
+          tl.seg[ne] = (uint8_t)sgi;
+          tl.u_off[ne] = (uint16_t)u;
+          u += (pl.tt.in_dim[is_rel ? ctx->rel_src[sgi] : d] + 127) / 128;
+          ++ne;
+        }
+      tl.u_total[d] = (uint16_t)u;
+    }
+    tl.first[T] = (uint16_t)ne;
+    const int tiles_h = (pl.H + 127) / 128;
     int split_rows = 4096;
     for (;;) {
       int64_t tiles = 0;
-      for (int sgi = 0; sgi < R + T; ++sgi) {
-        int d, F;
-        if (live_seg(sgi, d, F))
-          tiles += (int64_t)((F + 127) / 128) * ((pl.H + 127) / 128) * ((pl.tt.n_dst[d] + split_rows - 1) / split_rows);
-      }
-      static const int64_t want = getenv("HGNN_DW_TILES") ? atoi(getenv("HGNN_DW_TILES")) : 320;
-      if (tiles >= want || split_rows <= 128) break;
+      for (int d = 0; d < T; ++d) tiles += (int64_t)tl.u_total[d] * tiles_h * ((pl.tt.n_dst[d] + split_rows - 1) / split_rows);
+      if (tiles >= 320 || split_rows <= 1024) break;
       split_rows /= 2;
     }
-    for (int sgi = 0; sgi < R + T; ++sgi) {
-      int d, F, cnt = 0;
-      if (live_seg(sgi, d, F))
-        cnt = ((F + 127) / 128) * ((pl.H + 127) / 128) * ((pl.tt.n_dst[d] + split_rows - 1) / split_rows);
-      tl.tile_off[sgi + 1] = tl.tile_off[sgi] + cnt;
-    }
+    for (int d = 0; d < T; ++d)
+      tl.tile_off[d + 1] = tl.tile_off[d] + tl.u_total[d] * tiles_h * ((pl.tt.n_dst[d] + split_rows - 1) / split_rows);
     Probe pb(ctx, s, HGNN_K_GEMM_DW, layer);
     if ((st = launch_gemm_dw(s, ctx->dtype, pl.dev, pl.tt, pl.rt, gt, tl, split_rows, pl.H, ldg, fast, x_merged, saved, gp)) != HGNN_OK) return st;
   }

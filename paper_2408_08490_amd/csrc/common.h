@@ -80,6 +80,16 @@ struct SegTab {
   int32_t tile_off[kMaxSeg + 1];
   int32_t num_segs;
 };
+// Work list of the weight-gradient GEMM: tiles grouped by destination type, inside a type by slice of
+// destination rows, so that the tiles that read the same rows of G' (every segment ending in the type, every
+// column block) are neighbours and meet in one L2.
+struct DwTab {
+  int32_t tile_off[kMaxT + 1];   // tiles before destination type d
+  uint16_t first[kMaxT + 1];     // entries [first[d], first[d+1]) of seg / u_off belong to type d
+  uint16_t u_total[kMaxT];       // 128-row blocks of dW over all segments of type d
+  uint16_t u_off[kMaxSeg];       // first block of entry i inside its type
+  uint8_t seg[kMaxSeg];          // segment of entry i (relation r -> r, root of type t -> R + t)
+};
 struct WtTab {                      // where each transposed weight lives in the scratch area
   uint32_t rel4[kMaxR];
   uint32_t root4[kMaxT];
@@ -214,7 +224,7 @@ hgnn_status launch_bias_act(hipStream_t s, int dtype, const TypeTab &tt, const P
 hgnn_status launch_gemm_da(hipStream_t s, int dtype, const LayerDev &L, const TypeTab &tt, const RelTab &rt,
                            const PtrTab &pt, const SegTab &tiles, int ldg, bool fast, const void *gp, void *dz);
 hgnn_status launch_gemm_dw(hipStream_t s, int dtype, const LayerDev &L, const TypeTab &tt, const RelTab &rt,
-                           const GradPtrTab &gt, const SegTab &tiles, int split_rows, int H, int ldg, bool fast,
+                           const GradPtrTab &gt, const DwTab &tiles, int split_rows, int H, int ldg, bool fast,
                            const void *x, const void *z, const void *gp);
 // gp (leading dimension ldo >= H, zero beyond H) = grad_h * [h > 0] (or a plain copy without ReLU); dbias = column sums
 hgnn_status launch_relu_bias_bwd(hipStream_t s, int dtype, const TypeTab &tt, int H, int ldo, int relu,

@@ -520,25 +520,30 @@ hgnn_status launch_gemm_da(hipStream_t s, int dtype, const LayerDev &L, const Ty
 // ------------------------------------------------------------------------------------------
 // dW_s += A_s^T G' over the destination-row slice [k_begin, k_end) of this block.
 template <typename T, bool FAST>
-__global__ void __launch_bounds__(kThreads, 2) gemm_dw_kernel(TypeTab tt, RelTab rt, GradPtrTab gt, SegTab tiles, int split_rows, int H,
+__global__ void __launch_bounds__(kThreads, 2) gemm_dw_kernel(TypeTab tt, RelTab rt, GradPtrTab gt, DwTab tiles, int split_rows, int H,
                                                            int ldg, const T *__restrict__ x, const T *__restrict__ z,
                                                            const T *__restrict__ gp) {
   __shared__ GemmLds<T> sm;
   const int tile = xcd_tile(blockIdx.x, gridDim.x);
-  const int R = rt.num_rels;
-  if (tile >= tiles.tile_off[tiles.num_segs]) return;
-  const int seg = find_seg(tiles, tile);
+  const int R = rt.num_rels, T_ = tt.num_types;
+  if (tile >= tiles.tile_off[T_]) return;
+  int d = 0;
+  while (tile >= tiles.tile_off[d + 1]) ++d;
+  // inside the type: row slice, then block of dW rows over the type's segments, then column block
+  const int tiles_h = (H + BN - 1) / BN;
+  int local = tile - tiles.tile_off[d];
+  const int th = local % tiles_h;
+  local /= tiles_h;
+  const int u = local % tiles.u_total[d];
+  const int sp = local / tiles.u_total[d];
+  int e = tiles.first[d];
+  while (e + 1 < tiles.first[d + 1] && u >= tiles.u_off[e + 1]) ++e;
+  const int seg = tiles.seg[e];
+  const int tf = u - tiles.u_off[e];
   const bool is_rel = seg < R;
-  const int d = is_rel ? rt.dst[seg] : seg - R;
   const int F = tt.in_dim[is_rel ? rt.src[seg] : d];
   float *dW = is_rel ? gt.dw_rel[seg] : gt.dw_root[d];
   const int M = tt.n_dst[d];
-  const int tiles_f = (F + BM - 1) / BM, tiles_h = (H + BN - 1) / BN;
-  int local = tile - tiles.tile_off[seg];
-  const int th = local % tiles_h;
-  local /= tiles_h;
-  const int tf = local % tiles_f;
-  const int sp = local / tiles_f;
   const int f0 = tf * BM, h0 = th * BN;
   const int k_begin = sp * split_rows, k_end = min(M, k_begin + split_rows);
   f32x16 acc[2][2];
@@ -554,9 +559,9 @@ __global__ void __launch_bounds__(kThreads, 2) gemm_dw_kernel(TypeTab tt, RelTab
 }
 
 hgnn_status launch_gemm_dw(hipStream_t s, int dtype, const LayerDev &L, const TypeTab &tt, const RelTab &rt,
-                           const GradPtrTab &gt, const SegTab &tiles, int split_rows, int H, int ldg, bool fast,
+                           const GradPtrTab &gt, const DwTab &tiles, int split_rows, int H, int ldg, bool fast,
                            const void *x, const void *z, const void *gp) {
-  const int n = tiles.tile_off[tiles.num_segs];
+  const int n = tiles.tile_off[tt.num_types];
   if (n == 0) return HGNN_OK;
   (void)L;
   dim3 grid(round_up8(n)), blk(kThreads);
