@@ -28,9 +28,10 @@ project/aggregate commutation, finite-difference gradients, numpy.lexsort for
 the index outputs, closed forms for the cross-entropy.
 
 Parity unpinned by the paper: the attention variant's definition (functions
-`rgat_*`): the paper cites R-GAT without equations, so those functions are
-pinned only by special cases that reduce to the mean layer, by softmax
-invariants and by finite differences.
+`rgat_*`): the paper cites R-GAT without equations, so those functions follow
+the form written out in their docstrings and are pinned by special cases that
+reduce to the mean layer, by a dense masked-softmax brute force, by softmax
+invariants and by finite differences - not by anything the paper prints.
 """
 from __future__ import annotations
 
@@ -256,6 +257,148 @@ def rgcn_layer_forward_merged(flat, feat_dim, csr, rel_src, rel_dst, n_dst, w_re
 # --------------------------------------------------------------------------- #
 # Loss used by the two academic-graph configurations
 # --------------------------------------------------------------------------- #
+# --------------------------------------------------------------------------- #
+# Attention variant: per-relation edge attention + semantic attention fusion
+# (the paper evaluates R-GAT, Section 5.1, without printing its equations)
+# --------------------------------------------------------------------------- #
+LEAKY_SLOPE = 0.2
+SEM_DIM = 128
+
+
+def rgat_layer_forward(x, rel_edges, rel_src, rel_dst, n_dst, w_type, a_src, a_dst, w_sem, b_sem, q_sem,
+                       bias, relu, heads):
+    """Attention layer, the four stages in order.
+      projection   z_t = x_t W_t                       per vertex type, H = heads * D columns
+      aggregation  for relation r (s -> d), destination v, head k, neighbours u in N_r(v):
+                     e_u = LeakyReLU_0.2( a_src[r][k] . z_s[u]^k  +  a_dst[r][k] . z_d[v]^k )
+                     alpha = softmax_u(e)             (row maximum subtracted first)
+                     m_v^r = concat_k sum_u alpha_u z_s[u]^k ;   empty neighbourhood -> 0
+      fusion       per destination type d, over R_d = {r : dst(r) = d}:
+                     w_r = (1/M_d) sum_v q . tanh(m_v^r W_s + b_s)    (all M_d rows, empty ones with m = 0)
+                     beta = softmax_{r in R_d}(w)
+                     pre_v = sum_r beta_r m_v^r + b_d ;  h = ReLU(pre) if relu
+    No root term.  x: per type [N_t, F_t]; w_type[t]: [F_t, H]; a_src[r], a_dst[r]: [heads, D];
+    w_sem [H, 128], b_sem [128], q_sem [128]; bias[t]: [H] or None.  Returns (h per type, cache)."""
+    T, R = len(x), len(rel_src)
+    x = [np.asarray(a, dtype=F64) for a in x]
+    H = int(np.asarray(w_type[0]).shape[1])
+    K = int(heads)
+    D = H // K
+    assert K * D == H
+    z = [x[t] @ np.asarray(w_type[t], dtype=F64) for t in range(T)]          # feature projection
+    ws, bs, q = np.asarray(w_sem, dtype=F64), np.asarray(b_sem, dtype=F64), np.asarray(q_sem, dtype=F64)
+    nbrs, alphas, scores, m = [], [], [], []
+    for r in range(R):                                                       # neighbour aggregation
+        s, d = rel_src[r], rel_dst[r]
+        M = int(n_dst[d])
+        nb = _neighbour_lists(rel_edges[r][0], rel_edges[r][1], M)
+        As, Ad = np.asarray(a_src[r], dtype=F64), np.asarray(a_dst[r], dtype=F64)
+        mr = np.zeros((M, H), dtype=F64)
+        al, sc = [None] * M, [None] * M
+        for v in range(M):
+            if not nb[v]:
+                continue
+            zu = z[s][nb[v]].reshape(len(nb[v]), K, D)
+            zv = z[d][v].reshape(K, D)
+            sv = (zu * As[None]).sum(axis=2) + (zv * Ad).sum(axis=1)[None, :]    # [n, K] before the LeakyReLU
+            e = np.where(sv > 0, sv, LEAKY_SLOPE * sv)
+            e = e - e.max(axis=0, keepdims=True)
+            a = np.exp(e)
+            a /= a.sum(axis=0, keepdims=True)
+            mr[v] = (a[:, :, None] * zu).sum(axis=0).reshape(H)
+            al[v], sc[v] = a, sv
+        nbrs.append(nb); alphas.append(al); scores.append(sc); m.append(mr)
+    pre, beta, tanhs = [], [None] * R, [None] * R
+    for d in range(T):                                                       # semantic fusion
+        M = int(n_dst[d])
+        p = np.zeros((M, H), dtype=F64)
+        Rd = [r for r in range(R) if rel_dst[r] == d]
+        if M > 0 and Rd:
+            w = np.zeros(len(Rd), dtype=F64)
+            for i, r in enumerate(Rd):
+                tanhs[r] = np.tanh(m[r] @ ws + bs[None, :])
+                w[i] = (tanhs[r] @ q).sum() / M
+            ew = np.exp(w - w.max())
+            b = ew / ew.sum()
+            for i, r in enumerate(Rd):
+                beta[r] = float(b[i])
+                p += b[i] * m[r]
+        if M > 0 and bias[d] is not None:
+            p += np.asarray(bias[d], dtype=F64)[None, :]
+        pre.append(p)
+    h = [np.maximum(p, 0.0) if relu else p.copy() for p in pre]
+    cache = dict(x=x, z=z, nbrs=nbrs, alphas=alphas, scores=scores, m=m, beta=beta, tanhs=tanhs, pre=pre,
+                 rel_src=rel_src, rel_dst=rel_dst, n_dst=list(n_dst), w_type=w_type, a_src=a_src, a_dst=a_dst,
+                 w_sem=ws, b_sem=bs, q_sem=q, bias=bias, relu=relu, heads=K)
+    return h, cache
+
+
+def rgat_layer_backward(cache, grad_h, relu_mask=None):
+    """Reverse of `rgat_layer_forward`, step by step.  Returns a dict with dx (per type), dw_type, da_src,
+    da_dst, dw_sem, db_sem, dq_sem, dbias (None where the parameter is None)."""
+    x, z, nbrs, alphas, scores, m = (cache[k] for k in ("x", "z", "nbrs", "alphas", "scores", "m"))
+    beta, tanhs, pre = cache["beta"], cache["tanhs"], cache["pre"]
+    rel_src, rel_dst, n_dst = cache["rel_src"], cache["rel_dst"], cache["n_dst"]
+    ws, bs, q, K = cache["w_sem"], cache["b_sem"], cache["q_sem"], cache["heads"]
+    T, R = len(x), len(rel_src)
+    H = z[0].shape[1]
+    D = H // K
+    gp = []
+    for t in range(T):
+        g = np.asarray(grad_h[t], dtype=F64).reshape(pre[t].shape)
+        if not cache["relu"]:
+            gp.append(g.copy())
+        elif relu_mask is not None:
+            gp.append(g * np.asarray(relu_mask[t], dtype=bool).reshape(pre[t].shape))
+        else:
+            gp.append(g * (pre[t] > 0))
+    dbias = [None if cache["bias"][t] is None else gp[t].sum(axis=0) for t in range(T)]
+    dws, dbs, dq = np.zeros_like(ws), np.zeros_like(bs), np.zeros_like(q)
+    dm = [np.zeros_like(a) for a in m]
+    for d in range(T):                                                       # fusion, reversed
+        M = int(n_dst[d])
+        Rd = [r for r in range(R) if rel_dst[r] == d]
+        if M == 0 or not Rd:
+            continue
+        dbeta = np.array([(gp[d] * m[r]).sum() for r in Rd])
+        b = np.array([beta[r] for r in Rd])
+        dw = b * (dbeta - (b * dbeta).sum())                                 # softmax over relations
+        for i, r in enumerate(Rd):
+            dm[r] += b[i] * gp[d]
+            t = tanhs[r]
+            dq += dw[i] / M * t.sum(axis=0)
+            du = (dw[i] / M) * q[None, :] * (1.0 - t * t)
+            dws += m[r].T @ du
+            dbs += du.sum(axis=0)
+            dm[r] += du @ ws.T
+    dz = [np.zeros_like(a) for a in z]
+    da_src, da_dst = [], []
+    for r in range(R):                                                       # aggregation, reversed
+        s, d = rel_src[r], rel_dst[r]
+        As, Ad = np.asarray(cache["a_src"][r], dtype=F64), np.asarray(cache["a_dst"][r], dtype=F64)
+        das, dad = np.zeros_like(As), np.zeros_like(Ad)
+        for v in range(int(n_dst[d])):
+            nb = nbrs[r][v]
+            if not nb:
+                continue
+            a, sv = alphas[r][v], scores[r][v]
+            zu = z[s][nb].reshape(len(nb), K, D)
+            zv = z[d][v].reshape(K, D)
+            g = dm[r][v].reshape(K, D)
+            dalpha = (zu * g[None]).sum(axis=2)                              # [n, K]
+            np.add.at(dz[s], nb, (a[:, :, None] * g[None]).reshape(len(nb), H))
+            de = a * (dalpha - (a * dalpha).sum(axis=0, keepdims=True))      # softmax over the neighbours
+            ds = de * np.where(sv > 0, 1.0, LEAKY_SLOPE)                     # LeakyReLU
+            das += (ds[:, :, None] * zu).sum(axis=0)
+            dad += ds.sum(axis=0)[:, None] * zv
+            np.add.at(dz[s], nb, (ds[:, :, None] * As[None]).reshape(len(nb), H))
+            dz[d][v] += (ds.sum(axis=0)[:, None] * Ad).reshape(H)
+        da_src.append(das); da_dst.append(dad)
+    dw_type = [x[t].T @ dz[t] for t in range(T)]                             # projection, reversed
+    dx = [dz[t] @ np.asarray(cache["w_type"][t], dtype=F64).T for t in range(T)]
+    return dict(dx=dx, dw_type=dw_type, da_src=da_src, da_dst=da_dst, dw_sem=dws, db_sem=dbs, dq_sem=dq, dbias=dbias)
+
+
 def softmax_xent(logits, labels):
     """Mean softmax cross-entropy over the rows and its gradient w.r.t. the logits."""
     z = np.asarray(logits, dtype=F64)
@@ -276,8 +419,13 @@ def rgcn_model_forward(x0, blocks_sel, rel_src, rel_dst, blocks_n_dst, layers):
     """Layers stacked: returns per-layer outputs `h` and the per-layer caches."""
     xs, caches, hs = [x0], [], []
     for l, lw in enumerate(layers):
-        h, c = rgcn_layer_forward(xs[-1], blocks_sel[l], rel_src, rel_dst, blocks_n_dst[l],
-                                  lw["w_rel"], lw["w_root"], lw["bias"], lw["relu"])
+        if "w_type" in lw:      # attention variant
+            h, c = rgat_layer_forward(xs[-1], blocks_sel[l], rel_src, rel_dst, blocks_n_dst[l], lw["w_type"],
+                                      lw["a_src"], lw["a_dst"], lw["w_sem"], lw["b_sem"], lw["q_sem"], lw["bias"],
+                                      lw["relu"], lw["heads"])
+        else:
+            h, c = rgcn_layer_forward(xs[-1], blocks_sel[l], rel_src, rel_dst, blocks_n_dst[l],
+                                      lw["w_rel"], lw["w_root"], lw["bias"], lw["relu"])
         caches.append(c); hs.append(h); xs.append(h)
     return dict(h=hs, caches=caches)
 
@@ -286,7 +434,8 @@ def rgcn_model_forward_backward(x0, blocks_sel, rel_src, rel_dst, blocks_n_dst, 
                                 labels=None, grad_out=None, target_type=0, forward=None, relu_masks=None,
                                 num_types=None):
     """x0: per type first-layer input; blocks_sel[l]: per-relation selected edges of
-    layer l; layers[l]: dict(w_rel, w_root, bias, relu).  loss: "xent" (mean softmax
+    layer l; layers[l]: dict(w_rel, w_root, bias, relu) for the mean layer or dict(w_type, a_src, a_dst,
+    w_sem, b_sem, q_sem, bias, relu, heads) for the attention layer.  loss: "xent" (mean softmax
     cross-entropy of the target type's last-layer rows) or "dot" (sum of grad_out*h).
     `forward` may carry the result of `rgcn_model_forward` (then it is not recomputed);
     `relu_masks[l]` is passed to layer l's backward.
@@ -303,7 +452,12 @@ def rgcn_model_forward_backward(x0, blocks_sel, rel_src, rel_dst, blocks_n_dst, 
         val = sum(float((g[t] * hs[-1][t]).sum()) for t in range(T))
     grads = [None] * len(layers)
     for l in reversed(range(len(layers))):
-        dx, dw_rel, dw_root, dbias = rgcn_layer_backward(caches[l], g, None if relu_masks is None else relu_masks[l])
-        grads[l] = dict(dw_rel=dw_rel, dw_root=dw_root, dbias=dbias, dx=dx)
+        mask = None if relu_masks is None else relu_masks[l]
+        if "w_type" in layers[l]:
+            grads[l] = rgat_layer_backward(caches[l], g, mask)
+            dx = grads[l]["dx"]
+        else:
+            dx, dw_rel, dw_root, dbias = rgcn_layer_backward(caches[l], g, mask)
+            grads[l] = dict(dw_rel=dw_rel, dw_root=dw_root, dbias=dbias, dx=dx)
         g = dx
     return dict(h=hs, loss=val, grads=grads, dx0=g, caches=caches)
