@@ -161,6 +161,13 @@ typedef struct {
   const void *const *bias;     /* [T] b_t [H] or NULL entry; the array itself may be NULL      */
   const int32_t *input_grad;   /* host [T] or NULL (= all 1): 0 = hgnn_layer_bwd leaves the grad_x_merged rows
                                   of type t unwritten and skips their work (fixed, non-learnable input features) */
+  /* attention variant (schema agg = HGNN_AGG_ATTN, fuse = HGNN_FUSE_SEMATTN); unused otherwise */
+  const void *const *w_type;   /* [T] W_t [in_dim[t] x H]: per-type projection                              */
+  const void *const *a_src;    /* [R] attention vector of the source side      [heads x H/heads]            */
+  const void *const *a_dst;    /* [R] attention vector of the destination side [heads x H/heads]            */
+  const void *w_sem;           /* semantic attention: W_s [H x 128]                                          */
+  const void *b_sem;           /*                     b_s [128]                                              */
+  const void *q_sem;           /*                     q   [128]                                              */
 } hgnn_layer_params;
 
 /* fp32 gradient buffers mirroring hgnn_layer_params (device, caller-owned, OVERWRITTEN).
@@ -169,6 +176,11 @@ typedef struct {
   float *const *dw_rel;  /* [R] */
   float *const *dw_root; /* [T] */
   float *const *dbias;   /* [T] */
+  /* attention variant */
+  float *const *dw_type; /* [T] */
+  float *const *da_src;  /* [R] */
+  float *const *da_dst;  /* [R] */
+  float *dw_sem, *db_sem, *dq_sem;
 } hgnn_layer_grads;
 
 /* Bytes of the two device work areas of one layer on this graph:
@@ -193,6 +205,17 @@ hgnn_status hgnn_layer_workspace_bytes(hgnn_ctx *ctx, hgnn_graph *g, int32_t lay
 hgnn_status hgnn_layer_fwd(hgnn_ctx *ctx, void *stream, hgnn_graph *g, int32_t layer,
                            const hgnn_layer_params *p, const void *x_merged, void *h_out,
                            void *saved, size_t saved_bytes, void *scratch, size_t scratch_bytes);
+
+/* Attention variant (the paper evaluates R-GAT, Section 5.1; semantic fusion, Section 2.2): with a schema
+ * created with agg = HGNN_AGG_ATTN and fuse = HGNN_FUSE_SEMATTN, hgnn_layer_fwd / hgnn_layer_bwd evaluate
+ *   z_t = x_t W_t                                                     (H = heads * D columns)
+ *   e   = LeakyReLU_0.2( a_src[r][k] . z_u^k + a_dst[r][k] . z_v^k )  per relation r, head k, edge u -> v
+ *   m_v^r = concat_k sum_u softmax_u(e) z_u^k                         (empty neighbourhood: 0)
+ *   w_r = mean_v q . tanh(m_v^r W_s + b_s),  beta = softmax over the relations ending in type(v)
+ *   h_v = act( sum_r beta_r m_v^r + b_type(v) )
+ * and its gradients.  Requirements: D a multiple of 8 (bf16) / 4 (fp32) scalars and a power of two times
+ * that; every in_dim and H a multiple of 16 bytes; weight pointers 16-byte aligned; the graph built with
+ * transpose entries for every type.  hgnn_layer_fwd_naive is not available for this variant. */
 
 /* Backward of the same layer.  grad_h: device [sum_t n_dst[t] x H] (dtype), h_out: the forward's
  * output (needed for the ReLU mask).  Outputs: grad_x_merged (device, layout of x_merged, dtype;

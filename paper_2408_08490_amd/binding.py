@@ -50,12 +50,16 @@ class CsrView(C.Structure):
 class LayerParams(C.Structure):
     _fields_ = [("in_dim", C.POINTER(C.c_int32)), ("out_dim", C.c_int32), ("relu", C.c_int32),
                 ("w_rel", C.POINTER(C.c_void_p)), ("w_root", C.POINTER(C.c_void_p)),
-                ("bias", C.POINTER(C.c_void_p)), ("input_grad", C.POINTER(C.c_int32))]
+                ("bias", C.POINTER(C.c_void_p)), ("input_grad", C.POINTER(C.c_int32)),
+                ("w_type", C.POINTER(C.c_void_p)), ("a_src", C.POINTER(C.c_void_p)), ("a_dst", C.POINTER(C.c_void_p)),
+                ("w_sem", C.c_void_p), ("b_sem", C.c_void_p), ("q_sem", C.c_void_p)]
 
 
 class LayerGrads(C.Structure):
     _fields_ = [("dw_rel", C.POINTER(C.c_void_p)), ("dw_root", C.POINTER(C.c_void_p)),
-                ("dbias", C.POINTER(C.c_void_p))]
+                ("dbias", C.POINTER(C.c_void_p)),
+                ("dw_type", C.POINTER(C.c_void_p)), ("da_src", C.POINTER(C.c_void_p)), ("da_dst", C.POINTER(C.c_void_p)),
+                ("dw_sem", C.c_void_p), ("db_sem", C.c_void_p), ("dq_sem", C.c_void_p)]
 
 
 def _load():
@@ -155,34 +159,56 @@ class Layer:
     """Marshalled hgnn_layer_params (+ optional gradient table) for one layer; holds the tensors."""
 
     def __init__(self, ctx, in_dim, out_dim, relu, w_rel, w_root, bias, dw_rel=None, dw_root=None, dbias=None,
-                 input_grad=None):
+                 input_grad=None, attn=None, dattn=None):
+        """attn / dattn: dicts of tensors (w_type [T], a_src [R], a_dst [R], w_sem, b_sem, q_sem) and of their
+        fp32 gradient buffers (dw_type, da_src, da_dst, dw_sem, db_sem, dq_sem) for the attention variant."""
         T, R = ctx.num_types, ctx.num_rels
-        self.tensors = (w_rel, w_root, bias, dw_rel, dw_root, dbias)
+        self.tensors = (w_rel, w_root, bias, dw_rel, dw_root, dbias, attn, dattn)
+        nullv, nulli = C.POINTER(C.c_void_p)(), C.POINTER(C.c_int32)()
+
+        def arr(ts, n):
+            return (C.c_void_p * n)(*[_ptr(w) for w in ts]) if ts is not None else None
+
         self._in_dim = (C.c_int32 * T)(*in_dim)
-        self._w_rel = (C.c_void_p * R)(*[_ptr(w) for w in w_rel])
-        self._w_root = (C.c_void_p * T)(*[_ptr(w) for w in w_root])
-        self._bias = (C.c_void_p * T)(*[_ptr(b) for b in bias]) if bias is not None else None
+        self._w_rel, self._w_root, self._bias = arr(w_rel, R), arr(w_root, T), arr(bias, T)
         self._input_grad = (C.c_int32 * T)(*[int(x) for x in input_grad]) if input_grad is not None else None
-        self.params = LayerParams(self._in_dim, out_dim, int(relu), self._w_rel, self._w_root,
-                                  self._bias if self._bias is not None else C.POINTER(C.c_void_p)(),
-                                  self._input_grad if self._input_grad is not None else C.POINTER(C.c_int32)())
+        a = attn or {}
+        self._w_type, self._a_src, self._a_dst = arr(a.get("w_type"), T), arr(a.get("a_src"), R), arr(a.get("a_dst"), R)
+        self.params = LayerParams(self._in_dim, out_dim, int(relu),
+                                  self._w_rel if self._w_rel is not None else nullv,
+                                  self._w_root if self._w_root is not None else nullv,
+                                  self._bias if self._bias is not None else nullv,
+                                  self._input_grad if self._input_grad is not None else nulli,
+                                  self._w_type if self._w_type is not None else nullv,
+                                  self._a_src if self._a_src is not None else nullv,
+                                  self._a_dst if self._a_dst is not None else nullv,
+                                  _ptr(a.get("w_sem")), _ptr(a.get("b_sem")), _ptr(a.get("q_sem")))
         self.in_dim, self.out_dim, self.relu = list(in_dim), out_dim, bool(relu)
         self.grads = None
-        if dw_rel is not None:
-            self._dw_rel = (C.c_void_p * R)(*[_ptr(w) for w in dw_rel])
-            self._dw_root = (C.c_void_p * T)(*[_ptr(w) for w in dw_root])
-            self._dbias = (C.c_void_p * T)(*[_ptr(b) for b in dbias]) if dbias is not None else None
-            self.grads = LayerGrads(self._dw_rel, self._dw_root,
-                                    self._dbias if self._dbias is not None else C.POINTER(C.c_void_p)())
+        if dw_rel is not None or dattn is not None:
+            d = dattn or {}
+            self._dw_rel, self._dw_root, self._dbias = arr(dw_rel, R), arr(dw_root, T), arr(dbias, T)
+            self._dw_type, self._da_src, self._da_dst = arr(d.get("dw_type"), T), arr(d.get("da_src"), R), arr(d.get("da_dst"), R)
+            self.grads = LayerGrads(self._dw_rel if self._dw_rel is not None else nullv,
+                                    self._dw_root if self._dw_root is not None else nullv,
+                                    self._dbias if self._dbias is not None else nullv,
+                                    self._dw_type if self._dw_type is not None else nullv,
+                                    self._da_src if self._da_src is not None else nullv,
+                                    self._da_dst if self._da_dst is not None else nullv,
+                                    _ptr(d.get("dw_sem")), _ptr(d.get("db_sem")), _ptr(d.get("dq_sem")))
 
 
 class Context:
     def __init__(self, rel_src: Sequence[int], rel_dst: Sequence[int], num_types: int, dtype: str = "f32",
-                 device: int = 0, host_threads: int = 0, concurrent_builds: int = 0):
+                 device: int = 0, host_threads: int = 0, concurrent_builds: int = 0, heads: int = 1,
+                 attention: bool = False):
+        """attention=True: per-relation edge attention with `heads` heads and semantic-attention fusion
+        (HGNN_AGG_ATTN / HGNN_FUSE_SEMATTN) instead of mean aggregation with sum fusion."""
         R = len(rel_src)
         self._rs = (C.c_int32 * R)(*rel_src)
         self._rd = (C.c_int32 * R)(*rel_dst)
-        sch = Schema(num_types, R, self._rs, self._rd, 1, 0, 0, HGNN_BF16 if dtype == "bf16" else HGNN_F32)
+        sch = Schema(num_types, R, self._rs, self._rd, heads, 1 if attention else 0, 1 if attention else 0,
+                     HGNN_BF16 if dtype == "bf16" else HGNN_F32)
         h = C.c_void_p()
         _check(lib.hgnn_create(C.byref(h), C.byref(sch), device, host_threads, concurrent_builds))
         self.handle, self.num_types, self.num_rels, self.dtype = h, num_types, R, dtype

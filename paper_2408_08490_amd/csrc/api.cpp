@@ -57,6 +57,8 @@ struct Plan {
   size_t off_wt = 0, off_gp = 0, off_dz = 0, off_partial = 0, off_acc32 = 0, off_zlo = 0;
 };
 
+static hgnn_status layer_dev(hgnn_ctx *ctx, hgnn_graph *g, int32_t layer, LayerDev &D);
+
 static hgnn_status make_plan(hgnn_ctx *ctx, hgnn_graph *g, int32_t layer, const hgnn_layer_params *p, Plan &pl,
                              bool need_built) {
   if (!ctx || !g || !p) HGNN_FAIL(HGNN_EINVAL, "NULL context, graph or parameters");
@@ -128,13 +130,23 @@ static hgnn_status make_plan(hgnn_ctx *ctx, hgnn_graph *g, int32_t layer, const 
   pl.off_zlo = o;     o += align_up(std::max<size_t>(z, 1) * pl.es, 256);
   pl.scratch_bytes = o;
   if (need_built) {
+    hgnn_status st = layer_dev(ctx, g, layer, pl.dev);
+    if (st != HGNN_OK) return st;
+  }
+  return HGNN_OK;
+}
+
+// Waits for the host build and fills the device-side view of one layer's index arrays.
+static hgnn_status layer_dev(hgnn_ctx *ctx, hgnn_graph *g, int32_t layer, LayerDev &D) {
+  const LayerHost &L = g->L[layer];
+  {
     hgnn_status st = wait_built(g);
     if (st != HGNN_OK) return st;
     if (ctx->device < 0) HGNN_FAIL(HGNN_EUNSUPPORTED, "host-only context cannot run device work");
     const int32_t *b = g->slab.dev;
-    LayerDev &D = pl.dev;
     D.rel_row_off = b + L.o_rel_row_off; D.rel_edge_off = b + L.o_rel_edge_off;
     D.rowptr = b + L.o_rowptr; D.colidx = b + L.o_colidx; D.cptr = b + L.o_cptr; D.crow = b + L.o_crow;
+    D.cperm = b + L.o_cperm;
     D.chunk_row = b + L.o_chunk_row; D.chunk_beg = b + L.o_chunk_beg;
     D.long_row = b + L.o_long_row; D.long_chunk0 = b + L.o_long_chunk0;
     D.rows = (int32_t)L.rows; D.edges = (int32_t)L.edges; D.src_rows = (int32_t)L.src_rows;
@@ -183,6 +195,261 @@ bool probe_take_events(hipEvent_t *start, hipEvent_t *stop) {
   *start = pr.first;
   *stop = pr.second;
   return true;
+}
+
+// ---------------------------------------------------------------------------------------------
+// Attention variant: plan (tables, work-area layout) shared by forward and backward.
+// ---------------------------------------------------------------------------------------------
+struct AttnPlan {
+  TypeTab tt;
+  RelTab rt;
+  PtrTab pt;      // w_root := w_type (per-type projection), bias
+  LayerDev dev;
+  int H = 0, heads = 1, es = 4;
+  int64_t src_rows = 0, rows = 0, edges = 0, total_dst = 0;
+  // saved (forward -> backward)
+  size_t s_z = 0, s_m = 0, s_t = 0, s_mx = 0, s_ls = 0, s_beta = 0, s_wsum = 0, saved_bytes = 0;
+  // scratch (backward)
+  size_t c_gp = 0, c_small = 0, c_du = 0, c_dm = 0, c_alpha = 0, c_ds = 0, c_dsum = 0, c_dz = 0, scratch_bytes = 0;
+};
+constexpr int kSemDimHost = 128;
+
+static hgnn_status make_attn_plan(hgnn_ctx *ctx, hgnn_graph *g, int32_t layer, const hgnn_layer_params *p, AttnPlan &pl,
+                                  bool need_built) {
+  if (!ctx || !g || !p) HGNN_FAIL(HGNN_EINVAL, "NULL context, graph or parameters");
+  if (layer < 0 || layer >= g->num_layers) HGNN_FAIL(HGNN_EINVAL, "layer %d outside [0,%d)", layer, g->num_layers);
+  if (ctx->fuse != HGNN_FUSE_SEMATTN) HGNN_FAIL(HGNN_EUNSUPPORTED, "attention aggregation is implemented with semantic-attention fusion only");
+  if (!p->in_dim || !p->w_type || !p->a_src || !p->a_dst || !p->w_sem || !p->b_sem || !p->q_sem || p->out_dim <= 0)
+    HGNN_FAIL(HGNN_EINVAL, "incomplete attention layer parameters");
+  const int T = ctx->T, R = ctx->R;
+  const LayerHost &L = g->L[layer];
+  pl.es = esize(ctx->dtype);
+  const int vec = 16 / pl.es;
+  pl.H = p->out_dim;
+  pl.heads = ctx->heads;
+  if (pl.H % pl.heads) HGNN_FAIL(HGNN_EINVAL, "out_dim %d is not a multiple of heads %d", pl.H, pl.heads);
+  const int D = pl.H / pl.heads;
+  auto pow2 = [](int n) { return n > 0 && (n & (n - 1)) == 0; };
+  if (D % vec || !pow2(D / vec) || !pow2(pl.H / vec) || pl.H / vec > 64)
+    HGNN_FAIL(HGNN_EUNSUPPORTED, "attention needs out_dim/heads = %d scalars x a power of two and out_dim/%d a power of two <= 64", vec, vec);
+  if (L.tmask != ~0u) HGNN_FAIL(HGNN_EINVAL, "the attention variant needs the transpose entries of every vertex type");
+  std::memset(&pl.tt, 0, sizeof(pl.tt));
+  std::memset(&pl.rt, 0, sizeof(pl.rt));
+  std::memset(&pl.pt, 0, sizeof(pl.pt));
+  pl.tt.num_types = T;
+  pl.rt.num_rels = R;
+  int64_t eo = 0;
+  for (int t = 0; t < T; ++t) {
+    if (p->in_dim[t] <= 0 || p->in_dim[t] % vec != 0)
+      HGNN_FAIL(HGNN_EUNSUPPORTED, "in_dim[%d]=%d is not a positive multiple of %d", t, p->in_dim[t], vec);
+    if (!p->w_type[t] || ((uintptr_t)p->w_type[t] & 15)) HGNN_FAIL(HGNN_EINVAL, "w_type[%d] is NULL or not 16-byte aligned", t);
+    pl.tt.in_dim[t] = p->in_dim[t];
+    pl.tt.n_dst[t] = (int32_t)L.n_dst[t];
+    pl.tt.elem_off[t] = eo;
+    eo += L.n_src[t] * (int64_t)p->in_dim[t];
+    pl.tt.row_off[t + 1] = pl.tt.row_off[t] + (int32_t)L.n_src[t];
+    pl.tt.out_row_off[t + 1] = pl.tt.out_row_off[t] + (int32_t)L.n_dst[t];
+    pl.pt.w_root[t] = p->w_type[t];
+    pl.pt.bias[t] = p->bias ? p->bias[t] : nullptr;
+  }
+  pl.tt.elem_off[T] = eo;
+  for (int r = 0; r < R; ++r) {
+    if (!p->a_src[r] || !p->a_dst[r] || (((uintptr_t)p->a_src[r] | (uintptr_t)p->a_dst[r]) & 15))
+      HGNN_FAIL(HGNN_EINVAL, "a_src[%d] / a_dst[%d] is NULL or not 16-byte aligned", r, r);
+    pl.rt.src[r] = (uint8_t)ctx->rel_src[r];
+    pl.rt.dst[r] = (uint8_t)ctx->rel_dst[r];
+  }
+  if (((uintptr_t)p->w_sem | (uintptr_t)p->b_sem | (uintptr_t)p->q_sem) & 15) HGNN_FAIL(HGNN_EINVAL, "semantic attention parameters must be 16-byte aligned");
+  pl.src_rows = L.src_rows; pl.rows = L.rows; pl.edges = L.edges; pl.total_dst = pl.tt.out_row_off[T];
+  const size_t H = (size_t)pl.H, es = (size_t)pl.es, hd = (size_t)pl.heads;
+  auto take = [](size_t &o, size_t bytes) { const size_t at = o; o += align_up(std::max<size_t>(bytes, 1), 256); return at; };
+  size_t o = 0;
+  pl.s_z = take(o, (size_t)pl.src_rows * H * es);
+  pl.s_m = take(o, (size_t)pl.rows * H * es);
+  pl.s_t = take(o, (size_t)pl.rows * kSemDimHost * es);
+  pl.s_mx = take(o, (size_t)pl.rows * hd * 4);
+  pl.s_ls = take(o, (size_t)pl.rows * hd * 4);
+  pl.s_beta = take(o, (size_t)kMaxR * 4);
+  pl.s_wsum = take(o, (size_t)kMaxR * 4);
+  pl.saved_bytes = o;
+  o = 0;
+  pl.c_gp = take(o, (size_t)pl.total_dst * H * es);
+  pl.c_small = take(o, (size_t)4 * kMaxR * 4);                 // dbeta, coef
+  pl.c_du = take(o, (size_t)pl.rows * kSemDimHost * es);
+  pl.c_dm = take(o, (size_t)pl.rows * H * es);
+  pl.c_alpha = take(o, (size_t)pl.edges * hd * 4);
+  pl.c_ds = take(o, (size_t)pl.edges * hd * 4);
+  pl.c_dsum = take(o, (size_t)pl.rows * hd * 4);
+  pl.c_dz = take(o, (size_t)pl.src_rows * H * es);
+  pl.scratch_bytes = o;
+  if (need_built) return layer_dev(ctx, g, layer, pl.dev);
+  return HGNN_OK;
+}
+
+static hgnn_status attn_fwd(hgnn_ctx *ctx, void *stream, hgnn_graph *g, int32_t layer, const hgnn_layer_params *p, const void *x,
+                            void *h, void *saved, size_t saved_bytes, void *scratch, size_t scratch_bytes) {
+  AttnPlan pl;
+  hgnn_status st = make_attn_plan(ctx, g, layer, p, pl, true);
+  if (st != HGNN_OK) return st;
+  if (pl.src_rows > 0 && !x) HGNN_FAIL(HGNN_EINVAL, "x_merged is NULL");
+  if (pl.total_dst > 0 && !h) HGNN_FAIL(HGNN_EINVAL, "h_out is NULL");
+  if (!saved || !scratch) HGNN_FAIL(HGNN_EINVAL, "NULL work area");
+  if (saved_bytes < pl.saved_bytes || scratch_bytes < pl.scratch_bytes)
+    HGNN_FAIL(HGNN_EINVAL, "work areas too small: need %zu saved, %zu scratch bytes", pl.saved_bytes, pl.scratch_bytes);
+  if (((uintptr_t)saved | (uintptr_t)scratch | (uintptr_t)x | (uintptr_t)h) & 15)
+    HGNN_FAIL(HGNN_EINVAL, "device buffers must be 16-byte aligned");
+  hipStream_t s = (hipStream_t)stream;
+  HGNN_HIP(hipStreamWaitEvent(s, g->ready, 0));
+  char *sv = (char *)saved;
+  const int T = ctx->T;
+  SegTab tl;   // projection tiles: every source row of every type
+  std::memset(&tl, 0, sizeof(tl));
+  tl.num_segs = T;
+  const int tn = (pl.H + 127) / 128;
+  for (int t = 0; t < T; ++t) tl.tile_off[t + 1] = tl.tile_off[t] + (int)((g->L[layer].n_src[t] + 127) / 128) * tn;
+  {
+    Probe pb(ctx, s, HGNN_K_GEMM_FWD, layer);
+    if ((st = launch_attn_proj(s, ctx->dtype, pl.tt, pl.pt, tl, pl.H, x, sv + pl.s_z)) != HGNN_OK) return st;
+  }
+  {
+    Probe pb(ctx, s, HGNN_K_SPMM_FWD, layer);
+    if ((st = launch_attn_agg(s, ctx->dtype, pl.dev, pl.tt, pl.rt, p->a_src, p->a_dst, pl.H, pl.heads, sv + pl.s_z, sv + pl.s_m,
+                              (float *)(sv + pl.s_mx), (float *)(sv + pl.s_ls))) != HGNN_OK) return st;
+  }
+  float *wsum = (float *)(sv + pl.s_wsum), *beta = (float *)(sv + pl.s_beta);
+  if ((st = launch_fill_zero(s, wsum, (size_t)kMaxR * 4)) != HGNN_OK) return st;
+  if ((st = launch_attn_sem(s, ctx->dtype, pl.dev, pl.tt, pl.rt, pl.H, sv + pl.s_m, p->w_sem, p->b_sem, p->q_sem, sv + pl.s_t, wsum)) != HGNN_OK) return st;
+  if ((st = launch_attn_beta(s, pl.tt, pl.rt, wsum, beta, nullptr, nullptr, 0)) != HGNN_OK) return st;
+  return launch_attn_fuse(s, ctx->dtype, pl.dev, pl.tt, pl.rt, pl.pt, pl.H, p->relu, sv + pl.s_m, beta, h);
+}
+
+static hgnn_status attn_bwd(hgnn_ctx *ctx, void *stream, hgnn_graph *g, int32_t layer, const hgnn_layer_params *p, const void *x,
+                            const void *h_out, const void *saved, const void *grad_h, void *grad_x, const hgnn_layer_grads *go,
+                            void *scratch, size_t scratch_bytes) {
+  AttnPlan pl;
+  hgnn_status st = make_attn_plan(ctx, g, layer, p, pl, true);
+  if (st != HGNN_OK) return st;
+  if (!saved || !scratch || !go) HGNN_FAIL(HGNN_EINVAL, "NULL work area or gradient table");
+  if (!go->dw_type || !go->da_src || !go->da_dst || !go->dw_sem || !go->db_sem || !go->dq_sem)
+    HGNN_FAIL(HGNN_EINVAL, "the attention backward needs every gradient buffer of the attention parameters");
+  if (pl.total_dst > 0 && (!x || !grad_h || (p->relu && !h_out))) HGNN_FAIL(HGNN_EINVAL, "NULL input");
+  if (scratch_bytes < pl.scratch_bytes) HGNN_FAIL(HGNN_EINVAL, "scratch too small: need %zu bytes", pl.scratch_bytes);
+  if (((uintptr_t)saved | (uintptr_t)scratch | (uintptr_t)x | (uintptr_t)grad_h | (uintptr_t)grad_x) & 15)
+    HGNN_FAIL(HGNN_EINVAL, "device buffers must be 16-byte aligned");
+  const int R = ctx->R, T = ctx->T, H = pl.H;
+  hipStream_t s = (hipStream_t)stream;
+  HGNN_HIP(hipStreamWaitEvent(s, g->ready, 0));
+  const char *sv = (const char *)saved;
+  char *sc = (char *)scratch;
+  const LayerHost &L = g->L[layer];
+  float *dbeta = (float *)(sc + pl.c_small), *coef = dbeta + kMaxR;
+  const float *beta = (const float *)(sv + pl.s_beta);
+  // zero everything that is accumulated into
+  GradPtrTab gt;
+  std::memset(&gt, 0, sizeof(gt));
+  bool any_db = false;
+  {
+    std::vector<float *> zp;
+    std::vector<int64_t> zn;
+    for (int t = 0; t < T; ++t) {
+      if (!go->dw_type[t]) HGNN_FAIL(HGNN_EINVAL, "dw_type[%d] is NULL", t);
+      gt.dw_root[t] = go->dw_type[t];
+      gt.dbias[t] = (go->dbias && p->bias && p->bias[t]) ? go->dbias[t] : nullptr;
+      any_db |= gt.dbias[t] != nullptr;
+      zp.push_back(go->dw_type[t]); zn.push_back((int64_t)p->in_dim[t] * H);
+      if (gt.dbias[t]) { zp.push_back(gt.dbias[t]); zn.push_back(H); }
+    }
+    for (int r = 0; r < R; ++r) {
+      if (!go->da_src[r] || !go->da_dst[r]) HGNN_FAIL(HGNN_EINVAL, "da_src[%d] / da_dst[%d] is NULL", r, r);
+      zp.push_back(go->da_src[r]); zn.push_back(H);
+      zp.push_back(go->da_dst[r]); zn.push_back(H);
+    }
+    zp.push_back(go->dw_sem); zn.push_back((int64_t)H * kSemDimHost);
+    zp.push_back(go->db_sem); zn.push_back(kSemDimHost);
+    zp.push_back(go->dq_sem); zn.push_back(kSemDimHost);
+    zp.push_back(dbeta); zn.push_back(2 * kMaxR);
+    Probe pb(ctx, s, HGNN_K_ZERO_GRADS, layer);
+    if ((st = launch_attn_zero(s, zp.data(), zn.data(), (int)zp.size())) != HGNN_OK) return st;
+  }
+  // activation / bias backward
+  const void *gp = grad_h;
+  if (pl.total_dst > 0 && (p->relu || any_db)) {
+    Probe pb(ctx, s, HGNN_K_RELU_BIAS_BWD, layer);
+    if ((st = launch_relu_bias_bwd(s, ctx->dtype, pl.tt, H, H, p->relu, grad_h, h_out, sc + pl.c_gp, gt)) != HGNN_OK) return st;
+    if (p->relu) gp = sc + pl.c_gp;   // without an activation the pass only sums the bias gradient
+  }
+  // semantic-attention fusion backward
+  if ((st = launch_attn_dbeta(s, ctx->dtype, pl.dev, pl.tt, pl.rt, H, H, gp, sv + pl.s_m, dbeta)) != HGNN_OK) return st;
+  if ((st = launch_attn_beta(s, pl.tt, pl.rt, nullptr, const_cast<float *>(beta), dbeta, coef, 1)) != HGNN_OK) return st;
+  if ((st = launch_attn_du(s, ctx->dtype, pl.dev, pl.rt, sv + pl.s_t, p->q_sem, coef, sc + pl.c_du, go->dq_sem, go->db_sem)) != HGNN_OK) return st;
+  {
+    Probe pb(ctx, s, HGNN_K_GEMM_DW, layer);
+    if ((st = launch_attn_dws(s, ctx->dtype, pl.rows, H, sv + pl.s_m, sc + pl.c_du, go->dw_sem)) != HGNN_OK) return st;
+  }
+  {
+    Probe pb(ctx, s, HGNN_K_GEMM_DA, layer);
+    if ((st = launch_attn_dm(s, ctx->dtype, pl.dev, pl.tt, pl.rt, H, H, sc + pl.c_du, p->w_sem, gp, beta, sc + pl.c_dm)) != HGNN_OK) return st;
+  }
+  // aggregation backward
+  {
+    Probe pb(ctx, s, HGNN_K_SPMM_BWD, layer);
+    if ((st = launch_attn_agg_bwd(s, ctx->dtype, pl.dev, pl.tt, pl.rt, p->a_src, p->a_dst, go->da_src, go->da_dst, H, pl.heads, sv + pl.s_z,
+                                  sv + pl.s_m, sc + pl.c_dm, (const float *)(sv + pl.s_mx), (const float *)(sv + pl.s_ls),
+                                  (float *)(sc + pl.c_alpha), (float *)(sc + pl.c_ds), (float *)(sc + pl.c_dsum), sc + pl.c_dz)) != HGNN_OK) return st;
+  }
+  // projection backward on the layer GEMMs: every type is a "root" segment over ALL its source rows
+  TypeTab tt2 = pl.tt;
+  RelTab rt2 = pl.rt;
+  for (int t = 0; t < T; ++t) {
+    tt2.n_dst[t] = (int32_t)L.n_src[t];
+    tt2.out_row_off[t + 1] = pl.tt.row_off[t + 1];
+    rt2.zroot_off4[t] = (uint32_t)(pl.tt.elem_off[t] / 4);
+  }
+  tt2.out_row_off[0] = 0;
+  if (pl.src_rows > 0) {
+    DwTab dt;
+    std::memset(&dt, 0, sizeof(dt));
+    int ne = 0;
+    for (int t = 0; t < T; ++t) {
+      dt.first[t] = (uint16_t)ne;
+      int u = 0;
+      if (L.n_src[t] > 0) {
+        dt.seg[ne] = (uint8_t)(R + t);
+        dt.u_off[ne] = 0;
+        u = (p->in_dim[t] + 127) / 128;
+        ++ne;
+      }
+      dt.u_total[t] = (uint16_t)u;
+    }
+    dt.first[T] = (uint16_t)ne;
+    const int tiles_h = (H + 127) / 128;
+    int split_rows = 4096;
+    for (;;) {
+      int64_t tiles = 0;
+      for (int t = 0; t < T; ++t) tiles += (int64_t)dt.u_total[t] * tiles_h * ((L.n_src[t] + split_rows - 1) / split_rows);
+      if (tiles >= 320 || split_rows <= 1024) break;
+      split_rows /= 2;
+    }
+    for (int t = 0; t < T; ++t)
+      dt.tile_off[t + 1] = dt.tile_off[t] + dt.u_total[t] * tiles_h * (int)((L.n_src[t] + split_rows - 1) / split_rows);
+    if ((st = launch_gemm_dw(s, ctx->dtype, pl.dev, tt2, rt2, gt, dt, split_rows, H, H, true, x, nullptr, sc + pl.c_dz)) != HGNN_OK) return st;
+    if (grad_x) {
+      SegTab tl;
+      std::memset(&tl, 0, sizeof(tl));
+      tl.num_segs = R + T;
+      for (int sgi = 0; sgi < R + T; ++sgi) {
+        int cnt = 0;
+        if (sgi >= R) {
+          const int t = sgi - R;
+          const bool want = !p->input_grad || p->input_grad[t];
+          if (want && L.n_src[t] > 0) cnt = (int)((L.n_src[t] + 127) / 128) * ((p->in_dim[t] + 127) / 128);
+        }
+        tl.tile_off[sgi + 1] = tl.tile_off[sgi] + cnt;
+      }
+      if ((st = launch_gemm_da(s, ctx->dtype, pl.dev, tt2, rt2, pl.pt, tl, H, true, sc + pl.c_dz, grad_x)) != HGNN_OK) return st;
+    }
+  }
+  return HGNN_OK;
 }
 
 static void fwd_tiles(const Plan &pl, SegTab &tl) {
@@ -365,10 +632,13 @@ hgnn_status hgnn_build_semantic_csr(hgnn_ctx *ctx, int32_t num_layers, const hgn
     L.o_long_row = take(L.max_long);
     L.o_long_chunk0 = take(L.max_long + 1);
   }
+  const bool cperm_on_device = ctx->agg == HGNN_AGG_ATTN;   // the attention backward walks edges by CSR position
+  if (cperm_on_device)
+    for (int l = 0; l < num_layers; ++l) g->L[l].o_cperm = take(g->L[l].edges);
   const size_t dev_used = o;  // arrays below stay on the host (views only)
   for (int l = 0; l < num_layers; ++l) {
     g->L[l].o_perm = take(g->L[l].edges);
-    g->L[l].o_cperm = take(g->L[l].edges);
+    if (!cperm_on_device) g->L[l].o_cperm = take(g->L[l].edges);
   }
   g->used = dev_used;
   const size_t need = std::max<size_t>(o, 64);
@@ -467,6 +737,14 @@ void hgnn_graph_release(hgnn_ctx *ctx, hgnn_graph *g) {
 
 hgnn_status hgnn_layer_workspace_bytes(hgnn_ctx *ctx, hgnn_graph *g, int32_t layer, const hgnn_layer_params *p,
                                        size_t *saved_bytes, size_t *scratch_bytes) {
+  if (ctx && ctx->agg == HGNN_AGG_ATTN) {
+    AttnPlan ap;
+    hgnn_status sa = make_attn_plan(ctx, g, layer, p, ap, false);
+    if (sa != HGNN_OK) return sa;
+    if (saved_bytes) *saved_bytes = ap.saved_bytes;
+    if (scratch_bytes) *scratch_bytes = ap.scratch_bytes;
+    return HGNN_OK;
+  }
   Plan pl;
   hgnn_status st = make_plan(ctx, g, layer, p, pl, false);
   if (st != HGNN_OK) return st;
@@ -563,6 +841,8 @@ static hgnn_status fwd_common(hgnn_ctx *ctx, void *stream, hgnn_graph *g, int32_
 hgnn_status hgnn_layer_fwd(hgnn_ctx *ctx, void *stream, hgnn_graph *g, int32_t layer, const hgnn_layer_params *p,
                            const void *x_merged, void *h_out, void *saved, size_t saved_bytes, void *scratch,
                            size_t scratch_bytes) {
+  if (ctx && ctx->agg == HGNN_AGG_ATTN)
+    return attn_fwd(ctx, stream, g, layer, p, x_merged, h_out, saved, saved_bytes, scratch, scratch_bytes);
   return fwd_common(ctx, stream, g, layer, p, x_merged, h_out, saved, saved_bytes, scratch, scratch_bytes, false, nullptr);
 }
 
@@ -591,6 +871,8 @@ static void seg_tiles_da(hgnn_ctx *ctx, const Plan &pl, const hgnn_layer_params 
 hgnn_status hgnn_layer_bwd(hgnn_ctx *ctx, void *stream, hgnn_graph *g, int32_t layer, const hgnn_layer_params *p,
                            const void *x_merged, const void *h_out, const void *saved, const void *grad_h,
                            void *grad_x_merged, const hgnn_layer_grads *go, void *scratch, size_t scratch_bytes) {
+  if (ctx && ctx->agg == HGNN_AGG_ATTN)
+    return attn_bwd(ctx, stream, g, layer, p, x_merged, h_out, saved, grad_h, grad_x_merged, go, scratch, scratch_bytes);
   Plan pl;
   hgnn_status st = make_plan(ctx, g, layer, p, pl, true);
   if (st != HGNN_OK) return st;

@@ -98,6 +98,7 @@ struct WtTab {                      // where each transposed weight lives in the
 // Device-side index arrays of one layer (all int32, inside the graph's device block).
 struct LayerDev {
   const int32_t *rel_row_off, *rel_edge_off, *rowptr, *colidx, *cptr, *crow;
+  const int32_t *cperm;                  // CSR position of each transpose entry (uploaded for the attention variant only)
   const int32_t *chunk_row, *chunk_beg;  // transpose rows longer than kLongRow, split in chunks of kChunk edges
   const int32_t *long_row, *long_chunk0; // the long rows and the first chunk of each (n_long + 1 entries)
   int32_t rows, edges, src_rows, n_long, n_chunks;
@@ -218,6 +219,30 @@ hgnn_status launch_gemm_fwd(hipStream_t s, int dtype, const LayerDev &L, const T
                             const PtrTab &pt, const WtTab &wt, const SegTab &tiles, const uint32_t *live_mask, int H,
                             int relu, const void *x, const void *z, const void *zlo, const void *wt_buf, void *h,
                             int only_seg, float *acc32);
+// attention variant
+hgnn_status launch_attn_proj(hipStream_t s, int dtype, const TypeTab &tt, const PtrTab &w_type_as_root, const SegTab &tiles, int H,
+                             const void *x, void *z);
+hgnn_status launch_attn_agg(hipStream_t s, int dtype, const LayerDev &L, const TypeTab &tt, const RelTab &rt,
+                            const void *const *a_src, const void *const *a_dst, int H, int heads, const void *z, void *mout,
+                            float *mx, float *ls);
+hgnn_status launch_attn_sem(hipStream_t s, int dtype, const LayerDev &L, const TypeTab &tt, const RelTab &rt, int H, const void *mbuf,
+                            const void *w_sem, const void *b_sem, const void *q_sem, void *tbuf, float *wsum);
+hgnn_status launch_attn_beta(hipStream_t s, const TypeTab &tt, const RelTab &rt, const float *wsum, float *beta, const float *dbeta,
+                             float *coef, int mode);
+hgnn_status launch_attn_fuse(hipStream_t s, int dtype, const LayerDev &L, const TypeTab &tt, const RelTab &rt, const PtrTab &pt, int H,
+                             int relu, const void *mbuf, const float *beta, void *h);
+hgnn_status launch_attn_zero(hipStream_t s, float *const *ptrs, const int64_t *counts, int n);
+hgnn_status launch_attn_dbeta(hipStream_t s, int dtype, const LayerDev &L, const TypeTab &tt, const RelTab &rt, int H, int ldg,
+                              const void *gp, const void *mbuf, float *dbeta);
+hgnn_status launch_attn_du(hipStream_t s, int dtype, const LayerDev &L, const RelTab &rt, const void *tbuf, const void *q_sem,
+                           const float *coef, void *du, float *dq, float *dbs);
+hgnn_status launch_attn_dm(hipStream_t s, int dtype, const LayerDev &L, const TypeTab &tt, const RelTab &rt, int H, int ldg, const void *du,
+                           const void *w_sem, const void *gp, const float *beta, void *dm);
+hgnn_status launch_attn_dws(hipStream_t s, int dtype, int64_t rows, int H, const void *mbuf, const void *du, float *dws);
+hgnn_status launch_attn_agg_bwd(hipStream_t s, int dtype, const LayerDev &L, const TypeTab &tt, const RelTab &rt, const void *const *a_src,
+                                const void *const *a_dst, float *const *da_src, float *const *da_dst, int H, int heads, const void *z,
+                                const void *mbuf, const void *dm, const float *mx, const float *ls, float *alpha, float *dsb,
+                                float *dsum, void *dz);
 hgnn_status launch_bias_act(hipStream_t s, int dtype, const TypeTab &tt, const PtrTab &pt, int H, int relu,
                             int type, const float *acc32, void *h);
 // gp has leading dimension ldg >= H (zero beyond H), and so have the weights in `pt`

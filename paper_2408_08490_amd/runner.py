@@ -45,12 +45,33 @@ class Model:
         self.dtype, self.loss, self.target_type = dtype, loss, target_type
         self.first_layer_input_grad = first_layer_input_grad
         self.T, self.R = schema.num_types, schema.num_rels
-        self.ctx = B.Context(schema.rel_src, schema.rel_dst, schema.num_types, dtype, device, host_threads, concurrent_builds)
+        self.attention = bool(layers) and len(getattr(layers[0], "w_type", []) or []) > 0
+        heads = 1
+        if self.attention:
+            heads = int(layers[0].a_src[0].shape[0])
+        self.ctx = B.Context(schema.rel_src, schema.rel_dst, schema.num_types, dtype, device, host_threads, concurrent_builds,
+                             heads=heads, attention=self.attention)
         self.feat_dim = list(feat_dim)
         self.stores = [to_device(s, dtype, self.dev) for s in stores]
         self.layers: List[B.Layer] = []
         self.weights = []
         for lw in layers:
+            if self.attention:
+                f32 = dict(device=self.dev, dtype=torch.float32)
+                dev = lambda a: to_device(a, dtype, self.dev)
+                attn = dict(w_type=[dev(w) for w in lw.w_type], a_src=[dev(a) for a in lw.a_src], a_dst=[dev(a) for a in lw.a_dst],
+                            w_sem=dev(lw.w_sem), b_sem=dev(lw.b_sem), q_sem=dev(lw.q_sem))
+                bias = [None if b is None else dev(b) for b in lw.bias]
+                dattn = dict(dw_type=[torch.empty(w.shape, **f32) for w in attn["w_type"]],
+                             da_src=[torch.empty(a.shape, **f32) for a in attn["a_src"]],
+                             da_dst=[torch.empty(a.shape, **f32) for a in attn["a_dst"]],
+                             dw_sem=torch.empty(attn["w_sem"].shape, **f32), db_sem=torch.empty(attn["b_sem"].shape, **f32),
+                             dq_sem=torch.empty(attn["q_sem"].shape, **f32))
+                dbias = [None if b is None else torch.empty(b.shape, **f32) for b in bias]
+                self.weights.append(dict(attn=attn, dattn=dattn, bias=bias, dbias=dbias))
+                self.layers.append(B.Layer(self.ctx, lw.in_dim, lw.out_dim, lw.relu, None, None, bias, None, None, dbias,
+                                           attn=attn, dattn=dattn))
+                continue
             w_rel = [to_device(w, dtype, self.dev) for w in lw.w_rel]
             w_root = [None if w is None else to_device(w, dtype, self.dev) for w in lw.w_root]
             bias = [None if b is None else to_device(b, dtype, self.dev) for b in lw.bias]
@@ -67,7 +88,7 @@ class Model:
     def transpose_types(self, num_layers):
         """Per layer: which vertex types need transpose entries (the first layer skips the types whose input
         gradient is not wanted)."""
-        if self.first_layer_input_grad is None:
+        if self.first_layer_input_grad is None or self.attention:
             return None
         return [list(self.first_layer_input_grad)] + [None] * (num_layers - 1)
 

@@ -32,9 +32,21 @@ def prepare_inputs(index, scale=1.0, batch=None, graph=None):
             lw.w_rel = [bf16_round(w) for w in lw.w_rel]
             lw.w_root = [None if w is None else bf16_round(w) for w in lw.w_root]
             lw.bias = [None if b is None else bf16_round(b) for b in lw.bias]
+            if cfg.kind == "rgat":
+                lw.w_type = [bf16_round(w) for w in lw.w_type]
+                lw.a_src = [bf16_round(a) for a in lw.a_src]
+                lw.a_dst = [bf16_round(a) for a in lw.a_dst]
+                lw.w_sem, lw.b_sem, lw.q_sem = bf16_round(lw.w_sem), bf16_round(lw.b_sem), bf16_round(lw.q_sem)
         if mb.grad_out is not None:
             mb.grad_out = [bf16_round(x) for x in mb.grad_out]
     return cfg, g, mb, ws
+
+
+def layer_dicts(cfg, ws):
+    if cfg.kind == "rgat":
+        return [dict(w_type=lw.w_type, a_src=lw.a_src, a_dst=lw.a_dst, w_sem=lw.w_sem, b_sem=lw.b_sem, q_sem=lw.q_sem,
+                     bias=lw.bias, relu=lw.relu, heads=cfg.heads) for lw in ws]
+    return [dict(w_rel=lw.w_rel, w_root=lw.w_root, bias=lw.bias, relu=lw.relu) for lw in ws]
 
 
 def oracle_run(cfg, g, mb, ws, input_grad=None):
@@ -46,7 +58,7 @@ def oracle_run(cfg, g, mb, ws, input_grad=None):
         sels.append(sel)
         csrs.append(O.semantic_csr(sel, sch.rel_src, sch.rel_dst, b.n_src, b.n_dst,
                                    transpose_types=input_grad if len(csrs) == 0 else None))
-    layers = [dict(w_rel=lw.w_rel, w_root=lw.w_root, bias=lw.bias, relu=lw.relu) for lw in ws]
+    layers = layer_dicts(cfg, ws)
     loss = "xent" if cfg.loss == "xent" else "dot"
     res = O.rgcn_model_forward_backward(blocks_x, sels, sch.rel_src, sch.rel_dst, [b.n_dst for b in mb.blocks],
                                         layers, loss, labels=mb.labels, grad_out=mb.grad_out,
@@ -57,10 +69,14 @@ def oracle_run(cfg, g, mb, ws, input_grad=None):
 
 
 def run_case(index, scale=1.0, batch=None, verbose=False, use_edge_id=True, check_naive=False, graph=None,
-             input_grad=None):
+             input_grad=None, backward=True, cfg_edit=None):
+    """cfg_edit(cfg, g, mb, ws): optional hook that changes the prepared inputs (e.g. the storage type) before
+    both sides run."""
     import torch
     from paper_2408_08490_amd.runner import Model
     cfg, g, mb, ws = prepare_inputs(index, scale, batch, graph)
+    if cfg_edit is not None:
+        cfg_edit(cfg, g, mb, ws)
     sch = g.schema
     t0 = time.time()
     ref = oracle_run(cfg, g, mb, ws, input_grad)
@@ -68,7 +84,7 @@ def run_case(index, scale=1.0, batch=None, verbose=False, use_edge_id=True, chec
     model = Model(sch, g.feat_dim, g.stores, ws, dtype=cfg.dtype, loss=("xent" if cfg.loss == "xent" else "dot"),
                   target_type=mb.target_type, first_layer_input_grad=input_grad)
     bt = model.prepare(mb, g.edge_type, use_edge_id=use_edge_id)
-    out = model.run(bt)
+    out = model.run(bt, backward=backward)
     torch.cuda.synchronize()
     tol = TOL[cfg.dtype]
     report, ok = {}, True
@@ -130,7 +146,7 @@ def run_case(index, scale=1.0, batch=None, verbose=False, use_edge_id=True, chec
         ok = False
     ref_tb = ref
     if n_amb:
-        layers = [dict(w_rel=lw.w_rel, w_root=lw.w_root, bias=lw.bias, relu=lw.relu) for lw in ws]
+        layers = layer_dicts(cfg, ws)
         ref_tb = O.rgcn_model_forward_backward(None, None, sch.rel_src, sch.rel_dst, None, layers,
                                                "xent" if cfg.loss == "xent" else "dot", labels=mb.labels,
                                                grad_out=mb.grad_out, target_type=mb.target_type,
@@ -150,14 +166,27 @@ def run_case(index, scale=1.0, batch=None, verbose=False, use_edge_id=True, chec
     for l in range(len(ws)):
         want = np.concatenate([h.ravel() for h in ref["h"][l]])
         chk(f"L{l}.h", out["h"][l].float().cpu().numpy(), want)
+        if not backward:
+            continue
         gr, gt, w = ref["grads"][l], ref_tb["grads"][l], model.weights[l]
-        for r in range(sch.num_rels):
-            chk2(f"L{l}.dw_rel{r}", w["dw_rel"][r].cpu().numpy(), gr["dw_rel"][r], gt["dw_rel"][r])
-        for t in range(sch.num_types):
-            if gr["dw_root"][t] is not None:
-                chk2(f"L{l}.dw_root{t}", w["dw_root"][t].cpu().numpy(), gr["dw_root"][t], gt["dw_root"][t])
-            if gr["dbias"][t] is not None:
-                chk2(f"L{l}.dbias{t}", w["dbias"][t].cpu().numpy(), gr["dbias"][t], gt["dbias"][t])
+        if cfg.kind == "rgat":
+            for t in range(sch.num_types):
+                chk2(f"L{l}.dw_type{t}", w["dattn"]["dw_type"][t].cpu().numpy(), gr["dw_type"][t], gt["dw_type"][t])
+                if gr["dbias"][t] is not None:
+                    chk2(f"L{l}.dbias{t}", w["dbias"][t].cpu().numpy(), gr["dbias"][t], gt["dbias"][t])
+            for r in range(sch.num_rels):
+                chk2(f"L{l}.da_src{r}", w["dattn"]["da_src"][r].cpu().numpy(), gr["da_src"][r], gt["da_src"][r])
+                chk2(f"L{l}.da_dst{r}", w["dattn"]["da_dst"][r].cpu().numpy(), gr["da_dst"][r], gt["da_dst"][r])
+            for k in ("dw_sem", "db_sem", "dq_sem"):
+                chk2(f"L{l}.{k}", w["dattn"][k].cpu().numpy(), gr[k], gt[k])
+        else:
+            for r in range(sch.num_rels):
+                chk2(f"L{l}.dw_rel{r}", w["dw_rel"][r].cpu().numpy(), gr["dw_rel"][r], gt["dw_rel"][r])
+            for t in range(sch.num_types):
+                if gr["dw_root"][t] is not None:
+                    chk2(f"L{l}.dw_root{t}", w["dw_root"][t].cpu().numpy(), gr["dw_root"][t], gt["dw_root"][t])
+                if gr["dbias"][t] is not None:
+                    chk2(f"L{l}.dbias{t}", w["dbias"][t].cpu().numpy(), gr["dbias"][t], gt["dbias"][t])
         got_dx = out["dx"][l].float().cpu().numpy()
         if l == 0 and input_grad is not None:          # rows of types without input gradients are left unwritten
             eo = np.concatenate([[0], np.cumsum([d.size for d in gr["dx"]])])
