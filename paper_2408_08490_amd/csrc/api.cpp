@@ -1001,6 +1001,16 @@ hgnn_status hgnn_layer_bwd(hgnn_ctx *ctx, void *stream, hgnn_graph *g, int32_t l
 
 hgnn_status hgnn_layer_launch_count(hgnn_ctx *ctx, hgnn_graph *g, int32_t layer, const hgnn_layer_params *p,
                                     int32_t *fwd_launches, int32_t *bwd_launches) {
+  if (ctx && ctx->agg == HGNN_AGG_ATTN) {
+    AttnPlan ap;
+    hgnn_status sa = make_attn_plan(ctx, g, layer, p, ap, true);
+    if (sa != HGNN_OK) return sa;
+    // forward: projection, aggregation, zero scores, semantic scores, relation softmax, fusion
+    if (fwd_launches) *fwd_launches = 6;
+    // backward: zero, (activation/bias), relation dots, relation softmax, du, dW_s, dm, row pass, transpose pass, dW_t, dX
+    if (bwd_launches) *bwd_launches = 10 + ((p->relu || p->bias) ? 1 : 0);
+    return HGNN_OK;
+  }
   Plan pl;
   hgnn_status st = make_plan(ctx, g, layer, p, pl, true);
   if (st != HGNN_OK) return st;

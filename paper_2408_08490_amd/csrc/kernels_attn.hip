@@ -370,7 +370,7 @@ hgnn_status launch_attn_fuse(hipStream_t s, int dtype, const LayerDev &L, const 
 //   fusion      dbeta_r = sum_v G'_v . m_v^r ; softmax over relations backward -> coef_r (attn_beta_kernel, mode 1)
 //               du = coef_r q (1 - t^2), dq, db_s (column sums) ; dW_s += m^T du (MFMA, split over rows)
 //               dm = beta_r G'_v + du W_s^T (MFMA)
-//   aggregation per merged row: alpha recomputed from the saved maximum and sum; sum_u alpha_u dalpha_u = dm . m ;
+//   aggregation per merged row: alpha recomputed from the saved maximum and sum; sum_u alpha_u dalpha_u in a first pass;
 //               per edge alpha and ds (gradient before the LeakyReLU) are stored by CSR position, da_src / da_dst
 //               accumulated in registers over a run of rows; per source row (transpose): dz = sum over its edges
 //               of alpha dm_v + ds a_src, plus, for a destination row, sum_r (sum_u ds) a_dst
@@ -506,7 +506,7 @@ __global__ void __launch_bounds__(kThreads, 2) attn_dws_kernel(int64_t rows, int
 template <typename T>
 __global__ void __launch_bounds__(256) attn_agg_bwd_rows_kernel(LayerDev L, TypeTab tt, RelTab rt, AttnPtrs ap, AttnPtrs dap, int H, int heads,
                                                                 int lpr_log2, int hl, int rows_per_group, const T *__restrict__ z,
-                                                                const T *__restrict__ mbuf, const T *__restrict__ dm,
+                                                                const T *__restrict__ dm,
                                                                 const float *__restrict__ mx, const float *__restrict__ ls,
                                                                 float *__restrict__ alpha, float *__restrict__ dsb,
                                                                 float *__restrict__ dsum) {
@@ -545,21 +545,35 @@ __global__ void __launch_bounds__(256) attn_agg_bwd_rows_kernel(LayerDev L, Type
     }
     const int v = (int)rho - L.rel_row_off[r];
     const int d = rt.dst[r];
-    float zv[P::N], g[P::N], mv[P::N];
+    float zv[P::N], g[P::N];
     P::load(zv, z + ((int64_t)tt.row_off[d] + v) * H + q * P::N);
     P::load(g, dm + rho * H + q * P::N);
-    P::load(mv, mbuf + rho * H + q * P::N);
-    float sd = 0.f, gm = 0.f;
+    float sd = 0.f;
 #pragma unroll
-    for (int i = 0; i < P::N; ++i) {
-      sd += ad[i] * zv[i];
-      gm += g[i] * mv[i];
-    }
-    for (int o = hl >> 1; o > 0; o >>= 1) {
-      sd += __shfl_xor(sd, o);
-      gm += __shfl_xor(gm, o);
-    }
+    for (int i = 0; i < P::N; ++i) sd += ad[i] * zv[i];
+    for (int o = hl >> 1; o > 0; o >>= 1) sd += __shfl_xor(sd, o);
     const float mxk = mx[rho * heads + k], inv_l = 1.f / ls[rho * heads + k];
+    // first pass: gm = sum_u alpha_u dalpha_u, summed edge by edge.  (It equals dm . m in exact arithmetic, but the
+    // stored m is rounded to the storage type and the difference would not cancel in alpha (dalpha - gm).)
+    float gm = 0.f;
+    for (int e = e0; e < e1; ++e) {
+      const int u = L.colidx[e];
+      float zu[P::N];
+      P::load(zu, z + (int64_t)u * H + q * P::N);
+      float ss = 0.f, da = 0.f;
+#pragma unroll
+      for (int i = 0; i < P::N; ++i) {
+        ss += as[i] * zu[i];
+        da += g[i] * zu[i];
+      }
+      for (int o = hl >> 1; o > 0; o >>= 1) {
+        ss += __shfl_xor(ss, o);
+        da += __shfl_xor(da, o);
+      }
+      const float sc = ss + sd;
+      const float ev = sc > 0.f ? sc : kLeaky * sc;
+      gm += __expf(ev - mxk) * inv_l * da;
+    }
     float dsv_sum = 0.f;
     for (int e = e0; e < e1; ++e) {
       const int u = L.colidx[e];
@@ -729,10 +743,10 @@ hgnn_status launch_attn_agg_bwd(hipStream_t s, int dtype, const LayerDev &L, con
     dim3 grid((unsigned)((L.rows + (int64_t)gpb * rpg - 1) / ((int64_t)gpb * rpg)));
     if (dtype == HGNN_BF16)
       HGNN_LAUNCH(attn_agg_bwd_rows_kernel<bf16>, grid, dim3(256), 0, s, L, tt, rt, ap, dap, H, heads, l2, hl, rpg, (const bf16 *)z,
-                  (const bf16 *)mbuf, (const bf16 *)dm, mx, ls, alpha, dsb, dsum);
+                  (const bf16 *)dm, mx, ls, alpha, dsb, dsum);
     else
       HGNN_LAUNCH(attn_agg_bwd_rows_kernel<float>, grid, dim3(256), 0, s, L, tt, rt, ap, dap, H, heads, l2, hl, rpg, (const float *)z,
-                  (const float *)mbuf, (const float *)dm, mx, ls, alpha, dsb, dsum);
+                  (const float *)dm, mx, ls, alpha, dsb, dsum);
     HGNN_HIP(hipGetLastError());
   }
   if (L.src_rows > 0) {
