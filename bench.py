@@ -177,11 +177,13 @@ def main():
     # launches per layer: merged vs per-relation / per-type launch loop
     launches = []
     b0 = batch_of(slots[0], graphs[0])
-    out_naive = model.run(b0, backward=False, naive=True)
+    attention = cfg.kind == "rgat"   # the per-relation launch loop exists for the mean variant only
+    out_naive = None if attention else model.run(b0, backward=False, naive=True)
     torch.cuda.synchronize()
     for l in range(len(model.layers)):
         f, bw = ctx.hgnn_layer_launch_count(graphs[0], l, model.layers[l])
-        launches.append(dict(layer=l, merged_fwd=f, merged_bwd=bw, naive_fwd=out_naive["launches"][l]))
+        launches.append(dict(layer=l, merged_fwd=f, merged_bwd=bw,
+                             naive_fwd=None if attention else out_naive["launches"][l]))
 
     # algorithmic traffic / flops of the probed kernels, from the first mini-batch's shapes
     es = 2 if cfg.dtype == "bf16" else 4
@@ -195,6 +197,24 @@ def main():
         view = graphs[0].host_view(layer)
         rows, E = int(view["rows"]), int(view["edges"])
         live = [view["rel_edge_off"][r + 1] > view["rel_edge_off"][r] for r in range(sch.num_rels)]
+        if kname == "spmm_fwd" and attention:
+            # attention aggregation over projected rows of width H: each referenced source row once per relation
+            # segment, the destination's own row, index arrays, the aggregate and the softmax statistics
+            H = lw.out_dim
+            uniq = sum(len(np.unique(view["colidx"][view["rel_edge_off"][r]: view["rel_edge_off"][r + 1]]))
+                       for r in range(sch.num_rels))
+            alg = (uniq + 2 * rows) * H * es + 4 * E + 4 * (rows + 1) + 2 * rows * cfg.heads * 4
+            ach = alg / (avg_ms * 1e-3) / 1e9 if avg_ms > 0 else 0.0
+            return dict(kernel="attn_agg_kernel (layer %d: segment-softmax aggregation)" % (layer + 1), bound="hbm",
+                        achieved=round(ach, 1), peak=HBM_PEAK_GBS, unit="GB/s", frac=round(ach / HBM_PEAK_GBS, 4),
+                        traffic=None, algorithmic_bytes=int(alg), avg_kernel_us=round(avg_ms * 1e3, 2), launches_timed=probe_n)
+        if kname == "gemm_fwd" and attention:
+            flops = sum(2 * blk.n_src[t] * lw.in_dim[t] * lw.out_dim for t in range(sch.num_types))
+            ach = flops / (avg_ms * 1e-3) / 1e12 if avg_ms > 0 else 0.0
+            peak = MFMA_BF16_PEAK_TFLOPS if cfg.dtype == "bf16" else 157.3
+            return dict(kernel="attn_proj_kernel (layer %d: per-type projection)" % (layer + 1), bound="mfma",
+                        achieved=round(ach, 1), peak=peak, unit="TFLOP/s", frac=round(ach / peak, 4), traffic=None,
+                        algorithmic_flops=int(flops), avg_kernel_us=round(avg_ms * 1e3, 2), launches_timed=probe_n)
         if kname == "spmm_fwd":
             # each referenced source row once per relation segment + index arrays + the output plane(s)
             uniq = sum(len(np.unique(view["colidx"][view["rel_edge_off"][r]: view["rel_edge_off"][r + 1]])) *
@@ -229,8 +249,9 @@ def main():
     roof_agg = roofline_of(*probes[1]) if len(probes) > 1 else None
     if roof_agg is not None:
         # HBM bytes per launch from rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE runs of this command (profiles/)
-        roof["traffic"] = TRAFFIC_BYTES.get("gemm_fwd")
-        roof_agg["traffic"] = TRAFFIC_BYTES.get("spmm_fwd")
+        if cfg.index == 2 and args.scale == 1.0:     # measured on the default workload only
+            roof["traffic"] = TRAFFIC_BYTES.get("gemm_fwd")
+            roof_agg["traffic"] = TRAFFIC_BYTES.get("spmm_fwd")
 
     for gr in graphs:
         gr.release()
