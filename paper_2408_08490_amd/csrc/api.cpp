@@ -210,7 +210,7 @@ struct AttnPlan {
   // saved (forward -> backward)
   size_t s_z = 0, s_m = 0, s_t = 0, s_mx = 0, s_ls = 0, s_beta = 0, s_wsum = 0, saved_bytes = 0;
   // scratch (backward)
-  size_t c_gp = 0, c_small = 0, c_du = 0, c_dm = 0, c_alpha = 0, c_ds = 0, c_dsum = 0, c_dz = 0, scratch_bytes = 0;
+  size_t c_gp = 0, c_small = 0, c_du = 0, c_dm = 0, c_alpha = 0, c_ds = 0, c_dsum = 0, c_dz = 0, c_partial = 0, scratch_bytes = 0;
 };
 constexpr int kSemDimHost = 128;
 
@@ -281,6 +281,7 @@ static hgnn_status make_attn_plan(hgnn_ctx *ctx, hgnn_graph *g, int32_t layer, c
   pl.c_ds = take(o, (size_t)pl.edges * hd * 4);
   pl.c_dsum = take(o, (size_t)pl.rows * hd * 4);
   pl.c_dz = take(o, (size_t)pl.src_rows * H * es);
+  pl.c_partial = take(o, (size_t)L.max_chunks * H * 4);
   pl.scratch_bytes = o;
   if (need_built) return layer_dev(ctx, g, layer, pl.dev);
   return HGNN_OK;
@@ -395,7 +396,8 @@ static hgnn_status attn_bwd(hgnn_ctx *ctx, void *stream, hgnn_graph *g, int32_t 
     Probe pb(ctx, s, HGNN_K_SPMM_BWD, layer);
     if ((st = launch_attn_agg_bwd(s, ctx->dtype, pl.dev, pl.tt, pl.rt, p->a_src, p->a_dst, go->da_src, go->da_dst, H, pl.heads, sv + pl.s_z,
                                   sv + pl.s_m, sc + pl.c_dm, (const float *)(sv + pl.s_mx), (const float *)(sv + pl.s_ls),
-                                  (float *)(sc + pl.c_alpha), (float *)(sc + pl.c_ds), (float *)(sc + pl.c_dsum), sc + pl.c_dz)) != HGNN_OK) return st;
+                                  (float *)(sc + pl.c_alpha), (float *)(sc + pl.c_ds), (float *)(sc + pl.c_dsum), sc + pl.c_dz,
+                                  (float *)(sc + pl.c_partial))) != HGNN_OK) return st;
   }
   // projection backward on the layer GEMMs: every type is a "root" segment over ALL its source rows
   TypeTab tt2 = pl.tt;

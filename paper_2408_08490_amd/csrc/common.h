@@ -242,7 +242,7 @@ hgnn_status launch_attn_dws(hipStream_t s, int dtype, int64_t rows, int H, const
 hgnn_status launch_attn_agg_bwd(hipStream_t s, int dtype, const LayerDev &L, const TypeTab &tt, const RelTab &rt, const void *const *a_src,
                                 const void *const *a_dst, float *const *da_src, float *const *da_dst, int H, int heads, const void *z,
                                 const void *mbuf, const void *dm, const float *mx, const float *ls, float *alpha, float *dsb,
-                                float *dsum, void *dz);
+                                float *dsum, void *dz, float *partial);
 hgnn_status launch_bias_act(hipStream_t s, int dtype, const TypeTab &tt, const PtrTab &pt, int H, int relu,
                             int type, const float *acc32, void *h);
 // gp has leading dimension ldg >= H (zero beyond H), and so have the weights in `pt`

@@ -13,6 +13,7 @@ namespace hgnn {
 
 constexpr float kLeaky = 0.2f;
 constexpr int kSemDim = 128;
+constexpr int kAttnMaxH = 1024;  // widest layer output of the attention variant (64 lanes x 16 bytes)
 
 struct AttnPtrs {
   const void *a_src[kMaxR];
@@ -516,11 +517,28 @@ __global__ void __launch_bounds__(256) attn_agg_bwd_rows_kernel(LayerDev L, Type
   const int k = (q * P::N) / (H / heads);
   const bool head_lead = (q & (hl - 1)) == 0;
   const int64_t g0 = ((int64_t)blockIdx.x * (256 >> lpr_log2) + (threadIdx.x >> lpr_log2)) * rows_per_group;
-  if (g0 >= L.rows) return;
+  // The block's sums for da_src / da_dst meet in LDS first (nearly every block lies inside one relation); only a
+  // group in another relation than the block's first row adds to global memory directly.
+  __shared__ float s_das[kAttnMaxH], s_dad[kAttnMaxH];
+  __shared__ int s_rel;
+  for (int i = threadIdx.x; i < H; i += 256) s_das[i] = s_dad[i] = 0.f;
+  if (threadIdx.x == 0) {
+    const int64_t first = (int64_t)blockIdx.x * (256 >> lpr_log2) * rows_per_group;
+    s_rel = first < L.rows ? find_le(L.rel_row_off, rt.num_rels, (int)first) : -1;
+  }
+  __syncthreads();
   int r = -1;
   float as[P::N], ad[P::N], das[P::N], dad[P::N];
   auto flush = [&]() {
     if (r < 0) return;
+    if (r == s_rel) {
+#pragma unroll
+      for (int i = 0; i < P::N; ++i) {
+        if (das[i] != 0.f) atomicAdd(&s_das[q * P::N + i], das[i]);
+        if (dad[i] != 0.f) atomicAdd(&s_dad[q * P::N + i], dad[i]);
+      }
+      return;
+    }
     float *ps = reinterpret_cast<float *>(const_cast<void *>(dap.a_src[r])) + q * P::N;
     float *pd = reinterpret_cast<float *>(const_cast<void *>(dap.a_dst[r])) + q * P::N;
 #pragma unroll
@@ -606,53 +624,151 @@ __global__ void __launch_bounds__(256) attn_agg_bwd_rows_kernel(LayerDev L, Type
     if (head_lead) dsum[rho * heads + k] = dsv_sum;
   }
   flush();
+  __syncthreads();
+  if (s_rel >= 0) {
+    float *ps = reinterpret_cast<float *>(const_cast<void *>(dap.a_src[s_rel]));
+    float *pd = reinterpret_cast<float *>(const_cast<void *>(dap.a_dst[s_rel]));
+    for (int i = threadIdx.x; i < H; i += 256) {
+      if (s_das[i] != 0.f) atomicAdd(ps + i, s_das[i]);
+      if (s_dad[i] != 0.f) atomicAdd(pd + i, s_dad[i]);
+    }
+  }
 }
 
 // Aggregation backward, by source row (transpose): dz[c] = sum_j alpha_j dm[crow_j] + ds_j a_src[rel(crow_j)]
 // (+ for a destination row: sum over the relations ending in its type of dsum[row] a_dst[r]).
+// Work items: one per source row (rows longer than kLongRow entries are left to the chunk items), then one per
+// chunk of a long row, which writes an fp32 partial sum; attn_agg_bwd_long_kernel adds a long row's partials up.
 template <typename T>
 __global__ void __launch_bounds__(256) attn_agg_bwd_cols_kernel(LayerDev L, TypeTab tt, RelTab rt, RelsOfType ro, AttnPtrs ap, int H, int heads,
                                                                 int lpr_log2, const T *__restrict__ dm, const float *__restrict__ alpha,
                                                                 const float *__restrict__ dsb, const float *__restrict__ dsum,
-                                                                T *__restrict__ dz) {
+                                                                T *__restrict__ dz, float *__restrict__ partial) {
   using P = Piece<T>;
   const int lpr = 1 << lpr_log2;
   const int q = threadIdx.x & (lpr - 1);
   const int k = (q * P::N) / (H / heads);
-  const int64_t c = (int64_t)blockIdx.x * (256 >> lpr_log2) + (threadIdx.x >> lpr_log2);
-  if (c >= L.src_rows) return;
+  const int64_t item = (int64_t)blockIdx.x * (256 >> lpr_log2) + (threadIdx.x >> lpr_log2);
+  if (item >= (int64_t)L.src_rows + L.n_chunks) return;
+  const bool chunk = item >= L.src_rows;
+  const int64_t c = chunk ? L.chunk_row[item - L.src_rows] : item;
+  int j0 = L.cptr[c], j1 = L.cptr[c + 1];
+  if (chunk) {
+    j0 = L.chunk_beg[item - L.src_rows];
+    j1 = min(j1, j0 + kChunk);
+  } else if (j1 - j0 > kLongRow) {
+    return;
+  }
   float acc[P::N];
 #pragma unroll
   for (int i = 0; i < P::N; ++i) acc[i] = 0.f;
-  int r = -1, r_lo = 0, r_hi = 0;
+  int r_lo = 0, r_hi = 0;
   float as[P::N];
-  for (int j = L.cptr[c]; j < L.cptr[c + 1]; ++j) {
-    const int rho = L.crow[j], e = L.cperm[j];
+  auto rel_of = [&](int rho) {
     if (rho < r_lo || rho >= r_hi) {
-      r = find_le(L.rel_row_off, rt.num_rels, rho);
+      const int r = find_le(L.rel_row_off, rt.num_rels, rho);
       r_lo = L.rel_row_off[r];
       r_hi = L.rel_row_off[r + 1];
       P::load(as, reinterpret_cast<const T *>(ap.a_src[r]) + q * P::N);
     }
-    const float a = alpha[(int64_t)e * heads + k], dsv = dsb[(int64_t)e * heads + k];
-    float g[P::N];
-    P::load(g, dm + (int64_t)rho * H + q * P::N);
+  };
+  int j = j0;
+  for (; j + 2 <= j1; j += 2) {   // two rows of dm in flight
+    const int rho0 = L.crow[j], e0 = L.cperm[j], rho1 = L.crow[j + 1], e1 = L.cperm[j + 1];
+    float g0[P::N], g1[P::N];
+    P::load(g0, dm + (int64_t)rho0 * H + q * P::N);
+    P::load(g1, dm + (int64_t)rho1 * H + q * P::N);
+    const float a0 = alpha[(int64_t)e0 * heads + k], d0 = dsb[(int64_t)e0 * heads + k];
+    const float a1 = alpha[(int64_t)e1 * heads + k], d1 = dsb[(int64_t)e1 * heads + k];
+    rel_of(rho0);
 #pragma unroll
-    for (int i = 0; i < P::N; ++i) acc[i] += a * g[i] + dsv * as[i];
+    for (int i = 0; i < P::N; ++i) acc[i] += a0 * g0[i] + d0 * as[i];
+    rel_of(rho1);
+#pragma unroll
+    for (int i = 0; i < P::N; ++i) acc[i] += a1 * g1[i] + d1 * as[i];
+  }
+  if (j < j1) {
+    const int rho0 = L.crow[j], e0 = L.cperm[j];
+    float g0[P::N];
+    P::load(g0, dm + (int64_t)rho0 * H + q * P::N);
+    const float a0 = alpha[(int64_t)e0 * heads + k], d0 = dsb[(int64_t)e0 * heads + k];
+    rel_of(rho0);
+#pragma unroll
+    for (int i = 0; i < P::N; ++i) acc[i] += a0 * g0[i] + d0 * as[i];
+  }
+  if (chunk) {
+    float *pp = partial + (item - L.src_rows) * H + q * P::N;
+#pragma unroll
+    for (int i = 0; i < P::N; ++i) pp[i] = acc[i];
+    return;
   }
   const int t = find_le(tt.row_off, tt.num_types, (int)c);
   const int v = (int)c - tt.row_off[t];
   if (v < tt.n_dst[t]) {
-    for (int j = ro.first[t]; j < ro.first[t + 1]; ++j) {
-      const int rr = ro.rel[j];
-      const float s = dsum[((int64_t)L.rel_row_off[rr] + v) * heads + k];
+    for (int jj = ro.first[t]; jj < ro.first[t + 1]; ++jj) {
+      const int rr = ro.rel[jj];
+      const float sv = dsum[((int64_t)L.rel_row_off[rr] + v) * heads + k];
       float ad[P::N];
       P::load(ad, reinterpret_cast<const T *>(ap.a_dst[rr]) + q * P::N);
 #pragma unroll
-      for (int i = 0; i < P::N; ++i) acc[i] += s * ad[i];
+      for (int i = 0; i < P::N; ++i) acc[i] += sv * ad[i];
     }
   }
   P::store(dz + c * H + q * P::N, acc);
+}
+
+// Long rows: one block per row adds the chunk partials (threads form groups over four columns each, group g takes
+// chunks g, g + groups, ...; LDS adds the groups), then the destination-side term, and writes the row.
+template <typename T>
+__global__ void __launch_bounds__(256) attn_agg_bwd_long_kernel(LayerDev L, TypeTab tt, RelsOfType ro, AttnPtrs ap, int H, int heads,
+                                                                const float *__restrict__ partial, const float *__restrict__ dsum,
+                                                                T *__restrict__ dz) {
+  __shared__ float red[256 * 4];
+  const int i = blockIdx.x;
+  const int c = L.long_row[i];
+  const int j0 = L.long_chunk0[i], j1 = L.long_chunk0[i + 1];
+  const int nw = H / 4;
+  int lanes = 1;
+  while (lanes < nw && lanes < 256) lanes <<= 1;
+  const int groups = 256 / lanes, g = threadIdx.x / lanes, ln = threadIdx.x % lanes;
+  const int t = find_le(tt.row_off, tt.num_types, c);
+  const int v = c - tt.row_off[t];
+  for (int q0 = 0; q0 < nw; q0 += lanes) {
+    const int q = q0 + ln;
+    f32x4 acc = {0.f, 0.f, 0.f, 0.f};
+    if (q < nw) {
+      int j = j0 + g;
+      for (; j + 3 * groups < j1; j += 4 * groups) {
+        const f32x4 v0 = *reinterpret_cast<const f32x4 *>(partial + (int64_t)j * H + q * 4);
+        const f32x4 v1 = *reinterpret_cast<const f32x4 *>(partial + (int64_t)(j + groups) * H + q * 4);
+        const f32x4 v2 = *reinterpret_cast<const f32x4 *>(partial + (int64_t)(j + 2 * groups) * H + q * 4);
+        const f32x4 v3 = *reinterpret_cast<const f32x4 *>(partial + (int64_t)(j + 3 * groups) * H + q * 4);
+        acc += (v0 + v1) + (v2 + v3);
+      }
+      for (; j < j1; j += groups) acc += *reinterpret_cast<const f32x4 *>(partial + (int64_t)j * H + q * 4);
+    }
+    if (groups > 1) {
+      *reinterpret_cast<f32x4 *>(red + threadIdx.x * 4) = acc;
+      __syncthreads();
+      if (g == 0)
+        for (int o = 1; o < groups; ++o) acc += *reinterpret_cast<const f32x4 *>(red + (o * lanes + ln) * 4);
+    }
+    if (g == 0 && q < nw) {
+      const int k = (q * 4) / (H / heads);
+      if (v < tt.n_dst[t]) {
+        for (int jj = ro.first[t]; jj < ro.first[t + 1]; ++jj) {
+          const int rr = ro.rel[jj];
+          const float sv = dsum[((int64_t)L.rel_row_off[rr] + v) * heads + k];
+          const T *ad = reinterpret_cast<const T *>(ap.a_dst[rr]) + q * 4;
+#pragma unroll
+          for (int e = 0; e < 4; ++e) acc[e] += sv * to_float(ad[e]);
+        }
+      }
+#pragma unroll
+      for (int e = 0; e < 4; ++e) dz[(int64_t)c * H + q * 4 + e] = from_float<T>(acc[e]);
+    }
+    if (groups > 1) __syncthreads();
+  }
 }
 
 // ------------------------------------------------------------------------------------------
@@ -727,7 +843,7 @@ hgnn_status launch_attn_dws(hipStream_t s, int dtype, int64_t rows, int H, const
 hgnn_status launch_attn_agg_bwd(hipStream_t s, int dtype, const LayerDev &L, const TypeTab &tt, const RelTab &rt, const void *const *a_src,
                                 const void *const *a_dst, float *const *da_src, float *const *da_dst, int H, int heads, const void *z,
                                 const void *mbuf, const void *dm, const float *mx, const float *ls, float *alpha, float *dsb,
-                                float *dsum, void *dz) {
+                                float *dsum, void *dz, float *partial) {
   AttnPtrs ap, dap;
   std::memset(&ap, 0, sizeof(ap));
   std::memset(&dap, 0, sizeof(dap));
@@ -738,7 +854,7 @@ hgnn_status launch_attn_agg_bwd(hipStream_t s, int dtype, const LayerDev &L, con
     dap.a_dst[r] = da_dst[r];
   }
   const int es = dtype == HGNN_BF16 ? 2 : 4;
-  const int lpr = H * es / 16, l2 = log2_exact(lpr), hl = (H / heads) * es / 16, gpb = 256 >> l2, rpg = 32;
+  const int lpr = H * es / 16, l2 = log2_exact(lpr), hl = (H / heads) * es / 16, gpb = 256 >> l2, rpg = 8;
   if (L.rows > 0) {
     dim3 grid((unsigned)((L.rows + (int64_t)gpb * rpg - 1) / ((int64_t)gpb * rpg)));
     if (dtype == HGNN_BF16)
@@ -752,14 +868,21 @@ hgnn_status launch_attn_agg_bwd(hipStream_t s, int dtype, const LayerDev &L, con
   if (L.src_rows > 0) {
     RelsOfType ro;
     rels_of_type(tt, rt, ro);
-    dim3 grid((unsigned)((L.src_rows + gpb - 1) / gpb));
+    dim3 grid((unsigned)(((int64_t)L.src_rows + L.n_chunks + gpb - 1) / gpb));
     if (dtype == HGNN_BF16)
       HGNN_LAUNCH(attn_agg_bwd_cols_kernel<bf16>, grid, dim3(256), 0, s, L, tt, rt, ro, ap, H, heads, l2, (const bf16 *)dm, alpha, dsb, dsum,
-                  (bf16 *)dz);
+                  (bf16 *)dz, partial);
     else
       HGNN_LAUNCH(attn_agg_bwd_cols_kernel<float>, grid, dim3(256), 0, s, L, tt, rt, ro, ap, H, heads, l2, (const float *)dm, alpha, dsb, dsum,
-                  (float *)dz);
+                  (float *)dz, partial);
     HGNN_HIP(hipGetLastError());
+    if (L.n_long > 0) {
+      if (dtype == HGNN_BF16)
+        HGNN_LAUNCH(attn_agg_bwd_long_kernel<bf16>, dim3(L.n_long), dim3(256), 0, s, L, tt, ro, ap, H, heads, partial, dsum, (bf16 *)dz);
+      else
+        HGNN_LAUNCH(attn_agg_bwd_long_kernel<float>, dim3(L.n_long), dim3(256), 0, s, L, tt, ro, ap, H, heads, partial, dsum, (float *)dz);
+      HGNN_HIP(hipGetLastError());
+    }
   }
   return HGNN_OK;
 }
