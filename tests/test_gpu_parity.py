@@ -1,4 +1,5 @@
 """GPU parity: the C-ABI path against the CPU oracle, element by element, on seeded inputs."""
+import numpy as np
 import pytest
 
 from tests.parity import run_case
@@ -66,4 +67,34 @@ def test_config4_attention_bf16_scaled():
     loose = {"da_src": None, "da_dst": None, "dw_type": 0.1, "dbias": 0.1, "dw_sem": 0.1, "db_sem": 0.1, "dq_sem": 0.1,
              ".dx": 0.1}
     r = run_case(4, scale=0.02, batch=64, verbose=True, grad_tol=loose)
+    assert r["ok"], r
+
+
+def _drop_edges(keep):
+    """Hook for run_case: keeps only the edges of the first block for which keep(edge_type) is true."""
+    def edit(cfg, g, mb, ws):
+        b = mb.blocks[0]
+        m = np.array([bool(keep(int(t))) for t in b.edge_type], dtype=bool)
+        b.edge_index = np.ascontiguousarray(b.edge_index[:, m])
+        b.edge_id, b.edge_type = b.edge_id[m], b.edge_type[m]
+    return edit
+
+
+def test_relation_without_edges_and_block_without_edges():
+    """Degenerate inputs: a relation that loses all its edges (its aggregate rows are zero, its weight gradient
+    exactly zero), and a block with no edge at all (only the root term and the bias remain)."""
+    r = run_case(0, verbose=True, cfg_edit=_drop_edges(lambda t: t != 0))
+    assert r["ok"], r
+    r = run_case(0, verbose=True, cfg_edit=_drop_edges(lambda t: False))
+    assert r["ok"], r
+    r = run_case(4, scale=0.02, batch=16, verbose=True, cfg_edit=lambda c, g, mb, ws: (_as_f32(c, g, mb, ws),
+                                                                                       _drop_edges(lambda t: t != 1)(c, g, mb, ws)))
+    assert r["ok"], r
+
+
+def test_single_target_minibatch():
+    """One target vertex: every tile and lane group is ragged."""
+    r = run_case(1, scale=0.05, batch=1, verbose=True)
+    assert r["ok"], r
+    r = run_case(2, scale=0.05, batch=1, verbose=True)
     assert r["ok"], r
