@@ -207,3 +207,42 @@ def test_transpose_restricted_to_wanted_types(B):
             assert v["transpose_edges"] < v["edges"] and v["cptr"][b.n_src[0]] == 0
     gr.release()
     ctx.close()
+
+
+def test_attention_plan_validation_without_gpu(B):
+    """hgnn_layer_workspace_bytes needs no GPU: the attention variant's shape rules are checked on a host-only
+    context (head width a power of two times 16 bytes, H a multiple of the head count, all transpose entries)."""
+    import torch
+    cfg = make_config(4, scale=0.01, batch=8)
+    g = build_graph(cfg)
+    mb = sample_minibatch(cfg, g)
+    sch = g.schema
+    T, R = sch.num_types, sch.num_rels
+    ctx = B.Context(sch.rel_src, sch.rel_dst, T, "f32", device=-1, host_threads=2, heads=8, attention=True)
+    gr = ctx.hgnn_build_semantic_csr(mb.blocks, g.edge_type, use_edge_id=True)
+    gr.wait()
+
+    def layer(H):
+        D = max(H // 8, 1)
+        attn = dict(w_type=[torch.zeros(f, H) for f in g.feat_dim], a_src=[torch.zeros(8, D) for _ in range(R)],
+                    a_dst=[torch.zeros(8, D) for _ in range(R)], w_sem=torch.zeros(H, 128), b_sem=torch.zeros(128),
+                    q_sem=torch.zeros(128))
+        return B.Layer(ctx, g.feat_dim, H, True, None, None, None, attn=attn)
+
+    saved, scratch = ctx.hgnn_layer_workspace_bytes(gr, 0, layer(256))
+    b0 = mb.blocks[0]
+    rows = sum(b0.n_dst[d] for d in sch.rel_dst)
+    assert saved >= (sum(b0.n_src) + rows) * 256 * 4 and scratch > 0
+    for bad_h in (250, 8 * 12, 8 * 2):          # not a multiple of 8 heads / head width 12 or 2 floats
+        with pytest.raises(B.HgnnError) as e:
+            ctx.hgnn_layer_workspace_bytes(gr, 0, layer(bad_h))
+        assert e.value.status in (-1, -6)
+    gr.release()
+    # a graph whose transpose skips a type cannot serve the attention backward
+    gr2 = ctx.hgnn_build_semantic_csr(mb.blocks, g.edge_type, use_edge_id=True,
+                                      transpose_types=[[0, 1, 1, 1]] + [None] * (len(mb.blocks) - 1))
+    gr2.wait()
+    with pytest.raises(B.HgnnError):
+        ctx.hgnn_layer_workspace_bytes(gr2, 0, layer(256))
+    gr2.release()
+    ctx.close()
