@@ -220,7 +220,7 @@ def main():
             uniq = sum(len(np.unique(view["colidx"][view["rel_edge_off"][r]: view["rel_edge_off"][r + 1]])) *
                        lw.in_dim[sch.rel_src[r]] for r in range(sch.num_rels))
             zel = sum(blk.n_dst[sch.rel_dst[r]] * lw.in_dim[sch.rel_src[r]] for r in range(sch.num_rels))
-            nplanes = 2 if (cfg.dtype == "bf16" and lw.relu) else 1
+            nplanes = 1
             alg = uniq * es + 4 * E + 4 * (rows + 1) + zel * es * nplanes
             req = alg + (sum(lw.in_dim[sch.rel_src[r]] * int(view["rel_edge_off"][r + 1] - view["rel_edge_off"][r])
                              for r in range(sch.num_rels)) - uniq) * es
@@ -230,8 +230,7 @@ def main():
                         traffic=None, algorithmic_bytes=int(alg), requested_bytes=int(req),
                         avg_kernel_us=round(avg_ms * 1e3, 2), launches_timed=probe_n)
         if kname in ("gemm_fwd", "gemm_dw", "gemm_da"):
-            # 2*M*K*N over the live K-segments (relations with edges + root); the low-order plane the bf16
-            # forward multiplies as well is not counted: it is not part of the method
+            # 2*M*K*N over the live K-segments (relations with edges + root)
             flops = 0
             for t in range(sch.num_types):
                 k = sum(lw.in_dim[sch.rel_src[r]] for r in range(sch.num_rels) if sch.rel_dst[r] == t and live[r])

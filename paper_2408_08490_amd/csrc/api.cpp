@@ -54,7 +54,7 @@ struct Plan {
   int64_t total_dst = 0;
   size_t z_elems = 0, zroot_elems = 0, wt_elems = 0;
   size_t saved_bytes = 0, scratch_bytes = 0;
-  size_t off_wt = 0, off_gp = 0, off_dz = 0, off_partial = 0, off_acc32 = 0, off_zlo = 0;
+  size_t off_wt = 0, off_gp = 0, off_dz = 0, off_partial = 0, off_acc32 = 0;
 };
 
 static hgnn_status layer_dev(hgnn_ctx *ctx, hgnn_graph *g, int32_t layer, LayerDev &D);
@@ -127,7 +127,6 @@ static hgnn_status make_plan(hgnn_ctx *ctx, hgnn_graph *g, int32_t layer, const 
   pl.off_dz = o;      o += align_up(std::max<size_t>(zr, 1) * pl.es, 256);
   pl.off_partial = o; o += align_up(std::max<size_t>((size_t)L.max_chunks * std::max(pl.max_dim, 1), 1) * 4, 256);
   pl.off_acc32 = o;   o += align_up(std::max<size_t>((size_t)pl.total_dst * pl.H, 1) * 4, 256);
-  pl.off_zlo = o;     o += align_up(std::max<size_t>(z, 1) * pl.es, 256);
   pl.scratch_bytes = o;
   if (need_built) {
     hgnn_status st = layer_dev(ctx, g, layer, pl.dev);
@@ -771,9 +770,6 @@ static hgnn_status fwd_common(hgnn_ctx *ctx, void *stream, hgnn_graph *g, int32_
   HGNN_HIP(hipStreamWaitEvent(s, g->ready, 0));
   char *sc = (char *)scratch;
   void *wtb = sc + pl.off_wt;
-  // bf16 storage: the aggregate is kept as a pair (rounded value, remainder) so that the pre-activation,
-  // and with it the ReLU mask the backward pass uses, does not inherit the rounding of the aggregate
-  void *zlo = (ctx->dtype == HGNN_BF16 && p->relu) ? sc + pl.off_zlo : nullptr;
   int n = 0;
   SegTab tl;
   fwd_tiles(pl, tl);
@@ -792,12 +788,12 @@ static hgnn_status fwd_common(hgnn_ctx *ctx, void *stream, hgnn_graph *g, int32_
   if (!naive) {
     {
       Probe pb(ctx, s, HGNN_K_SPMM_FWD, layer);
-      if ((st = launch_spmm_fwd(s, ctx->dtype, pl.dev, pl.tt, pl.rt, pl.max_dim, x, saved, zlo, 0, pl.dev.rows)) != HGNN_OK) return st;
+      if ((st = launch_spmm_fwd(s, ctx->dtype, pl.dev, pl.tt, pl.rt, pl.max_dim, x, saved, 0, pl.dev.rows)) != HGNN_OK) return st;
     }
     if (pl.dev.rows > 0) ++n;
     {
       Probe pb(ctx, s, HGNN_K_GEMM_FWD, layer);
-      if ((st = launch_gemm_fwd(s, ctx->dtype, pl.dev, pl.tt, pl.rt, pl.pt, pl.wt, tl, live, pl.H, p->relu, x, saved, zlo, wtb, h, -1, nullptr)) != HGNN_OK) return st;
+      if ((st = launch_gemm_fwd(s, ctx->dtype, pl.dev, pl.tt, pl.rt, pl.pt, pl.wt, tl, live, pl.H, p->relu, x, saved, wtb, h, -1, nullptr)) != HGNN_OK) return st;
     }
     if (tl.tile_off[T] > 0) ++n;
   } else {
@@ -810,7 +806,7 @@ static hgnn_status fwd_common(hgnn_ctx *ctx, void *stream, hgnn_graph *g, int32_
     const int32_t *rro = g->slab.host + L.o_rel_row_off;
     for (int r = 0; r < R; ++r) {
       if (rro[r + 1] == rro[r]) continue;
-      if ((st = launch_spmm_fwd(s, ctx->dtype, pl.dev, pl.tt, pl.rt, pl.max_dim, x, saved, zlo, rro[r], rro[r + 1])) != HGNN_OK) return st;
+      if ((st = launch_spmm_fwd(s, ctx->dtype, pl.dev, pl.tt, pl.rt, pl.max_dim, x, saved, rro[r], rro[r + 1])) != HGNN_OK) return st;
       ++n;
       SegTab one;
       std::memset(&one, 0, sizeof(one));
@@ -818,7 +814,7 @@ static hgnn_status fwd_common(hgnn_ctx *ctx, void *stream, hgnn_graph *g, int32_
       const int d = ctx->rel_dst[r];
       for (int t = 0; t < T; ++t)
         one.tile_off[t + 1] = one.tile_off[t] + (t == d ? tl.tile_off[t + 1] - tl.tile_off[t] : 0);
-      if ((st = launch_gemm_fwd(s, ctx->dtype, pl.dev, pl.tt, pl.rt, pl.pt, pl.wt, one, live, pl.H, 0, x, saved, zlo, wtb, h, r, acc32)) != HGNN_OK) return st;
+      if ((st = launch_gemm_fwd(s, ctx->dtype, pl.dev, pl.tt, pl.rt, pl.pt, pl.wt, one, live, pl.H, 0, x, saved, wtb, h, r, acc32)) != HGNN_OK) return st;
       ++n;
     }
     for (int t = 0; t < T; ++t) {
@@ -829,7 +825,7 @@ static hgnn_status fwd_common(hgnn_ctx *ctx, void *stream, hgnn_graph *g, int32_
         one.num_segs = T;
         for (int u = 0; u < T; ++u)
           one.tile_off[u + 1] = one.tile_off[u] + (u == t ? tl.tile_off[u + 1] - tl.tile_off[u] : 0);
-        if ((st = launch_gemm_fwd(s, ctx->dtype, pl.dev, pl.tt, pl.rt, pl.pt, pl.wt, one, live, pl.H, 0, x, saved, zlo, wtb, h, R + t, acc32)) != HGNN_OK) return st;
+        if ((st = launch_gemm_fwd(s, ctx->dtype, pl.dev, pl.tt, pl.rt, pl.pt, pl.wt, one, live, pl.H, 0, x, saved, wtb, h, R + t, acc32)) != HGNN_OK) return st;
         ++n;
       }
       if ((st = launch_bias_act(s, ctx->dtype, pl.tt, pl.pt, pl.H, p->relu, t, acc32, h)) != HGNN_OK) return st;

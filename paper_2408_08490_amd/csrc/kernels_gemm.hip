@@ -26,7 +26,7 @@ struct LiveMask {
 template <typename T, bool FAST>
 __global__ void __launch_bounds__(kThreads, 2) gemm_fwd_kernel(TypeTab tt, RelTab rt, PtrTab pt, WtTab wt, SegTab tiles, LiveMask live,
                                                             int H, int relu, const T *__restrict__ x, const T *__restrict__ z,
-                                                            const T *__restrict__ zlo, const T *__restrict__ wtb,
+                                                            const T *__restrict__ wtb,
                                                             T *__restrict__ h, int only_seg,
                                                             float *__restrict__ acc32) {
   __shared__ GemmLds<T> sm;
@@ -42,8 +42,8 @@ __global__ void __launch_bounds__(kThreads, 2) gemm_fwd_kernel(TypeTab tt, RelTa
   const int M = tt.n_dst[d];
   f32x16 acc[2][2];
   zero_acc(acc);
-  // K-segments of this destination type: every relation ending in d (aggregate, and for bf16 storage its
-  // low-order remainder against the same weights), then the root term.  The first wavefront looks at a
+  // K-segments of this destination type: the aggregate of every relation ending in d, then the root term.
+  // The first wavefront looks at a
   // window of relations at once, one per lane, and packs the ones that take part with a ballot.
   for (int cursor = 0; cursor < R; cursor += kRelWindow) {
     if (threadIdx.x < 64) {
@@ -51,16 +51,14 @@ __global__ void __launch_bounds__(kThreads, 2) gemm_fwd_kernel(TypeTab tt, RelTa
       bool use = lane < kRelWindow && r < R;
       if (use) use = rt.dst[r] == d && (only_seg < 0 || only_seg == r) && ((live.w[r >> 5] >> (r & 31)) & 1u);  // no edge: all zero
       const unsigned long long m = __ballot(use);
-      const int mult = zlo ? 2 : 1;
       if (use) {
-        const int pos = __popcll(m & ((1ull << lane) - 1ull)) * mult;
+        const int pos = __popcll(m & ((1ull << lane) - 1ull));
         const int F = tt.in_dim[rt.src[r]];
         const T *B = wtb + (int64_t)wt.rel4[r] * 4;
         put_seg(sm.seg[pos], z + (int64_t)rt.z_off4[r] * 4, F, B, F, 0, F);
-        if (zlo) put_seg(sm.seg[pos + 1], zlo + (int64_t)rt.z_off4[r] * 4, F, B, F, 0, F);
       }
       if (lane == 0) {
-        int n = __popcll(m) * mult;
+        int n = __popcll(m);
         if (cursor + kRelWindow >= R && pt.w_root[d] && (only_seg < 0 || only_seg == R + d)) {
           const int F = tt.in_dim[d];
           put_seg(sm.seg[n++], x + tt.elem_off[d], F, wtb + (int64_t)wt.root4[d] * 4, F, 0, F);
@@ -94,7 +92,7 @@ __global__ void __launch_bounds__(kThreads, 2) gemm_fwd_kernel(TypeTab tt, RelTa
 
 hgnn_status launch_gemm_fwd(hipStream_t s, int dtype, const LayerDev &L, const TypeTab &tt, const RelTab &rt,
                             const PtrTab &pt, const WtTab &wt, const SegTab &tiles, const uint32_t *live_mask, int H,
-                            int relu, const void *x, const void *z, const void *zlo, const void *wt_buf, void *h,
+                            int relu, const void *x, const void *z, const void *wt_buf, void *h,
                             int only_seg, float *acc32) {
   const int n = tiles.tile_off[tt.num_types];
   if (n == 0) return HGNN_OK;
@@ -106,10 +104,10 @@ hgnn_status launch_gemm_fwd(hipStream_t s, int dtype, const LayerDev &L, const T
   // x_merged, whose row widths are multiples of 16 bytes: always the FAST form
   if (dtype == HGNN_BF16)
     HGNN_LAUNCH((gemm_fwd_kernel<bf16, true>), grid, dim3(kThreads), 0, s, tt, rt, pt, wt, tiles, live, H, relu,
-                       (const bf16 *)x, (const bf16 *)z, (const bf16 *)zlo, (const bf16 *)wt_buf, (bf16 *)h, only_seg, acc32);
+                       (const bf16 *)x, (const bf16 *)z, (const bf16 *)wt_buf, (bf16 *)h, only_seg, acc32);
   else
     HGNN_LAUNCH((gemm_fwd_kernel<float, true>), grid, dim3(kThreads), 0, s, tt, rt, pt, wt, tiles, live, H, relu,
-                       (const float *)x, (const float *)z, (const float *)nullptr, (const float *)wt_buf, (float *)h,
+                       (const float *)x, (const float *)z, (const float *)wt_buf, (float *)h,
                        only_seg, acc32);
   HGNN_HIP(hipGetLastError());
   return HGNN_OK;

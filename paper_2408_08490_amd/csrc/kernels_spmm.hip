@@ -23,8 +23,8 @@ __device__ __forceinline__ int wave_col(int c0, int c1, int rel) {
 
 template <typename T, int LPRL, int C>
 __global__ void __launch_bounds__(256) spmm_fwd_uniform_kernel(const int32_t *__restrict__ rowptr, const int32_t *__restrict__ colidx,
-                                                                const T *__restrict__ x, T *__restrict__ z, T *__restrict__ zlo,
-                                                                int F, int row_begin, int row_end) {
+                                                                const T *__restrict__ x, T *__restrict__ z, int F, int row_begin,
+                                                                int row_end) {
   using V = Vec16<T>;
   constexpr int LPR = 1 << LPRL, RPW = 64 / LPR;
   const int lane = threadIdx.x & 63;
@@ -78,26 +78,16 @@ __global__ void __launch_bounds__(256) spmm_fwd_uniform_kernel(const int32_t *__
     if (q >= nvec) continue;
 #pragma unroll
     for (int i = 0; i < V::N; ++i) acc[p][i] *= inv;
-    const uint4 hi = V::pack(acc[p]);
-    reinterpret_cast<uint4 *>(z + zoff)[q] = hi;
-    if (zlo) {  // what the storage type dropped, so that the projection can add it back
-      float back[V::N];
-#pragma unroll
-      for (int i = 0; i < V::N; ++i) back[i] = 0.f;
-      V::add(back, hi);
-#pragma unroll
-      for (int i = 0; i < V::N; ++i) back[i] = acc[p][i] - back[i];
-      reinterpret_cast<uint4 *>(zlo + zoff)[q] = V::pack(back);
-    }
+    reinterpret_cast<uint4 *>(z + zoff)[q] = V::pack(acc[p]);
   }
 }
 
 template <typename T, int LPRL, int C>
-static void launch_fwd_uniform(hipStream_t s, const LayerDev &L, const void *x, void *z, void *zlo, int F, int row_begin, int row_end) {
+static void launch_fwd_uniform(hipStream_t s, const LayerDev &L, const void *x, void *z, int F, int row_begin, int row_end) {
   constexpr int RPB = 4 * (64 >> LPRL);
   dim3 grid((row_end - row_begin + RPB - 1) / RPB);
   HGNN_LAUNCH((spmm_fwd_uniform_kernel<T, LPRL, C>), grid, dim3(256), 0, s, L.rowptr, L.colidx, (const T *)x, (T *)z,
-                     (T *)zlo, F, row_begin, row_end);
+                     F, row_begin, row_end);
 }
 
 // Returns false when the shape is outside what the uniform kernels cover (the generic kernels then run).
@@ -116,13 +106,13 @@ template <typename T, typename FN> static bool dispatch_width(int nvec, FN fn) {
   return true;
 }
 
-bool launch_spmm_fwd_uniform(hipStream_t s, int dtype, const LayerDev &L, int F, const void *x, void *z, void *zlo,
-                             int row_begin, int row_end) {
+bool launch_spmm_fwd_uniform(hipStream_t s, int dtype, const LayerDev &L, int F, const void *x, void *z, int row_begin,
+                             int row_end) {
   const int es = dtype == HGNN_BF16 ? 2 : 4;
   const int nvec = F * es / 16;
   if (dtype == HGNN_BF16)
-    return dispatch_width<bf16>(nvec, [&]<int LPRL, int C>() { launch_fwd_uniform<bf16, LPRL, C>(s, L, x, z, zlo, F, row_begin, row_end); });
-  return dispatch_width<float>(nvec, [&]<int LPRL, int C>() { launch_fwd_uniform<float, LPRL, C>(s, L, x, z, nullptr, F, row_begin, row_end); });
+    return dispatch_width<bf16>(nvec, [&]<int LPRL, int C>() { launch_fwd_uniform<bf16, LPRL, C>(s, L, x, z, F, row_begin, row_end); });
+  return dispatch_width<float>(nvec, [&]<int LPRL, int C>() { launch_fwd_uniform<float, LPRL, C>(s, L, x, z, F, row_begin, row_end); });
 }
 
 // ------------------------------------------------------------------------------------------
