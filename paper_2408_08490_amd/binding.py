@@ -118,9 +118,11 @@ def _ptr(t) -> Optional[int]:
     return None if t is None else t.data_ptr()
 
 
-def _stream_ptr():
+def _stream_ptr(device=None):
+    """HIP stream PyTorch currently uses on `device` (an explicit index keeps torch from probing the
+    environment on every call)."""
     import torch
-    return torch.cuda.current_stream().cuda_stream
+    return torch.cuda.current_stream(device).cuda_stream
 
 
 class Graph:
@@ -212,6 +214,7 @@ class Context:
         h = C.c_void_p()
         _check(lib.hgnn_create(C.byref(h), C.byref(sch), device, host_threads, concurrent_builds))
         self.handle, self.num_types, self.num_rels, self.dtype = h, num_types, R, dtype
+        self.device = device if device >= 0 else None
         self.rel_src, self.rel_dst = list(rel_src), list(rel_dst)
 
     def close(self):
@@ -235,7 +238,7 @@ class Context:
         nr = (C.c_int64 * T)(*[(0 if i is None else i.numel()) for i in ids])
         row_off = (C.c_int32 * (T + 1))()
         elem_off = (C.c_int64 * (T + 1))()
-        _check(lib.hgnn_merge_features(self.handle, _stream_ptr(), st, fd, idp, nr, _ptr(x_merged), row_off, elem_off))
+        _check(lib.hgnn_merge_features(self.handle, _stream_ptr(self.device), st, fd, idp, nr, _ptr(x_merged), row_off, elem_off))
         return np.array(row_off[:], dtype=np.int32), np.array(elem_off[:], dtype=np.int64)
 
     # ---- hgnn_build_semantic_csr ----
@@ -284,19 +287,19 @@ class Context:
         return a.value, b.value
 
     def hgnn_layer_fwd(self, graph, layer, lp, x_merged, h_out, saved, scratch):
-        _check(lib.hgnn_layer_fwd(self.handle, _stream_ptr(), graph.handle, layer, C.byref(lp.params), _ptr(x_merged),
+        _check(lib.hgnn_layer_fwd(self.handle, _stream_ptr(self.device), graph.handle, layer, C.byref(lp.params), _ptr(x_merged),
                                   _ptr(h_out), _ptr(saved), saved.numel() * saved.element_size(), _ptr(scratch),
                                   scratch.numel() * scratch.element_size()))
 
     def hgnn_layer_fwd_naive(self, graph, layer, lp, x_merged, h_out, saved, scratch) -> int:
         n = C.c_int32()
-        _check(lib.hgnn_layer_fwd_naive(self.handle, _stream_ptr(), graph.handle, layer, C.byref(lp.params),
+        _check(lib.hgnn_layer_fwd_naive(self.handle, _stream_ptr(self.device), graph.handle, layer, C.byref(lp.params),
                                         _ptr(x_merged), _ptr(h_out), _ptr(saved), saved.numel() * saved.element_size(),
                                         _ptr(scratch), scratch.numel() * scratch.element_size(), C.byref(n)))
         return n.value
 
     def hgnn_layer_bwd(self, graph, layer, lp, x_merged, h_out, saved, grad_h, grad_x_merged, scratch):
-        _check(lib.hgnn_layer_bwd(self.handle, _stream_ptr(), graph.handle, layer, C.byref(lp.params), _ptr(x_merged),
+        _check(lib.hgnn_layer_bwd(self.handle, _stream_ptr(self.device), graph.handle, layer, C.byref(lp.params), _ptr(x_merged),
                                   _ptr(h_out), _ptr(saved), _ptr(grad_h), _ptr(grad_x_merged), C.byref(lp.grads),
                                   _ptr(scratch), scratch.numel() * scratch.element_size()))
 
@@ -315,5 +318,5 @@ class Context:
 
     def hgnn_softmax_xent(self, logits, labels, loss, grad_logits):
         rows, classes = logits.shape
-        _check(lib.hgnn_softmax_xent(self.handle, _stream_ptr(), _ptr(logits), _ptr(labels), rows, classes,
+        _check(lib.hgnn_softmax_xent(self.handle, _stream_ptr(self.device), _ptr(logits), _ptr(labels), rows, classes,
                                      _ptr(loss), _ptr(grad_logits)))
