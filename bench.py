@@ -26,7 +26,7 @@ HBM_PEAK_GBS = 8000.0
 MFMA_BF16_PEAK_TFLOPS = 2500.0
 # HBM bytes per launch of the two probed kernels on the default workload, from the rocprofv3 --pmc runs
 # summarised under profiles/ (FETCH_SIZE + WRITE_SIZE, scaled by the copy-kernel calibration); None = not measured
-TRAFFIC_BYTES = {"gemm_fwd": 151.9e6, "spmm_fwd": 254.6e6}
+TRAFFIC_BYTES = {"gemm_fwd": 111.9e6, "spmm_fwd": 216.0e6}
 
 
 def main():
@@ -104,8 +104,10 @@ def main():
 
     from paper_2408_08490_amd.runner import Batch
 
+    ctx.hgnn_set_edge_types(g.edge_type)        # graph-resident, like the feature stores: registered once
+
     def start_build(slot):
-        return ctx.hgnn_build_semantic_csr(slot.mb.blocks, g.edge_type, use_edge_id=True,
+        return ctx.hgnn_build_semantic_csr(slot.mb.blocks, None, use_edge_id=True,
                                            transpose_types=model.transpose_types(len(slot.mb.blocks)))
 
     def batch_of(slot, graph):

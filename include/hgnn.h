@@ -104,7 +104,8 @@ typedef struct {
   int32_t index_is_i64;            /* 1: int64 entries, 0: int32 entries */
   const int32_t *edge_type;        /* host [num_edges] relation of each edge, or NULL, then: */
   const int64_t *edge_id;          /* host [num_edges] ids into global_edge_type (Algorithm 2's EdgeID) */
-  const int32_t *global_edge_type; /* host [num_global_edges] (Algorithm 2's EdgeType) */
+  const int32_t *global_edge_type; /* host [num_global_edges] (Algorithm 2's EdgeType); NULL with edge_id given =
+                                      the table registered with hgnn_set_edge_types */
   int64_t num_global_edges;
   const int64_t *n_src;            /* host [T] source-side rows per type (rows of this layer's x_merged) */
   const int64_t *n_dst;            /* host [T] destination rows per type; the destinations of type t are
@@ -113,6 +114,13 @@ typedef struct {
                                       entries (their input gradient will not be asked for; see
                                       hgnn_layer_params.input_grad, which must then be 0 for t as well) */
 } hgnn_coo_layer;
+
+/* Registers the graph's global edge-type table (Algorithm 2's EdgeType, one entry per edge of the whole graph):
+ * the context keeps a compact copy (one byte per edge), so that later hgnn_coo_layer entries may pass edge_id
+ * alone.  The look-up EdgeType[EdgeID] is a random access per sampled edge; the compact table keeps most of it
+ * in the host caches.  Host array, copied (may be freed afterwards); entries outside [0, num_rels) are an
+ * error.  Replaces an earlier table; must not be called while builds are in flight. */
+hgnn_status hgnn_set_edge_types(hgnn_ctx *ctx, const int32_t *global_edge_type, int64_t num_global_edges);
 
 /* Starts the build of all `num_layers` layers (execution order) on the context's host threads
  * and returns; the threads select edges by relation (Algorithm 2), sort them stably into one

@@ -73,6 +73,7 @@ def _load():
         "hgnn_merge_features": [vp, vp, C.POINTER(vp), C.POINTER(i32), C.POINTER(vp), C.POINTER(i64), vp,
                                 C.POINTER(i32), C.POINTER(i64)],
         "hgnn_build_semantic_csr": [vp, i32, C.POINTER(CooLayer), C.POINTER(vp)],
+        "hgnn_set_edge_types": [vp, vp, i64],
         "hgnn_graph_wait": [vp, vp],
         "hgnn_graph_host_view": [vp, vp, i32, C.POINTER(CsrView)],
         "hgnn_layer_workspace_bytes": [vp, vp, i32, C.POINTER(LayerParams), C.POINTER(C.c_size_t),
@@ -99,7 +100,8 @@ def _load():
 
 lib = _load()
 
-EXPORTS = ["hgnn_create", "hgnn_destroy", "hgnn_last_error", "hgnn_merge_features", "hgnn_build_semantic_csr",
+EXPORTS = ["hgnn_create", "hgnn_destroy", "hgnn_last_error", "hgnn_merge_features", "hgnn_set_edge_types",
+           "hgnn_build_semantic_csr",
            "hgnn_graph_wait", "hgnn_graph_host_view", "hgnn_graph_release", "hgnn_layer_workspace_bytes",
            "hgnn_layer_fwd", "hgnn_layer_bwd", "hgnn_layer_fwd_naive", "hgnn_layer_launch_count",
            "hgnn_softmax_xent", "hgnn_probe_select", "hgnn_probe_read"]
@@ -242,8 +244,13 @@ class Context:
         return np.array(row_off[:], dtype=np.int32), np.array(elem_off[:], dtype=np.int64)
 
     # ---- hgnn_build_semantic_csr ----
+    def hgnn_set_edge_types(self, global_edge_type):
+        t = np.ascontiguousarray(global_edge_type, dtype=np.int32)
+        _check(lib.hgnn_set_edge_types(self.handle, t.ctypes.data, t.shape[0]))
+
     def hgnn_build_semantic_csr(self, blocks, global_edge_type=None, use_edge_id=False, transpose_types=None) -> Graph:
         """blocks: objects with n_src, n_dst, edge_index (2 x E, int64 or int32), edge_type / edge_id.
+        use_edge_id with global_edge_type None: the table registered with hgnn_set_edge_types is used.
         transpose_types: per layer, None or a 0/1 list per vertex type (hgnn_coo_layer.transpose_types)."""
         n = len(blocks)
         arr = (CooLayer * n)()
@@ -259,12 +266,14 @@ class Context:
             arr[i].index_is_i64 = 1 if ei.dtype == np.int64 else 0
             if use_edge_id:
                 eid = np.ascontiguousarray(b.edge_id, dtype=np.int64)
-                get = np.ascontiguousarray(global_edge_type, dtype=np.int32)
-                keep += [eid, get]
+                keep.append(eid)
                 arr[i].edge_type = None
                 arr[i].edge_id = eid.ctypes.data
-                arr[i].global_edge_type = get.ctypes.data
-                arr[i].num_global_edges = get.shape[0]
+                if global_edge_type is not None:
+                    get = np.ascontiguousarray(global_edge_type, dtype=np.int32)
+                    keep.append(get)
+                    arr[i].global_edge_type = get.ctypes.data
+                    arr[i].num_global_edges = get.shape[0]
             else:
                 et = np.ascontiguousarray(b.edge_type, dtype=np.int32)
                 keep.append(et)

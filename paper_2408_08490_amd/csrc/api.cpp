@@ -598,7 +598,11 @@ hgnn_status hgnn_build_semantic_csr(hgnn_ctx *ctx, int32_t num_layers, const hgn
     LayerHost &L = g->L[l];
     auto bad = [&](hgnn_status st) { delete g; return st; };
     if (in.num_edges < 0 || !in.n_src || !in.n_dst) { set_error("layer %d: bad edge count or NULL n_src/n_dst", l); return bad(HGNN_EINVAL); }
-    if (in.num_edges > 0 && (!in.edge_index || (!in.edge_type && (!in.edge_id || !in.global_edge_type)))) {
+    if (in.num_edges > 0 && !in.edge_type && in.edge_id && !in.global_edge_type && ctx->edge_types8.empty()) {
+      set_error("layer %d: edge_id without a global edge-type table (none given, none registered)", l);
+      return bad(HGNN_EINVAL);
+    }
+    if (in.num_edges > 0 && (!in.edge_index || (!in.edge_type && !in.edge_id))) {
       set_error("layer %d: NULL edge arrays", l);
       return bad(HGNN_EINVAL);
     }
@@ -695,6 +699,18 @@ hgnn_status hgnn_build_semantic_csr(hgnn_ctx *ctx, int32_t num_layers, const hgn
   }
   ctx->qcv.notify_one();
   *out = g;
+  return HGNN_OK;
+}
+
+hgnn_status hgnn_set_edge_types(hgnn_ctx *ctx, const int32_t *global_edge_type, int64_t num_global_edges) {
+  if (!ctx || num_global_edges < 0 || (num_global_edges > 0 && !global_edge_type)) HGNN_FAIL(HGNN_EINVAL, "NULL argument");
+  std::vector<uint8_t> t((size_t)num_global_edges);
+  for (int64_t i = 0; i < num_global_edges; ++i) {
+    const int32_t r = global_edge_type[i];
+    if (r < 0 || r >= ctx->R) HGNN_FAIL(HGNN_EINVAL, "global_edge_type[%lld]=%d outside [0,%d)", (long long)i, r, ctx->R);
+    t[(size_t)i] = (uint8_t)r;
+  }
+  ctx->edge_types8.swap(t);
   return HGNN_OK;
 }
 

@@ -185,6 +185,7 @@ struct hgnn_ctx {
   std::mutex pm;  // slab / event pool
   std::vector<hgnn::Slab> free_slabs;
   std::vector<hipEvent_t> free_events;
+  std::vector<uint8_t> edge_types8;  // compact copy of the registered global edge-type table
   // kernel probe (measurement aid)
   int probe_sel[4][2];  // selected (kernel, layer) pairs
   int probe_n = 0;

@@ -163,10 +163,24 @@ static bool build_layer(hgnn_ctx *ctx, Builder &bd, hgnn_graph *g, int l, BuildE
     const int64_t *ei64 = in.index_is_i64 ? (const int64_t *)in.edge_index : nullptr;
     const int32_t *ei32 = in.index_is_i64 ? nullptr : (const int32_t *)in.edge_index;
     int32_t *cnt = cnt1 + (size_t)p * S1;
+    const uint8_t *types8 = ctx->edge_types8.data();
+    const int64_t n_types8 = (int64_t)ctx->edge_types8.size();
     for (int64_t e = a; e < b; ++e) {
       int64_t r;
       if (in.edge_type) {
         r = in.edge_type[e];
+      } else if (!in.global_edge_type) {   // the registered compact table
+        if (e + 48 < b) {
+          const int64_t nid = in.edge_id[e + 48];
+          if (nid >= 0 && nid < n_types8) __builtin_prefetch(types8 + nid);
+        }
+        const int64_t id = in.edge_id[e];
+        if (id < 0 || id >= n_types8) {
+          err.set(HGNN_EINVAL, "layer " + std::to_string(l) + ": edge_id[" + std::to_string(e) + "]=" +
+                                   std::to_string(id) + " outside the registered edge-type table");
+          return;
+        }
+        r = types8[id];
       } else {
         if (e + 48 < b) {
           const int64_t nid = in.edge_id[e + 48];

@@ -39,13 +39,17 @@ def _host_ctx(B, sch, dtype="f32", threads=4, concurrent_builds=0):
 
 
 @pytest.mark.parametrize("index,scale,threads", [(0, 1.0, 1), (0, 1.0, 4), (2, 0.02, 8), (3, 0.003, 3)])
-@pytest.mark.parametrize("use_edge_id", [False, True])
+@pytest.mark.parametrize("use_edge_id", [False, True, "registered"])
 def test_host_build_bit_exact(B, index, scale, threads, use_edge_id):
     cfg = make_config(index, scale=scale, batch=96)
     g = build_graph(cfg)
     mb = sample_minibatch(cfg, g)
     ctx = _host_ctx(B, g.schema, threads=threads)
-    gr = ctx.hgnn_build_semantic_csr(mb.blocks, g.edge_type, use_edge_id=use_edge_id)
+    if use_edge_id == "registered":                 # edge ids alone, types from the table the context keeps
+        ctx.hgnn_set_edge_types(g.edge_type)
+        gr = ctx.hgnn_build_semantic_csr(mb.blocks, None, use_edge_id=True)
+    else:
+        gr = ctx.hgnn_build_semantic_csr(mb.blocks, g.edge_type, use_edge_id=use_edge_id)
     gr.wait()
     for l, b in enumerate(mb.blocks):
         sel = O.edge_index_select(b.edge_index, g.schema.num_rels, edge_type=b.edge_type)
@@ -54,6 +58,30 @@ def test_host_build_bit_exact(B, index, scale, threads, use_edge_id):
         assert v["rows"] == ref["rowptr"].size - 1 and v["edges"] == ref["colidx"].size
         for k in ("rel_row_off", "rel_edge_off", "rowptr", "colidx", "perm", "cptr", "crow", "cperm"):
             assert np.array_equal(v[k], ref[k]), (l, k)
+    gr.release()
+    ctx.close()
+
+
+def test_registered_edge_types_errors(B):
+    cfg = make_config(0)
+    g = build_graph(cfg)
+    mb = sample_minibatch(cfg, g)
+    ctx = _host_ctx(B, g.schema)
+    with pytest.raises(B.HgnnError, match="none registered"):       # edge ids alone need a table
+        ctx.hgnn_build_semantic_csr(mb.blocks, None, use_edge_id=True)
+    bad = g.edge_type.copy()
+    bad[3] = g.schema.num_rels
+    with pytest.raises(B.HgnnError, match="outside"):
+        ctx.hgnn_set_edge_types(bad)
+    short = g.edge_type[: int(mb.blocks[0].edge_id.max())]         # at least one sampled id is past its end
+    ctx.hgnn_set_edge_types(short)
+    gr = ctx.hgnn_build_semantic_csr(mb.blocks, None, use_edge_id=True)
+    with pytest.raises(B.HgnnError, match="registered edge-type table"):
+        gr.wait()
+    gr.release()
+    ctx.hgnn_set_edge_types(g.edge_type)                            # a later registration replaces the table
+    gr = ctx.hgnn_build_semantic_csr(mb.blocks, None, use_edge_id=True)
+    gr.wait()
     gr.release()
     ctx.close()
 
