@@ -337,6 +337,40 @@ __device__ __forceinline__ int xcd_tile(int bid, int nblocks) {
 }
 static inline int round_up8(int n) { return (n + 7) & ~7; }
 
+// The same idea for tiles of unequal cost: group g holds tiles [tile_off[g], tile_off[g+1]) of cost[g] each;
+// every XCD gets a contiguous range of about one eighth of the total cost.  Block b works on tile
+// first[b & 7] + (b >> 3) when that lies below first[(b & 7) + 1], else on nothing.
+struct XcdMap {
+  int32_t first[9];
+};
+__device__ __forceinline__ int xcd_tile(const XcdMap &m, int bid) {
+  const int x = bid & 7, t = m.first[x] + (bid >> 3);
+  return t < m.first[x + 1] ? t : -1;
+}
+// Returns the number of blocks to launch.
+static inline int balance_xcd(const int32_t *tile_off, const int64_t *cost, int ngroups, XcdMap &m) {
+  int64_t total = 0;
+  for (int g = 0; g < ngroups; ++g) total += (int64_t)(tile_off[g + 1] - tile_off[g]) * cost[g];
+  const int ntiles = tile_off[ngroups];
+  m.first[0] = 0;
+  int g = 0, longest = 0;
+  int64_t before = 0;  // cost of the tiles before group g
+  for (int x = 1; x <= 8; ++x) {
+    int t = ntiles;
+    if (x < 8) {
+      const int64_t target = (total * x + 7) / 8;  // first tile whose preceding cost reaches the target
+      while (g < ngroups && before + (int64_t)(tile_off[g + 1] - tile_off[g]) * cost[g] < target)
+        before += (int64_t)(tile_off[g + 1] - tile_off[g]) * cost[g++];
+      t = g < ngroups ? tile_off[g] + (int)((target - before + cost[g] - 1) / cost[g]) : ntiles;
+      if (t < m.first[x - 1]) t = m.first[x - 1];
+      if (t > ntiles) t = ntiles;
+    }
+    m.first[x] = t;
+    if (t - m.first[x - 1] > longest) longest = t - m.first[x - 1];
+  }
+  return longest * 8;
+}
+
 template <typename T>
 __device__ __forceinline__ void put_seg(Seg<T> &g, const T *A, int lda, const T *B, int ldb, int kb, int ke) {
   g.A = A; g.B = B; g.lda = lda; g.ldb = ldb; g.kb = kb; g.ke = ke;

@@ -24,7 +24,7 @@ struct LiveMask {
 };
 
 template <typename T, bool FAST>
-__global__ void __launch_bounds__(kThreads, 2) gemm_fwd_kernel(TypeTab tt, RelTab rt, PtrTab pt, WtTab wt, SegTab tiles, LiveMask live,
+__global__ void __launch_bounds__(kThreads, 2) gemm_fwd_kernel(TypeTab tt, RelTab rt, PtrTab pt, WtTab wt, SegTab tiles, XcdMap xmap, LiveMask live,
                                                             int H, int relu, const T *__restrict__ x, const T *__restrict__ z,
                                                             const T *__restrict__ wtb,
                                                             T *__restrict__ h, int only_seg,
@@ -32,8 +32,8 @@ __global__ void __launch_bounds__(kThreads, 2) gemm_fwd_kernel(TypeTab tt, RelTa
   __shared__ GemmLds<T> sm;
   __shared__ int s_nseg;
   const int T_ = tt.num_types, R = rt.num_rels;
-  const int tile = xcd_tile(blockIdx.x, gridDim.x);
-  if (tile >= tiles.tile_off[T_]) return;
+  const int tile = xcd_tile(xmap, blockIdx.x);
+  if (tile < 0) return;
   int d = 0;
   while (tile >= tiles.tile_off[d + 1]) ++d;
   const int tiles_n = (H + BN - 1) / BN;
@@ -99,14 +99,27 @@ hgnn_status launch_gemm_fwd(hipStream_t s, int dtype, const LayerDev &L, const T
   (void)L;
   LiveMask live;
   for (int i = 0; i < kMaxR / 32; ++i) live.w[i] = live_mask[i];
-  dim3 grid(round_up8(n));
+  // A tile's cost: its K-steps (destination types differ in the number of relations that end in them) plus
+  // the fixed part (segment table, pipeline fill, epilogue), which is worth about four K-steps.
+  int64_t cost[kMaxT];
+  const int bk = dtype == HGNN_BF16 ? Mma<bf16>::BK : Mma<float>::BK;
+  for (int d = 0; d < tt.num_types; ++d) {
+    int64_t steps = 0;
+    for (int r = 0; r < rt.num_rels; ++r)
+      if (rt.dst[r] == d && (only_seg < 0 || only_seg == r) && ((live.w[r >> 5] >> (r & 31)) & 1u))
+        steps += (tt.in_dim[rt.src[r]] + bk - 1) / bk;
+    if (pt.w_root[d] && (only_seg < 0 || only_seg == rt.num_rels + d)) steps += (tt.in_dim[d] + bk - 1) / bk;
+    cost[d] = steps + 4;
+  }
+  XcdMap xmap;
+  dim3 grid(balance_xcd(tiles.tile_off, cost, tt.num_types, xmap));
   // operands of the forward are the library's own aligned buffers (aggregates, transposed weights) and
   // x_merged, whose row widths are multiples of 16 bytes: always the FAST form
   if (dtype == HGNN_BF16)
-    HGNN_LAUNCH((gemm_fwd_kernel<bf16, true>), grid, dim3(kThreads), 0, s, tt, rt, pt, wt, tiles, live, H, relu,
+    HGNN_LAUNCH((gemm_fwd_kernel<bf16, true>), grid, dim3(kThreads), 0, s, tt, rt, pt, wt, tiles, xmap, live, H, relu,
                        (const bf16 *)x, (const bf16 *)z, (const bf16 *)wt_buf, (bf16 *)h, only_seg, acc32);
   else
-    HGNN_LAUNCH((gemm_fwd_kernel<float, true>), grid, dim3(kThreads), 0, s, tt, rt, pt, wt, tiles, live, H, relu,
+    HGNN_LAUNCH((gemm_fwd_kernel<float, true>), grid, dim3(kThreads), 0, s, tt, rt, pt, wt, tiles, xmap, live, H, relu,
                        (const float *)x, (const float *)z, (const float *)wt_buf, (float *)h,
                        only_seg, acc32);
   HGNN_HIP(hipGetLastError());
