@@ -219,7 +219,7 @@ hgnn_status launch_transpose_weights(hipStream_t s, int dtype, const TypeTab &tt
 hgnn_status launch_gemm_fwd(hipStream_t s, int dtype, const LayerDev &L, const TypeTab &tt, const RelTab &rt,
                             const PtrTab &pt, const WtTab &wt, const SegTab &tiles, const uint32_t *live_mask, int H,
                             int relu, const void *x, const void *z, const void *wt_buf, void *h,
-                            int only_seg, float *acc32);
+                            int only_seg, float *acc32, int tile_mn = 128);
 // attention variant
 hgnn_status launch_attn_proj(hipStream_t s, int dtype, const TypeTab &tt, const PtrTab &w_type_as_root, const SegTab &tiles, int H,
                              const void *x, void *z);

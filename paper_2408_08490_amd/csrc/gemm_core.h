@@ -12,19 +12,24 @@ typedef unsigned int u32x4 __attribute__((ext_vector_type(4)));
 typedef unsigned int u32x2 __attribute__((ext_vector_type(2)));
 typedef float f32x4 __attribute__((ext_vector_type(4)));
 
+// A block is 2x2 wavefronts; every wavefront owns MI x NI accumulators of 32x32, so the block tile is
+// (64 MI) x (64 NI).  BM x BN is the default tile (MI = NI = 2); launches that would not fill the chip with
+// those use 64x64 tiles (MI = NI = 1).
 constexpr int BM = 128, BN = 128, kThreads = 256;
 constexpr int kSegCap = 96;  // K-segments staged in LDS at a time
 constexpr int kRelWindow = 64;  // relations examined per pass of the forward kernel: one per lane of the first wavefront
 
 template <typename T> struct Mma;
 template <> struct Mma<bf16> {
-  static constexpr int BK = 64, KSTEP = 16, VEC = 8, PKC = BK + 8, PKS = 128 + 16;  // PKS: four k-rows of a transposing read on disjoint banks
+  static constexpr int BK = 64, KSTEP = 16, VEC = 8, PKC = BK + 8, KSPAD = 16;  // KS pitch = extent + KSPAD: four k-rows of a transposing read on disjoint banks
 };
 template <> struct Mma<float> {
-  static constexpr int BK = 32, KSTEP = 2, VEC = 4, PKC = BK + 4, PKS = 128 + 4;
+  static constexpr int BK = 32, KSTEP = 2, VEC = 4, PKC = BK + 4, KSPAD = 4;
 };
-template <typename T> constexpr int lds_elems() {
-  return (BM * Mma<T>::PKC > Mma<T>::BK * Mma<T>::PKS) ? BM * Mma<T>::PKC : Mma<T>::BK * Mma<T>::PKS;
+// elements of one LDS stage of an operand tile with `extent` output indices, in either orientation
+template <typename T> constexpr int lds_elems(int extent) {
+  return (extent * Mma<T>::PKC > Mma<T>::BK * (extent + Mma<T>::KSPAD)) ? extent * Mma<T>::PKC
+                                                                        : Mma<T>::BK * (extent + Mma<T>::KSPAD);
 }
 
 // One K-segment of a tile's reduction: sum over k in [kb, ke) of Aop[.][k] * Bop[.][k].
@@ -130,10 +135,9 @@ struct TileMover {
 };
 
 // MFMA operand fragments out of LDS.  `o` = output index handled by this lane's fragment block.
-template <bool KC> __device__ __forceinline__ bf16x8_t frag_bf16(const bf16 *s, int o, int ks, int lane) {
-  using M = Mma<bf16>;
+template <bool KC, int PITCH> __device__ __forceinline__ bf16x8_t frag_bf16(const bf16 *s, int o, int ks, int lane) {
   if constexpr (KC) {
-    return *reinterpret_cast<const bf16x8_t *>(s + (o + (lane & 31)) * M::PKC + ks * 16 + 8 * (lane >> 5));
+    return *reinterpret_cast<const bf16x8_t *>(s + (o + (lane & 31)) * PITCH + ks * 16 + 8 * (lane >> 5));
   } else {
     // The operand lies in LDS with the output index contiguous; the transposing LDS read hands every lane
     // four consecutive k of one output index.  Within a group of 16 lanes, lane p passes the address of four
@@ -142,68 +146,69 @@ template <bool KC> __device__ __forceinline__ bf16x8_t frag_bf16(const bf16 *s, 
     typedef short v4i16 __attribute__((ext_vector_type(4)));
     typedef __attribute__((address_space(3))) v4i16 *lds_v4;
     const int p = lane & 15;
-    const bf16 *q = s + (ks * 16 + 8 * (lane >> 5) + (p >> 2)) * M::PKS + o + 16 * ((lane >> 4) & 1) + 4 * (p & 3);
+    const bf16 *q = s + (ks * 16 + 8 * (lane >> 5) + (p >> 2)) * PITCH + o + 16 * ((lane >> 4) & 1) + 4 * (p & 3);
     union { bf16x8_t v; v4i16 h[2]; } u;
     u.h[0] = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_v4)q);
-    u.h[1] = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_v4)(q + 4 * M::PKS));
+    u.h[1] = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_v4)(q + 4 * PITCH));
     return u.v;
   }
 }
-template <bool KC> __device__ __forceinline__ float frag_f32(const float *s, int o, int ks, int lane) {
-  using M = Mma<float>;
-  if constexpr (KC) return s[(o + (lane & 31)) * M::PKC + ks * 2 + (lane >> 5)];
-  else return s[(ks * 2 + (lane >> 5)) * M::PKS + o + (lane & 31)];
+template <bool KC, int PITCH> __device__ __forceinline__ float frag_f32(const float *s, int o, int ks, int lane) {
+  if constexpr (KC) return s[(o + (lane & 31)) * PITCH + ks * 2 + (lane >> 5)];
+  else return s[(ks * 2 + (lane >> 5)) * PITCH + o + (lane & 31)];
 }
 
-template <typename T, bool AKC, bool BKC>
-__device__ __forceinline__ void mma_tile(f32x16 (&acc)[2][2], const T *As, const T *Bs, int wm, int wn, int lane) {
+template <typename T, bool AKC, bool BKC, int MI, int NI>
+__device__ __forceinline__ void mma_tile(f32x16 (&acc)[MI][NI], const T *As, const T *Bs, int wm, int wn, int lane) {
   using M = Mma<T>;
+  constexpr int PA = AKC ? M::PKC : 64 * MI + M::KSPAD, PB = BKC ? M::PKC : 64 * NI + M::KSPAD;
 #pragma unroll
   for (int ks = 0; ks < M::BK / M::KSTEP; ++ks) {
     if constexpr (sizeof(T) == 2) {
-      bf16x8_t a[2], b[2];
+      bf16x8_t a[MI], b[NI];
 #pragma unroll
-      for (int i = 0; i < 2; ++i) a[i] = frag_bf16<AKC>(reinterpret_cast<const bf16 *>(As), wm + i * 32, ks, lane);
+      for (int i = 0; i < MI; ++i) a[i] = frag_bf16<AKC, PA>(reinterpret_cast<const bf16 *>(As), wm + i * 32, ks, lane);
 #pragma unroll
-      for (int j = 0; j < 2; ++j) b[j] = frag_bf16<BKC>(reinterpret_cast<const bf16 *>(Bs), wn + j * 32, ks, lane);
+      for (int j = 0; j < NI; ++j) b[j] = frag_bf16<BKC, PB>(reinterpret_cast<const bf16 *>(Bs), wn + j * 32, ks, lane);
 #pragma unroll
-      for (int i = 0; i < 2; ++i)
+      for (int i = 0; i < MI; ++i)
 #pragma unroll
-        for (int j = 0; j < 2; ++j) acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a[i], b[j], acc[i][j], 0, 0, 0);
+        for (int j = 0; j < NI; ++j) acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a[i], b[j], acc[i][j], 0, 0, 0);
     } else {
-      float a[2], b[2];
+      float a[MI], b[NI];
 #pragma unroll
-      for (int i = 0; i < 2; ++i) a[i] = frag_f32<AKC>(reinterpret_cast<const float *>(As), wm + i * 32, ks, lane);
+      for (int i = 0; i < MI; ++i) a[i] = frag_f32<AKC, PA>(reinterpret_cast<const float *>(As), wm + i * 32, ks, lane);
 #pragma unroll
-      for (int j = 0; j < 2; ++j) b[j] = frag_f32<BKC>(reinterpret_cast<const float *>(Bs), wn + j * 32, ks, lane);
+      for (int j = 0; j < NI; ++j) b[j] = frag_f32<BKC, PB>(reinterpret_cast<const float *>(Bs), wn + j * 32, ks, lane);
 #pragma unroll
-      for (int i = 0; i < 2; ++i)
+      for (int i = 0; i < MI; ++i)
 #pragma unroll
-        for (int j = 0; j < 2; ++j) acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x2f32(a[i], b[j], acc[i][j], 0, 0, 0);
+        for (int j = 0; j < NI; ++j) acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x2f32(a[i], b[j], acc[i][j], 0, 0, 0);
     }
   }
 }
 
 // LDS of one block: two stages of (A tile, B tile) -- reused as the output staging tile by the epilogues --
 // and the K-segment table.
-template <typename T> struct GemmLds {
-  __attribute__((aligned(16))) T a[2][lds_elems<T>()];
-  __attribute__((aligned(16))) T b[2][lds_elems<T>()];
+template <typename T, int MI = 2, int NI = 2> struct GemmLds {
+  __attribute__((aligned(16))) T a[2][lds_elems<T>(64 * MI)];
+  __attribute__((aligned(16))) T b[2][lds_elems<T>(64 * NI)];
   Seg<T> seg[kSegCap];
-  float rowscale[BM];
+  float rowscale[64 * MI];
 };
 constexpr int kOutPitchPad = 8;  // floats: staged rows stay 16-byte aligned, rows r and r + 4 lie 32 banks apart
 
 // Runs the K-steps of sm.seg[0..nseg) (must be visible to the whole block) into `acc`.
 // KC operand: matrix [extent x K] row-major (ld); KS operand: matrix [K x extent] row-major (ld).
-template <typename T, bool FAST, bool AKC, bool BKC>
-__device__ __forceinline__ void gemm_run(f32x16 (&acc)[2][2], GemmLds<T> &sm, int nseg, int a_extent, int a0,
+template <typename T, bool FAST, bool AKC, bool BKC, int MI, int NI>
+__device__ __forceinline__ void gemm_run(f32x16 (&acc)[MI][NI], GemmLds<T, MI, NI> &sm, int nseg, int a_extent, int a0,
                                          int b_extent, int b0) {
   using M = Mma<T>;
+  constexpr int TM = 64 * MI, TN = 64 * NI;
   const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
-  const int wm = (wave >> 1) * 64, wn = (wave & 1) * 64;
-  using MoverA = TileMover<T, AKC ? BM : M::BK, AKC ? M::BK : BM, AKC ? M::PKC : M::PKS, AKC>;
-  using MoverB = TileMover<T, BKC ? BN : M::BK, BKC ? M::BK : BN, BKC ? M::PKC : M::PKS, BKC>;
+  const int wm = (wave >> 1) * 32 * MI, wn = (wave & 1) * 32 * NI;
+  using MoverA = TileMover<T, AKC ? TM : M::BK, AKC ? M::BK : TM, AKC ? M::PKC : TM + M::KSPAD, AKC>;
+  using MoverB = TileMover<T, BKC ? TN : M::BK, BKC ? M::BK : TN, BKC ? M::PKC : TN + M::KSPAD, BKC>;
   MoverA ta0, ta1;
   MoverB tb0, tb1;
   int total = 0;
@@ -252,11 +257,11 @@ __device__ __forceinline__ void gemm_run(f32x16 (&acc)[2][2], GemmLds<T> &sm, in
   __syncthreads();  // the segment table and the stages may be rewritten by the caller
 }
 
-__device__ __forceinline__ void zero_acc(f32x16 (&acc)[2][2]) {
+template <int MI, int NI> __device__ __forceinline__ void zero_acc(f32x16 (&acc)[MI][NI]) {
 #pragma unroll
-  for (int i = 0; i < 2; ++i)
+  for (int i = 0; i < MI; ++i)
 #pragma unroll
-    for (int j = 0; j < 2; ++j)
+    for (int j = 0; j < NI; ++j)
 #pragma unroll
       for (int v = 0; v < 16; ++v) acc[i][j][v] = 0.f;
 }
@@ -266,33 +271,35 @@ __device__ __forceinline__ void zero_acc(f32x16 (&acc)[2][2]) {
 #define HGNN_FOR_EACH_ACC(body)                                                     \
   {                                                                                 \
     const int lane_ = threadIdx.x & 63, wave_ = threadIdx.x >> 6;                   \
-    _Pragma("unroll") for (int i_ = 0; i_ < 2; ++i_) _Pragma("unroll") for (int j_ = 0; j_ < 2; ++j_) \
+    constexpr int MI_ = sizeof(acc) / sizeof(acc[0]), NI_ = sizeof(acc[0]) / sizeof(acc[0][0]); \
+    _Pragma("unroll") for (int i_ = 0; i_ < MI_; ++i_) _Pragma("unroll") for (int j_ = 0; j_ < NI_; ++j_) \
     _Pragma("unroll") for (int v_ = 0; v_ < 16; ++v_) {                             \
-      const int row = (wave_ >> 1) * 64 + i_ * 32 + 8 * (v_ >> 2) + 4 * (lane_ >> 5) + (v_ & 3); \
-      const int col = (wave_ & 1) * 64 + j_ * 32 + (lane_ & 31);                    \
+      const int row = (wave_ >> 1) * 32 * MI_ + i_ * 32 + 8 * (v_ >> 2) + 4 * (lane_ >> 5) + (v_ & 3); \
+      const int col = (wave_ & 1) * 32 * NI_ + j_ * 32 + (lane_ & 31);              \
       const float val = acc[i_][j_][v_];                                            \
       body                                                                          \
     }                                                                               \
   }
 
-// Writes the block's 128x128 tile `out[(row0 + r) * ld + col0 + c] = f(acc, r, c)` for r < rows, c < cols.
+// Writes the block's tile `out[(row0 + r) * ld + col0 + c] = f(acc, r, c)` for r < rows, c < cols.
 // When rows of `out` are 16-byte aligned the tile goes through LDS (the K loop's stages are free by then)
 // and leaves as whole 16-byte pieces; otherwise element by element.  `f(val, row, col)` returns the value.
 // The staged tile is fp32 whatever T is: 32-bit LDS writes with a pitch that puts the two half-waves
 // (rows r and r + 4 of one store) on disjoint banks; two lanes writing the halves of one dword would be
 // serialised.  Conversion to T happens on the way out.
-template <typename T, typename F>
-__device__ __forceinline__ void write_tile(f32x16 (&acc)[2][2], GemmLds<T> &sm, T *out, int64_t ld, int rows, int cols, F f) {
-  constexpr int V = 16 / sizeof(T), P = BN + kOutPitchPad;
-  static_assert(sizeof(sm.a) + sizeof(sm.b) >= sizeof(float) * P * BM, "fp32 output tile must fit the stages");
+template <typename T, typename F, int MI, int NI>
+__device__ __forceinline__ void write_tile(f32x16 (&acc)[MI][NI], GemmLds<T, MI, NI> &sm, T *out, int64_t ld, int rows, int cols, F f) {
+  constexpr int TM = 64 * MI, TN = 64 * NI;
+  constexpr int V = 16 / sizeof(T), P = TN + kOutPitchPad;
+  static_assert(sizeof(sm.a) + sizeof(sm.b) >= sizeof(float) * P * TM, "fp32 output tile must fit the stages");
   const bool vec = (ld % V) == 0 && (reinterpret_cast<uintptr_t>(out) & 15) == 0;
   if (vec) {
     float *stage = reinterpret_cast<float *>(&sm.a[0][0]);
     HGNN_FOR_EACH_ACC({ stage[row * P + col] = f(val, row, col); })
     __syncthreads();
-    constexpr int VPR = BN / V;
+    constexpr int VPR = TN / V;
 #pragma unroll
-    for (int i = 0; i < BM * VPR / kThreads; ++i) {
+    for (int i = 0; i < TM * VPR / kThreads; ++i) {
       const int v = threadIdx.x + i * kThreads;
       const int r = v / VPR, c = (v % VPR) * V;
       if (r < rows && c < cols) {

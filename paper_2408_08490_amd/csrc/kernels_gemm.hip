@@ -23,15 +23,16 @@ struct LiveMask {
   uint32_t w[kMaxR / 32];
 };
 
-template <typename T, bool FAST>
-__global__ void __launch_bounds__(kThreads, 2) gemm_fwd_kernel(TypeTab tt, RelTab rt, PtrTab pt, WtTab wt, SegTab tiles, XcdMap xmap, LiveMask live,
+template <typename T, bool FAST, int MI>
+__global__ void __launch_bounds__(kThreads, MI == 1 ? 4 : 2) gemm_fwd_kernel(TypeTab tt, RelTab rt, PtrTab pt, WtTab wt, SegTab tiles, XcdMap xmap, LiveMask live,
                                                             int H, int relu, const T *__restrict__ x, const T *__restrict__ z,
                                                             const T *__restrict__ wtb,
                                                             T *__restrict__ h, int only_seg,
                                                             float *__restrict__ acc32) {
-  __shared__ GemmLds<T> sm;
+  constexpr int BM = 64 * MI, BN = 64 * MI;
+  __shared__ GemmLds<T, MI, MI> sm;
   __shared__ int s_nseg;
-  const int T_ = tt.num_types, R = rt.num_rels;
+  const int R = rt.num_rels;
   const int tile = xcd_tile(xmap, blockIdx.x);
   if (tile < 0) return;
   int d = 0;
@@ -40,7 +41,7 @@ __global__ void __launch_bounds__(kThreads, 2) gemm_fwd_kernel(TypeTab tt, RelTa
   const int local = tile - tiles.tile_off[d];
   const int m0 = (local / tiles_n) * BM, n0 = (local % tiles_n) * BN;
   const int M = tt.n_dst[d];
-  f32x16 acc[2][2];
+  f32x16 acc[MI][MI];
   zero_acc(acc);
   // K-segments of this destination type: the aggregate of every relation ending in d, then the root term.
   // The first wavefront looks at a
@@ -77,13 +78,13 @@ __global__ void __launch_bounds__(kThreads, 2) gemm_fwd_kernel(TypeTab tt, RelTa
     return;
   }
   const T *bias = reinterpret_cast<const T *>(pt.bias[d]);
-  float bv[2];
+  float bv[MI];
+  const int wn0 = ((threadIdx.x >> 6) & 1) * 32 * MI;
 #pragma unroll
-  for (int j = 0; j < 2; ++j) {
-    const int c = n0 + ((threadIdx.x >> 6) & 1) * 64 + j * 32 + (threadIdx.x & 31);
+  for (int j = 0; j < MI; ++j) {
+    const int c = n0 + wn0 + j * 32 + (threadIdx.x & 31);
     bv[j] = (bias && c < H) ? to_float(bias[c]) : 0.f;
   }
-  const int wn0 = ((threadIdx.x >> 6) & 1) * 64;
   write_tile(acc, sm, h + (orow + m0) * H + n0, H, M - m0, H - n0, [&](float v, int, int col) {
     const float o = v + bv[(col - wn0) >> 5];
     return relu ? fmaxf(o, 0.f) : o;
@@ -93,7 +94,7 @@ __global__ void __launch_bounds__(kThreads, 2) gemm_fwd_kernel(TypeTab tt, RelTa
 hgnn_status launch_gemm_fwd(hipStream_t s, int dtype, const LayerDev &L, const TypeTab &tt, const RelTab &rt,
                             const PtrTab &pt, const WtTab &wt, const SegTab &tiles, const uint32_t *live_mask, int H,
                             int relu, const void *x, const void *z, const void *wt_buf, void *h,
-                            int only_seg, float *acc32) {
+                            int only_seg, float *acc32, int tile_mn) {
   const int n = tiles.tile_off[tt.num_types];
   if (n == 0) return HGNN_OK;
   (void)L;
@@ -115,13 +116,15 @@ hgnn_status launch_gemm_fwd(hipStream_t s, int dtype, const LayerDev &L, const T
   dim3 grid(balance_xcd(tiles.tile_off, cost, tt.num_types, xmap));
   // operands of the forward are the library's own aligned buffers (aggregates, transposed weights) and
   // x_merged, whose row widths are multiples of 16 bytes: always the FAST form
-  if (dtype == HGNN_BF16)
-    HGNN_LAUNCH((gemm_fwd_kernel<bf16, true>), grid, dim3(kThreads), 0, s, tt, rt, pt, wt, tiles, xmap, live, H, relu,
-                       (const bf16 *)x, (const bf16 *)z, (const bf16 *)wt_buf, (bf16 *)h, only_seg, acc32);
-  else
-    HGNN_LAUNCH((gemm_fwd_kernel<float, true>), grid, dim3(kThreads), 0, s, tt, rt, pt, wt, tiles, xmap, live, H, relu,
-                       (const float *)x, (const float *)z, (const float *)wt_buf, (float *)h,
-                       only_seg, acc32);
+#define HGNN_FWD(TY, MI_)                                                                                        \
+  HGNN_LAUNCH((gemm_fwd_kernel<TY, true, MI_>), grid, dim3(kThreads), 0, s, tt, rt, pt, wt, tiles, xmap, live, H, relu, \
+              (const TY *)x, (const TY *)z, (const TY *)wt_buf, (TY *)h, only_seg, acc32)
+  if (dtype == HGNN_BF16) {
+    if (tile_mn == 64) HGNN_FWD(bf16, 1); else HGNN_FWD(bf16, 2);
+  } else {
+    if (tile_mn == 64) HGNN_FWD(float, 1); else HGNN_FWD(float, 2);
+  }
+#undef HGNN_FWD
   HGNN_HIP(hipGetLastError());
   return HGNN_OK;
 }
@@ -139,10 +142,11 @@ __device__ __forceinline__ int find_seg(const SegTab &tiles, int tile) {
 // dZ_s = (G' W_s^T) / deg.  G' has leading dimension ldg (>= H; the columns H..ldg-1 are zero), and so have
 // the weights handed in through `pt` (the caller's own when H is a multiple of 16 bytes, zero-padded copies
 // otherwise), so that the reduction simply runs over ldg.
-template <typename T, bool FAST>
-__global__ void __launch_bounds__(kThreads, 2) gemm_da_kernel(LayerDev L, TypeTab tt, RelTab rt, PtrTab pt, SegTab tiles, int ldg,
+template <typename T, bool FAST, int MI>
+__global__ void __launch_bounds__(kThreads, MI == 1 ? 4 : 2) gemm_da_kernel(LayerDev L, TypeTab tt, RelTab rt, PtrTab pt, SegTab tiles, int ldg,
                                                            const T *__restrict__ gp, T *__restrict__ dz) {
-  __shared__ GemmLds<T> sm;
+  constexpr int BM = 64 * MI, BN = 64 * MI;
+  __shared__ GemmLds<T, MI, MI> sm;
   const int tile = xcd_tile(blockIdx.x, gridDim.x);
   const int R = rt.num_rels;
   if (tile >= tiles.tile_off[tiles.num_segs]) return;
@@ -155,7 +159,7 @@ __global__ void __launch_bounds__(kThreads, 2) gemm_da_kernel(LayerDev L, TypeTa
   const int tiles_n = (F + BN - 1) / BN;
   const int local = tile - tiles.tile_off[seg];
   const int m0 = (local / tiles_n) * BM, n0 = (local % tiles_n) * BN;
-  f32x16 acc[2][2];
+  f32x16 acc[MI][MI];
   zero_acc(acc);
   if (threadIdx.x == 0) put_seg(sm.seg[0], gp + (int64_t)tt.out_row_off[d] * ldg, ldg, W, ldg, 0, ldg);
   if (threadIdx.x < BM) {  // 1/|N_r(v)| of the tile's rows (1 for the root term)
@@ -180,27 +184,31 @@ hgnn_status launch_gemm_da(hipStream_t s, int dtype, const LayerDev &L, const Ty
   const int n = tiles.tile_off[tiles.num_segs];
   if (n == 0) return HGNN_OK;
   dim3 grid(round_up8(n)), blk(kThreads);
+#define HGNN_DA(TY, FA, MI_) \
+  HGNN_LAUNCH((gemm_da_kernel<TY, FA, MI_>), grid, blk, 0, s, L, tt, rt, pt, tiles, ldg, (const TY *)gp, (TY *)dz)
+#define HGNN_DA2(TY, FA) { HGNN_DA(TY, FA, 2); }
   if (dtype == HGNN_BF16) {
-    if (fast) HGNN_LAUNCH((gemm_da_kernel<bf16, true>), grid, blk, 0, s, L, tt, rt, pt, tiles, ldg, (const bf16 *)gp, (bf16 *)dz);
-    else HGNN_LAUNCH((gemm_da_kernel<bf16, false>), grid, blk, 0, s, L, tt, rt, pt, tiles, ldg, (const bf16 *)gp, (bf16 *)dz);
+    if (fast) HGNN_DA2(bf16, true) else HGNN_DA2(bf16, false)
   } else {
-    if (fast) HGNN_LAUNCH((gemm_da_kernel<float, true>), grid, blk, 0, s, L, tt, rt, pt, tiles, ldg, (const float *)gp, (float *)dz);
-    else HGNN_LAUNCH((gemm_da_kernel<float, false>), grid, blk, 0, s, L, tt, rt, pt, tiles, ldg, (const float *)gp, (float *)dz);
+    if (fast) HGNN_DA2(float, true) else HGNN_DA2(float, false)
   }
+#undef HGNN_DA2
+#undef HGNN_DA
   HGNN_HIP(hipGetLastError());
   return HGNN_OK;
 }
 
 // ------------------------------------------------------------------------------------------
 // dW_s += A_s^T G' over the destination-row slice [k_begin, k_end) of this block.
-template <typename T, bool FAST>
-__global__ void __launch_bounds__(kThreads, 2) gemm_dw_kernel(TypeTab tt, RelTab rt, GradPtrTab gt, DwTab tiles, int split_rows, int H,
+template <typename T, bool FAST, int MI>
+__global__ void __launch_bounds__(kThreads, MI == 1 ? 4 : 2) gemm_dw_kernel(TypeTab tt, RelTab rt, GradPtrTab gt, DwTab tiles, XcdMap xmap, int split_rows, int H,
                                                            int ldg, const T *__restrict__ x, const T *__restrict__ z,
                                                            const T *__restrict__ gp) {
-  __shared__ GemmLds<T> sm;
-  const int tile = xcd_tile(blockIdx.x, gridDim.x);
-  const int R = rt.num_rels, T_ = tt.num_types;
-  if (tile >= tiles.tile_off[T_]) return;
+  constexpr int BM = 64 * MI, BN = 64 * MI;
+  __shared__ GemmLds<T, MI, MI> sm;
+  const int tile = xcd_tile(xmap, blockIdx.x);
+  const int R = rt.num_rels;
+  if (tile < 0) return;
   int d = 0;
   while (tile >= tiles.tile_off[d + 1]) ++d;
   // inside the type: row slice, then block of dW rows over the type's segments, then column block
@@ -220,7 +228,7 @@ __global__ void __launch_bounds__(kThreads, 2) gemm_dw_kernel(TypeTab tt, RelTab
   const int M = tt.n_dst[d];
   const int f0 = tf * BM, h0 = th * BN;
   const int k_begin = sp * split_rows, k_end = min(M, k_begin + split_rows);
-  f32x16 acc[2][2];
+  f32x16 acc[MI][MI];
   zero_acc(acc);
   if (threadIdx.x == 0)
     put_seg(sm.seg[0], is_rel ? z + (int64_t)rt.z_off4[seg] * 4 : x + tt.elem_off[d], F,
@@ -238,14 +246,26 @@ hgnn_status launch_gemm_dw(hipStream_t s, int dtype, const LayerDev &L, const Ty
   const int n = tiles.tile_off[tt.num_types];
   if (n == 0) return HGNN_OK;
   (void)L;
-  dim3 grid(round_up8(n)), blk(kThreads);
-  if (dtype == HGNN_BF16) {
-    if (fast) HGNN_LAUNCH((gemm_dw_kernel<bf16, true>), grid, blk, 0, s, tt, rt, gt, tiles, split_rows, H, ldg, (const bf16 *)x, (const bf16 *)z, (const bf16 *)gp);
-    else HGNN_LAUNCH((gemm_dw_kernel<bf16, false>), grid, blk, 0, s, tt, rt, gt, tiles, split_rows, H, ldg, (const bf16 *)x, (const bf16 *)z, (const bf16 *)gp);
-  } else {
-    if (fast) HGNN_LAUNCH((gemm_dw_kernel<float, true>), grid, blk, 0, s, tt, rt, gt, tiles, split_rows, H, ldg, (const float *)x, (const float *)z, (const float *)gp);
-    else HGNN_LAUNCH((gemm_dw_kernel<float, false>), grid, blk, 0, s, tt, rt, gt, tiles, split_rows, H, ldg, (const float *)x, (const float *)z, (const float *)gp);
+  // a tile's cost: the K-steps of its row slice (the average over the type's slices) plus the fixed part
+  int64_t cost[kMaxT];
+  const int bk = dtype == HGNN_BF16 ? Mma<bf16>::BK : Mma<float>::BK;
+  for (int d = 0; d < tt.num_types; ++d) {
+    const int64_t slices = (tt.n_dst[d] + split_rows - 1) / split_rows;
+    cost[d] = 4 + (slices > 0 ? (tt.n_dst[d] / slices + bk - 1) / bk : 0);
   }
+  XcdMap xmap;
+  dim3 grid(balance_xcd(tiles.tile_off, cost, tt.num_types, xmap)), blk(kThreads);
+#define HGNN_DW(TY, FA, MI_)                                                                                  \
+  HGNN_LAUNCH((gemm_dw_kernel<TY, FA, MI_>), grid, blk, 0, s, tt, rt, gt, tiles, xmap, split_rows, H, ldg, (const TY *)x, \
+              (const TY *)z, (const TY *)gp)
+#define HGNN_DW2(TY, FA) { HGNN_DW(TY, FA, 2); }
+  if (dtype == HGNN_BF16) {
+    if (fast) HGNN_DW2(bf16, true) else HGNN_DW2(bf16, false)
+  } else {
+    if (fast) HGNN_DW2(float, true) else HGNN_DW2(float, false)
+  }
+#undef HGNN_DW2
+#undef HGNN_DW
   HGNN_HIP(hipGetLastError());
   return HGNN_OK;
 }

@@ -37,6 +37,17 @@ def test_config3_many_types_fp32_scaled():
     _assert_ok(run_case(3, scale=0.02, batch=128, verbose=True, check_naive=True))
 
 
+def test_config5_relation_heavy_small_fp32():
+    """104 relations over 7 vertex types on a graph of a few thousand vertices: more relations than the forward
+    GEMM examines in one pass, most of them with a handful of edges or none."""
+    _assert_ok(run_case(5, verbose=True, check_naive=True))
+
+
+def test_config6_relation_heavy_large_bf16():
+    """108 relations, ~1.9 M vertices, ~5.5 M edges, bf16."""
+    _assert_ok(run_case(6, verbose=True))
+
+
 def test_config2_full_size_headline_workload():
     """The workload bench.py times (full graph, 4096 targets, bf16, hidden 512, input gradients only for the
     learnable embeddings), compared element by element with the oracle."""

@@ -27,7 +27,8 @@ import numpy as np
 
 MASTER_SEED = 240808490
 CONFIG_NAMES = ["tiny_rgcn_f32", "academic_rgcn_f32", "academic_rgcn_bf16",
-                "many_types_rgcn_f32", "academic_rgat_bf16"]
+                "many_types_rgcn_f32", "academic_rgat_bf16",
+                "relation_heavy_small_f32", "relation_heavy_large_bf16"]
 
 
 # --------------------------------------------------------------------------- #
@@ -163,8 +164,16 @@ def make_config(index: int, scale: float = 1.0, batch: Optional[int] = None) -> 
     elif index == 4:
         c = Config(4, CONFIG_NAMES[4], "bf16", "rgat", [256, 256, 256], [True, True, False], True,
                    [15, 10, 5], 2048, "dot", heads=8)
+    elif index == 5:
+        # the regime of the smallest graph of the paper's Table 2: a few thousand vertices, ~100 relations
+        c = Config(5, CONFIG_NAMES[5], "f32", "rgcn", [64, 32], [True, False], True,
+                   [10, 10], 128, "dot")
+    elif index == 6:
+        # the regime of its largest graph: ~1.9 M vertices, ~5.7 M edges, 7 vertex types, 108 relations
+        c = Config(6, CONFIG_NAMES[6], "bf16", "rgcn", [128, 64], [True, False], True,
+                   [10, 10], 1024, "dot")
     else:
-        raise ValueError("config index must be 0..4")
+        raise ValueError("config index must be 0..6")
     c.scale = scale
     if batch is not None:
         c.batch = batch
@@ -278,14 +287,36 @@ def build_graph(cfg: Config) -> HeteroGraph:
                  for s, d in zip(rel_src, rel_dst)]
         stores = [_normal_store(f, n, d) for n, d in zip(num_nodes, feat_dim)]
         return _finish_graph(schema, num_nodes, feat_dim, pairs, stores)
+    if cfg.index in (5, 6):
+        # Shapes only: 7 vertex types of very unequal size, 52 / 54 forward relations between random type pairs
+        # plus their reverses, edge counts spread over three orders of magnitude (many relations are tiny).
+        T = 7
+        n_fwd, total_nodes, total_edges, width = ((52, 7_300, 24_000, 64) if cfg.index == 5
+                                                  else (54, 1_900_000, 2_850_000, 128))
+        share = g.dirichlet(np.full(T, 0.6))
+        num_nodes = [max(8, int(round(total_nodes * sc * x))) for x in share]
+        feat_dim = [width] * T
+        e_share = np.exp(g.normal(0.0, 1.8, n_fwd))
+        e_share /= e_share.sum()
+        rel_src, rel_dst, pairs = [], [], []
+        for i in range(n_fwd):
+            sT, dT = int(g.integers(0, T)), int(g.integers(0, T))
+            src, dst = _zipf_pairs(g, num_nodes[sT], num_nodes[dT], max(4, int(round(total_edges * sc * e_share[i]))))
+            rel_src += [sT, dT]; rel_dst += [dT, sT]
+            pairs += [(src, dst), (dst, src)]
+        schema = Schema(T, rel_src, rel_dst)
+        stores = [_normal_store(f, n, d, scale=0.1) for n, d in zip(num_nodes, feat_dim)]
+        return _finish_graph(schema, num_nodes, feat_dim, pairs, stores)
     raise ValueError(cfg.index)
 
 
 def default_target_type(cfg: Config, graph: HeteroGraph) -> int:
     if cfg.index == 0:
         return 1
-    if cfg.index == 3:
+    if cfg.index in (3, 5, 6):
         inc = np.bincount(graph.schema.rel_dst, minlength=graph.schema.num_types)
+        if cfg.index != 3:                             # a type too small to draw the batch from is no target
+            inc = np.where(np.asarray(graph.num_nodes) >= cfg.batch, inc, -1)
         return int(np.argmax(inc))                     # ties -> lowest id
     return 0
 
