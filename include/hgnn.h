@@ -158,6 +158,63 @@ hgnn_status hgnn_graph_host_view(hgnn_ctx *ctx, hgnn_graph *g, int32_t layer, hg
  * simply finished. */
 void hgnn_graph_release(hgnn_ctx *ctx, hgnn_graph *g);
 
+/* ---- Sampling in the loop (Section 2.3 step 1; Fig. 6: one CPU thread samples the mini-batch
+ * and selects its edge indices, the side stream uploads, the compute stream trains) -----------
+ * The whole graph, as host arrays that the caller keeps alive and unchanged until
+ * hgnn_sampler_destroy.  In-neighbour lists per relation: the sources of destination vertex v of
+ * relation r are in_nbr[r][in_indptr[r][v] .. in_indptr[r][v+1]); position p of in_nbr[r] is the
+ * edge with global id edge_off[r] + p. */
+typedef struct hgnn_sampler hgnn_sampler;
+typedef struct {
+  const int64_t *num_nodes;        /* [T] vertices per type */
+  const int64_t *const *in_indptr; /* [R] -> [num_nodes[rel_dst_type[r]] + 1] */
+  const int32_t *const *in_nbr;    /* [R] -> [edge_off[r+1] - edge_off[r]] source vertex ids */
+  const int64_t *edge_off;         /* [R+1] */
+} hgnn_host_graph;
+/* Also registers the graph's edge-type table with the context (as hgnn_set_edge_types would). */
+hgnn_status hgnn_sampler_create(hgnn_ctx *ctx, const hgnn_host_graph *graph, hgnn_sampler **out);
+void hgnn_sampler_destroy(hgnn_ctx *ctx, hgnn_sampler *s);
+/* Enqueues ONE task for the context's host threads: layer-wise neighbour sampling of the
+ * mini-batch of `targets` (distinct vertices of type target_type; copied), then the build of
+ * hgnn_build_semantic_csr on the sampled edges (edge ids, types through the registered table),
+ * then the upload, which also carries the global ids of the first layer's source rows.
+ * fanouts[h-1] = neighbours kept per destination vertex and relation in hop h, hop 1 nearest the
+ * targets; the block of hop h feeds layer num_layers - h + 1.  transpose_types: NULL, or per
+ * layer NULL or [T] as in hgnn_coo_layer.
+ * The sample is a pure function of (graph, targets, fanouts, seed):
+ *  - a hop's destination vertices are the previous hop's source vertices (hop 1: the targets);
+ *    a hop's source list of a type starts with its destination list and grows by each vertex
+ *    reached for the first time, in the order reached;
+ *  - relations are visited in ascending id, their destination vertices in list order;
+ *    destination v (global id) with deg in-neighbours keeps all of them in stored order when
+ *    deg <= fanout, else the positions that Floyd's subset algorithm picks: for c = 0..fanout-1,
+ *    j = deg - fanout + c, t = mix64(key + c) mod (j+1), position = j if t was picked before
+ *    else t, where key = mix64(mix64(mix64(mix64(seed) ^ hop) ^ r) ^ v) and mix64 is the
+ *    SplitMix64 output function; every kept position gives one edge, appended in that order. */
+hgnn_status hgnn_sample_and_build(hgnn_ctx *ctx, const hgnn_sampler *s, int32_t target_type,
+                                  const int64_t *targets, int64_t num_targets, int32_t num_layers,
+                                  const int32_t *fanouts, uint64_t seed,
+                                  const int32_t *const *transpose_types, hgnn_graph **out);
+/* The sampled mini-batch of a graph made by hgnn_sample_and_build (HGNN_EINVAL for any other).
+ * hgnn_graph_ids blocks until the sampling (not the build) has finished: per type the number of
+ * first-layer source rows, their global ids on the host and -- valid for device work ordered
+ * after hgnn_graph_wait_stream -- on the device (NULL on a host-only context); each output array
+ * has T entries and may be NULL.  hgnn_graph_minibatch_view blocks like hgnn_graph_host_view:
+ * the layer's row counts and its COO edges as the build consumed them. */
+hgnn_status hgnn_graph_ids(hgnn_ctx *ctx, hgnn_graph *g, int64_t *n_rows, const int64_t **host_ids,
+                           const int64_t **device_ids);
+typedef struct {
+  int64_t n_src[HGNN_MAX_TYPES], n_dst[HGNN_MAX_TYPES];
+  int64_t num_edges;
+  const int64_t *edge_index; /* [2 x num_edges]: local source, local destination */
+  const int64_t *edge_id;    /* [num_edges] */
+} hgnn_minibatch_view;
+hgnn_status hgnn_graph_minibatch_view(hgnn_ctx *ctx, hgnn_graph *g, int32_t layer, hgnn_minibatch_view *view);
+/* Makes `stream` wait (on the device; the host does not block once the upload is enqueued) for
+ * the graph's upload, so that work enqueued afterwards may read the graph's device arrays --
+ * hgnn_layer_fwd/bwd do this themselves; hgnn_merge_features on hgnn_graph_ids' device ids needs it. */
+hgnn_status hgnn_graph_wait_stream(hgnn_ctx *ctx, hgnn_graph *g, void *stream);
+
 /* ---- Stages 2-4: projection, aggregation, fusion (Section 2.2; Algorithm 1) ---------------
  * Layer parameters.  All arrays are HOST arrays of DEVICE pointers (dtype elements). */
 typedef struct {

@@ -47,6 +47,19 @@ class CsrView(C.Structure):
                 ("rel_row_off", "rel_edge_off", "rowptr", "colidx", "perm", "cptr", "crow", "cperm")]
 
 
+class HostGraph(C.Structure):
+    _fields_ = [("num_nodes", C.POINTER(C.c_int64)), ("in_indptr", C.POINTER(C.c_void_p)),
+                ("in_nbr", C.POINTER(C.c_void_p)), ("edge_off", C.POINTER(C.c_int64))]
+
+
+MAX_TYPES = 32
+
+
+class MinibatchView(C.Structure):
+    _fields_ = [("n_src", C.c_int64 * MAX_TYPES), ("n_dst", C.c_int64 * MAX_TYPES), ("num_edges", C.c_int64),
+                ("edge_index", C.POINTER(C.c_int64)), ("edge_id", C.POINTER(C.c_int64))]
+
+
 class LayerParams(C.Structure):
     _fields_ = [("in_dim", C.POINTER(C.c_int32)), ("out_dim", C.c_int32), ("relu", C.c_int32),
                 ("w_rel", C.POINTER(C.c_void_p)), ("w_root", C.POINTER(C.c_void_p)),
@@ -75,6 +88,11 @@ def _load():
         "hgnn_build_semantic_csr": [vp, i32, C.POINTER(CooLayer), C.POINTER(vp)],
         "hgnn_set_edge_types": [vp, vp, i64],
         "hgnn_graph_wait": [vp, vp],
+        "hgnn_sampler_create": [vp, C.POINTER(HostGraph), C.POINTER(vp)],
+        "hgnn_sample_and_build": [vp, vp, i32, vp, i64, i32, C.POINTER(i32), C.c_uint64, C.POINTER(vp), C.POINTER(vp)],
+        "hgnn_graph_ids": [vp, vp, C.POINTER(i64), C.POINTER(vp), C.POINTER(vp)],
+        "hgnn_graph_minibatch_view": [vp, vp, i32, C.POINTER(MinibatchView)],
+        "hgnn_graph_wait_stream": [vp, vp, vp],
         "hgnn_graph_host_view": [vp, vp, i32, C.POINTER(CsrView)],
         "hgnn_layer_workspace_bytes": [vp, vp, i32, C.POINTER(LayerParams), C.POINTER(C.c_size_t),
                                        C.POINTER(C.c_size_t)],
@@ -94,6 +112,7 @@ def _load():
         f.restype = C.c_int
     lib.hgnn_destroy.argtypes = [vp]; lib.hgnn_destroy.restype = None
     lib.hgnn_graph_release.argtypes = [vp, vp]; lib.hgnn_graph_release.restype = None
+    lib.hgnn_sampler_destroy.argtypes = [vp, vp]; lib.hgnn_sampler_destroy.restype = None
     lib.hgnn_last_error.argtypes = []; lib.hgnn_last_error.restype = C.c_char_p
     return lib
 
@@ -101,7 +120,8 @@ def _load():
 lib = _load()
 
 EXPORTS = ["hgnn_create", "hgnn_destroy", "hgnn_last_error", "hgnn_merge_features", "hgnn_set_edge_types",
-           "hgnn_build_semantic_csr",
+           "hgnn_build_semantic_csr", "hgnn_sampler_create", "hgnn_sampler_destroy", "hgnn_sample_and_build",
+           "hgnn_graph_ids", "hgnn_graph_minibatch_view", "hgnn_graph_wait_stream",
            "hgnn_graph_wait", "hgnn_graph_host_view", "hgnn_graph_release", "hgnn_layer_workspace_bytes",
            "hgnn_layer_fwd", "hgnn_layer_bwd", "hgnn_layer_fwd_naive", "hgnn_layer_launch_count",
            "hgnn_softmax_xent", "hgnn_probe_select", "hgnn_probe_read"]
@@ -147,6 +167,29 @@ class Graph:
             out[k] = np.ctypeslib.as_array(getattr(v, k), shape=(n,)).copy() if n > 0 else np.zeros(0, np.int32)
         return out
 
+    # ---- graphs made by hgnn_sample_and_build ----
+    def ids(self, device=False):
+        """(n_rows per type, host id arrays per type[, device pointers per type]) of the first layer's source rows;
+        blocks until the sampling has finished (with device=True: until the build has)."""
+        T = self.ctx.num_types
+        n = (C.c_int64 * T)()
+        hp, dp = (C.c_void_p * T)(), (C.c_void_p * T)()
+        _check(lib.hgnn_graph_ids(self.ctx.handle, self.handle, n, hp, dp if device else None))
+        host = [np.ctypeslib.as_array(C.cast(hp[t], C.POINTER(C.c_int64)), shape=(n[t],)).copy() if n[t] else
+                np.zeros(0, np.int64) for t in range(T)]
+        return (list(n), host, [dp[t] or 0 for t in range(T)]) if device else (list(n), host)
+
+    def minibatch_view(self, layer):
+        v = MinibatchView()
+        _check(lib.hgnn_graph_minibatch_view(self.ctx.handle, self.handle, layer, C.byref(v)))
+        T, E = self.ctx.num_types, v.num_edges
+        ei = np.ctypeslib.as_array(v.edge_index, shape=(2, E)).copy() if E else np.zeros((2, 0), np.int64)
+        eid = np.ctypeslib.as_array(v.edge_id, shape=(E,)).copy() if E else np.zeros(0, np.int64)
+        return dict(n_src=list(v.n_src[:T]), n_dst=list(v.n_dst[:T]), edge_index=ei, edge_id=eid)
+
+    def wait_stream(self):
+        _check(lib.hgnn_graph_wait_stream(self.ctx.handle, self.handle, _stream_ptr(self.ctx.device)))
+
     def release(self):
         if self.handle is not None:
             lib.hgnn_graph_release(self.ctx.handle, self.handle)
@@ -157,6 +200,16 @@ class Graph:
             self.release()
         except Exception:
             pass
+
+
+class Sampler:
+    def __init__(self, ctx, handle, keep):
+        self.ctx, self.handle, self._keep = ctx, handle, keep
+
+    def close(self):
+        if self.handle is not None:
+            lib.hgnn_sampler_destroy(self.ctx.handle, self.handle)
+            self.handle = None
 
 
 class Layer:
@@ -242,6 +295,39 @@ class Context:
         elem_off = (C.c_int64 * (T + 1))()
         _check(lib.hgnn_merge_features(self.handle, _stream_ptr(self.device), st, fd, idp, nr, _ptr(x_merged), row_off, elem_off))
         return np.array(row_off[:], dtype=np.int32), np.array(elem_off[:], dtype=np.int64)
+
+    # ---- sampling in the loop ----
+    def hgnn_sampler_create(self, num_nodes, in_indptr, in_nbr, edge_off):
+        """Host arrays of the whole graph (kept alive by the returned object)."""
+        R, T = self.num_rels, self.num_types
+        nn = np.ascontiguousarray(num_nodes, dtype=np.int64)
+        eo = np.ascontiguousarray(edge_off, dtype=np.int64)
+        ptrs = [np.ascontiguousarray(p, dtype=np.int64) for p in in_indptr]
+        nbrs = [np.ascontiguousarray(p, dtype=np.int32) for p in in_nbr]
+        assert len(nn) == T and len(eo) == R + 1 and len(ptrs) == R and len(nbrs) == R
+        pa = (C.c_void_p * R)(*[p.ctypes.data for p in ptrs])
+        na = (C.c_void_p * R)(*[p.ctypes.data for p in nbrs])
+        hg = HostGraph(nn.ctypes.data_as(C.POINTER(C.c_int64)), pa, na, eo.ctypes.data_as(C.POINTER(C.c_int64)))
+        h = C.c_void_p()
+        _check(lib.hgnn_sampler_create(self.handle, C.byref(hg), C.byref(h)))
+        return Sampler(self, h, (nn, eo, ptrs, nbrs, pa, na))
+
+    def hgnn_sample_and_build(self, sampler, target_type, targets, fanouts, seed, transpose_types=None) -> Graph:
+        tg = np.ascontiguousarray(targets, dtype=np.int64)
+        L = len(fanouts)
+        fo = (C.c_int32 * L)(*[int(f) for f in fanouts])
+        keep, tp = [], None
+        if transpose_types is not None:
+            tp = (C.c_void_p * L)()
+            for l, tt in enumerate(transpose_types):
+                if tt is not None:
+                    a = np.ascontiguousarray(tt, dtype=np.int32)
+                    keep.append(a)
+                    tp[l] = a.ctypes.data
+        h = C.c_void_p()
+        _check(lib.hgnn_sample_and_build(self.handle, sampler.handle, int(target_type), tg.ctypes.data, tg.shape[0], L, fo,
+                                         C.c_uint64(int(seed) & (2 ** 64 - 1)), tp, C.byref(h)))
+        return Graph(self, h, None)
 
     # ---- hgnn_build_semantic_csr ----
     def hgnn_set_edge_types(self, global_edge_type):

@@ -590,14 +590,19 @@ hgnn_status hgnn_merge_features(hgnn_ctx *ctx, void *stream, const void *const *
   return HGNN_OK;
 }
 
-hgnn_status hgnn_build_semantic_csr(hgnn_ctx *ctx, int32_t num_layers, const hgnn_coo_layer *layers, hgnn_graph **out) {
-  if (!ctx || !layers || !out) HGNN_FAIL(HGNN_EINVAL, "NULL argument");
-  *out = nullptr;
-  if (num_layers < 1 || num_layers > kMaxLayers) HGNN_FAIL(HGNN_EINVAL, "num_layers %d outside [1,%d]", num_layers, kMaxLayers);
-  const int T = ctx->T, R = ctx->R;
-  hgnn_graph *g = new (std::nothrow) hgnn_graph();
-  if (!g) HGNN_FAIL(HGNN_ENOMEM, "out of host memory");
-  g->num_layers = num_layers;
+extern "C++" {
+namespace hgnn {
+// Validates the layers' inputs (g->L[l].in), lays the index arrays out in one block and takes a pinned/device
+// block and an event from the context's pool (or allocates them).  Runs on the caller's thread for
+// hgnn_build_semantic_csr and on a builder's thread for sampled mini-batches, hence the message by reference.
+hgnn_status plan_graph(hgnn_ctx *ctx, hgnn_graph *g, std::string &msg) {
+  const int T = ctx->T, R = ctx->R, num_layers = g->num_layers;
+  char buf[256];
+  auto fail = [&](hgnn_status st, const char *fmt, auto... a) {
+    std::snprintf(buf, sizeof(buf), fmt, a...);
+    msg = buf;
+    return st;
+  };
   size_t o = 0;
   auto take = [&](size_t n) {
     size_t at = o;
@@ -605,34 +610,26 @@ hgnn_status hgnn_build_semantic_csr(hgnn_ctx *ctx, int32_t num_layers, const hgn
     return at;
   };
   for (int l = 0; l < num_layers; ++l) {
-    const hgnn_coo_layer &in = layers[l];
     LayerHost &L = g->L[l];
-    auto bad = [&](hgnn_status st) { delete g; return st; };
-    if (in.num_edges < 0 || !in.n_src || !in.n_dst) { set_error("layer %d: bad edge count or NULL n_src/n_dst", l); return bad(HGNN_EINVAL); }
-    if (in.num_edges > 0 && !in.edge_type && in.edge_id && !in.global_edge_type && ctx->edge_types8.empty()) {
-      set_error("layer %d: edge_id without a global edge-type table (none given, none registered)", l);
-      return bad(HGNN_EINVAL);
-    }
-    if (in.num_edges > 0 && (!in.edge_index || (!in.edge_type && !in.edge_id))) {
-      set_error("layer %d: NULL edge arrays", l);
-      return bad(HGNN_EINVAL);
-    }
-    if (in.num_edges > INT32_MAX) { set_error("layer %d: more than 2^31-1 edges", l); return bad(HGNN_EOVERFLOW); }
-    L.in = in;
+    const hgnn_coo_layer &in = L.in;
+    if (in.num_edges < 0 || !in.n_src || !in.n_dst) return fail(HGNN_EINVAL, "layer %d: bad edge count or NULL n_src/n_dst", l);
+    if (in.num_edges > 0 && !in.edge_type && in.edge_id && !in.global_edge_type && ctx->edge_types8.empty())
+      return fail(HGNN_EINVAL, "layer %d: edge_id without a global edge-type table (none given, none registered)", l);
+    if (in.num_edges > 0 && (!in.edge_index || (!in.edge_type && !in.edge_id))) return fail(HGNN_EINVAL, "layer %d: NULL edge arrays", l);
+    if (in.num_edges > INT32_MAX) return fail(HGNN_EOVERFLOW, "layer %d: more than 2^31-1 edges", l);
     L.edges = in.num_edges;
     int64_t src_rows = 0, rows = 0;
     for (int t = 0; t < T; ++t) {
-      if (in.n_src[t] < 0 || in.n_dst[t] < 0 || in.n_dst[t] > in.n_src[t]) {
-        set_error("layer %d: type %d has n_dst=%lld, n_src=%lld (need 0 <= n_dst <= n_src)", l, t, (long long)in.n_dst[t], (long long)in.n_src[t]);
-        return bad(HGNN_EINVAL);
-      }
+      if (in.n_src[t] < 0 || in.n_dst[t] < 0 || in.n_dst[t] > in.n_src[t])
+        return fail(HGNN_EINVAL, "layer %d: type %d has n_dst=%lld, n_src=%lld (need 0 <= n_dst <= n_src)", l, t,
+                    (long long)in.n_dst[t], (long long)in.n_src[t]);
       L.n_src[t] = in.n_src[t];
       L.n_dst[t] = in.n_dst[t];
       if (in.transpose_types && !in.transpose_types[t]) L.tmask &= ~(1u << t);
       src_rows += in.n_src[t];
     }
     for (int r = 0; r < R; ++r) rows += in.n_dst[ctx->rel_dst[r]];
-    if (src_rows > INT32_MAX - 1 || rows > INT32_MAX - 1) { set_error("layer %d: more than 2^31-2 rows", l); return bad(HGNN_EOVERFLOW); }
+    if (src_rows > INT32_MAX - 1 || rows > INT32_MAX - 1) return fail(HGNN_EOVERFLOW, "layer %d: more than 2^31-2 rows", l);
     L.rows = rows;
     L.src_rows = src_rows;
     L.max_long = (int32_t)(L.edges / kLongRow + 1);
@@ -651,6 +648,8 @@ hgnn_status hgnn_build_semantic_csr(hgnn_ctx *ctx, int32_t num_layers, const hgn
   const bool cperm_on_device = ctx->agg == HGNN_AGG_ATTN;   // the attention backward walks edges by CSR position
   if (cperm_on_device)
     for (int l = 0; l < num_layers; ++l) g->L[l].o_cperm = take(g->L[l].edges);
+  if (g->job)  // a sampled mini-batch carries the global ids of its first layer's source rows (int64)
+    for (int t = 0; t < T; ++t) g->o_ids[t] = take(2 * g->job->ids[t].size());
   const size_t dev_used = o;  // arrays below stay on the host (views only)
   for (int l = 0; l < num_layers; ++l) {
     g->L[l].o_perm = take(g->L[l].edges);
@@ -684,32 +683,140 @@ hgnn_status hgnn_build_semantic_csr(hgnn_ctx *ctx, int32_t num_layers, const hgn
       if (e == hipSuccess) e = hipMalloc((void **)&g->slab.dev, cap * sizeof(int32_t));
       if (e != hipSuccess) {
         free_slab(ctx, g->slab);
-        delete g;
-        HGNN_FAIL(HGNN_ENOMEM, "graph buffers (%zu bytes): %s", cap * sizeof(int32_t), hipGetErrorString(e));
+        g->slab = Slab();
+        return fail(HGNN_ENOMEM, "graph buffers (%zu bytes): %s", cap * sizeof(int32_t), hipGetErrorString(e));
       }
     } else {
       g->slab.host = (int32_t *)malloc(cap * sizeof(int32_t));
-      if (!g->slab.host) {
-        delete g;
-        HGNN_FAIL(HGNN_ENOMEM, "out of host memory");
-      }
+      if (!g->slab.host) return fail(HGNN_ENOMEM, "out of host memory (%zu bytes)", cap * sizeof(int32_t));
     }
     g->slab.cap = cap;
   }
   if (ctx->device >= 0 && !g->ready) {
     hipError_t e = hipEventCreateWithFlags(&g->ready, hipEventDisableTiming);
-    if (e != hipSuccess) {
-      free_slab(ctx, g->slab);
-      delete g;
-      HGNN_FAIL(HGNN_EHIP, "hipEventCreate: %s", hipGetErrorString(e));
-    }
+    if (e != hipSuccess) return fail(HGNN_EHIP, "hipEventCreate: %s", hipGetErrorString(e));
   }
+  return HGNN_OK;
+}
+}  // namespace hgnn
+}  // extern "C++"
+
+// Hands a planned (or to-be-sampled) graph to the builders.
+static void enqueue_graph(hgnn_ctx *ctx, hgnn_graph *g) {
   {
     std::lock_guard<std::mutex> lk(ctx->qm);
     ctx->queue.push_back(g);
   }
   ctx->qcv.notify_one();
+}
+
+// Gives back whatever plan_graph took and deletes the graph (error paths before the graph reaches a builder).
+static void drop_graph(hgnn_ctx *ctx, hgnn_graph *g) {
+  {
+    std::lock_guard<std::mutex> lk(ctx->pm);
+    if (g->slab.host) ctx->free_slabs.push_back(g->slab);
+    if (g->ready) ctx->free_events.push_back(g->ready);
+  }
+  delete g;
+}
+
+hgnn_status hgnn_build_semantic_csr(hgnn_ctx *ctx, int32_t num_layers, const hgnn_coo_layer *layers, hgnn_graph **out) {
+  if (!ctx || !layers || !out) HGNN_FAIL(HGNN_EINVAL, "NULL argument");
+  *out = nullptr;
+  if (num_layers < 1 || num_layers > kMaxLayers) HGNN_FAIL(HGNN_EINVAL, "num_layers %d outside [1,%d]", num_layers, kMaxLayers);
+  hgnn_graph *g = new (std::nothrow) hgnn_graph();
+  if (!g) HGNN_FAIL(HGNN_ENOMEM, "out of host memory");
+  g->num_layers = num_layers;
+  for (int l = 0; l < num_layers; ++l) g->L[l].in = layers[l];
+  std::string msg;
+  const hgnn_status st = plan_graph(ctx, g, msg);
+  if (st != HGNN_OK) {
+    drop_graph(ctx, g);
+    HGNN_FAIL(st, "%s", msg.c_str());
+  }
+  enqueue_graph(ctx, g);
   *out = g;
+  return HGNN_OK;
+}
+
+hgnn_status hgnn_sample_and_build(hgnn_ctx *ctx, const hgnn_sampler *sm, int32_t target_type, const int64_t *targets,
+                                  int64_t num_targets, int32_t num_layers, const int32_t *fanouts, uint64_t seed,
+                                  const int32_t *const *transpose_types, hgnn_graph **out) {
+  if (!ctx || !sm || !fanouts || !out || num_targets < 0 || (num_targets > 0 && !targets)) HGNN_FAIL(HGNN_EINVAL, "NULL argument");
+  *out = nullptr;
+  if (num_layers < 1 || num_layers > kMaxLayers) HGNN_FAIL(HGNN_EINVAL, "num_layers %d outside [1,%d]", num_layers, kMaxLayers);
+  if (target_type < 0 || target_type >= ctx->T) HGNN_FAIL(HGNN_EINVAL, "target_type %d outside [0,%d)", target_type, ctx->T);
+  for (int h = 0; h < num_layers; ++h)
+    if (fanouts[h] < 1 || fanouts[h] > 64) HGNN_FAIL(HGNN_EINVAL, "fanouts[%d]=%d outside [1,64]", h, fanouts[h]);
+  for (int64_t i = 0; i < num_targets; ++i)
+    if (targets[i] < 0 || targets[i] >= sm->num_nodes[target_type])
+      HGNN_FAIL(HGNN_EINVAL, "targets[%lld]=%lld is not a vertex of type %d", (long long)i, (long long)targets[i], target_type);
+  hgnn_graph *g = new (std::nothrow) hgnn_graph();
+  if (!g) HGNN_FAIL(HGNN_ENOMEM, "out of host memory");
+  g->num_layers = num_layers;
+  g->job.reset(new SampleJob());
+  SampleJob &job = *g->job;
+  job.sampler = sm;
+  job.target_type = target_type;
+  job.seed = seed;
+  job.targets.assign(targets, targets + num_targets);
+  job.fanouts.assign(fanouts, fanouts + num_layers);
+  if (transpose_types)
+    for (int l = 0; l < num_layers; ++l)
+      if (transpose_types[l]) job.transpose[l].assign(transpose_types[l], transpose_types[l] + ctx->T);
+  enqueue_graph(ctx, g);
+  *out = g;
+  return HGNN_OK;
+}
+
+hgnn_status hgnn_graph_ids(hgnn_ctx *ctx, hgnn_graph *g, int64_t *n_rows, const int64_t **host_ids, const int64_t **device_ids) {
+  if (!ctx || !g) HGNN_FAIL(HGNN_EINVAL, "NULL argument");
+  if (!g->job) HGNN_FAIL(HGNN_EINVAL, "the graph was not made by hgnn_sample_and_build");
+  {
+    std::unique_lock<std::mutex> lk(g->m);
+    g->cv.wait(lk, [&] { return g->sampled || g->state != 0; });
+    if (!g->sampled) HGNN_FAIL((hgnn_status)g->status, "%s", g->err.c_str());
+  }
+  if (device_ids) {  // their place in the block is fixed by the plan that follows the sampling
+    std::unique_lock<std::mutex> lk(g->m);
+    g->cv.wait(lk, [&] { return g->state != 0; });
+    if (g->state != 1) HGNN_FAIL((hgnn_status)g->status, "%s", g->err.c_str());
+  }
+  for (int t = 0; t < ctx->T; ++t) {
+    const size_t n = g->job->ids[t].size();
+    if (n_rows) n_rows[t] = (int64_t)n;
+    if (host_ids) host_ids[t] = n ? g->job->ids[t].data() : nullptr;
+    if (device_ids) device_ids[t] = (n && g->slab.dev) ? reinterpret_cast<const int64_t *>(g->slab.dev + g->o_ids[t]) : nullptr;
+  }
+  return HGNN_OK;
+}
+
+hgnn_status hgnn_graph_minibatch_view(hgnn_ctx *ctx, hgnn_graph *g, int32_t layer, hgnn_minibatch_view *view) {
+  if (!ctx || !g || !view) HGNN_FAIL(HGNN_EINVAL, "NULL argument");
+  if (!g->job) HGNN_FAIL(HGNN_EINVAL, "the graph was not made by hgnn_sample_and_build");
+  if (layer < 0 || layer >= g->num_layers) HGNN_FAIL(HGNN_EINVAL, "layer %d outside [0,%d)", layer, g->num_layers);
+  const hgnn_status st = hgnn_graph_wait(ctx, g);
+  if (st != HGNN_OK) return st;
+  std::memset(view, 0, sizeof(*view));
+  for (int t = 0; t < ctx->T; ++t) {
+    view->n_src[t] = g->job->n_src[layer][t];
+    view->n_dst[t] = g->job->n_dst[layer][t];
+  }
+  view->num_edges = (int64_t)g->job->edge_id[layer].size();
+  view->edge_index = g->job->edge_index[layer].data();
+  view->edge_id = g->job->edge_id[layer].data();
+  return HGNN_OK;
+}
+
+hgnn_status hgnn_graph_wait_stream(hgnn_ctx *ctx, hgnn_graph *g, void *stream) {
+  if (!ctx || !g) HGNN_FAIL(HGNN_EINVAL, "NULL argument");
+  if (ctx->device < 0) HGNN_FAIL(HGNN_EUNSUPPORTED, "host-only context cannot run device work");
+  {
+    std::unique_lock<std::mutex> lk(g->m);
+    g->cv.wait(lk, [&] { return g->state != 0; });
+    if (g->state != 1) HGNN_FAIL((hgnn_status)g->status, "%s", g->err.c_str());
+  }
+  HGNN_HIP(hipStreamWaitEvent((hipStream_t)stream, g->ready, 0));
   return HGNN_OK;
 }
 

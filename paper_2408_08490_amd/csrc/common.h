@@ -9,6 +9,7 @@
 #include <cstdio>
 #include <deque>
 #include <functional>
+#include <memory>
 #include <mutex>
 #include <string>
 #include <thread>
@@ -154,9 +155,31 @@ struct Builder {
   std::thread th;
   std::vector<int32_t> key, col, rowid, hist, tkey;
   std::vector<std::vector<int32_t>> long_lists;
+  std::vector<int32_t> local_of[kMaxT];  // sampler: local row of a global vertex id (-1 = not in the hop), per type
+};
+
+// A mini-batch to be sampled on a builder's thread before its index arrays are built, and what the sampling
+// produced (the arrays hgnn_coo_layer points to).
+struct SampleJob {
+  const hgnn_sampler *sampler = nullptr;
+  int32_t target_type = 0;
+  uint64_t seed = 0;
+  std::vector<int64_t> targets;
+  std::vector<int32_t> fanouts;                 // per hop, nearest the targets first
+  std::vector<int32_t> transpose[kMaxLayers];   // per layer: empty (= all types) or [T]
+  std::vector<int64_t> edge_index[kMaxLayers];  // [2 x E]: local source, local destination
+  std::vector<int64_t> edge_id[kMaxLayers];
+  int64_t n_src[kMaxLayers][kMaxT], n_dst[kMaxLayers][kMaxT];
+  std::vector<int64_t> ids[kMaxT];              // global ids of the first layer's source rows
 };
 
 }  // namespace hgnn
+
+struct hgnn_sampler {
+  std::vector<int64_t> num_nodes, edge_off;
+  std::vector<const int64_t *> in_indptr;
+  std::vector<const int32_t *> in_nbr;
+};
 
 struct hgnn_graph {
   int32_t num_layers = 0;
@@ -169,6 +192,9 @@ struct hgnn_graph {
   int status = HGNN_OK;
   std::string err;
   hipEvent_t ready = nullptr;
+  std::unique_ptr<hgnn::SampleJob> job;  // set for hgnn_sample_and_build
+  bool sampled = false;                  // the job's results are complete (guarded by m)
+  size_t o_ids[hgnn::kMaxT] = {};        // per type: offset of the sampled ids in the block (int32 units)
 };
 
 struct hgnn_ctx {
@@ -197,6 +223,8 @@ struct hgnn_ctx {
 
 namespace hgnn {
 void build_graph_job(hgnn_ctx *ctx, Builder &b, hgnn_graph *g);  // host_build.cpp
+hgnn_status plan_graph(hgnn_ctx *ctx, hgnn_graph *g, std::string &msg);  // api.cpp
+hgnn_status run_sample_job(hgnn_ctx *ctx, Builder &b, hgnn_graph *g, std::string &msg);  // sampler.cpp
 
 // ---- kernel launchers (kernels_*.hip); all enqueue on `s` and return ----
 hgnn_status launch_merge(hipStream_t s, int dtype, int T, const void *const *store, const int32_t *feat_dim,

@@ -365,6 +365,26 @@ static bool build_layer(hgnn_ctx *ctx, Builder &bd, hgnn_graph *g, int l, BuildE
 void build_graph_job(hgnn_ctx *ctx, Builder &bd, hgnn_graph *g) {
   BuildError err;
   bool ok = true;
+  if (g->job) {  // sample first; only then are the sizes known that the block is laid out for
+    std::string m;
+    hgnn_status st = run_sample_job(ctx, bd, g, m);
+    if (st == HGNN_OK) {
+      {
+        std::lock_guard<std::mutex> lk(g->m);
+        g->sampled = true;
+      }
+      g->cv.notify_all();
+      st = plan_graph(ctx, g, m);
+    }
+    if (st != HGNN_OK) {
+      err.set(st, m);
+      ok = false;
+    } else {
+      for (int t = 0; t < ctx->T; ++t)
+        if (!g->job->ids[t].empty())
+          std::memcpy(g->slab.host + g->o_ids[t], g->job->ids[t].data(), g->job->ids[t].size() * sizeof(int64_t));
+    }
+  }
   for (int l = 0; l < g->num_layers && ok; ++l) ok = build_layer(ctx, bd, g, l, err);
   int status = ok ? HGNN_OK : err.status;
   std::string msg = err.msg;

@@ -275,3 +275,78 @@ def test_attention_plan_validation_without_gpu(B):
         ctx.hgnn_layer_workspace_bytes(gr2, 0, layer(256))
     gr2.release()
     ctx.close()
+
+
+# ---- sampling in the loop: the library's sampler against the sampler oracle, bit for bit ----
+def _sampler(B, ctx, g):
+    return ctx.hgnn_sampler_create(g.num_nodes, g.in_indptr, g.in_nbr, g.edge_off)
+
+
+@pytest.mark.parametrize("index,scale,fanouts,nt,threads,conc", [(0, 1.0, [5], 64, 1, 0), (0, 1.0, [3, 2, 2], 40, 4, 2),
+                                                                 (2, 0.02, [6, 4], 300, 4, 4), (5, 1.0, [4, 4], 60, 2, 0),
+                                                                 (3, 0.003, [5, 5], 50, 3, 0)])
+def test_sampler_matches_oracle_and_feeds_the_build(B, index, scale, fanouts, nt, threads, conc):
+    from oracle import sampler_oracle as SO
+    from workloads.synth import default_target_type
+    cfg = make_config(index, scale=scale, batch=nt)
+    g = build_graph(cfg)
+    sch = g.schema
+    tt = default_target_type(cfg, g)
+    ctx = _host_ctx(B, sch, threads=threads, concurrent_builds=conc)
+    sm = _sampler(B, ctx, g)
+    rng = np.random.default_rng(11)
+    graphs, wants = [], []
+    for k in range(3):                                              # several in flight on the same builders
+        targets = rng.choice(g.num_nodes[tt], nt, replace=False)
+        graphs.append(ctx.hgnn_sample_and_build(sm, tt, targets, fanouts, seed=1000 + k))
+        wants.append(SO.sample_minibatch(g.num_nodes, sch.rel_src, sch.rel_dst, g.in_indptr, g.in_nbr, g.edge_off, tt,
+                                         targets, fanouts, 1000 + k))
+    for gr, want in zip(graphs, wants):
+        n_rows, ids = gr.ids()
+        assert n_rows == [len(x) for x in want["ids"]]
+        for t in range(sch.num_types):
+            assert np.array_equal(ids[t], want["ids"][t]), t
+        for l, wb in enumerate(want["blocks"]):
+            v = gr.minibatch_view(l)
+            assert v["n_src"] == wb["n_src"] and v["n_dst"] == wb["n_dst"]
+            assert np.array_equal(v["edge_index"], wb["edge_index"]) and np.array_equal(v["edge_id"], wb["edge_id"])
+            sel = O.edge_index_select(wb["edge_index"], sch.num_rels, edge_id=wb["edge_id"], global_edge_type=g.edge_type)
+            ref = O.semantic_csr(sel, sch.rel_src, sch.rel_dst, wb["n_src"], wb["n_dst"])
+            hv = gr.host_view(l)
+            for key in ("rel_row_off", "rel_edge_off", "rowptr", "colidx", "perm", "cptr", "crow", "cperm"):
+                assert np.array_equal(hv[key], ref[key]), (l, key)
+        gr.release()
+    sm.close()
+    ctx.close()
+
+
+def test_sampler_errors(B):
+    cfg = make_config(0)
+    g = build_graph(cfg)
+    ctx = _host_ctx(B, g.schema)
+    sm = _sampler(B, ctx, g)
+    with pytest.raises(B.HgnnError, match="not a vertex"):
+        ctx.hgnn_sample_and_build(sm, 1, [0, g.num_nodes[1]], [5], 1)
+    with pytest.raises(B.HgnnError, match="fanouts"):
+        ctx.hgnn_sample_and_build(sm, 1, [0, 1], [0], 1)
+    with pytest.raises(B.HgnnError, match="target_type"):
+        ctx.hgnn_sample_and_build(sm, 7, [0, 1], [5], 1)
+    gr = ctx.hgnn_sample_and_build(sm, 1, [3, 4, 3], [5], 1)       # a repeated target is found by the sampling task
+    with pytest.raises(B.HgnnError, match="listed twice"):
+        gr.ids()
+    with pytest.raises(B.HgnnError, match="listed twice"):
+        gr.wait()
+    gr.release()
+    gr = ctx.hgnn_sample_and_build(sm, 1, [3, 4, 5], [5], 1)       # the tables were put back: the next one works
+    assert gr.ids()[0][1] >= 3
+    gr.release()
+    plain = ctx.hgnn_build_semantic_csr(sample_minibatch(cfg, g).blocks, g.edge_type, use_edge_id=True)
+    with pytest.raises(B.HgnnError, match="not made by"):
+        plain.ids()
+    plain.release()
+    bad = [p.copy() for p in g.in_indptr]
+    bad[0][-1] += 1
+    with pytest.raises(B.HgnnError, match="does not span"):
+        ctx.hgnn_sampler_create(g.num_nodes, bad, g.in_nbr, g.edge_off)
+    sm.close()
+    ctx.close()
