@@ -179,13 +179,15 @@ class Graph:
                 np.zeros(0, np.int64) for t in range(T)]
         return (list(n), host, [dp[t] or 0 for t in range(T)]) if device else (list(n), host)
 
-    def minibatch_view(self, layer):
+    def minibatch_view(self, layer, arrays=True):
         v = MinibatchView()
         _check(lib.hgnn_graph_minibatch_view(self.ctx.handle, self.handle, layer, C.byref(v)))
         T, E = self.ctx.num_types, v.num_edges
-        ei = np.ctypeslib.as_array(v.edge_index, shape=(2, E)).copy() if E else np.zeros((2, 0), np.int64)
-        eid = np.ctypeslib.as_array(v.edge_id, shape=(E,)).copy() if E else np.zeros(0, np.int64)
-        return dict(n_src=list(v.n_src[:T]), n_dst=list(v.n_dst[:T]), edge_index=ei, edge_id=eid)
+        out = dict(n_src=list(v.n_src[:T]), n_dst=list(v.n_dst[:T]))
+        if arrays:
+            out["edge_index"] = np.ctypeslib.as_array(v.edge_index, shape=(2, E)).copy() if E else np.zeros((2, 0), np.int64)
+            out["edge_id"] = np.ctypeslib.as_array(v.edge_id, shape=(E,)).copy() if E else np.zeros(0, np.int64)
+        return out
 
     def wait_stream(self):
         _check(lib.hgnn_graph_wait_stream(self.ctx.handle, self.handle, _stream_ptr(self.ctx.device)))

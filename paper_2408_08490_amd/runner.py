@@ -31,6 +31,25 @@ class Batch:
         self.grad_out_dev = None
         self.blocks = None
         self.n_rows = None
+        self.sampled = False
+
+
+class _DevIds:
+    """Device id list that lives in a graph's buffers (what hgnn_merge_features needs of a tensor)."""
+
+    def __init__(self, ptr, n):
+        self._ptr, self._n = ptr, n
+
+    def data_ptr(self):
+        return self._ptr
+
+    def numel(self):
+        return self._n
+
+
+class _Sizes:
+    def __init__(self, n_src, n_dst):
+        self.n_src, self.n_dst = n_src, n_dst
 
 
 class Model:
@@ -120,9 +139,32 @@ class Model:
             b.grad_out_dev = to_device(np.concatenate([g.reshape(-1) for g in mb.grad_out]), self.dtype, self.dev)
         return b
 
+    def prepare_sampled(self, sampler, targets, fanouts, seed, labels=None, grad_out=None) -> Batch:
+        """The mini-batch is sampled by the library's host threads (then built and uploaded, all one task)."""
+        b = Batch()
+        b.sampled = True
+        b.graph = self.ctx.hgnn_sample_and_build(sampler, self.target_type, targets, fanouts, seed,
+                                                 self.transpose_types(len(fanouts)))
+        if labels is not None:
+            b.labels_dev = labels if torch.is_tensor(labels) else torch.from_numpy(np.asarray(labels, np.int64)).to(self.dev)
+        if grad_out is not None:
+            b.grad_out_dev = to_device(np.concatenate([g.reshape(-1) for g in grad_out]), self.dtype, self.dev)
+        return b
+
+    def _resolve_sampled(self, b: Batch):
+        """Sizes and device id lists of a sampled mini-batch (waits for its host task) and the stream dependency
+        of the merge on the upload."""
+        n_rows, _, dptr = b.graph.ids(device=True)
+        b.n_rows = n_rows
+        b.ids_dev = [_DevIds(p, n) for p, n in zip(dptr, n_rows)]
+        b.blocks = [_Sizes(**b.graph.minibatch_view(l, arrays=False)) for l in range(len(self.layers))]
+        b.graph.wait_stream()
+
     # ---- device side of a step ----
     def run(self, b: Batch, backward=True, naive=False, need_input_grad=True):
         ctx, L = self.ctx, len(self.layers)
+        if b.sampled and b.ids_dev is None:
+            self._resolve_sampled(b)
         n0 = sum(n * f for n, f in zip(b.n_rows, self.feat_dim))
         x = self._typed("x0", n0)
         row_off, elem_off = ctx.hgnn_merge_features(self.stores, b.ids_dev, x, self.feat_dim)

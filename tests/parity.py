@@ -110,22 +110,38 @@ def oracle_run(cfg, g, mb, ws, input_grad=None):
 
 
 def run_case(index, scale=1.0, batch=None, verbose=False, use_edge_id=True, check_naive=False, graph=None,
-             input_grad=None, backward=True, cfg_edit=None, grad_tol=None):
+             input_grad=None, backward=True, cfg_edit=None, grad_tol=None, sampled=None):
     """cfg_edit(cfg, g, mb, ws): optional hook that changes the prepared inputs (e.g. the storage type) before
     both sides run.  grad_tol: optional {substring of a gradient's name: tolerance or None}; a matching
-    gradient is held to that tolerance in both norms against the tie-broken oracle (None: reported only)."""
+    gradient is held to that tolerance in both norms against the tie-broken oracle (None: reported only).
+    sampled: optional dict(seed=..., fanouts=...): the mini-batch of the same targets is sampled by the library's
+    sampler on the HIP side and by the sampler oracle on the other."""
     import torch
     from paper_2408_08490_amd.runner import Model
     cfg, g, mb, ws = prepare_inputs(index, scale, batch, graph)
     if cfg_edit is not None:
         cfg_edit(cfg, g, mb, ws)
     sch = g.schema
+    if sampled is not None:
+        from oracle import sampler_oracle as SO
+        from workloads.synth import Block
+        nt = mb.blocks[-1].n_dst[mb.target_type]
+        targets = mb.ids[mb.target_type][:nt].copy()
+        fanouts = sampled.get("fanouts", cfg.fanouts)
+        smb = SO.sample_minibatch(g.num_nodes, sch.rel_src, sch.rel_dst, g.in_indptr, g.in_nbr, g.edge_off,
+                                  mb.target_type, targets, fanouts, sampled["seed"])
+        mb.ids = smb["ids"]
+        mb.blocks = [Block(b["n_src"], b["n_dst"], b["edge_index"], b["edge_id"], b["edge_type"]) for b in smb["blocks"]]
     t0 = time.time()
     ref = oracle_run(cfg, g, mb, ws, input_grad)
     t_oracle = time.time() - t0
     model = Model(sch, g.feat_dim, g.stores, ws, dtype=cfg.dtype, loss=("xent" if cfg.loss == "xent" else "dot"),
                   target_type=mb.target_type, first_layer_input_grad=input_grad)
-    bt = model.prepare(mb, g.edge_type, use_edge_id=use_edge_id)
+    if sampled is not None:
+        sampler = model.ctx.hgnn_sampler_create(g.num_nodes, g.in_indptr, g.in_nbr, g.edge_off)
+        bt = model.prepare_sampled(sampler, targets, fanouts, sampled["seed"], labels=mb.labels, grad_out=mb.grad_out)
+    else:
+        bt = model.prepare(mb, g.edge_type, use_edge_id=use_edge_id)
     out = model.run(bt, backward=backward)
     torch.cuda.synchronize()
     tol = TOL[cfg.dtype]

@@ -48,6 +48,16 @@ def test_config6_relation_heavy_large_bf16():
     _assert_ok(run_case(6, verbose=True))
 
 
+def test_config2_sampled_in_the_loop():
+    """The mini-batch is drawn by the library's own sampler (sample, select edge indices, upload: one host task)
+    and by the sampler oracle; ids, index arrays, outputs and gradients are compared as everywhere else."""
+    _assert_ok(run_case(2, scale=0.05, batch=256, verbose=True, input_grad=[0, 1, 1, 1], sampled=dict(seed=4242)))
+
+
+def test_config5_sampled_in_the_loop_many_relations():
+    _assert_ok(run_case(5, verbose=True, sampled=dict(seed=7, fanouts=[4, 3])))
+
+
 def test_config2_full_size_headline_workload():
     """The workload bench.py times (full graph, 4096 targets, bf16, hidden 512, input gradients only for the
     learnable embeddings), compared element by element with the oracle."""
