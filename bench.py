@@ -41,6 +41,7 @@ def main():
                     "(auto: forward GEMM and gather-mean of layer 1)")
     ap.add_argument("--probe-layer", type=int, default=0)
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--no-sampler-loop", action="store_true", help="skip the run with the sampler in the loop")
     ap.add_argument("--cpu-sample-batch", type=int, default=4096)
     ap.add_argument("--host-threads", type=int, default=0)
     ap.add_argument("--all-input-grads", action="store_true", help="also compute gradients w.r.t. the fixed T0 features")
@@ -176,6 +177,68 @@ def main():
         gr.release()
     t_build = (time.perf_counter() - t3) / nb
 
+    # sampling in the loop: every step's mini-batch is drawn, selected, built and uploaded by one task of the
+    # library's host threads while the GPU works on earlier steps (fresh targets every step)
+    sil = None
+    if not args.no_sampler_loop:
+        sampler = ctx.hgnn_sampler_create(g.num_nodes, g.in_indptr, g.in_nbr, g.edge_off)
+        tt, nt = model.target_type, len(mbs[0].ids[mbs[0].target_type][: mbs[0].blocks[-1].n_dst[mbs[0].target_type]])
+        order = np.random.default_rng([MASTER_SEED + cfg.index, 77]).permutation(g.num_nodes[tt])
+        n_chunks = max(1, len(order) // nt)
+        labels_all = order_dev = None
+        if cfg.loss == "xent":
+            labels_all = torch.from_numpy(np.random.default_rng([MASTER_SEED + cfg.index, 78])
+                                          .integers(0, cfg.num_classes, g.num_nodes[tt])).to(model.dev)
+            order_dev = torch.from_numpy(order).to(model.dev)
+
+        def start_sampled(i):
+            c = i % n_chunks
+            labels = None if labels_all is None else labels_all[order_dev[c * nt:(c + 1) * nt]]
+            b = model.prepare_sampled(sampler, order[c * nt:(c + 1) * nt], cfg.fanouts, seed=1_000_003 * i + 17, labels=labels)
+            b.grad_out_dev = slots[0].grad_out_dev
+            return b
+
+        def sampled_loop(nsteps, first):
+            ahead = [start_sampled(first + j) for j in range(min(args.lookahead, nsteps))]
+            started, pending = len(ahead), []
+            for i in range(nsteps):
+                cur = ahead.pop(0)
+                if started < nsteps:
+                    ahead.append(start_sampled(first + started))
+                    started += 1
+                model.run(cur)
+                ev = torch.cuda.Event()
+                ev.record()
+                pending.append((ev, cur.graph))
+                while len(pending) > 2:
+                    e, gr = pending.pop(0)
+                    e.synchronize()
+                    gr.release()
+            for e, gr in pending:
+                e.synchronize()
+                gr.release()
+
+        sampled_loop(W, 0)
+        torch.cuda.synchronize()
+        t4 = time.perf_counter()
+        sampled_loop(K, W)
+        torch.cuda.synchronize()
+        t_sil = time.perf_counter() - t4
+        t5 = time.perf_counter()
+        for i in range(10):                          # one task at a time: its own duration
+            b = start_sampled(W + K + i)
+            b.graph.wait()
+            b.graph.release()
+        t_task = (time.perf_counter() - t5) / 10
+        nb_conc = max(1, args.concurrent_builds)
+        sil = dict(value=round(K / t_sil, 2), unit="mini-batches/s", ms_per_step=round(1e3 * t_sil / K, 4),
+                   host_task_ms=round(1e3 * t_task, 3), host_tasks_in_parallel=nb_conc,
+                   cpu_gpu_time_ratio=round((t_task / nb_conc) / (t_gpu / K), 3),
+                   note="neighbour sampling + edge index selection + upload per step on the host threads, fresh "
+                        "targets every step; cpu_gpu_time_ratio = host time per mini-batch at that parallelism / "
+                        "GPU time per mini-batch")
+        sampler.close()
+
     # launches per layer: merged vs per-relation / per-type launch loop
     launches = []
     b0 = batch_of(slots[0], graphs[0])
@@ -292,11 +355,12 @@ def main():
         metric="HGNN layer fwd+bwd mini-batches/s (1 GPU)", value=round(K / t_pipe, 2), unit="mini-batches/s",
         n_gpus=1, steps=K, warmup=W, ms_per_step=round(1e3 * t_pipe / K, 4), higher_is_better=True, scaling="weak",
         vs_baseline=None, dtype=cfg.dtype, data="synthetic",
-        config=dict(workload="configs[%d] %s: 4 types / 8 relations, %d targets, fanout %s, layers %s, scale %.3g" %
-                    (cfg.index, cfg.name, cfg.batch, cfg.fanouts[::-1], [g.feat_dim[0]] + cfg.layer_out, cfg.scale),
+        config=dict(workload="configs[%d] %s: %d types / %d relations, %d targets, fanout %s, layers %s, scale %.3g" %
+                    (cfg.index, cfg.name, sch.num_types, sch.num_rels, cfg.batch, cfg.fanouts[::-1],
+                     [g.feat_dim[0]] + cfg.layer_out, cfg.scale),
                     minibatch_sizes=sizes, distinct_minibatches=len(slots)),
         gpu_only_mb_per_s=round(K / t_gpu, 2), gpu_only_ms_per_step=round(1e3 * t_gpu / K, 4),
-        host_build_ms=round(1e3 * t_build, 3), launches_per_layer=launches,
+        host_build_ms=round(1e3 * t_build, 3), sampler_in_loop=sil, launches_per_layer=launches,
         roofline=roof, roofline_aggregation=roof_agg, cpu_baseline=cpu, setup_s=round(t_setup, 1))
     print(json.dumps(line))
     model.close()

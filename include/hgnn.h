@@ -188,7 +188,7 @@ void hgnn_sampler_destroy(hgnn_ctx *ctx, hgnn_sampler *s);
  *  - relations are visited in ascending id, their destination vertices in list order;
  *    destination v (global id) with deg in-neighbours keeps all of them in stored order when
  *    deg <= fanout, else the positions that Floyd's subset algorithm picks: for c = 0..fanout-1,
- *    j = deg - fanout + c, t = mix64(key + c) mod (j+1), position = j if t was picked before
+ *    j = deg - fanout + c, t = floor(mix64(key + c) (j+1) / 2^64), position = j if t was picked before
  *    else t, where key = mix64(mix64(mix64(mix64(seed) ^ hop) ^ r) ^ v) and mix64 is the
  *    SplitMix64 output function; every kept position gives one edge, appended in that order. */
 hgnn_status hgnn_sample_and_build(hgnn_ctx *ctx, const hgnn_sampler *s, int32_t target_type,

@@ -15,7 +15,7 @@ list nb (deg entries, the graph's stored order) contributes
 
     all positions 0..deg-1 in order                         if deg <= fanout
     a subset of `fanout` positions chosen with Floyd's      otherwise:
-      for c = 0..fanout-1:  j = deg - fanout + c;  t = draw(c) mod (j + 1);
+      for c = 0..fanout-1:  j = deg - fanout + c;  t = floor(draw(c) * (j + 1) / 2^64);
                             position = j if t was chosen before else t
 
 with draw(c) = mix64(key + c), key = mix64(mix64(mix64(mix64(seed) ^ h) ^ r) ^ v) (v the global id), and
@@ -43,7 +43,7 @@ def choose_positions(deg: int, fanout: int, key: int):
     chosen = []
     for c in range(fanout):
         j = deg - fanout + c
-        t = mix64((key + c) & _M) % (j + 1)
+        t = (mix64((key + c) & _M) * (j + 1)) >> 64
         chosen.append(j if t in chosen else t)
     return chosen
 

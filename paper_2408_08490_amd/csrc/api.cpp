@@ -754,8 +754,16 @@ hgnn_status hgnn_sample_and_build(hgnn_ctx *ctx, const hgnn_sampler *sm, int32_t
   hgnn_graph *g = new (std::nothrow) hgnn_graph();
   if (!g) HGNN_FAIL(HGNN_ENOMEM, "out of host memory");
   g->num_layers = num_layers;
-  g->job.reset(new SampleJob());
+  {
+    std::lock_guard<std::mutex> lk(ctx->pm);
+    if (!ctx->free_jobs.empty()) {
+      g->job = std::move(ctx->free_jobs.back());
+      ctx->free_jobs.pop_back();
+    }
+  }
+  if (!g->job) g->job.reset(new SampleJob());
   SampleJob &job = *g->job;
+  for (int l = 0; l < kMaxLayers; ++l) job.transpose[l].clear();
   job.sampler = sm;
   job.target_type = target_type;
   job.seed = seed;
@@ -866,6 +874,7 @@ void hgnn_graph_release(hgnn_ctx *ctx, hgnn_graph *g) {
     std::lock_guard<std::mutex> lk(ctx->pm);
     if (g->slab.host) ctx->free_slabs.push_back(g->slab);
     if (g->ready) ctx->free_events.push_back(g->ready);
+    if (g->job && ctx->free_jobs.size() < 64) ctx->free_jobs.push_back(std::move(g->job));
   }
   delete g;
 }

@@ -156,6 +156,7 @@ struct Builder {
   std::vector<int32_t> key, col, rowid, hist, tkey;
   std::vector<std::vector<int32_t>> long_lists;
   std::vector<int32_t> local_of[kMaxT];  // sampler: local row of a global vertex id (-1 = not in the hop), per type
+  std::vector<int64_t> hop_ids[2][kMaxT], edge_dst;  // sampler: destination / source lists of the current hop
 };
 
 // A mini-batch to be sampled on a builder's thread before its index arrays are built, and what the sampling
@@ -212,6 +213,7 @@ struct hgnn_ctx {
   std::vector<hgnn::Slab> free_slabs;
   std::vector<hipEvent_t> free_events;
   std::vector<uint8_t> edge_types8;  // compact copy of the registered global edge-type table
+  std::vector<std::unique_ptr<hgnn::SampleJob>> free_jobs;  // released sampled mini-batches: their buffers are reused (pm)
   // kernel probe (measurement aid)
   int probe_sel[4][2];  // selected (kernel, layer) pairs
   int probe_n = 0;

@@ -2,6 +2,7 @@
 // part of a builder's task so that sampling, edge index selection and upload of mini-batch i+k overlap the GPU
 // work of mini-batch i.  The rule (order of visits, subset choice, generator) is the one stated with
 // hgnn_sample_and_build in hgnn.h.
+#include <algorithm>
 #include <cstring>
 
 #include "common.h"
@@ -22,9 +23,12 @@ hgnn_status run_sample_job(hgnn_ctx *ctx, Builder &bd, hgnn_graph *g, std::strin
   const int T = ctx->T, R = ctx->R, L = g->num_layers;
   for (int t = 0; t < T; ++t)
     if ((int64_t)bd.local_of[t].size() != sm.num_nodes[t]) bd.local_of[t].assign((size_t)sm.num_nodes[t], -1);
-  std::vector<int64_t> dst[kMaxT], src[kMaxT];  // global ids per type of the current hop
+  // global ids per type of the current hop; the buffers live in the builder and in the (pooled) job, so that a
+  // steady stream of mini-batches allocates nothing and touches no fresh pages
+  std::vector<int64_t> *dst = bd.hop_ids[0], *src = bd.hop_ids[1];
+  for (int t = 0; t < T; ++t) dst[t].clear();
   dst[job.target_type] = job.targets;
-  std::vector<int64_t> es, ed;
+  std::vector<int64_t> &ed = bd.edge_dst;
   const uint64_t k0 = mix64(job.seed);
   hgnn_status st = HGNN_OK;
   for (int h = 1; h <= L && st == HGNN_OK; ++h) {
@@ -46,10 +50,19 @@ hgnn_status run_sample_job(hgnn_ctx *ctx, Builder &bd, hgnn_graph *g, std::strin
       }
       job.n_dst[l][t] = (int64_t)dst[t].size();
     }
+    std::vector<int64_t> &es = job.edge_index[l];  // local sources first; the destinations are appended below
     es.clear();
     ed.clear();
     std::vector<int64_t> &eid = job.edge_id[l];
     eid.clear();
+    {
+      size_t bound = 0;  // every destination keeps at most `fanout` edges per relation
+      for (int r = 0; r < R; ++r) bound += dst[ctx->rel_dst[r]].size() * (size_t)fanout;
+      bound = std::min<size_t>(bound, (size_t)sm.edge_off[R]);
+      es.reserve(2 * bound);
+      ed.reserve(bound);
+      eid.reserve(bound);
+    }
     for (int r = 0; r < R && st == HGNN_OK; ++r) {
       const int s = ctx->rel_src[r], d = ctx->rel_dst[r];
       const int64_t nd = (int64_t)dst[d].size();
@@ -60,39 +73,57 @@ hgnn_status run_sample_job(hgnn_ctx *ctx, Builder &bd, hgnn_graph *g, std::strin
       int32_t *lut = bd.local_of[s].data();
       std::vector<int64_t> &sl = src[s];
       const uint64_t kr = mix64(kh ^ (uint64_t)r);
-      int64_t picked[64];
-      auto emit = [&](int64_t pos, int64_t i) {
-        const int64_t u = nbr[pos];
-        int32_t loc = lut[u];
-        if (loc < 0) {
-          loc = (int32_t)sl.size();
-          lut[u] = loc;
-          sl.push_back(u);
-        }
-        es.push_back(loc);
-        ed.push_back(i);
-        eid.push_back(e0 + pos);
-      };
-      for (int64_t i = 0; i < nd; ++i) {
-        const int64_t v = dst[d][i];
-        if (i + 8 < nd) __builtin_prefetch(ptr + dst[d][i + 8]);
-        const int64_t first = ptr[v], deg = ptr[v + 1] - first;
-        if (deg <= fanout) {
-          for (int64_t p = 0; p < deg; ++p) emit(first + p, i);
-        } else {
-          const uint64_t key = mix64(kr ^ (uint64_t)v);
-          for (int64_t c = 0; c < fanout; ++c) {
-            const int64_t j = deg - fanout + c;
-            int64_t t = (int64_t)(mix64(key + (uint64_t)c) % (uint64_t)(j + 1));
-            for (int64_t q = 0; q < c; ++q)
-              if (picked[q] == t) {
-                t = j;
-                break;
-              }
-            picked[c] = t;
+      // Destination vertices are taken in blocks; inside a block every step (row pointers, neighbour positions,
+      // neighbour ids, local-row table) is done for all vertices before the next, each step prefetching what the
+      // next one reads: the reads are random accesses into arrays far larger than the caches, and this keeps
+      // dozens of them in flight instead of one.
+      constexpr int kBlock = 32, kMaxFan = 64;
+      int64_t pos[kBlock][kMaxFan];
+      int32_t cnt[kBlock];
+      for (int64_t i0 = 0; i0 < nd; i0 += kBlock) {
+        const int nb = (int)std::min<int64_t>(kBlock, nd - i0);
+        for (int b = 0; b < nb; ++b) __builtin_prefetch(ptr + dst[d][i0 + b]);
+        if (i0 + kBlock < nd)
+          for (int b = 0; b < kBlock && i0 + kBlock + b < nd; b += 8) __builtin_prefetch(&dst[d][i0 + kBlock + b]);
+        for (int b = 0; b < nb; ++b) {
+          const int64_t v = dst[d][i0 + b];
+          const int64_t first = ptr[v], deg = ptr[v + 1] - first;
+          int64_t *pb = pos[b];
+          if (deg <= fanout) {
+            for (int64_t p = 0; p < deg; ++p) pb[p] = first + p;
+            cnt[b] = (int32_t)deg;
+            for (int64_t p = 0; p < deg; p += 16) __builtin_prefetch(nbr + first + p);
+          } else {
+            const uint64_t key = mix64(kr ^ (uint64_t)v);
+            for (int64_t c = 0; c < fanout; ++c) {
+              const int64_t j = deg - fanout + c;
+              int64_t t = (int64_t)(((unsigned __int128)mix64(key + (uint64_t)c) * (uint64_t)(j + 1)) >> 64);
+              bool again = false;
+              for (int64_t q = 0; q < c; ++q) again |= pb[q] == first + t;  // no early exit: the loop vectorises
+              if (again) t = j;
+              pb[c] = first + t;
+              __builtin_prefetch(nbr + first + t);
+            }
+            cnt[b] = (int32_t)fanout;
           }
-          for (int64_t c = 0; c < fanout; ++c) __builtin_prefetch(nbr + first + picked[c]);
-          for (int64_t c = 0; c < fanout; ++c) emit(first + picked[c], i);
+        }
+        for (int b = 0; b < nb; ++b)
+          for (int c = 0; c < cnt[b]; ++c) __builtin_prefetch(lut + nbr[pos[b][c]]);
+        for (int b = 0; b < nb; ++b) {
+          const int64_t i = i0 + b;
+          for (int c = 0; c < cnt[b]; ++c) {
+            const int64_t p = pos[b][c];
+            const int64_t u = nbr[p];
+            int32_t loc = lut[u];
+            if (loc < 0) {
+              loc = (int32_t)sl.size();
+              lut[u] = loc;
+              sl.push_back(u);
+            }
+            es.push_back(loc);
+            ed.push_back(i);
+            eid.push_back(e0 + p);
+          }
         }
       }
       if (sl.size() > (size_t)INT32_MAX - 1) {
@@ -101,21 +132,16 @@ hgnn_status run_sample_job(hgnn_ctx *ctx, Builder &bd, hgnn_graph *g, std::strin
       }
     }
     // this hop's block; the lookup tables go back to "not in the hop"
-    const size_t E = es.size();
-    job.edge_index[l].resize(2 * E);
-    if (E) {
-      std::memcpy(job.edge_index[l].data(), es.data(), E * sizeof(int64_t));
-      std::memcpy(job.edge_index[l].data() + E, ed.data(), E * sizeof(int64_t));
-    }
+    es.insert(es.end(), ed.begin(), ed.end());
     for (int t = 0; t < T; ++t) {
       job.n_src[l][t] = (int64_t)src[t].size();
       int32_t *lut = bd.local_of[t].data();
       for (int64_t v : src[t]) lut[v] = -1;
-      dst[t].swap(src[t]);
     }
+    std::swap(dst, src);
   }
   if (st != HGNN_OK) return st;
-  for (int t = 0; t < T; ++t) job.ids[t].swap(dst[t]);
+  for (int t = 0; t < T; ++t) job.ids[t].assign(dst[t].begin(), dst[t].end());
   for (int l = 0; l < L; ++l) {
     hgnn_coo_layer &in = g->L[l].in;
     std::memset(&in, 0, sizeof(in));
