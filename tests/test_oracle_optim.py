@@ -24,10 +24,10 @@ def test_rows_adam_against_torch_sparse_adam():
     V, F = 30, 4
     th0 = rng.normal(size=(V, F))
     p = torch.nn.Parameter(torch.tensor(th0, dtype=torch.float64))
-    # torch's sparse variant adds eps before the bias correction of the second moment; with eps = 0 (and non-zero
+    # torch's sparse variant adds eps before the bias correction of the second moment; with eps -> 0 (and non-zero
     # gradients) the two forms coincide, so this pins what is specific to rows: untouched rows keep their moments,
     # the bias correction counts global steps.  Where eps goes is pinned by the dense comparison above.
-    opt = torch.optim.SparseAdam([p], lr=2e-2, betas=(0.9, 0.99), eps=0.0)
+    opt = torch.optim.SparseAdam([p], lr=2e-2, betas=(0.9, 0.99), eps=1e-300)   # (it refuses an exact zero)
     th, m, v = th0, np.zeros_like(th0), np.zeros_like(th0)
     for step in range(1, 7):
         ids = rng.choice(V, size=rng.integers(1, 12), replace=False)
