@@ -309,6 +309,33 @@ hgnn_status hgnn_layer_launch_count(hgnn_ctx *ctx, hgnn_graph *g, int32_t layer,
 hgnn_status hgnn_softmax_xent(hgnn_ctx *ctx, void *stream, const void *logits, const int64_t *labels,
                               int64_t rows, int32_t classes, float *loss, void *grad_logits);
 
+/* ---- Parameter update (Section 2.3, step 4; the paper names no optimiser: this library offers
+ * Adam, Kingma & Ba 2015, Algorithm 1) -----------------------------------------------------
+ * step counts updates from 1.  Per element, in fp32:
+ *   m = beta1 m + (1 - beta1) g;  v = beta2 v + (1 - beta2) g^2
+ *   theta -= lr (m / (1 - beta1^step)) / (sqrt(v / (1 - beta2^step)) + eps) */
+typedef struct {
+  float lr, beta1, beta2, eps;
+  int64_t step;
+} hgnn_adam_params;
+/* Updates n tensors in one launch per 48 of them.  Host arrays of device pointers: param[i]
+ * (context dtype, numel[i] elements), master[i] (fp32 copy the update is applied to; param[i] is
+ * then its rounded copy; the array or an entry may be NULL when the dtype is fp32: the parameter
+ * is its own master), grad[i] (fp32, as hgnn_layer_bwd writes them), m[i], v[i] (fp32 moments,
+ * zero before the first step). */
+hgnn_status hgnn_adam_update(hgnn_ctx *ctx, void *stream, int32_t n, void *const *param, float *const *master,
+                             const float *const *grad, float *const *m, float *const *v, const int64_t *numel,
+                             const hgnn_adam_params *hp);
+/* The same update on the rows ids[0..n_rows) (device, distinct) of an embedding table
+ * store [V x feat_dim] (context dtype) with fp32 master / m / v tables of the same shape (master
+ * may be NULL for fp32); grad_rows [n_rows x feat_dim] (context dtype) is the gradient of row
+ * ids[i] -- the type's block of hgnn_layer_bwd's grad_x_merged of the first layer.  Rows that
+ * are not listed keep their values and moments.  feat_dim * sizeof(dtype) must be a multiple of
+ * 16 and the tables 16-byte aligned. */
+hgnn_status hgnn_adam_update_rows(hgnn_ctx *ctx, void *stream, void *store, float *master, float *m, float *v,
+                                  int32_t feat_dim, const int64_t *ids, int64_t n_rows, const void *grad_rows,
+                                  const hgnn_adam_params *hp);
+
 /* ---- Measurement aid --------------------------------------------------------------------
  * Attaches a pair of HIP events to every later dispatch of the selected kernels (the events carry the
  * dispatch's own begin and end timestamps) so that a benchmark can report a kernel's average duration

@@ -60,6 +60,10 @@ class MinibatchView(C.Structure):
                 ("edge_index", C.POINTER(C.c_int64)), ("edge_id", C.POINTER(C.c_int64))]
 
 
+class AdamParams(C.Structure):
+    _fields_ = [("lr", C.c_float), ("beta1", C.c_float), ("beta2", C.c_float), ("eps", C.c_float), ("step", C.c_int64)]
+
+
 class LayerParams(C.Structure):
     _fields_ = [("in_dim", C.POINTER(C.c_int32)), ("out_dim", C.c_int32), ("relu", C.c_int32),
                 ("w_rel", C.POINTER(C.c_void_p)), ("w_root", C.POINTER(C.c_void_p)),
@@ -103,6 +107,9 @@ def _load():
                            vp, C.c_size_t],
         "hgnn_layer_launch_count": [vp, vp, i32, C.POINTER(LayerParams), C.POINTER(i32), C.POINTER(i32)],
         "hgnn_softmax_xent": [vp, vp, vp, vp, i64, i32, vp, vp],
+        "hgnn_adam_update": [vp, vp, i32, C.POINTER(vp), C.POINTER(vp), C.POINTER(vp), C.POINTER(vp), C.POINTER(vp),
+                             C.POINTER(i64), C.POINTER(AdamParams)],
+        "hgnn_adam_update_rows": [vp, vp, vp, vp, vp, vp, i32, vp, i64, vp, C.POINTER(AdamParams)],
         "hgnn_probe_select": [vp, i32, i32],
         "hgnn_probe_read": [vp, i32, i32, C.POINTER(C.c_double), C.POINTER(i64)],
     }
@@ -124,7 +131,7 @@ EXPORTS = ["hgnn_create", "hgnn_destroy", "hgnn_last_error", "hgnn_merge_feature
            "hgnn_graph_ids", "hgnn_graph_minibatch_view", "hgnn_graph_wait_stream",
            "hgnn_graph_wait", "hgnn_graph_host_view", "hgnn_graph_release", "hgnn_layer_workspace_bytes",
            "hgnn_layer_fwd", "hgnn_layer_bwd", "hgnn_layer_fwd_naive", "hgnn_layer_launch_count",
-           "hgnn_softmax_xent", "hgnn_probe_select", "hgnn_probe_read"]
+           "hgnn_softmax_xent", "hgnn_adam_update", "hgnn_adam_update_rows", "hgnn_probe_select", "hgnn_probe_read"]
 
 KERNEL_IDS = dict(merge=0, transpose_w=1, spmm_fwd=2, gemm_fwd=3, zero_grads=4, relu_bias_bwd=5, gemm_dw=6,
                   gemm_da=7, spmm_bwd=8, xent=9)
@@ -297,6 +304,30 @@ class Context:
         elem_off = (C.c_int64 * (T + 1))()
         _check(lib.hgnn_merge_features(self.handle, _stream_ptr(self.device), st, fd, idp, nr, _ptr(x_merged), row_off, elem_off))
         return np.array(row_off[:], dtype=np.int32), np.array(elem_off[:], dtype=np.int64)
+
+    # ---- parameter update ----
+    class AdamList:
+        """Marshalled tensor lists of hgnn_adam_update (built once, reused every step)."""
+
+        def __init__(self, params, masters, grads, ms, vs):
+            n = len(params)
+            self.keep = (params, masters, grads, ms, vs)
+            arr = lambda ts: (C.c_void_p * n)(*[_ptr(t) for t in ts])
+            self.n = n
+            self.param, self.grad, self.m, self.v = arr(params), arr(grads), arr(ms), arr(vs)
+            self.master = arr(masters) if masters is not None else None
+            self.numel = (C.c_int64 * n)(*[p.numel() for p in params])
+
+    def hgnn_adam_update(self, lst, lr, beta1, beta2, eps, step):
+        hp = AdamParams(lr, beta1, beta2, eps, step)
+        _check(lib.hgnn_adam_update(self.handle, _stream_ptr(self.device), lst.n, lst.param, lst.master, lst.grad, lst.m, lst.v,
+                                    lst.numel, C.byref(hp)))
+
+    def hgnn_adam_update_rows(self, store, master, m, v, ids, grad_rows, lr, beta1, beta2, eps, step):
+        """ids: device int64 tensor (or any object with data_ptr() / numel()); grad_rows: [len(ids) x F] rows."""
+        hp = AdamParams(lr, beta1, beta2, eps, step)
+        _check(lib.hgnn_adam_update_rows(self.handle, _stream_ptr(self.device), _ptr(store), _ptr(master), _ptr(m), _ptr(v),
+                                         store.shape[1], _ptr(ids), ids.numel(), _ptr(grad_rows), C.byref(hp)))
 
     # ---- sampling in the loop ----
     def hgnn_sampler_create(self, num_nodes, in_indptr, in_nbr, edge_off):

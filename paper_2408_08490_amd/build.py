@@ -6,7 +6,7 @@ import subprocess
 HERE = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(HERE, "csrc")
 LIB = os.path.join(HERE, "libhgnn.so")
-SOURCES = ["api.cpp", "host_build.cpp", "sampler.cpp", "kernels_mem.hip", "kernels_spmm.hip", "kernels_gemm.hip", "kernels_attn.hip"]
+SOURCES = ["api.cpp", "host_build.cpp", "sampler.cpp", "kernels_mem.hip", "kernels_spmm.hip", "kernels_gemm.hip", "kernels_attn.hip", "kernels_optim.hip"]
 
 
 def hipcc_path():

@@ -1,5 +1,6 @@
 // C ABI entry points: argument checks, per-call planning (offset tables), launch sequences.
 #include <algorithm>
+#include <cmath>
 #include <cstring>
 #include <unistd.h>
 
@@ -1171,6 +1172,51 @@ hgnn_status hgnn_softmax_xent(hgnn_ctx *ctx, void *stream, const void *logits, c
   if (ctx->device < 0) HGNN_FAIL(HGNN_EUNSUPPORTED, "host-only context cannot run device work");
   Probe pb(ctx, (hipStream_t)stream, HGNN_K_XENT, -1);
   return launch_xent((hipStream_t)stream, ctx->dtype, logits, labels, rows, classes, loss, grad_logits);
+}
+
+static hgnn_status check_adam(const hgnn_adam_params *hp, double &c1, double &c2) {
+  if (!hp) HGNN_FAIL(HGNN_EINVAL, "NULL argument");
+  if (hp->step < 1 || !(hp->beta1 >= 0.f && hp->beta1 < 1.f) || !(hp->beta2 >= 0.f && hp->beta2 < 1.f) || !(hp->eps >= 0.f))
+    HGNN_FAIL(HGNN_EINVAL, "Adam needs step >= 1, beta1 and beta2 in [0,1), eps >= 0");
+  c1 = 1.0 / (1.0 - std::pow((double)hp->beta1, (double)hp->step));
+  c2 = 1.0 / (1.0 - std::pow((double)hp->beta2, (double)hp->step));
+  return HGNN_OK;
+}
+
+hgnn_status hgnn_adam_update(hgnn_ctx *ctx, void *stream, int32_t n, void *const *param, float *const *master,
+                             const float *const *grad, float *const *m, float *const *v, const int64_t *numel,
+                             const hgnn_adam_params *hp) {
+  if (!ctx || n < 0 || (n > 0 && (!param || !grad || !m || !v || !numel))) HGNN_FAIL(HGNN_EINVAL, "NULL argument");
+  double c1, c2;
+  hgnn_status st = check_adam(hp, c1, c2);
+  if (st != HGNN_OK) return st;
+  for (int i = 0; i < n; ++i) {
+    if (numel[i] < 0 || numel[i] > (int64_t)INT32_MAX * 1024) HGNN_FAIL(HGNN_EINVAL, "numel[%d]=%lld out of range", i, (long long)numel[i]);
+    if (numel[i] > 0 && (!param[i] || !grad[i] || !m[i] || !v[i])) HGNN_FAIL(HGNN_EINVAL, "tensor %d: NULL pointer", i);
+    if (numel[i] > 0 && ctx->dtype != HGNN_F32 && (!master || !master[i]))
+      HGNN_FAIL(HGNN_EINVAL, "tensor %d: a bf16 parameter needs an fp32 master copy", i);
+  }
+  if (ctx->device < 0) HGNN_FAIL(HGNN_EUNSUPPORTED, "host-only context cannot run device work");
+  return launch_adam_dense((hipStream_t)stream, ctx->dtype, n, param, master, grad, m, v, numel, hp->lr, hp->beta1, hp->beta2,
+                           hp->eps, c1, c2);
+}
+
+hgnn_status hgnn_adam_update_rows(hgnn_ctx *ctx, void *stream, void *store, float *master, float *m, float *v,
+                                  int32_t feat_dim, const int64_t *ids, int64_t n_rows, const void *grad_rows,
+                                  const hgnn_adam_params *hp) {
+  if (!ctx || n_rows < 0) HGNN_FAIL(HGNN_EINVAL, "NULL argument");
+  double c1, c2;
+  hgnn_status st = check_adam(hp, c1, c2);
+  if (st != HGNN_OK) return st;
+  const int vec = 16 / esize(ctx->dtype);
+  if (feat_dim <= 0 || feat_dim % vec != 0) HGNN_FAIL(HGNN_EINVAL, "feat_dim=%d is not a positive multiple of %d", feat_dim, vec);
+  if (n_rows > 0 && (!store || !m || !v || !ids || !grad_rows)) HGNN_FAIL(HGNN_EINVAL, "NULL argument");
+  if (n_rows > 0 && ctx->dtype != HGNN_F32 && !master) HGNN_FAIL(HGNN_EINVAL, "a bf16 table needs an fp32 master copy");
+  for (const void *p : {(const void *)store, (const void *)master, (const void *)m, (const void *)v, grad_rows})
+    if (reinterpret_cast<uintptr_t>(p) & 15) HGNN_FAIL(HGNN_EINVAL, "tables and gradient rows must be 16-byte aligned");
+  if (ctx->device < 0) HGNN_FAIL(HGNN_EUNSUPPORTED, "host-only context cannot run device work");
+  return launch_adam_rows((hipStream_t)stream, ctx->dtype, store, master, m, v, feat_dim, ids, n_rows, grad_rows, hp->lr,
+                          hp->beta1, hp->beta2, hp->eps, c1, c2);
 }
 
 hgnn_status hgnn_probe_select(hgnn_ctx *ctx, int32_t kernel, int32_t layer) {

@@ -224,6 +224,14 @@ struct hgnn_ctx {
 };
 
 namespace hgnn {
+// log2 of the lanes that share one feature row of `max_dim` scalars: 16 bytes per lane, at most a wavefront
+static inline int lanes_log2_for(int max_dim, int esize) {
+  int nvec = (max_dim * esize + 15) / 16;
+  int l = 0;
+  while ((1 << l) < nvec && l < 6) ++l;
+  return l;
+}
+
 void build_graph_job(hgnn_ctx *ctx, Builder &b, hgnn_graph *g);  // host_build.cpp
 hgnn_status plan_graph(hgnn_ctx *ctx, hgnn_graph *g, std::string &msg);  // api.cpp
 hgnn_status run_sample_job(hgnn_ctx *ctx, Builder &b, hgnn_graph *g, std::string &msg);  // sampler.cpp
@@ -282,6 +290,12 @@ hgnn_status launch_gemm_da(hipStream_t s, int dtype, const LayerDev &L, const Ty
 hgnn_status launch_gemm_dw(hipStream_t s, int dtype, const LayerDev &L, const TypeTab &tt, const RelTab &rt,
                            const GradPtrTab &gt, const DwTab &tiles, int split_rows, int H, int ldg, bool fast,
                            const void *x, const void *z, const void *gp);
+hgnn_status launch_adam_dense(hipStream_t s, int dtype, int n, void *const *param, float *const *master,
+                              const float *const *grad, float *const *m, float *const *v, const int64_t *numel,
+                              float lr, float b1, float b2, float eps, double c1, double c2);
+hgnn_status launch_adam_rows(hipStream_t s, int dtype, void *store, float *master, float *m, float *v, int F,
+                             const int64_t *ids, int64_t n_rows, const void *grad, float lr, float b1, float b2,
+                             float eps, double c1, double c2);
 // gp (leading dimension ldo >= H, zero beyond H) = grad_h * [h > 0] (or a plain copy without ReLU); dbias = column sums
 hgnn_status launch_relu_bias_bwd(hipStream_t s, int dtype, const TypeTab &tt, int H, int ldo, int relu,
                                  const void *grad_h, const void *h, void *gp, const GradPtrTab &gt);

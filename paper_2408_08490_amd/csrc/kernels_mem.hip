@@ -7,13 +7,6 @@
 
 namespace hgnn {
 
-static inline int lanes_log2_for(int max_dim, int esize) {
-  int nvec = (max_dim * esize + 15) / 16;
-  int l = 0;
-  while ((1 << l) < nvec && l < 6) ++l;
-  return l;
-}
-
 // ------------------------------------------------------------------------------------------
 // Stage 0: gather mini-batch rows from the per-type stores into the type-first buffer.
 // ------------------------------------------------------------------------------------------

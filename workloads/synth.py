@@ -461,3 +461,15 @@ def init_weights(cfg: Config, graph: HeteroGraph) -> List[LayerWeights]:
         layers.append(lw)
         in_dim = [H] * T
     return layers
+
+
+# --------------------------------------------------------------------------- #
+# inputs of the optimiser tests (plain normal draws; no update arithmetic here)
+# --------------------------------------------------------------------------- #
+def optimizer_case(seed: int, shapes: Sequence[Sequence[int]], steps: int):
+    """Parameters ~ N(0, 0.1) and, per step, gradients ~ N(0, 1) * 10^U(-4, 0) per tensor."""
+    rng = np.random.default_rng([MASTER_SEED, 31337, seed])
+    theta = [rng.normal(0.0, 0.1, size=s).astype(np.float32) for s in shapes]
+    grads = [[(rng.normal(0.0, 1.0, size=s) * 10.0 ** rng.uniform(-4, 0)).astype(np.float32) for s in shapes]
+             for _ in range(steps)]
+    return theta, grads
