@@ -42,6 +42,7 @@ def main():
     ap.add_argument("--probe-layer", type=int, default=0)
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-sampler-loop", action="store_true", help="skip the run with the sampler in the loop")
+    ap.add_argument("--no-train-loop", action="store_true", help="skip the run with the parameter update in the step")
     ap.add_argument("--cpu-sample-batch", type=int, default=4096)
     ap.add_argument("--host-threads", type=int, default=0)
     ap.add_argument("--all-input-grads", action="store_true", help="also compute gradients w.r.t. the fixed T0 features")
@@ -317,6 +318,27 @@ def main():
             roof["traffic"] = TRAFFIC_BYTES.get("gemm_fwd")
             roof_agg["traffic"] = TRAFFIC_BYTES.get("spmm_fwd")
 
+    # whole training steps (forward, loss, backward, Adam on all weights and on the embedding rows read), index
+    # arrays resident: what the parameter update adds to a step.  Runs last: it changes weights and embeddings.
+    train = None
+    if not args.no_train_loop and not attention:
+        model.enable_training()
+        for i in range(W):
+            b = batch_of(slots[i % len(slots)], graphs[i % len(slots)])
+            model.optimizer_step(b, model.run(b))
+        torch.cuda.synchronize()
+        t6 = time.perf_counter()
+        for i in range(K):
+            b = batch_of(slots[i % len(slots)], graphs[i % len(slots)])
+            model.optimizer_step(b, model.run(b))
+        torch.cuda.synchronize()
+        t_train = time.perf_counter() - t6
+        n_par = sum(p.numel() for p in model.adam["params"])
+        train = dict(gpu_only_mb_per_s=round(K / t_train, 2), gpu_only_ms_per_step=round(1e3 * t_train / K, 4),
+                     optimizer="Adam: %d weights in one launch, embedding rows of the learnable types touched by the "
+                               "mini-batch in one launch per type (fp32 masters and moments)" % n_par,
+                     loss_after=round(float(model.loss_dev.item()), 4))
+
     for gr in graphs:
         gr.release()
 
@@ -360,7 +382,7 @@ def main():
                      [g.feat_dim[0]] + cfg.layer_out, cfg.scale),
                     minibatch_sizes=sizes, distinct_minibatches=len(slots)),
         gpu_only_mb_per_s=round(K / t_gpu, 2), gpu_only_ms_per_step=round(1e3 * t_gpu / K, 4),
-        host_build_ms=round(1e3 * t_build, 3), sampler_in_loop=sil, launches_per_layer=launches,
+        host_build_ms=round(1e3 * t_build, 3), sampler_in_loop=sil, training_step=train, launches_per_layer=launches,
         roofline=roof, roofline_aggregation=roof_agg, cpu_baseline=cpu, setup_s=round(t_setup, 1))
     print(json.dumps(line))
     model.close()

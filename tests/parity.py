@@ -289,3 +289,86 @@ def run_case(index, scale=1.0, batch=None, verbose=False, use_edge_id=True, chec
         print("worst:", worst, flush=True)
         print("all:", {k: v for k, v in report.items() if isinstance(v, tuple) and len(v) == 2}, flush=True)
     return report
+
+
+def train_case(index, scale=1.0, batch=None, steps=3, input_grad=None, verbose=False):
+    """`steps` training steps (forward, loss, backward, Adam on every weight and on the embedding rows the
+    mini-batch read) on one mini-batch: the C-ABI path against the same steps taken with the model oracle and the
+    optimiser oracle.  Returns the losses of both sides and the relative rms distance of every updated tensor."""
+    import torch
+    from oracle import optim_oracle as P
+    from paper_2408_08490_amd.runner import Model
+    cfg, g, mb, ws = prepare_inputs(index, scale, batch)
+    assert cfg.kind == "rgcn" and cfg.loss == "xent"
+    sch = g.schema
+    hp = {k: float(np.float32(x)) for k, x in dict(lr=1e-2, beta1=0.9, beta2=0.999, eps=1e-8).items()}
+    model = Model(sch, g.feat_dim, g.stores, ws, dtype=cfg.dtype, loss="xent", target_type=mb.target_type,
+                  first_layer_input_grad=input_grad)
+    model.enable_training(**hp)
+    bt = model.prepare(mb, g.edge_type, use_edge_id=True)
+    got_loss = []
+    for _ in range(steps):
+        out = model.run(bt)
+        got_loss.append(float(out["loss"].item()))
+        model.optimizer_step(bt, out)
+    torch.cuda.synchronize()
+    # the oracle's loop
+    learn = [t for t in range(sch.num_types) if input_grad is None or input_grad[t]]
+    stores = [np.asarray(s, dtype=np.float64).copy() for s in g.stores]
+    layers = layer_dicts(cfg, ws)
+    for lw in layers:
+        lw["w_rel"] = [np.asarray(w, np.float64) for w in lw["w_rel"]]
+        lw["w_root"] = [None if w is None else np.asarray(w, np.float64) for w in lw["w_root"]]
+        lw["bias"] = [None if b is None else np.asarray(b, np.float64) for b in lw["bias"]]
+    mom = {}
+    sels = [O.edge_index_select(b.edge_index, sch.num_rels, edge_id=b.edge_id, global_edge_type=g.edge_type)
+            for b in mb.blocks]
+    want_loss = []
+
+    def upd(key, theta, grad, step):
+        m, v = mom.get(key, (np.zeros_like(theta), np.zeros_like(theta)))
+        theta, m, v = P.adam_step(theta, grad, m, v, step, **hp)
+        mom[key] = (m, v)
+        return theta
+
+    for step in range(1, steps + 1):
+        blocks_x, _, _, _ = O.merge_features(stores, mb.ids)
+        res = O.rgcn_model_forward_backward(blocks_x, sels, sch.rel_src, sch.rel_dst, [b.n_dst for b in mb.blocks],
+                                            layers, "xent", labels=mb.labels, grad_out=None, target_type=mb.target_type)
+        want_loss.append(float(res["loss"]))
+        for l, lw in enumerate(layers):
+            gr = res["grads"][l]
+            lw["w_rel"] = [upd((l, "r", r), w, gr["dw_rel"][r], step) for r, w in enumerate(lw["w_rel"])]
+            lw["w_root"] = [None if w is None else upd((l, "0", t), w, gr["dw_root"][t], step) for t, w in enumerate(lw["w_root"])]
+            lw["bias"] = [None if b is None else upd((l, "b", t), b, gr["dbias"][t], step) for t, b in enumerate(lw["bias"])]
+        for t in learn:
+            if len(mb.ids[t]) == 0:
+                continue
+            m, v = mom.get(("e", t), (np.zeros_like(stores[t]), np.zeros_like(stores[t])))
+            stores[t], m, v = P.adam_rows_step(stores[t], mb.ids[t], res["dx0"][t], m, v, step, **hp)
+            mom[("e", t)] = (m, v)
+
+    def dist(got, want):
+        want = np.asarray(want, np.float64)
+        return float(np.sqrt(np.mean((np.asarray(got, np.float64) - want) ** 2)) / max(np.sqrt(np.mean(want ** 2)), 1e-30))
+
+    dists = {}
+    for l, (lw, w) in enumerate(zip(layers, model.weights)):
+        for r in range(sch.num_rels):
+            dists[f"L{l}.w_rel{r}"] = dist(w["w_rel"][r].float().cpu().numpy(), lw["w_rel"][r])
+        for t in range(sch.num_types):
+            if lw["w_root"][t] is not None:
+                dists[f"L{l}.w_root{t}"] = dist(w["w_root"][t].float().cpu().numpy(), lw["w_root"][t])
+            if lw["bias"][t] is not None:
+                dists[f"L{l}.bias{t}"] = dist(w["bias"][t].float().cpu().numpy(), lw["bias"][t])
+    for t in learn:
+        if len(mb.ids[t]):
+            dists[f"emb{t}"] = dist(model.stores[t][torch.from_numpy(mb.ids[t]).to(model.dev)].float().cpu().numpy(),
+                                    stores[t][mb.ids[t]])
+    for t in range(sch.num_types):
+        if t not in learn:   # fixed features are never written
+            assert np.array_equal(model.stores[t].float().cpu().numpy(), np.asarray(g.stores[t], np.float32))
+    model.close()
+    if verbose:
+        print("losses", got_loss, want_loss, "max dist", max(dists.values()), flush=True)
+    return dict(got_loss=got_loss, want_loss=want_loss, dists=dists)

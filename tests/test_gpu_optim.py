@@ -86,3 +86,18 @@ def test_adam_rows_kernel(dtype, F):
         if master is not None:
             assert np.array_equal(store.float().cpu().numpy(), bf16_round(got))
     ctx.close()
+
+
+@pytest.mark.parametrize("index,tol_loss,tol_w", [(1, 1e-4, 5e-3), (2, 2e-2, 5e-2)])
+def test_three_training_steps(index, tol_loss, tol_w):
+    """Losses: the path's tolerance (1e-4 fp32, 2e-2 bf16).  Updated tensors: Adam's move is lr * m^ / (sqrt(v^) +
+    eps), a function of the gradient's SIGN in the first steps, so an element whose gradient is smaller than the
+    kernels' rounding error of it may move by up to lr either way; with lr = 1e-2 against weights of rms ~ 5e-2
+    and ~1e-5 (fp32) / ~1e-2 (bf16) of the elements that close to zero, the rms distance of a tensor is bounded
+    by ~1.3e-3 / ~4e-2 -- hence the looser bars on the tensors (the update itself is held to 1e-5 above)."""
+    from tests.parity import train_case
+    r = train_case(index, scale=0.05, batch=256, steps=3, input_grad=[0, 1, 1, 1], verbose=True)
+    for a, b in zip(r["got_loss"], r["want_loss"]):
+        assert abs(a - b) <= tol_loss * abs(b), r
+    assert r["want_loss"][-1] < r["want_loss"][0]                  # and it trains
+    assert max(r["dists"].values()) <= tol_w, r["dists"]
