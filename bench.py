@@ -43,6 +43,9 @@ def main():
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-sampler-loop", action="store_true", help="skip the run with the sampler in the loop")
     ap.add_argument("--no-train-loop", action="store_true", help="skip the run with the parameter update in the step")
+    ap.add_argument("--ablation", action="store_true",
+                    help="also time the switchable pieces one by one (the paper's Fig. 9 analogue): per-relation launch "
+                         "loop vs merged launches, serial vs overlapped host build, one host builder vs all")
     ap.add_argument("--cpu-sample-batch", type=int, default=4096)
     ap.add_argument("--host-threads", type=int, default=0)
     ap.add_argument("--all-input-grads", action="store_true", help="also compute gradients w.r.t. the fixed T0 features")
@@ -318,6 +321,51 @@ def main():
             roof["traffic"] = TRAFFIC_BYTES.get("gemm_fwd")
             roof_agg["traffic"] = TRAFFIC_BYTES.get("spmm_fwd")
 
+    # ablation: what each piece buys on this machine
+    abl = None
+    if args.ablation:
+        def gpu_ms(fn, n):
+            torch.cuda.synchronize()
+            a, b_ = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+            a.record()
+            for i in range(n):
+                fn(i)
+            b_.record()
+            torch.cuda.synchronize()
+            return a.elapsed_time(b_) / n
+
+        def fwd_only(naive):
+            def f(i):
+                model.run(batch_of(slots[i % len(slots)], graphs[i % len(slots)]), backward=False, naive=naive)
+            return f
+        n_ab = max(20, K // 4)
+        fwd_only(False)(0)
+        merged_fwd_ms = gpu_ms(fwd_only(False), n_ab)
+        naive_fwd_ms = None
+        if not attention:
+            fwd_only(True)(0)
+            naive_fwd_ms = gpu_ms(fwd_only(True), n_ab)
+
+        def serial_loop(n):          # build, wait, compute, wait: nothing overlaps
+            t = time.perf_counter()
+            for i in range(n):
+                gr = start_build(slots[i % len(slots)])
+                gr.wait()
+                model.run(batch_of(slots[i % len(slots)], gr))
+                torch.cuda.synchronize()
+                gr.release()
+            return (time.perf_counter() - t) / n
+        serial_loop(3)
+        serial_ms = 1e3 * serial_loop(n_ab)
+        abl = dict(forward_merged_ms=round(merged_fwd_ms, 4),
+                   forward_per_relation_launches_ms=None if naive_fwd_ms is None else round(naive_fwd_ms, 4),
+                   step_serial_build_then_compute_ms=round(serial_ms, 4),
+                   step_overlapped_ms=round(1e3 * t_pipe / K, 4), step_gpu_only_ms=round(1e3 * t_gpu / K, 4),
+                   host_builders=args.concurrent_builds,
+                   note="forward_*: merge + all layers forward, index arrays resident (GPU time between events); "
+                        "serial: every step builds its index arrays with one builder, waits, computes, waits; "
+                        "overlapped: bench.py's `value` loop")
+
     # whole training steps (forward, loss, backward, Adam on all weights and on the embedding rows read), index
     # arrays resident: what the parameter update adds to a step.  Runs last: it changes weights and embeddings.
     train = None
@@ -382,7 +430,7 @@ def main():
                      [g.feat_dim[0]] + cfg.layer_out, cfg.scale),
                     minibatch_sizes=sizes, distinct_minibatches=len(slots)),
         gpu_only_mb_per_s=round(K / t_gpu, 2), gpu_only_ms_per_step=round(1e3 * t_gpu / K, 4),
-        host_build_ms=round(1e3 * t_build, 3), sampler_in_loop=sil, training_step=train, launches_per_layer=launches,
+        host_build_ms=round(1e3 * t_build, 3), sampler_in_loop=sil, training_step=train, ablation=abl, launches_per_layer=launches,
         roofline=roof, roofline_aggregation=roof_agg, cpu_baseline=cpu, setup_s=round(t_setup, 1))
     print(json.dumps(line))
     model.close()
