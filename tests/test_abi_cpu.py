@@ -39,7 +39,7 @@ def _host_ctx(B, sch, dtype="f32", threads=4, concurrent_builds=0):
 
 
 @pytest.mark.parametrize("index,scale,threads", [(0, 1.0, 1), (0, 1.0, 4), (2, 0.02, 8), (3, 0.003, 3), (5, 1.0, 2),
-                                                 (6, 0.1, 4)])
+                                                 (6, 0.1, 4), (7, 1.0, 3)])
 @pytest.mark.parametrize("use_edge_id", [False, True, "registered"])
 def test_host_build_bit_exact(B, index, scale, threads, use_edge_id):
     cfg = make_config(index, scale=scale, batch=96)

@@ -113,6 +113,43 @@ def test_relation_without_edges_and_block_without_edges():
     assert r["ok"], r
 
 
+def test_config7_widest_schema():
+    """32 vertex types and 128 relations (the library's limits), ragged widths, two passes of the forward GEMM's
+    relation window, most relations with a handful of edges."""
+    _assert_ok(run_case(7, verbose=True, check_naive=True))
+    _assert_ok(run_case(7, verbose=True, sampled=dict(seed=5)))
+
+
+def test_empty_minibatch():
+    """No target at all: every launch is skipped or empty, the outputs are empty, and the weight gradients -- sums
+    over nothing -- are exactly zero."""
+    import torch
+    from paper_2408_08490_amd.runner import Model
+    from workloads import build_graph, init_weights, make_config
+    from workloads.synth import Block, MiniBatch
+    cfg = make_config(0)
+    g = build_graph(cfg)
+    ws = init_weights(cfg, g)
+    T = g.schema.num_types
+    blk = Block([0] * T, [0] * T, np.zeros((2, 0), np.int64), np.zeros(0, np.int64), np.zeros(0, np.int32))
+    mb = MiniBatch(ids=[np.zeros(0, np.int64) for _ in range(T)], blocks=[blk], target_type=1,
+                   grad_out=[np.zeros((0, cfg.layer_out[-1]), np.float32) for _ in range(T)])
+    model = Model(g.schema, g.feat_dim, g.stores, ws, dtype="f32", loss="dot", target_type=1)
+    for w in model.weights:                              # the backward overwrites them: make that visible
+        for t in w["dw_rel"] + [x for x in w["dw_root"] if x is not None]:
+            t.fill_(7.0)
+    bt = model.prepare(mb, g.edge_type, use_edge_id=True)
+    view = bt.graph.host_view(0)
+    assert view["rows"] == 0 and view["edges"] == 0 and np.array_equal(view["rowptr"], [0])
+    out = model.run(bt)
+    torch.cuda.synchronize()
+    assert out["h"][0].numel() == 0 and out["dx"][0].numel() == 0
+    for w in model.weights:
+        for t in w["dw_rel"] + [x for x in w["dw_root"] if x is not None]:
+            assert float(t.abs().max()) == 0.0
+    model.close()
+
+
 def test_single_target_minibatch():
     """One target vertex: every tile and lane group is ragged."""
     r = run_case(1, scale=0.05, batch=1, verbose=True)

@@ -28,7 +28,7 @@ import numpy as np
 MASTER_SEED = 240808490
 CONFIG_NAMES = ["tiny_rgcn_f32", "academic_rgcn_f32", "academic_rgcn_bf16",
                 "many_types_rgcn_f32", "academic_rgat_bf16",
-                "relation_heavy_small_f32", "relation_heavy_large_bf16"]
+                "relation_heavy_small_f32", "relation_heavy_large_bf16", "widest_schema_f32"]
 
 
 # --------------------------------------------------------------------------- #
@@ -172,8 +172,11 @@ def make_config(index: int, scale: float = 1.0, batch: Optional[int] = None) -> 
         # the regime of its largest graph: ~1.9 M vertices, ~5.7 M edges, 7 vertex types, 108 relations
         c = Config(6, CONFIG_NAMES[6], "bf16", "rgcn", [128, 64], [True, False], True,
                    [10, 10], 1024, "dot")
+    elif index == 7:
+        # the widest schema the library takes: 32 vertex types, 128 relations, ragged widths, small graph
+        c = Config(7, CONFIG_NAMES[7], "f32", "rgcn", [24, 16], [True, False], True, [4, 3], 48, "dot")
     else:
-        raise ValueError("config index must be 0..6")
+        raise ValueError("config index must be 0..7")
     c.scale = scale
     if batch is not None:
         c.batch = batch
@@ -287,6 +290,19 @@ def build_graph(cfg: Config) -> HeteroGraph:
                  for s, d in zip(rel_src, rel_dst)]
         stores = [_normal_store(f, n, d) for n, d in zip(num_nodes, feat_dim)]
         return _finish_graph(schema, num_nodes, feat_dim, pairs, stores)
+    if cfg.index == 7:
+        T, n_fwd = 32, 64
+        num_nodes = [max(8, int(round(x * sc))) for x in g.integers(60, 400, T)]
+        feat_dim = [int(x) for x in g.choice([8, 16, 32, 40], T)]
+        rel_src, rel_dst, pairs = [], [], []
+        for i in range(n_fwd):
+            sT, dT = int(g.integers(0, T)), int(g.integers(0, T))
+            src, dst = _zipf_pairs(g, num_nodes[sT], num_nodes[dT], max(4, int(round(g.integers(20, 900) * sc))))
+            rel_src += [sT, dT]; rel_dst += [dT, sT]
+            pairs += [(src, dst), (dst, src)]
+        schema = Schema(T, rel_src, rel_dst)
+        stores = [_normal_store(f, n, d) for n, d in zip(num_nodes, feat_dim)]
+        return _finish_graph(schema, num_nodes, feat_dim, pairs, stores)
     if cfg.index in (5, 6):
         # Shapes only: 7 vertex types of very unequal size, 52 / 54 forward relations between random type pairs
         # plus their reverses, edge counts spread over three orders of magnitude (many relations are tiny).
@@ -313,7 +329,7 @@ def build_graph(cfg: Config) -> HeteroGraph:
 def default_target_type(cfg: Config, graph: HeteroGraph) -> int:
     if cfg.index == 0:
         return 1
-    if cfg.index in (3, 5, 6):
+    if cfg.index in (3, 5, 6, 7):
         inc = np.bincount(graph.schema.rel_dst, minlength=graph.schema.num_types)
         if cfg.index != 3:                             # a type too small to draw the batch from is no target
             inc = np.where(np.asarray(graph.num_nodes) >= cfg.batch, inc, -1)
