@@ -26,7 +26,7 @@ HBM_PEAK_GBS = 8000.0
 MFMA_BF16_PEAK_TFLOPS = 2500.0
 # HBM bytes per launch of the two probed kernels on the default workload, from the rocprofv3 --pmc runs
 # summarised under profiles/ (FETCH_SIZE + WRITE_SIZE, scaled by the copy-kernel calibration); None = not measured
-TRAFFIC_BYTES = {"gemm_fwd": 113.5e6, "spmm_fwd": 216.0e6}
+TRAFFIC_BYTES = {"gemm_fwd": 113.4e6, "spmm_fwd": 216.0e6, "gemm_dw": 257.9e6}
 
 
 def main():
@@ -147,7 +147,8 @@ def main():
     W, K = args.warmup, args.steps
     # kernels bracketed with HIP event pairs inside the timed region: the dominant kernel (forward GEMM of
     # layer 1: projection + fusion) and the aggregation kernel of layer 1, or the one asked for
-    probes = [("gemm_fwd", 0), ("spmm_fwd", 0)] if args.probe == "auto" else [(args.probe, args.probe_layer)]
+    probes = ([("gemm_fwd", 0), ("spmm_fwd", 0)] + ([] if cfg.kind == "rgat" else [("gemm_dw", 0)])
+              if args.probe == "auto" else [(k_, args.probe_layer) for k_ in args.probe.split(",")])
     pipelined(W, 0)
     torch.cuda.synchronize()
     for k_, l_ in probes:
@@ -305,21 +306,39 @@ def main():
                 k = sum(lw.in_dim[sch.rel_src[r]] for r in range(sch.num_rels) if sch.rel_dst[r] == t and live[r])
                 k += lw.in_dim[t] if lw.w_root[t] is not None else 0
                 flops += 2 * blk.n_dst[t] * k * lw.out_dim
+            label = "%s_kernel (layer %d)" % (kname, layer + 1)
+            if kname == "gemm_dw":
+                # the weight-gradient tiles share their launch with the input-gradient tiles (dZ_s = G' W_s^T for
+                # the segments whose source type wants an input gradient): count both
+                ig = model.first_layer_input_grad if layer == 0 and model.first_layer_input_grad is not None \
+                    else [1] * sch.num_types
+                fl_da = sum(2 * blk.n_dst[sch.rel_dst[r]] * lw.in_dim[sch.rel_src[r]] * lw.out_dim
+                            for r in range(sch.num_rels) if live[r] and ig[sch.rel_src[r]])
+                fl_da += sum(2 * blk.n_dst[t] * lw.in_dim[t] * lw.out_dim for t in range(sch.num_types)
+                             if lw.w_root[t] is not None and ig[t])
+                if fl_da > 0:
+                    flops += fl_da
+                    label = "gemm_bwd_kernel (layer %d: weight-gradient and input-gradient GEMM tiles in one launch)" % (layer + 1)
             ach = flops / (avg_ms * 1e-3) / 1e12 if avg_ms > 0 else 0.0
             peak = MFMA_BF16_PEAK_TFLOPS if cfg.dtype == "bf16" else 157.3
-            return dict(kernel="%s_kernel (layer %d)" % (kname, layer + 1), bound="mfma", achieved=round(ach, 1), peak=peak,
+            return dict(kernel=label, bound="mfma", achieved=round(ach, 1), peak=peak,
                         unit="TFLOP/s", frac=round(ach / peak, 4), traffic=None, algorithmic_flops=int(flops),
                         avg_kernel_us=round(avg_ms * 1e3, 2), launches_timed=probe_n)
         return dict(kernel=kname, bound="hbm", achieved=None, peak=HBM_PEAK_GBS, unit="GB/s", frac=None, traffic=None,
                     avg_kernel_us=round(avg_ms * 1e3, 2), launches_timed=probe_n)
 
-    roof = roofline_of(*probes[0])
+    roof_proj = roofline_of(*probes[0])
     roof_agg = roofline_of(*probes[1]) if len(probes) > 1 else None
+    roof_dw = roofline_of(*probes[2]) if len(probes) > 2 else None
     if roof_agg is not None:
         # HBM bytes per launch from rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE runs of this command (profiles/)
         if cfg.index == 2 and args.scale == 1.0:     # measured on the default workload only
-            roof["traffic"] = TRAFFIC_BYTES.get("gemm_fwd")
+            roof_proj["traffic"] = TRAFFIC_BYTES.get("gemm_fwd")
             roof_agg["traffic"] = TRAFFIC_BYTES.get("spmm_fwd")
+            if roof_dw is not None:
+                roof_dw["traffic"] = TRAFFIC_BYTES.get("gemm_dw")
+    # `roofline` is the dominant kernel: the longest of the probed launches (the two layer-1 GEMMs are close)
+    roof = max([r for r in (roof_proj, roof_dw) if r is not None], key=lambda r: r["avg_kernel_us"])
 
     # ablation: what each piece buys on this machine
     abl = None
@@ -431,7 +450,8 @@ def main():
                     minibatch_sizes=sizes, distinct_minibatches=len(slots)),
         gpu_only_mb_per_s=round(K / t_gpu, 2), gpu_only_ms_per_step=round(1e3 * t_gpu / K, 4),
         host_build_ms=round(1e3 * t_build, 3), sampler_in_loop=sil, training_step=train, ablation=abl, launches_per_layer=launches,
-        roofline=roof, roofline_aggregation=roof_agg, cpu_baseline=cpu, setup_s=round(t_setup, 1))
+        roofline=roof, roofline_projection=roof_proj, roofline_weight_grad=roof_dw, roofline_aggregation=roof_agg,
+        cpu_baseline=cpu, setup_s=round(t_setup, 1))
     print(json.dumps(line))
     model.close()
 

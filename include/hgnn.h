@@ -345,7 +345,9 @@ hgnn_status hgnn_adam_update_rows(hgnn_ctx *ctx, void *stream, void *store, floa
  *     kernel = hgnn_kernel_id, layer = layer index or < 0 for every layer; kernel < 0 clears the
  *     selection and discards what was collected.
  *   hgnn_probe_read(kernel, layer, ...): waits for the recorded events of that entry and returns their
- *     summed duration in milliseconds and the number of timed calls. */
+ *     summed duration in milliseconds and the number of timed calls.
+ * HGNN_K_GEMM_DW is the launch that holds the weight-gradient GEMM; in a mean layer's backward it also holds
+ * the input-gradient GEMM's tiles when both are computed (HGNN_K_GEMM_DA then times nothing). */
 typedef enum {
   HGNN_K_MERGE = 0, HGNN_K_TRANSPOSE_W = 1, HGNN_K_SPMM_FWD = 2, HGNN_K_GEMM_FWD = 3, HGNN_K_ZERO_GRADS = 4,
   HGNN_K_RELU_BIAS_BWD = 5, HGNN_K_GEMM_DW = 6, HGNN_K_GEMM_DA = 7, HGNN_K_SPMM_BWD = 8, HGNN_K_XENT = 9

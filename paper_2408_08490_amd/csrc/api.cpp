@@ -1085,6 +1085,15 @@ hgnn_status hgnn_layer_bwd(hgnn_ctx *ctx, void *stream, hgnn_graph *g, int32_t l
     if (p->relu || ldg != pl.H) gp = gpw;
   }
   const bool fast = (ldg % vec) == 0;
+  const bool want_dx = grad_x_merged && pl.dev.src_rows > 0;
+  if (want_dx)
+    for (int t = 0; t < T; ++t)
+      if ((!p->input_grad || p->input_grad[t]) && !((L.tmask >> t) & 1u) && L.n_src[t] > 0)
+        HGNN_FAIL(HGNN_EINVAL, "input gradient of type %d asked for, but the graph was built without its transpose entries", t);
+  SegTab da_tl;
+  if (want_dx) seg_tiles_da(ctx, pl, p, reo, da_tl);
+  void *dz = sc + pl.off_dz;
+  bool da_done = false;
   if (any_dw && pl.total_dst > 0) {
     // Work list: per destination type its live segments (relations with edges, then the root) and the 128-row
     // blocks of their weight gradients.  The reduction is split over destination rows so that the launch has
@@ -1119,18 +1128,19 @@ hgnn_status hgnn_layer_bwd(hgnn_ctx *ctx, void *stream, hgnn_graph *g, int32_t l
     for (int d = 0; d < T; ++d)
       tl.tile_off[d + 1] = tl.tile_off[d] + tl.u_total[d] * tiles_h * ((pl.tt.n_dst[d] + split_rows - 1) / split_rows);
     Probe pb(ctx, s, HGNN_K_GEMM_DW, layer);
-    if ((st = launch_gemm_dw(s, ctx->dtype, pl.dev, pl.tt, pl.rt, gt, tl, split_rows, pl.H, ldg, fast, x_merged, saved, gp)) != HGNN_OK) return st;
+    if (want_dx && da_tl.tile_off[da_tl.num_segs] > 0 && tl.tile_off[T] > 0) {
+      // both backward GEMMs read G' and are independent of each other: one launch
+      if ((st = launch_gemm_bwd(s, ctx->dtype, pl.dev, pl.tt, pl.rt, wpt, da_tl, gt, tl, split_rows, pl.H, ldg, fast, x_merged,
+                                saved, gp, dz)) != HGNN_OK) return st;
+      da_done = true;
+    } else if ((st = launch_gemm_dw(s, ctx->dtype, pl.dev, pl.tt, pl.rt, gt, tl, split_rows, pl.H, ldg, fast, x_merged, saved, gp)) != HGNN_OK) {
+      return st;
+    }
   }
-  if (grad_x_merged && pl.dev.src_rows > 0) {
-    for (int t = 0; t < T; ++t)
-      if ((!p->input_grad || p->input_grad[t]) && !((L.tmask >> t) & 1u) && L.n_src[t] > 0)
-        HGNN_FAIL(HGNN_EINVAL, "input gradient of type %d asked for, but the graph was built without its transpose entries", t);
-    SegTab tl;
-    seg_tiles_da(ctx, pl, p, reo, tl);
-    void *dz = sc + pl.off_dz;
-    {
+  if (want_dx) {
+    if (!da_done) {
       Probe pb(ctx, s, HGNN_K_GEMM_DA, layer);
-      if ((st = launch_gemm_da(s, ctx->dtype, pl.dev, pl.tt, pl.rt, wpt, tl, ldg, fast, gp, dz)) != HGNN_OK) return st;
+      if ((st = launch_gemm_da(s, ctx->dtype, pl.dev, pl.tt, pl.rt, wpt, da_tl, ldg, fast, gp, dz)) != HGNN_OK) return st;
     }
     Probe pb(ctx, s, HGNN_K_SPMM_BWD, layer);
     uint32_t want = 0;
@@ -1158,8 +1168,8 @@ hgnn_status hgnn_layer_launch_count(hgnn_ctx *ctx, hgnn_graph *g, int32_t layer,
   if (st != HGNN_OK) return st;
   if (fwd_launches) *fwd_launches = 1 + (pl.dev.rows > 0) + (pl.total_dst > 0);
   if (bwd_launches) {
-    // zero grads, ReLU mask + bias grad, dW GEMM, dA GEMM, transposed aggregation (+ long-row pass)
-    *bwd_launches = 1 + (pl.total_dst > 0) + (pl.total_dst > 0) + (pl.dev.src_rows > 0 ? 2 + (pl.dev.n_long > 0) : 0);
+    // zero grads, ReLU mask + bias grad, dW and dA GEMMs (one launch), transposed aggregation (+ long-row pass)
+    *bwd_launches = 1 + (pl.total_dst > 0) + (pl.total_dst > 0) + (pl.dev.src_rows > 0 ? 1 + (pl.dev.n_long > 0) : 0);
   }
   return HGNN_OK;
 }

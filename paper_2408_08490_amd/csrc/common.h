@@ -50,7 +50,7 @@ bool probe_take_events(hipEvent_t *start, hipEvent_t *stop);
   } while (0)
 
 // ---------------------------------------------------------------------------------------------
-// By-value kernel argument tables (each launch stays under the 4 KiB kernel-argument limit).
+// By-value kernel argument tables.
 // ---------------------------------------------------------------------------------------------
 struct TypeTab {
   int64_t elem_off[kMaxT + 1];     // scalars of x_merged before type t (source rows)
@@ -287,6 +287,9 @@ hgnn_status launch_bias_act(hipStream_t s, int dtype, const TypeTab &tt, const P
 // gp has leading dimension ldg >= H (zero beyond H), and so have the weights in `pt`
 hgnn_status launch_gemm_da(hipStream_t s, int dtype, const LayerDev &L, const TypeTab &tt, const RelTab &rt,
                            const PtrTab &pt, const SegTab &tiles, int ldg, bool fast, const void *gp, void *dz);
+hgnn_status launch_gemm_bwd(hipStream_t s, int dtype, const LayerDev &L, const TypeTab &tt, const RelTab &rt,
+                            const PtrTab &pt, const SegTab &da_tiles, const GradPtrTab &gt, const DwTab &dw_tiles,
+                            int split_rows, int H, int ldg, bool fast, const void *x, const void *z, const void *gp, void *dz);
 hgnn_status launch_gemm_dw(hipStream_t s, int dtype, const LayerDev &L, const TypeTab &tt, const RelTab &rt,
                            const GradPtrTab &gt, const DwTab &tiles, int split_rows, int H, int ldg, bool fast,
                            const void *x, const void *z, const void *gp);

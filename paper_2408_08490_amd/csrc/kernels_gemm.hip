@@ -143,11 +143,11 @@ __device__ __forceinline__ int find_seg(const SegTab &tiles, int tile) {
 // the weights handed in through `pt` (the caller's own when H is a multiple of 16 bytes, zero-padded copies
 // otherwise), so that the reduction simply runs over ldg.
 template <typename T, bool FAST, int MI>
-__global__ void __launch_bounds__(kThreads, MI == 1 ? 4 : 2) gemm_da_kernel(LayerDev L, TypeTab tt, RelTab rt, PtrTab pt, SegTab tiles, int ldg,
-                                                           const T *__restrict__ gp, T *__restrict__ dz) {
+__device__ __forceinline__ void da_tile(GemmLds<T, MI, MI> &sm, int bid, int nblocks, const LayerDev &L, const TypeTab &tt,
+                                        const RelTab &rt, const PtrTab &pt, const SegTab &tiles, int ldg,
+                                        const T *__restrict__ gp, T *__restrict__ dz) {
   constexpr int BM = 64 * MI, BN = 64 * MI;
-  __shared__ GemmLds<T, MI, MI> sm;
-  const int tile = xcd_tile(blockIdx.x, gridDim.x);
+  const int tile = xcd_tile(bid, nblocks);
   const int R = rt.num_rels;
   if (tile >= tiles.tile_off[tiles.num_segs]) return;
   const int seg = find_seg(tiles, tile);
@@ -179,6 +179,13 @@ __global__ void __launch_bounds__(kThreads, MI == 1 ? 4 : 2) gemm_da_kernel(Laye
              [&](float v, int row, int) { return v * sm.rowscale[row]; });
 }
 
+template <typename T, bool FAST, int MI>
+__global__ void __launch_bounds__(kThreads, MI == 1 ? 4 : 2) gemm_da_kernel(LayerDev L, TypeTab tt, RelTab rt, PtrTab pt, SegTab tiles, int ldg,
+                                                           const T *__restrict__ gp, T *__restrict__ dz) {
+  __shared__ GemmLds<T, MI, MI> sm;
+  da_tile<T, FAST, MI>(sm, blockIdx.x, gridDim.x, L, tt, rt, pt, tiles, ldg, gp, dz);
+}
+
 hgnn_status launch_gemm_da(hipStream_t s, int dtype, const LayerDev &L, const TypeTab &tt, const RelTab &rt,
                            const PtrTab &pt, const SegTab &tiles, int ldg, bool fast, const void *gp, void *dz) {
   const int n = tiles.tile_off[tiles.num_segs];
@@ -201,12 +208,12 @@ hgnn_status launch_gemm_da(hipStream_t s, int dtype, const LayerDev &L, const Ty
 // ------------------------------------------------------------------------------------------
 // dW_s += A_s^T G' over the destination-row slice [k_begin, k_end) of this block.
 template <typename T, bool FAST, int MI>
-__global__ void __launch_bounds__(kThreads, MI == 1 ? 4 : 2) gemm_dw_kernel(TypeTab tt, RelTab rt, GradPtrTab gt, DwTab tiles, XcdMap xmap, int split_rows, int H,
-                                                           int ldg, const T *__restrict__ x, const T *__restrict__ z,
-                                                           const T *__restrict__ gp) {
+__device__ __forceinline__ void dw_tile(GemmLds<T, MI, MI> &sm, int bid, const TypeTab &tt, const RelTab &rt,
+                                        const GradPtrTab &gt, const DwTab &tiles, const XcdMap &xmap, int split_rows, int H,
+                                        int ldg, const T *__restrict__ x, const T *__restrict__ z,
+                                        const T *__restrict__ gp) {
   constexpr int BM = 64 * MI, BN = 64 * MI;
-  __shared__ GemmLds<T, MI, MI> sm;
-  const int tile = xcd_tile(xmap, blockIdx.x);
+  const int tile = xcd_tile(xmap, bid);
   const int R = rt.num_rels;
   if (tile < 0) return;
   int d = 0;
@@ -240,12 +247,28 @@ __global__ void __launch_bounds__(kThreads, MI == 1 ? 4 : 2) gemm_dw_kernel(Type
   })
 }
 
-hgnn_status launch_gemm_dw(hipStream_t s, int dtype, const LayerDev &L, const TypeTab &tt, const RelTab &rt,
-                           const GradPtrTab &gt, const DwTab &tiles, int split_rows, int H, int ldg, bool fast,
-                           const void *x, const void *z, const void *gp) {
-  const int n = tiles.tile_off[tt.num_types];
-  if (n == 0) return HGNN_OK;
-  (void)L;
+template <typename T, bool FAST, int MI>
+__global__ void __launch_bounds__(kThreads, MI == 1 ? 4 : 2) gemm_dw_kernel(TypeTab tt, RelTab rt, GradPtrTab gt, DwTab tiles, XcdMap xmap, int split_rows, int H,
+                                                           int ldg, const T *__restrict__ x, const T *__restrict__ z,
+                                                           const T *__restrict__ gp) {
+  __shared__ GemmLds<T, MI, MI> sm;
+  dw_tile<T, FAST, MI>(sm, blockIdx.x, tt, rt, gt, tiles, xmap, split_rows, H, ldg, x, z, gp);
+}
+
+// Both backward GEMMs of a layer in ONE launch: the first n_dw blocks compute weight-gradient tiles (long
+// reductions), the others input-gradient tiles (short ones).  Each kernel alone leaves compute units idle at its
+// end -- the weight gradient has fewer tiles than the chip has block slots -- and the other one's tiles fill them.
+template <typename T, bool FAST>
+__global__ void __launch_bounds__(kThreads, 2) gemm_bwd_kernel(LayerDev L, TypeTab tt, RelTab rt, PtrTab pt, SegTab da_tiles,
+                                                            GradPtrTab gt, DwTab dw_tiles, XcdMap xmap, int n_dw, int split_rows,
+                                                            int H, int ldg, const T *__restrict__ x, const T *__restrict__ z,
+                                                            const T *__restrict__ gp, T *__restrict__ dz) {
+  __shared__ GemmLds<T, 2, 2> sm;
+  if ((int)blockIdx.x < n_dw) dw_tile<T, FAST, 2>(sm, blockIdx.x, tt, rt, gt, dw_tiles, xmap, split_rows, H, ldg, x, z, gp);
+  else da_tile<T, FAST, 2>(sm, blockIdx.x - n_dw, gridDim.x - n_dw, L, tt, rt, pt, da_tiles, ldg, gp, dz);
+}
+
+static int dw_blocks(int dtype, const TypeTab &tt, const DwTab &tiles, int split_rows, XcdMap &xmap) {
   // a tile's cost: the K-steps of its row slice (the average over the type's slices) plus the fixed part
   int64_t cost[kMaxT];
   const int bk = dtype == HGNN_BF16 ? Mma<bf16>::BK : Mma<float>::BK;
@@ -253,8 +276,37 @@ hgnn_status launch_gemm_dw(hipStream_t s, int dtype, const LayerDev &L, const Ty
     const int64_t slices = (tt.n_dst[d] + split_rows - 1) / split_rows;
     cost[d] = 4 + (slices > 0 ? (tt.n_dst[d] / slices + bk - 1) / bk : 0);
   }
+  return balance_xcd(tiles.tile_off, cost, tt.num_types, xmap);
+}
+
+hgnn_status launch_gemm_bwd(hipStream_t s, int dtype, const LayerDev &L, const TypeTab &tt, const RelTab &rt,
+                            const PtrTab &pt, const SegTab &da_tiles, const GradPtrTab &gt, const DwTab &dw_tiles,
+                            int split_rows, int H, int ldg, bool fast, const void *x, const void *z, const void *gp, void *dz) {
   XcdMap xmap;
-  dim3 grid(balance_xcd(tiles.tile_off, cost, tt.num_types, xmap)), blk(kThreads);
+  const int n_dw = dw_blocks(dtype, tt, dw_tiles, split_rows, xmap);
+  const int n_da = round_up8(da_tiles.tile_off[da_tiles.num_segs]);
+  dim3 grid(n_dw + n_da), blk(kThreads);
+#define HGNN_BWD(TY, FA)                                                                                             \
+  HGNN_LAUNCH((gemm_bwd_kernel<TY, FA>), grid, blk, 0, s, L, tt, rt, pt, da_tiles, gt, dw_tiles, xmap, n_dw, split_rows, H, \
+              ldg, (const TY *)x, (const TY *)z, (const TY *)gp, (TY *)dz)
+  if (dtype == HGNN_BF16) {
+    if (fast) HGNN_BWD(bf16, true); else HGNN_BWD(bf16, false);
+  } else {
+    if (fast) HGNN_BWD(float, true); else HGNN_BWD(float, false);
+  }
+#undef HGNN_BWD
+  HGNN_HIP(hipGetLastError());
+  return HGNN_OK;
+}
+
+hgnn_status launch_gemm_dw(hipStream_t s, int dtype, const LayerDev &L, const TypeTab &tt, const RelTab &rt,
+                           const GradPtrTab &gt, const DwTab &tiles, int split_rows, int H, int ldg, bool fast,
+                           const void *x, const void *z, const void *gp) {
+  const int n = tiles.tile_off[tt.num_types];
+  if (n == 0) return HGNN_OK;
+  (void)L;
+  XcdMap xmap;
+  dim3 grid(dw_blocks(dtype, tt, tiles, split_rows, xmap)), blk(kThreads);
 #define HGNN_DW(TY, FA, MI_)                                                                                  \
   HGNN_LAUNCH((gemm_dw_kernel<TY, FA, MI_>), grid, blk, 0, s, tt, rt, gt, tiles, xmap, split_rows, H, ldg, (const TY *)x, \
               (const TY *)z, (const TY *)gp)
