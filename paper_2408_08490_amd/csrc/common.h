@@ -153,7 +153,7 @@ class ThreadPool {
 struct Builder {
   ThreadPool *pool = nullptr;
   std::thread th;
-  std::vector<int32_t> key, col, rowid, hist, tkey;
+  std::vector<int32_t> key, col, hist, tkey;
   std::vector<std::vector<int32_t>> long_lists;
   std::vector<int32_t> local_of[kMaxT];  // sampler: local row of a global vertex id (-1 = not in the hop), per type
   std::vector<int64_t> hop_ids[2][kMaxT], edge_dst;  // sampler: destination / source lists of the current hop

@@ -140,12 +140,11 @@ static bool build_layer(hgnn_ctx *ctx, Builder &bd, hgnn_graph *g, int l, BuildE
   };
   grow(bd.key, (size_t)E);
   grow(bd.col, (size_t)E);
-  grow(bd.rowid, (size_t)E);
   grow(bd.tkey, (size_t)E * 3);  // level-1 records: (key, item, payload)
   // counter rows are padded to whole 128-byte lines: neighbouring threads must not share a line
   const size_t S1 = ((size_t)B1 + 63) / 32 * 32, S2 = ((size_t)B2 + 63) / 32 * 32;
   grow(bd.hist, (size_t)P * S1 + (size_t)std::max(B1, 1) * S2 + B1 + B2 + 2 + 64);
-  int32_t *key = bd.key.data(), *col = bd.col.data(), *rowid = bd.rowid.data();
+  int32_t *key = bd.key.data(), *col = bd.col.data();
   int32_t *trec = bd.tkey.data();
   int32_t *cnt1 = reinterpret_cast<int32_t *>((reinterpret_cast<uintptr_t>(bd.hist.data()) + 127) & ~(uintptr_t)127);  // [P][S1]
   int32_t *cnt2 = cnt1 + (size_t)P * S1;                     // [B1][S2]
@@ -277,7 +276,6 @@ static bool build_layer(hgnn_ctx *ctx, Builder &bd, hgnn_graph *g, int l, BuildE
       const int32_t pos = h[k - k0]++;
       colidx[pos] = c;
       perm[pos] = e;
-      rowid[pos] = k;
       if (wanted(c)) ++c2[c >> kBucketShift];
     }
   });
@@ -301,13 +299,16 @@ static bool build_layer(hgnn_ctx *ctx, Builder &bd, hgnn_graph *g, int l, BuildE
   }
   pool.parallel_for(B1, [&](int b1) {
     int32_t *off = cnt2 + (size_t)b1 * S2;
+    // the merged row of CSR position k: positions are walked in order, so the row pointer is walked along
+    int32_t row = b1 << kBucketShift;
     for (int32_t k = base1[b1]; k < base1[b1 + 1]; ++k) {
+      while (rowptr[row + 1] <= k) ++row;
       if (!wanted(colidx[k])) continue;
       const int32_t q = off[colidx[k] >> kBucketShift]++;
       int32_t *rec = trec + (size_t)q * 3;
       rec[0] = colidx[k];
       rec[1] = k;
-      rec[2] = rowid[k];
+      rec[2] = row;
     }
   });
   tm.lap("csc level-1 scatter");
