@@ -118,7 +118,8 @@ typedef struct {
 /* Registers the graph's global edge-type table (Algorithm 2's EdgeType, one entry per edge of the whole graph):
  * the context keeps a compact copy (one byte per edge), so that later hgnn_coo_layer entries may pass edge_id
  * alone.  The look-up EdgeType[EdgeID] is a random access per sampled edge; the compact table keeps most of it
- * in the host caches.  Host array, copied (may be freed afterwards); entries outside [0, num_rels) are an
+ * in the host caches (and a table made of a few runs of equal type is searched by its run boundaries
+ * instead).  Host array, copied (may be freed afterwards); entries outside [0, num_rels) are an
  * error.  Replaces an earlier table; must not be called while builds are in flight. */
 hgnn_status hgnn_set_edge_types(hgnn_ctx *ctx, const int32_t *global_edge_type, int64_t num_global_edges);
 

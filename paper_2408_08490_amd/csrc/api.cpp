@@ -593,6 +593,23 @@ hgnn_status hgnn_merge_features(hgnn_ctx *ctx, void *stream, const void *const *
 
 extern "C++" {
 namespace hgnn {
+constexpr size_t kMaxTypeRuns = 32;
+void index_edge_type_runs(hgnn_ctx *ctx) {
+  ctx->run_end.clear();
+  ctx->run_rel.clear();
+  const std::vector<uint8_t> &t = ctx->edge_types8;
+  for (size_t i = 0; i < t.size(); ++i)
+    if (i + 1 == t.size() || t[i + 1] != t[i]) {
+      ctx->run_end.push_back((int64_t)i + 1);
+      ctx->run_rel.push_back(t[i]);
+      if (ctx->run_end.size() > kMaxTypeRuns) {  // not grouped by relation: the byte table it is
+        ctx->run_end.clear();
+        ctx->run_rel.clear();
+        return;
+      }
+    }
+}
+
 // Validates the layers' inputs (g->L[l].in), lays the index arrays out in one block and takes a pinned/device
 // block and an event from the context's pool (or allocates them).  Runs on the caller's thread for
 // hgnn_build_semantic_csr and on a builder's thread for sampled mini-batches, hence the message by reference.
@@ -838,6 +855,7 @@ hgnn_status hgnn_set_edge_types(hgnn_ctx *ctx, const int32_t *global_edge_type, 
     t[(size_t)i] = (uint8_t)r;
   }
   ctx->edge_types8.swap(t);
+  index_edge_type_runs(ctx);
   return HGNN_OK;
 }
 

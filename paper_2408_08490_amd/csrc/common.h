@@ -213,6 +213,11 @@ struct hgnn_ctx {
   std::vector<hgnn::Slab> free_slabs;
   std::vector<hipEvent_t> free_events;
   std::vector<uint8_t> edge_types8;  // compact copy of the registered global edge-type table
+  // the same table as runs of equal type, kept when there are few of them (edge ids grouped by relation, the usual
+  // case): type of id = run_rel[number of run_end entries <= id]; a search over a handful of cached boundaries
+  // replaces a random read into a table far larger than the caches
+  std::vector<int64_t> run_end;
+  std::vector<uint8_t> run_rel;
   std::vector<std::unique_ptr<hgnn::SampleJob>> free_jobs;  // released sampled mini-batches: their buffers are reused (pm)
   // kernel probe (measurement aid)
   int probe_sel[4][2];  // selected (kernel, layer) pairs
@@ -234,6 +239,7 @@ static inline int lanes_log2_for(int max_dim, int esize) {
 
 void build_graph_job(hgnn_ctx *ctx, Builder &b, hgnn_graph *g);  // host_build.cpp
 hgnn_status plan_graph(hgnn_ctx *ctx, hgnn_graph *g, std::string &msg);  // api.cpp
+void index_edge_type_runs(hgnn_ctx *ctx);                                   // api.cpp: fills run_end / run_rel
 hgnn_status run_sample_job(hgnn_ctx *ctx, Builder &b, hgnn_graph *g, std::string &msg);  // sampler.cpp
 
 // ---- kernel launchers (kernels_*.hip); all enqueue on `s` and return ----

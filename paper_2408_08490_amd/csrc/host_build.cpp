@@ -164,10 +164,23 @@ static bool build_layer(hgnn_ctx *ctx, Builder &bd, hgnn_graph *g, int l, BuildE
     int32_t *cnt = cnt1 + (size_t)p * S1;
     const uint8_t *types8 = ctx->edge_types8.data();
     const int64_t n_types8 = (int64_t)ctx->edge_types8.size();
+    const int nruns = (int)ctx->run_end.size();
+    const int64_t *run_end = ctx->run_end.data();
+    const uint8_t *run_rel = ctx->run_rel.data();
     for (int64_t e = a; e < b; ++e) {
       int64_t r;
       if (in.edge_type) {
         r = in.edge_type[e];
+      } else if (!in.global_edge_type && nruns > 0) {   // the registered table, as runs of equal type
+        const int64_t id = in.edge_id[e];
+        if (id < 0 || id >= n_types8) {
+          err.set(HGNN_EINVAL, "layer " + std::to_string(l) + ": edge_id[" + std::to_string(e) + "]=" +
+                                   std::to_string(id) + " outside the registered edge-type table");
+          return;
+        }
+        int j = 0;
+        for (int q = 0; q + 1 < nruns; ++q) j += id >= run_end[q];
+        r = run_rel[j];
       } else if (!in.global_edge_type) {   // the registered compact table
         if (e + 48 < b) {
           const int64_t nid = in.edge_id[e + 48];

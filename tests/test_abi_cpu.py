@@ -40,15 +40,27 @@ def _host_ctx(B, sch, dtype="f32", threads=4, concurrent_builds=0):
 
 @pytest.mark.parametrize("index,scale,threads", [(0, 1.0, 1), (0, 1.0, 4), (2, 0.02, 8), (3, 0.003, 3), (5, 1.0, 2),
                                                  (6, 0.1, 4), (7, 1.0, 3)])
-@pytest.mark.parametrize("use_edge_id", [False, True, "registered"])
+@pytest.mark.parametrize("use_edge_id", [False, True, "registered", "registered_interleaved"])
 def test_host_build_bit_exact(B, index, scale, threads, use_edge_id):
     cfg = make_config(index, scale=scale, batch=96)
     g = build_graph(cfg)
     mb = sample_minibatch(cfg, g)
     ctx = _host_ctx(B, g.schema, threads=threads)
     if use_edge_id == "registered":                 # edge ids alone, types from the table the context keeps
-        ctx.hgnn_set_edge_types(g.edge_type)
+        ctx.hgnn_set_edge_types(g.edge_type)        # (ids grouped by relation: few runs of equal type)
         gr = ctx.hgnn_build_semantic_csr(mb.blocks, None, use_edge_id=True)
+    elif use_edge_id == "registered_interleaved":   # the same through renumbered ids: types alternate all along
+        import copy
+        p = np.random.default_rng(3).permutation(g.edge_type.size)
+        table = np.empty_like(g.edge_type)
+        table[p] = g.edge_type
+        ctx.hgnn_set_edge_types(table)
+        blocks = []
+        for b in mb.blocks:
+            b2 = copy.copy(b)
+            b2.edge_id = p[b.edge_id]
+            blocks.append(b2)
+        gr = ctx.hgnn_build_semantic_csr(blocks, None, use_edge_id=True)
     else:
         gr = ctx.hgnn_build_semantic_csr(mb.blocks, g.edge_type, use_edge_id=use_edge_id)
     gr.wait()
