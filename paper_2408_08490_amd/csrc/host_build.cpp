@@ -310,18 +310,38 @@ static bool build_layer(hgnn_ctx *ctx, Builder &bd, hgnn_graph *g, int l, BuildE
     }
     base2[B2] = run;
   }
+  // All sources of a relation have one type, and the CSR is ordered by relation: the positions whose source row
+  // is wanted are whole relation ranges, so the others are skipped without being read.
+  int n_pr = 0;
+  int32_t pr_lo[kMaxR], pr_hi[kMaxR];
+  for (int r = 0; r < R; ++r) {
+    if (!((L.tmask >> ctx->rel_src[r]) & 1u) || rel_edge_off[r + 1] == rel_edge_off[r]) continue;
+    if (n_pr > 0 && pr_hi[n_pr - 1] == rel_edge_off[r]) pr_hi[n_pr - 1] = rel_edge_off[r + 1];
+    else { pr_lo[n_pr] = rel_edge_off[r]; pr_hi[n_pr] = rel_edge_off[r + 1]; ++n_pr; }
+  }
   pool.parallel_for(B1, [&](int b1) {
     int32_t *off = cnt2 + (size_t)b1 * S2;
-    // the merged row of CSR position k: positions are walked in order, so the row pointer is walked along
-    int32_t row = b1 << kBucketShift;
-    for (int32_t k = base1[b1]; k < base1[b1 + 1]; ++k) {
-      while (rowptr[row + 1] <= k) ++row;
-      if (!wanted(colidx[k])) continue;
-      const int32_t q = off[colidx[k] >> kBucketShift]++;
-      int32_t *rec = trec + (size_t)q * 3;
-      rec[0] = colidx[k];
-      rec[1] = k;
-      rec[2] = row;
+    for (int i = 0; i < n_pr; ++i) {
+      const int32_t ka = std::max(base1[b1], pr_lo[i]), kb = std::min(base1[b1 + 1], pr_hi[i]);
+      if (ka >= kb) continue;
+      // the merged row of CSR position k: positions are walked in order, so the row pointer is walked along
+      int32_t row = b1 << kBucketShift;
+      {  // first row of the bucket that ends after ka
+        int32_t hi = (int32_t)std::min<int64_t>(rows, (int64_t)(b1 + 1) << kBucketShift);
+        while (row + 1 < hi) {
+          const int32_t mid = row + (hi - row) / 2;
+          if (rowptr[mid] <= ka) row = mid; else hi = mid;
+        }
+      }
+      for (int32_t k = ka; k < kb; ++k) {
+        while (rowptr[row + 1] <= k) ++row;
+        const int32_t c = colidx[k];
+        const int32_t q = off[c >> kBucketShift]++;
+        int32_t *rec = trec + (size_t)q * 3;
+        rec[0] = c;
+        rec[1] = k;
+        rec[2] = row;
+      }
     }
   });
   tm.lap("csc level-1 scatter");
