@@ -172,7 +172,9 @@ typedef struct {
   const int32_t *const *in_nbr;    /* [R] -> [edge_off[r+1] - edge_off[r]] source vertex ids */
   const int64_t *edge_off;         /* [R+1] */
 } hgnn_host_graph;
-/* Also registers the graph's edge-type table with the context (as hgnn_set_edge_types would). */
+/* Also registers the graph's edge-type table with the context (as hgnn_set_edge_types would, and like it
+ * not while builds are in flight).  A sampler must outlive every graph made from it that is still being
+ * built (hgnn_graph_wait has not returned yet). */
 hgnn_status hgnn_sampler_create(hgnn_ctx *ctx, const hgnn_host_graph *graph, hgnn_sampler **out);
 void hgnn_sampler_destroy(hgnn_ctx *ctx, hgnn_sampler *s);
 /* Enqueues ONE task for the context's host threads: layer-wise neighbour sampling of the
