@@ -256,7 +256,7 @@ def main():
         sil = dict(value=round(K / t_sil, 2), unit="mini-batches/s", ms_per_step=round(1e3 * t_sil / K, 4),
                    host_task_ms=round(1e3 * t_task, 3), host_tasks_in_parallel=nb_conc,
                    cpu_gpu_time_ratio=round((t_task / nb_conc) / (t_gpu / K), 3),
-                   note="neighbour sampling + edge index selection + upload per step on the host threads, fresh "
+                   note="neighbour sampling + index arrays + upload per step on the host threads, fresh "
                         "targets every step; cpu_gpu_time_ratio = host time per mini-batch at that parallelism / "
                         "GPU time per mini-batch")
         sampler.close()

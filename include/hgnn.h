@@ -178,9 +178,11 @@ typedef struct {
 hgnn_status hgnn_sampler_create(hgnn_ctx *ctx, const hgnn_host_graph *graph, hgnn_sampler **out);
 void hgnn_sampler_destroy(hgnn_ctx *ctx, hgnn_sampler *s);
 /* Enqueues ONE task for the context's host threads: layer-wise neighbour sampling of the
- * mini-batch of `targets` (distinct vertices of type target_type; copied), then the build of
- * hgnn_build_semantic_csr on the sampled edges (edge ids, types through the registered table),
- * then the upload, which also carries the global ids of the first layer's source rows.
+ * mini-batch of `targets` (distinct vertices of type target_type; copied), then the index arrays
+ * hgnn_build_semantic_csr would make of the sampled lists -- the sampler emits its edges relation
+ * by relation with destinations ascending, which IS the merged CSR order, so nothing is looked up
+ * or sorted for it; the transpose is built as usual -- then the upload, which also carries the
+ * global ids of the first layer's source rows.
  * fanouts[h-1] = neighbours kept per destination vertex and relation in hop h, hop 1 nearest the
  * targets; the block of hop h feeds layer num_layers - h + 1.  transpose_types: NULL, or per
  * layer NULL or [T] as in hgnn_coo_layer.

@@ -170,6 +170,7 @@ struct SampleJob {
   std::vector<int32_t> transpose[kMaxLayers];   // per layer: empty (= all types) or [T]
   std::vector<int64_t> edge_index[kMaxLayers];  // [2 x E]: local source, local destination
   std::vector<int64_t> edge_id[kMaxLayers];
+  int64_t rel_edge_off[kMaxLayers][kMaxR + 1];  // edges of relation r in a layer's lists: [rel_edge_off[r], rel_edge_off[r+1])
   int64_t n_src[kMaxLayers][kMaxT], n_dst[kMaxLayers][kMaxT];
   std::vector<int64_t> ids[kMaxT];              // global ids of the first layer's source rows
 };

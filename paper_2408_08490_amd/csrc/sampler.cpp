@@ -66,6 +66,7 @@ hgnn_status run_sample_job(hgnn_ctx *ctx, Builder &bd, hgnn_graph *g, std::strin
     for (int r = 0; r < R && st == HGNN_OK; ++r) {
       const int s = ctx->rel_src[r], d = ctx->rel_dst[r];
       const int64_t nd = (int64_t)dst[d].size();
+      job.rel_edge_off[l][r] = (int64_t)eid.size();
       if (nd == 0) continue;
       const int64_t *ptr = sm.in_indptr[r];
       const int32_t *nbr = sm.in_nbr[r];
@@ -132,6 +133,7 @@ hgnn_status run_sample_job(hgnn_ctx *ctx, Builder &bd, hgnn_graph *g, std::strin
       }
     }
     // this hop's block; the lookup tables go back to "not in the hop"
+    job.rel_edge_off[l][R] = (int64_t)eid.size();
     es.insert(es.end(), ed.begin(), ed.end());
     for (int t = 0; t < T; ++t) {
       job.n_src[l][t] = (int64_t)src[t].size();
