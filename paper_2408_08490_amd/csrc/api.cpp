@@ -608,6 +608,13 @@ void index_edge_type_runs(hgnn_ctx *ctx) {
         return;
       }
     }
+  ctx->run_shift = 0;
+  while ((t.size() >> ctx->run_shift) > 1024) ++ctx->run_shift;
+  ctx->run_lut.assign((t.size() >> ctx->run_shift) + 1, 0);
+  for (size_t b = 0, j = 0; b < ctx->run_lut.size(); ++b) {
+    while (j + 1 < ctx->run_end.size() && (int64_t)(b << ctx->run_shift) >= ctx->run_end[j]) ++j;
+    ctx->run_lut[b] = (uint8_t)j;
+  }
 }
 
 // Validates the layers' inputs (g->L[l].in), lays the index arrays out in one block and takes a pinned/device

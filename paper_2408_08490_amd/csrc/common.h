@@ -215,10 +215,12 @@ struct hgnn_ctx {
   std::vector<hipEvent_t> free_events;
   std::vector<uint8_t> edge_types8;  // compact copy of the registered global edge-type table
   // the same table as runs of equal type, kept when there are few of them (edge ids grouped by relation, the usual
-  // case): type of id = run_rel[number of run_end entries <= id]; a search over a handful of cached boundaries
-  // replaces a random read into a table far larger than the caches
+  // case): type of id = run_rel[j], j = the run that holds id, found from run_lut[id >> run_shift] (the run in which
+  // that block of ids starts) by stepping over at most the few boundaries inside the block; a few hundred cached
+  // bytes replace a random read into a table far larger than the caches
   std::vector<int64_t> run_end;
-  std::vector<uint8_t> run_rel;
+  std::vector<uint8_t> run_rel, run_lut;
+  int run_shift = 0;
   std::vector<std::unique_ptr<hgnn::SampleJob>> free_jobs;  // released sampled mini-batches: their buffers are reused (pm)
   // kernel probe (measurement aid)
   int probe_sel[4][2];  // selected (kernel, layer) pairs

@@ -208,7 +208,8 @@ static bool build_layer(hgnn_ctx *ctx, Builder &bd, hgnn_graph *g, int l, BuildE
     const int64_t n_types8 = (int64_t)ctx->edge_types8.size();
     const int nruns = (int)ctx->run_end.size();
     const int64_t *run_end = ctx->run_end.data();
-    const uint8_t *run_rel = ctx->run_rel.data();
+    const uint8_t *run_rel = ctx->run_rel.data(), *run_lut = ctx->run_lut.data();
+    const int run_shift = ctx->run_shift;
     for (int64_t e = a; e < b; ++e) {
       int64_t r;
       if (in.edge_type) {
@@ -220,8 +221,8 @@ static bool build_layer(hgnn_ctx *ctx, Builder &bd, hgnn_graph *g, int l, BuildE
                                    std::to_string(id) + " outside the registered edge-type table");
           return;
         }
-        int j = 0;
-        for (int q = 0; q + 1 < nruns; ++q) j += id >= run_end[q];
+        int j = run_lut[id >> run_shift];
+        while (id >= run_end[j]) ++j;  // ends: id < n_types8 = the last run's end
         r = run_rel[j];
       } else if (!in.global_edge_type) {   // the registered compact table
         if (e + 48 < b) {
