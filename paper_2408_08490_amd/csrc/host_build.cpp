@@ -311,14 +311,12 @@ static bool build_layer(hgnn_ctx *ctx, Builder &bd, hgnn_graph *g, int l, BuildE
       rowptr[k0 + i] = run;
       run += t;
     }
-    int32_t *c2 = cnt2 + (size_t)b * S2;
     for (int32_t j = ja; j < jb; ++j) {
       const int32_t *rec = trec + (size_t)j * 3;
       const int32_t k = rec[0], e = rec[1], c = rec[2];
       const int32_t pos = h[k - k0]++;
       colidx[pos] = c;
       perm[pos] = e;
-      if (wanted(c)) ++c2[c >> kBucketShift];
     }
   });
   tm.lap("csr level-2 buckets");
@@ -326,6 +324,26 @@ static bool build_layer(hgnn_ctx *ctx, Builder &bd, hgnn_graph *g, int l, BuildE
   rowptr[rows] = (int32_t)E;
   for (int r = 0; r <= R; ++r) rel_edge_off[r] = rowptr[rel_row_off[r]];
 
+  // All sources of a relation have one type, and the CSR is ordered by relation: the positions whose source row
+  // is wanted are whole relation ranges, so the others are skipped without being read.
+  int n_pr = 0;
+  int32_t pr_lo[kMaxR], pr_hi[kMaxR];
+  for (int r = 0; r < R; ++r) {
+    if (!((L.tmask >> ctx->rel_src[r]) & 1u) || rel_edge_off[r + 1] == rel_edge_off[r]) continue;
+    if (n_pr > 0 && pr_hi[n_pr - 1] == rel_edge_off[r]) pr_hi[n_pr - 1] = rel_edge_off[r + 1];
+    else { pr_lo[n_pr] = rel_edge_off[r]; pr_hi[n_pr] = rel_edge_off[r + 1]; ++n_pr; }
+  }
+  // level-1 counts of the transpose: per CSR bucket, how many of its wanted positions fall into each bucket of
+  // source rows (a sweep of its own over the wanted ranges: inside the scatter loop above the test "is this
+  // source row wanted" is a coin flip for the branch predictor and cost more than the whole sweep)
+  if (!presorted)
+    pool.parallel_for(B1, [&](int b1) {
+      int32_t *c2 = cnt2 + (size_t)b1 * S2;
+      for (int i = 0; i < n_pr; ++i) {
+        const int32_t ka = std::max(base1[b1], pr_lo[i]), kb = std::min(base1[b1 + 1], pr_hi[i]);
+        for (int32_t k = ka; k < kb; ++k) ++c2[colidx[k] >> kBucketShift];
+      }
+    });
   // ---- transpose: CSR positions grouped by source row, ascending position inside a group ----
   // the level-1 slices are the CSR position ranges of the buckets above (already in CSR order)
   {
@@ -339,15 +357,6 @@ static bool build_layer(hgnn_ctx *ctx, Builder &bd, hgnn_graph *g, int l, BuildE
       }
     }
     base2[B2] = run;
-  }
-  // All sources of a relation have one type, and the CSR is ordered by relation: the positions whose source row
-  // is wanted are whole relation ranges, so the others are skipped without being read.
-  int n_pr = 0;
-  int32_t pr_lo[kMaxR], pr_hi[kMaxR];
-  for (int r = 0; r < R; ++r) {
-    if (!((L.tmask >> ctx->rel_src[r]) & 1u) || rel_edge_off[r + 1] == rel_edge_off[r]) continue;
-    if (n_pr > 0 && pr_hi[n_pr - 1] == rel_edge_off[r]) pr_hi[n_pr - 1] = rel_edge_off[r + 1];
-    else { pr_lo[n_pr] = rel_edge_off[r]; pr_hi[n_pr] = rel_edge_off[r + 1]; ++n_pr; }
   }
   pool.parallel_for(B1, [&](int b1) {
     int32_t *off = cnt2 + (size_t)b1 * S2;
