@@ -104,6 +104,27 @@ constexpr int kBucketShift = 12;  // 4096 consecutive keys form one bucket (its 
 // row).  Level 1 splits the items into key-range buckets (threads own contiguous item slices, so the
 // order inside a bucket is the input order); level 2 sorts every bucket on its own with a local
 // histogram and writes the final arrays and the bucket's part of the row pointer.
+// A level-1 record carries (key, item, payload).  Wide: three ints.  Packed: two ints -- only the key's offset
+// inside its bucket is needed once the record lies in the bucket, and it fits above the payload when the
+// payload stays below 2^(32 - kBucketShift): a third less to write, to fetch for ownership and to read back.
+struct WideRec {
+  static constexpr int W = 3;
+  static void put(int32_t *r, int32_t key, int32_t item, int32_t payload) { r[0] = key; r[1] = item; r[2] = payload; }
+  static int32_t key_low(const int32_t *r, int32_t k0) { return r[0] - k0; }
+  static int32_t item(const int32_t *r) { return r[1]; }
+  static int32_t payload(const int32_t *r) { return r[2]; }
+};
+struct PackedRec {
+  static constexpr int W = 2, kPayloadBits = 32 - kBucketShift;
+  static void put(int32_t *r, int32_t key, int32_t item, int32_t payload) {
+    r[0] = item;
+    r[1] = (int32_t)(((uint32_t)key << kPayloadBits) | (uint32_t)payload);  // the shift drops the bucket's bits
+  }
+  static int32_t key_low(const int32_t *r, int32_t) { return (int32_t)((uint32_t)r[1] >> kPayloadBits); }
+  static int32_t item(const int32_t *r) { return r[0]; }
+  static int32_t payload(const int32_t *r) { return (int32_t)((uint32_t)r[1] & ((1u << kPayloadBits) - 1u)); }
+};
+
 struct PhaseTimer {
   bool on;
   std::chrono::steady_clock::time_point t0;
@@ -171,6 +192,9 @@ static bool build_layer(hgnn_ctx *ctx, Builder &bd, hgnn_graph *g, int l, BuildE
   // A mini-batch drawn by the library's own sampler arrives relation by relation, destinations ascending, and
   // its edges were read off the graph: there is nothing to look up, check or sort -- the merged CSR is the input
   // order itself.
+  // (a test can ask for the three-int records where the two-int ones would do)
+  static const bool wide_records = getenv("HGNN_WIDE_RECORDS") != nullptr;
+  const bool csc_packed = rows <= (int64_t)1 << PackedRec::kPayloadBits && !wide_records;
   const bool presorted = g->job != nullptr;
   if (presorted) {
     const SampleJob &job = *g->job;
@@ -285,41 +309,42 @@ static bool build_layer(hgnn_ctx *ctx, Builder &bd, hgnn_graph *g, int l, BuildE
     }
     base1[B1] = run;
   }
-  pool.parallel_for(P, [&](int p) {
-    const int64_t a = std::min<int64_t>(E, p * slice), b = std::min<int64_t>(E, a + slice);
-    int32_t *off = cnt1 + (size_t)p * S1;
-    for (int64_t e = a; e < b; ++e) {
-      const int32_t q = off[key[e] >> kBucketShift]++;
-      int32_t *rec = trec + (size_t)q * 3;
-      rec[0] = key[e];
-      rec[1] = (int32_t)e;
-      rec[2] = col[e];
-    }
-  });
-  tm.lap("csr level-1 scatter");
-  pool.parallel_for(B1, [&](int b) {
-    int32_t h[(1 << kBucketShift) + 1];
-    const int32_t k0 = b << kBucketShift;
-    const int32_t nk = (int32_t)std::min<int64_t>(1 << kBucketShift, rows - k0);
-    std::memset(h, 0, sizeof(int32_t) * (nk + 1));
-    const int32_t ja = base1[b], jb = base1[b + 1];
-    for (int32_t j = ja; j < jb; ++j) ++h[trec[(size_t)j * 3] - k0];
-    int32_t run = ja;
-    for (int32_t i = 0; i < nk; ++i) {
-      const int32_t t = h[i];
-      h[i] = run;
-      rowptr[k0 + i] = run;
-      run += t;
-    }
-    for (int32_t j = ja; j < jb; ++j) {
-      const int32_t *rec = trec + (size_t)j * 3;
-      const int32_t k = rec[0], e = rec[1], c = rec[2];
-      const int32_t pos = h[k - k0]++;
-      colidx[pos] = c;
-      perm[pos] = e;
-    }
-  });
-  tm.lap("csr level-2 buckets");
+  auto csr_sort = [&](auto rec_format) {
+    using Rec = decltype(rec_format);
+    pool.parallel_for(P, [&](int p) {
+      const int64_t a = std::min<int64_t>(E, p * slice), b = std::min<int64_t>(E, a + slice);
+      int32_t *off = cnt1 + (size_t)p * S1;
+      for (int64_t e = a; e < b; ++e) {
+        const int32_t q = off[key[e] >> kBucketShift]++;
+        Rec::put(trec + (size_t)q * Rec::W, key[e], (int32_t)e, col[e]);
+      }
+    });
+    tm.lap("csr level-1 scatter");
+    pool.parallel_for(B1, [&](int b) {
+      int32_t h[(1 << kBucketShift) + 1];
+      const int32_t k0 = b << kBucketShift;
+      const int32_t nk = (int32_t)std::min<int64_t>(1 << kBucketShift, rows - k0);
+      std::memset(h, 0, sizeof(int32_t) * (nk + 1));
+      const int32_t ja = base1[b], jb = base1[b + 1];
+      for (int32_t j = ja; j < jb; ++j) ++h[Rec::key_low(trec + (size_t)j * Rec::W, k0)];
+      int32_t run = ja;
+      for (int32_t i = 0; i < nk; ++i) {
+        const int32_t t = h[i];
+        h[i] = run;
+        rowptr[k0 + i] = run;
+        run += t;
+      }
+      for (int32_t j = ja; j < jb; ++j) {
+        const int32_t *rec = trec + (size_t)j * Rec::W;
+        const int32_t pos = h[Rec::key_low(rec, k0)]++;
+        colidx[pos] = Rec::payload(rec);
+        perm[pos] = Rec::item(rec);
+      }
+    });
+    tm.lap("csr level-2 buckets");
+  };
+  if (src_rows <= (int64_t)1 << PackedRec::kPayloadBits && !wide_records) csr_sort(PackedRec());
+  else csr_sort(WideRec());
   }
   rowptr[rows] = (int32_t)E;
   for (int r = 0; r <= R; ++r) rel_edge_off[r] = rowptr[rel_row_off[r]];
@@ -376,39 +401,42 @@ static bool build_layer(hgnn_ctx *ctx, Builder &bd, hgnn_graph *g, int l, BuildE
         while (rowptr[row + 1] <= k) ++row;
         const int32_t c = colidx[k];
         const int32_t q = off[c >> kBucketShift]++;
-        int32_t *rec = trec + (size_t)q * 3;
-        rec[0] = c;
-        rec[1] = k;
-        rec[2] = row;
+        if (csc_packed) PackedRec::put(trec + (size_t)q * PackedRec::W, c, k, row);
+        else WideRec::put(trec + (size_t)q * WideRec::W, c, k, row);
       }
     }
   });
   tm.lap("csc level-1 scatter");
   std::vector<std::vector<int32_t>> &longs = bd.long_lists;
   if ((int)longs.size() < B2) longs.resize(B2);
-  pool.parallel_for(B2, [&](int b) {
-    int32_t h[(1 << kBucketShift) + 1];
-    const int32_t k0 = b << kBucketShift;
-    const int32_t nk = (int32_t)std::min<int64_t>(1 << kBucketShift, src_rows - k0);
-    std::memset(h, 0, sizeof(int32_t) * (nk + 1));
-    const int32_t ja = base2[b], jb = base2[b + 1];
-    for (int32_t j = ja; j < jb; ++j) ++h[trec[(size_t)j * 3] - k0];
-    int32_t run = ja;
-    longs[b].clear();
-    for (int32_t i = 0; i < nk; ++i) {
-      const int32_t t = h[i];
-      if (t > kLongRow) longs[b].push_back(k0 + i);
-      h[i] = run;
-      cptr[k0 + i] = run;
-      run += t;
-    }
-    for (int32_t j = ja; j < jb; ++j) {
-      const int32_t *rec = trec + (size_t)j * 3;
-      const int32_t pos = h[rec[0] - k0]++;
-      crow[pos] = rec[2];
-      cperm[pos] = rec[1];
-    }
-  });
+  auto csc_level2 = [&](auto rec_format) {
+    using Rec = decltype(rec_format);
+    pool.parallel_for(B2, [&](int b) {
+      int32_t h[(1 << kBucketShift) + 1];
+      const int32_t k0 = b << kBucketShift;
+      const int32_t nk = (int32_t)std::min<int64_t>(1 << kBucketShift, src_rows - k0);
+      std::memset(h, 0, sizeof(int32_t) * (nk + 1));
+      const int32_t ja = base2[b], jb = base2[b + 1];
+      for (int32_t j = ja; j < jb; ++j) ++h[Rec::key_low(trec + (size_t)j * Rec::W, k0)];
+      int32_t run = ja;
+      longs[b].clear();
+      for (int32_t i = 0; i < nk; ++i) {
+        const int32_t t = h[i];
+        if (t > kLongRow) longs[b].push_back(k0 + i);
+        h[i] = run;
+        cptr[k0 + i] = run;
+        run += t;
+      }
+      for (int32_t j = ja; j < jb; ++j) {
+        const int32_t *rec = trec + (size_t)j * Rec::W;
+        const int32_t pos = h[Rec::key_low(rec, k0)]++;
+        crow[pos] = Rec::payload(rec);
+        cperm[pos] = Rec::item(rec);
+      }
+    });
+  };
+  if (csc_packed) csc_level2(PackedRec());
+  else csc_level2(WideRec());
   cptr[src_rows] = base2[B2];
   L.tedges = base2[B2];
   tm.lap("csc level-2 buckets");

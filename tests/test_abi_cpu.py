@@ -362,3 +362,29 @@ def test_sampler_errors(B):
         ctx.hgnn_sampler_create(g.num_nodes, bad, g.in_nbr, g.edge_off)
     sm.close()
     ctx.close()
+
+
+def test_host_build_three_int_records():
+    """The sort's level-1 records take two ints where the payload fits 20 bits and three otherwise; no test graph is
+    large enough for the latter, so a child process asks for it and repeats a bit-exact comparison."""
+    import subprocess
+    import sys
+    code = (
+        "import numpy as np\n"
+        "from oracle import hgnn_oracle as O\n"
+        "from paper_2408_08490_amd import binding as B\n"
+        "from workloads import make_config, build_graph, sample_minibatch\n"
+        "cfg = make_config(2, scale=0.02, batch=96); g = build_graph(cfg); mb = sample_minibatch(cfg, g)\n"
+        "ctx = B.Context(g.schema.rel_src, g.schema.rel_dst, g.schema.num_types, 'f32', device=-1, host_threads=3)\n"
+        "gr = ctx.hgnn_build_semantic_csr(mb.blocks, g.edge_type, use_edge_id=True, transpose_types=[[0, 1, 1, 1], None])\n"
+        "for l, b in enumerate(mb.blocks):\n"
+        "    sel = O.edge_index_select(b.edge_index, g.schema.num_rels, edge_type=b.edge_type)\n"
+        "    ref = O.semantic_csr(sel, g.schema.rel_src, g.schema.rel_dst, b.n_src, b.n_dst,\n"
+        "                         transpose_types=[0, 1, 1, 1] if l == 0 else None)\n"
+        "    v = gr.host_view(l)\n"
+        "    for k in ('rowptr', 'colidx', 'perm', 'cptr', 'crow', 'cperm'):\n"
+        "        assert np.array_equal(v[k], ref[k]), (l, k)\n"
+        "print('ok')\n")
+    env = dict(os.environ, HGNN_WIDE_RECORDS="1")
+    r = subprocess.run([sys.executable, "-c", code], env=env, capture_output=True, text=True, cwd=ROOT, timeout=300)
+    assert r.returncode == 0 and r.stdout.strip().endswith("ok"), r.stderr[-2000:]
