@@ -55,7 +55,7 @@ def main():
     ap.add_argument("--host-warmup-s", type=float, default=3.0,
                     help="seconds of further untimed pipelined steps after the W warm-up steps (0 with --warmup 0)")
     ap.add_argument("--lookahead", type=int, default=24, help="mini-batches whose index build is started ahead of the GPU")
-    ap.add_argument("--concurrent-builds", type=int, default=16,
+    ap.add_argument("--concurrent-builds", type=int, default=15,
                     help="host builders working on separate mini-batches at once (the host threads are split over them; "
                          "0: the library's low-latency default)")
     args = ap.parse_args()
