@@ -89,7 +89,7 @@ def main():
 
     model = Model(g.schema, g.feat_dim, g.stores, ws, dtype=cfg.dtype,
                   loss=("xent" if cfg.loss == "xent" else "dot"), target_type=mbs[0].target_type,
-                  host_threads=args.host_threads, concurrent_builds=args.concurrent_builds,
+                  host_threads=args.host_threads or args.concurrent_builds, concurrent_builds=args.concurrent_builds,
                   # T0 carries fixed input features; only the learnable embeddings of T1-T3 need input gradients
                   first_layer_input_grad=([0, 1, 1, 1] if cfg.index in (1, 2, 4) and not args.all_input_grads else None))
     ctx = model.ctx
