@@ -258,7 +258,7 @@ hgnn_status launch_spmm_bwd(hipStream_t s, int dtype, const LayerDev &L, const T
 bool launch_spmm_fwd_uniform(hipStream_t s, int dtype, const LayerDev &L, int F, const void *x, void *z,
                              int row_begin, int row_end);
 bool launch_spmm_bwd_uniform(hipStream_t s, int dtype, const LayerDev &L, const TypeTab &tt, const RelTab &rt, const PtrTab &pt,
-                             int F, uint32_t want, const void *dz, void *dx);
+                             int F, uint32_t want, const void *dz, void *dx, float *partial);
 hgnn_status launch_transpose_weights(hipStream_t s, int dtype, const TypeTab &tt, const RelTab &rt,
                                      const PtrTab &pt, const WtTab &wt, int H, void *wt_buf);
 // mode 0: all segments of every type fused (bias/activation epilogue, writes h)

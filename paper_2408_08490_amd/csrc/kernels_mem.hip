@@ -266,7 +266,7 @@ hgnn_status launch_spmm_bwd(hipStream_t s, int dtype, const LayerDev &L, const T
   const int l2 = lanes_log2_for(max_dim, es);
   const int gpb = 256 >> l2;
   int row_blocks = (L.src_rows + gpb - 1) / gpb;
-  const int chunk_blocks = (L.n_chunks + gpb - 1) / gpb;
+  int chunk_blocks = (L.n_chunks + gpb - 1) / gpb;
   uint32_t root_mask = 0;
   bool uniform = true;  // every relation's aggregate rows have the same width: dz row rho starts at rho * F
   for (int t = 0; t < tt.num_types; ++t) {
@@ -274,9 +274,11 @@ hgnn_status launch_spmm_bwd(hipStream_t s, int dtype, const LayerDev &L, const T
     if (tt.in_dim[t] != tt.in_dim[0]) uniform = false;
   }
   // rows up to kLongRow edges: the uniform-width kernel when it applies, else the generic one below
-  if (uniform && launch_spmm_bwd_uniform(s, dtype, L, tt, rt, pt, tt.in_dim[0], want, dz, dx)) {
+  // (the uniform kernel's launch also carries the chunks of the long rows; max_dim is the common width then)
+  if (uniform && launch_spmm_bwd_uniform(s, dtype, L, tt, rt, pt, tt.in_dim[0], want, dz, dx, partial)) {
     HGNN_HIP(hipGetLastError());
     row_blocks = 0;
+    chunk_blocks = 0;
   }
   dim3 grid(row_blocks + chunk_blocks);
   if (grid.x > 0) {

@@ -132,12 +132,44 @@ struct RowRanges {
 
 template <typename T, int LPRL, int C>
 __global__ void __launch_bounds__(256) spmm_bwd_uniform_kernel(const int32_t *__restrict__ cptr, const int32_t *__restrict__ crow,
-                                                                RowRanges rr, const T *__restrict__ dz, T *__restrict__ dx, int F) {
+                                                                RowRanges rr, const T *__restrict__ dz, T *__restrict__ dx, int F,
+                                                                const int32_t *__restrict__ chunk_row,
+                                                                const int32_t *__restrict__ chunk_beg, int n_chunks,
+                                                                float *__restrict__ partial) {
   using V = Vec16<T>;
   constexpr int LPR = 1 << LPRL, RPW = 64 / LPR;
   const int lane = threadIdx.x & 63;
   const int wave = blockIdx.x * 4 + (threadIdx.x >> 6);
-  if (wave >= rr.total_waves) return;
+  if (wave >= rr.total_waves) {
+    // The waves behind the row waves take the chunks of the long rows (kChunk entries each): fp32 partial sums
+    // for the pass that adds them up.  They ride in this launch because on their own they are a launch of a few
+    // blocks that the stream would run after this one.
+    const int item = (wave - rr.total_waves) * RPW + (lane >> LPRL), sub = lane & (LPR - 1);
+    if (item >= n_chunks) return;
+    const int c = chunk_row[item];
+    bool wanted = false;
+    for (int i = 0; i < rr.n; ++i) wanted |= c >= rr.r[i].lo && c < rr.r[i].hi;
+    if (!wanted) return;
+    const int beg = chunk_beg[item], end = min(beg + kChunk, cptr[c + 1]);
+    const int nvec = F / V::N;
+    const uint4 *zb = reinterpret_cast<const uint4 *>(dz);
+    for (int q = sub; q < nvec; q += LPR) {
+      float acc[V::N];
+#pragma unroll
+      for (int i = 0; i < V::N; ++i) acc[i] = 0.f;
+      int e = beg;
+      for (; e + 4 <= end; e += 4) {
+        const uint4 v0 = zb[(int64_t)crow[e] * nvec + q], v1 = zb[(int64_t)crow[e + 1] * nvec + q];
+        const uint4 v2 = zb[(int64_t)crow[e + 2] * nvec + q], v3 = zb[(int64_t)crow[e + 3] * nvec + q];
+        V::add(acc, v0); V::add(acc, v1); V::add(acc, v2); V::add(acc, v3);
+      }
+      for (; e < end; ++e) V::add(acc, zb[(int64_t)crow[e] * nvec + q]);
+      float *pp = partial + (int64_t)item * F + q * V::N;
+#pragma unroll
+      for (int i = 0; i < V::N; ++i) pp[i] = acc[i];
+    }
+    return;
+  }
   int ri = 0;
   while (ri + 1 < rr.n && wave >= rr.r[ri + 1].wave0) ++ri;
   const RowRange R = rr.r[ri];
@@ -195,7 +227,7 @@ __global__ void __launch_bounds__(256) spmm_bwd_uniform_kernel(const int32_t *__
 }
 
 template <typename T, int LPRL, int C>
-static void launch_bwd_uniform(hipStream_t s, const LayerDev &L, RowRanges &rr, const void *dz, void *dx, int F) {
+static void launch_bwd_uniform(hipStream_t s, const LayerDev &L, RowRanges &rr, const void *dz, void *dx, int F, float *partial) {
   constexpr int RPW = 64 >> LPRL;
   int w = 0;
   for (int i = 0; i < rr.n; ++i) {
@@ -203,13 +235,14 @@ static void launch_bwd_uniform(hipStream_t s, const LayerDev &L, RowRanges &rr, 
     w += (rr.r[i].hi - rr.r[i].lo + RPW - 1) / RPW;
   }
   rr.total_waves = w;
+  w += (L.n_chunks + RPW - 1) / RPW;  // the chunk waves
   if (w == 0) return;
   HGNN_LAUNCH((spmm_bwd_uniform_kernel<T, LPRL, C>), dim3((w + 3) / 4), dim3(256), 0, s, L.cptr, L.crow, rr, (const T *)dz,
-                     (T *)dx, F);
+                     (T *)dx, F, L.chunk_row, L.chunk_beg, L.n_chunks, partial);
 }
 
 bool launch_spmm_bwd_uniform(hipStream_t s, int dtype, const LayerDev &L, const TypeTab &tt, const RelTab &rt, const PtrTab &pt,
-                             int F, uint32_t want, const void *dz, void *dx) {
+                             int F, uint32_t want, const void *dz, void *dx, float *partial) {
   RowRanges rr;
   rr.n = 0;
   for (int t = 0; t < tt.num_types; ++t) {
@@ -225,8 +258,8 @@ bool launch_spmm_bwd_uniform(hipStream_t s, int dtype, const LayerDev &L, const 
   const int es = dtype == HGNN_BF16 ? 2 : 4;
   const int nvec = F * es / 16;
   if (dtype == HGNN_BF16)
-    return dispatch_width<bf16>(nvec, [&]<int LPRL, int C>() { launch_bwd_uniform<bf16, LPRL, C>(s, L, rr, dz, dx, F); });
-  return dispatch_width<float>(nvec, [&]<int LPRL, int C>() { launch_bwd_uniform<float, LPRL, C>(s, L, rr, dz, dx, F); });
+    return dispatch_width<bf16>(nvec, [&]<int LPRL, int C>() { launch_bwd_uniform<bf16, LPRL, C>(s, L, rr, dz, dx, F, partial); });
+  return dispatch_width<float>(nvec, [&]<int LPRL, int C>() { launch_bwd_uniform<float, LPRL, C>(s, L, rr, dz, dx, F, partial); });
 }
 
 }  // namespace hgnn
