@@ -70,6 +70,26 @@ def _as_f32(cfg, g, mb, ws):
     cfg.dtype = "f32"
 
 
+def _as_bf16(cfg, g, mb, ws):
+    """Hook for run_case: the same inputs in bf16 storage (every value rounded first, so both sides start equal)."""
+    from workloads import bf16_round
+    cfg.dtype = "bf16"
+    g.stores = [bf16_round(s) for s in g.stores]
+    for lw in ws:
+        lw.w_rel = [bf16_round(w) for w in lw.w_rel]
+        lw.w_root = [None if w is None else bf16_round(w) for w in lw.w_root]
+        lw.bias = [None if b is None else bf16_round(b) for b in lw.bias]
+    if mb.grad_out is not None:
+        mb.grad_out = [bf16_round(x) for x in mb.grad_out]
+
+
+def test_ragged_widths_in_bf16():
+    """Configs 3 and 7 (10 / 32 vertex types with different feature widths, 30 / 128 relations) in bf16 storage: the
+    ragged-width gather kernels and the GEMM tables with 16-bit elements."""
+    _assert_ok(run_case(3, scale=0.02, batch=128, verbose=True, cfg_edit=_as_bf16))
+    _assert_ok(run_case(7, verbose=True, cfg_edit=_as_bf16))
+
+
 def test_config4_attention_fp32_scaled():
     """Attention variant (3 layers, 8 heads, semantic-attention fusion) at config 4's shape on a reduced graph, in
     fp32 storage: every output and every gradient (per-type projections, attention vectors, semantic-attention
