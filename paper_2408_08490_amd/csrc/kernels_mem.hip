@@ -435,24 +435,40 @@ __global__ void __launch_bounds__(256) relu_bias_bwd_vec_kernel(TypeTab tt, int 
 #pragma unroll
   for (int i = 0; i < V::N; ++i) sum[i] = 0.f;
   if (rg < rif) {
-    for (int r = r0 + rg; r < r1; r += rif) {
-      const int64_t i = ((int64_t)r * H) / V::N + c;
-      float v[V::N];
+    // four rows per trip: eight 16-byte loads in flight per lane (a block is only 128 rows, so there are few
+    // wavefronts per compute unit to hide the latency otherwise)
+    constexpr int U = 4;
+    for (int r = r0 + rg; r < r1; r += U * rif) {
+      uint4 gv[U], hv4[U];
 #pragma unroll
-      for (int k = 0; k < V::N; ++k) v[k] = 0.f;
-      V::add(v, reinterpret_cast<const uint4 *>(g)[i]);
-      if (relu) {
-        float hv[V::N];
-#pragma unroll
-        for (int k = 0; k < V::N; ++k) hv[k] = 0.f;
-        V::add(hv, reinterpret_cast<const uint4 *>(h)[i]);
-#pragma unroll
-        for (int k = 0; k < V::N; ++k)
-          if (!(hv[k] > 0.f)) v[k] = 0.f;
-        reinterpret_cast<uint4 *>(gp)[i] = V::pack(v);
+      for (int u = 0; u < U; ++u) {
+        const int ru = r + u * rif;
+        const int64_t i = ((int64_t)(ru < r1 ? ru : r) * H) / V::N + c;
+        gv[u] = reinterpret_cast<const uint4 *>(g)[i];
+        if (relu) hv4[u] = reinterpret_cast<const uint4 *>(h)[i];
       }
 #pragma unroll
-      for (int k = 0; k < V::N; ++k) sum[k] += v[k];
+      for (int u = 0; u < U; ++u) {
+        const int ru = r + u * rif;
+        if (ru >= r1) break;
+        const int64_t i = ((int64_t)ru * H) / V::N + c;
+        float v[V::N];
+#pragma unroll
+        for (int k = 0; k < V::N; ++k) v[k] = 0.f;
+        V::add(v, gv[u]);
+        if (relu) {
+          float hv[V::N];
+#pragma unroll
+          for (int k = 0; k < V::N; ++k) hv[k] = 0.f;
+          V::add(hv, hv4[u]);
+#pragma unroll
+          for (int k = 0; k < V::N; ++k)
+            if (!(hv[k] > 0.f)) v[k] = 0.f;
+          reinterpret_cast<uint4 *>(gp)[i] = V::pack(v);
+        }
+#pragma unroll
+        for (int k = 0; k < V::N; ++k) sum[k] += v[k];
+      }
     }
   }
   float *db = gt.dbias[t];
