@@ -364,16 +364,14 @@ __global__ void __launch_bounds__(256) pad_weights_kernel(TypeTab tt, RelTab rt,
   if (!w) return;
   const int F = tt.in_dim[seg < R ? rt.src[seg] : seg - R];
   T *o = out + (int64_t)(seg < R ? wo.rel4[seg] : wo.root4[seg - R]) * 4;
-  const int64_t n = (int64_t)F * Hp;
-  for (int64_t i = (int64_t)blockIdx.x * 256 + threadIdx.x; i < n; i += (int64_t)gridDim.x * 256) {
-    const int f = (int)(i / Hp), c = (int)(i % Hp);
-    o[i] = c < H ? w[(int64_t)f * H + c] : from_float<T>(0.f);
-  }
+  // a block takes whole rows (no division per element)
+  for (int f = blockIdx.x; f < F; f += gridDim.x)
+    for (int c = threadIdx.x; c < Hp; c += 256) o[(int64_t)f * Hp + c] = c < H ? w[(int64_t)f * H + c] : from_float<T>(0.f);
 }
 
 hgnn_status launch_pad_weights(hipStream_t s, int dtype, const TypeTab &tt, const RelTab &rt, const PtrTab &pt,
                                const WtTab &wo, int H, int Hp, void *out) {
-  dim3 grid(32, rt.num_rels + tt.num_types);
+  dim3 grid(64, rt.num_rels + tt.num_types);
   if (dtype == HGNN_BF16)
     HGNN_LAUNCH(pad_weights_kernel<bf16>, grid, dim3(256), 0, s, tt, rt, pt, wo, H, Hp, (bf16 *)out);
   else
@@ -400,17 +398,28 @@ __global__ void __launch_bounds__(256) relu_bias_bwd_kernel(TypeTab tt, int H, i
   float *db = gt.dbias[t];
   for (int c = threadIdx.x; c < ldo; c += 256) {
     float sum = 0.f;
-    for (int r = r0; r < r1; ++r) {
-      float v = 0.f;
-      if (c < H) {
-        const int64_t i = (int64_t)r * H + c;
-        v = to_float(g[i]);
-        if (relu && !(to_float(h[i]) > 0.f)) v = 0.f;
+    if (c < H) {
+      // the block's 16 rows in two rounds of eight independent loads
+      for (int rb = r0; rb < r1; rb += 8) {
+        float v[8], hv[8];
+#pragma unroll
+        for (int u = 0; u < 8; ++u) {
+          const int64_t i = (int64_t)min(rb + u, r1 - 1) * H + c;
+          v[u] = to_float(g[i]);
+          hv[u] = relu ? to_float(h[i]) : 1.f;
+        }
+#pragma unroll
+        for (int u = 0; u < 8; ++u) {
+          if (rb + u >= r1) break;
+          const float x = hv[u] > 0.f ? v[u] : 0.f;
+          if (write) gp[(int64_t)(rb + u) * ldo + c] = from_float<T>(x);
+          sum += x;
+        }
       }
-      if (write) gp[(int64_t)r * ldo + c] = from_float<T>(v);
-      sum += v;
+      if (db) atomicAdd(db + c, sum);
+    } else if (write) {
+      for (int r = r0; r < r1; ++r) gp[(int64_t)r * ldo + c] = from_float<T>(0.f);
     }
-    if (db && c < H) atomicAdd(db + c, sum);
   }
 }
 
