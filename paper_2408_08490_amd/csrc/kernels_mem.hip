@@ -606,7 +606,6 @@ hgnn_status launch_bias_act(hipStream_t s, int dtype, const TypeTab &tt, const P
 // ------------------------------------------------------------------------------------------
 // Mean softmax cross-entropy and its gradient; one wavefront per row.
 // ------------------------------------------------------------------------------------------
-constexpr int kXentRegs = 8;  // rows of up to 512 classes are held in registers
 template <typename T>
 __global__ void __launch_bounds__(256) xent_kernel(const T *__restrict__ logits, const int64_t *__restrict__ labels,
                                                     int64_t rows, int C, float *loss, T *__restrict__ grad) {
@@ -616,40 +615,6 @@ __global__ void __launch_bounds__(256) xent_kernel(const T *__restrict__ logits,
   float my_loss = 0.f;
   for (int64_t row = (int64_t)blockIdx.x * 4 + wave; row < rows; row += (int64_t)gridDim.x * 4) {
     const T *z = logits + row * C;
-    if (C <= 64 * kXentRegs) {
-      // the whole row in registers: one round of independent loads instead of three dependent passes
-      float v[kXentRegs];
-#pragma unroll
-      for (int j = 0; j < kXentRegs; ++j) {
-        const int c = lane + 64 * j;
-        v[j] = c < C ? to_float(z[c]) : -INFINITY;
-      }
-      const int lab = (int)labels[row];
-      float m = v[0];
-#pragma unroll
-      for (int j = 1; j < kXentRegs; ++j) m = fmaxf(m, v[j]);
-      for (int o = 32; o > 0; o >>= 1) m = fmaxf(m, __shfl_xor(m, o));
-      float sum = 0.f, zl = 0.f;
-#pragma unroll
-      for (int j = 0; j < kXentRegs; ++j) {
-        const int c = lane + 64 * j;
-        if (c == lab) zl = v[j];
-        v[j] = c < C ? __expf(v[j] - m) : 0.f;
-        sum += v[j];
-      }
-      for (int o = 32; o > 0; o >>= 1) {
-        sum += __shfl_xor(sum, o);
-        zl += __shfl_xor(zl, o);
-      }
-      const float inv_sum = 1.0f / sum;
-#pragma unroll
-      for (int j = 0; j < kXentRegs; ++j) {
-        const int c = lane + 64 * j;
-        if (c < C) grad[row * C + c] = from_float<T>((v[j] * inv_sum - (c == lab ? 1.0f : 0.0f)) * inv_rows);
-      }
-      my_loss += (logf(sum) + m - zl) * inv_rows;
-      continue;
-    }
     float m = -INFINITY;
     for (int c = lane; c < C; c += 64) m = fmaxf(m, to_float(z[c]));
     for (int o = 32; o > 0; o >>= 1) m = fmaxf(m, __shfl_xor(m, o));
@@ -675,7 +640,7 @@ hgnn_status launch_xent(hipStream_t s, int dtype, const void *logits, const int6
   hgnn_status st = launch_fill_zero(s, loss, sizeof(float));
   if (st != HGNN_OK) return st;
   if (rows == 0) return HGNN_OK;
-  dim3 grid((unsigned)std::min<int64_t>(2048, (rows + 3) / 4));
+  dim3 grid((unsigned)std::min<int64_t>(512, (rows + 3) / 4));
   if (dtype == HGNN_BF16)
     HGNN_LAUNCH(xent_kernel<bf16>, grid, dim3(256), 0, s, (const bf16 *)logits, labels, rows, classes, loss, (bf16 *)grad);
   else
