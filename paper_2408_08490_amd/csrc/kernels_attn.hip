@@ -574,11 +574,12 @@ __global__ void __launch_bounds__(256) attn_agg_bwd_rows_kernel(LayerDev L, Type
     // first pass: gm = sum_u alpha_u dalpha_u, summed edge by edge.  (It equals dm . m in exact arithmetic, but the
     // stored m is rounded to the storage type and the difference would not cancel in alpha (dalpha - gm).)
     float gm = 0.f;
-    for (int e = e0; e < e1; ++e) {
-      const int u = L.colidx[e];
-      float zu[P::N];
-      P::load(zu, z + (int64_t)u * H + q * P::N);
-      float ss = 0.f, da = 0.f;
+    // both passes take four edges at a time: their source rows are loaded together (independent loads in
+    // flight), the sums are then taken edge by edge in the row's order
+    constexpr int U = 4;
+    auto dots = [&](const float (&zu)[P::N], float &ss, float &da) {
+      ss = 0.f;
+      da = 0.f;
 #pragma unroll
       for (int i = 0; i < P::N; ++i) {
         ss += as[i] * zu[i];
@@ -588,36 +589,50 @@ __global__ void __launch_bounds__(256) attn_agg_bwd_rows_kernel(LayerDev L, Type
         ss += __shfl_xor(ss, o);
         da += __shfl_xor(da, o);
       }
-      const float sc = ss + sd;
-      const float ev = sc > 0.f ? sc : kLeaky * sc;
-      gm += __expf(ev - mxk) * inv_l * da;
+    };
+    for (int eb = e0; eb < e1; eb += U) {
+      float zu[U][P::N];
+#pragma unroll
+      for (int j = 0; j < U; ++j) {
+        const int u = L.colidx[min(eb + j, e1 - 1)];
+        P::load(zu[j], z + (int64_t)u * H + q * P::N);
+      }
+#pragma unroll
+      for (int j = 0; j < U; ++j) {
+        if (eb + j >= e1) break;
+        float ss, da;
+        dots(zu[j], ss, da);
+        const float sc = ss + sd;
+        const float ev = sc > 0.f ? sc : kLeaky * sc;
+        gm += __expf(ev - mxk) * inv_l * da;
+      }
     }
     float dsv_sum = 0.f;
-    for (int e = e0; e < e1; ++e) {
-      const int u = L.colidx[e];
-      float zu[P::N];
-      P::load(zu, z + (int64_t)u * H + q * P::N);
-      float ss = 0.f, da = 0.f;
+    for (int eb = e0; eb < e1; eb += U) {
+      float zu[U][P::N];
 #pragma unroll
-      for (int i = 0; i < P::N; ++i) {
-        ss += as[i] * zu[i];
-        da += g[i] * zu[i];
-      }
-      for (int o = hl >> 1; o > 0; o >>= 1) {
-        ss += __shfl_xor(ss, o);
-        da += __shfl_xor(da, o);
-      }
-      const float sc = ss + sd;
-      const float ev = sc > 0.f ? sc : kLeaky * sc;
-      const float a = __expf(ev - mxk) * inv_l;
-      const float dsv = a * (da - gm) * (sc > 0.f ? 1.f : kLeaky);
-      if (head_lead) {
-        alpha[(int64_t)e * heads + k] = a;
-        dsb[(int64_t)e * heads + k] = dsv;
+      for (int j = 0; j < U; ++j) {
+        const int u = L.colidx[min(eb + j, e1 - 1)];
+        P::load(zu[j], z + (int64_t)u * H + q * P::N);
       }
 #pragma unroll
-      for (int i = 0; i < P::N; ++i) das[i] += dsv * zu[i];
-      dsv_sum += dsv;
+      for (int j = 0; j < U; ++j) {
+        const int e = eb + j;
+        if (e >= e1) break;
+        float ss, da;
+        dots(zu[j], ss, da);
+        const float sc = ss + sd;
+        const float ev = sc > 0.f ? sc : kLeaky * sc;
+        const float a = __expf(ev - mxk) * inv_l;
+        const float dsv = a * (da - gm) * (sc > 0.f ? 1.f : kLeaky);
+        if (head_lead) {
+          alpha[(int64_t)e * heads + k] = a;
+          dsb[(int64_t)e * heads + k] = dsv;
+        }
+#pragma unroll
+        for (int i = 0; i < P::N; ++i) das[i] += dsv * zu[j][i];
+        dsv_sum += dsv;
+      }
     }
 #pragma unroll
     for (int i = 0; i < P::N; ++i) dad[i] += dsv_sum * zv[i];
