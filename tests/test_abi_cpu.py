@@ -388,3 +388,17 @@ def test_host_build_three_int_records():
     env = dict(os.environ, HGNN_WIDE_RECORDS="1")
     r = subprocess.run([sys.executable, "-c", code], env=env, capture_output=True, text=True, cwd=ROOT, timeout=300)
     assert r.returncode == 0 and r.stdout.strip().endswith("ok"), r.stderr[-2000:]
+
+
+def test_header_compiles_as_c99(tmp_path):
+    """The boundary is a C ABI: include/hgnn.h alone must go through a C99 compiler without warnings."""
+    import shutil
+    import subprocess
+    gcc = shutil.which("gcc")
+    if gcc is None:
+        pytest.skip("no C compiler")
+    src = tmp_path / "use_hgnn.c"
+    src.write_text('#include "hgnn.h"\nint main(void) { return (int)sizeof(hgnn_layer_params) == 0; }\n')
+    r = subprocess.run([gcc, "-std=c99", "-Wall", "-Wextra", "-pedantic", "-Werror", "-I", os.path.join(ROOT, "include"),
+                        "-fsyntax-only", str(src)], capture_output=True, text=True)
+    assert r.returncode == 0, r.stderr
