@@ -175,6 +175,37 @@ static bool build_layer(hgnn_ctx *ctx, Builder &bd, hgnn_graph *g, int l, BuildE
   std::memset(cnt2, 0, sizeof(int32_t) * (size_t)std::max(B1, 1) * S2);
   tm.lap("setup");
 
+  // A mini-batch drawn by the library's own sampler arrives relation by relation, destinations ascending, and
+  // its edges were read off the graph: there is nothing to look up, check or sort -- the merged CSR is the input
+  // order itself.
+  // (a test can ask for the three-int records where the two-int ones would do)
+  static const bool wide_records = getenv("HGNN_WIDE_RECORDS") != nullptr;
+  const bool csc_packed = rows <= (int64_t)1 << PackedRec::kPayloadBits && !wide_records;
+  const bool presorted = g->job != nullptr;
+  if (presorted) {
+    const SampleJob &job = *g->job;
+    const int64_t *es = job.edge_index[l].data(), *ed = es + E;
+    const int64_t *reo = job.rel_edge_off[l];
+    for (int r = 0; r < R; ++r) {
+      const int32_t row0 = rel_row_off[r], col0 = row_off[ctx->rel_src[r]];
+      const int32_t nd = rel_row_off[r + 1] - row0;
+      const bool want = (L.tmask >> ctx->rel_src[r]) & 1u;
+      int64_t e = reo[r];
+      const int64_t e_end = reo[r + 1];
+      for (int32_t i = 0; i < nd; ++i) {
+        rowptr[row0 + i] = (int32_t)e;
+        int32_t *c2 = cnt2 + (size_t)((row0 + i) >> kBucketShift) * S2;
+        for (; e < e_end && ed[e] == i; ++e) {
+          const int32_t c = col0 + (int32_t)es[e];
+          colidx[e] = c;
+          perm[e] = (int32_t)e;
+          if (want) ++c2[c >> kBucketShift];
+        }
+      }
+    }
+    for (int b = 0; b <= B1; ++b) base1[b] = b < B1 ? rowptr[(size_t)b << kBucketShift] : (int32_t)E;
+    tm.lap("csr from sampler order");
+  } else {
   // Algorithm 2: the layer's edge types are looked up through the edge ids (or taken as given) and matched
   // against the relations -- for all relations in one pass: each edge gets its merged row and source row.
   const int64_t slice = (E + P - 1) / P;
