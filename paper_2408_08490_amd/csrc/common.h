@@ -150,13 +150,36 @@ class ThreadPool {
 };
 
 // One builder: a host thread that takes whole graphs off the context's queue, its worker pool and its scratch.
+// Growable int64 array whose new space stays uninitialised (a std::vector would zero it, and its push_back
+// checks the capacity on every element).
+struct I64Buf {
+  int64_t *p = nullptr;
+  size_t n = 0, cap = 0;
+  I64Buf() = default;
+  I64Buf(const I64Buf &) = delete;
+  I64Buf &operator=(const I64Buf &) = delete;
+  ~I64Buf() { free(p); }
+  bool reserve(size_t c) {
+    if (c <= cap) return true;
+    c = std::max(c, cap + cap / 2);  // grow in few, large steps: each one is a system call that remaps pages
+    void *q = realloc(p, c * sizeof(int64_t));
+    if (!q) return false;
+    p = (int64_t *)q;
+    cap = c;
+    return true;
+  }
+  const int64_t *data() const { return p; }
+  size_t size() const { return n; }
+};
+
 struct Builder {
   ThreadPool *pool = nullptr;
   std::thread th;
   std::vector<int32_t> key, col, hist, tkey;
   std::vector<std::vector<int32_t>> long_lists;
   std::vector<int32_t> local_of[kMaxT];  // sampler: local row of a global vertex id (-1 = not in the hop), per type
-  std::vector<int64_t> hop_ids[2][kMaxT], edge_dst;  // sampler: destination / source lists of the current hop
+  std::vector<int64_t> hop_ids[2][kMaxT];  // sampler: destination / source lists of the current hop
+  I64Buf edge_dst;                         // sampler: local destinations of the hop's edges
 };
 
 // A mini-batch to be sampled on a builder's thread before its index arrays are built, and what the sampling
@@ -168,8 +191,8 @@ struct SampleJob {
   std::vector<int64_t> targets;
   std::vector<int32_t> fanouts;                 // per hop, nearest the targets first
   std::vector<int32_t> transpose[kMaxLayers];   // per layer: empty (= all types) or [T]
-  std::vector<int64_t> edge_index[kMaxLayers];  // [2 x E]: local source, local destination
-  std::vector<int64_t> edge_id[kMaxLayers];
+  I64Buf edge_index[kMaxLayers];                // [2 x E]: local source, local destination
+  I64Buf edge_id[kMaxLayers];
   int64_t rel_edge_off[kMaxLayers][kMaxR + 1];  // edges of relation r in a layer's lists: [rel_edge_off[r], rel_edge_off[r+1])
   int64_t n_src[kMaxLayers][kMaxT], n_dst[kMaxLayers][kMaxT];
   std::vector<int64_t> ids[kMaxT];              // global ids of the first layer's source rows

@@ -28,7 +28,7 @@ hgnn_status run_sample_job(hgnn_ctx *ctx, Builder &bd, hgnn_graph *g, std::strin
   std::vector<int64_t> *dst = bd.hop_ids[0], *src = bd.hop_ids[1];
   for (int t = 0; t < T; ++t) dst[t].clear();
   dst[job.target_type] = job.targets;
-  std::vector<int64_t> &ed = bd.edge_dst;
+  I64Buf &ed = bd.edge_dst;
   const uint64_t k0 = mix64(job.seed);
   hgnn_status st = HGNN_OK;
   for (int h = 1; h <= L && st == HGNN_OK; ++h) {
@@ -50,23 +50,23 @@ hgnn_status run_sample_job(hgnn_ctx *ctx, Builder &bd, hgnn_graph *g, std::strin
       }
       job.n_dst[l][t] = (int64_t)dst[t].size();
     }
-    std::vector<int64_t> &es = job.edge_index[l];  // local sources first; the destinations are appended below
-    es.clear();
-    ed.clear();
-    std::vector<int64_t> &eid = job.edge_id[l];
-    eid.clear();
+    I64Buf &es = job.edge_index[l];  // local sources first; the destinations are appended below
+    I64Buf &eid = job.edge_id[l];
     {
       size_t bound = 0;  // every destination keeps at most `fanout` edges per relation
       for (int r = 0; r < R; ++r) bound += dst[ctx->rel_dst[r]].size() * (size_t)fanout;
       bound = std::min<size_t>(bound, (size_t)sm.edge_off[R]);
-      es.reserve(2 * bound);
-      ed.reserve(bound);
-      eid.reserve(bound);
+      if (!es.reserve(2 * bound + 1) || !ed.reserve(bound + 1) || !eid.reserve(bound + 1)) {
+        msg = "out of host memory";
+        st = HGNN_ENOMEM;
+      }
     }
+    int64_t *pes = es.p, *ped = ed.p, *peid = eid.p;
+    size_t ne = 0;  // edges of this hop so far (the bound above holds, so the writes below need no check)
     for (int r = 0; r < R && st == HGNN_OK; ++r) {
       const int s = ctx->rel_src[r], d = ctx->rel_dst[r];
       const int64_t nd = (int64_t)dst[d].size();
-      job.rel_edge_off[l][r] = (int64_t)eid.size();
+      job.rel_edge_off[l][r] = (int64_t)ne;
       if (nd == 0) continue;
       const int64_t *ptr = sm.in_indptr[r];
       const int32_t *nbr = sm.in_nbr[r];
@@ -121,9 +121,10 @@ hgnn_status run_sample_job(hgnn_ctx *ctx, Builder &bd, hgnn_graph *g, std::strin
               lut[u] = loc;
               sl.push_back(u);
             }
-            es.push_back(loc);
-            ed.push_back(i);
-            eid.push_back(e0 + p);
+            pes[ne] = loc;
+            ped[ne] = i;
+            peid[ne] = e0 + p;
+            ++ne;
           }
         }
       }
@@ -133,8 +134,10 @@ hgnn_status run_sample_job(hgnn_ctx *ctx, Builder &bd, hgnn_graph *g, std::strin
       }
     }
     // this hop's block; the lookup tables go back to "not in the hop"
-    job.rel_edge_off[l][R] = (int64_t)eid.size();
-    es.insert(es.end(), ed.begin(), ed.end());
+    job.rel_edge_off[l][R] = (int64_t)ne;
+    if (st == HGNN_OK && ne) std::memcpy(pes + ne, ped, ne * sizeof(int64_t));
+    es.n = 2 * ne;
+    eid.n = ne;
     for (int t = 0; t < T; ++t) {
       job.n_src[l][t] = (int64_t)src[t].size();
       int32_t *lut = bd.local_of[t].data();
