@@ -55,7 +55,7 @@ struct Plan {
   int64_t total_dst = 0;
   size_t z_elems = 0, zroot_elems = 0, wt_elems = 0;
   size_t saved_bytes = 0, scratch_bytes = 0;
-  size_t off_wt = 0, off_gp = 0, off_dz = 0, off_partial = 0, off_acc32 = 0;
+  size_t off_wt = 0, off_gp = 0, off_dz = 0, off_partial = 0, off_acc32 = 0, off_bpart = 0;
 };
 
 static hgnn_status layer_dev(hgnn_ctx *ctx, hgnn_graph *g, int32_t layer, LayerDev &D);
@@ -128,6 +128,8 @@ static hgnn_status make_plan(hgnn_ctx *ctx, hgnn_graph *g, int32_t layer, const 
   pl.off_dz = o;      o += align_up(std::max<size_t>(zr, 1) * pl.es, 256);
   pl.off_partial = o; o += align_up(std::max<size_t>((size_t)L.max_chunks * std::max(pl.max_dim, 1), 1) * 4, 256);
   pl.off_acc32 = o;   o += align_up(std::max<size_t>((size_t)pl.total_dst * pl.H, 1) * 4, 256);
+  // partial bias-gradient sums: one row of H floats per block of (at least) 16 destination rows of a type
+  pl.off_bpart = o;   o += align_up(((size_t)pl.total_dst / 16 + T) * pl.H * 4, 256);
   pl.scratch_bytes = o;
   if (need_built) {
     hgnn_status st = layer_dev(ctx, g, layer, pl.dev);
@@ -1067,9 +1069,9 @@ hgnn_status hgnn_layer_bwd(hgnn_ctx *ctx, void *stream, hgnn_graph *g, int32_t l
   char *sc = (char *)scratch;
   const LayerHost &L = g->L[layer];
   const int32_t *reo = g->slab.host + L.o_rel_edge_off;
-  if (any_dw || any_db) {
+  if ((any_dw || any_db) && pl.total_dst == 0) {  // nothing flows back: the gradients are zero
     Probe pb(ctx, s, HGNN_K_ZERO_GRADS, layer);
-    if ((st = launch_zero_grads(s, pl.tt, pl.rt, gt, pl.H)) != HGNN_OK) return st;
+    return launch_zero_grads(s, pl.tt, pl.rt, gt, pl.H);
   }
   // The GEMMs want 16-byte aligned rows.  When H is not a multiple of 16 bytes (or a weight pointer is not
   // aligned) they run on zero-padded copies: G' gets leading dimension Hp in the scratch area (written by the
@@ -1081,10 +1083,11 @@ hgnn_status hgnn_layer_bwd(hgnn_ctx *ctx, void *stream, hgnn_graph *g, int32_t l
   for (int t = 0; t < T; ++t) pad |= p->w_root[t] && ((uintptr_t)p->w_root[t] & 15) != 0;
   int ldg = pl.H;
   PtrTab wpt = pl.pt;
+  WtTab wo;
+  std::memset(&wo, 0, sizeof(wo));
+  void *wpad = nullptr;
   if (pad && pl.total_dst > 0) {
     ldg = Hp;
-    WtTab wo;
-    std::memset(&wo, 0, sizeof(wo));
     size_t w = 0;
     char *wp = sc + pl.off_wt;
     for (int r = 0; r < R; ++r) {
@@ -1099,14 +1102,20 @@ hgnn_status hgnn_layer_bwd(hgnn_ctx *ctx, void *stream, hgnn_graph *g, int32_t l
         w += (size_t)p->in_dim[t] * Hp;
       }
     }
-    if (grad_x_merged)
-      if ((st = launch_pad_weights(s, ctx->dtype, pl.tt, pl.rt, pl.pt, wo, pl.H, Hp, wp)) != HGNN_OK) return st;
+    if (grad_x_merged) wpad = wp;
   }
+  // One launch: the row pass over G (ReLU mask, padded copy, column sums for the bias gradient as partial sums
+  // per block), zeroing of the weight gradients, the padded weights.  The partial sums are added up by a few
+  // blocks of the backward GEMM launch below, or by a launch of their own when that one does not run.
   const void *gp = grad_h;
-  if (pl.total_dst > 0 && (p->relu || any_db || ldg != pl.H)) {
+  const bool row_pass = pl.total_dst > 0 && (p->relu || any_db || ldg != pl.H);
+  float *bpart = any_db ? (float *)(sc + pl.off_bpart) : nullptr;
+  int rpb = 16;
+  if (pl.total_dst > 0) {
     void *gpw = sc + pl.off_gp;
     Probe pb(ctx, s, HGNN_K_RELU_BIAS_BWD, layer);
-    if ((st = launch_relu_bias_bwd(s, ctx->dtype, pl.tt, pl.H, ldg, p->relu, grad_h, h_out, gpw, gt)) != HGNN_OK) return st;
+    if ((st = launch_bwd_prep(s, ctx->dtype, pl.tt, pl.rt, pl.pt, wo, gt, pl.H, ldg, p->relu, row_pass, any_dw, grad_h, h_out, gpw,
+                              bpart, wpad, &rpb)) != HGNN_OK) return st;
     if (p->relu || ldg != pl.H) gp = gpw;
   }
   const bool fast = (ldg % vec) == 0;
@@ -1156,12 +1165,14 @@ hgnn_status hgnn_layer_bwd(hgnn_ctx *ctx, void *stream, hgnn_graph *g, int32_t l
     if (want_dx && da_tl.tile_off[da_tl.num_segs] > 0 && tl.tile_off[T] > 0) {
       // both backward GEMMs read G' and are independent of each other: one launch
       if ((st = launch_gemm_bwd(s, ctx->dtype, pl.dev, pl.tt, pl.rt, wpt, da_tl, gt, tl, split_rows, pl.H, ldg, fast, x_merged,
-                                saved, gp, dz)) != HGNN_OK) return st;
+                                saved, gp, dz, bpart, rpb)) != HGNN_OK) return st;
       da_done = true;
+      bpart = nullptr;
     } else if ((st = launch_gemm_dw(s, ctx->dtype, pl.dev, pl.tt, pl.rt, gt, tl, split_rows, pl.H, ldg, fast, x_merged, saved, gp)) != HGNN_OK) {
       return st;
     }
   }
+  if (bpart && (st = launch_bias_reduce(s, pl.tt, gt, pl.H, rpb, bpart)) != HGNN_OK) return st;
   if (want_dx) {
     if (!da_done) {
       Probe pb(ctx, s, HGNN_K_GEMM_DA, layer);
@@ -1193,8 +1204,9 @@ hgnn_status hgnn_layer_launch_count(hgnn_ctx *ctx, hgnn_graph *g, int32_t layer,
   if (st != HGNN_OK) return st;
   if (fwd_launches) *fwd_launches = 1 + (pl.dev.rows > 0) + (pl.total_dst > 0);
   if (bwd_launches) {
-    // zero grads, ReLU mask + bias grad, dW and dA GEMMs (one launch), transposed aggregation (+ long-row pass)
-    *bwd_launches = 1 + (pl.total_dst > 0) + (pl.total_dst > 0) + (pl.dev.src_rows > 0 ? 1 + (pl.dev.n_long > 0) : 0);
+    // zero grads + ReLU mask + bias partial sums (one launch), dW and dA GEMMs + bias sums (one launch), transposed
+    // aggregation (+ long-row pass); without destination rows only the zeroing
+    *bwd_launches = pl.total_dst > 0 ? 2 + (pl.dev.src_rows > 0 ? 1 + (pl.dev.n_long > 0) : 0) : 1;
   }
   return HGNN_OK;
 }

@@ -321,7 +321,8 @@ hgnn_status launch_gemm_da(hipStream_t s, int dtype, const LayerDev &L, const Ty
                            const PtrTab &pt, const SegTab &tiles, int ldg, bool fast, const void *gp, void *dz);
 hgnn_status launch_gemm_bwd(hipStream_t s, int dtype, const LayerDev &L, const TypeTab &tt, const RelTab &rt,
                             const PtrTab &pt, const SegTab &da_tiles, const GradPtrTab &gt, const DwTab &dw_tiles,
-                            int split_rows, int H, int ldg, bool fast, const void *x, const void *z, const void *gp, void *dz);
+                            int split_rows, int H, int ldg, bool fast, const void *x, const void *z, const void *gp, void *dz,
+                            const float *bpart, int rpb);  // bpart != NULL: the launch also reduces the partial bias sums
 hgnn_status launch_gemm_dw(hipStream_t s, int dtype, const LayerDev &L, const TypeTab &tt, const RelTab &rt,
                            const GradPtrTab &gt, const DwTab &tiles, int split_rows, int H, int ldg, bool fast,
                            const void *x, const void *z, const void *gp);
@@ -338,6 +339,15 @@ hgnn_status launch_relu_bias_bwd(hipStream_t s, int dtype, const TypeTab &tt, in
 hgnn_status launch_pad_weights(hipStream_t s, int dtype, const TypeTab &tt, const RelTab &rt, const PtrTab &pt,
                                const WtTab &wo, int H, int Hp, void *out);
 hgnn_status launch_zero_grads(hipStream_t s, const TypeTab &tt, const RelTab &rt, const GradPtrTab &gt, int H);
+// ReLU mask / bias column sums (into bpart, rows_per_block rows of G per row of bpart), weight-gradient zeroing and
+// padded weight copies (wpad != NULL) in one launch; launch_bias_reduce (or the blocks the merged backward GEMM
+// launch sets aside for it) then turns bpart into dbias.
+hgnn_status launch_bwd_prep(hipStream_t s, int dtype, const TypeTab &tt, const RelTab &rt, const PtrTab &pt, const WtTab &wo,
+                            const GradPtrTab &gt, int H, int ldo, int relu, bool do_rows, bool do_zero, const void *grad_h,
+                            const void *h, void *gp, float *bpart, void *wpad, int *rows_per_block);
+hgnn_status launch_bias_reduce(hipStream_t s, const TypeTab &tt, const GradPtrTab &gt, int H, int rpb, const float *bpart);
+// blocks of 256 threads that add up the partial bias sums: 32 columns of one type each
+inline int bias_reduce_blocks(int num_types, int H) { return num_types * ((H + 31) / 32); }
 hgnn_status launch_fill_zero(hipStream_t s, void *p, size_t bytes);
 hgnn_status launch_xent(hipStream_t s, int dtype, const void *logits, const int64_t *labels, int64_t rows,
                         int classes, float *loss, void *grad);

@@ -366,8 +366,10 @@ static inline int balance_xcd(const int32_t *tile_off, const int64_t *cost, int 
     int t = ntiles;
     if (x < 8) {
       const int64_t target = (total * x + 7) / 8;  // first tile whose preceding cost reaches the target
-      while (g < ngroups && before + (int64_t)(tile_off[g + 1] - tile_off[g]) * cost[g] < target)
-        before += (int64_t)(tile_off[g + 1] - tile_off[g]) * cost[g++];
+      while (g < ngroups && before + (int64_t)(tile_off[g + 1] - tile_off[g]) * cost[g] < target) {
+        before += (int64_t)(tile_off[g + 1] - tile_off[g]) * cost[g];
+        ++g;
+      }
       t = g < ngroups ? tile_off[g] + (int)((target - before + cost[g] - 1) / cost[g]) : ntiles;
       if (t < m.first[x - 1]) t = m.first[x - 1];
       if (t > ntiles) t = ntiles;

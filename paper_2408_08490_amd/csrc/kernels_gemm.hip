@@ -13,6 +13,7 @@
 // Every kernel exists in a FAST form (all operands 16-byte aligned: per-thread offsets are computed once
 // per segment, a K-step is 8 vector loads from wave-uniform bases) and a generic form (element-wise,
 // zero-filled loads) for unaligned shapes.
+#include "bias_reduce.h"
 #include "gemm_core.h"
 
 namespace hgnn {
@@ -258,14 +259,22 @@ __global__ void __launch_bounds__(kThreads, MI == 1 ? 4 : 2) gemm_dw_kernel(Type
 // Both backward GEMMs of a layer in ONE launch: the first n_dw blocks compute weight-gradient tiles (long
 // reductions), the others input-gradient tiles (short ones).  Each kernel alone leaves compute units idle at its
 // end -- the weight gradient has fewer tiles than the chip has block slots -- and the other one's tiles fill them.
+// The last n_bias blocks (when bpart is given) add up the partial bias-gradient sums that the row pass over G'
+// left: a few microseconds of work that would otherwise be a launch of its own.
 template <typename T, bool FAST>
 __global__ void __launch_bounds__(kThreads, 2) gemm_bwd_kernel(LayerDev L, TypeTab tt, RelTab rt, PtrTab pt, SegTab da_tiles,
                                                             GradPtrTab gt, DwTab dw_tiles, XcdMap xmap, int n_dw, int split_rows,
                                                             int H, int ldg, const T *__restrict__ x, const T *__restrict__ z,
-                                                            const T *__restrict__ gp, T *__restrict__ dz) {
+                                                            const T *__restrict__ gp, T *__restrict__ dz,
+                                                            const float *__restrict__ bpart, int rpb, int n_bias) {
   __shared__ GemmLds<T, 2, 2> sm;
+  const int n_gemm = (int)gridDim.x - n_bias;
+  if ((int)blockIdx.x >= n_gemm) {
+    bias_reduce_part(tt, gt, H, rpb, bpart, (int)blockIdx.x - n_gemm);
+    return;
+  }
   if ((int)blockIdx.x < n_dw) dw_tile<T, FAST, 2>(sm, blockIdx.x, tt, rt, gt, dw_tiles, xmap, split_rows, H, ldg, x, z, gp);
-  else da_tile<T, FAST, 2>(sm, blockIdx.x - n_dw, gridDim.x - n_dw, L, tt, rt, pt, da_tiles, ldg, gp, dz);
+  else da_tile<T, FAST, 2>(sm, blockIdx.x - n_dw, n_gemm - n_dw, L, tt, rt, pt, da_tiles, ldg, gp, dz);
 }
 
 static int dw_blocks(int dtype, const TypeTab &tt, const DwTab &tiles, int split_rows, XcdMap &xmap) {
@@ -281,14 +290,16 @@ static int dw_blocks(int dtype, const TypeTab &tt, const DwTab &tiles, int split
 
 hgnn_status launch_gemm_bwd(hipStream_t s, int dtype, const LayerDev &L, const TypeTab &tt, const RelTab &rt,
                             const PtrTab &pt, const SegTab &da_tiles, const GradPtrTab &gt, const DwTab &dw_tiles,
-                            int split_rows, int H, int ldg, bool fast, const void *x, const void *z, const void *gp, void *dz) {
+                            int split_rows, int H, int ldg, bool fast, const void *x, const void *z, const void *gp, void *dz,
+                            const float *bpart, int rpb) {
   XcdMap xmap;
   const int n_dw = dw_blocks(dtype, tt, dw_tiles, split_rows, xmap);
   const int n_da = round_up8(da_tiles.tile_off[da_tiles.num_segs]);
-  dim3 grid(n_dw + n_da), blk(kThreads);
+  const int n_bias = bpart ? bias_reduce_blocks(tt.num_types, H) : 0;
+  dim3 grid(n_dw + n_da + n_bias), blk(kThreads);
 #define HGNN_BWD(TY, FA)                                                                                             \
   HGNN_LAUNCH((gemm_bwd_kernel<TY, FA>), grid, blk, 0, s, L, tt, rt, pt, da_tiles, gt, dw_tiles, xmap, n_dw, split_rows, H, \
-              ldg, (const TY *)x, (const TY *)z, (const TY *)gp, (TY *)dz)
+              ldg, (const TY *)x, (const TY *)z, (const TY *)gp, (TY *)dz, bpart, rpb, n_bias)
   if (dtype == HGNN_BF16) {
     if (fast) HGNN_BWD(bf16, true); else HGNN_BWD(bf16, false);
   } else {

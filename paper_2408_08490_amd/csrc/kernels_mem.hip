@@ -3,6 +3,7 @@
 // the per-edge feature copies), its transpose for the backward pass, and small element-wise
 // helpers.  Every feature row is moved in 16-byte pieces by a power-of-two group of lanes.
 #include "common.h"
+#include "bias_reduce.h"
 #include "device_types.h"
 
 namespace hgnn {
@@ -357,16 +358,23 @@ hgnn_status launch_transpose_weights(hipStream_t s, int dtype, const TypeTab &tt
 }
 
 // Zero-padded copies: out[off + f*Hp + c] = c < H ? W[f*H + c] : 0  (segment = blockIdx.y).
+// Block bx of gx works on segment seg.
 template <typename T>
-__global__ void __launch_bounds__(256) pad_weights_kernel(TypeTab tt, RelTab rt, PtrTab pt, WtTab wo, int H, int Hp, T *out) {
-  const int seg = blockIdx.y, R = rt.num_rels;
+__device__ __forceinline__ void pad_weights_part(const TypeTab &tt, const RelTab &rt, const PtrTab &pt, const WtTab &wo, int H,
+                                                 int Hp, T *out, int seg, int bx, int gx) {
+  const int R = rt.num_rels;
   const T *w = (const T *)(seg < R ? pt.w_rel[seg] : pt.w_root[seg - R]);
   if (!w) return;
   const int F = tt.in_dim[seg < R ? rt.src[seg] : seg - R];
   T *o = out + (int64_t)(seg < R ? wo.rel4[seg] : wo.root4[seg - R]) * 4;
   // a block takes whole rows (no division per element)
-  for (int f = blockIdx.x; f < F; f += gridDim.x)
+  for (int f = bx; f < F; f += gx)
     for (int c = threadIdx.x; c < Hp; c += 256) o[(int64_t)f * Hp + c] = c < H ? w[(int64_t)f * H + c] : from_float<T>(0.f);
+}
+
+template <typename T>
+__global__ void __launch_bounds__(256) pad_weights_kernel(TypeTab tt, RelTab rt, PtrTab pt, WtTab wo, int H, int Hp, T *out) {
+  pad_weights_part<T>(tt, rt, pt, wo, H, Hp, out, blockIdx.y, blockIdx.x, gridDim.x);
 }
 
 hgnn_status launch_pad_weights(hipStream_t s, int dtype, const TypeTab &tt, const RelTab &rt, const PtrTab &pt,
@@ -382,12 +390,15 @@ hgnn_status launch_pad_weights(hipStream_t s, int dtype, const TypeTab &tt, cons
 
 // ------------------------------------------------------------------------------------------
 // Backward epilogue: gp = grad_h * [h > 0] (when the layer has a ReLU) and dbias_t = column sums.
-// One block = 64 rows of one type; a thread owns columns tid, tid+256, ...
+// One block = 16 rows of one type; a thread owns columns tid, tid+256, ...  The block's column sums are added
+// to dbias_t, or, when `bpart` is given, stored as row `block` of bpart [blocks x H] for a later pass that adds
+// the rows of a type up (no atomics, and dbias needs no zeroing first).
 // ------------------------------------------------------------------------------------------
 template <typename T>
-__global__ void __launch_bounds__(256) relu_bias_bwd_kernel(TypeTab tt, int H, int ldo, int relu, int write, const T *__restrict__ g,
-                                                             const T *__restrict__ h, T *__restrict__ gp, GradPtrTab gt) {
-  int b = blockIdx.x, t = 0;
+__device__ __forceinline__ void relu_bias_rows(const TypeTab &tt, int block, int H, int ldo, int relu, int write,
+                                               const T *__restrict__ g, const T *__restrict__ h, T *__restrict__ gp,
+                                               const GradPtrTab &gt, float *__restrict__ bpart) {
+  int b = block, t = 0;
   for (;; ++t) {
     const int nb = (tt.n_dst[t] + 15) / 16;
     if (b < nb) break;
@@ -416,20 +427,28 @@ __global__ void __launch_bounds__(256) relu_bias_bwd_kernel(TypeTab tt, int H, i
           sum += x;
         }
       }
-      if (db) atomicAdd(db + c, sum);
+      if (bpart) bpart[(int64_t)block * H + c] = sum;
+      else if (db) atomicAdd(db + c, sum);
     } else if (write) {
       for (int r = r0; r < r1; ++r) gp[(int64_t)r * ldo + c] = from_float<T>(0.f);
     }
   }
 }
 
+template <typename T>
+__global__ void __launch_bounds__(256) relu_bias_bwd_kernel(TypeTab tt, int H, int ldo, int relu, int write, const T *__restrict__ g,
+                                                             const T *__restrict__ h, T *__restrict__ gp, GradPtrTab gt) {
+  relu_bias_rows<T>(tt, blockIdx.x, H, ldo, relu, write, g, h, gp, gt, nullptr);
+}
+
 // Same, 16 bytes per lane: a block owns 128 rows of one type, 256/(H/VEC) rows are in flight at a time.
 template <typename T>
-__global__ void __launch_bounds__(256) relu_bias_bwd_vec_kernel(TypeTab tt, int H, int relu, const T *__restrict__ g,
-                                                                 const T *__restrict__ h, T *__restrict__ gp, GradPtrTab gt) {
+__device__ __forceinline__ void relu_bias_rows_vec(const TypeTab &tt, int block, int H, int relu, const T *__restrict__ g,
+                                                   const T *__restrict__ h, T *__restrict__ gp, const GradPtrTab &gt,
+                                                   float *__restrict__ bpart) {
   using V = Vec16<T>;
   __shared__ float red[256 * V::N];
-  int b = blockIdx.x, t = 0;
+  int b = block, t = 0;
   for (;; ++t) {
     const int nb = (tt.n_dst[t] + 127) / 128;
     if (b < nb) break;
@@ -489,8 +508,15 @@ __global__ void __launch_bounds__(256) relu_bias_bwd_vec_kernel(TypeTab tt, int 
     const int cc = col / V::N, k = col % V::N;
     float a = 0.f;
     for (int q = 0; q < rif; ++q) a += red[(q * chunks + cc) * V::N + k];
-    atomicAdd(db + col, a);
+    if (bpart) bpart[(int64_t)block * H + col] = a;
+    else atomicAdd(db + col, a);
   }
+}
+
+template <typename T>
+__global__ void __launch_bounds__(256) relu_bias_bwd_vec_kernel(TypeTab tt, int H, int relu, const T *__restrict__ g,
+                                                                 const T *__restrict__ h, T *__restrict__ gp, GradPtrTab gt) {
+  relu_bias_rows_vec<T>(tt, blockIdx.x, H, relu, g, h, gp, gt, nullptr);
 }
 
 hgnn_status launch_relu_bias_bwd(hipStream_t s, int dtype, const TypeTab &tt, int H, int ldo, int relu,
@@ -521,8 +547,9 @@ hgnn_status launch_relu_bias_bwd(hipStream_t s, int dtype, const TypeTab &tt, in
 }
 
 // ------------------------------------------------------------------------------------------
-__global__ void __launch_bounds__(256) zero_grads_kernel(TypeTab tt, RelTab rt, GradPtrTab gt, int H) {
-  const int seg = blockIdx.y, R = rt.num_rels;
+__device__ __forceinline__ void zero_grads_part(const TypeTab &tt, const RelTab &rt, const GradPtrTab &gt, int H, int seg,
+                                                int bx, int gx, bool bias_too) {
+  const int R = rt.num_rels;
   float *w;
   int64_t n;
   if (seg < R) {
@@ -533,15 +560,80 @@ __global__ void __launch_bounds__(256) zero_grads_kernel(TypeTab tt, RelTab rt, 
     w = gt.dw_root[t];
     n = (int64_t)tt.in_dim[t] * H;
     float *b = gt.dbias[t];
-    if (b)
-      for (int i = blockIdx.x * 256 + threadIdx.x; i < H; i += gridDim.x * 256) b[i] = 0.f;
+    if (b && bias_too)
+      for (int i = bx * 256 + threadIdx.x; i < H; i += gx * 256) b[i] = 0.f;
   }
   if (!w) return;
-  for (int64_t i = blockIdx.x * 256 + threadIdx.x; i < n; i += (int64_t)gridDim.x * 256) w[i] = 0.f;
+  for (int64_t i = bx * 256 + threadIdx.x; i < n; i += (int64_t)gx * 256) w[i] = 0.f;
+}
+
+__global__ void __launch_bounds__(256) zero_grads_kernel(TypeTab tt, RelTab rt, GradPtrTab gt, int H) {
+  zero_grads_part(tt, rt, gt, H, blockIdx.y, blockIdx.x, gridDim.x, true);
 }
 
 hgnn_status launch_zero_grads(hipStream_t s, const TypeTab &tt, const RelTab &rt, const GradPtrTab &gt, int H) {
   HGNN_LAUNCH(zero_grads_kernel, dim3(32, rt.num_rels + tt.num_types), dim3(256), 0, s, tt, rt, gt, H);
+  HGNN_HIP(hipGetLastError());
+  return HGNN_OK;
+}
+
+// The start of a layer's backward pass in ONE launch: the ReLU mask / bias column sums over G (the first
+// nb_relu blocks; column sums go to bpart), zeroing of the weight gradients (nb_zero blocks) and the zero-padded
+// weight copies (the rest).  The three touch different memory and none is big enough to fill the chip alone.
+template <typename T, bool VEC>
+__global__ void __launch_bounds__(256) bwd_prep_kernel(TypeTab tt, RelTab rt, PtrTab pt, WtTab wo, GradPtrTab gt, int H, int ldo,
+                                                        int relu, int write, const T *__restrict__ g, const T *__restrict__ h,
+                                                        T *__restrict__ gp, float *__restrict__ bpart, int nb_relu, int nb_zero,
+                                                        T *__restrict__ wpad) {
+  int b = blockIdx.x;
+  if (b < nb_relu) {
+    if constexpr (VEC) relu_bias_rows_vec<T>(tt, b, H, relu, g, h, gp, gt, bpart);
+    else relu_bias_rows<T>(tt, b, H, ldo, relu, write, g, h, gp, gt, bpart);
+    return;
+  }
+  b -= nb_relu;
+  if (b < nb_zero) {
+    zero_grads_part(tt, rt, gt, H, b / 32, b % 32, 32, false);
+    return;
+  }
+  b -= nb_zero;
+  pad_weights_part<T>(tt, rt, pt, wo, H, ldo, wpad, b / 64, b % 64, 64);
+}
+
+hgnn_status launch_bwd_prep(hipStream_t s, int dtype, const TypeTab &tt, const RelTab &rt, const PtrTab &pt, const WtTab &wo,
+                            const GradPtrTab &gt, int H, int ldo, int relu, bool do_rows, bool do_zero, const void *grad_h,
+                            const void *h, void *gp, float *bpart, void *wpad, int *rows_per_block) {
+  const int vec = dtype == HGNN_BF16 ? 8 : 4;
+  const bool fast = ldo == H && H % vec == 0 && H / vec <= 256 && (((uintptr_t)grad_h | (uintptr_t)h | (uintptr_t)gp) & 15) == 0;
+  const int rpb = fast ? 128 : 16;
+  *rows_per_block = rpb;
+  const int write = relu || ldo != H;
+  int nb_relu = 0;
+  if (do_rows)
+    for (int t = 0; t < tt.num_types; ++t) nb_relu += (tt.n_dst[t] + rpb - 1) / rpb;
+  const int segs = rt.num_rels + tt.num_types;
+  const int nb_zero = do_zero ? 32 * segs : 0, nb_pad = wpad ? 64 * segs : 0;
+  const int blocks = nb_relu + nb_zero + nb_pad;
+  if (blocks == 0) return HGNN_OK;
+#define HGNN_PREP(TY, VE)                                                                                              \
+  HGNN_LAUNCH((bwd_prep_kernel<TY, VE>), dim3(blocks), dim3(256), 0, s, tt, rt, pt, wo, gt, H, ldo, relu, write,        \
+              (const TY *)grad_h, (const TY *)h, (TY *)gp, bpart, nb_relu, nb_zero, (TY *)wpad)
+  if (dtype == HGNN_BF16) {
+    if (fast) HGNN_PREP(bf16, true); else HGNN_PREP(bf16, false);
+  } else {
+    if (fast) HGNN_PREP(float, true); else HGNN_PREP(float, false);
+  }
+#undef HGNN_PREP
+  HGNN_HIP(hipGetLastError());
+  return HGNN_OK;
+}
+
+__global__ void __launch_bounds__(256) bias_reduce_kernel(TypeTab tt, GradPtrTab gt, int H, int rpb, const float *__restrict__ bpart) {
+  bias_reduce_part(tt, gt, H, rpb, bpart, blockIdx.x);
+}
+
+hgnn_status launch_bias_reduce(hipStream_t s, const TypeTab &tt, const GradPtrTab &gt, int H, int rpb, const float *bpart) {
+  HGNN_LAUNCH(bias_reduce_kernel, dim3(bias_reduce_blocks(tt.num_types, H)), dim3(256), 0, s, tt, gt, H, rpb, bpart);
   HGNN_HIP(hipGetLastError());
   return HGNN_OK;
 }

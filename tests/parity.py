@@ -110,12 +110,13 @@ def oracle_run(cfg, g, mb, ws, input_grad=None):
 
 
 def run_case(index, scale=1.0, batch=None, verbose=False, use_edge_id=True, check_naive=False, graph=None,
-             input_grad=None, backward=True, cfg_edit=None, grad_tol=None, sampled=None):
+             input_grad=None, backward=True, cfg_edit=None, grad_tol=None, sampled=None, need_input_grad=True):
     """cfg_edit(cfg, g, mb, ws): optional hook that changes the prepared inputs (e.g. the storage type) before
     both sides run.  grad_tol: optional {substring of a gradient's name: tolerance or None}; a matching
     gradient is held to that tolerance in both norms against the tie-broken oracle (None: reported only).
     sampled: optional dict(seed=..., fanouts=...): the mini-batch of the same targets is sampled by the library's
-    sampler on the HIP side and by the sampler oracle on the other."""
+    sampler on the HIP side and by the sampler oracle on the other.  need_input_grad=False: the first layer's
+    backward gets no input-gradient buffer (its weight and bias gradients are still checked)."""
     import torch
     from paper_2408_08490_amd.runner import Model
     cfg, g, mb, ws = prepare_inputs(index, scale, batch, graph)
@@ -142,7 +143,7 @@ def run_case(index, scale=1.0, batch=None, verbose=False, use_edge_id=True, chec
         bt = model.prepare_sampled(sampler, targets, fanouts, sampled["seed"], labels=mb.labels, grad_out=mb.grad_out)
     else:
         bt = model.prepare(mb, g.edge_type, use_edge_id=use_edge_id)
-    out = model.run(bt, backward=backward)
+    out = model.run(bt, backward=backward, need_input_grad=need_input_grad)
     torch.cuda.synchronize()
     tol = TOL[cfg.dtype]
     report, ok = {}, True
@@ -257,6 +258,9 @@ def run_case(index, scale=1.0, batch=None, verbose=False, use_edge_id=True, chec
                     chk2(f"L{l}.dw_root{t}", w["dw_root"][t].cpu().numpy(), gr["dw_root"][t], gt["dw_root"][t])
                 if gr["dbias"][t] is not None:
                     chk2(f"L{l}.dbias{t}", w["dbias"][t].cpu().numpy(), gr["dbias"][t], gt["dbias"][t])
+        if out["dx"][l] is None:
+            assert l == 0 and not need_input_grad
+            continue
         got_dx = out["dx"][l].float().cpu().numpy()
         if l == 0 and input_grad is not None:          # rows of types without input gradients are left unwritten
             eo = np.concatenate([[0], np.cumsum([d.size for d in gr["dx"]])])

@@ -33,6 +33,13 @@ def test_config2_bf16_scaled_without_input_grads_of_fixed_features():
     _assert_ok(run_case(2, scale=0.05, batch=512, verbose=True, input_grad=[0, 1, 1, 1]))
 
 
+def test_first_layer_without_input_gradient_buffer():
+    """Without an input-gradient buffer the first layer's backward runs the weight-gradient GEMM alone and adds
+    the partial bias sums up in a launch of their own (fp32; bf16 with an output width that is no multiple of eight)."""
+    _assert_ok(run_case(1, scale=0.05, batch=256, verbose=True, need_input_grad=False))
+    _assert_ok(run_case(2, scale=0.05, batch=256, verbose=True, need_input_grad=False))
+
+
 def test_config3_many_types_fp32_scaled():
     _assert_ok(run_case(3, scale=0.02, batch=128, verbose=True, check_naive=True))
 
