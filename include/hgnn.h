@@ -352,7 +352,10 @@ hgnn_status hgnn_adam_update_rows(hgnn_ctx *ctx, void *stream, void *store, floa
  *   hgnn_probe_read(kernel, layer, ...): waits for the recorded events of that entry and returns their
  *     summed duration in milliseconds and the number of timed calls.
  * HGNN_K_GEMM_DW is the launch that holds the weight-gradient GEMM; in a mean layer's backward it also holds
- * the input-gradient GEMM's tiles when both are computed (HGNN_K_GEMM_DA then times nothing). */
+ * the input-gradient GEMM's tiles when both are computed (HGNN_K_GEMM_DA then times nothing).
+ * HGNN_K_RELU_BIAS_BWD is the launch at the start of a mean layer's backward: the ReLU mask / bias pass
+ * over grad_h together with the zeroing of the weight gradients (HGNN_K_ZERO_GRADS times only the
+ * zeroing of a layer without destination rows). */
 typedef enum {
   HGNN_K_MERGE = 0, HGNN_K_TRANSPOSE_W = 1, HGNN_K_SPMM_FWD = 2, HGNN_K_GEMM_FWD = 3, HGNN_K_ZERO_GRADS = 4,
   HGNN_K_RELU_BIAS_BWD = 5, HGNN_K_GEMM_DW = 6, HGNN_K_GEMM_DA = 7, HGNN_K_SPMM_BWD = 8, HGNN_K_XENT = 9

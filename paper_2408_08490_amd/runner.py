@@ -233,7 +233,8 @@ class Model:
             r0 = sum(blk.n_dst[:t])
             logits = hs[-1].view(-1, H)[r0: r0 + blk.n_dst[t]]
             g = self._typed("g_last", sum(blk.n_dst) * H)
-            g.zero_()
+            if sum(blk.n_dst) != blk.n_dst[t]:   # rows of other types get no loss gradient
+                g.zero_()
             gv = g.view(-1, H)[r0: r0 + blk.n_dst[t]]
             ctx.hgnn_softmax_xent(logits, b.labels_dev, self.loss_dev, gv)
             out["loss"] = self.loss_dev
