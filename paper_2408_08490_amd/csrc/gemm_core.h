@@ -198,6 +198,13 @@ template <typename T, int MI = 2, int NI = 2> struct GemmLds {
 };
 constexpr int kOutPitchPad = 8;  // floats: staged rows stay 16-byte aligned, rows r and r + 4 lie 32 banks apart
 
+// A pointer that is the same in every lane, moved to scalar registers.
+template <typename P> __device__ __forceinline__ const P *uniform_ptr(const P *p) {
+  const uint64_t v = reinterpret_cast<uint64_t>(p);
+  const uint32_t lo = __builtin_amdgcn_readfirstlane((uint32_t)v), hi = __builtin_amdgcn_readfirstlane((uint32_t)(v >> 32));
+  return reinterpret_cast<const P *>(((uint64_t)hi << 32) | lo);
+}
+
 // Runs the K-steps of sm.seg[0..nseg) (must be visible to the whole block) into `acc`.
 // KC operand: matrix [extent x K] row-major (ld); KS operand: matrix [K x extent] row-major (ld).
 template <typename T, bool FAST, bool AKC, bool BKC, int MI, int NI>
@@ -215,9 +222,22 @@ __device__ __forceinline__ void gemm_run(f32x16 (&acc)[MI][NI], GemmLds<T, MI, N
   for (int s = 0; s < nseg; ++s) total += (sm.seg[s].ke - sm.seg[s].kb + M::BK - 1) / M::BK;
   int s_ld = 0, k_ld = nseg > 0 ? sm.seg[0].kb : 0;  // cursor of the loader, two K-steps ahead of the multiplier
   int s_set0 = -1, s_set1 = -1;                      // segment each register set's offsets were computed for
+  // The loader's segment is kept in scalar registers and read from LDS only when the loader moves on to the next
+  // one: read per K-step, the LDS round trip sits in the step's chain of dependent operations.
+  Seg<T> g;
+  int s_cached = -1;
   auto issue = [&](MoverA &ta, MoverB &tb, int &s_set) {
     if (s_ld >= nseg) return;
-    const Seg<T> g = sm.seg[s_ld];
+    if (s_cached != s_ld) {
+      const Seg<T> v = sm.seg[s_ld];
+      g.A = uniform_ptr(v.A);
+      g.B = uniform_ptr(v.B);
+      g.lda = __builtin_amdgcn_readfirstlane(v.lda);
+      g.ldb = __builtin_amdgcn_readfirstlane(v.ldb);
+      g.kb = __builtin_amdgcn_readfirstlane(v.kb);
+      g.ke = __builtin_amdgcn_readfirstlane(v.ke);
+      s_cached = s_ld;
+    }
     if constexpr (FAST) {
       if (s_set != s_ld) {
         ta.setup(g.lda, a_extent, a0);
