@@ -385,17 +385,20 @@ def main():
             torch.cuda.synchronize()
             return a.elapsed_time(b_) / n
 
-        def fwd_only(naive):
+        def fwd_only(naive, two_step=False):
             def f(i):
-                model.run(batch_of(slots[i % len(slots)], graphs[i % len(slots)]), backward=False, naive=naive)
+                model.run(batch_of(slots[i % len(slots)], graphs[i % len(slots)]), backward=False, naive=naive, two_step=two_step)
             return f
         n_ab = max(20, K // 4)
         fwd_only(False)(0)
         merged_fwd_ms = gpu_ms(fwd_only(False), n_ab)
-        naive_fwd_ms = None
+        naive_fwd_ms = two_step_fwd_ms = None
         if not attention:
             fwd_only(True)(0)
             naive_fwd_ms = gpu_ms(fwd_only(True), n_ab)
+            if len(set(g.feat_dim)) == 1 and all(len(set(lw.in_dim)) == 1 for lw in model.layers):
+                fwd_only(False, True)(0)
+                two_step_fwd_ms = gpu_ms(fwd_only(False, True), n_ab)
 
         def serial_loop(n):          # build, wait, compute, wait: nothing overlaps
             t = time.perf_counter()
@@ -410,10 +413,13 @@ def main():
         serial_ms = 1e3 * serial_loop(n_ab)
         abl = dict(forward_merged_ms=round(merged_fwd_ms, 4),
                    forward_per_relation_launches_ms=None if naive_fwd_ms is None else round(naive_fwd_ms, 4),
+                   forward_two_step_aggregation_ms=None if two_step_fwd_ms is None else round(two_step_fwd_ms, 4),
                    step_serial_build_then_compute_ms=round(serial_ms, 4),
                    step_overlapped_ms=round(1e3 * t_pipe / K, 4), step_gpu_only_ms=round(1e3 * t_gpu / K, 4),
                    host_builders=args.concurrent_builds,
-                   note="forward_*: merge + all layers forward, index arrays resident (GPU time between events); "
+                   note="forward_*: merge + all layers forward, index arrays resident (GPU time between events); two_step: "
+                        "the aggregation as Algorithm 1 states it (source rows of all semantic graphs gathered into "
+                        "FeatureCat, then reduced by destination) instead of the fused gather-mean; "
                         "serial: every step builds its index arrays with one builder, waits, computes, waits; "
                         "overlapped: bench.py's `value` loop")
 

@@ -303,6 +303,18 @@ hgnn_status hgnn_layer_fwd_naive(hgnn_ctx *ctx, void *stream, hgnn_graph *g, int
                                  const hgnn_layer_params *p, const void *x_merged, void *h_out,
                                  void *saved, size_t saved_bytes, void *scratch,
                                  size_t scratch_bytes, int32_t *launches);
+/* Materialising baseline: the same layer forward with the aggregation done in the two steps in which
+ * Algorithm 1 (Section 4.2) states it -- the source rows of all semantic graphs gathered and concatenated
+ * into FeatureCat [num_edges x F] (dtype), then reduced by destination -- instead of the fused gather-mean
+ * of hgnn_layer_fwd, which never writes FeatureCat.  Results (h_out, saved) are bit-identical to
+ * hgnn_layer_fwd's; hgnn_layer_bwd can follow.  Mean aggregation only, and every vertex type must have
+ * the same input width F (else HGNN_EUNSUPPORTED).  feature_cat: device scratch of at least
+ * num_edges(layer) * F * sizeof(dtype) bytes, 16-byte aligned (HGNN_EINVAL if smaller); the other
+ * arguments as for hgnn_layer_fwd.  `launches` (host out, may be NULL): kernels enqueued. */
+hgnn_status hgnn_layer_fwd_two_step(hgnn_ctx *ctx, void *stream, hgnn_graph *g, int32_t layer,
+                                    const hgnn_layer_params *p, const void *x_merged, void *h_out,
+                                    void *saved, size_t saved_bytes, void *scratch, size_t scratch_bytes,
+                                    void *feature_cat, size_t feature_cat_bytes, int32_t *launches);
 /* Number of kernels hgnn_layer_fwd / hgnn_layer_bwd enqueue for this layer. */
 hgnn_status hgnn_layer_launch_count(hgnn_ctx *ctx, hgnn_graph *g, int32_t layer,
                                     const hgnn_layer_params *p, int32_t *fwd_launches,

@@ -103,6 +103,8 @@ def _load():
         "hgnn_layer_fwd": [vp, vp, vp, i32, C.POINTER(LayerParams), vp, vp, vp, C.c_size_t, vp, C.c_size_t],
         "hgnn_layer_fwd_naive": [vp, vp, vp, i32, C.POINTER(LayerParams), vp, vp, vp, C.c_size_t, vp, C.c_size_t,
                                  C.POINTER(i32)],
+        "hgnn_layer_fwd_two_step": [vp, vp, vp, i32, C.POINTER(LayerParams), vp, vp, vp, C.c_size_t, vp, C.c_size_t,
+                                    vp, C.c_size_t, C.POINTER(i32)],
         "hgnn_layer_bwd": [vp, vp, vp, i32, C.POINTER(LayerParams), vp, vp, vp, vp, vp, C.POINTER(LayerGrads),
                            vp, C.c_size_t],
         "hgnn_layer_launch_count": [vp, vp, i32, C.POINTER(LayerParams), C.POINTER(i32), C.POINTER(i32)],
@@ -130,7 +132,7 @@ EXPORTS = ["hgnn_create", "hgnn_destroy", "hgnn_last_error", "hgnn_merge_feature
            "hgnn_build_semantic_csr", "hgnn_sampler_create", "hgnn_sampler_destroy", "hgnn_sample_and_build",
            "hgnn_graph_ids", "hgnn_graph_minibatch_view", "hgnn_graph_wait_stream",
            "hgnn_graph_wait", "hgnn_graph_host_view", "hgnn_graph_release", "hgnn_layer_workspace_bytes",
-           "hgnn_layer_fwd", "hgnn_layer_bwd", "hgnn_layer_fwd_naive", "hgnn_layer_launch_count",
+           "hgnn_layer_fwd", "hgnn_layer_bwd", "hgnn_layer_fwd_naive", "hgnn_layer_fwd_two_step", "hgnn_layer_launch_count",
            "hgnn_softmax_xent", "hgnn_adam_update", "hgnn_adam_update_rows", "hgnn_probe_select", "hgnn_probe_read"]
 
 KERNEL_IDS = dict(merge=0, transpose_w=1, spmm_fwd=2, gemm_fwd=3, zero_grads=4, relu_bias_bwd=5, gemm_dw=6,
@@ -173,6 +175,12 @@ class Graph:
                      ("perm", v.edges), ("cptr", v.src_rows + 1), ("crow", v.transpose_edges), ("cperm", v.transpose_edges)):
             out[k] = np.ctypeslib.as_array(getattr(v, k), shape=(n,)).copy() if n > 0 else np.zeros(0, np.int32)
         return out
+
+    def num_edges(self, layer) -> int:
+        """Edges of the layer's merged CSR (waits for the build)."""
+        v = CsrView()
+        _check(lib.hgnn_graph_host_view(self.ctx.handle, self.handle, layer, C.byref(v)))
+        return int(v.edges)
 
     # ---- graphs made by hgnn_sample_and_build ----
     def ids(self, device=False):
@@ -424,6 +432,14 @@ class Context:
         _check(lib.hgnn_layer_fwd_naive(self.handle, _stream_ptr(self.device), graph.handle, layer, C.byref(lp.params),
                                         _ptr(x_merged), _ptr(h_out), _ptr(saved), saved.numel() * saved.element_size(),
                                         _ptr(scratch), scratch.numel() * scratch.element_size(), C.byref(n)))
+        return n.value
+
+    def hgnn_layer_fwd_two_step(self, graph, layer, lp, x_merged, h_out, saved, scratch, feature_cat) -> int:
+        n = C.c_int32()
+        _check(lib.hgnn_layer_fwd_two_step(self.handle, _stream_ptr(self.device), graph.handle, layer, C.byref(lp.params),
+                                           _ptr(x_merged), _ptr(h_out), _ptr(saved), saved.numel() * saved.element_size(),
+                                           _ptr(scratch), scratch.numel() * scratch.element_size(), _ptr(feature_cat),
+                                           feature_cat.numel() * feature_cat.element_size(), C.byref(n)))
         return n.value
 
     def hgnn_layer_bwd(self, graph, layer, lp, x_merged, h_out, saved, grad_h, grad_x_merged, scratch):

@@ -927,7 +927,7 @@ hgnn_status hgnn_layer_workspace_bytes(hgnn_ctx *ctx, hgnn_graph *g, int32_t lay
 
 static hgnn_status fwd_common(hgnn_ctx *ctx, void *stream, hgnn_graph *g, int32_t layer, const hgnn_layer_params *p,
                               const void *x, void *h, void *saved, size_t saved_bytes, void *scratch, size_t scratch_bytes,
-                              bool naive, int32_t *launches) {
+                              bool naive, int32_t *launches, void *feature_cat = nullptr, size_t feature_cat_bytes = 0) {
   Plan pl;
   hgnn_status st = make_plan(ctx, g, layer, p, pl, true);
   if (st != HGNN_OK) return st;
@@ -957,11 +957,21 @@ static hgnn_status fwd_common(hgnn_ctx *ctx, void *stream, hgnn_graph *g, int32_
   }
   ++n;
   if (!naive) {
-    {
+    if (feature_cat) {
+      // Algorithm 1 in two steps (gather into FeatureCat, then reduce by destination) instead of the fused kernel
+      for (int t = 0; t < T; ++t)
+        if (p->in_dim[t] != p->in_dim[0]) HGNN_FAIL(HGNN_EUNSUPPORTED, "the two-step aggregation needs one input width for all types");
+      const size_t need = (size_t)pl.dev.edges * p->in_dim[0] * pl.es;
+      if (feature_cat_bytes < need) HGNN_FAIL(HGNN_EINVAL, "feature_cat too small: need %zu bytes", need);
+      if ((uintptr_t)feature_cat & 15) HGNN_FAIL(HGNN_EINVAL, "device buffers must be 16-byte aligned");
+      Probe pb(ctx, s, HGNN_K_SPMM_FWD, layer);
+      if ((st = launch_aggregate_literal(s, ctx->dtype, pl.dev, p->in_dim[0], x, feature_cat, saved)) != HGNN_OK) return st;
+      n += (pl.dev.edges > 0) + (pl.dev.rows > 0);
+    } else {
       Probe pb(ctx, s, HGNN_K_SPMM_FWD, layer);
       if ((st = launch_spmm_fwd(s, ctx->dtype, pl.dev, pl.tt, pl.rt, pl.max_dim, x, saved, 0, pl.dev.rows)) != HGNN_OK) return st;
+      if (pl.dev.rows > 0) ++n;
     }
-    if (pl.dev.rows > 0) ++n;
     {
       Probe pb(ctx, s, HGNN_K_GEMM_FWD, layer);
       if ((st = launch_gemm_fwd(s, ctx->dtype, pl.dev, pl.tt, pl.rt, pl.pt, pl.wt, tl, live, pl.H, p->relu, x, saved, wtb, h, -1, nullptr, tile_mn)) != HGNN_OK) return st;
@@ -1019,6 +1029,14 @@ hgnn_status hgnn_layer_fwd_naive(hgnn_ctx *ctx, void *stream, hgnn_graph *g, int
                                  const void *x_merged, void *h_out, void *saved, size_t saved_bytes, void *scratch,
                                  size_t scratch_bytes, int32_t *launches) {
   return fwd_common(ctx, stream, g, layer, p, x_merged, h_out, saved, saved_bytes, scratch, scratch_bytes, true, launches);
+}
+
+hgnn_status hgnn_layer_fwd_two_step(hgnn_ctx *ctx, void *stream, hgnn_graph *g, int32_t layer, const hgnn_layer_params *p,
+                                    const void *x_merged, void *h_out, void *saved, size_t saved_bytes, void *scratch,
+                                    size_t scratch_bytes, void *feature_cat, size_t feature_cat_bytes, int32_t *launches) {
+  if (!feature_cat) HGNN_FAIL(HGNN_EINVAL, "feature_cat is NULL");
+  return fwd_common(ctx, stream, g, layer, p, x_merged, h_out, saved, saved_bytes, scratch, scratch_bytes, false, launches,
+                    feature_cat, feature_cat_bytes);
 }
 
 static void seg_tiles_da(hgnn_ctx *ctx, const Plan &pl, const hgnn_layer_params *p, const int32_t *rel_edge_off, SegTab &tl) {

@@ -274,6 +274,10 @@ hgnn_status launch_merge(hipStream_t s, int dtype, int T, const void *const *sto
 // rows [row_begin,row_end) of the merged CSR: z[row] = mean of the x rows in colidx
 hgnn_status launch_spmm_fwd(hipStream_t s, int dtype, const LayerDev &L, const TypeTab &tt, const RelTab &rt,
                             int max_dim, const void *x, void *z, int row_begin, int row_end);
+// the same aggregate in the two steps of the paper's Algorithm 1: FeatureCat [edges x F] = gathered source rows,
+// then a mean per merged row (all types one width F)
+hgnn_status launch_aggregate_literal(hipStream_t s, int dtype, const LayerDev &L, int F, const void *x, void *feature_cat,
+                                     void *z);
 // dx[c] = sum over transpose row c of dz[crow] (+ root part for destination rows)
 hgnn_status launch_spmm_bwd(hipStream_t s, int dtype, const LayerDev &L, const TypeTab &tt, const RelTab &rt,
                             const PtrTab &pt, int max_dim, uint32_t want_types, const void *dz, void *dx, float *partial);

@@ -116,6 +116,69 @@ bool launch_spmm_fwd_uniform(hipStream_t s, int dtype, const LayerDev &L, int F,
 }
 
 // ------------------------------------------------------------------------------------------
+// Algorithm 1 of the paper taken literally, as a baseline for the fused gather-mean above: the source rows of
+// all semantic graphs are collected into one matrix FeatureCat [E x F] (IndexSelect per relation + Concat: in
+// the merged CSR the edges of all relations are already one list, so this is one gather), and Aggregate then
+// reduces FeatureCat by destination (one segment per merged row).  The sums run over the edges in the order
+// of the fused kernel, so the two give the same bits.
+template <typename T>
+__global__ void __launch_bounds__(256) feature_cat_kernel(const int32_t *__restrict__ colidx, const T *__restrict__ x,
+                                                           T *__restrict__ fc, int nvec, int64_t pieces) {
+  const uint4 *xb = reinterpret_cast<const uint4 *>(x);
+  uint4 *fb = reinterpret_cast<uint4 *>(fc);
+  for (int64_t i = (int64_t)blockIdx.x * 256 + threadIdx.x; i < pieces; i += (int64_t)gridDim.x * 256) {
+    const int64_t e = i / nvec;
+    const int q = (int)(i - e * nvec);
+    fb[i] = xb[(int64_t)colidx[e] * nvec + q];
+  }
+}
+
+// one lane per 16-byte piece of a merged row: z[row] = mean of fc[rowptr[row] .. rowptr[row + 1])
+template <typename T>
+__global__ void __launch_bounds__(256) segment_mean_kernel(const int32_t *__restrict__ rowptr, const T *__restrict__ fc,
+                                                            T *__restrict__ z, int nvec, int64_t pieces) {
+  using V = Vec16<T>;
+  const uint4 *fb = reinterpret_cast<const uint4 *>(fc);
+  for (int64_t i = (int64_t)blockIdx.x * 256 + threadIdx.x; i < pieces; i += (int64_t)gridDim.x * 256) {
+    const int64_t row = i / nvec;
+    const int q = (int)(i - row * nvec);
+    const int beg = rowptr[row], end = rowptr[row + 1];
+    float acc[V::N];
+#pragma unroll
+    for (int k = 0; k < V::N; ++k) acc[k] = 0.f;
+    for (int e = beg; e < end; ++e) V::add(acc, fb[(int64_t)e * nvec + q]);
+    const float inv = end > beg ? 1.0f / (float)(end - beg) : 0.0f;
+#pragma unroll
+    for (int k = 0; k < V::N; ++k) acc[k] *= inv;
+    reinterpret_cast<uint4 *>(z)[i] = V::pack(acc);
+  }
+}
+
+hgnn_status launch_aggregate_literal(hipStream_t s, int dtype, const LayerDev &L, int F, const void *x, void *feature_cat,
+                                     void *z) {
+  const int es = dtype == HGNN_BF16 ? 2 : 4;
+  const int nvec = F * es / 16;
+  const int64_t pe = (int64_t)L.edges * nvec, pr = (int64_t)L.rows * nvec;
+  if (pe > 0) {
+    const int blocks = (int)std::min<int64_t>((pe + 255) / 256, 1 << 16);
+    if (dtype == HGNN_BF16)
+      HGNN_LAUNCH(feature_cat_kernel<bf16>, dim3(blocks), dim3(256), 0, s, L.colidx, (const bf16 *)x, (bf16 *)feature_cat, nvec, pe);
+    else
+      HGNN_LAUNCH(feature_cat_kernel<float>, dim3(blocks), dim3(256), 0, s, L.colidx, (const float *)x, (float *)feature_cat, nvec, pe);
+    HGNN_HIP(hipGetLastError());
+  }
+  if (pr > 0) {
+    const int blocks = (int)std::min<int64_t>((pr + 255) / 256, 1 << 16);
+    if (dtype == HGNN_BF16)
+      HGNN_LAUNCH(segment_mean_kernel<bf16>, dim3(blocks), dim3(256), 0, s, L.rowptr, (const bf16 *)feature_cat, (bf16 *)z, nvec, pr);
+    else
+      HGNN_LAUNCH(segment_mean_kernel<float>, dim3(blocks), dim3(256), 0, s, L.rowptr, (const float *)feature_cat, (float *)z, nvec, pr);
+    HGNN_HIP(hipGetLastError());
+  }
+  return HGNN_OK;
+}
+
+// ------------------------------------------------------------------------------------------
 // Transpose: dx[c] = sum over transpose row c of dz[crow] (+ root-term gradient for destination rows).
 // Only the source rows of the vertex types listed in `ranges` are produced; rows longer than kLongRow are
 // left to the chunked path.

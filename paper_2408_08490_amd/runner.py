@@ -205,7 +205,7 @@ class Model:
         b.graph.wait_stream()
 
     # ---- device side of a step ----
-    def run(self, b: Batch, backward=True, naive=False, need_input_grad=True):
+    def run(self, b: Batch, backward=True, naive=False, need_input_grad=True, two_step=False):
         ctx, L = self.ctx, len(self.layers)
         if b.sampled and b.ids_dev is None:
             self._resolve_sampled(b)
@@ -220,7 +220,10 @@ class Model:
             sv = self._get(f"saved{l}", sb)
             sc = self._get("scratch", cb)
             h = self._typed(f"h{l}", sum(blk.n_dst) * lp.out_dim)
-            if naive:
+            if two_step:     # the materialising form of the aggregation (FeatureCat, then reduce)
+                fc = self._typed("feature_cat", max(1, b.graph.num_edges(l)) * max(lp.in_dim))
+                launches.append(ctx.hgnn_layer_fwd_two_step(b.graph, l, lp, xs[-1], h, sv, sc, fc))
+            elif naive:
                 launches.append(ctx.hgnn_layer_fwd_naive(b.graph, l, lp, xs[-1], h, sv, sc))
             else:
                 ctx.hgnn_layer_fwd(b.graph, l, lp, xs[-1], h, sv, sc)

@@ -110,7 +110,8 @@ def oracle_run(cfg, g, mb, ws, input_grad=None):
 
 
 def run_case(index, scale=1.0, batch=None, verbose=False, use_edge_id=True, check_naive=False, graph=None,
-             input_grad=None, backward=True, cfg_edit=None, grad_tol=None, sampled=None, need_input_grad=True):
+             input_grad=None, backward=True, cfg_edit=None, grad_tol=None, sampled=None, need_input_grad=True,
+             check_two_step=False):
     """cfg_edit(cfg, g, mb, ws): optional hook that changes the prepared inputs (e.g. the storage type) before
     both sides run.  grad_tol: optional {substring of a gradient's name: tolerance or None}; a matching
     gradient is held to that tolerance in both norms against the tie-broken oracle (None: reported only).
@@ -281,6 +282,18 @@ def run_case(index, scale=1.0, batch=None, verbose=False, use_edge_id=True, chec
         report["naive_launches"] = out2["launches"]
         report["merged_launches"] = [model.ctx.hgnn_layer_launch_count(bt.graph, l, model.layers[l])
                                      for l in range(len(ws))]
+    if check_two_step:
+        # Algorithm 1 in its two stated steps (FeatureCat, then reduce): against the oracle like the fused path,
+        # and bit for bit against the fused path's outputs
+        fused = [h.clone() for h in out["h"]]
+        out3 = model.run(bt, backward=False, two_step=True)
+        torch.cuda.synchronize()
+        for l in range(len(ws)):
+            want = np.concatenate([h.ravel() for h in ref["h"][l]])
+            chk(f"L{l}.h_two_step", out3["h"][l].float().cpu().numpy(), want)
+            chk(f"L{l}.h_two_step_bits", out3["h"][l].view(torch.uint8).cpu().numpy(), fused[l].view(torch.uint8).cpu().numpy(),
+                exact=True)
+        report["two_step_launches"] = out3["launches"]
     bt.graph.release()
     model.close()
     report["ok"] = ok

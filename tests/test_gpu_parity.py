@@ -40,6 +40,20 @@ def test_first_layer_without_input_gradient_buffer():
     _assert_ok(run_case(2, scale=0.05, batch=256, verbose=True, need_input_grad=False))
 
 
+def test_two_step_aggregation_of_algorithm_1():
+    """The materialising form of Algorithm 1 (gather into FeatureCat, then reduce by destination) gives the
+    oracle's outputs and the fused kernel's bits: fp32 (config 1), bf16 (config 2), many relations (config 5)."""
+    _assert_ok(run_case(1, scale=0.05, batch=256, verbose=True, backward=False, check_two_step=True))
+    _assert_ok(run_case(2, scale=0.05, batch=512, verbose=True, backward=False, check_two_step=True))
+    _assert_ok(run_case(5, verbose=True, backward=False, check_two_step=True))
+
+
+def test_two_step_aggregation_rejects_ragged_widths():
+    from paper_2408_08490_amd.binding import HgnnError
+    with pytest.raises(HgnnError, match="one input width"):
+        run_case(0, backward=False, check_two_step=True)
+
+
 def test_config3_many_types_fp32_scaled():
     _assert_ok(run_case(3, scale=0.02, batch=128, verbose=True, check_naive=True))
 
