@@ -99,7 +99,7 @@ template <typename T, typename FN> static bool dispatch_width(int nvec, FN fn) {
   else if (nvec <= 8) fn.template operator()<3, 1>();
   else if (nvec <= 16) fn.template operator()<4, 1>();
   else if (nvec <= 32) fn.template operator()<4, 2>();
-  else if (nvec <= 64) fn.template operator()<5, 2>();
+  else if (nvec <= 64) fn.template operator()<6, 1>();
   else if (nvec <= 128) fn.template operator()<6, 2>();
   else if (nvec <= 256) fn.template operator()<6, 4>();
   else return false;
