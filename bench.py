@@ -54,6 +54,9 @@ def main():
                          "three times: reference for scaling rocprofv3 FETCH_SIZE / WRITE_SIZE readings")
     ap.add_argument("--host-warmup-s", type=float, default=3.0,
                     help="seconds of further untimed pipelined steps after the W warm-up steps (0 with --warmup 0)")
+    ap.add_argument("--build-permutation", action="store_true",
+                    help="the index build also writes perm / cperm (input position of every CSR / transpose entry), which "
+                         "the mean layers never read; the attention variant always gets them")
     ap.add_argument("--lookahead", type=int, default=24, help="mini-batches whose index build is started ahead of the GPU")
     ap.add_argument("--concurrent-builds", type=int, default=15,
                     help="host builders working on separate mini-batches at once (the host threads are split over them; "
@@ -90,6 +93,7 @@ def main():
     model = Model(g.schema, g.feat_dim, g.stores, ws, dtype=cfg.dtype,
                   loss=("xent" if cfg.loss == "xent" else "dot"), target_type=mbs[0].target_type,
                   host_threads=args.host_threads or args.concurrent_builds, concurrent_builds=args.concurrent_builds,
+                  build_permutation=args.build_permutation,
                   # T0 carries fixed input features; only the learnable embeddings of T1-T3 need input gradients
                   first_layer_input_grad=([0, 1, 1, 1] if cfg.index in (1, 2, 4) and not args.all_input_grads else None))
     ctx = model.ctx
@@ -485,7 +489,10 @@ def main():
         config=dict(workload="configs[%d] %s: %d types / %d relations, %d targets, fanout %s, layers %s, scale %.3g" %
                     (cfg.index, cfg.name, sch.num_types, sch.num_rels, cfg.batch, cfg.fanouts[::-1],
                      [g.feat_dim[0]] + cfg.layer_out, cfg.scale),
-                    minibatch_sizes=sizes, distinct_minibatches=len(slots)),
+                    minibatch_sizes=sizes, distinct_minibatches=len(slots),
+                    index_build_outputs=("rowptr, colidx, cptr, crow, chunk lists" +
+                                         (", perm, cperm" if args.build_permutation or attention else
+                                          " (perm / cperm, which no kernel of this path reads, are left out)"))),
         gpu_only_mb_per_s=round(K / t_gpu, 2), gpu_only_ms_per_step=round(1e3 * t_gpu / K, 4),
         host_build_ms=round(1e3 * t_build, 3), sampler_in_loop=sil, training_step=train, ablation=abl, launches_per_layer=launches,
         roofline=roof, roofline_projection=roof_proj, roofline_weight_grad=roof_dw, roofline_aggregation=roof_agg,

@@ -133,6 +133,13 @@ hgnn_status hgnn_set_edge_types(hgnn_ctx *ctx, const int32_t *global_edge_type, 
  * status of the build.  Argument errors (NULL, num_layers outside 1..8) are reported here. */
 hgnn_status hgnn_build_semantic_csr(hgnn_ctx *ctx, int32_t num_layers, const hgnn_coo_layer *layers,
                                     hgnn_graph **out);
+/* Whether later builds (hgnn_build_semantic_csr, hgnn_sample_and_build) produce the two permutations
+ * `perm` and `cperm` (default: they do).  The mean-aggregation layers read neither; without them the sorts
+ * carry one int per edge instead of two and write half as much, which shortens the build by about a
+ * tenth.  With enabled = 0 the host view returns NULL for perm and cperm; every other array is unchanged.
+ * Ignored by a context of the attention variant (its backward needs cperm).  Must not be called while
+ * builds are in flight. */
+hgnn_status hgnn_set_build_permutation(hgnn_ctx *ctx, int32_t enabled);
 /* Blocks the calling host thread until the build and the upload have finished; returns the
  * build's status. */
 hgnn_status hgnn_graph_wait(hgnn_ctx *ctx, hgnn_graph *g);
@@ -144,7 +151,7 @@ hgnn_status hgnn_graph_wait(hgnn_ctx *ctx, hgnn_graph *g);
  *   rel_edge_off[R+1]   CSR position range of relation r's edges
  *   rowptr [rows+1], colidx [edges]  merged CSR; colidx = row of the source in x_merged
  *                       (= row_off[src type] + local source); inside a row, input order is kept
- *   perm   [edges]      input position of the CSR edge
+ *   perm   [edges]      input position of the CSR edge (NULL after hgnn_set_build_permutation(ctx, 0), as is cperm)
  *   cptr [src_rows+1], crow [edges], cperm [edges]  transpose: for every x_merged row the edges
  *                       that read it, ascending CSR position; crow = merged CSR row, cperm = CSR position
  * Any output pointer may be NULL. */

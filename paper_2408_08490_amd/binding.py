@@ -91,6 +91,7 @@ def _load():
                                 C.POINTER(i32), C.POINTER(i64)],
         "hgnn_build_semantic_csr": [vp, i32, C.POINTER(CooLayer), C.POINTER(vp)],
         "hgnn_set_edge_types": [vp, vp, i64],
+        "hgnn_set_build_permutation": [vp, i32],
         "hgnn_graph_wait": [vp, vp],
         "hgnn_sampler_create": [vp, C.POINTER(HostGraph), C.POINTER(vp)],
         "hgnn_sample_and_build": [vp, vp, i32, vp, i64, i32, C.POINTER(i32), C.c_uint64, C.POINTER(vp), C.POINTER(vp)],
@@ -131,7 +132,7 @@ lib = _load()
 EXPORTS = ["hgnn_create", "hgnn_destroy", "hgnn_last_error", "hgnn_merge_features", "hgnn_set_edge_types",
            "hgnn_build_semantic_csr", "hgnn_sampler_create", "hgnn_sampler_destroy", "hgnn_sample_and_build",
            "hgnn_graph_ids", "hgnn_graph_minibatch_view", "hgnn_graph_wait_stream",
-           "hgnn_graph_wait", "hgnn_graph_host_view", "hgnn_graph_release", "hgnn_layer_workspace_bytes",
+           "hgnn_set_build_permutation", "hgnn_graph_wait", "hgnn_graph_host_view", "hgnn_graph_release", "hgnn_layer_workspace_bytes",
            "hgnn_layer_fwd", "hgnn_layer_bwd", "hgnn_layer_fwd_naive", "hgnn_layer_fwd_two_step", "hgnn_layer_launch_count",
            "hgnn_softmax_xent", "hgnn_adam_update", "hgnn_adam_update_rows", "hgnn_probe_select", "hgnn_probe_read"]
 
@@ -173,6 +174,9 @@ class Graph:
         out = dict(rows=v.rows, edges=v.edges, src_rows=v.src_rows, transpose_edges=v.transpose_edges)
         for k, n in (("rel_row_off", R + 1), ("rel_edge_off", R + 1), ("rowptr", v.rows + 1), ("colidx", v.edges),
                      ("perm", v.edges), ("cptr", v.src_rows + 1), ("crow", v.transpose_edges), ("cperm", v.transpose_edges)):
+            if k in ("perm", "cperm") and not getattr(v, k):   # built without the permutations
+                out[k] = None
+                continue
             out[k] = np.ctypeslib.as_array(getattr(v, k), shape=(n,)).copy() if n > 0 else np.zeros(0, np.int32)
         return out
 
@@ -374,6 +378,9 @@ class Context:
     def hgnn_set_edge_types(self, global_edge_type):
         t = np.ascontiguousarray(global_edge_type, dtype=np.int32)
         _check(lib.hgnn_set_edge_types(self.handle, t.ctypes.data, t.shape[0]))
+
+    def hgnn_set_build_permutation(self, enabled: bool):
+        _check(lib.hgnn_set_build_permutation(self.handle, 1 if enabled else 0))
 
     def hgnn_build_semantic_csr(self, blocks, global_edge_type=None, use_edge_id=False, transpose_types=None) -> Graph:
         """blocks: objects with n_src, n_dst, edge_index (2 x E, int64 or int32), edge_type / edge_id.

@@ -624,6 +624,7 @@ void index_edge_type_runs(hgnn_ctx *ctx) {
 // hgnn_build_semantic_csr and on a builder's thread for sampled mini-batches, hence the message by reference.
 hgnn_status plan_graph(hgnn_ctx *ctx, hgnn_graph *g, std::string &msg) {
   const int T = ctx->T, R = ctx->R, num_layers = g->num_layers;
+  g->with_perm = ctx->build_perm || ctx->agg == HGNN_AGG_ATTN;  // the attention backward walks cperm
   char buf[256];
   auto fail = [&](hgnn_status st, const char *fmt, auto... a) {
     std::snprintf(buf, sizeof(buf), fmt, a...);
@@ -868,6 +869,12 @@ hgnn_status hgnn_set_edge_types(hgnn_ctx *ctx, const int32_t *global_edge_type, 
   return HGNN_OK;
 }
 
+hgnn_status hgnn_set_build_permutation(hgnn_ctx *ctx, int32_t enabled) {
+  if (!ctx) HGNN_FAIL(HGNN_EINVAL, "NULL context");
+  ctx->build_perm = enabled != 0;
+  return HGNN_OK;
+}
+
 hgnn_status hgnn_graph_wait(hgnn_ctx *ctx, hgnn_graph *g) {
   if (!ctx || !g) HGNN_FAIL(HGNN_EINVAL, "NULL argument");
   hgnn_status st = wait_built(g);
@@ -885,8 +892,8 @@ hgnn_status hgnn_graph_host_view(hgnn_ctx *ctx, hgnn_graph *g, int32_t layer, hg
   const int32_t *b = g->slab.host;
   v->rows = L.rows; v->edges = L.edges; v->src_rows = L.src_rows; v->transpose_edges = L.tedges;
   v->rel_row_off = b + L.o_rel_row_off; v->rel_edge_off = b + L.o_rel_edge_off;
-  v->rowptr = b + L.o_rowptr; v->colidx = b + L.o_colidx; v->perm = b + L.o_perm;
-  v->cptr = b + L.o_cptr; v->crow = b + L.o_crow; v->cperm = b + L.o_cperm;
+  v->rowptr = b + L.o_rowptr; v->colidx = b + L.o_colidx; v->perm = g->with_perm ? b + L.o_perm : nullptr;
+  v->cptr = b + L.o_cptr; v->crow = b + L.o_crow; v->cperm = g->with_perm ? b + L.o_cperm : nullptr;
   return HGNN_OK;
 }
 

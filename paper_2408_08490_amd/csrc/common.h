@@ -219,6 +219,7 @@ struct hgnn_graph {
   hipEvent_t ready = nullptr;
   std::unique_ptr<hgnn::SampleJob> job;  // set for hgnn_sample_and_build
   bool sampled = false;                  // the job's results are complete (guarded by m)
+  bool with_perm = true;                 // the build writes perm / cperm (fixed when the build is planned)
   size_t o_ids[hgnn::kMaxT] = {};        // per type: offset of the sampled ids in the block (int32 units)
 };
 
@@ -236,6 +237,7 @@ struct hgnn_ctx {
   std::mutex pm;  // slab / event pool
   std::vector<hgnn::Slab> free_slabs;
   std::vector<hipEvent_t> free_events;
+  bool build_perm = true;            // later builds produce perm / cperm (hgnn_set_build_permutation)
   std::vector<uint8_t> edge_types8;  // compact copy of the registered global edge-type table
   // the same table as runs of equal type, kept when there are few of them (edge ids grouped by relation, the usual
   // case): type of id = run_rel[j], j = the run that holds id, found from run_lut[id >> run_shift] (the run in which

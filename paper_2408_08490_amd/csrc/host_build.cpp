@@ -125,6 +125,17 @@ struct PackedRec {
   static int32_t payload(const int32_t *r) { return (int32_t)((uint32_t)r[1] & ((1u << kPayloadBits) - 1u)); }
 };
 
+// One int: for builds that leave the permutation out, the item is not carried at all.
+struct SlimRec {
+  static constexpr int W = 1, kPayloadBits = 32 - kBucketShift;
+  static void put(int32_t *r, int32_t key, int32_t, int32_t payload) {
+    r[0] = (int32_t)(((uint32_t)key << kPayloadBits) | (uint32_t)payload);
+  }
+  static int32_t key_low(const int32_t *r, int32_t) { return (int32_t)((uint32_t)r[0] >> kPayloadBits); }
+  static int32_t item(const int32_t *) { return 0; }
+  static int32_t payload(const int32_t *r) { return (int32_t)((uint32_t)r[0] & ((1u << kPayloadBits) - 1u)); }
+};
+
 struct PhaseTimer {
   bool on;
   std::chrono::steady_clock::time_point t0;
@@ -182,6 +193,7 @@ static bool build_layer(hgnn_ctx *ctx, Builder &bd, hgnn_graph *g, int l, BuildE
   static const bool wide_records = getenv("HGNN_WIDE_RECORDS") != nullptr;
   const bool csc_packed = rows <= (int64_t)1 << PackedRec::kPayloadBits && !wide_records;
   const bool presorted = g->job != nullptr;
+  const bool with_perm = g->with_perm;
   if (presorted) {
     const SampleJob &job = *g->job;
     const int64_t *es = job.edge_index[l].data(), *ed = es + E;
@@ -198,7 +210,7 @@ static bool build_layer(hgnn_ctx *ctx, Builder &bd, hgnn_graph *g, int l, BuildE
         for (; e < e_end && ed[e] == i; ++e) {
           const int32_t c = col0 + (int32_t)es[e];
           colidx[e] = c;
-          perm[e] = (int32_t)e;
+          if (with_perm) perm[e] = (int32_t)e;
           if (want) ++c2[c >> kBucketShift];
         }
       }
@@ -295,8 +307,9 @@ static bool build_layer(hgnn_ctx *ctx, Builder &bd, hgnn_graph *g, int l, BuildE
     }
     base1[B1] = run;
   }
-  auto csr_sort = [&](auto rec_format) {
+  auto csr_sort = [&](auto rec_format, auto perm_flag) {
     using Rec = decltype(rec_format);
+    constexpr bool kPerm = decltype(perm_flag)::value;
     pool.parallel_for(P, [&](int p) {
       const int64_t a = std::min<int64_t>(E, p * slice), b = std::min<int64_t>(E, a + slice);
       int32_t *off = cnt1 + (size_t)p * S1;
@@ -324,13 +337,19 @@ static bool build_layer(hgnn_ctx *ctx, Builder &bd, hgnn_graph *g, int l, BuildE
         const int32_t *rec = trec + (size_t)j * Rec::W;
         const int32_t pos = h[Rec::key_low(rec, k0)]++;
         colidx[pos] = Rec::payload(rec);
-        perm[pos] = Rec::item(rec);
+        if constexpr (kPerm) perm[pos] = Rec::item(rec);
       }
     });
     tm.lap("csr level-2 buckets");
   };
-  if (src_rows <= (int64_t)1 << PackedRec::kPayloadBits && !wide_records) csr_sort(PackedRec());
-  else csr_sort(WideRec());
+  const bool fits = src_rows <= (int64_t)1 << PackedRec::kPayloadBits && !wide_records;
+  if (with_perm) {
+    if (fits) csr_sort(PackedRec(), std::true_type());
+    else csr_sort(WideRec(), std::true_type());
+  } else {
+    if (fits) csr_sort(SlimRec(), std::false_type());
+    else csr_sort(WideRec(), std::false_type());
+  }
   }
   rowptr[rows] = (int32_t)E;
   for (int r = 0; r <= R; ++r) rel_edge_off[r] = rowptr[rel_row_off[r]];
@@ -387,16 +406,18 @@ static bool build_layer(hgnn_ctx *ctx, Builder &bd, hgnn_graph *g, int l, BuildE
         while (rowptr[row + 1] <= k) ++row;
         const int32_t c = colidx[k];
         const int32_t q = off[c >> kBucketShift]++;
-        if (csc_packed) PackedRec::put(trec + (size_t)q * PackedRec::W, c, k, row);
-        else WideRec::put(trec + (size_t)q * WideRec::W, c, k, row);
+        if (!csc_packed) WideRec::put(trec + (size_t)q * WideRec::W, c, k, row);
+        else if (with_perm) PackedRec::put(trec + (size_t)q * PackedRec::W, c, k, row);
+        else SlimRec::put(trec + q, c, k, row);
       }
     }
   });
   tm.lap("csc level-1 scatter");
   std::vector<std::vector<int32_t>> &longs = bd.long_lists;
   if ((int)longs.size() < B2) longs.resize(B2);
-  auto csc_level2 = [&](auto rec_format) {
+  auto csc_level2 = [&](auto rec_format, auto perm_flag) {
     using Rec = decltype(rec_format);
+    constexpr bool kPerm = decltype(perm_flag)::value;
     pool.parallel_for(B2, [&](int b) {
       int32_t h[(1 << kBucketShift) + 1];
       const int32_t k0 = b << kBucketShift;
@@ -417,12 +438,17 @@ static bool build_layer(hgnn_ctx *ctx, Builder &bd, hgnn_graph *g, int l, BuildE
         const int32_t *rec = trec + (size_t)j * Rec::W;
         const int32_t pos = h[Rec::key_low(rec, k0)]++;
         crow[pos] = Rec::payload(rec);
-        cperm[pos] = Rec::item(rec);
+        if constexpr (kPerm) cperm[pos] = Rec::item(rec);
       }
     });
   };
-  if (csc_packed) csc_level2(PackedRec());
-  else csc_level2(WideRec());
+  if (with_perm) {
+    if (csc_packed) csc_level2(PackedRec(), std::true_type());
+    else csc_level2(WideRec(), std::true_type());
+  } else {
+    if (csc_packed) csc_level2(SlimRec(), std::false_type());
+    else csc_level2(WideRec(), std::false_type());
+  }
   cptr[src_rows] = base2[B2];
   L.tedges = base2[B2];
   tm.lap("csc level-2 buckets");

@@ -56,9 +56,11 @@ class Model:
     """Weights, feature stores and work buffers of one configuration on one GPU."""
 
     def __init__(self, schema, feat_dim, stores, layers, dtype="f32", loss="xent", target_type=0, device=0,
-                 host_threads=0, first_layer_input_grad=None, concurrent_builds=0):
+                 host_threads=0, first_layer_input_grad=None, concurrent_builds=0, build_permutation=False):
         """first_layer_input_grad: per type 0/1, which vertex types need gradients w.r.t. their input
-        features in the first layer (learnable embeddings); None = all."""
+        features in the first layer (learnable embeddings); None = all.
+        build_permutation: whether the index build also writes perm / cperm, which the mean layers never read
+        (the attention variant always gets them)."""
         self.dev = torch.device("cuda", device)
         torch.cuda.set_device(self.dev)
         self.dtype, self.loss, self.target_type = dtype, loss, target_type
@@ -70,6 +72,7 @@ class Model:
             heads = int(layers[0].a_src[0].shape[0])
         self.ctx = B.Context(schema.rel_src, schema.rel_dst, schema.num_types, dtype, device, host_threads, concurrent_builds,
                              heads=heads, attention=self.attention)
+        self.ctx.hgnn_set_build_permutation(bool(build_permutation))
         self.feat_dim = list(feat_dim)
         self.stores = [to_device(s, dtype, self.dev) for s in stores]
         self.layers: List[B.Layer] = []

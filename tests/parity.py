@@ -111,7 +111,7 @@ def oracle_run(cfg, g, mb, ws, input_grad=None):
 
 def run_case(index, scale=1.0, batch=None, verbose=False, use_edge_id=True, check_naive=False, graph=None,
              input_grad=None, backward=True, cfg_edit=None, grad_tol=None, sampled=None, need_input_grad=True,
-             check_two_step=False):
+             check_two_step=False, build_permutation=False):
     """cfg_edit(cfg, g, mb, ws): optional hook that changes the prepared inputs (e.g. the storage type) before
     both sides run.  grad_tol: optional {substring of a gradient's name: tolerance or None}; a matching
     gradient is held to that tolerance in both norms against the tie-broken oracle (None: reported only).
@@ -138,7 +138,7 @@ def run_case(index, scale=1.0, batch=None, verbose=False, use_edge_id=True, chec
     ref = oracle_run(cfg, g, mb, ws, input_grad)
     t_oracle = time.time() - t0
     model = Model(sch, g.feat_dim, g.stores, ws, dtype=cfg.dtype, loss=("xent" if cfg.loss == "xent" else "dot"),
-                  target_type=mb.target_type, first_layer_input_grad=input_grad)
+                  target_type=mb.target_type, first_layer_input_grad=input_grad, build_permutation=build_permutation)
     if sampled is not None:
         sampler = model.ctx.hgnn_sampler_create(g.num_nodes, g.in_indptr, g.in_nbr, g.edge_off)
         bt = model.prepare_sampled(sampler, targets, fanouts, sampled["seed"], labels=mb.labels, grad_out=mb.grad_out)
@@ -167,6 +167,9 @@ def run_case(index, scale=1.0, batch=None, verbose=False, use_edge_id=True, chec
     for l in range(len(mb.blocks)):
         view = bt.graph.host_view(l)
         for k in ("rel_row_off", "rel_edge_off", "rowptr", "colidx", "perm", "cptr", "crow", "cperm"):
+            if view[k] is None:      # perm / cperm of a build without the permutations (the mean layers' default)
+                assert k in ("perm", "cperm") and not build_permutation
+                continue
             chk(f"L{l}.{k}", view[k], ref["csr"][l][k], exact=True)
     want_ro = np.concatenate([[0], np.cumsum([len(i) for i in mb.ids])]).astype(np.int32)
     want_eo = np.concatenate([[0], np.cumsum([len(i) * f for i, f in zip(mb.ids, g.feat_dim)])]).astype(np.int64)

@@ -40,12 +40,16 @@ def _host_ctx(B, sch, dtype="f32", threads=4, concurrent_builds=0):
 
 @pytest.mark.parametrize("index,scale,threads", [(0, 1.0, 1), (0, 1.0, 4), (2, 0.02, 8), (3, 0.003, 3), (5, 1.0, 2),
                                                  (6, 0.1, 4), (7, 1.0, 3)])
-@pytest.mark.parametrize("use_edge_id", [False, True, "registered", "registered_interleaved"])
+@pytest.mark.parametrize("use_edge_id", [False, True, "registered", "registered_interleaved", "no_permutation"])
 def test_host_build_bit_exact(B, index, scale, threads, use_edge_id):
     cfg = make_config(index, scale=scale, batch=96)
     g = build_graph(cfg)
     mb = sample_minibatch(cfg, g)
     ctx = _host_ctx(B, g.schema, threads=threads)
+    with_perm = use_edge_id != "no_permutation"
+    if not with_perm:                               # the build that leaves perm / cperm out: all else unchanged
+        ctx.hgnn_set_build_permutation(False)
+        use_edge_id = True
     if use_edge_id == "registered":                 # edge ids alone, types from the table the context keeps
         ctx.hgnn_set_edge_types(g.edge_type)        # (ids grouped by relation: few runs of equal type)
         gr = ctx.hgnn_build_semantic_csr(mb.blocks, None, use_edge_id=True)
@@ -70,6 +74,9 @@ def test_host_build_bit_exact(B, index, scale, threads, use_edge_id):
         v = gr.host_view(l)
         assert v["rows"] == ref["rowptr"].size - 1 and v["edges"] == ref["colidx"].size
         for k in ("rel_row_off", "rel_edge_off", "rowptr", "colidx", "perm", "cptr", "crow", "cperm"):
+            if k in ("perm", "cperm") and not with_perm:
+                assert v[k] is None
+                continue
             assert np.array_equal(v[k], ref[k]), (l, k)
     gr.release()
     ctx.close()
@@ -383,6 +390,17 @@ def test_host_build_three_int_records():
         "                         transpose_types=[0, 1, 1, 1] if l == 0 else None)\n"
         "    v = gr.host_view(l)\n"
         "    for k in ('rowptr', 'colidx', 'perm', 'cptr', 'crow', 'cperm'):\n"
+        "        assert np.array_equal(v[k], ref[k]), (l, k)\n"
+        "gr.release()\n"
+        "ctx.hgnn_set_build_permutation(False)\n"      # the same records with the permutations left out
+        "gr = ctx.hgnn_build_semantic_csr(mb.blocks, g.edge_type, use_edge_id=True, transpose_types=[[0, 1, 1, 1], None])\n"
+        "for l, b in enumerate(mb.blocks):\n"
+        "    sel = O.edge_index_select(b.edge_index, g.schema.num_rels, edge_type=b.edge_type)\n"
+        "    ref = O.semantic_csr(sel, g.schema.rel_src, g.schema.rel_dst, b.n_src, b.n_dst,\n"
+        "                         transpose_types=[0, 1, 1, 1] if l == 0 else None)\n"
+        "    v = gr.host_view(l)\n"
+        "    assert v['perm'] is None and v['cperm'] is None\n"
+        "    for k in ('rowptr', 'colidx', 'cptr', 'crow'):\n"
         "        assert np.array_equal(v[k], ref[k]), (l, k)\n"
         "print('ok')\n")
     env = dict(os.environ, HGNN_WIDE_RECORDS="1")

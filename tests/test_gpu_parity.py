@@ -16,6 +16,17 @@ def test_config0_tiny_rgcn_fp32():
     _assert_ok(run_case(0, verbose=True, check_naive=True))
 
 
+def test_builds_with_the_permutations():
+    """The runner's default leaves perm / cperm out of the index build (the mean layers never read them); here
+    they are asked for and compared bit for bit like the other index arrays."""
+    rep = run_case(0, verbose=True, build_permutation=True)
+    _assert_ok(rep)
+    assert rep["L0.perm"] == "exact" and rep["L0.cperm"] == "exact"
+    rep = run_case(2, scale=0.05, batch=512, verbose=True, build_permutation=True, sampled=dict(seed=11))
+    _assert_ok(rep)
+    assert rep["L0.perm"] == "exact" and rep["L1.cperm"] == "exact"
+
+
 def test_config0_per_edge_type_input():
     _assert_ok(run_case(0, verbose=True, use_edge_id=False))
 
