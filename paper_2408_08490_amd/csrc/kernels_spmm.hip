@@ -91,13 +91,19 @@ static void launch_fwd_uniform(hipStream_t s, const LayerDev &L, const void *x, 
 }
 
 // Returns false when the shape is outside what the uniform kernels cover (the generic kernels then run).
-template <typename T, typename FN> static bool dispatch_width(int nvec, FN fn) {
-  // lanes per row: the largest power of two <= 64 that keeps the pieces per lane at 1, 2 or 4
+// Lanes per row and 16-byte pieces per lane, measured per width on the headline's two layers: the forward's rows
+// are up to `fanout` long and run best with more rows per wavefront (256-byte rows: 8 lanes x 2 pieces, 48 -> 41 us),
+// the transpose's rows are mostly one or two entries long and run best with 16 lanes x 1 piece (32 vs 37 us);
+// 1 KB rows take a whole wavefront each in both directions.
+template <typename T, bool FWD, typename FN> static bool dispatch_width(int nvec, FN fn) {
   if (nvec <= 1) fn.template operator()<0, 1>();
   else if (nvec <= 2) fn.template operator()<1, 1>();
   else if (nvec <= 4) fn.template operator()<2, 1>();
   else if (nvec <= 8) fn.template operator()<3, 1>();
-  else if (nvec <= 16) fn.template operator()<4, 1>();
+  else if (nvec <= 16) {
+    if constexpr (FWD) fn.template operator()<3, 2>();
+    else fn.template operator()<4, 1>();
+  }
   else if (nvec <= 32) fn.template operator()<4, 2>();
   else if (nvec <= 64) fn.template operator()<6, 1>();
   else if (nvec <= 128) fn.template operator()<6, 2>();
@@ -111,8 +117,8 @@ bool launch_spmm_fwd_uniform(hipStream_t s, int dtype, const LayerDev &L, int F,
   const int es = dtype == HGNN_BF16 ? 2 : 4;
   const int nvec = F * es / 16;
   if (dtype == HGNN_BF16)
-    return dispatch_width<bf16>(nvec, [&]<int LPRL, int C>() { launch_fwd_uniform<bf16, LPRL, C>(s, L, x, z, F, row_begin, row_end); });
-  return dispatch_width<float>(nvec, [&]<int LPRL, int C>() { launch_fwd_uniform<float, LPRL, C>(s, L, x, z, F, row_begin, row_end); });
+    return dispatch_width<bf16, true>(nvec, [&]<int LPRL, int C>() { launch_fwd_uniform<bf16, LPRL, C>(s, L, x, z, F, row_begin, row_end); });
+  return dispatch_width<float, true>(nvec, [&]<int LPRL, int C>() { launch_fwd_uniform<float, LPRL, C>(s, L, x, z, F, row_begin, row_end); });
 }
 
 // ------------------------------------------------------------------------------------------
@@ -321,8 +327,8 @@ bool launch_spmm_bwd_uniform(hipStream_t s, int dtype, const LayerDev &L, const 
   const int es = dtype == HGNN_BF16 ? 2 : 4;
   const int nvec = F * es / 16;
   if (dtype == HGNN_BF16)
-    return dispatch_width<bf16>(nvec, [&]<int LPRL, int C>() { launch_bwd_uniform<bf16, LPRL, C>(s, L, rr, dz, dx, F, partial); });
-  return dispatch_width<float>(nvec, [&]<int LPRL, int C>() { launch_bwd_uniform<float, LPRL, C>(s, L, rr, dz, dx, F, partial); });
+    return dispatch_width<bf16, false>(nvec, [&]<int LPRL, int C>() { launch_bwd_uniform<bf16, LPRL, C>(s, L, rr, dz, dx, F, partial); });
+  return dispatch_width<float, false>(nvec, [&]<int LPRL, int C>() { launch_bwd_uniform<float, LPRL, C>(s, L, rr, dz, dx, F, partial); });
 }
 
 }  // namespace hgnn
