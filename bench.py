@@ -26,7 +26,7 @@ HBM_PEAK_GBS = 8000.0
 MFMA_BF16_PEAK_TFLOPS = 2500.0
 # HBM bytes per launch of the two probed kernels on the default workload, from the rocprofv3 --pmc runs
 # summarised under profiles/ (FETCH_SIZE + WRITE_SIZE, scaled by the copy-kernel calibration); None = not measured
-TRAFFIC_BYTES = {"gemm_fwd": 113.3e6, "spmm_fwd": 215.9e6, "gemm_dw": 257.7e6}
+TRAFFIC_BYTES = {"gemm_fwd": 113.0e6, "spmm_fwd": 221.0e6, "gemm_dw": 261.0e6}
 
 
 def main():

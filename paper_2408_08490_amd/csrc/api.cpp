@@ -128,8 +128,8 @@ static hgnn_status make_plan(hgnn_ctx *ctx, hgnn_graph *g, int32_t layer, const 
   pl.off_dz = o;      o += align_up(std::max<size_t>(zr, 1) * pl.es, 256);
   pl.off_partial = o; o += align_up(std::max<size_t>((size_t)L.max_chunks * std::max(pl.max_dim, 1), 1) * 4, 256);
   pl.off_acc32 = o;   o += align_up(std::max<size_t>((size_t)pl.total_dst * pl.H, 1) * 4, 256);
-  // partial bias-gradient sums: one row of H floats per block of (at least) 16 destination rows of a type
-  pl.off_bpart = o;   o += align_up(((size_t)pl.total_dst / 16 + T) * pl.H * 4, 256);
+  // partial bias-gradient sums: one row of H floats per block of (at least) 8 destination rows of a type
+  pl.off_bpart = o;   o += align_up(((size_t)pl.total_dst / 8 + T) * pl.H * 4, 256);
   pl.scratch_bytes = o;
   if (need_built) {
     hgnn_status st = layer_dev(ctx, g, layer, pl.dev);
@@ -1135,7 +1135,7 @@ hgnn_status hgnn_layer_bwd(hgnn_ctx *ctx, void *stream, hgnn_graph *g, int32_t l
   const void *gp = grad_h;
   const bool row_pass = pl.total_dst > 0 && (p->relu || any_db || ldg != pl.H);
   float *bpart = any_db ? (float *)(sc + pl.off_bpart) : nullptr;
-  int rpb = 16;
+  int rpb = 0;  // rows of G per row of bpart: set by the launcher
   if (pl.total_dst > 0) {
     void *gpw = sc + pl.off_gp;
     Probe pb(ctx, s, HGNN_K_RELU_BIAS_BWD, layer);

@@ -398,27 +398,28 @@ hgnn_status launch_pad_weights(hipStream_t s, int dtype, const TypeTab &tt, cons
 
 // ------------------------------------------------------------------------------------------
 // Backward epilogue: gp = grad_h * [h > 0] (when the layer has a ReLU) and dbias_t = column sums.
-// One block = 16 rows of one type; a thread owns columns tid, tid+256, ...  The block's column sums are added
+// One block = kRowsPerBlock rows of one type; a thread owns columns tid, tid+256, ...  The block's column sums are added
 // to dbias_t, or, when `bpart` is given, stored as row `block` of bpart [blocks x H] for a later pass that adds
 // the rows of a type up (no atomics, and dbias needs no zeroing first).
 // ------------------------------------------------------------------------------------------
+constexpr int kRowsPerBlock = 8;  // of the element-wise row pass (a multiple of the eight loads in flight per lane)
 template <typename T>
 __device__ __forceinline__ void relu_bias_rows(const TypeTab &tt, int block, int H, int ldo, int relu, int write,
                                                const T *__restrict__ g, const T *__restrict__ h, T *__restrict__ gp,
                                                const GradPtrTab &gt, float *__restrict__ bpart) {
   int b = block, t = 0;
   for (;; ++t) {
-    const int nb = (tt.n_dst[t] + 15) / 16;
+    const int nb = (tt.n_dst[t] + kRowsPerBlock - 1) / kRowsPerBlock;
     if (b < nb) break;
     b -= nb;
   }
-  const int r0 = tt.out_row_off[t] + b * 16;
-  const int r1 = min(r0 + 16, tt.out_row_off[t] + tt.n_dst[t]);
+  const int r0 = tt.out_row_off[t] + b * kRowsPerBlock;
+  const int r1 = min(r0 + kRowsPerBlock, tt.out_row_off[t] + tt.n_dst[t]);
   float *db = gt.dbias[t];
   for (int c = threadIdx.x; c < ldo; c += 256) {
     float sum = 0.f;
     if (c < H) {
-      // the block's 16 rows in two rounds of eight independent loads
+      // the block's rows, eight independent loads at a time
       for (int rb = r0; rb < r1; rb += 8) {
         float v[8], hv[8];
 #pragma unroll
@@ -531,7 +532,7 @@ hgnn_status launch_relu_bias_bwd(hipStream_t s, int dtype, const TypeTab &tt, in
                                  const void *grad_h, const void *h, void *gp, const GradPtrTab &gt) {
   const int vec = dtype == HGNN_BF16 ? 8 : 4;
   const bool fast = ldo == H && H % vec == 0 && H / vec <= 256 && (((uintptr_t)grad_h | (uintptr_t)h | (uintptr_t)gp) & 15) == 0;
-  const int rpb = fast ? 128 : 16;
+  const int rpb = fast ? 128 : kRowsPerBlock;
   const int write = relu || ldo != H;
   int blocks = 0;
   for (int t = 0; t < tt.num_types; ++t) blocks += (tt.n_dst[t] + rpb - 1) / rpb;
@@ -613,7 +614,7 @@ hgnn_status launch_bwd_prep(hipStream_t s, int dtype, const TypeTab &tt, const R
                             const void *h, void *gp, float *bpart, void *wpad, int *rows_per_block) {
   const int vec = dtype == HGNN_BF16 ? 8 : 4;
   const bool fast = ldo == H && H % vec == 0 && H / vec <= 256 && (((uintptr_t)grad_h | (uintptr_t)h | (uintptr_t)gp) & 15) == 0;
-  const int rpb = fast ? 128 : 16;
+  const int rpb = fast ? 128 : kRowsPerBlock;
   *rows_per_block = rpb;
   const int write = relu || ldo != H;
   int nb_relu = 0;
