@@ -339,6 +339,28 @@ def test_sampler_matches_oracle_and_feeds_the_build(B, index, scale, fanouts, nt
     ctx.close()
 
 
+def test_attention_context_keeps_the_permutations(B):
+    """hgnn_set_build_permutation(0) is ignored by a context of the attention variant (its backward walks cperm);
+    a NULL context is an error."""
+    import ctypes as C
+    cfg = make_config(0)
+    g = build_graph(cfg)
+    mb = sample_minibatch(cfg, g)
+    sch = g.schema
+    ctx = B.Context(sch.rel_src, sch.rel_dst, sch.num_types, "f32", device=-1, host_threads=2, heads=2, attention=True)
+    ctx.hgnn_set_build_permutation(False)
+    gr = ctx.hgnn_build_semantic_csr(mb.blocks, g.edge_type, use_edge_id=True)
+    gr.wait()
+    for l, b in enumerate(mb.blocks):
+        sel = O.edge_index_select(b.edge_index, sch.num_rels, edge_type=b.edge_type)
+        ref = O.semantic_csr(sel, sch.rel_src, sch.rel_dst, b.n_src, b.n_dst)
+        v = gr.host_view(l)
+        assert np.array_equal(v["perm"], ref["perm"]) and np.array_equal(v["cperm"], ref["cperm"])
+    gr.release()
+    ctx.close()
+    assert B.STATUS_NAMES[B.lib.hgnn_set_build_permutation(None, 0)] == "HGNN_EINVAL"
+
+
 def test_sampler_errors(B):
     cfg = make_config(0)
     g = build_graph(cfg)
