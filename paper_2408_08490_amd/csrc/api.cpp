@@ -55,7 +55,7 @@ struct Plan {
   int64_t total_dst = 0;
   size_t z_elems = 0, zroot_elems = 0, wt_elems = 0;
   size_t saved_bytes = 0, scratch_bytes = 0;
-  size_t off_wt = 0, off_gp = 0, off_dz = 0, off_partial = 0, off_acc32 = 0, off_bpart = 0;
+  size_t off_wt = 0, off_gp = 0, off_dz = 0, off_partial = 0, off_acc32 = 0, off_bpart = 0, bpart_rows = 0;
 };
 
 static hgnn_status layer_dev(hgnn_ctx *ctx, hgnn_graph *g, int32_t layer, LayerDev &D);
@@ -128,8 +128,11 @@ static hgnn_status make_plan(hgnn_ctx *ctx, hgnn_graph *g, int32_t layer, const 
   pl.off_dz = o;      o += align_up(std::max<size_t>(zr, 1) * pl.es, 256);
   pl.off_partial = o; o += align_up(std::max<size_t>((size_t)L.max_chunks * std::max(pl.max_dim, 1), 1) * 4, 256);
   pl.off_acc32 = o;   o += align_up(std::max<size_t>((size_t)pl.total_dst * pl.H, 1) * 4, 256);
-  // partial bias-gradient sums: one row of H floats per block of (at least) 8 destination rows of a type
-  pl.off_bpart = o;   o += align_up(((size_t)pl.total_dst / 8 + T) * pl.H * 4, 256);
+  // partial bias-gradient sums: one row of H floats per block of destination rows of a type (64 rows per block
+  // when the row pass runs in its 16-bytes-per-lane form, which the width decides; 8 otherwise)
+  const bool row_pass_vec = pl.H % vec == 0 && pl.H / vec <= 256;
+  pl.bpart_rows = (size_t)pl.total_dst / (row_pass_vec ? 64 : 8) + T;
+  pl.off_bpart = o;   o += align_up(pl.bpart_rows * pl.H * 4, 256);
   pl.scratch_bytes = o;
   if (need_built) {
     hgnn_status st = layer_dev(ctx, g, layer, pl.dev);
@@ -1073,7 +1076,8 @@ hgnn_status hgnn_layer_bwd(hgnn_ctx *ctx, void *stream, hgnn_graph *g, int32_t l
   if (!saved || !scratch || !go) HGNN_FAIL(HGNN_EINVAL, "NULL work area or gradient table");
   if (pl.total_dst > 0 && (!x_merged || !grad_h || (p->relu && !h_out))) HGNN_FAIL(HGNN_EINVAL, "NULL input");
   if (scratch_bytes < pl.scratch_bytes) HGNN_FAIL(HGNN_EINVAL, "scratch too small: need %zu bytes", pl.scratch_bytes);
-  if (((uintptr_t)saved | (uintptr_t)scratch | (uintptr_t)x_merged | (uintptr_t)grad_h | (uintptr_t)grad_x_merged) & 15)
+  if (((uintptr_t)saved | (uintptr_t)scratch | (uintptr_t)x_merged | (uintptr_t)grad_h | (uintptr_t)grad_x_merged |
+       (uintptr_t)h_out) & 15)
     HGNN_FAIL(HGNN_EINVAL, "device buffers must be 16-byte aligned");
   const int R = ctx->R, T = ctx->T;
   GradPtrTab gt;
@@ -1140,7 +1144,7 @@ hgnn_status hgnn_layer_bwd(hgnn_ctx *ctx, void *stream, hgnn_graph *g, int32_t l
     void *gpw = sc + pl.off_gp;
     Probe pb(ctx, s, HGNN_K_RELU_BIAS_BWD, layer);
     if ((st = launch_bwd_prep(s, ctx->dtype, pl.tt, pl.rt, pl.pt, wo, gt, pl.H, ldg, p->relu, row_pass, any_dw, grad_h, h_out, gpw,
-                              bpart, wpad, &rpb)) != HGNN_OK) return st;
+                              bpart, pl.bpart_rows, wpad, &rpb)) != HGNN_OK) return st;
     if (p->relu || ldg != pl.H) gp = gpw;
   }
   const bool fast = (ldg % vec) == 0;

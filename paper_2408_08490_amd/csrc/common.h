@@ -350,7 +350,7 @@ hgnn_status launch_zero_grads(hipStream_t s, const TypeTab &tt, const RelTab &rt
 // launch sets aside for it) then turns bpart into dbias.
 hgnn_status launch_bwd_prep(hipStream_t s, int dtype, const TypeTab &tt, const RelTab &rt, const PtrTab &pt, const WtTab &wo,
                             const GradPtrTab &gt, int H, int ldo, int relu, bool do_rows, bool do_zero, const void *grad_h,
-                            const void *h, void *gp, float *bpart, void *wpad, int *rows_per_block);
+                            const void *h, void *gp, float *bpart, size_t bpart_rows, void *wpad, int *rows_per_block);
 hgnn_status launch_bias_reduce(hipStream_t s, const TypeTab &tt, const GradPtrTab &gt, int H, int rpb, const float *bpart);
 // blocks of 256 threads that add up the partial bias sums: 32 columns of one type each
 inline int bias_reduce_blocks(int num_types, int H) { return num_types * ((H + 31) / 32); }

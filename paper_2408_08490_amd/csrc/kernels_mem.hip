@@ -612,7 +612,7 @@ __global__ void __launch_bounds__(256) bwd_prep_kernel(TypeTab tt, RelTab rt, Pt
 
 hgnn_status launch_bwd_prep(hipStream_t s, int dtype, const TypeTab &tt, const RelTab &rt, const PtrTab &pt, const WtTab &wo,
                             const GradPtrTab &gt, int H, int ldo, int relu, bool do_rows, bool do_zero, const void *grad_h,
-                            const void *h, void *gp, float *bpart, void *wpad, int *rows_per_block) {
+                            const void *h, void *gp, float *bpart, size_t bpart_rows, void *wpad, int *rows_per_block) {
   const int vec = dtype == HGNN_BF16 ? 8 : 4;
   const bool fast = ldo == H && H % vec == 0 && H / vec <= 256 && (((uintptr_t)grad_h | (uintptr_t)h | (uintptr_t)gp) & 15) == 0;
   const int rpb = fast ? kVecRows : kRowsPerBlock;
@@ -621,6 +621,10 @@ hgnn_status launch_bwd_prep(hipStream_t s, int dtype, const TypeTab &tt, const R
   int nb_relu = 0;
   if (do_rows)
     for (int t = 0; t < tt.num_types; ++t) nb_relu += (tt.n_dst[t] + rpb - 1) / rpb;
+  if (bpart && (size_t)nb_relu > bpart_rows) {  // the caller sized the area for another form of the row pass
+    set_error("partial bias sums: %d rows for an area of %zu", nb_relu, bpart_rows);
+    return HGNN_EINVAL;
+  }
   const int segs = rt.num_rels + tt.num_types;
   const int nb_zero = do_zero ? 32 * segs : 0, nb_pad = wpad ? 64 * segs : 0;
   const int blocks = nb_relu + nb_zero + nb_pad;
