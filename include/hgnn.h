@@ -23,6 +23,8 @@
  *    fp32; weight and bias gradients are always fp32.
  *  - Every feature width (in_dim[t]) must be a multiple of 16 bytes / sizeof(dtype)
  *    (4 for fp32, 8 for bf16); out_dim may be any positive value.
+ *  - Device buffers handed to the layer entry points (x_merged, h_out, saved, scratch,
+ *    grad_h, grad_x_merged, feature_cat) must be 16-byte aligned (HGNN_EINVAL otherwise).
  *  - Every function returns HGNN_OK or a negative hgnn_status; hgnn_last_error gives
  *    the text of the calling thread's most recent failure.  On failure no caller
  *    output buffer has been handed to a kernel by that call.
