@@ -32,7 +32,7 @@ TRAFFIC_BYTES = {"gemm_fwd": 113.0e6, "spmm_fwd": 221.0e6, "gemm_dw": 261.0e6}
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
-    ap.add_argument("--steps", type=int, default=200)
+    ap.add_argument("--steps", type=int, default=1000)
     ap.add_argument("--warmup", type=int, default=20)
     ap.add_argument("--config", type=int, default=2)
     ap.add_argument("--scale", type=float, default=1.0)
