@@ -105,8 +105,8 @@ struct LayerDev {
   int32_t rows, edges, src_rows, n_long, n_chunks;
 };
 
-constexpr int kLongRow = 32;  // transpose rows above this length are reduced chunk-wise
-constexpr int kChunk = 32;
+constexpr int kLongRow = 16;  // transpose rows above this length are reduced chunk-wise
+constexpr int kChunk = 16;
 
 struct LayerHost {
   int64_t rows = 0, edges = 0, src_rows = 0, tedges = 0;
