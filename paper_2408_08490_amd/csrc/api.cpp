@@ -55,7 +55,7 @@ struct Plan {
   int64_t total_dst = 0;
   size_t z_elems = 0, zroot_elems = 0, wt_elems = 0;
   size_t saved_bytes = 0, scratch_bytes = 0;
-  size_t off_wt = 0, off_gp = 0, off_dz = 0, off_partial = 0, off_acc32 = 0, off_bpart = 0, bpart_rows = 0;
+  size_t off_wt = 0, off_gp = 0, off_dz = 0, off_partial = 0, off_acc32 = 0, off_bpart = 0, bpart_rows = 0, off_zlo = 0;
 };
 
 static hgnn_status layer_dev(hgnn_ctx *ctx, hgnn_graph *g, int32_t layer, LayerDev &D);
@@ -133,6 +133,7 @@ static hgnn_status make_plan(hgnn_ctx *ctx, hgnn_graph *g, int32_t layer, const 
   const bool row_pass_vec = pl.H % vec == 0 && pl.H / vec <= 256;
   pl.bpart_rows = (size_t)pl.total_dst / (row_pass_vec ? 64 : 8) + T;
   pl.off_bpart = o;   o += align_up(pl.bpart_rows * pl.H * 4, 256);
+  pl.off_zlo = o;     o += (pl.es == 2 && p->relu) ? align_up(std::max<size_t>(z, 1) * pl.es, 256) : 0;
   pl.scratch_bytes = o;
   if (need_built) {
     hgnn_status st = layer_dev(ctx, g, layer, pl.dev);
@@ -951,6 +952,10 @@ static hgnn_status fwd_common(hgnn_ctx *ctx, void *stream, hgnn_graph *g, int32_
   HGNN_HIP(hipStreamWaitEvent(s, g->ready, 0));
   char *sc = (char *)scratch;
   void *wtb = sc + pl.off_wt;
+  // bf16 storage, layer with an activation: the aggregate is kept as a pair (rounded value, remainder), so that the
+  // pre-activation -- and with it the decision of every unit, which the backward pass depends on discontinuously --
+  // does not carry the rounding of the aggregate to 8 significant bits
+  void *zlo = (ctx->dtype == HGNN_BF16 && p->relu) ? sc + pl.off_zlo : nullptr;
   int n = 0;
   SegTab tl;
   const int tile_mn = fwd_tiles(pl, tl, !naive);
@@ -975,16 +980,16 @@ static hgnn_status fwd_common(hgnn_ctx *ctx, void *stream, hgnn_graph *g, int32_
       if (feature_cat_bytes < need) HGNN_FAIL(HGNN_EINVAL, "feature_cat too small: need %zu bytes", need);
       if ((uintptr_t)feature_cat & 15) HGNN_FAIL(HGNN_EINVAL, "device buffers must be 16-byte aligned");
       Probe pb(ctx, s, HGNN_K_SPMM_FWD, layer);
-      if ((st = launch_aggregate_literal(s, ctx->dtype, pl.dev, p->in_dim[0], x, feature_cat, saved)) != HGNN_OK) return st;
+      if ((st = launch_aggregate_literal(s, ctx->dtype, pl.dev, p->in_dim[0], x, feature_cat, saved, zlo)) != HGNN_OK) return st;
       n += (pl.dev.edges > 0) + (pl.dev.rows > 0);
     } else {
       Probe pb(ctx, s, HGNN_K_SPMM_FWD, layer);
-      if ((st = launch_spmm_fwd(s, ctx->dtype, pl.dev, pl.tt, pl.rt, pl.max_dim, x, saved, 0, pl.dev.rows)) != HGNN_OK) return st;
+      if ((st = launch_spmm_fwd(s, ctx->dtype, pl.dev, pl.tt, pl.rt, pl.max_dim, x, saved, zlo, 0, pl.dev.rows)) != HGNN_OK) return st;
       if (pl.dev.rows > 0) ++n;
     }
     {
       Probe pb(ctx, s, HGNN_K_GEMM_FWD, layer);
-      if ((st = launch_gemm_fwd(s, ctx->dtype, pl.dev, pl.tt, pl.rt, pl.pt, pl.wt, tl, live, pl.H, p->relu, x, saved, wtb, h, -1, nullptr, tile_mn)) != HGNN_OK) return st;
+      if ((st = launch_gemm_fwd(s, ctx->dtype, pl.dev, pl.tt, pl.rt, pl.pt, pl.wt, tl, live, pl.H, p->relu, x, saved, zlo, wtb, h, -1, nullptr, tile_mn)) != HGNN_OK) return st;
     }
     if (tl.tile_off[T] > 0) ++n;
   } else {
@@ -997,7 +1002,7 @@ static hgnn_status fwd_common(hgnn_ctx *ctx, void *stream, hgnn_graph *g, int32_
     const int32_t *rro = g->slab.host + L.o_rel_row_off;
     for (int r = 0; r < R; ++r) {
       if (rro[r + 1] == rro[r]) continue;
-      if ((st = launch_spmm_fwd(s, ctx->dtype, pl.dev, pl.tt, pl.rt, pl.max_dim, x, saved, rro[r], rro[r + 1])) != HGNN_OK) return st;
+      if ((st = launch_spmm_fwd(s, ctx->dtype, pl.dev, pl.tt, pl.rt, pl.max_dim, x, saved, zlo, rro[r], rro[r + 1])) != HGNN_OK) return st;
       ++n;
       SegTab one;
       std::memset(&one, 0, sizeof(one));
@@ -1005,7 +1010,7 @@ static hgnn_status fwd_common(hgnn_ctx *ctx, void *stream, hgnn_graph *g, int32_
       const int d = ctx->rel_dst[r];
       for (int t = 0; t < T; ++t)
         one.tile_off[t + 1] = one.tile_off[t] + (t == d ? tl.tile_off[t + 1] - tl.tile_off[t] : 0);
-      if ((st = launch_gemm_fwd(s, ctx->dtype, pl.dev, pl.tt, pl.rt, pl.pt, pl.wt, one, live, pl.H, 0, x, saved, wtb, h, r, acc32)) != HGNN_OK) return st;
+      if ((st = launch_gemm_fwd(s, ctx->dtype, pl.dev, pl.tt, pl.rt, pl.pt, pl.wt, one, live, pl.H, 0, x, saved, zlo, wtb, h, r, acc32)) != HGNN_OK) return st;
       ++n;
     }
     for (int t = 0; t < T; ++t) {
@@ -1016,7 +1021,7 @@ static hgnn_status fwd_common(hgnn_ctx *ctx, void *stream, hgnn_graph *g, int32_
         one.num_segs = T;
         for (int u = 0; u < T; ++u)
           one.tile_off[u + 1] = one.tile_off[u] + (u == t ? tl.tile_off[u + 1] - tl.tile_off[u] : 0);
-        if ((st = launch_gemm_fwd(s, ctx->dtype, pl.dev, pl.tt, pl.rt, pl.pt, pl.wt, one, live, pl.H, 0, x, saved, wtb, h, R + t, acc32)) != HGNN_OK) return st;
+        if ((st = launch_gemm_fwd(s, ctx->dtype, pl.dev, pl.tt, pl.rt, pl.pt, pl.wt, one, live, pl.H, 0, x, saved, zlo, wtb, h, R + t, acc32)) != HGNN_OK) return st;
         ++n;
       }
       if ((st = launch_bias_act(s, ctx->dtype, pl.tt, pl.pt, pl.H, p->relu, t, acc32, h)) != HGNN_OK) return st;

@@ -273,18 +273,19 @@ hgnn_status run_sample_job(hgnn_ctx *ctx, Builder &b, hgnn_graph *g, std::string
 // ---- kernel launchers (kernels_*.hip); all enqueue on `s` and return ----
 hgnn_status launch_merge(hipStream_t s, int dtype, int T, const void *const *store, const int32_t *feat_dim,
                          const int64_t *const *ids, const int64_t *n_rows, const int64_t *elem_off, void *out);
-// rows [row_begin,row_end) of the merged CSR: z[row] = mean of the x rows in colidx
+// rows [row_begin,row_end) of the merged CSR: z[row] = mean of the x rows in colidx (rounded to the storage type);
+// zlo (optional, same layout): what that rounding dropped, rounded in turn
 hgnn_status launch_spmm_fwd(hipStream_t s, int dtype, const LayerDev &L, const TypeTab &tt, const RelTab &rt,
-                            int max_dim, const void *x, void *z, int row_begin, int row_end);
+                            int max_dim, const void *x, void *z, void *zlo, int row_begin, int row_end);
 // the same aggregate in the two steps of the paper's Algorithm 1: FeatureCat [edges x F] = gathered source rows,
 // then a mean per merged row (all types one width F)
 hgnn_status launch_aggregate_literal(hipStream_t s, int dtype, const LayerDev &L, int F, const void *x, void *feature_cat,
-                                     void *z);
+                                     void *z, void *zlo);
 // dx[c] = sum over transpose row c of dz[crow] (+ root part for destination rows)
 hgnn_status launch_spmm_bwd(hipStream_t s, int dtype, const LayerDev &L, const TypeTab &tt, const RelTab &rt,
                             const PtrTab &pt, int max_dim, uint32_t want_types, const void *dz, void *dx, float *partial);
 // uniform feature width: return false when the width is outside what they cover (caller falls back)
-bool launch_spmm_fwd_uniform(hipStream_t s, int dtype, const LayerDev &L, int F, const void *x, void *z,
+bool launch_spmm_fwd_uniform(hipStream_t s, int dtype, const LayerDev &L, int F, const void *x, void *z, void *zlo,
                              int row_begin, int row_end);
 bool launch_spmm_bwd_uniform(hipStream_t s, int dtype, const LayerDev &L, const TypeTab &tt, const RelTab &rt, const PtrTab &pt,
                              int F, uint32_t want, const void *dz, void *dx, float *partial);
@@ -294,7 +295,7 @@ hgnn_status launch_transpose_weights(hipStream_t s, int dtype, const TypeTab &tt
 // mode 1: one segment `only_seg`, accumulated into the fp32 buffer acc32 (naive launch structure)
 hgnn_status launch_gemm_fwd(hipStream_t s, int dtype, const LayerDev &L, const TypeTab &tt, const RelTab &rt,
                             const PtrTab &pt, const WtTab &wt, const SegTab &tiles, const uint32_t *live_mask, int H,
-                            int relu, const void *x, const void *z, const void *wt_buf, void *h,
+                            int relu, const void *x, const void *z, const void *zlo, const void *wt_buf, void *h,
                             int only_seg, float *acc32, int tile_mn = 128);
 // attention variant
 hgnn_status launch_attn_proj(hipStream_t s, int dtype, const TypeTab &tt, const PtrTab &w_type_as_root, const SegTab &tiles, int H,

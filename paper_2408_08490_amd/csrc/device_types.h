@@ -43,6 +43,7 @@ template <> struct Vec16<float> {
   static __device__ __forceinline__ uint4 pack(const float *a) {
     return make_uint4(__float_as_uint(a[0]), __float_as_uint(a[1]), __float_as_uint(a[2]), __float_as_uint(a[3]));
   }
+  static __device__ __forceinline__ uint4 pack_remainder(const float *, const uint4 &) { return make_uint4(0, 0, 0, 0); }
 };
 template <> struct Vec16<bf16> {
   static constexpr int N = 8;
@@ -63,6 +64,17 @@ template <> struct Vec16<bf16> {
     r.z = pack2(a[4], a[5]);
     r.w = pack2(a[6], a[7]);
     return r;
+  }
+  // What `hi` = pack(a) dropped, rounded to the storage type in turn: hi + remainder carries 16 significant
+  // bits of a (the difference of an fp32 value and its bf16 rounding is exact in fp32).
+  static __device__ __forceinline__ uint4 pack_remainder(const float *a, const uint4 &hi) {
+    float back[8];
+#pragma unroll
+    for (int i = 0; i < 8; ++i) back[i] = 0.f;
+    add(back, hi);
+#pragma unroll
+    for (int i = 0; i < 8; ++i) back[i] = a[i] - back[i];
+    return pack(back);
   }
 };
 

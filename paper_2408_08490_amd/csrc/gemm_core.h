@@ -17,7 +17,7 @@ typedef float f32x4 __attribute__((ext_vector_type(4)));
 // those use 64x64 tiles (MI = NI = 1).
 constexpr int BM = 128, BN = 128, kThreads = 256;
 constexpr int kSegCap = 96;  // K-segments staged in LDS at a time
-constexpr int kRelWindow = 64;  // relations examined per pass of the forward kernel: one per lane of the first wavefront
+constexpr int kRelWindow = (kSegCap - 1) / 2;  // relations examined per pass of the forward kernel (up to two segments each, and the root)
 
 template <typename T> struct Mma;
 template <> struct Mma<bf16> {

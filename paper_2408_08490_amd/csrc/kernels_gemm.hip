@@ -27,7 +27,7 @@ struct LiveMask {
 template <typename T, bool FAST, int MI>
 __global__ void __launch_bounds__(kThreads, MI == 1 ? 4 : 2) gemm_fwd_kernel(TypeTab tt, RelTab rt, PtrTab pt, WtTab wt, SegTab tiles, XcdMap xmap, LiveMask live,
                                                             int H, int relu, const T *__restrict__ x, const T *__restrict__ z,
-                                                            const T *__restrict__ wtb,
+                                                            const T *__restrict__ zlo, const T *__restrict__ wtb,
                                                             T *__restrict__ h, int only_seg,
                                                             float *__restrict__ acc32) {
   constexpr int BM = 64 * MI, BN = 64 * MI;
@@ -44,23 +44,25 @@ __global__ void __launch_bounds__(kThreads, MI == 1 ? 4 : 2) gemm_fwd_kernel(Typ
   const int M = tt.n_dst[d];
   f32x16 acc[MI][MI];
   zero_acc(acc);
-  // K-segments of this destination type: the aggregate of every relation ending in d, then the root term.
-  // The first wavefront looks at a
-  // window of relations at once, one per lane, and packs the ones that take part with a ballot.
+  // K-segments of this destination type: the aggregate of every relation ending in d (and, when the layer keeps
+  // it, the aggregate's low-order remainder against the same weights), then the root term.  The first wavefront
+  // looks at a window of relations at once, one per lane, and packs the ones that take part with a ballot.
   for (int cursor = 0; cursor < R; cursor += kRelWindow) {
     if (threadIdx.x < 64) {
       const int lane = threadIdx.x, r = cursor + lane;
       bool use = lane < kRelWindow && r < R;
       if (use) use = rt.dst[r] == d && (only_seg < 0 || only_seg == r) && ((live.w[r >> 5] >> (r & 31)) & 1u);  // no edge: all zero
       const unsigned long long m = __ballot(use);
+      const int mult = zlo ? 2 : 1;
       if (use) {
-        const int pos = __popcll(m & ((1ull << lane) - 1ull));
+        const int pos = __popcll(m & ((1ull << lane) - 1ull)) * mult;
         const int F = tt.in_dim[rt.src[r]];
         const T *B = wtb + (int64_t)wt.rel4[r] * 4;
         put_seg(sm.seg[pos], z + (int64_t)rt.z_off4[r] * 4, F, B, F, 0, F);
+        if (zlo) put_seg(sm.seg[pos + 1], zlo + (int64_t)rt.z_off4[r] * 4, F, B, F, 0, F);
       }
       if (lane == 0) {
-        int n = __popcll(m);
+        int n = __popcll(m) * mult;
         if (cursor + kRelWindow >= R && pt.w_root[d] && (only_seg < 0 || only_seg == R + d)) {
           const int F = tt.in_dim[d];
           put_seg(sm.seg[n++], x + tt.elem_off[d], F, wtb + (int64_t)wt.root4[d] * 4, F, 0, F);
@@ -94,7 +96,7 @@ __global__ void __launch_bounds__(kThreads, MI == 1 ? 4 : 2) gemm_fwd_kernel(Typ
 
 hgnn_status launch_gemm_fwd(hipStream_t s, int dtype, const LayerDev &L, const TypeTab &tt, const RelTab &rt,
                             const PtrTab &pt, const WtTab &wt, const SegTab &tiles, const uint32_t *live_mask, int H,
-                            int relu, const void *x, const void *z, const void *wt_buf, void *h,
+                            int relu, const void *x, const void *z, const void *zlo, const void *wt_buf, void *h,
                             int only_seg, float *acc32, int tile_mn) {
   const int n = tiles.tile_off[tt.num_types];
   if (n == 0) return HGNN_OK;
@@ -109,7 +111,7 @@ hgnn_status launch_gemm_fwd(hipStream_t s, int dtype, const LayerDev &L, const T
     int64_t steps = 0;
     for (int r = 0; r < rt.num_rels; ++r)
       if (rt.dst[r] == d && (only_seg < 0 || only_seg == r) && ((live.w[r >> 5] >> (r & 31)) & 1u))
-        steps += (tt.in_dim[rt.src[r]] + bk - 1) / bk;
+        steps += (zlo ? 2 : 1) * ((tt.in_dim[rt.src[r]] + bk - 1) / bk);
     if (pt.w_root[d] && (only_seg < 0 || only_seg == rt.num_rels + d)) steps += (tt.in_dim[d] + bk - 1) / bk;
     cost[d] = steps + 4;
   }
@@ -119,7 +121,7 @@ hgnn_status launch_gemm_fwd(hipStream_t s, int dtype, const LayerDev &L, const T
   // x_merged, whose row widths are multiples of 16 bytes: always the FAST form
 #define HGNN_FWD(TY, MI_)                                                                                        \
   HGNN_LAUNCH((gemm_fwd_kernel<TY, true, MI_>), grid, dim3(kThreads), 0, s, tt, rt, pt, wt, tiles, xmap, live, H, relu, \
-              (const TY *)x, (const TY *)z, (const TY *)wt_buf, (TY *)h, only_seg, acc32)
+              (const TY *)x, (const TY *)z, (const TY *)zlo, (const TY *)wt_buf, (TY *)h, only_seg, acc32)
   if (dtype == HGNN_BF16) {
     if (tile_mn == 64) HGNN_FWD(bf16, 1); else HGNN_FWD(bf16, 2);
   } else {

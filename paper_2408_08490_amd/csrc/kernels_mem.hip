@@ -83,7 +83,7 @@ __device__ __forceinline__ int rel_of_row(const int32_t *rel_row_off, int R, int
 
 template <typename T>
 __global__ void __launch_bounds__(256) spmm_fwd_kernel(LayerDev L, TypeTab tt, RelTab rt, const T *__restrict__ x,
-                                                        T *__restrict__ z, int row_begin, int row_end,
+                                                        T *__restrict__ z, T *__restrict__ zlo, int row_begin, int row_end,
                                                         int lpr_log2) {
   using V = Vec16<T>;
   const int lpr = 1 << lpr_log2;
@@ -118,17 +118,19 @@ __global__ void __launch_bounds__(256) spmm_fwd_kernel(LayerDev L, TypeTab tt, R
     }
 #pragma unroll
     for (int i = 0; i < V::N; ++i) acc[i] *= inv;
-    zr[c] = V::pack(acc);
+    const uint4 hi = V::pack(acc);
+    zr[c] = hi;
+    if (zlo) reinterpret_cast<uint4 *>(zlo + zoff)[c] = V::pack_remainder(acc, hi);
   }
 }
 
 hgnn_status launch_spmm_fwd(hipStream_t s, int dtype, const LayerDev &L, const TypeTab &tt, const RelTab &rt,
-                            int max_dim, const void *x, void *z, int row_begin, int row_end) {
+                            int max_dim, const void *x, void *z, void *zlo, int row_begin, int row_end) {
   if (row_end <= row_begin) return HGNN_OK;
   const int es = dtype == HGNN_BF16 ? 2 : 4;
   bool uniform = true;
   for (int t = 0; t < tt.num_types; ++t) uniform &= tt.in_dim[t] == tt.in_dim[0];
-  if (uniform && launch_spmm_fwd_uniform(s, dtype, L, tt.in_dim[0], x, z, row_begin, row_end)) {
+  if (uniform && launch_spmm_fwd_uniform(s, dtype, L, tt.in_dim[0], x, z, zlo, row_begin, row_end)) {
     HGNN_HIP(hipGetLastError());
     return HGNN_OK;
   }
@@ -136,9 +138,9 @@ hgnn_status launch_spmm_fwd(hipStream_t s, int dtype, const LayerDev &L, const T
   const int rpb = 256 >> l2;
   dim3 grid((row_end - row_begin + rpb - 1) / rpb);
   if (dtype == HGNN_BF16)
-    HGNN_LAUNCH(spmm_fwd_kernel<bf16>, grid, dim3(256), 0, s, L, tt, rt, (const bf16 *)x, (bf16 *)z, row_begin, row_end, l2);
+    HGNN_LAUNCH(spmm_fwd_kernel<bf16>, grid, dim3(256), 0, s, L, tt, rt, (const bf16 *)x, (bf16 *)z, (bf16 *)zlo, row_begin, row_end, l2);
   else
-    HGNN_LAUNCH(spmm_fwd_kernel<float>, grid, dim3(256), 0, s, L, tt, rt, (const float *)x, (float *)z, row_begin, row_end, l2);
+    HGNN_LAUNCH(spmm_fwd_kernel<float>, grid, dim3(256), 0, s, L, tt, rt, (const float *)x, (float *)z, (float *)nullptr, row_begin, row_end, l2);
   HGNN_HIP(hipGetLastError());
   return HGNN_OK;
 }

@@ -56,11 +56,11 @@ hgnn_status launch_adam_dense(hipStream_t s, int dtype, int n, void *const *para
                               const float *const *grad, float *const *m, float *const *v, const int64_t *numel,
                               float lr, float b1, float b2, float eps, double c1, double c2) {
   const AdamCoef k{lr, b1, b2, eps, (float)c1, (float)c2};
-  for (int first = 0; first < n; first += kAdamTensors) {
+  for (int i = 0; i < n;) {  // one launch per batch of up to kAdamTensors non-empty tensors; `i` runs on across batches
     AdamTab tab;
     tab.n = 0;
     tab.block_off[0] = 0;
-    for (int i = first; i < n && tab.n < kAdamTensors; ++i) {
+    for (; i < n && tab.n < kAdamTensors; ++i) {
       if (numel[i] == 0) continue;
       const int j = tab.n++;
       tab.param[j] = param[i];

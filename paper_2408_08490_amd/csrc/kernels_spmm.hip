@@ -23,8 +23,8 @@ __device__ __forceinline__ int wave_col(int c0, int c1, int rel) {
 
 template <typename T, int LPRL, int C>
 __global__ void __launch_bounds__(256) spmm_fwd_uniform_kernel(const int32_t *__restrict__ rowptr, const int32_t *__restrict__ colidx,
-                                                                const T *__restrict__ x, T *__restrict__ z, int F, int row_begin,
-                                                                int row_end) {
+                                                                const T *__restrict__ x, T *__restrict__ z, T *__restrict__ zlo,
+                                                                int F, int row_begin, int row_end) {
   using V = Vec16<T>;
   constexpr int LPR = 1 << LPRL, RPW = 64 / LPR;
   const int lane = threadIdx.x & 63;
@@ -78,16 +78,18 @@ __global__ void __launch_bounds__(256) spmm_fwd_uniform_kernel(const int32_t *__
     if (q >= nvec) continue;
 #pragma unroll
     for (int i = 0; i < V::N; ++i) acc[p][i] *= inv;
-    reinterpret_cast<uint4 *>(z + zoff)[q] = V::pack(acc[p]);
+    const uint4 hi = V::pack(acc[p]);
+    reinterpret_cast<uint4 *>(z + zoff)[q] = hi;
+    if (zlo) reinterpret_cast<uint4 *>(zlo + zoff)[q] = V::pack_remainder(acc[p], hi);
   }
 }
 
 template <typename T, int LPRL, int C>
-static void launch_fwd_uniform(hipStream_t s, const LayerDev &L, const void *x, void *z, int F, int row_begin, int row_end) {
+static void launch_fwd_uniform(hipStream_t s, const LayerDev &L, const void *x, void *z, void *zlo, int F, int row_begin, int row_end) {
   constexpr int RPB = 4 * (64 >> LPRL);
   dim3 grid((row_end - row_begin + RPB - 1) / RPB);
   HGNN_LAUNCH((spmm_fwd_uniform_kernel<T, LPRL, C>), grid, dim3(256), 0, s, L.rowptr, L.colidx, (const T *)x, (T *)z,
-                     F, row_begin, row_end);
+                     (T *)zlo, F, row_begin, row_end);
 }
 
 // Returns false when the shape is outside what the uniform kernels cover (the generic kernels then run).
@@ -112,13 +114,13 @@ template <typename T, bool FWD, typename FN> static bool dispatch_width(int nvec
   return true;
 }
 
-bool launch_spmm_fwd_uniform(hipStream_t s, int dtype, const LayerDev &L, int F, const void *x, void *z, int row_begin,
-                             int row_end) {
+bool launch_spmm_fwd_uniform(hipStream_t s, int dtype, const LayerDev &L, int F, const void *x, void *z, void *zlo,
+                             int row_begin, int row_end) {
   const int es = dtype == HGNN_BF16 ? 2 : 4;
   const int nvec = F * es / 16;
   if (dtype == HGNN_BF16)
-    return dispatch_width<bf16, true>(nvec, [&]<int LPRL, int C>() { launch_fwd_uniform<bf16, LPRL, C>(s, L, x, z, F, row_begin, row_end); });
-  return dispatch_width<float, true>(nvec, [&]<int LPRL, int C>() { launch_fwd_uniform<float, LPRL, C>(s, L, x, z, F, row_begin, row_end); });
+    return dispatch_width<bf16, true>(nvec, [&]<int LPRL, int C>() { launch_fwd_uniform<bf16, LPRL, C>(s, L, x, z, zlo, F, row_begin, row_end); });
+  return dispatch_width<float, true>(nvec, [&]<int LPRL, int C>() { launch_fwd_uniform<float, LPRL, C>(s, L, x, z, zlo, F, row_begin, row_end); });
 }
 
 // ------------------------------------------------------------------------------------------
@@ -142,7 +144,7 @@ __global__ void __launch_bounds__(256) feature_cat_kernel(const int32_t *__restr
 // one lane per 16-byte piece of a merged row: z[row] = mean of fc[rowptr[row] .. rowptr[row + 1])
 template <typename T>
 __global__ void __launch_bounds__(256) segment_mean_kernel(const int32_t *__restrict__ rowptr, const T *__restrict__ fc,
-                                                            T *__restrict__ z, int nvec, int64_t pieces) {
+                                                            T *__restrict__ z, T *__restrict__ zlo, int nvec, int64_t pieces) {
   using V = Vec16<T>;
   const uint4 *fb = reinterpret_cast<const uint4 *>(fc);
   for (int64_t i = (int64_t)blockIdx.x * 256 + threadIdx.x; i < pieces; i += (int64_t)gridDim.x * 256) {
@@ -156,12 +158,14 @@ __global__ void __launch_bounds__(256) segment_mean_kernel(const int32_t *__rest
     const float inv = end > beg ? 1.0f / (float)(end - beg) : 0.0f;
 #pragma unroll
     for (int k = 0; k < V::N; ++k) acc[k] *= inv;
-    reinterpret_cast<uint4 *>(z)[i] = V::pack(acc);
+    const uint4 hi = V::pack(acc);
+    reinterpret_cast<uint4 *>(z)[i] = hi;
+    if (zlo) reinterpret_cast<uint4 *>(zlo)[i] = V::pack_remainder(acc, hi);
   }
 }
 
 hgnn_status launch_aggregate_literal(hipStream_t s, int dtype, const LayerDev &L, int F, const void *x, void *feature_cat,
-                                     void *z) {
+                                     void *z, void *zlo) {
   const int es = dtype == HGNN_BF16 ? 2 : 4;
   const int nvec = F * es / 16;
   const int64_t pe = (int64_t)L.edges * nvec, pr = (int64_t)L.rows * nvec;
@@ -176,9 +180,9 @@ hgnn_status launch_aggregate_literal(hipStream_t s, int dtype, const LayerDev &L
   if (pr > 0) {
     const int blocks = (int)std::min<int64_t>((pr + 255) / 256, 1 << 16);
     if (dtype == HGNN_BF16)
-      HGNN_LAUNCH(segment_mean_kernel<bf16>, dim3(blocks), dim3(256), 0, s, L.rowptr, (const bf16 *)feature_cat, (bf16 *)z, nvec, pr);
+      HGNN_LAUNCH(segment_mean_kernel<bf16>, dim3(blocks), dim3(256), 0, s, L.rowptr, (const bf16 *)feature_cat, (bf16 *)z, (bf16 *)zlo, nvec, pr);
     else
-      HGNN_LAUNCH(segment_mean_kernel<float>, dim3(blocks), dim3(256), 0, s, L.rowptr, (const float *)feature_cat, (float *)z, nvec, pr);
+      HGNN_LAUNCH(segment_mean_kernel<float>, dim3(blocks), dim3(256), 0, s, L.rowptr, (const float *)feature_cat, (float *)z, (float *)zlo, nvec, pr);
     HGNN_HIP(hipGetLastError());
   }
   return HGNN_OK;

@@ -42,45 +42,47 @@ def prepare_inputs(index, scale=1.0, batch=None, graph=None):
     return cfg, g, mb, ws
 
 
-def storage_precision_pre(cache, dtype, round_input):
-    """Pre-activation of the mean layer with the aggregate of the raw neighbour features rounded to the storage
-    type (bf16 or fp32) before the projection, everything else in fp64: the precision in which the kernel takes
-    the ReLU decision.  `cache` is the oracle's forward cache of the layer; `round_input`: the layer's input is an
-    activation of the previous layer, stored in the storage type as well."""
-    rnd = (lambda a: bf16_round(np.asarray(a, dtype=np.float32)).astype(np.float64)) if dtype == "bf16" else \
-          (lambda a: np.asarray(a, dtype=np.float32).astype(np.float64))
-    x = [rnd(a) if round_input else a for a in cache["x"]]
-    n_dst, rel_src, rel_dst = cache["n_dst"], cache["rel_src"], cache["rel_dst"]
-    pre = []
-    for t in range(len(x)):
-        H = cache["pre"][t].shape[1]
-        p = np.zeros((int(n_dst[t]), H))
-        if n_dst[t] > 0:
-            if cache["w_root"][t] is not None:
-                p += x[t][: n_dst[t]] @ np.asarray(cache["w_root"][t], dtype=np.float64)
-            if cache["bias"][t] is not None:
-                p += np.asarray(cache["bias"][t], dtype=np.float64)[None, :]
-        pre.append(p)
-    for r in range(len(rel_src)):
-        s_, d = rel_src[r], rel_dst[r]
-        nb = cache["nbrs"][r]
-        M = int(n_dst[d])
-        if M == 0:
-            continue
-        # the stored aggregate, formed as the kernel forms it: neighbours added one after the other in fp32, in the
-        # row's edge order, the sum multiplied by the fp32 reciprocal of the degree, the product rounded to storage
-        xs32 = x[s_].astype(np.float32)
-        deg = np.array([len(a) for a in nb], dtype=np.int64)
-        acc = np.zeros((M, xs32.shape[1]), dtype=np.float32)
-        for k in range(int(deg.max()) if M else 0):
-            rows = np.nonzero(deg > k)[0]
-            cols = np.fromiter((nb[v][k] for v in rows), dtype=np.int64, count=len(rows))
-            acc[rows] = acc[rows] + xs32[cols]
-        inv = np.zeros(M, dtype=np.float32)
-        inv[deg > 0] = np.float32(1.0) / deg[deg > 0].astype(np.float32)
-        z = rnd(acc * inv[:, None])
-        pre[d] += z @ np.asarray(cache["w_rel"][r], dtype=np.float64)
-    return pre
+# Rounding bound of the kernels' pre-activation, relative to the sum of the magnitudes of its terms
+#   S[v, c] = |b_c| + sum_k |x_vk| |W0_kc| + sum_r mean_u(|x_u|) . |W_r[:, c]|      (mean layer)
+#   S[v, c] = |b_c| + sum_r beta_r |m_r[v, c]|                                      (attention layer)
+# evaluated with the oracle's own forward on absolute values.  Sources of rounding in the kernels, all other
+# operations being exact on the common inputs: the aggregate, an fp32 sum of <= fanout rows times an fp32
+# reciprocal ((deg + 1) 2^-24 relative), kept in bf16 storage as value + remainder (residual <= 2^-17 relative:
+# the value drops <= 2^-9 of it, the remainder <= 2^-9 of that) or as it is in fp32 storage; products of two bf16
+# numbers are exact in fp32; the fp32 accumulation of the K products of a unit, whose error grows like 2^-24
+# times the running sums, i.e. ~2^-25 S for terms of random sign and at most K 2^-24 S.  EPS covers the residual
+# plus a 16-fold margin on the accumulation.  A layer whose INPUT is an activation that the previous layer
+# stored in bf16 starts from values that differ by 2^-9 relative from the oracle's unrounded ones: EPS_ACT.
+EPS = {"f32": 2.0 ** -21, "bf16": 2.0 ** -16}
+EPS_ACT = {"f32": 2.0 ** -19, "bf16": 2.0 ** -8}
+# attention layer: S has no sqrt(K) head-room (its terms are the few per-relation aggregates themselves), the
+# aggregates carry the fp32 exponentials and normalisation of the neighbour softmax (fp32 storage), or are stored,
+# like the projected features they are made of, in bf16 (two roundings of 2^-9)
+EPS_ATTN = {"f32": 2.0 ** -17, "bf16": 2.0 ** -8}
+BAND_MAX_FRAC = {"f32": 1e-4, "bf16": 1e-3}    # share of a model's ReLU units that may lie inside the band
+
+
+def decision_band(cfg, cache, sel, layer_index):
+    """Per vertex type: boolean array of the units whose oracle pre-activation is zero to within the kernels'
+    rounding bound, |pre| <= eps * S.  Everything is computed from the oracle's quantities."""
+    if "m" in cache:                                   # attention layer
+        T = len(cache["x"])
+        S = []
+        for d in range(T):
+            a = np.zeros_like(cache["pre"][d])
+            for r in range(len(cache["rel_src"])):
+                if cache["rel_dst"][r] == d and cache["beta"][r] is not None:
+                    a += cache["beta"][r] * np.abs(cache["m"][r])
+            if cache["bias"][d] is not None and a.shape[0]:
+                a += np.abs(np.asarray(cache["bias"][d], dtype=np.float64))[None, :]
+            S.append(a)
+        eps = EPS_ATTN[cfg.dtype]
+    else:
+        ab = lambda lst: [None if a is None else np.abs(np.asarray(a, dtype=np.float64)) for a in lst]
+        S, _ = O.rgcn_layer_forward(ab(cache["x"]), sel, cache["rel_src"], cache["rel_dst"], cache["n_dst"],
+                                    ab(cache["w_rel"]), ab(cache["w_root"]), ab(cache["bias"]), False)
+        eps = (EPS if layer_index == 0 else EPS_ACT)[cfg.dtype]
+    return [np.abs(p) <= eps * s for p, s in zip(cache["pre"], S)]
 
 
 def layer_dicts(cfg, ws):
@@ -105,16 +107,18 @@ def oracle_run(cfg, g, mb, ws, input_grad=None):
                                         layers, loss, labels=mb.labels, grad_out=mb.grad_out,
                                         target_type=mb.target_type)
     res["csr"] = csrs
+    res["sels"] = sels
     res["x0_flat"] = flat
     return res
 
 
 def run_case(index, scale=1.0, batch=None, verbose=False, use_edge_id=True, check_naive=False, graph=None,
              input_grad=None, backward=True, cfg_edit=None, grad_tol=None, sampled=None, need_input_grad=True,
-             check_two_step=False, build_permutation=False):
+             check_two_step=False, build_permutation=False, band_max_frac=None):
     """cfg_edit(cfg, g, mb, ws): optional hook that changes the prepared inputs (e.g. the storage type) before
     both sides run.  grad_tol: optional {substring of a gradient's name: tolerance or None}; a matching
-    gradient is held to that tolerance in both norms against the tie-broken oracle (None: reported only).
+    gradient is held to that tolerance instead of the storage type's (None: reported only).  band_max_frac:
+    replaces the bound on the share of ReLU units inside the decision band.
     sampled: optional dict(seed=..., fanouts=...): the mini-batch of the same targets is sampled by the library's
     sampler on the HIP side and by the sampler oracle on the other.  need_input_grad=False: the first layer's
     backward gets no input-gradient buffer (its weight and bias gradients are still checked)."""
@@ -176,48 +180,51 @@ def run_case(index, scale=1.0, batch=None, verbose=False, use_edge_id=True, chec
     chk("row_off", out["row_off"], want_ro, exact=True)
     chk("elem_off", out["elem_off"], want_eo, exact=True)
     chk("x_merged", out["x0"].float().cpu().numpy(), ref["x0_flat"].astype(np.float32), exact=True)
-    # floating point outputs.  A ReLU's backward needs a decision (unit active or not) that floating point takes;
-    # both sides take it in the same precision, the kernel's: the mean layer keeps the aggregate of the raw
-    # neighbour features in the storage type before it is projected, so the decision is taken on
-    #   pre_k = x_v W_0 + b + sum_r round_storage(mean_u x_u) W_r
-    # evaluated here in fp64 from the oracle's own inputs (`storage_precision_pre`).  The kernel accumulates the same
-    # products in fp32, so its decision may still differ where pre_k is zero to within that rounding
-    # (|pre_k| < AMBIG * rms): there the kernel's decision is taken over, after checking that it agrees everywhere
-    # else.  The oracle's backward then runs with those decisions; forward values are compared with the plain oracle.
-    AMBIG = {"f32": 1e-5, "bf16": 1e-4}[cfg.dtype]
-    amb_max_frac = 1e-3
-    if cfg.kind == "rgat" and cfg.dtype == "bf16":
-        # the attention layer stores the projected features z and the per-relation aggregates m in bf16 (they are
-        # gathered per edge, so their width is the layer's memory traffic): the pre-activation carries their
-        # rounding, ~2^-8 of its scale, and a unit inside that band may take either decision
-        AMBIG, amb_max_frac = 2.0 ** -7, 3e-2
-    masks, n_amb, n_units = [], 0, 0
+    # floating point outputs.  Forward values and the loss are compared with the plain oracle.  A ReLU's backward
+    # needs a decision per unit (active or not) that floating point takes, and a weight gradient depends on it
+    # discontinuously.  The reference decision is the oracle's own, pre > 0.  Where the oracle's pre-activation is
+    # zero to within the kernels' rounding bound (decision_band: |pre| <= eps * S, oracle quantities only) either
+    # decision is a correct result: there the kernel's is accepted, everywhere else it must equal the oracle's,
+    # and the share of such units is bounded.  Gradients are then held, in both norms, to the oracle's backward
+    # run with the accepted decisions, AND in the L2 norm to the plain oracle (a single flipped unit moves one
+    # element of a gradient by a whole term, so the max norm against the plain oracle is reported, not bounded).
+    # The L2 bound against the plain oracle is the tolerance itself when no unit inside the band took the other
+    # decision.  Otherwise it grows by what the accepted units can move: switching f of a type's A active units
+    # changes ~ sqrt(f / A) of the L2 norm of that type's masked output gradient when gradient magnitudes are
+    # alike, and every gradient downstream is linear in it; with a factor 4 for unlike magnitudes the bound is
+    # tol + 4 max_type sqrt(f / A), and never more than 2e-2 whatever the storage type.
+    masks, n_band, n_flip, n_units, flip_share = [], 0, 0, 0, 0.0
     for l in range(len(ws)):
         if not ws[l].relu:
             masks.append(None)
             continue
         hg = out["h"][l].float().cpu().numpy().reshape(-1, ws[l].out_dim)
-        pre_k = ref["caches"][l]["pre"] if cfg.kind == "rgat" else storage_precision_pre(ref["caches"][l], cfg.dtype, l > 0)
+        band = decision_band(cfg, ref["caches"][l], ref["sels"][l], l)
         ml, r0 = [], 0
         for t in range(sch.num_types):
-            pre = pre_k[t]
+            pre = ref["caches"][l]["pre"][t]
             hgt = hg[r0: r0 + pre.shape[0]]
             r0 += pre.shape[0]
             if pre.size == 0:
                 ml.append(np.zeros(pre.shape, bool))
                 continue
-            amb = np.abs(pre) < AMBIG * np.sqrt(np.mean(pre * pre))
-            if not np.array_equal((hgt > 0)[~amb], (pre > 0)[~amb]):
+            if not np.array_equal((hgt > 0)[~band[t]], (pre > 0)[~band[t]]):
                 ok = False
                 report[f"L{l}.relu_decisions_type{t}"] = "MISMATCH"
-            ml.append(np.where(amb, hgt > 0, pre > 0))
-            n_amb += int(amb.sum()); n_units += amb.size
+            ml.append(np.where(band[t], hgt > 0, pre > 0))
+            n_band += int(band[t].sum()); n_units += band[t].size
+            f = int(((hgt > 0) != (pre > 0)).sum())
+            n_flip += f
+            flip_share = max(flip_share, f / max(int((pre > 0).sum()), 1))
         masks.append(ml)
-    report["ambiguous_relu_units"] = (n_amb, n_units)
-    if n_units and n_amb > amb_max_frac * n_units:
+    report["relu_units_in_band"] = (n_band, n_units)
+    report["relu_units_flipped"] = n_flip
+    band_max = band_max_frac if band_max_frac is not None else BAND_MAX_FRAC[cfg.dtype]
+    if n_units and n_band > max(band_max * n_units, 2):
         ok = False
+        report["relu_band"] = "MISMATCH"
     ref_tb = ref
-    if any(m is not None for m in masks):
+    if n_flip:
         layers = layer_dicts(cfg, ws)
         ref_tb = O.rgcn_model_forward_backward(None, None, sch.rel_src, sch.rel_dst, None, layers,
                                                "xent" if cfg.loss == "xent" else "dot", labels=mb.labels,
@@ -228,15 +235,17 @@ def run_case(index, scale=1.0, batch=None, verbose=False, use_edge_id=True, chec
     def chk2(name, got, want_plain, want_tb):
         nonlocal ok
         e_plain, e_tb = rel_errors(got, want_plain), rel_errors(got, want_tb)
-        good = e_tb[0] <= tol and e_tb[1] <= tol     # against the oracle with the decisions of the storage precision
+        t_tb, t_plain = tol, min(tol + 4.0 * np.sqrt(flip_share), max(tol, 2e-2))
         for key, t2 in (grad_tol or {}).items():
             if key in name:
-                good = True if t2 is None else (e_tb[0] <= t2 and e_tb[1] <= t2)
-        report[name] = (round(e_tb[0], 7), round(e_plain[1], 7))
+                t_tb = t_plain = t2
+        good = (t_tb is None or (e_tb[0] <= t_tb and e_tb[1] <= t_tb)) and (t_plain is None or e_plain[1] <= t_plain)
+        report[name] = (round(e_tb[0], 7), round(e_tb[1], 7))
+        report[name + "|plain"] = (round(e_plain[0], 7), round(e_plain[1], 7))
         if not good:
             ok = False
             if verbose:
-                print("FAIL", name, "plain", e_plain, "tie-broken", e_tb, flush=True)
+                print("FAIL", name, "plain", e_plain, "accepted decisions", e_tb, flush=True)
 
     for l in range(len(ws)):
         want = np.concatenate([h.ravel() for h in ref["h"][l]])
@@ -304,10 +313,13 @@ def run_case(index, scale=1.0, batch=None, verbose=False, use_edge_id=True, chec
     report["sizes"] = [(sum(b.n_src), sum(b.n_dst), int(b.edge_index.shape[1])) for b in mb.blocks]
     if verbose:
         print({k: v for k, v in report.items() if not k.startswith("L")}, flush=True)
-        worst = sorted(((v[0], k) for k, v in report.items() if isinstance(v, tuple) and len(v) == 2
-                        and isinstance(v[0], float)), reverse=True)[:6]
-        print("worst:", worst, flush=True)
-        print("all:", {k: v for k, v in report.items() if isinstance(v, tuple) and len(v) == 2}, flush=True)
+        worst = sorted(((max(v), k) for k, v in report.items() if isinstance(v, tuple) and len(v) == 2
+                        and isinstance(v[0], float) and not k.endswith("|plain")), reverse=True)[:6]
+        print("worst (accepted decisions, max of both norms):", worst, flush=True)
+        worst = sorted(((v[1], k) for k, v in report.items() if isinstance(v, tuple) and k.endswith("|plain")), reverse=True)[:6]
+        print("worst (plain oracle, L2):", worst, flush=True)
+        if not ok:
+            print("all:", {k: v for k, v in report.items() if isinstance(v, tuple) and len(v) == 2}, flush=True)
     return report
 
 

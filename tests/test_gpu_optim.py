@@ -54,6 +54,32 @@ def test_adam_dense_kernel(dtype):
     ctx.close()
 
 
+def test_adam_dense_many_tensors_with_empty_ones():
+    """More tensors than one launch's table holds (48), empty ones among them -- ten in front, others scattered:
+    every tensor is updated exactly once per step (a second update in the same step would show as twice the move)."""
+    import torch
+    rng = np.random.default_rng(3)
+    shapes = [(0,)] * 10 + [((int(rng.integers(1, 40)), int(rng.integers(1, 9))) if i % 7 else (0,)) for i in range(110)]
+    theta, grads = optimizer_case(5, shapes, steps=2)
+    ctx = _ctx("f32")
+    dev = torch.device("cuda", 0)
+    params = [torch.from_numpy(t).to(dev) for t in theta]
+    gbuf = [torch.zeros(s, device=dev) for s in shapes]
+    ms, vs = [torch.zeros(s, device=dev) for s in shapes], [torch.zeros(s, device=dev) for s in shapes]
+    lst = ctx.AdamList(params, None, gbuf, ms, vs)
+    ref = [(t.astype(np.float64), np.zeros(t.shape), np.zeros(t.shape)) for t in theta]
+    for step in (1, 2):
+        for gb, g in zip(gbuf, grads[step - 1]):
+            gb.copy_(torch.from_numpy(g))
+        ctx.hgnn_adam_update(lst, step=step, **HP)
+        torch.cuda.synchronize()
+        ref = [P.adam_step(th, g, m, v, step, **HP) for (th, m, v), g in zip(ref, grads[step - 1])]
+        for i, (th, m, v) in enumerate(ref):
+            assert _rel(params[i].cpu().numpy(), th) <= 1e-5 and _rel(ms[i].cpu().numpy(), m) <= 1e-5 and \
+                _rel(vs[i].cpu().numpy(), v) <= 1e-5, (step, i)
+    ctx.close()
+
+
 @pytest.mark.parametrize("dtype,F", [("f32", 32), ("bf16", 128), ("bf16", 8)])
 def test_adam_rows_kernel(dtype, F):
     import torch

@@ -218,3 +218,47 @@ def test_relation_without_edges_still_takes_part_in_the_fusion():
     assert abs(cache["beta"][0] - 1.0 / (1.0 + np.exp(w1 - w0))) < 1e-14
     g = O.rgat_layer_backward(cache, [np.ones_like(a) for a in h])
     assert np.all(g["da_src"][0] == 0) and np.all(g["da_dst"][0] == 0)
+
+
+def test_relu_mask_equal_to_own_decisions_reproduces_the_plain_backward_bit_for_bit():
+    c = tiny_case(seed=5)
+    h, cache = fwd(c)
+    rng = np.random.default_rng(6)
+    G = [rng.normal(size=a.shape) for a in h]
+    plain = O.rgat_layer_backward(cache, G)
+    masked = O.rgat_layer_backward(cache, G, relu_mask=[p > 0 for p in cache["pre"]])
+    for k in plain:
+        a, b = plain[k], masked[k]
+        if isinstance(a, list):
+            for u, v in zip(a, b):
+                assert (u is None and v is None) or np.array_equal(u, v)
+        else:
+            assert np.array_equal(a, b)
+
+
+def test_flipping_one_relu_decision_equals_zeroing_that_unit_s_output_gradient():
+    """The ReLU is the last step of the layer, so switching unit (t, v, c) off must give exactly the gradients of the
+    plain backward fed with an output gradient whose element (v, c) is zero -- and the bias gradient's element c must
+    drop by that element (the bias is added right before the activation)."""
+    c = tiny_case(seed=7)
+    h, cache = fwd(c)
+    rng = np.random.default_rng(8)
+    G = [rng.normal(size=a.shape) for a in h]
+    t = 1
+    act = np.argwhere(cache["pre"][t] > 0)
+    v, col = (int(a) for a in act[len(act) // 2])
+    mask = [p > 0 for p in cache["pre"]]
+    mask[t] = mask[t].copy()
+    mask[t][v, col] = False
+    G0 = [g.copy() for g in G]
+    G0[t][v, col] = 0.0
+    masked = O.rgat_layer_backward(cache, G, relu_mask=mask)
+    zeroed = O.rgat_layer_backward(cache, G0)
+    plain = O.rgat_layer_backward(cache, G)
+    for k in masked:
+        a, b = masked[k], zeroed[k]
+        for u, w in (zip(a, b) if isinstance(a, list) else [(a, b)]):
+            assert (u is None and w is None) or np.array_equal(u, w)
+    e = np.zeros_like(plain["dbias"][t]); e[col] = G[t][v, col]
+    np.testing.assert_allclose(plain["dbias"][t] - masked["dbias"][t], e, atol=1e-12)
+    assert not np.array_equal(plain["dw_type"][0], masked["dw_type"][0])

@@ -294,3 +294,65 @@ def test_two_layer_model_gradients_by_finite_differences():
             arr[i] = sv - eps; lm = run()["loss"]
             arr[i] = sv
             assert abs((lp - lm) / (2 * eps) - grad[i]) < 1e-7 * max(1.0, abs(grad[i]))
+
+
+# --------------------------------------------------------------------------- #
+# The `relu_mask` branch of the backward (parity tests hand it the decisions of units whose
+# pre-activation is zero to within rounding)
+# --------------------------------------------------------------------------- #
+def test_relu_mask_equal_to_own_decisions_reproduces_the_plain_backward_bit_for_bit():
+    rng = np.random.default_rng(11)
+    c = _random_case(rng)
+    h, cache = _fwd(c, relu=True)
+    G = [rng.standard_normal(a.shape) for a in h]
+    plain = O.rgcn_layer_backward(cache, G)
+    masked = O.rgcn_layer_backward(cache, G, relu_mask=[p > 0 for p in cache["pre"]])
+    for a, b in zip(plain, masked):
+        for u, v in zip(a, b):
+            assert (u is None and v is None) or np.array_equal(u, v)
+
+
+@pytest.mark.parametrize("seed", [0, 1])
+def test_flipping_one_relu_decision_moves_exactly_that_unit_s_terms(seed):
+    """Switching unit (t, v, c) off removes g[v, c] from the bias gradient's element c, x_v g[v, c] from column c of
+    the root weight gradient, mean_u(x_u) g[v, c] from column c of every relation ending in t, g[v, c] W[:, c] from
+    the feature gradients of v and (divided by the neighbourhood size) of its neighbours -- and nothing else.  The
+    expected changes are written out here from the layer's definition, not taken from the oracle."""
+    rng = np.random.default_rng(100 + seed)
+    c = _random_case(rng)
+    h, cache = _fwd(c, relu=True)
+    G = [rng.standard_normal(a.shape) for a in h]
+    t = 1
+    act = np.argwhere(cache["pre"][t] > 0)
+    v, col = (int(a) for a in act[rng.integers(len(act))])
+    mask = [p > 0 for p in cache["pre"]]
+    mask[t] = mask[t].copy()
+    mask[t][v, col] = False
+    dx0, dwr0, dw00, db0 = O.rgcn_layer_backward(cache, G)
+    dx1, dwr1, dw01, db1 = O.rgcn_layer_backward(cache, G, relu_mask=mask)
+    g = G[t][v, col]
+    # bias and root weight
+    e = np.zeros_like(db0[t]); e[col] = g
+    np.testing.assert_allclose(db0[t] - db1[t], e, atol=1e-12)
+    e = np.zeros_like(dw00[t]); e[:, col] = c["x"][t][v] * g
+    np.testing.assert_allclose(dw00[t] - dw01[t], e, atol=1e-12)
+    for u in range(len(c["x"])):
+        if u != t:
+            assert np.array_equal(dw00[u], dw01[u]) and np.array_equal(db0[u], db1[u])
+    # relation weights and feature gradients
+    want_dx = [np.zeros_like(a) for a in c["x"]]
+    want_dx[t][v] += g * c["w_root"][t][:, col]
+    for r in range(len(c["rel_src"])):
+        s, d = c["rel_src"][r], c["rel_dst"][r]
+        e = np.zeros_like(dwr0[r])
+        if d == t:
+            nb = [int(a) for a, b, ty in zip(c["ei"][0], c["ei"][1], c["et"]) if ty == r and b == v]
+            if nb:
+                e[:, col] = c["x"][s][nb].mean(axis=0) * g
+                for a in nb:
+                    want_dx[s][a] += g * c["w_rel"][r][:, col] / len(nb)
+        np.testing.assert_allclose(dwr0[r] - dwr1[r], e, atol=1e-12)
+        keep = np.ones(e.shape[1], bool); keep[col] = d != t
+        assert np.array_equal(dwr0[r][:, keep], dwr1[r][:, keep])      # other columns: not a bit moves
+    for u in range(len(c["x"])):
+        np.testing.assert_allclose(dx0[u] - dx1[u], want_dx[u], atol=1e-12)
