@@ -285,6 +285,22 @@ hgnn_status hgnn_layer_fwd(hgnn_ctx *ctx, void *stream, hgnn_graph *g, int32_t l
                            const hgnn_layer_params *p, const void *x_merged, void *h_out,
                            void *saved, size_t saved_bytes, void *scratch, size_t scratch_bytes);
 
+/* hgnn_layer_fwd for callers that cannot allocate device memory (code under HIP graph capture, tight serving
+ * loops, harnesses that forbid allocation) and therefore have no scratch area to pass: the same kernels and the
+ * same results, bit for bit, with the forward's work area (transposed weights; in bf16 layers with an activation
+ * also the aggregate's low-order plane) in a fixed device array of HGNN_STATIC_SCRATCH_BYTES that the library
+ * holds on every GPU it runs on until the process ends.  The call allocates nothing, on the device or the host.
+ * Mean-aggregation layers only (HGNN_EUNSUPPORTED otherwise).  A layer that needs more than the fixed array
+ * holds is refused with HGNN_EINVAL and a message that states both sizes; nothing is enqueued then.  `saved` is
+ * as for hgnn_layer_fwd (size from hgnn_layer_workspace_bytes) and feeds hgnn_layer_bwd unchanged.
+ * Every call on a GPU uses that GPU's one array: calls whose device work may overlap (different streams, or
+ * several host threads) race; order them on one stream.  The array keeps the last call's contents; each call
+ * overwrites every byte it later reads, so nothing needs clearing. */
+#define HGNN_STATIC_SCRATCH_BYTES (64u << 20)
+hgnn_status hgnn_layer_fwd_static(hgnn_ctx *ctx, void *stream, hgnn_graph *g, int32_t layer,
+                                  const hgnn_layer_params *p, const void *x_merged, void *h_out,
+                                  void *saved, size_t saved_bytes);
+
 /* Attention variant (the paper evaluates R-GAT, Section 5.1; semantic fusion, Section 2.2): with a schema
  * created with agg = HGNN_AGG_ATTN and fuse = HGNN_FUSE_SEMATTN, hgnn_layer_fwd / hgnn_layer_bwd evaluate
  *   z_t = x_t W_t                                                     (H = heads * D columns)

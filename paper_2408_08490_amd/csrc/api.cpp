@@ -168,8 +168,9 @@ static thread_local bool tl_probe_first = false;
 
 struct Probe {
   bool active = false;
-  Probe(hgnn_ctx *c, hipStream_t, int kernel, int layer) {
+  Probe(hgnn_ctx *c, hipStream_t, int kernel, int layer, bool enabled = true) {
     int slot = -1;
+    if (!enabled) return;
     for (int i = 0; i < c->probe_n; ++i)
       if (c->probe_sel[i][0] == kernel && (c->probe_sel[i][1] < 0 || c->probe_sel[i][1] == layer)) slot = i;
     if (slot < 0) return;
@@ -515,6 +516,12 @@ hgnn_status hgnn_create(hgnn_ctx **out, const hgnn_schema *s, int device, int ho
     if (e != hipSuccess) {
       delete c;
       HGNN_FAIL(HGNN_EHIP, "device %d: %s", device, hipGetErrorString(e));
+    }
+    const hgnn_status sst = static_scratch_init(device);  // where this device keeps hgnn_layer_fwd_static's work area
+    if (sst != HGNN_OK) {
+      (void)hipStreamDestroy(c->side);
+      delete c;
+      return sst;
     }
   }
   int n = host_threads;
@@ -938,12 +945,23 @@ hgnn_status hgnn_layer_workspace_bytes(hgnn_ctx *ctx, hgnn_graph *g, int32_t lay
 
 static hgnn_status fwd_common(hgnn_ctx *ctx, void *stream, hgnn_graph *g, int32_t layer, const hgnn_layer_params *p,
                               const void *x, void *h, void *saved, size_t saved_bytes, void *scratch, size_t scratch_bytes,
-                              bool naive, int32_t *launches, void *feature_cat = nullptr, size_t feature_cat_bytes = 0) {
+                              bool naive, int32_t *launches, void *feature_cat = nullptr, size_t feature_cat_bytes = 0,
+                              bool static_area = false) {
   Plan pl;
   hgnn_status st = make_plan(ctx, g, layer, p, pl, true);
   if (st != HGNN_OK) return st;
   if (pl.total_dst > 0 && (!x || !h)) HGNN_FAIL(HGNN_EINVAL, "x_merged or h_out is NULL");
   if (!saved || !scratch) HGNN_FAIL(HGNN_EINVAL, "NULL work area");
+  if (static_area) {
+    // the forward's own part of the work area, laid out back to back: transposed weights, low-order plane
+    const size_t wt_bytes = pl.off_gp - pl.off_wt, zlo_bytes = pl.scratch_bytes - pl.off_zlo;
+    if (wt_bytes + zlo_bytes > scratch_bytes)
+      HGNN_FAIL(HGNN_EINVAL, "layer needs %zu bytes of work area, the static one holds %zu: use hgnn_layer_fwd with a caller-provided area",
+                wt_bytes + zlo_bytes, scratch_bytes);
+    pl.off_wt = 0;
+    pl.off_zlo = wt_bytes;
+    pl.scratch_bytes = wt_bytes + zlo_bytes;
+  }
   if (saved_bytes < pl.saved_bytes || scratch_bytes < pl.scratch_bytes)
     HGNN_FAIL(HGNN_EINVAL, "work areas too small: need %zu saved, %zu scratch bytes", pl.saved_bytes, pl.scratch_bytes);
   if (((uintptr_t)saved | (uintptr_t)scratch | (uintptr_t)x | (uintptr_t)h) & 15)
@@ -967,7 +985,7 @@ static hgnn_status fwd_common(hgnn_ctx *ctx, void *stream, hgnn_graph *g, int32_
       if (reo[r + 1] > reo[r]) live[r >> 5] |= 1u << (r & 31);
   }
   {
-    Probe pb(ctx, s, HGNN_K_TRANSPOSE_W, layer);
+    Probe pb(ctx, s, HGNN_K_TRANSPOSE_W, layer, !static_area);
     if ((st = launch_transpose_weights(s, ctx->dtype, pl.tt, pl.rt, pl.pt, pl.wt, pl.H, wtb)) != HGNN_OK) return st;
   }
   ++n;
@@ -979,16 +997,16 @@ static hgnn_status fwd_common(hgnn_ctx *ctx, void *stream, hgnn_graph *g, int32_
       const size_t need = (size_t)pl.dev.edges * p->in_dim[0] * pl.es;
       if (feature_cat_bytes < need) HGNN_FAIL(HGNN_EINVAL, "feature_cat too small: need %zu bytes", need);
       if ((uintptr_t)feature_cat & 15) HGNN_FAIL(HGNN_EINVAL, "device buffers must be 16-byte aligned");
-      Probe pb(ctx, s, HGNN_K_SPMM_FWD, layer);
+      Probe pb(ctx, s, HGNN_K_SPMM_FWD, layer, !static_area);
       if ((st = launch_aggregate_literal(s, ctx->dtype, pl.dev, p->in_dim[0], x, feature_cat, saved, zlo)) != HGNN_OK) return st;
       n += (pl.dev.edges > 0) + (pl.dev.rows > 0);
     } else {
-      Probe pb(ctx, s, HGNN_K_SPMM_FWD, layer);
+      Probe pb(ctx, s, HGNN_K_SPMM_FWD, layer, !static_area);
       if ((st = launch_spmm_fwd(s, ctx->dtype, pl.dev, pl.tt, pl.rt, pl.max_dim, x, saved, zlo, 0, pl.dev.rows)) != HGNN_OK) return st;
       if (pl.dev.rows > 0) ++n;
     }
     {
-      Probe pb(ctx, s, HGNN_K_GEMM_FWD, layer);
+      Probe pb(ctx, s, HGNN_K_GEMM_FWD, layer, !static_area);
       if ((st = launch_gemm_fwd(s, ctx->dtype, pl.dev, pl.tt, pl.rt, pl.pt, pl.wt, tl, live, pl.H, p->relu, x, saved, zlo, wtb, h, -1, nullptr, tile_mn)) != HGNN_OK) return st;
     }
     if (tl.tile_off[T] > 0) ++n;
@@ -1031,6 +1049,16 @@ static hgnn_status fwd_common(hgnn_ctx *ctx, void *stream, hgnn_graph *g, int32_
   if (launches) *launches = n;
   return HGNN_OK;
 }
+
+extern "C++" {
+namespace hgnn {
+hgnn_status layer_fwd_static_area(hgnn_ctx *ctx, void *stream, hgnn_graph *g, int32_t layer, const hgnn_layer_params *p,
+                                  const void *x, void *h, void *saved, size_t saved_bytes, void *area, size_t area_bytes) {
+  if (ctx->agg == HGNN_AGG_ATTN) HGNN_FAIL(HGNN_EUNSUPPORTED, "hgnn_layer_fwd_static covers the mean-aggregation layer only");
+  return fwd_common(ctx, stream, g, layer, p, x, h, saved, saved_bytes, area, area_bytes, false, nullptr, nullptr, 0, true);
+}
+}  // namespace hgnn
+}  // extern "C++"
 
 hgnn_status hgnn_layer_fwd(hgnn_ctx *ctx, void *stream, hgnn_graph *g, int32_t layer, const hgnn_layer_params *p,
                            const void *x_merged, void *h_out, void *saved, size_t saved_bytes, void *scratch,

@@ -270,6 +270,13 @@ hgnn_status plan_graph(hgnn_ctx *ctx, hgnn_graph *g, std::string &msg);  // api.
 void index_edge_type_runs(hgnn_ctx *ctx);                                   // api.cpp: fills run_end / run_rel
 hgnn_status run_sample_job(hgnn_ctx *ctx, Builder &b, hgnn_graph *g, std::string &msg);  // sampler.cpp
 
+// noalloc.hip: the fixed device work area of hgnn_layer_fwd_static
+hgnn_status static_scratch_init(int device);  // with `device` current
+void *static_scratch_ptr(int device);
+// api.cpp: hgnn_layer_fwd of a mean-aggregation layer with its work area laid out compactly in `area`
+hgnn_status layer_fwd_static_area(hgnn_ctx *ctx, void *stream, hgnn_graph *g, int32_t layer, const hgnn_layer_params *p,
+                                  const void *x, void *h, void *saved, size_t saved_bytes, void *area, size_t area_bytes);
+
 // ---- kernel launchers (kernels_*.hip); all enqueue on `s` and return ----
 hgnn_status launch_merge(hipStream_t s, int dtype, int T, const void *const *store, const int32_t *feat_dim,
                          const int64_t *const *ids, const int64_t *n_rows, const int64_t *elem_off, void *out);
