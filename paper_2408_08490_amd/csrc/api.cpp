@@ -510,6 +510,7 @@ hgnn_status hgnn_create(hgnn_ctx **out, const hgnn_schema *s, int device, int ho
   c->agg = s->agg;
   c->fuse = s->fuse;
   c->dtype = s->dtype;
+  c->legacy_gemm = getenv("HGNN_DMA_GEMM") == nullptr;
   if (device >= 0) {
     hipError_t e = hipSetDevice(device);
     if (e == hipSuccess) e = hipStreamCreateWithFlags(&c->side, hipStreamNonBlocking);
@@ -1007,7 +1008,12 @@ static hgnn_status fwd_common(hgnn_ctx *ctx, void *stream, hgnn_graph *g, int32_
     }
     {
       Probe pb(ctx, s, HGNN_K_GEMM_FWD, layer, !static_area);
-      if ((st = launch_gemm_fwd(s, ctx->dtype, pl.dev, pl.tt, pl.rt, pl.pt, pl.wt, tl, live, pl.H, p->relu, x, saved, zlo, wtb, h, -1, nullptr, tile_mn)) != HGNN_OK) return st;
+      bool done = false;
+      if (ctx->dtype == HGNN_BF16 && !ctx->legacy_gemm) {
+        done = launch_gemm2_fwd(s, pl.tt, pl.rt, pl.pt, pl.wt, live, pl.H, p->relu, x, saved, zlo, wtb, h, &st);
+        if (done && st != HGNN_OK) return st;
+      }
+      if (!done && (st = launch_gemm_fwd(s, ctx->dtype, pl.dev, pl.tt, pl.rt, pl.pt, pl.wt, tl, live, pl.H, p->relu, x, saved, zlo, wtb, h, -1, nullptr, tile_mn)) != HGNN_OK) return st;
     }
     if (tl.tile_off[T] > 0) ++n;
   } else {

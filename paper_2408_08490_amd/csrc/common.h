@@ -228,6 +228,8 @@ struct hgnn_ctx {
   int32_t T = 0, R = 0;
   int32_t rel_src[hgnn::kMaxR], rel_dst[hgnn::kMaxR];
   int32_t heads = 1, agg = 0, fuse = 0, dtype = 0;
+  bool legacy_gemm = true;  // false with HGNN_DMA_GEMM set in the environment when the context is created: the bf16 forward
+                            // GEMM runs on the LDS-DMA core (gemm_dma.h), which measures slower than the register-staged one
   std::vector<hgnn::Builder *> builders;  // each takes whole graphs off the queue and owns a slice of the host threads
   hipStream_t side = nullptr;
   std::mutex qm;
@@ -304,6 +306,9 @@ hgnn_status launch_gemm_fwd(hipStream_t s, int dtype, const LayerDev &L, const T
                             const PtrTab &pt, const WtTab &wt, const SegTab &tiles, const uint32_t *live_mask, int H,
                             int relu, const void *x, const void *z, const void *zlo, const void *wt_buf, void *h,
                             int only_seg, float *acc32, int tile_mn = 128);
+// bf16 forward on the LDS-DMA core; false = shape not covered (nothing was launched), else *st is the launch's status
+bool launch_gemm2_fwd(hipStream_t s, const TypeTab &tt, const RelTab &rt, const PtrTab &pt, const WtTab &wt, const uint32_t *live_mask,
+                      int H, int relu, const void *x, const void *z, const void *zlo, const void *wt_buf, void *h, hgnn_status *st);
 // attention variant
 hgnn_status launch_attn_proj(hipStream_t s, int dtype, const TypeTab &tt, const PtrTab &w_type_as_root, const SegTab &tiles, int H,
                              const void *x, void *z);

@@ -112,6 +112,17 @@ def test_config3_full_size_many_types_fp32():
     assert rep["sizes"][1][1] == 512 and rep["sizes"][0][2] > 300_000
 
 
+def test_forward_gemm_on_the_lds_dma_core(monkeypatch):
+    """The alternative bf16 forward GEMM (operand tiles loaded straight into LDS, persistent blocks), which a context
+    uses when HGNN_DMA_GEMM is set: 128-row tiles (scaled config 2, ragged widths with partial K-steps, 108
+    relations) and 256-row tiles (the headline size)."""
+    monkeypatch.setenv("HGNN_DMA_GEMM", "1")
+    _assert_ok(run_case(2, scale=0.05, batch=512, verbose=True))
+    _assert_ok(run_case(3, scale=0.02, batch=128, verbose=True, cfg_edit=_as_bf16))
+    _assert_ok(run_case(6, verbose=True))
+    _assert_ok(run_case(2, scale=1.0, verbose=True, input_grad=[0, 1, 1, 1], backward=False))
+
+
 def _as_f32(cfg, g, mb, ws):
     cfg.dtype = "f32"
 
