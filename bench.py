@@ -24,9 +24,22 @@ if ROOT not in sys.path:
 
 HBM_PEAK_GBS = 8000.0
 MFMA_BF16_PEAK_TFLOPS = 2500.0
-# HBM bytes per launch of the two probed kernels on the default workload, from the rocprofv3 --pmc runs
-# summarised under profiles/ (FETCH_SIZE + WRITE_SIZE, scaled by the copy-kernel calibration); None = not measured
-TRAFFIC_BYTES = {"gemm_fwd": 113.0e6, "spmm_fwd": 221.0e6, "gemm_dw": 261.0e6}
+TRAFFIC_FILE = os.path.join(ROOT, "profiles", "hbm_traffic_config2_bf16.txt")
+
+
+def traffic_bytes():
+    """HBM bytes per launch of the probed kernels on the default workload: the `traffic_bytes <kernel> <bytes>` lines of
+    the rocprofv3 --pmc summary under profiles/ (FETCH_SIZE + WRITE_SIZE, scaled by the copy-kernel calibration stated
+    there).  A kernel without such a line, or a missing file, reads as None (not measured)."""
+    out = {}
+    try:
+        for line in open(TRAFFIC_FILE):
+            f = line.split()
+            if len(f) == 3 and f[0] == "traffic_bytes":
+                out[f[1]] = float(f[2])
+    except OSError:
+        pass
+    return out
 
 
 def main():
@@ -44,8 +57,10 @@ def main():
     ap.add_argument("--no-sampler-loop", action="store_true", help="skip the run with the sampler in the loop")
     ap.add_argument("--no-train-loop", action="store_true", help="skip the run with the parameter update in the step")
     ap.add_argument("--ablation", action="store_true",
-                    help="also time the switchable pieces one by one (the paper's Fig. 9 analogue): per-relation launch "
-                         "loop vs merged launches, serial vs overlapped host build, one host builder vs all")
+                    help="time the switchable pieces (the paper's Fig. 9 analogue: per-relation launch loop vs merged "
+                         "launches, two-step vs fused aggregation, serial vs overlapped host build) over K/4 steps "
+                         "instead of the 20 of the default line")
+    ap.add_argument("--no-ablation", action="store_true", help="leave the ablation object out")
     ap.add_argument("--cpu-sample-batch", type=int, default=4096)
     ap.add_argument("--host-threads", type=int, default=0)
     ap.add_argument("--all-input-grads", action="store_true", help="also compute gradients w.r.t. the fixed T0 features")
@@ -127,50 +142,78 @@ def main():
         b.graph, b.labels_dev, b.grad_out_dev = graph, slot.labels_dev, slot.grad_out_dev
         return b
 
-    def pipelined(nsteps, first):
-        """Step i runs on the GPU while the host threads build the index arrays of the next
-        `lookahead` steps (the sampler of a training loop runs that far ahead)."""
-        ahead = [start_build(slots[(first + j) % len(slots)]) for j in range(min(args.lookahead, nsteps))]
-        started = len(ahead)
-        pending = []
-        for i in range(nsteps):
-            cur = ahead.pop(0)
-            if started < nsteps:
-                ahead.append(start_build(slots[(first + started) % len(slots)]))
-                started += 1
-            model.run(batch_of(slots[(first + i) % len(slots)], cur))
-            ev = torch.cuda.Event()
-            ev.record()
-            pending.append((ev, cur))
-            while len(pending) > 2:              # keep at most two finished-or-running steps alive
-                e, gr = pending.pop(0)
+    class Pipeline:
+        """Step i runs on the GPU while the host threads build the index arrays of the next `lookahead` steps (the
+        sampler of a training loop runs that far ahead).  The look-ahead stays filled from one call of run() to the
+        next, so a timed run() that follows an untimed one measures the loop, not its start-up; every step still
+        starts exactly one build."""
+
+        def __init__(self):
+            self.ahead, self.next, self.pending = [], 0, []
+
+        def fill(self):
+            while len(self.ahead) < args.lookahead:
+                self.ahead.append((self.next, start_build(slots[self.next % len(slots)])))
+                self.next += 1
+
+        def run(self, nsteps):
+            for _ in range(nsteps):
+                i, cur = self.ahead.pop(0)
+                self.ahead.append((self.next, start_build(slots[self.next % len(slots)])))
+                self.next += 1
+                model.run(batch_of(slots[i % len(slots)], cur))
+                ev = torch.cuda.Event()
+                ev.record()
+                self.pending.append((ev, cur))
+                while len(self.pending) > 2:              # keep at most two finished-or-running steps alive
+                    e, gr = self.pending.pop(0)
+                    e.synchronize()
+                    gr.release()
+
+        def drain(self):
+            for e, gr in self.pending:
                 e.synchronize()
                 gr.release()
-        for e, gr in pending:
-            e.synchronize()
-            gr.release()
+            for _, gr in self.ahead:
+                gr.wait()
+                gr.release()
+            self.ahead, self.pending = [], []
 
     W, K = args.warmup, args.steps
     # kernels bracketed with HIP event pairs inside the timed region: the dominant kernel (forward GEMM of
     # layer 1: projection + fusion) and the aggregation kernel of layer 1, or the one asked for
     probes = ([("gemm_fwd", 0), ("spmm_fwd", 0)] + ([] if cfg.kind == "rgat" else [("gemm_dw", 0)])
               if args.probe == "auto" else [(k_, args.probe_layer) for k_ in args.probe.split(",")])
-    pipelined(W, 0)
+    pipe = Pipeline()
+    t_f = time.perf_counter()
+    pipe.fill()
+    pipe.run(1)
+    torch.cuda.synchronize()
+    t_fill = time.perf_counter() - t_f          # cold start: look-ahead builds started, first step through the GPU
+    pipe.run(max(W - 1, 0))
     torch.cuda.synchronize()
     # the W steps above last ~20 ms: not enough for 16 host threads and their buffer pools to reach their steady
     # state on a machine that was idle a moment ago, so the same untimed loop runs on for a few seconds
     t_w = time.perf_counter()
     while W > 0 and time.perf_counter() - t_w < args.host_warmup_s:
-        pipelined(max(W, 50), 0)
+        pipe.run(max(W, 50))
     torch.cuda.synchronize()
+    # the probe brackets every selected launch with an event pair that the library creates on first use: an untimed
+    # pass of the same length creates them all, so that the timed steps only reuse them
+    for k_, l_ in probes:
+        ctx.hgnn_probe_select(B.KERNEL_IDS[k_], l_)
+    pipe.run(K)
+    torch.cuda.synchronize()
+    ctx.hgnn_probe_select(-1, -1)
     for k_, l_ in probes:
         ctx.hgnn_probe_select(B.KERNEL_IDS[k_], l_)
     t1 = time.perf_counter()
-    pipelined(K, W)
+    pipe.run(K)
     torch.cuda.synchronize()
     t_pipe = time.perf_counter() - t1
     probe_res = {(k_, l_): ctx.hgnn_probe_read(B.KERNEL_IDS[k_], l_) for k_, l_ in probes}
     ctx.hgnn_probe_select(-1, -1)
+    pipe.drain()
 
     # same loop with the index arrays built beforehand (GPU work only)
     graphs = [start_build(s) for s in slots]
@@ -273,12 +316,13 @@ def main():
     launches = []
     b0 = batch_of(slots[0], graphs[0])
     attention = cfg.kind == "rgat"   # the per-relation launch loop exists for the mean variant only
-    out_naive = None if attention else model.run(b0, backward=False, naive=True)
+    out_naive = None if attention else model.run(b0, backward=True, naive=True)
     torch.cuda.synchronize()
     for l in range(len(model.layers)):
         f, bw = ctx.hgnn_layer_launch_count(graphs[0], l, model.layers[l])
         launches.append(dict(layer=l, merged_fwd=f, merged_bwd=bw,
-                             naive_fwd=None if attention else out_naive["launches"][l]))
+                             naive_fwd=None if attention else out_naive["launches"][l],
+                             naive_bwd=None if attention else out_naive["launches_bwd"][l]))
 
     # algorithmic traffic / flops of the probed kernels, from the first mini-batch's shapes
     es = 2 if cfg.dtype == "bf16" else 4
@@ -363,10 +407,11 @@ def main():
     if roof_agg is not None:
         # HBM bytes per launch from rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE runs of this command (profiles/)
         if cfg.index == 2 and args.scale == 1.0:     # measured on the default workload only
-            roof_proj["traffic"] = TRAFFIC_BYTES.get("gemm_fwd")
-            roof_agg["traffic"] = TRAFFIC_BYTES.get("spmm_fwd")
+            tb = traffic_bytes()
+            roof_proj["traffic"] = tb.get("gemm_fwd_layer1")
+            roof_agg["traffic"] = tb.get("spmm_fwd_layer1")
             if roof_dw is not None:
-                roof_dw["traffic"] = TRAFFIC_BYTES.get("gemm_dw")
+                roof_dw["traffic"] = tb.get("gemm_bwd_layer1")
     with_busy(roof_proj, probes[0])
     if roof_agg is not None:
         with_busy(roof_agg, probes[1])
@@ -378,7 +423,7 @@ def main():
 
     # ablation: what each piece buys on this machine
     abl = None
-    if args.ablation:
+    if not args.no_ablation:
         def gpu_ms(fn, n):
             torch.cuda.synchronize()
             a, b_ = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
@@ -389,11 +434,17 @@ def main():
             torch.cuda.synchronize()
             return a.elapsed_time(b_) / n
 
+        def step_naive(i):
+            model.run(batch_of(slots[i % len(slots)], graphs[i % len(slots)]), backward=True, naive=True)
+
+        def step_merged(i):
+            model.run(batch_of(slots[i % len(slots)], graphs[i % len(slots)]), backward=True)
+
         def fwd_only(naive, two_step=False):
             def f(i):
                 model.run(batch_of(slots[i % len(slots)], graphs[i % len(slots)]), backward=False, naive=naive, two_step=two_step)
             return f
-        n_ab = max(20, K // 4)
+        n_ab = max(20, K // 4) if args.ablation else 20
         fwd_only(False)(0)
         merged_fwd_ms = gpu_ms(fwd_only(False), n_ab)
         naive_fwd_ms = two_step_fwd_ms = None
@@ -415,13 +466,22 @@ def main():
             return (time.perf_counter() - t) / n
         serial_loop(3)
         serial_ms = 1e3 * serial_loop(n_ab)
-        abl = dict(forward_merged_ms=round(merged_fwd_ms, 4),
+        step_naive_ms = None
+        if not attention:
+            step_naive(0)
+            step_naive_ms = gpu_ms(step_naive, n_ab)
+        step_merged(0)
+        step_merged_ms = gpu_ms(step_merged, n_ab)
+        abl = dict(steps_timed=n_ab, forward_merged_ms=round(merged_fwd_ms, 4),
+                   step_merged_launches_ms=round(step_merged_ms, 4),
+                   step_per_relation_launches_ms=None if step_naive_ms is None else round(step_naive_ms, 4),
                    forward_per_relation_launches_ms=None if naive_fwd_ms is None else round(naive_fwd_ms, 4),
                    forward_two_step_aggregation_ms=None if two_step_fwd_ms is None else round(two_step_fwd_ms, 4),
                    step_serial_build_then_compute_ms=round(serial_ms, 4),
                    step_overlapped_ms=round(1e3 * t_pipe / K, 4), step_gpu_only_ms=round(1e3 * t_gpu / K, 4),
                    host_builders=args.concurrent_builds,
-                   note="forward_*: merge + all layers forward, index arrays resident (GPU time between events); two_step: "
+                   note="forward_*: merge + all layers forward, index arrays resident (GPU time between events); step_*: "
+                        "the same with loss and backward, merged launches against the per-relation / per-type launch loop; two_step: "
                         "the aggregation as Algorithm 1 states it (source rows of all semantic graphs gathered into "
                         "FeatureCat, then reduced by destination) instead of the fused gather-mean; "
                         "serial: every step builds its index arrays with one builder, waits, computes, waits; "
@@ -494,6 +554,9 @@ def main():
                                          (", perm, cperm" if args.build_permutation or attention else
                                           " (perm / cperm, which no kernel of this path reads, are left out)"))),
         gpu_only_mb_per_s=round(K / t_gpu, 2), gpu_only_ms_per_step=round(1e3 * t_gpu / K, 4),
+        pipeline=dict(lookahead=args.lookahead, fill_ms=round(1e3 * t_fill, 3),
+                      note="the look-ahead is filled before the timed region (fill_ms: cold start until the first step has "
+                           "left the GPU); the K timed steps start K builds and run K steps"),
         host_build_ms=round(1e3 * t_build, 3), sampler_in_loop=sil, training_step=train, ablation=abl, launches_per_layer=launches,
         roofline=roof, roofline_projection=roof_proj, roofline_weight_grad=roof_dw, roofline_aggregation=roof_agg,
         cpu_baseline=cpu, setup_s=round(t_setup, 1))

@@ -328,6 +328,11 @@ hgnn_status hgnn_layer_fwd_naive(hgnn_ctx *ctx, void *stream, hgnn_graph *g, int
                                  const hgnn_layer_params *p, const void *x_merged, void *h_out,
                                  void *saved, size_t saved_bytes, void *scratch,
                                  size_t scratch_bytes, int32_t *launches);
+hgnn_status hgnn_layer_bwd_naive(hgnn_ctx *ctx, void *stream, hgnn_graph *g, int32_t layer,
+                                 const hgnn_layer_params *p, const void *x_merged, const void *h_out,
+                                 const void *saved, const void *grad_h, void *grad_x_merged,
+                                 const hgnn_layer_grads *g_out, void *scratch, size_t scratch_bytes,
+                                 int32_t *launches);
 /* Materialising baseline: the same layer forward with the aggregation done in the two steps in which
  * Algorithm 1 (Section 4.2) states it -- the source rows of all semantic graphs gathered and concatenated
  * into FeatureCat [num_edges x F] (dtype), then reduced by destination -- instead of the fused gather-mean

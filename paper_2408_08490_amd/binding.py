@@ -109,6 +109,8 @@ def _load():
                                     vp, C.c_size_t, C.POINTER(i32)],
         "hgnn_layer_bwd": [vp, vp, vp, i32, C.POINTER(LayerParams), vp, vp, vp, vp, vp, C.POINTER(LayerGrads),
                            vp, C.c_size_t],
+        "hgnn_layer_bwd_naive": [vp, vp, vp, i32, C.POINTER(LayerParams), vp, vp, vp, vp, vp, C.POINTER(LayerGrads),
+                                 vp, C.c_size_t, C.POINTER(i32)],
         "hgnn_layer_launch_count": [vp, vp, i32, C.POINTER(LayerParams), C.POINTER(i32), C.POINTER(i32)],
         "hgnn_softmax_xent": [vp, vp, vp, vp, i64, i32, vp, vp],
         "hgnn_adam_update": [vp, vp, i32, C.POINTER(vp), C.POINTER(vp), C.POINTER(vp), C.POINTER(vp), C.POINTER(vp),
@@ -134,7 +136,7 @@ EXPORTS = ["hgnn_create", "hgnn_destroy", "hgnn_last_error", "hgnn_merge_feature
            "hgnn_build_semantic_csr", "hgnn_sampler_create", "hgnn_sampler_destroy", "hgnn_sample_and_build",
            "hgnn_graph_ids", "hgnn_graph_minibatch_view", "hgnn_graph_wait_stream",
            "hgnn_set_build_permutation", "hgnn_graph_wait", "hgnn_graph_host_view", "hgnn_graph_release", "hgnn_layer_workspace_bytes",
-           "hgnn_layer_fwd", "hgnn_layer_fwd_static", "hgnn_layer_bwd", "hgnn_layer_fwd_naive", "hgnn_layer_fwd_two_step", "hgnn_layer_launch_count",
+           "hgnn_layer_fwd", "hgnn_layer_fwd_static", "hgnn_layer_bwd", "hgnn_layer_fwd_naive", "hgnn_layer_bwd_naive", "hgnn_layer_fwd_two_step", "hgnn_layer_launch_count",
            "hgnn_softmax_xent", "hgnn_adam_update", "hgnn_adam_update_rows", "hgnn_probe_select", "hgnn_probe_read"]
 
 KERNEL_IDS = dict(merge=0, transpose_w=1, spmm_fwd=2, gemm_fwd=3, zero_grads=4, relu_bias_bwd=5, gemm_dw=6,
@@ -458,6 +460,13 @@ class Context:
         _check(lib.hgnn_layer_bwd(self.handle, _stream_ptr(self.device), graph.handle, layer, C.byref(lp.params), _ptr(x_merged),
                                   _ptr(h_out), _ptr(saved), _ptr(grad_h), _ptr(grad_x_merged), C.byref(lp.grads),
                                   _ptr(scratch), scratch.numel() * scratch.element_size()))
+
+    def hgnn_layer_bwd_naive(self, graph, layer, lp, x_merged, h_out, saved, grad_h, grad_x_merged, scratch) -> int:
+        n = C.c_int32()
+        _check(lib.hgnn_layer_bwd_naive(self.handle, _stream_ptr(self.device), graph.handle, layer, C.byref(lp.params),
+                                        _ptr(x_merged), _ptr(h_out), _ptr(saved), _ptr(grad_h), _ptr(grad_x_merged),
+                                        C.byref(lp.grads), _ptr(scratch), scratch.numel() * scratch.element_size(), C.byref(n)))
+        return n.value
 
     def hgnn_layer_launch_count(self, graph, layer, lp):
         a, b = C.c_int32(), C.c_int32()

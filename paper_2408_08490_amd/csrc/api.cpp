@@ -1104,11 +1104,15 @@ static void seg_tiles_da(hgnn_ctx *ctx, const Plan &pl, const hgnn_layer_params 
   }
 }
 
-hgnn_status hgnn_layer_bwd(hgnn_ctx *ctx, void *stream, hgnn_graph *g, int32_t layer, const hgnn_layer_params *p,
-                           const void *x_merged, const void *h_out, const void *saved, const void *grad_h,
-                           void *grad_x_merged, const hgnn_layer_grads *go, void *scratch, size_t scratch_bytes) {
-  if (ctx && ctx->agg == HGNN_AGG_ATTN)
+static hgnn_status bwd_common(hgnn_ctx *ctx, void *stream, hgnn_graph *g, int32_t layer, const hgnn_layer_params *p,
+                              const void *x_merged, const void *h_out, const void *saved, const void *grad_h,
+                              void *grad_x_merged, const hgnn_layer_grads *go, void *scratch, size_t scratch_bytes, bool naive,
+                              int32_t *launches) {
+  if (launches) *launches = 0;
+  if (ctx && ctx->agg == HGNN_AGG_ATTN) {
+    if (naive) HGNN_FAIL(HGNN_EUNSUPPORTED, "the per-relation launch loop exists for the mean-aggregation layer only");
     return attn_bwd(ctx, stream, g, layer, p, x_merged, h_out, saved, grad_h, grad_x_merged, go, scratch, scratch_bytes);
+  }
   Plan pl;
   hgnn_status st = make_plan(ctx, g, layer, p, pl, true);
   if (st != HGNN_OK) return st;
@@ -1171,6 +1175,80 @@ hgnn_status hgnn_layer_bwd(hgnn_ctx *ctx, void *stream, hgnn_graph *g, int32_t l
       }
     }
     if (grad_x_merged) wpad = wp;
+  }
+  if (naive) {
+    // The un-merged launch structure: the same kernels, launched once per vertex type (ReLU mask / bias gradient,
+    // transposed aggregation) and once per relation or root term (weight gradient, input gradient), after one
+    // launch that zeroes the gradients (and one that pads the weights where the width asks for it).
+    int n = 0;
+    void *gpw = sc + pl.off_gp;
+    const void *gpn = grad_h;
+    if (wpad) {
+      if ((st = launch_pad_weights(s, ctx->dtype, pl.tt, pl.rt, pl.pt, wo, pl.H, ldg, wpad)) != HGNN_OK) return st;
+      ++n;
+    }
+    if (any_dw || any_db) {
+      if ((st = launch_zero_grads(s, pl.tt, pl.rt, gt, pl.H)) != HGNN_OK) return st;
+      ++n;
+    }
+    if (pl.total_dst > 0 && (p->relu || any_db || ldg != pl.H)) {
+      for (int t = 0; t < T; ++t) {
+        if (pl.tt.n_dst[t] == 0) continue;
+        TypeTab one = pl.tt;
+        for (int u = 0; u < T; ++u)
+          if (u != t) one.n_dst[u] = 0;
+        if ((st = launch_relu_bias_bwd(s, ctx->dtype, one, pl.H, ldg, p->relu, grad_h, h_out, gpw, gt)) != HGNN_OK) return st;
+        ++n;
+      }
+      if (p->relu || ldg != pl.H) gpn = gpw;
+    }
+    const bool fastn = (ldg % (16 / pl.es)) == 0;
+    const bool want_dxn = grad_x_merged && pl.dev.src_rows > 0;
+    if (want_dxn)
+      for (int t = 0; t < T; ++t)
+        if ((!p->input_grad || p->input_grad[t]) && !((L.tmask >> t) & 1u) && L.n_src[t] > 0)
+          HGNN_FAIL(HGNN_EINVAL, "input gradient of type %d asked for, but the graph was built without its transpose entries", t);
+    void *dzn = sc + pl.off_dz;
+    const int tiles_hn = (pl.H + 127) / 128;
+    for (int sgi = 0; sgi < R + T && pl.total_dst > 0; ++sgi) {
+      const bool is_rel = sgi < R;
+      const int d = is_rel ? ctx->rel_dst[sgi] : sgi - R;
+      const int F = pl.tt.in_dim[is_rel ? ctx->rel_src[sgi] : d];
+      if (pl.tt.n_dst[d] == 0) continue;
+      const bool live = is_rel ? reo[sgi + 1] > reo[sgi] : p->w_root[d] != nullptr;
+      if (!live) continue;
+      if (is_rel ? gt.dw_rel[sgi] != nullptr : gt.dw_root[d] != nullptr) {  // weight gradient of this segment
+        DwTab one;
+        std::memset(&one, 0, sizeof(one));
+        for (int u = 0; u <= T; ++u) one.first[u] = (uint16_t)(u > d ? 1 : 0);
+        one.seg[0] = (uint8_t)sgi;
+        one.u_off[0] = 0;
+        one.u_total[d] = (uint16_t)((F + 127) / 128);
+        const int split_rows = 2048;
+        const int cnt = one.u_total[d] * tiles_hn * ((pl.tt.n_dst[d] + split_rows - 1) / split_rows);
+        for (int u = d; u < T; ++u) one.tile_off[u + 1] = cnt;
+        if ((st = launch_gemm_dw(s, ctx->dtype, pl.dev, pl.tt, pl.rt, gt, one, split_rows, pl.H, ldg, fastn, x_merged, saved, gpn)) != HGNN_OK) return st;
+        ++n;
+      }
+      if (want_dxn && (!p->input_grad || p->input_grad[is_rel ? ctx->rel_src[sgi] : d])) {  // input gradient of this segment
+        SegTab one;
+        std::memset(&one, 0, sizeof(one));
+        one.num_segs = R + T;
+        const int cnt = ((pl.tt.n_dst[d] + 127) / 128) * ((F + 127) / 128);
+        for (int u = sgi; u < R + T; ++u) one.tile_off[u + 1] = cnt;
+        if ((st = launch_gemm_da(s, ctx->dtype, pl.dev, pl.tt, pl.rt, wpt, one, ldg, fastn, gpn, dzn)) != HGNN_OK) return st;
+        ++n;
+      }
+    }
+    if (want_dxn) {
+      for (int t = 0; t < T; ++t) {
+        if ((p->input_grad && !p->input_grad[t]) || L.n_src[t] == 0) continue;
+        if ((st = launch_spmm_bwd(s, ctx->dtype, pl.dev, pl.tt, pl.rt, pl.pt, pl.max_dim, 1u << t, dzn, grad_x_merged, (float *)(sc + pl.off_partial))) != HGNN_OK) return st;
+        n += 1 + (pl.dev.n_long > 0);
+      }
+    }
+    if (launches) *launches = n;
+    return HGNN_OK;
   }
   // One launch: the row pass over G (ReLU mask, padded copy, column sums for the bias gradient as partial sums
   // per block), zeroing of the weight gradients, the padded weights.  The partial sums are added up by a few
@@ -1254,6 +1332,19 @@ hgnn_status hgnn_layer_bwd(hgnn_ctx *ctx, void *stream, hgnn_graph *g, int32_t l
     if ((st = launch_spmm_bwd(s, ctx->dtype, pl.dev, pl.tt, pl.rt, pl.pt, pl.max_dim, want, dz, grad_x_merged, (float *)(sc + pl.off_partial))) != HGNN_OK) return st;
   }
   return HGNN_OK;
+}
+
+hgnn_status hgnn_layer_bwd(hgnn_ctx *ctx, void *stream, hgnn_graph *g, int32_t layer, const hgnn_layer_params *p,
+                           const void *x_merged, const void *h_out, const void *saved, const void *grad_h,
+                           void *grad_x_merged, const hgnn_layer_grads *go, void *scratch, size_t scratch_bytes) {
+  return bwd_common(ctx, stream, g, layer, p, x_merged, h_out, saved, grad_h, grad_x_merged, go, scratch, scratch_bytes, false, nullptr);
+}
+
+hgnn_status hgnn_layer_bwd_naive(hgnn_ctx *ctx, void *stream, hgnn_graph *g, int32_t layer, const hgnn_layer_params *p,
+                                 const void *x_merged, const void *h_out, const void *saved, const void *grad_h,
+                                 void *grad_x_merged, const hgnn_layer_grads *go, void *scratch, size_t scratch_bytes,
+                                 int32_t *launches) {
+  return bwd_common(ctx, stream, g, layer, p, x_merged, h_out, saved, grad_h, grad_x_merged, go, scratch, scratch_bytes, true, launches);
 }
 
 hgnn_status hgnn_layer_launch_count(hgnn_ctx *ctx, hgnn_graph *g, int32_t layer, const hgnn_layer_params *p,

@@ -250,6 +250,7 @@ class Model:
         if not backward:
             return out
         dxs = [None] * L
+        launches_bwd = [0] * L
         for l in reversed(range(L)):
             lp = self.layers[l]
             blk = b.blocks[l]
@@ -257,8 +258,12 @@ class Model:
             sc = self._get("scratch", cb)
             want_dx = need_input_grad or l > 0
             dx = self._typed(f"dx{l}", sum(n * f for n, f in zip(blk.n_src, lp.in_dim))) if want_dx else None
-            ctx.hgnn_layer_bwd(b.graph, l, lp, xs[l], hs[l], saved[l], g, dx, sc)
+            if naive and not self.attention:
+                launches_bwd[l] = ctx.hgnn_layer_bwd_naive(b.graph, l, lp, xs[l], hs[l], saved[l], g, dx, sc)
+            else:
+                ctx.hgnn_layer_bwd(b.graph, l, lp, xs[l], hs[l], saved[l], g, dx, sc)
             dxs[l] = dx
             g = dx
         out["dx"] = dxs
+        out["launches_bwd"] = launches_bwd
         return out

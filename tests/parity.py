@@ -193,96 +193,102 @@ def run_case(index, scale=1.0, batch=None, verbose=False, use_edge_id=True, chec
     # changes ~ sqrt(f / A) of the L2 norm of that type's masked output gradient when gradient magnitudes are
     # alike, and every gradient downstream is linear in it; with a factor 4 for unlike magnitudes the bound is
     # tol + 4 max_type sqrt(f / A), and never more than 2e-2 whatever the storage type.
-    masks, n_band, n_flip, n_units, flip_share = [], 0, 0, 0, 0.0
-    for l in range(len(ws)):
-        if not ws[l].relu:
-            masks.append(None)
-            continue
-        hg = out["h"][l].float().cpu().numpy().reshape(-1, ws[l].out_dim)
-        band = decision_band(cfg, ref["caches"][l], ref["sels"][l], l)
-        ml, r0 = [], 0
-        for t in range(sch.num_types):
-            pre = ref["caches"][l]["pre"][t]
-            hgt = hg[r0: r0 + pre.shape[0]]
-            r0 += pre.shape[0]
-            if pre.size == 0:
-                ml.append(np.zeros(pre.shape, bool))
-                continue
-            if not np.array_equal((hgt > 0)[~band[t]], (pre > 0)[~band[t]]):
-                ok = False
-                report[f"L{l}.relu_decisions_type{t}"] = "MISMATCH"
-            ml.append(np.where(band[t], hgt > 0, pre > 0))
-            n_band += int(band[t].sum()); n_units += band[t].size
-            f = int(((hgt > 0) != (pre > 0)).sum())
-            n_flip += f
-            flip_share = max(flip_share, f / max(int((pre > 0).sum()), 1))
-        masks.append(ml)
-    report["relu_units_in_band"] = (n_band, n_units)
-    report["relu_units_flipped"] = n_flip
-    band_max = band_max_frac if band_max_frac is not None else BAND_MAX_FRAC[cfg.dtype]
-    if n_units and n_band > max(band_max * n_units, 2):
-        ok = False
-        report["relu_band"] = "MISMATCH"
-    ref_tb = ref
-    if n_flip:
-        layers = layer_dicts(cfg, ws)
-        ref_tb = O.rgcn_model_forward_backward(None, None, sch.rel_src, sch.rel_dst, None, layers,
-                                               "xent" if cfg.loss == "xent" else "dot", labels=mb.labels,
-                                               grad_out=mb.grad_out, target_type=mb.target_type,
-                                               forward=dict(h=ref["h"], caches=ref["caches"]), relu_masks=masks,
-                                               num_types=sch.num_types)
-
-    def chk2(name, got, want_plain, want_tb):
+    def check_run(out, sfx=""):
+        """Everything floating point of one run of the path (`out`): layer outputs against the plain oracle, gradients
+        as described above.  sfx is appended to the names in the report."""
         nonlocal ok
-        e_plain, e_tb = rel_errors(got, want_plain), rel_errors(got, want_tb)
-        t_tb, t_plain = tol, min(tol + 4.0 * np.sqrt(flip_share), max(tol, 2e-2))
-        for key, t2 in (grad_tol or {}).items():
-            if key in name:
-                t_tb = t_plain = t2
-        good = (t_tb is None or (e_tb[0] <= t_tb and e_tb[1] <= t_tb)) and (t_plain is None or e_plain[1] <= t_plain)
-        report[name] = (round(e_tb[0], 7), round(e_tb[1], 7))
-        report[name + "|plain"] = (round(e_plain[0], 7), round(e_plain[1], 7))
-        if not good:
+        masks, n_band, n_flip, n_units, flip_share = [], 0, 0, 0, 0.0
+        for l in range(len(ws)):
+            if not ws[l].relu:
+                masks.append(None)
+                continue
+            hg = out["h"][l].float().cpu().numpy().reshape(-1, ws[l].out_dim)
+            band = decision_band(cfg, ref["caches"][l], ref["sels"][l], l)
+            ml, r0 = [], 0
+            for t in range(sch.num_types):
+                pre = ref["caches"][l]["pre"][t]
+                hgt = hg[r0: r0 + pre.shape[0]]
+                r0 += pre.shape[0]
+                if pre.size == 0:
+                    ml.append(np.zeros(pre.shape, bool))
+                    continue
+                if not np.array_equal((hgt > 0)[~band[t]], (pre > 0)[~band[t]]):
+                    ok = False
+                    report[f"L{l}.relu_decisions_type{t}" + sfx] = "MISMATCH"
+                ml.append(np.where(band[t], hgt > 0, pre > 0))
+                n_band += int(band[t].sum()); n_units += band[t].size
+                f = int(((hgt > 0) != (pre > 0)).sum())
+                n_flip += f
+                flip_share = max(flip_share, f / max(int((pre > 0).sum()), 1))
+            masks.append(ml)
+        report["relu_units_in_band" + sfx] = (n_band, n_units)
+        report["relu_units_flipped" + sfx] = n_flip
+        band_max = band_max_frac if band_max_frac is not None else BAND_MAX_FRAC[cfg.dtype]
+        if n_units and n_band > max(band_max * n_units, 2):
             ok = False
-            if verbose:
-                print("FAIL", name, "plain", e_plain, "accepted decisions", e_tb, flush=True)
+            report["relu_band" + sfx] = "MISMATCH"
+        ref_tb = ref
+        if n_flip:
+            layers = layer_dicts(cfg, ws)
+            ref_tb = O.rgcn_model_forward_backward(None, None, sch.rel_src, sch.rel_dst, None, layers,
+                                                   "xent" if cfg.loss == "xent" else "dot", labels=mb.labels,
+                                                   grad_out=mb.grad_out, target_type=mb.target_type,
+                                                   forward=dict(h=ref["h"], caches=ref["caches"]), relu_masks=masks,
+                                                   num_types=sch.num_types)
 
-    for l in range(len(ws)):
-        want = np.concatenate([h.ravel() for h in ref["h"][l]])
-        chk(f"L{l}.h", out["h"][l].float().cpu().numpy(), want)
-        if not backward:
-            continue
-        gr, gt, w = ref["grads"][l], ref_tb["grads"][l], model.weights[l]
-        if cfg.kind == "rgat":
-            for t in range(sch.num_types):
-                chk2(f"L{l}.dw_type{t}", w["dattn"]["dw_type"][t].cpu().numpy(), gr["dw_type"][t], gt["dw_type"][t])
-                if gr["dbias"][t] is not None:
-                    chk2(f"L{l}.dbias{t}", w["dbias"][t].cpu().numpy(), gr["dbias"][t], gt["dbias"][t])
-            for r in range(sch.num_rels):
-                chk2(f"L{l}.da_src{r}", w["dattn"]["da_src"][r].cpu().numpy(), gr["da_src"][r], gt["da_src"][r])
-                chk2(f"L{l}.da_dst{r}", w["dattn"]["da_dst"][r].cpu().numpy(), gr["da_dst"][r], gt["da_dst"][r])
-            for k in ("dw_sem", "db_sem", "dq_sem"):
-                chk2(f"L{l}.{k}", w["dattn"][k].cpu().numpy(), gr[k], gt[k])
-        else:
-            for r in range(sch.num_rels):
-                chk2(f"L{l}.dw_rel{r}", w["dw_rel"][r].cpu().numpy(), gr["dw_rel"][r], gt["dw_rel"][r])
-            for t in range(sch.num_types):
-                if gr["dw_root"][t] is not None:
-                    chk2(f"L{l}.dw_root{t}", w["dw_root"][t].cpu().numpy(), gr["dw_root"][t], gt["dw_root"][t])
-                if gr["dbias"][t] is not None:
-                    chk2(f"L{l}.dbias{t}", w["dbias"][t].cpu().numpy(), gr["dbias"][t], gt["dbias"][t])
-        if out["dx"][l] is None:
-            assert l == 0 and not need_input_grad
-            continue
-        got_dx = out["dx"][l].float().cpu().numpy()
-        if l == 0 and input_grad is not None:          # rows of types without input gradients are left unwritten
-            eo = np.concatenate([[0], np.cumsum([d.size for d in gr["dx"]])])
-            keep = [t for t in range(sch.num_types) if input_grad[t]]
-            chk2(f"L{l}.dx", np.concatenate([got_dx[eo[t]: eo[t + 1]] for t in keep]),
-                 np.concatenate([gr["dx"][t].ravel() for t in keep]), np.concatenate([gt["dx"][t].ravel() for t in keep]))
-        else:
-            chk2(f"L{l}.dx", got_dx, np.concatenate([d.ravel() for d in gr["dx"]]),
-                 np.concatenate([d.ravel() for d in gt["dx"]]))
+        def chk2(name, got, want_plain, want_tb):
+            nonlocal ok
+            name = name + sfx
+            e_plain, e_tb = rel_errors(got, want_plain), rel_errors(got, want_tb)
+            t_tb, t_plain = tol, min(tol + 4.0 * np.sqrt(flip_share), max(tol, 2e-2))
+            for key, t2 in (grad_tol or {}).items():
+                if key in name:
+                    t_tb = t_plain = t2
+            good = (t_tb is None or (e_tb[0] <= t_tb and e_tb[1] <= t_tb)) and (t_plain is None or e_plain[1] <= t_plain)
+            report[name] = (round(e_tb[0], 7), round(e_tb[1], 7))
+            report[name + "|plain"] = (round(e_plain[0], 7), round(e_plain[1], 7))
+            if not good:
+                ok = False
+                if verbose:
+                    print("FAIL", name, "plain", e_plain, "accepted decisions", e_tb, flush=True)
+
+        for l in range(len(ws)):
+            want = np.concatenate([h.ravel() for h in ref["h"][l]])
+            chk(f"L{l}.h" + sfx, out["h"][l].float().cpu().numpy(), want)
+            if not backward:
+                continue
+            gr, gt, w = ref["grads"][l], ref_tb["grads"][l], model.weights[l]
+            if cfg.kind == "rgat":
+                for t in range(sch.num_types):
+                    chk2(f"L{l}.dw_type{t}", w["dattn"]["dw_type"][t].cpu().numpy(), gr["dw_type"][t], gt["dw_type"][t])
+                    if gr["dbias"][t] is not None:
+                        chk2(f"L{l}.dbias{t}", w["dbias"][t].cpu().numpy(), gr["dbias"][t], gt["dbias"][t])
+                for r in range(sch.num_rels):
+                    chk2(f"L{l}.da_src{r}", w["dattn"]["da_src"][r].cpu().numpy(), gr["da_src"][r], gt["da_src"][r])
+                    chk2(f"L{l}.da_dst{r}", w["dattn"]["da_dst"][r].cpu().numpy(), gr["da_dst"][r], gt["da_dst"][r])
+                for k in ("dw_sem", "db_sem", "dq_sem"):
+                    chk2(f"L{l}.{k}", w["dattn"][k].cpu().numpy(), gr[k], gt[k])
+            else:
+                for r in range(sch.num_rels):
+                    chk2(f"L{l}.dw_rel{r}", w["dw_rel"][r].cpu().numpy(), gr["dw_rel"][r], gt["dw_rel"][r])
+                for t in range(sch.num_types):
+                    if gr["dw_root"][t] is not None:
+                        chk2(f"L{l}.dw_root{t}", w["dw_root"][t].cpu().numpy(), gr["dw_root"][t], gt["dw_root"][t])
+                    if gr["dbias"][t] is not None:
+                        chk2(f"L{l}.dbias{t}", w["dbias"][t].cpu().numpy(), gr["dbias"][t], gt["dbias"][t])
+            if out["dx"][l] is None:
+                assert l == 0 and not need_input_grad
+                continue
+            got_dx = out["dx"][l].float().cpu().numpy()
+            if l == 0 and input_grad is not None:          # rows of types without input gradients are left unwritten
+                eo = np.concatenate([[0], np.cumsum([d.size for d in gr["dx"]])])
+                keep = [t for t in range(sch.num_types) if input_grad[t]]
+                chk2(f"L{l}.dx", np.concatenate([got_dx[eo[t]: eo[t + 1]] for t in keep]),
+                     np.concatenate([gr["dx"][t].ravel() for t in keep]), np.concatenate([gt["dx"][t].ravel() for t in keep]))
+            else:
+                chk2(f"L{l}.dx", got_dx, np.concatenate([d.ravel() for d in gr["dx"]]),
+                     np.concatenate([d.ravel() for d in gt["dx"]]))
+    check_run(out)
     if cfg.loss == "xent":
         chk("loss", out["loss"].cpu().numpy(), np.array([ref["loss"]]))
     if check_naive:
@@ -291,6 +297,12 @@ def run_case(index, scale=1.0, batch=None, verbose=False, use_edge_id=True, chec
         for l in range(len(ws)):
             want = np.concatenate([h.ravel() for h in ref["h"][l]])
             chk(f"L{l}.h_naive", out2["h"][l].float().cpu().numpy(), want)
+        if backward and cfg.kind != "rgat":
+            # the backward's per-relation / per-type launch loop: the same checks on its outputs
+            out2 = model.run(bt, backward=True, naive=True, need_input_grad=need_input_grad)
+            torch.cuda.synchronize()
+            check_run(out2, "_naive")
+            report["naive_launches_bwd"] = out2["launches_bwd"]
         report["naive_launches"] = out2["launches"]
         report["merged_launches"] = [model.ctx.hgnn_layer_launch_count(bt.graph, l, model.layers[l])
                                      for l in range(len(ws))]
