@@ -510,12 +510,14 @@ void build_graph_job(hgnn_ctx *ctx, Builder &bd, hgnn_graph *g) {
     }
   }
   {
+    // notified under the lock: a waiter may release (delete) the graph as soon as it sees the new state, so the
+    // unlock must be this thread's last touch of it
     std::lock_guard<std::mutex> lk(g->m);
     g->status = status;
     g->err = msg;
     g->state = (status == HGNN_OK) ? 1 : 2;
+    g->cv.notify_all();
   }
-  g->cv.notify_all();
 }
 
 }  // namespace hgnn

@@ -296,6 +296,52 @@ def test_attention_plan_validation_without_gpu(B):
     ctx.close()
 
 
+@pytest.mark.parametrize("dtype,width,vec", [("f32", 6, 4), ("f32", 130, 4), ("bf16", 12, 8), ("bf16", 4, 8)])
+def test_feature_widths_off_the_16_byte_grid_are_refused(B, dtype, width, vec):
+    """Rows move as 16-byte vectors, so every entry point that takes a feature width refuses one that is not a
+    multiple of 16 bytes / sizeof(dtype) before it touches the device: the layer plan (workspace query), the
+    feature merge and the row-wise Adam update, each with a message that names the width and the multiple."""
+    import torch
+    cfg = make_config(0)
+    g = build_graph(cfg)
+    mb = sample_minibatch(cfg, g)
+    sch = g.schema
+    T, R = sch.num_types, sch.num_rels
+    ctx = B.Context(sch.rel_src, sch.rel_dst, T, dtype, device=-1, host_threads=2)
+    gr = ctx.hgnn_build_semantic_csr(mb.blocks)
+    gr.wait()
+    good = [64] * T
+    tdt = torch.float32 if dtype == "f32" else torch.bfloat16
+
+    def layer(dims):                                     # host tensors: the query reads no weight, only pointers
+        return B.Layer(ctx, dims, 64, True, [torch.zeros(max(dims[s], 1), 64, dtype=tdt) for s in sch.rel_src],
+                       [torch.zeros(max(d, 1), 64, dtype=tdt) for d in dims], [torch.zeros(64) for _ in dims])
+
+    saved, scratch = ctx.hgnn_layer_workspace_bytes(gr, 0, layer(good))
+    assert saved > 0 and scratch > 0
+    for t in range(T):
+        dims = list(good); dims[t] = width
+        with pytest.raises(B.HgnnError) as e:
+            ctx.hgnn_layer_workspace_bytes(gr, 0, layer(dims))
+        assert e.value.status == -6 and "in_dim[%d]=%d is not a positive multiple of %d" % (t, width, vec) in str(e.value)
+    with pytest.raises(B.HgnnError):
+        ctx.hgnn_layer_workspace_bytes(gr, 0, layer([0] + good[1:]))
+    gr.release()
+    # the merge: arguments are validated before the host-only context is refused
+    vp = C.c_void_p
+    store = (vp * T)(*[None] * T)
+    ids = (vp * T)(*[None] * T)
+    nr = (C.c_int64 * T)(*[0] * T)
+    fd = (C.c_int32 * T)(*([64] * (T - 1) + [width]))
+    ro, eo = (C.c_int32 * (T + 1))(), (C.c_int64 * (T + 1))()
+    st = B.lib.hgnn_merge_features(ctx.handle, None, store, fd, ids, nr, None, ro, eo)
+    assert st == -1 and ("feat_dim[%d]=%d is not a positive multiple of %d" % (T - 1, width, vec)).encode() in B.lib.hgnn_last_error()
+    hp = B.AdamParams(1e-3, 0.9, 0.999, 1e-8, 1)
+    st = B.lib.hgnn_adam_update_rows(ctx.handle, None, None, None, None, None, width, None, 0, None, C.byref(hp))
+    assert st == -1 and ("feat_dim=%d is not a positive multiple of %d" % (width, vec)).encode() in B.lib.hgnn_last_error()
+    ctx.close()
+
+
 # ---- sampling in the loop: the library's sampler against the sampler oracle, bit for bit ----
 def _sampler(B, ctx, g):
     return ctx.hgnn_sampler_create(g.num_nodes, g.in_indptr, g.in_nbr, g.edge_off)
