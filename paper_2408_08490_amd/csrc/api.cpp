@@ -218,6 +218,9 @@ struct AttnPlan {
   size_t s_z = 0, s_m = 0, s_t = 0, s_mx = 0, s_ls = 0, s_beta = 0, s_wsum = 0, saved_bytes = 0;
   // scratch (backward)
   size_t c_gp = 0, c_small = 0, c_du = 0, c_dm = 0, c_alpha = 0, c_ds = 0, c_dsum = 0, c_dz = 0, c_partial = 0, scratch_bytes = 0;
+  // fp32 copies of what the boundary holds in bf16 (scratch; bf16 storage only)
+  bool widen = false;
+  size_t c_x32 = 0, c_w32 = 0, c_h32 = 0, c_g32 = 0, c_dx32 = 0;
 };
 constexpr int kSemDimHost = 128;
 
@@ -230,8 +233,15 @@ static hgnn_status make_attn_plan(hgnn_ctx *ctx, hgnn_graph *g, int32_t layer, c
     HGNN_FAIL(HGNN_EINVAL, "incomplete attention layer parameters");
   const int T = ctx->T, R = ctx->R;
   const LayerHost &L = g->L[layer];
-  pl.es = esize(ctx->dtype);
-  const int vec = 16 / pl.es;
+  // The attention variant computes and keeps its intermediates (projected features, aggregates, scores, every
+  // gradient between the stages) in fp32 whatever the storage type: the gradients of the attention vectors are what
+  // is left of a cancellation between the neighbours of a vertex (the softmax gradient sums to zero over them), and
+  // the ReLU decisions sit on sums without head-room, so both need more than bf16 intermediates carry.  In bf16
+  // storage the inputs, parameters and incoming gradients are widened into scratch (exact) and the layer output and
+  // the input gradient are rounded once on the way out.
+  pl.es = 4;
+  pl.widen = ctx->dtype == HGNN_BF16;
+  const int vec = 4, vec_io = 16 / esize(ctx->dtype);
   pl.H = p->out_dim;
   pl.heads = ctx->heads;
   if (pl.H % pl.heads) HGNN_FAIL(HGNN_EINVAL, "out_dim %d is not a multiple of heads %d", pl.H, pl.heads);
@@ -247,8 +257,8 @@ static hgnn_status make_attn_plan(hgnn_ctx *ctx, hgnn_graph *g, int32_t layer, c
   pl.rt.num_rels = R;
   int64_t eo = 0;
   for (int t = 0; t < T; ++t) {
-    if (p->in_dim[t] <= 0 || p->in_dim[t] % vec != 0)
-      HGNN_FAIL(HGNN_EUNSUPPORTED, "in_dim[%d]=%d is not a positive multiple of %d", t, p->in_dim[t], vec);
+    if (p->in_dim[t] <= 0 || p->in_dim[t] % vec_io != 0)
+      HGNN_FAIL(HGNN_EUNSUPPORTED, "in_dim[%d]=%d is not a positive multiple of %d", t, p->in_dim[t], vec_io);
     if (!p->w_type[t] || ((uintptr_t)p->w_type[t] & 15)) HGNN_FAIL(HGNN_EINVAL, "w_type[%d] is NULL or not 16-byte aligned", t);
     pl.tt.in_dim[t] = p->in_dim[t];
     pl.tt.n_dst[t] = (int32_t)L.n_dst[t];
@@ -289,9 +299,68 @@ static hgnn_status make_attn_plan(hgnn_ctx *ctx, hgnn_graph *g, int32_t layer, c
   pl.c_dsum = take(o, (size_t)pl.rows * hd * 4);
   pl.c_dz = take(o, (size_t)pl.src_rows * H * es);
   pl.c_partial = take(o, (size_t)L.max_chunks * H * 4);
+  if (pl.widen) {
+    if (pl.H % vec_io) HGNN_FAIL(HGNN_EUNSUPPORTED, "out_dim %d is not a multiple of %d", pl.H, vec_io);
+    size_t wf = (size_t)2 * R * H + H * kSemDimHost + 2 * kSemDimHost;
+    for (int t = 0; t < T; ++t) wf += (size_t)p->in_dim[t] * H + H;
+    pl.c_x32 = take(o, (size_t)eo * 4);
+    pl.c_w32 = take(o, wf * 4);
+    pl.c_h32 = take(o, (size_t)pl.total_dst * H * 4);
+    pl.c_g32 = take(o, (size_t)pl.total_dst * H * 4);
+    pl.c_dx32 = take(o, (size_t)eo * 4);
+  }
   pl.scratch_bytes = o;
   if (need_built) return layer_dev(ctx, g, layer, pl.dev);
   return HGNN_OK;
+}
+
+// fp32 stand-ins of a bf16 layer's parameters and input (in the scratch area); `q` then takes the place of the
+// caller's parameter block.  Not copyable: q points into the arrays beside it.
+struct AttnWide {
+  hgnn_layer_params q;
+  const void *w_type[kMaxT], *bias[kMaxT], *a_src[kMaxR], *a_dst[kMaxR];
+  const void *x = nullptr;
+  AttnWide() = default;
+  AttnWide(const AttnWide &) = delete;
+};
+static hgnn_status attn_widen(hgnn_ctx *ctx, hipStream_t s, AttnPlan &pl, const hgnn_layer_params *p, const void *x, char *sc,
+                              AttnWide &w) {
+  const int T = ctx->T, R = ctx->R;
+  const int64_t H = pl.H;
+  std::vector<const void *> src;
+  std::vector<void *> dst;
+  std::vector<int64_t> cnt;
+  float *at = (float *)(sc + pl.c_w32);
+  auto put = [&](const void *from, int64_t n) -> const void * {
+    if (!from) return nullptr;
+    float *to = at;
+    at += n;
+    src.push_back(from); dst.push_back(to); cnt.push_back(n);
+    return to;
+  };
+  w.q = *p;
+  for (int t = 0; t < T; ++t) {
+    w.w_type[t] = put(p->w_type[t], (int64_t)p->in_dim[t] * H);
+    w.bias[t] = put(p->bias ? p->bias[t] : nullptr, H);
+    pl.pt.w_root[t] = w.w_type[t];
+    pl.pt.bias[t] = w.bias[t];
+  }
+  for (int r = 0; r < R; ++r) {
+    w.a_src[r] = put(p->a_src[r], H);
+    w.a_dst[r] = put(p->a_dst[r], H);
+  }
+  w.q.w_type = w.w_type;
+  w.q.bias = p->bias ? w.bias : nullptr;
+  w.q.a_src = w.a_src;
+  w.q.a_dst = w.a_dst;
+  w.q.w_sem = put(p->w_sem, H * kSemDimHost);
+  w.q.b_sem = put(p->b_sem, kSemDimHost);
+  w.q.q_sem = put(p->q_sem, kSemDimHost);
+  if (x && pl.tt.elem_off[T] > 0) {
+    src.push_back(x); dst.push_back(sc + pl.c_x32); cnt.push_back(pl.tt.elem_off[T]);
+    w.x = sc + pl.c_x32;
+  }
+  return launch_convert(s, true, src.data(), dst.data(), cnt.data(), (int)src.size());
 }
 
 static hgnn_status attn_fwd(hgnn_ctx *ctx, void *stream, hgnn_graph *g, int32_t layer, const hgnn_layer_params *p, const void *x,
@@ -310,6 +379,14 @@ static hgnn_status attn_fwd(hgnn_ctx *ctx, void *stream, hgnn_graph *g, int32_t 
   HGNN_HIP(hipStreamWaitEvent(s, g->ready, 0));
   char *sv = (char *)saved;
   const int T = ctx->T;
+  AttnWide wide;
+  void *h_io = h;
+  if (pl.widen) {
+    if ((st = attn_widen(ctx, s, pl, p, x, (char *)scratch, wide)) != HGNN_OK) return st;
+    p = &wide.q;
+    x = wide.x;
+    h = (char *)scratch + pl.c_h32;
+  }
   SegTab tl;   // projection tiles: every source row of every type
   std::memset(&tl, 0, sizeof(tl));
   tl.num_segs = T;
@@ -317,18 +394,24 @@ static hgnn_status attn_fwd(hgnn_ctx *ctx, void *stream, hgnn_graph *g, int32_t 
   for (int t = 0; t < T; ++t) tl.tile_off[t + 1] = tl.tile_off[t] + (int)((g->L[layer].n_src[t] + 127) / 128) * tn;
   {
     Probe pb(ctx, s, HGNN_K_GEMM_FWD, layer);
-    if ((st = launch_attn_proj(s, ctx->dtype, pl.tt, pl.pt, tl, pl.H, x, sv + pl.s_z)) != HGNN_OK) return st;
+    if ((st = launch_attn_proj(s, HGNN_F32, pl.tt, pl.pt, tl, pl.H, x, sv + pl.s_z)) != HGNN_OK) return st;
   }
   {
     Probe pb(ctx, s, HGNN_K_SPMM_FWD, layer);
-    if ((st = launch_attn_agg(s, ctx->dtype, pl.dev, pl.tt, pl.rt, p->a_src, p->a_dst, pl.H, pl.heads, sv + pl.s_z, sv + pl.s_m,
+    if ((st = launch_attn_agg(s, HGNN_F32, pl.dev, pl.tt, pl.rt, p->a_src, p->a_dst, pl.H, pl.heads, sv + pl.s_z, sv + pl.s_m,
                               (float *)(sv + pl.s_mx), (float *)(sv + pl.s_ls))) != HGNN_OK) return st;
   }
   float *wsum = (float *)(sv + pl.s_wsum), *beta = (float *)(sv + pl.s_beta);
   if ((st = launch_fill_zero(s, wsum, (size_t)kMaxR * 4)) != HGNN_OK) return st;
-  if ((st = launch_attn_sem(s, ctx->dtype, pl.dev, pl.tt, pl.rt, pl.H, sv + pl.s_m, p->w_sem, p->b_sem, p->q_sem, sv + pl.s_t, wsum)) != HGNN_OK) return st;
+  if ((st = launch_attn_sem(s, HGNN_F32, pl.dev, pl.tt, pl.rt, pl.H, sv + pl.s_m, p->w_sem, p->b_sem, p->q_sem, sv + pl.s_t, wsum)) != HGNN_OK) return st;
   if ((st = launch_attn_beta(s, pl.tt, pl.rt, wsum, beta, nullptr, nullptr, 0)) != HGNN_OK) return st;
-  return launch_attn_fuse(s, ctx->dtype, pl.dev, pl.tt, pl.rt, pl.pt, pl.H, p->relu, sv + pl.s_m, beta, h);
+  if ((st = launch_attn_fuse(s, HGNN_F32, pl.dev, pl.tt, pl.rt, pl.pt, pl.H, p->relu, sv + pl.s_m, beta, h)) != HGNN_OK) return st;
+  if (pl.widen && pl.total_dst > 0) {
+    const void *src = h;
+    const int64_t n = pl.total_dst * (int64_t)pl.H;
+    return launch_convert(s, false, &src, &h_io, &n, 1);
+  }
+  return HGNN_OK;
 }
 
 static hgnn_status attn_bwd(hgnn_ctx *ctx, void *stream, hgnn_graph *g, int32_t layer, const hgnn_layer_params *p, const void *x,
@@ -350,6 +433,21 @@ static hgnn_status attn_bwd(hgnn_ctx *ctx, void *stream, hgnn_graph *g, int32_t 
   const char *sv = (const char *)saved;
   char *sc = (char *)scratch;
   const LayerHost &L = g->L[layer];
+  AttnWide wide;
+  void *grad_x_io = grad_x;
+  if (pl.widen) {
+    if ((st = attn_widen(ctx, s, pl, p, x, sc, wide)) != HGNN_OK) return st;
+    p = &wide.q;
+    x = wide.x;
+    // incoming gradient and (for the ReLU decisions, a sign test that the rounding of the output keeps) the output
+    const void *src[2] = {grad_h, p->relu ? h_out : nullptr};
+    void *dst[2] = {sc + pl.c_g32, sc + pl.c_h32};
+    const int64_t n[2] = {pl.total_dst * (int64_t)H, p->relu ? pl.total_dst * (int64_t)H : 0};
+    if ((st = launch_convert(s, true, src, dst, n, 2)) != HGNN_OK) return st;
+    grad_h = dst[0];
+    h_out = dst[1];
+    if (grad_x) grad_x = sc + pl.c_dx32;
+  }
   float *dbeta = (float *)(sc + pl.c_small), *coef = dbeta + kMaxR;
   const float *beta = (const float *)(sv + pl.s_beta);
   // zero everything that is accumulated into
@@ -383,25 +481,25 @@ static hgnn_status attn_bwd(hgnn_ctx *ctx, void *stream, hgnn_graph *g, int32_t 
   const void *gp = grad_h;
   if (pl.total_dst > 0 && (p->relu || any_db)) {
     Probe pb(ctx, s, HGNN_K_RELU_BIAS_BWD, layer);
-    if ((st = launch_relu_bias_bwd(s, ctx->dtype, pl.tt, H, H, p->relu, grad_h, h_out, sc + pl.c_gp, gt)) != HGNN_OK) return st;
+    if ((st = launch_relu_bias_bwd(s, HGNN_F32, pl.tt, H, H, p->relu, grad_h, h_out, sc + pl.c_gp, gt)) != HGNN_OK) return st;
     if (p->relu) gp = sc + pl.c_gp;   // without an activation the pass only sums the bias gradient
   }
   // semantic-attention fusion backward
-  if ((st = launch_attn_dbeta(s, ctx->dtype, pl.dev, pl.tt, pl.rt, H, H, gp, sv + pl.s_m, dbeta)) != HGNN_OK) return st;
+  if ((st = launch_attn_dbeta(s, HGNN_F32, pl.dev, pl.tt, pl.rt, H, H, gp, sv + pl.s_m, dbeta)) != HGNN_OK) return st;
   if ((st = launch_attn_beta(s, pl.tt, pl.rt, nullptr, const_cast<float *>(beta), dbeta, coef, 1)) != HGNN_OK) return st;
-  if ((st = launch_attn_du(s, ctx->dtype, pl.dev, pl.rt, sv + pl.s_t, p->q_sem, coef, sc + pl.c_du, go->dq_sem, go->db_sem)) != HGNN_OK) return st;
+  if ((st = launch_attn_du(s, HGNN_F32, pl.dev, pl.rt, sv + pl.s_t, p->q_sem, coef, sc + pl.c_du, go->dq_sem, go->db_sem)) != HGNN_OK) return st;
   {
     Probe pb(ctx, s, HGNN_K_GEMM_DW, layer);
-    if ((st = launch_attn_dws(s, ctx->dtype, pl.rows, H, sv + pl.s_m, sc + pl.c_du, go->dw_sem)) != HGNN_OK) return st;
+    if ((st = launch_attn_dws(s, HGNN_F32, pl.rows, H, sv + pl.s_m, sc + pl.c_du, go->dw_sem)) != HGNN_OK) return st;
   }
   {
     Probe pb(ctx, s, HGNN_K_GEMM_DA, layer);
-    if ((st = launch_attn_dm(s, ctx->dtype, pl.dev, pl.tt, pl.rt, H, H, sc + pl.c_du, p->w_sem, gp, beta, sc + pl.c_dm)) != HGNN_OK) return st;
+    if ((st = launch_attn_dm(s, HGNN_F32, pl.dev, pl.tt, pl.rt, H, H, sc + pl.c_du, p->w_sem, gp, beta, sc + pl.c_dm)) != HGNN_OK) return st;
   }
   // aggregation backward
   {
     Probe pb(ctx, s, HGNN_K_SPMM_BWD, layer);
-    if ((st = launch_attn_agg_bwd(s, ctx->dtype, pl.dev, pl.tt, pl.rt, p->a_src, p->a_dst, go->da_src, go->da_dst, H, pl.heads, sv + pl.s_z,
+    if ((st = launch_attn_agg_bwd(s, HGNN_F32, pl.dev, pl.tt, pl.rt, p->a_src, p->a_dst, go->da_src, go->da_dst, H, pl.heads, sv + pl.s_z,
                                   sv + pl.s_m, sc + pl.c_dm, (const float *)(sv + pl.s_mx), (const float *)(sv + pl.s_ls),
                                   (float *)(sc + pl.c_alpha), (float *)(sc + pl.c_ds), (float *)(sc + pl.c_dsum), sc + pl.c_dz,
                                   (float *)(sc + pl.c_partial))) != HGNN_OK) return st;
@@ -441,7 +539,7 @@ static hgnn_status attn_bwd(hgnn_ctx *ctx, void *stream, hgnn_graph *g, int32_t 
     }
     for (int t = 0; t < T; ++t)
       dt.tile_off[t + 1] = dt.tile_off[t] + dt.u_total[t] * tiles_h * (int)((L.n_src[t] + split_rows - 1) / split_rows);
-    if ((st = launch_gemm_dw(s, ctx->dtype, pl.dev, tt2, rt2, gt, dt, split_rows, H, H, true, x, nullptr, sc + pl.c_dz)) != HGNN_OK) return st;
+    if ((st = launch_gemm_dw(s, HGNN_F32, pl.dev, tt2, rt2, gt, dt, split_rows, H, H, true, x, nullptr, sc + pl.c_dz)) != HGNN_OK) return st;
     if (grad_x) {
       SegTab tl;
       std::memset(&tl, 0, sizeof(tl));
@@ -455,7 +553,19 @@ static hgnn_status attn_bwd(hgnn_ctx *ctx, void *stream, hgnn_graph *g, int32_t 
         }
         tl.tile_off[sgi + 1] = tl.tile_off[sgi] + cnt;
       }
-      if ((st = launch_gemm_da(s, ctx->dtype, pl.dev, tt2, rt2, pl.pt, tl, H, true, sc + pl.c_dz, grad_x)) != HGNN_OK) return st;
+      if ((st = launch_gemm_da(s, HGNN_F32, pl.dev, tt2, rt2, pl.pt, tl, H, true, sc + pl.c_dz, grad_x)) != HGNN_OK) return st;
+      if (pl.widen) {   // round the input gradient of the wanted types into the caller's buffer
+        std::vector<const void *> src;
+        std::vector<void *> dst;
+        std::vector<int64_t> cnt;
+        for (int t = 0; t < T; ++t) {
+          if ((p->input_grad && !p->input_grad[t]) || L.n_src[t] == 0) continue;
+          src.push_back((const float *)grad_x + pl.tt.elem_off[t]);
+          dst.push_back((char *)grad_x_io + pl.tt.elem_off[t] * 2);
+          cnt.push_back(L.n_src[t] * (int64_t)p->in_dim[t]);
+        }
+        if ((st = launch_convert(s, false, src.data(), dst.data(), cnt.data(), (int)src.size())) != HGNN_OK) return st;
+      }
     }
   }
   return HGNN_OK;

@@ -368,6 +368,8 @@ hgnn_status launch_bias_reduce(hipStream_t s, const TypeTab &tt, const GradPtrTa
 // blocks of 256 threads that add up the partial bias sums: 32 columns of one type each
 inline int bias_reduce_blocks(int num_types, int H) { return num_types * ((H + 31) / 32); }
 hgnn_status launch_fill_zero(hipStream_t s, void *p, size_t bytes);
+constexpr int kCvtItems = 64;  // tensors per launch of the storage-type conversion
+hgnn_status launch_convert(hipStream_t s, bool widen, const void *const *src, void *const *dst, const int64_t *n, int count);
 hgnn_status launch_xent(hipStream_t s, int dtype, const void *logits, const int64_t *labels, int64_t rows,
                         int classes, float *loss, void *grad);
 }  // namespace hgnn

@@ -2,6 +2,7 @@
 // segmented gather-mean over the merged CSR (paper Algorithm 1, evaluated without materialising
 // the per-edge feature copies), its transpose for the backward pass, and small element-wise
 // helpers.  Every feature row is moved in 16-byte pieces by a power-of-two group of lanes.
+#include <cstring>
 #include "common.h"
 #include "bias_reduce.h"
 #include "device_types.h"
@@ -666,6 +667,55 @@ hgnn_status launch_fill_zero(hipStream_t s, void *p, size_t bytes) {
   const int blocks = (int)std::min<size_t>(2048, (n16 + 255) / 256 + 1);
   HGNN_LAUNCH(fill_zero_kernel, dim3(blocks), dim3(256), 0, s, (uint4 *)p, n16, (char *)p + n16 * 16, bytes - n16 * 16);
   HGNN_HIP(hipGetLastError());
+  return HGNN_OK;
+}
+
+// ------------------------------------------------------------------------------------------
+// Storage-type conversion of a list of tensors in one launch (blockIdx.y = tensor): bf16 -> fp32 is exact,
+// fp32 -> bf16 rounds to nearest even.  The attention variant computes in fp32 whatever the storage type is
+// and uses this at its boundary.
+struct CvtList {
+  const void *src[kCvtItems];
+  void *dst[kCvtItems];
+  int64_t n[kCvtItems];
+  int32_t count;
+};
+template <bool WIDEN>
+__global__ void __launch_bounds__(256) convert_kernel(CvtList cl) {
+  const int it = blockIdx.y;
+  if (it >= cl.count) return;
+  const int64_t n = cl.n[it];
+  const int64_t stride = (int64_t)gridDim.x * 256;
+  if constexpr (WIDEN) {
+    const bf16 *a = (const bf16 *)cl.src[it];
+    float *b = (float *)cl.dst[it];
+    for (int64_t i = (int64_t)blockIdx.x * 256 + threadIdx.x; i < n; i += stride) b[i] = to_float(a[i]);
+  } else {
+    const float *a = (const float *)cl.src[it];
+    bf16 *b = (bf16 *)cl.dst[it];
+    for (int64_t i = (int64_t)blockIdx.x * 256 + threadIdx.x; i < n; i += stride) b[i] = from_float<bf16>(a[i]);
+  }
+}
+
+hgnn_status launch_convert(hipStream_t s, bool widen, const void *const *src, void *const *dst, const int64_t *n, int count) {
+  for (int i0 = 0; i0 < count; i0 += kCvtItems) {
+    CvtList cl;
+    std::memset(&cl, 0, sizeof(cl));
+    int64_t longest = 0;
+    for (int i = i0; i < count && i < i0 + kCvtItems; ++i) {
+      if (n[i] <= 0) continue;
+      cl.src[cl.count] = src[i];
+      cl.dst[cl.count] = dst[i];
+      cl.n[cl.count] = n[i];
+      longest = std::max(longest, n[i]);
+      ++cl.count;
+    }
+    if (cl.count == 0) continue;
+    const int bx = (int)std::min<int64_t>(1024, (longest + 255) / 256);
+    if (widen) HGNN_LAUNCH(convert_kernel<true>, dim3(bx, cl.count), dim3(256), 0, s, cl);
+    else HGNN_LAUNCH(convert_kernel<false>, dim3(bx, cl.count), dim3(256), 0, s, cl);
+    HGNN_HIP(hipGetLastError());
+  }
   return HGNN_OK;
 }
 

@@ -208,7 +208,11 @@ class Model:
         b.graph.wait_stream()
 
     # ---- device side of a step ----
-    def run(self, b: Batch, backward=True, naive=False, need_input_grad=True, two_step=False):
+    def run(self, b: Batch, backward=True, naive=False, need_input_grad=True, two_step=False, layer_inputs=None,
+            layer_grads=None):
+        """layer_inputs[l] (l >= 1) / layer_grads[l]: optional device tensors that take the place of layer l's input
+        (the previous layer's output) and of its incoming gradient (the next layer's input gradient, or the loss
+        gradient): every layer then runs on given tensors instead of its neighbour's results."""
         ctx, L = self.ctx, len(self.layers)
         if b.sampled and b.ids_dev is None:
             self._resolve_sampled(b)
@@ -219,6 +223,8 @@ class Model:
         launches = []
         for l, lp in enumerate(self.layers):
             blk = b.blocks[l]
+            if layer_inputs is not None and layer_inputs[l] is not None:
+                xs[-1] = layer_inputs[l]
             sb, cb = ctx.hgnn_layer_workspace_bytes(b.graph, l, lp)
             sv = self._get(f"saved{l}", sb)
             sc = self._get("scratch", cb)
@@ -257,6 +263,8 @@ class Model:
             sb, cb = ctx.hgnn_layer_workspace_bytes(b.graph, l, lp)
             sc = self._get("scratch", cb)
             want_dx = need_input_grad or l > 0
+            if layer_grads is not None and layer_grads[l] is not None:
+                g = layer_grads[l]
             dx = self._typed(f"dx{l}", sum(n * f for n, f in zip(blk.n_src, lp.in_dim))) if want_dx else None
             if naive and not self.attention:
                 launches_bwd[l] = ctx.hgnn_layer_bwd_naive(b.graph, l, lp, xs[l], hs[l], saved[l], g, dx, sc)

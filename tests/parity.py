@@ -55,10 +55,10 @@ def prepare_inputs(index, scale=1.0, batch=None, graph=None):
 # stored in bf16 starts from values that differ by 2^-9 relative from the oracle's unrounded ones: EPS_ACT.
 EPS = {"f32": 2.0 ** -21, "bf16": 2.0 ** -16}
 EPS_ACT = {"f32": 2.0 ** -19, "bf16": 2.0 ** -8}
-# attention layer: S has no sqrt(K) head-room (its terms are the few per-relation aggregates themselves), the
-# aggregates carry the fp32 exponentials and normalisation of the neighbour softmax (fp32 storage), or are stored,
-# like the projected features they are made of, in bf16 (two roundings of 2^-9)
-EPS_ATTN = {"f32": 2.0 ** -17, "bf16": 2.0 ** -8}
+# attention layer: S has no sqrt(K) head-room (its terms are the few per-relation aggregates themselves) and the
+# aggregates carry the fp32 exponentials and normalisation of the neighbour softmax.  The kernels compute the whole
+# layer in fp32 in both storage types (bf16 inputs are widened exactly), so one bound serves both.
+EPS_ATTN = {"f32": 2.0 ** -17, "bf16": 2.0 ** -17}
 BAND_MAX_FRAC = {"f32": 1e-4, "bf16": 1e-3}    # share of a model's ReLU units that may lie inside the band
 
 
@@ -92,7 +92,48 @@ def layer_dicts(cfg, ws):
     return [dict(w_rel=lw.w_rel, w_root=lw.w_root, bias=lw.bias, relu=lw.relu) for lw in ws]
 
 
-def oracle_run(cfg, g, mb, ws, input_grad=None):
+def _layer_forward(lw, x, sel, rel_src, rel_dst, n_dst):
+    if "w_type" in lw:
+        return O.rgat_layer_forward(x, sel, rel_src, rel_dst, n_dst, lw["w_type"], lw["a_src"], lw["a_dst"], lw["w_sem"],
+                                    lw["b_sem"], lw["q_sem"], lw["bias"], lw["relu"], lw["heads"])
+    return O.rgcn_layer_forward(x, sel, rel_src, rel_dst, n_dst, lw["w_rel"], lw["w_root"], lw["bias"], lw["relu"])
+
+
+def _layer_backward(lw, cache, g, mask=None):
+    if "w_type" in lw:
+        return O.rgat_layer_backward(cache, g, mask)
+    dx, dw_rel, dw_root, dbias = O.rgcn_layer_backward(cache, g, mask)
+    return dict(dw_rel=dw_rel, dw_root=dw_root, dbias=dbias, dx=dx)
+
+
+def layerwise_oracle(res, layers, store, loss, labels, grad_out, target_type, sch, blocks_x, sels, n_dsts):
+    """Every layer on its own, on inputs both sides share: what the boundary hands from one layer to the next is a
+    tensor in the storage type, so layer l's input is the ORACLE's output of layer l-1 rounded to the storage type
+    (`store`), and its incoming gradient the oracle's input gradient of layer l+1 (of the loss for the last
+    layer), rounded likewise.  The HIP path is given exactly these tensors, layer by layer, so that no layer is
+    judged on a predecessor's rounding.  Fills res with h, caches, grads, the shared inputs x_in / g_in."""
+    x_in, hs, caches = [blocks_x], [], []
+    for l, lw in enumerate(layers):
+        h, c = _layer_forward(lw, x_in[-1], sels[l], sch.rel_src, sch.rel_dst, n_dsts[l])
+        hs.append(h); caches.append(c)
+        x_in.append([store(t) for t in h])
+    T = len(blocks_x)
+    if loss == "xent":
+        val, g_t = O.softmax_xent(hs[-1][target_type], labels)
+        g = [np.zeros_like(h) for h in hs[-1]]
+        g[target_type] = g_t
+    else:
+        g = [np.asarray(grad_out[t], dtype=np.float64) for t in range(T)]
+        val = sum(float((g[t] * hs[-1][t]).sum()) for t in range(T))
+    grads, g_in = [None] * len(layers), [None] * len(layers)
+    for l in reversed(range(len(layers))):
+        g_in[l] = [store(t) for t in g]
+        grads[l] = _layer_backward(layers[l], caches[l], g_in[l])
+        g = grads[l]["dx"]
+    res.update(h=hs, caches=caches, grads=grads, loss=val, dx0=g, x_in=x_in[:-1], g_in=g_in)
+
+
+def oracle_run(cfg, g, mb, ws, input_grad=None, layerwise=False):
     sch = g.schema
     blocks_x, _, _, flat = O.merge_features(g.stores, mb.ids)
     sels, csrs = [], []
@@ -103,9 +144,16 @@ def oracle_run(cfg, g, mb, ws, input_grad=None):
                                    transpose_types=input_grad if len(csrs) == 0 else None))
     layers = layer_dicts(cfg, ws)
     loss = "xent" if cfg.loss == "xent" else "dot"
-    res = O.rgcn_model_forward_backward(blocks_x, sels, sch.rel_src, sch.rel_dst, [b.n_dst for b in mb.blocks],
-                                        layers, loss, labels=mb.labels, grad_out=mb.grad_out,
-                                        target_type=mb.target_type)
+    if layerwise:
+        res = {}
+        store = (lambda a: bf16_round(np.asarray(a, dtype=np.float32)).astype(np.float64)) if cfg.dtype == "bf16" else \
+                (lambda a: np.asarray(a, dtype=np.float32).astype(np.float64))
+        layerwise_oracle(res, layers, store, loss, mb.labels, mb.grad_out, mb.target_type, sch, blocks_x, sels,
+                         [b.n_dst for b in mb.blocks])
+    else:
+        res = O.rgcn_model_forward_backward(blocks_x, sels, sch.rel_src, sch.rel_dst, [b.n_dst for b in mb.blocks],
+                                            layers, loss, labels=mb.labels, grad_out=mb.grad_out,
+                                            target_type=mb.target_type)
     res["csr"] = csrs
     res["sels"] = sels
     res["x0_flat"] = flat
@@ -114,14 +162,15 @@ def oracle_run(cfg, g, mb, ws, input_grad=None):
 
 def run_case(index, scale=1.0, batch=None, verbose=False, use_edge_id=True, check_naive=False, graph=None,
              input_grad=None, backward=True, cfg_edit=None, grad_tol=None, sampled=None, need_input_grad=True,
-             check_two_step=False, build_permutation=False, band_max_frac=None):
+             check_two_step=False, build_permutation=False, band_max_frac=None, layerwise=False):
     """cfg_edit(cfg, g, mb, ws): optional hook that changes the prepared inputs (e.g. the storage type) before
     both sides run.  grad_tol: optional {substring of a gradient's name: tolerance or None}; a matching
     gradient is held to that tolerance instead of the storage type's (None: reported only).  band_max_frac:
     replaces the bound on the share of ReLU units inside the decision band.
     sampled: optional dict(seed=..., fanouts=...): the mini-batch of the same targets is sampled by the library's
     sampler on the HIP side and by the sampler oracle on the other.  need_input_grad=False: the first layer's
-    backward gets no input-gradient buffer (its weight and bias gradients are still checked)."""
+    backward gets no input-gradient buffer (its weight and bias gradients are still checked).
+    layerwise=True: every layer is run and compared on inputs that both sides share (layerwise_oracle)."""
     import torch
     from paper_2408_08490_amd.runner import Model
     cfg, g, mb, ws = prepare_inputs(index, scale, batch, graph)
@@ -139,7 +188,7 @@ def run_case(index, scale=1.0, batch=None, verbose=False, use_edge_id=True, chec
         mb.ids = smb["ids"]
         mb.blocks = [Block(b["n_src"], b["n_dst"], b["edge_index"], b["edge_id"], b["edge_type"]) for b in smb["blocks"]]
     t0 = time.time()
-    ref = oracle_run(cfg, g, mb, ws, input_grad)
+    ref = oracle_run(cfg, g, mb, ws, input_grad, layerwise=layerwise)
     t_oracle = time.time() - t0
     model = Model(sch, g.feat_dim, g.stores, ws, dtype=cfg.dtype, loss=("xent" if cfg.loss == "xent" else "dot"),
                   target_type=mb.target_type, first_layer_input_grad=input_grad, build_permutation=build_permutation)
@@ -148,7 +197,13 @@ def run_case(index, scale=1.0, batch=None, verbose=False, use_edge_id=True, chec
         bt = model.prepare_sampled(sampler, targets, fanouts, sampled["seed"], labels=mb.labels, grad_out=mb.grad_out)
     else:
         bt = model.prepare(mb, g.edge_type, use_edge_id=use_edge_id)
-    out = model.run(bt, backward=backward, need_input_grad=need_input_grad)
+    inject = {}
+    if layerwise:
+        from paper_2408_08490_amd.runner import to_device
+        flat = lambda per_type: np.concatenate([np.asarray(a, dtype=np.float32).ravel() for a in per_type])
+        inject = dict(layer_inputs=[None] + [to_device(flat(x), cfg.dtype, model.dev) for x in ref["x_in"][1:]],
+                      layer_grads=[to_device(flat(x), cfg.dtype, model.dev) for x in ref["g_in"]])
+    out = model.run(bt, backward=backward, need_input_grad=need_input_grad, **inject)
     torch.cuda.synchronize()
     tol = TOL[cfg.dtype]
     report, ok = {}, True
@@ -228,7 +283,11 @@ def run_case(index, scale=1.0, batch=None, verbose=False, use_edge_id=True, chec
             ok = False
             report["relu_band" + sfx] = "MISMATCH"
         ref_tb = ref
-        if n_flip:
+        if n_flip and layerwise:
+            layers = layer_dicts(cfg, ws)
+            ref_tb = dict(grads=[_layer_backward(layers[l], ref["caches"][l], ref["g_in"][l], masks[l])
+                                 for l in range(len(ws))])
+        elif n_flip:
             layers = layer_dicts(cfg, ws)
             ref_tb = O.rgcn_model_forward_backward(None, None, sch.rel_src, sch.rel_dst, None, layers,
                                                    "xent" if cfg.loss == "xent" else "dot", labels=mb.labels,

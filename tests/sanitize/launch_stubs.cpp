@@ -73,6 +73,7 @@ hgnn_status launch_bwd_prep(hipStream_t s, int dtype, const TypeTab &tt, const R
                             const void *h, void *gp, float *bpart, size_t bpart_rows, void *wpad, int *rows_per_block) { return HGNN_EUNSUPPORTED; }
 hgnn_status launch_bias_reduce(hipStream_t s, const TypeTab &tt, const GradPtrTab &gt, int H, int rpb, const float *bpart) { return HGNN_EUNSUPPORTED; }
 hgnn_status launch_fill_zero(hipStream_t s, void *p, size_t bytes) { return HGNN_EUNSUPPORTED; }
+hgnn_status launch_convert(hipStream_t s, bool widen, const void *const *src, void *const *dst, const int64_t *n, int count) { return HGNN_EUNSUPPORTED; }
 hgnn_status launch_xent(hipStream_t s, int dtype, const void *logits, const int64_t *labels, int64_t rows,
                         int classes, float *loss, void *grad) { return HGNN_EUNSUPPORTED; }
 hgnn_status static_scratch_init(int) { return HGNN_EUNSUPPORTED; }
