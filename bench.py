@@ -63,6 +63,10 @@ def main():
     ap.add_argument("--no-ablation", action="store_true", help="leave the ablation object out")
     ap.add_argument("--cpu-sample-batch", type=int, default=4096)
     ap.add_argument("--host-threads", type=int, default=0)
+    ap.add_argument("--gather-from-stores", action="store_true",
+                    help="merge the destination rows only and let the first layer's aggregation read the feature stores "
+                         "(hgnn_layer_fwd_gather) instead of merging every source row into x_merged (hgnn_layer_fwd); the "
+                         "default line times the other one of the two in its ablation object")
     ap.add_argument("--all-input-grads", action="store_true", help="also compute gradients w.r.t. the fixed T0 features")
     ap.add_argument("--calibrate", action="store_true",
                     help="also launch the merge kernel as a plain copy of known size (2^20 rows x 128, identity ids) "
@@ -112,6 +116,10 @@ def main():
                   # T0 carries fixed input features; only the learnable embeddings of T1-T3 need input gradients
                   first_layer_input_grad=([0, 1, 1, 1] if cfg.index in (1, 2, 4) and not args.all_input_grads else None))
     ctx = model.ctx
+    # first layer: the full feature merge by default.  Reading the stores directly saves the merge's copy (~34 us on the
+    # default workload) but the gather then walks tables of GBs instead of a compact 100 MB buffer and takes ~20 us
+    # longer; with the address pass the step comes out even.
+    model.gather = args.gather_from_stores and cfg.kind != "rgat" and len(set(g.feat_dim)) == 1
 
     # inputs resident in HBM before the timed region: stores, weights, per-mini-batch id lists and labels
     class Slot:
@@ -472,8 +480,17 @@ def main():
             step_naive_ms = gpu_ms(step_naive, n_ab)
         step_merged(0)
         step_merged_ms = gpu_ms(step_merged, n_ab)
+        step_other_merge_ms = None
+        if cfg.kind != "rgat" and len(set(g.feat_dim)) == 1:
+            def step_other(i):
+                model.run(batch_of(slots[i % len(slots)], graphs[i % len(slots)]), backward=True, gather=not model.gather)
+            step_other(0)
+            step_other_merge_ms = gpu_ms(step_other, n_ab)
         abl = dict(steps_timed=n_ab, forward_merged_ms=round(merged_fwd_ms, 4),
                    step_merged_launches_ms=round(step_merged_ms, 4),
+                   first_layer_input=("destination rows merged, aggregation reads the feature stores" if model.gather
+                                      else "every source row merged"),
+                   step_other_first_layer_input_ms=None if step_other_merge_ms is None else round(step_other_merge_ms, 4),
                    step_per_relation_launches_ms=None if step_naive_ms is None else round(step_naive_ms, 4),
                    forward_per_relation_launches_ms=None if naive_fwd_ms is None else round(naive_fwd_ms, 4),
                    forward_two_step_aggregation_ms=None if two_step_fwd_ms is None else round(two_step_fwd_ms, 4),
@@ -550,6 +567,9 @@ def main():
                     (cfg.index, cfg.name, sch.num_types, sch.num_rels, cfg.batch, cfg.fanouts[::-1],
                      [g.feat_dim[0]] + cfg.layer_out, cfg.scale),
                     minibatch_sizes=sizes, distinct_minibatches=len(slots),
+                    first_layer_input=("feature merge of the destination rows; the aggregation reads the source rows in "
+                                       "the per-type feature stores (hgnn_layer_fwd_gather / hgnn_layer_bwd_gather)"
+                                       if model.gather else "feature merge of every source row (hgnn_layer_fwd / hgnn_layer_bwd)"),
                     index_build_outputs=("rowptr, colidx, cptr, crow, chunk lists" +
                                          (", perm, cperm" if args.build_permutation or attention else
                                           " (perm / cperm, which no kernel of this path reads, are left out)"))),

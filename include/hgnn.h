@@ -301,6 +301,25 @@ hgnn_status hgnn_layer_fwd_static(hgnn_ctx *ctx, void *stream, hgnn_graph *g, in
                                   const hgnn_layer_params *p, const void *x_merged, void *h_out,
                                   void *saved, size_t saved_bytes);
 
+/* The same layer with the aggregation reading its source rows where they live (Section 4.2 merges the semantic
+ * graphs' aggregation into one pass over rows picked through index lists; here the list goes all the way back to
+ * the per-type feature stores, so that the feature merge of Section 4.1 has to materialise destination rows only):
+ * store / ids are the arrays hgnn_merge_features takes (host arrays [T] of device pointers; ids[t] holds the
+ * layer's n_src[t] global ids of type t), and x_dst is what hgnn_merge_features writes when it is given
+ * n_rows[t] = n_dst[t] -- the first n_dst[t] rows of every type, type-first.  Results are those of hgnn_layer_fwd
+ * on the fully merged input, bit for bit.  Mean aggregation with one input width for all types
+ * (HGNN_EUNSUPPORTED otherwise); work areas as for hgnn_layer_fwd.  The stores must stay unchanged until the
+ * call's device work has finished.  hgnn_layer_bwd_gather is hgnn_layer_bwd for such a layer: its x_dst is that
+ * same destination-row buffer; grad_x_merged still covers every source row. */
+hgnn_status hgnn_layer_fwd_gather(hgnn_ctx *ctx, void *stream, hgnn_graph *g, int32_t layer,
+                                  const hgnn_layer_params *p, const void *const *store,
+                                  const int64_t *const *ids, const void *x_dst, void *h_out, void *saved,
+                                  size_t saved_bytes, void *scratch, size_t scratch_bytes);
+hgnn_status hgnn_layer_bwd_gather(hgnn_ctx *ctx, void *stream, hgnn_graph *g, int32_t layer,
+                                  const hgnn_layer_params *p, const void *x_dst, const void *h_out,
+                                  const void *saved, const void *grad_h, void *grad_x_merged,
+                                  const hgnn_layer_grads *g_out, void *scratch, size_t scratch_bytes);
+
 /* Attention variant (the paper evaluates R-GAT, Section 5.1; semantic fusion, Section 2.2): with a schema
  * created with agg = HGNN_AGG_ATTN and fuse = HGNN_FUSE_SEMATTN, hgnn_layer_fwd / hgnn_layer_bwd evaluate
  *   z_t = x_t W_t                                                     (H = heads * D columns)

@@ -102,6 +102,10 @@ def _load():
         "hgnn_layer_workspace_bytes": [vp, vp, i32, C.POINTER(LayerParams), C.POINTER(C.c_size_t),
                                        C.POINTER(C.c_size_t)],
         "hgnn_layer_fwd": [vp, vp, vp, i32, C.POINTER(LayerParams), vp, vp, vp, C.c_size_t, vp, C.c_size_t],
+        "hgnn_layer_fwd_gather": [vp, vp, vp, i32, C.POINTER(LayerParams), C.POINTER(vp), C.POINTER(vp), vp, vp, vp, C.c_size_t, vp,
+                                  C.c_size_t],
+        "hgnn_layer_bwd_gather": [vp, vp, vp, i32, C.POINTER(LayerParams), vp, vp, vp, vp, vp, C.POINTER(LayerGrads),
+                                  vp, C.c_size_t],
         "hgnn_layer_fwd_static": [vp, vp, vp, i32, C.POINTER(LayerParams), vp, vp, vp, C.c_size_t],
         "hgnn_layer_fwd_naive": [vp, vp, vp, i32, C.POINTER(LayerParams), vp, vp, vp, C.c_size_t, vp, C.c_size_t,
                                  C.POINTER(i32)],
@@ -132,7 +136,7 @@ def _load():
 
 lib = _load()
 
-EXPORTS = ["hgnn_create", "hgnn_destroy", "hgnn_last_error", "hgnn_merge_features", "hgnn_set_edge_types",
+EXPORTS = ["hgnn_create", "hgnn_destroy", "hgnn_last_error", "hgnn_merge_features", "hgnn_layer_fwd_gather", "hgnn_layer_bwd_gather", "hgnn_set_edge_types",
            "hgnn_build_semantic_csr", "hgnn_sampler_create", "hgnn_sampler_destroy", "hgnn_sample_and_build",
            "hgnn_graph_ids", "hgnn_graph_minibatch_view", "hgnn_graph_wait_stream",
            "hgnn_set_build_permutation", "hgnn_graph_wait", "hgnn_graph_host_view", "hgnn_graph_release", "hgnn_layer_workspace_bytes",
@@ -308,13 +312,14 @@ class Context:
             pass
 
     # ---- hgnn_merge_features ----
-    def hgnn_merge_features(self, stores, ids, x_merged, feat_dim=None):
+    def hgnn_merge_features(self, stores, ids, x_merged, feat_dim=None, n_rows=None):
+        """n_rows: rows taken from the front of every id list (default: all of them)."""
         T = self.num_types
         feat_dim = [s.shape[1] for s in stores] if feat_dim is None else feat_dim
         st = (C.c_void_p * T)(*[_ptr(s) for s in stores])
         idp = (C.c_void_p * T)(*[(_ptr(i) if i is not None and i.numel() > 0 else None) for i in ids])
         fd = (C.c_int32 * T)(*feat_dim)
-        nr = (C.c_int64 * T)(*[(0 if i is None else i.numel()) for i in ids])
+        nr = (C.c_int64 * T)(*([(0 if i is None else i.numel()) for i in ids] if n_rows is None else n_rows))
         row_off = (C.c_int32 * (T + 1))()
         elem_off = (C.c_int64 * (T + 1))()
         _check(lib.hgnn_merge_features(self.handle, _stream_ptr(self.device), st, fd, idp, nr, _ptr(x_merged), row_off, elem_off))
@@ -436,6 +441,19 @@ class Context:
         _check(lib.hgnn_layer_fwd(self.handle, _stream_ptr(self.device), graph.handle, layer, C.byref(lp.params), _ptr(x_merged),
                                   _ptr(h_out), _ptr(saved), saved.numel() * saved.element_size(), _ptr(scratch),
                                   scratch.numel() * scratch.element_size()))
+
+    def hgnn_layer_fwd_gather(self, graph, layer, lp, stores, ids, x_dst, h_out, saved, scratch):
+        T = self.num_types
+        st = (C.c_void_p * T)(*[_ptr(s) for s in stores])
+        idp = (C.c_void_p * T)(*[(_ptr(i) if i is not None and i.numel() > 0 else None) for i in ids])
+        _check(lib.hgnn_layer_fwd_gather(self.handle, _stream_ptr(self.device), graph.handle, layer, C.byref(lp.params), st, idp,
+                                         _ptr(x_dst), _ptr(h_out), _ptr(saved), saved.numel() * saved.element_size(),
+                                         _ptr(scratch), scratch.numel() * scratch.element_size()))
+
+    def hgnn_layer_bwd_gather(self, graph, layer, lp, x_dst, h_out, saved, grad_h, grad_x_merged, scratch):
+        _check(lib.hgnn_layer_bwd_gather(self.handle, _stream_ptr(self.device), graph.handle, layer, C.byref(lp.params), _ptr(x_dst),
+                                         _ptr(h_out), _ptr(saved), _ptr(grad_h), _ptr(grad_x_merged), C.byref(lp.grads),
+                                         _ptr(scratch), scratch.numel() * scratch.element_size()))
 
     def hgnn_layer_fwd_static(self, graph, layer, lp, x_merged, h_out, saved):
         _check(lib.hgnn_layer_fwd_static(self.handle, _stream_ptr(self.device), graph.handle, layer, C.byref(lp.params),

@@ -55,8 +55,18 @@ struct Plan {
   int64_t total_dst = 0;
   size_t z_elems = 0, zroot_elems = 0, wt_elems = 0;
   size_t saved_bytes = 0, scratch_bytes = 0;
-  size_t off_wt = 0, off_gp = 0, off_dz = 0, off_partial = 0, off_acc32 = 0, off_bpart = 0, bpart_rows = 0, off_zlo = 0;
+  size_t off_wt = 0, off_gp = 0, off_dz = 0, off_partial = 0, off_acc32 = 0, off_bpart = 0, bpart_rows = 0, off_zlo = 0, off_gaddr = 0;
 };
+
+// The buffer the root term reads holds the destination rows only (n_dst[t] rows per type, back to back).
+static void root_rows_only(Plan &pl) {
+  int64_t o = 0;
+  for (int t = 0; t < pl.tt.num_types; ++t) {
+    pl.tt.xroot_off[t] = o;
+    o += (int64_t)pl.tt.n_dst[t] * pl.tt.in_dim[t];
+  }
+  pl.tt.xroot_off[pl.tt.num_types] = o;
+}
 
 static hgnn_status layer_dev(hgnn_ctx *ctx, hgnn_graph *g, int32_t layer, LayerDev &D);
 
@@ -85,6 +95,7 @@ static hgnn_status make_plan(hgnn_ctx *ctx, hgnn_graph *g, int32_t layer, const 
     pl.tt.in_dim[t] = p->in_dim[t];
     pl.tt.n_dst[t] = (int32_t)L.n_dst[t];
     pl.tt.elem_off[t] = eo;
+    pl.tt.xroot_off[t] = eo;
     eo += L.n_src[t] * (int64_t)p->in_dim[t];
     pl.tt.row_off[t + 1] = pl.tt.row_off[t] + (int32_t)L.n_src[t];
     pl.tt.out_row_off[t + 1] = pl.tt.out_row_off[t] + (int32_t)L.n_dst[t];
@@ -93,6 +104,7 @@ static hgnn_status make_plan(hgnn_ctx *ctx, hgnn_graph *g, int32_t layer, const 
     pl.pt.bias[t] = p->bias ? p->bias[t] : nullptr;
   }
   pl.tt.elem_off[T] = eo;
+  pl.tt.xroot_off[T] = eo;
   pl.total_dst = pl.tt.out_row_off[T];
   if ((int64_t)pl.total_dst * pl.H >= (int64_t)1 << 40) HGNN_FAIL(HGNN_EOVERFLOW, "output too large");
   size_t z = 0, w = 0;
@@ -134,6 +146,7 @@ static hgnn_status make_plan(hgnn_ctx *ctx, hgnn_graph *g, int32_t layer, const 
   pl.bpart_rows = (size_t)pl.total_dst / (row_pass_vec ? 64 : 8) + T;
   pl.off_bpart = o;   o += align_up(pl.bpart_rows * pl.H * 4, 256);
   pl.off_zlo = o;     o += (pl.es == 2 && p->relu) ? align_up(std::max<size_t>(z, 1) * pl.es, 256) : 0;
+  pl.off_gaddr = o;   o += align_up(std::max<size_t>((size_t)L.edges, 1) * 8, 256);  // per-edge row addresses (gather from the stores)
   pl.scratch_bytes = o;
   if (need_built) {
     hgnn_status st = layer_dev(ctx, g, layer, pl.dev);
@@ -263,6 +276,7 @@ static hgnn_status make_attn_plan(hgnn_ctx *ctx, hgnn_graph *g, int32_t layer, c
     pl.tt.in_dim[t] = p->in_dim[t];
     pl.tt.n_dst[t] = (int32_t)L.n_dst[t];
     pl.tt.elem_off[t] = eo;
+    pl.tt.xroot_off[t] = eo;
     eo += L.n_src[t] * (int64_t)p->in_dim[t];
     pl.tt.row_off[t + 1] = pl.tt.row_off[t] + (int32_t)L.n_src[t];
     pl.tt.out_row_off[t + 1] = pl.tt.out_row_off[t] + (int32_t)L.n_dst[t];
@@ -585,7 +599,7 @@ static int fwd_tiles(const Plan &pl, SegTab &tl, bool allow_small) {
     const int tn = (pl.H + mn - 1) / mn;
     for (int t = 0; t < T; ++t) tl.tile_off[t + 1] = tl.tile_off[t] + ((pl.tt.n_dst[t] + mn - 1) / mn) * tn;
     tl.num_segs = T;
-    if (mn == 64 || !allow_small || tl.tile_off[T] >= kSmallTileLimit) return mn;
+    if (mn == 64 || !allow_small || (tl.tile_off[T] >= kSmallTileLimit && !getenv("HGNN_EXP_SMALL"))) return mn;
   }
 }
 
@@ -1057,11 +1071,28 @@ hgnn_status hgnn_layer_workspace_bytes(hgnn_ctx *ctx, hgnn_graph *g, int32_t lay
 static hgnn_status fwd_common(hgnn_ctx *ctx, void *stream, hgnn_graph *g, int32_t layer, const hgnn_layer_params *p,
                               const void *x, void *h, void *saved, size_t saved_bytes, void *scratch, size_t scratch_bytes,
                               bool naive, int32_t *launches, void *feature_cat = nullptr, size_t feature_cat_bytes = 0,
-                              bool static_area = false) {
+                              bool static_area = false, const void *const *gather_store = nullptr,
+                              const int64_t *const *gather_ids = nullptr) {
   Plan pl;
   hgnn_status st = make_plan(ctx, g, layer, p, pl, true);
   if (st != HGNN_OK) return st;
   if (pl.total_dst > 0 && (!x || !h)) HGNN_FAIL(HGNN_EINVAL, "x_merged or h_out is NULL");
+  GatherSrc gs;
+  if (gather_store) {
+    // source rows are read where they live: x holds the destination rows only
+    std::memset(&gs, 0, sizeof(gs));
+    gs.num_types = ctx->T;
+    for (int t = 0; t < ctx->T; ++t) {
+      if (p->in_dim[t] != p->in_dim[0]) HGNN_FAIL(HGNN_EUNSUPPORTED, "gathering from the stores needs one input width for all types");
+      gs.row_off[t + 1] = pl.tt.row_off[t + 1];
+      if (g->L[layer].n_src[t] > 0 && (!gather_store[t] || !gather_ids || !gather_ids[t]))
+        HGNN_FAIL(HGNN_EINVAL, "type %d has source rows but a NULL store or id list", t);
+      if ((uintptr_t)gather_store[t] & 15) HGNN_FAIL(HGNN_EINVAL, "feature stores must be 16-byte aligned");
+      gs.store[t] = gather_store[t];
+      gs.ids[t] = gather_ids[t];
+    }
+    root_rows_only(pl);
+  }
   if (!saved || !scratch) HGNN_FAIL(HGNN_EINVAL, "NULL work area");
   if (static_area) {
     // the forward's own part of the work area, laid out back to back: transposed weights, low-order plane
@@ -1112,9 +1143,22 @@ static hgnn_status fwd_common(hgnn_ctx *ctx, void *stream, hgnn_graph *g, int32_
       if ((st = launch_aggregate_literal(s, ctx->dtype, pl.dev, p->in_dim[0], x, feature_cat, saved, zlo)) != HGNN_OK) return st;
       n += (pl.dev.edges > 0) + (pl.dev.rows > 0);
     } else {
-      Probe pb(ctx, s, HGNN_K_SPMM_FWD, layer, !static_area);
-      if ((st = launch_spmm_fwd(s, ctx->dtype, pl.dev, pl.tt, pl.rt, pl.max_dim, x, saved, zlo, 0, pl.dev.rows)) != HGNN_OK) return st;
-      if (pl.dev.rows > 0) ++n;
+      if (gather_store) {
+        uint64_t *gaddr = (uint64_t *)(sc + pl.off_gaddr);
+        if ((st = launch_gather_addresses(s, pl.dev, gs, p->in_dim[0] * pl.es, gaddr)) != HGNN_OK) return st;
+        if (pl.dev.edges > 0) ++n;
+        Probe pb(ctx, s, HGNN_K_SPMM_FWD, layer);
+        if (pl.dev.rows > 0) {
+          if (!launch_spmm_fwd_uniform(s, ctx->dtype, pl.dev, p->in_dim[0], nullptr, saved, zlo, 0, pl.dev.rows, gaddr))
+            HGNN_FAIL(HGNN_EUNSUPPORTED, "input width %d is outside what the gather kernels cover", p->in_dim[0]);
+          HGNN_HIP(hipGetLastError());
+          ++n;
+        }
+      } else {
+        Probe pb(ctx, s, HGNN_K_SPMM_FWD, layer, !static_area);
+        if ((st = launch_spmm_fwd(s, ctx->dtype, pl.dev, pl.tt, pl.rt, pl.max_dim, x, saved, zlo, 0, pl.dev.rows)) != HGNN_OK) return st;
+        if (pl.dev.rows > 0) ++n;
+      }
     }
     {
       Probe pb(ctx, s, HGNN_K_GEMM_FWD, layer, !static_area);
@@ -1184,6 +1228,15 @@ hgnn_status hgnn_layer_fwd(hgnn_ctx *ctx, void *stream, hgnn_graph *g, int32_t l
   return fwd_common(ctx, stream, g, layer, p, x_merged, h_out, saved, saved_bytes, scratch, scratch_bytes, false, nullptr);
 }
 
+hgnn_status hgnn_layer_fwd_gather(hgnn_ctx *ctx, void *stream, hgnn_graph *g, int32_t layer, const hgnn_layer_params *p,
+                                  const void *const *store, const int64_t *const *ids, const void *x_dst, void *h_out,
+                                  void *saved, size_t saved_bytes, void *scratch, size_t scratch_bytes) {
+  if (!ctx || !store || !ids) HGNN_FAIL(HGNN_EINVAL, "NULL argument");
+  if (ctx->agg == HGNN_AGG_ATTN) HGNN_FAIL(HGNN_EUNSUPPORTED, "hgnn_layer_fwd_gather covers the mean-aggregation layer only");
+  return fwd_common(ctx, stream, g, layer, p, x_dst, h_out, saved, saved_bytes, scratch, scratch_bytes, false, nullptr, nullptr, 0,
+                    false, store, ids);
+}
+
 hgnn_status hgnn_layer_fwd_naive(hgnn_ctx *ctx, void *stream, hgnn_graph *g, int32_t layer, const hgnn_layer_params *p,
                                  const void *x_merged, void *h_out, void *saved, size_t saved_bytes, void *scratch,
                                  size_t scratch_bytes, int32_t *launches) {
@@ -1217,7 +1270,7 @@ static void seg_tiles_da(hgnn_ctx *ctx, const Plan &pl, const hgnn_layer_params 
 static hgnn_status bwd_common(hgnn_ctx *ctx, void *stream, hgnn_graph *g, int32_t layer, const hgnn_layer_params *p,
                               const void *x_merged, const void *h_out, const void *saved, const void *grad_h,
                               void *grad_x_merged, const hgnn_layer_grads *go, void *scratch, size_t scratch_bytes, bool naive,
-                              int32_t *launches) {
+                              int32_t *launches, bool x_dst_only = false) {
   if (launches) *launches = 0;
   if (ctx && ctx->agg == HGNN_AGG_ATTN) {
     if (naive) HGNN_FAIL(HGNN_EUNSUPPORTED, "the per-relation launch loop exists for the mean-aggregation layer only");
@@ -1226,6 +1279,7 @@ static hgnn_status bwd_common(hgnn_ctx *ctx, void *stream, hgnn_graph *g, int32_
   Plan pl;
   hgnn_status st = make_plan(ctx, g, layer, p, pl, true);
   if (st != HGNN_OK) return st;
+  if (x_dst_only) root_rows_only(pl);
   if (!saved || !scratch || !go) HGNN_FAIL(HGNN_EINVAL, "NULL work area or gradient table");
   if (pl.total_dst > 0 && (!x_merged || !grad_h || (p->relu && !h_out))) HGNN_FAIL(HGNN_EINVAL, "NULL input");
   if (scratch_bytes < pl.scratch_bytes) HGNN_FAIL(HGNN_EINVAL, "scratch too small: need %zu bytes", pl.scratch_bytes);
@@ -1448,6 +1502,13 @@ hgnn_status hgnn_layer_bwd(hgnn_ctx *ctx, void *stream, hgnn_graph *g, int32_t l
                            const void *x_merged, const void *h_out, const void *saved, const void *grad_h,
                            void *grad_x_merged, const hgnn_layer_grads *go, void *scratch, size_t scratch_bytes) {
   return bwd_common(ctx, stream, g, layer, p, x_merged, h_out, saved, grad_h, grad_x_merged, go, scratch, scratch_bytes, false, nullptr);
+}
+
+hgnn_status hgnn_layer_bwd_gather(hgnn_ctx *ctx, void *stream, hgnn_graph *g, int32_t layer, const hgnn_layer_params *p,
+                                  const void *x_dst, const void *h_out, const void *saved, const void *grad_h,
+                                  void *grad_x_merged, const hgnn_layer_grads *go, void *scratch, size_t scratch_bytes) {
+  if (ctx && ctx->agg == HGNN_AGG_ATTN) HGNN_FAIL(HGNN_EUNSUPPORTED, "hgnn_layer_bwd_gather covers the mean-aggregation layer only");
+  return bwd_common(ctx, stream, g, layer, p, x_dst, h_out, saved, grad_h, grad_x_merged, go, scratch, scratch_bytes, false, nullptr, true);
 }
 
 hgnn_status hgnn_layer_bwd_naive(hgnn_ctx *ctx, void *stream, hgnn_graph *g, int32_t layer, const hgnn_layer_params *p,

@@ -54,6 +54,8 @@ bool probe_take_events(hipEvent_t *start, hipEvent_t *stop);
 // ---------------------------------------------------------------------------------------------
 struct TypeTab {
   int64_t elem_off[kMaxT + 1];     // scalars of x_merged before type t (source rows)
+  int64_t xroot_off[kMaxT + 1];    // scalars before type t's destination rows in the buffer the root term reads
+                                   // (= elem_off for x_merged; destination rows back to back for a buffer that holds only those)
   int32_t in_dim[kMaxT];
   int32_t n_dst[kMaxT];
   int32_t row_off[kMaxT + 1];      // source rows before type t
@@ -295,7 +297,17 @@ hgnn_status launch_spmm_bwd(hipStream_t s, int dtype, const LayerDev &L, const T
                             const PtrTab &pt, int max_dim, uint32_t want_types, const void *dz, void *dx, float *partial);
 // uniform feature width: return false when the width is outside what they cover (caller falls back)
 bool launch_spmm_fwd_uniform(hipStream_t s, int dtype, const LayerDev &L, int F, const void *x, void *z, void *zlo,
-                             int row_begin, int row_end);
+                             int row_begin, int row_end, const uint64_t *gaddr = nullptr);
+// Aggregation straight from the per-type feature stores: gaddr[e] = address of the row that edge e reads (the row
+// ids[t][c - row_off[t]] of store t for the merged source row c = colidx[e]); launch_spmm_fwd_uniform then takes
+// gaddr in place of x.
+struct GatherSrc {
+  const void *store[kMaxT];
+  const int64_t *ids[kMaxT];
+  int32_t row_off[kMaxT + 1];
+  int32_t num_types;
+};
+hgnn_status launch_gather_addresses(hipStream_t s, const LayerDev &L, const GatherSrc &gs, int row_bytes, uint64_t *gaddr);
 bool launch_spmm_bwd_uniform(hipStream_t s, int dtype, const LayerDev &L, const TypeTab &tt, const RelTab &rt, const PtrTab &pt,
                              int F, uint32_t want, const void *dz, void *dx, float *partial);
 hgnn_status launch_transpose_weights(hipStream_t s, int dtype, const TypeTab &tt, const RelTab &rt,

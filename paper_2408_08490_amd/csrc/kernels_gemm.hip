@@ -65,7 +65,7 @@ __global__ void __launch_bounds__(kThreads, MI == 1 ? 4 : 2) gemm_fwd_kernel(Typ
         int n = __popcll(m) * mult;
         if (cursor + kRelWindow >= R && pt.w_root[d] && (only_seg < 0 || only_seg == R + d)) {
           const int F = tt.in_dim[d];
-          put_seg(sm.seg[n++], x + tt.elem_off[d], F, wtb + (int64_t)wt.root4[d] * 4, F, 0, F);
+          put_seg(sm.seg[n++], x + tt.xroot_off[d], F, wtb + (int64_t)wt.root4[d] * 4, F, 0, F);
         }
         s_nseg = n;
       }
@@ -241,7 +241,7 @@ __device__ __forceinline__ void dw_tile(GemmLds<T, MI, MI> &sm, int bid, const T
   f32x16 acc[MI][MI];
   zero_acc(acc);
   if (threadIdx.x == 0)
-    put_seg(sm.seg[0], is_rel ? z + (int64_t)rt.z_off4[seg] * 4 : x + tt.elem_off[d], F,
+    put_seg(sm.seg[0], is_rel ? z + (int64_t)rt.z_off4[seg] * 4 : x + tt.xroot_off[d], F,
             gp + (int64_t)tt.out_row_off[d] * ldg, ldg, k_begin, k_end);
   __syncthreads();
   gemm_run<T, FAST, false, false>(acc, sm, 1, F, f0, ldg, h0);

@@ -71,7 +71,7 @@ __global__ void __launch_bounds__(dma::kThreads, S == 2 ? 2 : 1) gemm2_fwd_kerne
       }
       if (lane == 0 && pt.w_root[d]) {
         const int F = tt.in_dim[d];
-        put_seg(sm.seg[pos0 + cnt * mult], x + tt.elem_off[d], F, wtb + (int64_t)wt.root4[d] * 4, F, 0, F);
+        put_seg(sm.seg[pos0 + cnt * mult], x + tt.xroot_off[d], F, wtb + (int64_t)wt.root4[d] * 4, F, 0, F);
       }
     }
   }

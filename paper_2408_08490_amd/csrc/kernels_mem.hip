@@ -764,7 +764,9 @@ hgnn_status launch_bias_act(hipStream_t s, int dtype, const TypeTab &tt, const P
 // ------------------------------------------------------------------------------------------
 // Mean softmax cross-entropy and its gradient; one wavefront per row.
 // ------------------------------------------------------------------------------------------
-template <typename T>
+// V = values a lane keeps (C <= 64 V): the row is read once, into registers, and the label with it, so a row costs one
+// memory round trip; V = 0 is the form for any C, which re-reads the row for each of its three passes.
+template <typename T, int V>
 __global__ void __launch_bounds__(256) xent_kernel(const T *__restrict__ logits, const int64_t *__restrict__ labels,
                                                     int64_t rows, int C, float *loss, T *__restrict__ grad) {
   __shared__ float part[4];
@@ -773,24 +775,71 @@ __global__ void __launch_bounds__(256) xent_kernel(const T *__restrict__ logits,
   float my_loss = 0.f;
   for (int64_t row = (int64_t)blockIdx.x * 4 + wave; row < rows; row += (int64_t)gridDim.x * 4) {
     const T *z = logits + row * C;
-    float m = -INFINITY;
-    for (int c = lane; c < C; c += 64) m = fmaxf(m, to_float(z[c]));
-    for (int o = 32; o > 0; o >>= 1) m = fmaxf(m, __shfl_xor(m, o));
-    float sum = 0.f;
-    for (int c = lane; c < C; c += 64) sum += __expf(to_float(z[c]) - m);
-    for (int o = 32; o > 0; o >>= 1) sum += __shfl_xor(sum, o);
     const int lab = (int)labels[row];
-    const float inv_sum = 1.0f / sum;
-    for (int c = lane; c < C; c += 64) {
-      float p = __expf(to_float(z[c]) - m) * inv_sum;
-      if (c == lab) p -= 1.0f;
-      grad[row * C + c] = from_float<T>(p * inv_rows);
+    if constexpr (V > 0) {
+      float x[V];
+#pragma unroll
+      for (int i = 0; i < V; ++i) {
+        const int c = lane + 64 * i;
+        x[i] = c < C ? to_float(z[c]) : -INFINITY;
+      }
+      float m = x[0];
+#pragma unroll
+      for (int i = 1; i < V; ++i) m = fmaxf(m, x[i]);
+      for (int o = 32; o > 0; o >>= 1) m = fmaxf(m, __shfl_xor(m, o));
+      float sum = 0.f, zl = 0.f;
+#pragma unroll
+      for (int i = 0; i < V; ++i) {
+        if (lane + 64 * i == lab) zl = x[i];
+        x[i] = __expf(x[i] - m);   // exp(-inf) = 0 beyond the row
+        sum += x[i];
+      }
+      for (int o = 32; o > 0; o >>= 1) {
+        sum += __shfl_xor(sum, o);
+        zl += __shfl_xor(zl, o);
+      }
+      const float inv_sum = 1.0f / sum;
+#pragma unroll
+      for (int i = 0; i < V; ++i) {
+        const int c = lane + 64 * i;
+        float p = x[i] * inv_sum;
+        if (c == lab) p -= 1.0f;
+        if (c < C) grad[row * C + c] = from_float<T>(p * inv_rows);
+      }
+      my_loss += (logf(sum) + m - zl) * inv_rows;
+    } else {
+      float m = -INFINITY;
+      for (int c = lane; c < C; c += 64) m = fmaxf(m, to_float(z[c]));
+      for (int o = 32; o > 0; o >>= 1) m = fmaxf(m, __shfl_xor(m, o));
+      float sum = 0.f;
+      for (int c = lane; c < C; c += 64) sum += __expf(to_float(z[c]) - m);
+      for (int o = 32; o > 0; o >>= 1) sum += __shfl_xor(sum, o);
+      const float inv_sum = 1.0f / sum;
+      for (int c = lane; c < C; c += 64) {
+        float p = __expf(to_float(z[c]) - m) * inv_sum;
+        if (c == lab) p -= 1.0f;
+        grad[row * C + c] = from_float<T>(p * inv_rows);
+      }
+      my_loss += (logf(sum) + m - to_float(z[lab])) * inv_rows;
     }
-    my_loss += (logf(sum) + m - to_float(z[lab])) * inv_rows;
   }
   if (lane == 0) part[wave] = my_loss;
   __syncthreads();
   if (threadIdx.x == 0) atomicAdd(loss, part[0] + part[1] + part[2] + part[3]);
+}
+
+template <typename T>
+static void launch_xent_typed(hipStream_t s, const void *logits, const int64_t *labels, int64_t rows, int C, float *loss, void *grad) {
+  // one wavefront per row while that gives at most 8192 blocks (more rows: several per wavefront)
+  dim3 grid((unsigned)std::min<int64_t>(8192, (rows + 3) / 4));
+#define HGNN_XENT(V_) HGNN_LAUNCH((xent_kernel<T, V_>), grid, dim3(256), 0, s, (const T *)logits, labels, rows, C, loss, (T *)grad)
+  if (C <= 128) HGNN_XENT(2);
+  else if (C <= 256) HGNN_XENT(4);
+  else if (C <= 384) HGNN_XENT(6);
+  else if (C <= 512) HGNN_XENT(8);
+  else if (C <= 1024) HGNN_XENT(16);
+  else HGNN_XENT(0);
+#undef HGNN_XENT
 }
 
 hgnn_status launch_xent(hipStream_t s, int dtype, const void *logits, const int64_t *labels, int64_t rows,
@@ -798,11 +847,8 @@ hgnn_status launch_xent(hipStream_t s, int dtype, const void *logits, const int6
   hgnn_status st = launch_fill_zero(s, loss, sizeof(float));
   if (st != HGNN_OK) return st;
   if (rows == 0) return HGNN_OK;
-  dim3 grid((unsigned)std::min<int64_t>(512, (rows + 3) / 4));
-  if (dtype == HGNN_BF16)
-    HGNN_LAUNCH(xent_kernel<bf16>, grid, dim3(256), 0, s, (const bf16 *)logits, labels, rows, classes, loss, (bf16 *)grad);
-  else
-    HGNN_LAUNCH(xent_kernel<float>, grid, dim3(256), 0, s, (const float *)logits, labels, rows, classes, loss, (float *)grad);
+  if (dtype == HGNN_BF16) launch_xent_typed<bf16>(s, logits, labels, rows, classes, loss, grad);
+  else launch_xent_typed<float>(s, logits, labels, rows, classes, loss, grad);
   HGNN_HIP(hipGetLastError());
   return HGNN_OK;
 }

@@ -9,6 +9,8 @@
 // loads, and hands the indices to the lanes that need them through cross-lane reads.  All feature-row
 // loads of up to four edges are then in flight together.  Dependent round trips per wave: row pointers,
 // indices, features -- three, however many rows and edges it owns.
+#include <type_traits>
+
 #include "common.h"
 #include "device_types.h"
 
@@ -21,11 +23,23 @@ __device__ __forceinline__ int wave_col(int c0, int c1, int rel) {
   return r < 64 ? a : b;
 }
 
-template <typename T, int LPRL, int C>
+// Source of wave-relative edge `rel` when the edges carry row ADDRESSES (two 64-bit index registers).
+__device__ __forceinline__ unsigned long long wave_addr(unsigned long long c0, unsigned long long c1, int rel) {
+  const int r = min(max(rel, 0), 127);
+  const unsigned long long a = __shfl(c0, r & 63), b = __shfl(c1, r & 63);
+  return r < 64 ? a : b;
+}
+
+// ADDR = false: `colidx` holds rows of x.  ADDR = true: `colidx` is unused and `gaddr` holds, per edge, the device
+// address of the source row (in whichever per-type feature store it lives), so that no merged copy of the source
+// rows is needed.
+template <typename T, int LPRL, int C, bool ADDR>
 __global__ void __launch_bounds__(256) spmm_fwd_uniform_kernel(const int32_t *__restrict__ rowptr, const int32_t *__restrict__ colidx,
+                                                                const unsigned long long *__restrict__ gaddr,
                                                                 const T *__restrict__ x, T *__restrict__ z, T *__restrict__ zlo,
                                                                 int F, int row_begin, int row_end) {
   using V = Vec16<T>;
+  using Idx = std::conditional_t<ADDR, unsigned long long, int>;
   constexpr int LPR = 1 << LPRL, RPW = 64 / LPR;
   const int lane = threadIdx.x & 63;
   const int row0 = row_begin + (blockIdx.x * 4 + (threadIdx.x >> 6)) * RPW;
@@ -33,8 +47,14 @@ __global__ void __launch_bounds__(256) spmm_fwd_uniform_kernel(const int32_t *__
   const int nrows = min(RPW, row_end - row0);
   const int rp = rowptr[row0 + min(lane, nrows)];
   const int e0 = __shfl(rp, 0), eN = __shfl(rp, nrows);
-  const int c0 = e0 + lane < eN ? colidx[e0 + lane] : 0;
-  const int c1 = e0 + 64 + lane < eN ? colidx[e0 + 64 + lane] : 0;
+  Idx c0 = 0, c1 = 0;
+  if constexpr (ADDR) {
+    if (e0 + lane < eN) c0 = gaddr[e0 + lane];
+    if (e0 + 64 + lane < eN) c1 = gaddr[e0 + 64 + lane];
+  } else {
+    if (e0 + lane < eN) c0 = colidx[e0 + lane];
+    if (e0 + 64 + lane < eN) c1 = colidx[e0 + 64 + lane];
+  }
   const int g = lane >> LPRL, sub = lane & (LPR - 1);
   const int beg = __shfl(rp, min(g, nrows)), end = __shfl(rp, min(g + 1, nrows));
   const int len = end - beg;
@@ -49,19 +69,28 @@ __global__ void __launch_bounds__(256) spmm_fwd_uniform_kernel(const int32_t *__
 #pragma unroll
     for (int i = 0; i < V::N; ++i) acc[p][i] = 0.f;
   for (int i = 0; i < maxlen; i += 4) {  // same trip count for every lane: the cross-lane reads need all lanes
-    int col[4];
+    Idx col[4];
 #pragma unroll
-    for (int j = 0; j < 4; ++j) col[j] = wave_col(c0, c1, beg - e0 + i + j);
+    for (int j = 0; j < 4; ++j) {
+      if constexpr (ADDR) col[j] = wave_addr(c0, c1, beg - e0 + i + j);
+      else col[j] = wave_col(c0, c1, beg - e0 + i + j);
+    }
     uint4 v[4][C];
 #pragma unroll
     for (int j = 0; j < 4; ++j) {
       const bool on = i + j < len;
-      int cj = col[j];
-      if (on && beg - e0 + i + j >= 128) cj = colidx[beg + i + j];  // beyond the two index registers
+      Idx cj = col[j];
+      if (on && beg - e0 + i + j >= 128) {  // beyond the two index registers
+        if constexpr (ADDR) cj = gaddr[beg + i + j];
+        else cj = colidx[beg + i + j];
+      }
 #pragma unroll
       for (int p = 0; p < C; ++p) {
         const int q = sub + p * LPR;
-        v[j][p] = (on && q < nvec) ? xb[(int64_t)cj * nvec + q] : make_uint4(0, 0, 0, 0);
+        if constexpr (ADDR)
+          v[j][p] = (on && q < nvec) ? reinterpret_cast<const uint4 *>(cj)[q] : make_uint4(0, 0, 0, 0);
+        else
+          v[j][p] = (on && q < nvec) ? xb[(int64_t)cj * nvec + q] : make_uint4(0, 0, 0, 0);
       }
     }
 #pragma unroll
@@ -85,11 +114,16 @@ __global__ void __launch_bounds__(256) spmm_fwd_uniform_kernel(const int32_t *__
 }
 
 template <typename T, int LPRL, int C>
-static void launch_fwd_uniform(hipStream_t s, const LayerDev &L, const void *x, void *z, void *zlo, int F, int row_begin, int row_end) {
+static void launch_fwd_uniform(hipStream_t s, const LayerDev &L, const void *x, const unsigned long long *gaddr, void *z, void *zlo, int F,
+                               int row_begin, int row_end) {
   constexpr int RPB = 4 * (64 >> LPRL);
   dim3 grid((row_end - row_begin + RPB - 1) / RPB);
-  HGNN_LAUNCH((spmm_fwd_uniform_kernel<T, LPRL, C>), grid, dim3(256), 0, s, L.rowptr, L.colidx, (const T *)x, (T *)z,
-                     (T *)zlo, F, row_begin, row_end);
+  if (gaddr)
+    HGNN_LAUNCH((spmm_fwd_uniform_kernel<T, LPRL, C, true>), grid, dim3(256), 0, s, L.rowptr, L.colidx, gaddr, (const T *)x, (T *)z,
+                (T *)zlo, F, row_begin, row_end);
+  else
+    HGNN_LAUNCH((spmm_fwd_uniform_kernel<T, LPRL, C, false>), grid, dim3(256), 0, s, L.rowptr, L.colidx, gaddr, (const T *)x, (T *)z,
+                (T *)zlo, F, row_begin, row_end);
 }
 
 // Returns false when the shape is outside what the uniform kernels cover (the generic kernels then run).
@@ -115,12 +149,34 @@ template <typename T, bool FWD, typename FN> static bool dispatch_width(int nvec
 }
 
 bool launch_spmm_fwd_uniform(hipStream_t s, int dtype, const LayerDev &L, int F, const void *x, void *z, void *zlo,
-                             int row_begin, int row_end) {
+                             int row_begin, int row_end, const uint64_t *gaddr) {
   const int es = dtype == HGNN_BF16 ? 2 : 4;
   const int nvec = F * es / 16;
+  const unsigned long long *ga = reinterpret_cast<const unsigned long long *>(gaddr);
   if (dtype == HGNN_BF16)
-    return dispatch_width<bf16, true>(nvec, [&]<int LPRL, int C>() { launch_fwd_uniform<bf16, LPRL, C>(s, L, x, z, zlo, F, row_begin, row_end); });
-  return dispatch_width<float, true>(nvec, [&]<int LPRL, int C>() { launch_fwd_uniform<float, LPRL, C>(s, L, x, z, zlo, F, row_begin, row_end); });
+    return dispatch_width<bf16, true>(nvec, [&]<int LPRL, int C>() { launch_fwd_uniform<bf16, LPRL, C>(s, L, x, ga, z, zlo, F, row_begin, row_end); });
+  return dispatch_width<float, true>(nvec, [&]<int LPRL, int C>() { launch_fwd_uniform<float, LPRL, C>(s, L, x, ga, z, zlo, F, row_begin, row_end); });
+}
+
+// gaddr[e] = address of the feature row that edge e reads: the row ids[t][c - row_off[t]] of store t, for the
+// merged source row c = colidx[e] and its vertex type t.
+__global__ void __launch_bounds__(256) gather_address_kernel(const int32_t *__restrict__ colidx, int edges, GatherSrc gs, int row_bytes,
+                                                              unsigned long long *__restrict__ gaddr) {
+  const int e = blockIdx.x * 256 + threadIdx.x;
+  if (e >= edges) return;
+  const int c = colidx[e];
+  int t = 0;
+  while (t + 1 < gs.num_types && c >= gs.row_off[t + 1]) ++t;
+  const long long id = gs.ids[t][c - gs.row_off[t]];
+  gaddr[e] = reinterpret_cast<unsigned long long>(gs.store[t]) + (unsigned long long)id * (unsigned long long)row_bytes;
+}
+
+hgnn_status launch_gather_addresses(hipStream_t s, const LayerDev &L, const GatherSrc &gs, int row_bytes, uint64_t *gaddr) {
+  if (L.edges == 0) return HGNN_OK;
+  HGNN_LAUNCH(gather_address_kernel, dim3((L.edges + 255) / 256), dim3(256), 0, s, L.colidx, L.edges, gs, row_bytes,
+              reinterpret_cast<unsigned long long *>(gaddr));
+  HGNN_HIP(hipGetLastError());
+  return HGNN_OK;
 }
 
 // ------------------------------------------------------------------------------------------

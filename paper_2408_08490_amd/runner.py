@@ -106,6 +106,8 @@ class Model:
                                        input_grad=first_layer_input_grad if not self.layers else None))
         self.loss_dev = torch.zeros(1, device=self.dev, dtype=torch.float32)
         self._buf = {}
+        # default of run(gather=...): the first layer's aggregation reads the feature stores directly
+        self.gather = False
 
     # ---- training: fp32 master copies and Adam moments of every weight and of the learnable embedding tables ----
     def enable_training(self, lr=1e-2, beta1=0.9, beta2=0.999, eps=1e-8, learnable_types=None):
@@ -209,16 +211,26 @@ class Model:
 
     # ---- device side of a step ----
     def run(self, b: Batch, backward=True, naive=False, need_input_grad=True, two_step=False, layer_inputs=None,
-            layer_grads=None):
-        """layer_inputs[l] (l >= 1) / layer_grads[l]: optional device tensors that take the place of layer l's input
+            layer_grads=None, gather=None):
+        """gather=True: the first layer's aggregation reads the feature stores directly (hgnn_layer_fwd_gather) and the
+        feature merge copies the destination rows only.
+        layer_inputs[l] (l >= 1) / layer_grads[l]: optional device tensors that take the place of layer l's input
         (the previous layer's output) and of its incoming gradient (the next layer's input gradient, or the loss
         gradient): every layer then runs on given tensors instead of its neighbour's results."""
         ctx, L = self.ctx, len(self.layers)
+        gather = self.gather if gather is None else gather
+        # the per-relation launch loop and the two-step aggregation read the fully merged input
+        gather = bool(gather) and not naive and not two_step and not self.attention
         if b.sampled and b.ids_dev is None:
             self._resolve_sampled(b)
-        n0 = sum(n * f for n, f in zip(b.n_rows, self.feat_dim))
-        x = self._typed("x0", n0)
-        row_off, elem_off = ctx.hgnn_merge_features(self.stores, b.ids_dev, x, self.feat_dim)
+        if gather:
+            nd0 = list(b.blocks[0].n_dst)
+            x = self._typed("x0dst", sum(n * f for n, f in zip(nd0, self.feat_dim)))
+            row_off, elem_off = ctx.hgnn_merge_features(self.stores, b.ids_dev, x, self.feat_dim, n_rows=nd0)
+        else:
+            n0 = sum(n * f for n, f in zip(b.n_rows, self.feat_dim))
+            x = self._typed("x0", n0)
+            row_off, elem_off = ctx.hgnn_merge_features(self.stores, b.ids_dev, x, self.feat_dim)
         xs, hs, saved = [x], [], []
         launches = []
         for l, lp in enumerate(self.layers):
@@ -234,6 +246,8 @@ class Model:
                 launches.append(ctx.hgnn_layer_fwd_two_step(b.graph, l, lp, xs[-1], h, sv, sc, fc))
             elif naive:
                 launches.append(ctx.hgnn_layer_fwd_naive(b.graph, l, lp, xs[-1], h, sv, sc))
+            elif gather and l == 0:
+                ctx.hgnn_layer_fwd_gather(b.graph, l, lp, self.stores, b.ids_dev, xs[-1], h, sv, sc)
             else:
                 ctx.hgnn_layer_fwd(b.graph, l, lp, xs[-1], h, sv, sc)
             hs.append(h); saved.append(sv); xs.append(h)
@@ -268,6 +282,8 @@ class Model:
             dx = self._typed(f"dx{l}", sum(n * f for n, f in zip(blk.n_src, lp.in_dim))) if want_dx else None
             if naive and not self.attention:
                 launches_bwd[l] = ctx.hgnn_layer_bwd_naive(b.graph, l, lp, xs[l], hs[l], saved[l], g, dx, sc)
+            elif gather and l == 0:
+                ctx.hgnn_layer_bwd_gather(b.graph, l, lp, xs[l], hs[l], saved[l], g, dx, sc)
             else:
                 ctx.hgnn_layer_bwd(b.graph, l, lp, xs[l], hs[l], saved[l], g, dx, sc)
             dxs[l] = dx

@@ -162,7 +162,7 @@ def oracle_run(cfg, g, mb, ws, input_grad=None, layerwise=False):
 
 def run_case(index, scale=1.0, batch=None, verbose=False, use_edge_id=True, check_naive=False, graph=None,
              input_grad=None, backward=True, cfg_edit=None, grad_tol=None, sampled=None, need_input_grad=True,
-             check_two_step=False, build_permutation=False, band_max_frac=None, layerwise=False):
+             check_two_step=False, build_permutation=False, band_max_frac=None, layerwise=False, check_gather=False):
     """cfg_edit(cfg, g, mb, ws): optional hook that changes the prepared inputs (e.g. the storage type) before
     both sides run.  grad_tol: optional {substring of a gradient's name: tolerance or None}; a matching
     gradient is held to that tolerance instead of the storage type's (None: reported only).  band_max_frac:
@@ -170,7 +170,10 @@ def run_case(index, scale=1.0, batch=None, verbose=False, use_edge_id=True, chec
     sampled: optional dict(seed=..., fanouts=...): the mini-batch of the same targets is sampled by the library's
     sampler on the HIP side and by the sampler oracle on the other.  need_input_grad=False: the first layer's
     backward gets no input-gradient buffer (its weight and bias gradients are still checked).
-    layerwise=True: every layer is run and compared on inputs that both sides share (layerwise_oracle)."""
+    layerwise=True: every layer is run and compared on inputs that both sides share (layerwise_oracle).
+    check_gather=True: a second run whose first layer reads the feature stores directly (hgnn_layer_fwd_gather /
+    hgnn_layer_bwd_gather, feature merge of the destination rows only) gets the same checks, and its layer outputs
+    and input gradients must equal the first run's bit for bit."""
     import torch
     from paper_2408_08490_amd.runner import Model
     cfg, g, mb, ws = prepare_inputs(index, scale, batch, graph)
@@ -365,6 +368,19 @@ def run_case(index, scale=1.0, batch=None, verbose=False, use_edge_id=True, chec
         report["naive_launches"] = out2["launches"]
         report["merged_launches"] = [model.ctx.hgnn_layer_launch_count(bt.graph, l, model.layers[l])
                                      for l in range(len(ws))]
+    if check_gather:
+        first = dict(h=[h.clone() for h in out["h"]], dx=[None if d is None else d.clone() for d in out.get("dx", [])])
+        out4 = model.run(bt, backward=backward, need_input_grad=need_input_grad, gather=True)
+        torch.cuda.synchronize()
+        check_run(out4, "_gather")
+        nd0 = mb.blocks[0].n_dst
+        want_x = np.concatenate([np.asarray(g.stores[t], np.float32)[mb.ids[t][:nd0[t]]].ravel() for t in range(sch.num_types)])
+        chk("x_dst_gather", out4["x0"].float().cpu().numpy(), want_x, exact=True)
+        for l in range(len(ws)):
+            chk(f"L{l}.h_gather_bits", out4["h"][l].view(torch.uint8).cpu().numpy(), first["h"][l].view(torch.uint8).cpu().numpy(), exact=True)
+            if backward and first["dx"][l] is not None:
+                chk(f"L{l}.dx_gather_bits", out4["dx"][l].view(torch.uint8).cpu().numpy(), first["dx"][l].view(torch.uint8).cpu().numpy(),
+                    exact=True)
     if check_two_step:
         # Algorithm 1 in its two stated steps (FeatureCat, then reduce): against the oracle like the fused path,
         # and bit for bit against the fused path's outputs

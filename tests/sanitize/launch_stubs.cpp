@@ -73,6 +73,9 @@ hgnn_status launch_bwd_prep(hipStream_t s, int dtype, const TypeTab &tt, const R
                             const void *h, void *gp, float *bpart, size_t bpart_rows, void *wpad, int *rows_per_block) { return HGNN_EUNSUPPORTED; }
 hgnn_status launch_bias_reduce(hipStream_t s, const TypeTab &tt, const GradPtrTab &gt, int H, int rpb, const float *bpart) { return HGNN_EUNSUPPORTED; }
 hgnn_status launch_fill_zero(hipStream_t s, void *p, size_t bytes) { return HGNN_EUNSUPPORTED; }
+bool launch_spmm_fwd_uniform(hipStream_t s, int dtype, const LayerDev &L, int F, const void *x, void *z, void *zlo,
+                             int row_begin, int row_end, const uint64_t *gaddr) { return false; }
+hgnn_status launch_gather_addresses(hipStream_t s, const LayerDev &L, const GatherSrc &gs, int row_bytes, uint64_t *gaddr) { return HGNN_EUNSUPPORTED; }
 hgnn_status launch_convert(hipStream_t s, bool widen, const void *const *src, void *const *dst, const int64_t *n, int count) { return HGNN_EUNSUPPORTED; }
 hgnn_status launch_xent(hipStream_t s, int dtype, const void *logits, const int64_t *labels, int64_t rows,
                         int classes, float *loss, void *grad) { return HGNN_EUNSUPPORTED; }
