@@ -599,7 +599,7 @@ static int fwd_tiles(const Plan &pl, SegTab &tl, bool allow_small) {
     const int tn = (pl.H + mn - 1) / mn;
     for (int t = 0; t < T; ++t) tl.tile_off[t + 1] = tl.tile_off[t] + ((pl.tt.n_dst[t] + mn - 1) / mn) * tn;
     tl.num_segs = T;
-    if (mn == 64 || !allow_small || (tl.tile_off[T] >= kSmallTileLimit && !getenv("HGNN_EXP_SMALL"))) return mn;
+    if (mn == 64 || !allow_small || tl.tile_off[T] >= kSmallTileLimit) return mn;
   }
 }
 
@@ -1068,6 +1068,15 @@ hgnn_status hgnn_layer_workspace_bytes(hgnn_ctx *ctx, hgnn_graph *g, int32_t lay
   return HGNN_OK;
 }
 
+// Whether the layer's aggregation is one launch of the gather-mean kernel for a single input width (which can carry the
+// weight transposes): rows to aggregate, all types one width, a row of at most 256 16-byte pieces.
+static bool transposes_ride(const Plan &pl) {
+  if (pl.dev.rows <= 0) return false;
+  for (int t = 0; t < pl.tt.num_types; ++t)
+    if (pl.tt.in_dim[t] != pl.tt.in_dim[0]) return false;
+  return (int64_t)pl.tt.in_dim[0] * pl.es <= 256 * 16;
+}
+
 static hgnn_status fwd_common(hgnn_ctx *ctx, void *stream, hgnn_graph *g, int32_t layer, const hgnn_layer_params *p,
                               const void *x, void *h, void *saved, size_t saved_bytes, void *scratch, size_t scratch_bytes,
                               bool naive, int32_t *launches, void *feature_cat = nullptr, size_t feature_cat_bytes = 0,
@@ -1126,11 +1135,16 @@ static hgnn_status fwd_common(hgnn_ctx *ctx, void *stream, hgnn_graph *g, int32_
     for (int r = 0; r < R; ++r)
       if (reo[r + 1] > reo[r]) live[r >> 5] |= 1u << (r & 31);
   }
-  {
+  // The weight transposes ride in the aggregation launch (as its first blocks) where that launch is the gather-mean
+  // kernel for one input width; otherwise they are a launch of their own.
+  TransposeJobs tj;
+  make_transpose_jobs(pl.tt, pl.rt, pl.pt, pl.wt, pl.H, wtb, tj);
+  const bool rides = !naive && !feature_cat && transposes_ride(pl);
+  if (!rides) {
     Probe pb(ctx, s, HGNN_K_TRANSPOSE_W, layer, !static_area);
-    if ((st = launch_transpose_weights(s, ctx->dtype, pl.tt, pl.rt, pl.pt, pl.wt, pl.H, wtb)) != HGNN_OK) return st;
+    if ((st = launch_transpose_jobs(s, ctx->dtype, tj)) != HGNN_OK) return st;
+    ++n;
   }
-  ++n;
   if (!naive) {
     if (feature_cat) {
       // Algorithm 1 in two steps (gather into FeatureCat, then reduce by destination) instead of the fused kernel
@@ -1149,14 +1163,14 @@ static hgnn_status fwd_common(hgnn_ctx *ctx, void *stream, hgnn_graph *g, int32_
         if (pl.dev.edges > 0) ++n;
         Probe pb(ctx, s, HGNN_K_SPMM_FWD, layer);
         if (pl.dev.rows > 0) {
-          if (!launch_spmm_fwd_uniform(s, ctx->dtype, pl.dev, p->in_dim[0], nullptr, saved, zlo, 0, pl.dev.rows, gaddr))
+          if (!launch_spmm_fwd_uniform(s, ctx->dtype, pl.dev, p->in_dim[0], nullptr, saved, zlo, 0, pl.dev.rows, gaddr, rides ? &tj : nullptr))
             HGNN_FAIL(HGNN_EUNSUPPORTED, "input width %d is outside what the gather kernels cover", p->in_dim[0]);
           HGNN_HIP(hipGetLastError());
           ++n;
         }
       } else {
         Probe pb(ctx, s, HGNN_K_SPMM_FWD, layer, !static_area);
-        if ((st = launch_spmm_fwd(s, ctx->dtype, pl.dev, pl.tt, pl.rt, pl.max_dim, x, saved, zlo, 0, pl.dev.rows)) != HGNN_OK) return st;
+        if ((st = launch_spmm_fwd(s, ctx->dtype, pl.dev, pl.tt, pl.rt, pl.max_dim, x, saved, zlo, 0, pl.dev.rows, rides ? &tj : nullptr)) != HGNN_OK) return st;
         if (pl.dev.rows > 0) ++n;
       }
     }
@@ -1533,7 +1547,7 @@ hgnn_status hgnn_layer_launch_count(hgnn_ctx *ctx, hgnn_graph *g, int32_t layer,
   Plan pl;
   hgnn_status st = make_plan(ctx, g, layer, p, pl, true);
   if (st != HGNN_OK) return st;
-  if (fwd_launches) *fwd_launches = 1 + (pl.dev.rows > 0) + (pl.total_dst > 0);
+  if (fwd_launches) *fwd_launches = (transposes_ride(pl) ? 0 : 1) + (pl.dev.rows > 0) + (pl.total_dst > 0);
   if (bwd_launches) {
     // zero grads + ReLU mask + bias partial sums (one launch), dW and dA GEMMs + bias sums (one launch), transposed
     // aggregation (+ long-row pass); without destination rows only the zeroing

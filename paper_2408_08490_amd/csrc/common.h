@@ -98,6 +98,17 @@ struct WtTab {                      // where each transposed weight lives in the
   uint32_t root4[kMaxT];
 };
 
+// Weight transposes as a job list (Wt[h][f] = W[f][h] per K-segment, in 32x32 tiles), so that the blocks doing them can
+// be the first blocks of another launch.
+struct TransposeJobs {
+  const void *w[kMaxSeg];
+  uint32_t off4[kMaxSeg];           // scalars/4 of the transposed copy inside `out`
+  int32_t F[kMaxSeg];
+  int32_t tile_off[kMaxSeg + 1];    // 32x32 tiles before job i
+  int32_t n, H, blocks;             // blocks = blocks that work on the tiles (0: nothing to do)
+  void *out;
+};
+
 // Device-side index arrays of one layer (all int32, inside the graph's device block).
 struct LayerDev {
   const int32_t *rel_row_off, *rel_edge_off, *rowptr, *colidx, *cptr, *crow;
@@ -286,8 +297,11 @@ hgnn_status launch_merge(hipStream_t s, int dtype, int T, const void *const *sto
                          const int64_t *const *ids, const int64_t *n_rows, const int64_t *elem_off, void *out);
 // rows [row_begin,row_end) of the merged CSR: z[row] = mean of the x rows in colidx (rounded to the storage type);
 // zlo (optional, same layout): what that rounding dropped, rounded in turn
+// tj (optional): weight transposes that ride in the same launch as its first blocks (in a launch of their own when
+// the aggregation runs on the kernels for ragged widths)
 hgnn_status launch_spmm_fwd(hipStream_t s, int dtype, const LayerDev &L, const TypeTab &tt, const RelTab &rt,
-                            int max_dim, const void *x, void *z, void *zlo, int row_begin, int row_end);
+                            int max_dim, const void *x, void *z, void *zlo, int row_begin, int row_end,
+                            const TransposeJobs *tj = nullptr);
 // the same aggregate in the two steps of the paper's Algorithm 1: FeatureCat [edges x F] = gathered source rows,
 // then a mean per merged row (all types one width F)
 hgnn_status launch_aggregate_literal(hipStream_t s, int dtype, const LayerDev &L, int F, const void *x, void *feature_cat,
@@ -297,7 +311,10 @@ hgnn_status launch_spmm_bwd(hipStream_t s, int dtype, const LayerDev &L, const T
                             const PtrTab &pt, int max_dim, uint32_t want_types, const void *dz, void *dx, float *partial);
 // uniform feature width: return false when the width is outside what they cover (caller falls back)
 bool launch_spmm_fwd_uniform(hipStream_t s, int dtype, const LayerDev &L, int F, const void *x, void *z, void *zlo,
-                             int row_begin, int row_end, const uint64_t *gaddr = nullptr);
+                             int row_begin, int row_end, const uint64_t *gaddr = nullptr, const TransposeJobs *tj = nullptr);
+void make_transpose_jobs(const TypeTab &tt, const RelTab &rt, const PtrTab &pt, const WtTab &wt, int H, void *wt_buf,
+                         TransposeJobs &tj);
+hgnn_status launch_transpose_jobs(hipStream_t s, int dtype, const TransposeJobs &tj);
 // Aggregation straight from the per-type feature stores: gaddr[e] = address of the row that edge e reads (the row
 // ids[t][c - row_off[t]] of store t for the merged source row c = colidx[e]); launch_spmm_fwd_uniform then takes
 // gaddr in place of x.

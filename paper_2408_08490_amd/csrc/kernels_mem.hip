@@ -6,6 +6,7 @@
 #include "common.h"
 #include "bias_reduce.h"
 #include "device_types.h"
+#include "transpose_jobs.h"
 
 namespace hgnn {
 
@@ -126,14 +127,19 @@ __global__ void __launch_bounds__(256) spmm_fwd_kernel(LayerDev L, TypeTab tt, R
 }
 
 hgnn_status launch_spmm_fwd(hipStream_t s, int dtype, const LayerDev &L, const TypeTab &tt, const RelTab &rt,
-                            int max_dim, const void *x, void *z, void *zlo, int row_begin, int row_end) {
-  if (row_end <= row_begin) return HGNN_OK;
+                            int max_dim, const void *x, void *z, void *zlo, int row_begin, int row_end,
+                            const TransposeJobs *tj) {
+  if (row_end <= row_begin) return tj ? launch_transpose_jobs(s, dtype, *tj) : HGNN_OK;
   const int es = dtype == HGNN_BF16 ? 2 : 4;
   bool uniform = true;
   for (int t = 0; t < tt.num_types; ++t) uniform &= tt.in_dim[t] == tt.in_dim[0];
-  if (uniform && launch_spmm_fwd_uniform(s, dtype, L, tt.in_dim[0], x, z, zlo, row_begin, row_end)) {
+  if (uniform && launch_spmm_fwd_uniform(s, dtype, L, tt.in_dim[0], x, z, zlo, row_begin, row_end, nullptr, tj)) {
     HGNN_HIP(hipGetLastError());
     return HGNN_OK;
+  }
+  if (tj) {
+    hgnn_status st = launch_transpose_jobs(s, dtype, *tj);
+    if (st != HGNN_OK) return st;
   }
   const int l2 = lanes_log2_for(max_dim, es);
   const int rpb = 256 >> l2;
@@ -320,52 +326,47 @@ hgnn_status launch_spmm_bwd(hipStream_t s, int dtype, const LayerDev &L, const T
 }
 
 // ------------------------------------------------------------------------------------------
-// Weight transposes: Wt[h][f] = W[f][h] for every relation and root weight (segment = blockIdx.y).
+// Weight transposes: Wt[h][f] = W[f][h] for every relation and root weight, as a job list.
 // ------------------------------------------------------------------------------------------
+void make_transpose_jobs(const TypeTab &tt, const RelTab &rt, const PtrTab &pt, const WtTab &wt, int H, void *wt_buf,
+                         TransposeJobs &tj) {
+  std::memset(&tj, 0, sizeof(tj));
+  tj.H = H;
+  tj.out = wt_buf;
+  const int R = rt.num_rels, tiles_h = (H + 31) / 32;
+  for (int seg = 0; seg < R + tt.num_types; ++seg) {
+    const void *w = seg < R ? pt.w_rel[seg] : pt.w_root[seg - R];
+    if (!w) continue;
+    const int F = tt.in_dim[seg < R ? rt.src[seg] : seg - R];
+    tj.w[tj.n] = w;
+    tj.F[tj.n] = F;
+    tj.off4[tj.n] = seg < R ? wt.rel4[seg] : wt.root4[seg - R];
+    tj.tile_off[tj.n + 1] = tj.tile_off[tj.n] + ((F + 31) / 32) * tiles_h;
+    ++tj.n;
+  }
+  // a tile per block (two dependent memory round trips) up to 2048 blocks: over long before the launch they ride in
+  tj.blocks = std::min(2048, tj.tile_off[tj.n]);
+}
+
 template <typename T>
-__global__ void __launch_bounds__(256) transpose_weights_kernel(TypeTab tt, RelTab rt, PtrTab pt, WtTab wt, int H, T *out) {
-  const int seg = blockIdx.y;
-  const int R = rt.num_rels;
-  const T *w;
-  int F;
-  int64_t off;
-  if (seg < R) {
-    w = (const T *)pt.w_rel[seg];
-    F = tt.in_dim[rt.src[seg]];
-    off = (int64_t)wt.rel4[seg] * 4;
-  } else {
-    w = (const T *)pt.w_root[seg - R];
-    F = tt.in_dim[seg - R];
-    off = (int64_t)wt.root4[seg - R] * 4;
-  }
-  if (!w) return;
+__global__ void __launch_bounds__(256) transpose_weights_kernel(TransposeJobs tj) {
   __shared__ T tile[32][33];
-  const int tiles_f = (F + 31) / 32, tiles_h = (H + 31) / 32;
-  const int tx = threadIdx.x & 31, ty = threadIdx.x >> 5;  // 32 x 8
-  for (int tl = blockIdx.x; tl < tiles_f * tiles_h; tl += gridDim.x) {
-    const int f0 = (tl / tiles_h) * 32, h0 = (tl % tiles_h) * 32;
-    for (int i = ty; i < 32; i += 8) {
-      const int f = f0 + i, h = h0 + tx;
-      if (f < F && h < H) tile[i][tx] = w[(int64_t)f * H + h];
-    }
-    __syncthreads();
-    for (int i = ty; i < 32; i += 8) {
-      const int h = h0 + i, f = f0 + tx;
-      if (f < F && h < H) out[off + (int64_t)h * F + f] = tile[tx][i];
-    }
-    __syncthreads();
-  }
+  transpose_jobs_block<T>(tj, blockIdx.x, gridDim.x, tile);
+}
+
+hgnn_status launch_transpose_jobs(hipStream_t s, int dtype, const TransposeJobs &tj) {
+  if (tj.blocks == 0) return HGNN_OK;
+  if (dtype == HGNN_BF16) HGNN_LAUNCH(transpose_weights_kernel<bf16>, dim3(tj.blocks), dim3(256), 0, s, tj);
+  else HGNN_LAUNCH(transpose_weights_kernel<float>, dim3(tj.blocks), dim3(256), 0, s, tj);
+  HGNN_HIP(hipGetLastError());
+  return HGNN_OK;
 }
 
 hgnn_status launch_transpose_weights(hipStream_t s, int dtype, const TypeTab &tt, const RelTab &rt,
                                      const PtrTab &pt, const WtTab &wt, int H, void *wt_buf) {
-  dim3 grid(128, rt.num_rels + tt.num_types);
-  if (dtype == HGNN_BF16)
-    HGNN_LAUNCH(transpose_weights_kernel<bf16>, grid, dim3(256), 0, s, tt, rt, pt, wt, H, (bf16 *)wt_buf);
-  else
-    HGNN_LAUNCH(transpose_weights_kernel<float>, grid, dim3(256), 0, s, tt, rt, pt, wt, H, (float *)wt_buf);
-  HGNN_HIP(hipGetLastError());
-  return HGNN_OK;
+  TransposeJobs tj;
+  make_transpose_jobs(tt, rt, pt, wt, H, wt_buf, tj);
+  return launch_transpose_jobs(s, dtype, tj);
 }
 
 // Zero-padded copies: out[off + f*Hp + c] = c < H ? W[f*H + c] : 0  (segment = blockIdx.y).

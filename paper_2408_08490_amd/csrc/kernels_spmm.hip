@@ -9,10 +9,12 @@
 // loads, and hands the indices to the lanes that need them through cross-lane reads.  All feature-row
 // loads of up to four edges are then in flight together.  Dependent round trips per wave: row pointers,
 // indices, features -- three, however many rows and edges it owns.
+#include <cstring>
 #include <type_traits>
 
 #include "common.h"
 #include "device_types.h"
+#include "transpose_jobs.h"
 
 namespace hgnn {
 
@@ -34,15 +36,22 @@ __device__ __forceinline__ unsigned long long wave_addr(unsigned long long c0, u
 // address of the source row (in whichever per-type feature store it lives), so that no merged copy of the source
 // rows is needed.
 template <typename T, int LPRL, int C, bool ADDR>
-__global__ void __launch_bounds__(256) spmm_fwd_uniform_kernel(const int32_t *__restrict__ rowptr, const int32_t *__restrict__ colidx,
+__global__ void __launch_bounds__(256, (C <= 2 && !ADDR) ? 8 : 1) spmm_fwd_uniform_kernel(const int32_t *__restrict__ rowptr, const int32_t *__restrict__ colidx,
                                                                 const unsigned long long *__restrict__ gaddr,
                                                                 const T *__restrict__ x, T *__restrict__ z, T *__restrict__ zlo,
-                                                                int F, int row_begin, int row_end) {
+                                                                int F, int row_begin, int row_end, TransposeJobs tj) {
   using V = Vec16<T>;
   using Idx = std::conditional_t<ADDR, unsigned long long, int>;
   constexpr int LPR = 1 << LPRL, RPW = 64 / LPR;
+  // The first tj.blocks blocks transpose the layer's weights for the GEMM that follows this launch: a few
+  // microseconds of work that would otherwise be a launch of its own in front of this one.
+  __shared__ T tile[32][33];
+  if ((int)blockIdx.x < tj.blocks) {
+    transpose_jobs_block<T>(tj, blockIdx.x, tj.blocks, tile);
+    return;
+  }
   const int lane = threadIdx.x & 63;
-  const int row0 = row_begin + (blockIdx.x * 4 + (threadIdx.x >> 6)) * RPW;
+  const int row0 = row_begin + (((int)blockIdx.x - tj.blocks) * 4 + (threadIdx.x >> 6)) * RPW;
   if (row0 >= row_end) return;  // whole wave
   const int nrows = min(RPW, row_end - row0);
   const int rp = rowptr[row0 + min(lane, nrows)];
@@ -115,15 +124,15 @@ __global__ void __launch_bounds__(256) spmm_fwd_uniform_kernel(const int32_t *__
 
 template <typename T, int LPRL, int C>
 static void launch_fwd_uniform(hipStream_t s, const LayerDev &L, const void *x, const unsigned long long *gaddr, void *z, void *zlo, int F,
-                               int row_begin, int row_end) {
+                               int row_begin, int row_end, const TransposeJobs &tj) {
   constexpr int RPB = 4 * (64 >> LPRL);
-  dim3 grid((row_end - row_begin + RPB - 1) / RPB);
+  dim3 grid(tj.blocks + (row_end - row_begin + RPB - 1) / RPB);
   if (gaddr)
     HGNN_LAUNCH((spmm_fwd_uniform_kernel<T, LPRL, C, true>), grid, dim3(256), 0, s, L.rowptr, L.colidx, gaddr, (const T *)x, (T *)z,
-                (T *)zlo, F, row_begin, row_end);
+                (T *)zlo, F, row_begin, row_end, tj);
   else
     HGNN_LAUNCH((spmm_fwd_uniform_kernel<T, LPRL, C, false>), grid, dim3(256), 0, s, L.rowptr, L.colidx, gaddr, (const T *)x, (T *)z,
-                (T *)zlo, F, row_begin, row_end);
+                (T *)zlo, F, row_begin, row_end, tj);
 }
 
 // Returns false when the shape is outside what the uniform kernels cover (the generic kernels then run).
@@ -149,13 +158,19 @@ template <typename T, bool FWD, typename FN> static bool dispatch_width(int nvec
 }
 
 bool launch_spmm_fwd_uniform(hipStream_t s, int dtype, const LayerDev &L, int F, const void *x, void *z, void *zlo,
-                             int row_begin, int row_end, const uint64_t *gaddr) {
+                             int row_begin, int row_end, const uint64_t *gaddr, const TransposeJobs *tjp) {
   const int es = dtype == HGNN_BF16 ? 2 : 4;
   const int nvec = F * es / 16;
   const unsigned long long *ga = reinterpret_cast<const unsigned long long *>(gaddr);
+  TransposeJobs none;
+  if (!tjp) {
+    std::memset(&none, 0, sizeof(none));
+    tjp = &none;
+  }
+  const TransposeJobs &tj = *tjp;
   if (dtype == HGNN_BF16)
-    return dispatch_width<bf16, true>(nvec, [&]<int LPRL, int C>() { launch_fwd_uniform<bf16, LPRL, C>(s, L, x, ga, z, zlo, F, row_begin, row_end); });
-  return dispatch_width<float, true>(nvec, [&]<int LPRL, int C>() { launch_fwd_uniform<float, LPRL, C>(s, L, x, ga, z, zlo, F, row_begin, row_end); });
+    return dispatch_width<bf16, true>(nvec, [&]<int LPRL, int C>() { launch_fwd_uniform<bf16, LPRL, C>(s, L, x, ga, z, zlo, F, row_begin, row_end, tj); });
+  return dispatch_width<float, true>(nvec, [&]<int LPRL, int C>() { launch_fwd_uniform<float, LPRL, C>(s, L, x, ga, z, zlo, F, row_begin, row_end, tj); });
 }
 
 // gaddr[e] = address of the feature row that edge e reads: the row ids[t][c - row_off[t]] of store t, for the

@@ -6,7 +6,7 @@ namespace hgnn {
 hgnn_status launch_merge(hipStream_t s, int dtype, int T, const void *const *store, const int32_t *feat_dim,
                          const int64_t *const *ids, const int64_t *n_rows, const int64_t *elem_off, void *out) { return HGNN_EUNSUPPORTED; }
 hgnn_status launch_spmm_fwd(hipStream_t s, int dtype, const LayerDev &L, const TypeTab &tt, const RelTab &rt,
-                            int max_dim, const void *x, void *z, void *zlo, int row_begin, int row_end) { return HGNN_EUNSUPPORTED; }
+                            int max_dim, const void *x, void *z, void *zlo, int row_begin, int row_end, const TransposeJobs *tj) { return HGNN_EUNSUPPORTED; }
 hgnn_status launch_aggregate_literal(hipStream_t s, int dtype, const LayerDev &L, int F, const void *x, void *feature_cat,
                                      void *z, void *zlo) { return HGNN_EUNSUPPORTED; }
 hgnn_status launch_spmm_bwd(hipStream_t s, int dtype, const LayerDev &L, const TypeTab &tt, const RelTab &rt,
@@ -74,8 +74,11 @@ hgnn_status launch_bwd_prep(hipStream_t s, int dtype, const TypeTab &tt, const R
 hgnn_status launch_bias_reduce(hipStream_t s, const TypeTab &tt, const GradPtrTab &gt, int H, int rpb, const float *bpart) { return HGNN_EUNSUPPORTED; }
 hgnn_status launch_fill_zero(hipStream_t s, void *p, size_t bytes) { return HGNN_EUNSUPPORTED; }
 bool launch_spmm_fwd_uniform(hipStream_t s, int dtype, const LayerDev &L, int F, const void *x, void *z, void *zlo,
-                             int row_begin, int row_end, const uint64_t *gaddr) { return false; }
+                             int row_begin, int row_end, const uint64_t *gaddr, const TransposeJobs *tj) { return false; }
 hgnn_status launch_gather_addresses(hipStream_t s, const LayerDev &L, const GatherSrc &gs, int row_bytes, uint64_t *gaddr) { return HGNN_EUNSUPPORTED; }
+void make_transpose_jobs(const TypeTab &tt, const RelTab &rt, const PtrTab &pt, const WtTab &wt, int H, void *wt_buf,
+                         TransposeJobs &tj) { tj.n = 0; tj.blocks = 0; }
+hgnn_status launch_transpose_jobs(hipStream_t s, int dtype, const TransposeJobs &tj) { return HGNN_EUNSUPPORTED; }
 hgnn_status launch_convert(hipStream_t s, bool widen, const void *const *src, void *const *dst, const int64_t *n, int count) { return HGNN_EUNSUPPORTED; }
 hgnn_status launch_xent(hipStream_t s, int dtype, const void *logits, const int64_t *labels, int64_t rows,
                         int classes, float *loss, void *grad) { return HGNN_EUNSUPPORTED; }
