@@ -474,6 +474,24 @@ def main():
             return (time.perf_counter() - t) / n
         serial_loop(3)
         serial_ms = 1e3 * serial_loop(n_ab)
+
+        # the index arrays built by device kernels on the compute stream, in front of each step's compute
+        dev_build_gpu_ms = []
+
+        def device_build_loop(n):
+            t = time.perf_counter()
+            for i in range(n):
+                sl = slots[i % len(slots)]
+                gr = ctx.hgnn_build_semantic_csr_device(sl.mb.blocks, None, use_edge_id=True,
+                                                        transpose_types=model.transpose_types(len(sl.mb.blocks)))
+                dev_build_gpu_ms.append(gr.build_gpu_ms)
+                model.run(batch_of(sl, gr))
+                torch.cuda.synchronize()
+                gr.release()
+            return (time.perf_counter() - t) / n
+        device_build_loop(3)
+        del dev_build_gpu_ms[:]
+        device_build_step_ms = 1e3 * device_build_loop(n_ab)
         step_naive_ms = None
         if not attention:
             step_naive(0)
@@ -495,6 +513,8 @@ def main():
                    forward_per_relation_launches_ms=None if naive_fwd_ms is None else round(naive_fwd_ms, 4),
                    forward_two_step_aggregation_ms=None if two_step_fwd_ms is None else round(two_step_fwd_ms, 4),
                    step_serial_build_then_compute_ms=round(serial_ms, 4),
+                   step_device_build_then_compute_ms=round(device_build_step_ms, 4),
+                   device_build_gpu_ms=round(float(np.mean(dev_build_gpu_ms)), 4),
                    step_overlapped_ms=round(1e3 * t_pipe / K, 4), step_gpu_only_ms=round(1e3 * t_gpu / K, 4),
                    host_builders=args.concurrent_builds,
                    note="forward_*: merge + all layers forward, index arrays resident (GPU time between events); step_*: "
@@ -502,6 +522,9 @@ def main():
                         "the aggregation as Algorithm 1 states it (source rows of all semantic graphs gathered into "
                         "FeatureCat, then reduced by destination) instead of the fused gather-mean; "
                         "serial: every step builds its index arrays with one builder, waits, computes, waits; "
+                        "device_build: every step builds them with device kernels on the compute stream "
+                        "(hgnn_build_semantic_csr_device: keys, two radix sorts, prefix sums), then computes; device_build_gpu_ms "
+                        "is the GPU time of that build alone, input upload included; "
                         "overlapped: bench.py's `value` loop")
 
     # whole training steps (forward, loss, backward, Adam on all weights and on the embedding rows read), index

@@ -117,6 +117,16 @@ typedef struct {
                                       hgnn_layer_params.input_grad, which must then be 0 for t as well) */
 } hgnn_coo_layer;
 
+/* The same build done by device kernels on `stream` instead of by host threads (the arrangement Section 4.3
+ * moves away from; kept as the baseline to measure the host build against): edge-type matching, a stable radix
+ * sort by (relation, destination), a second one for the transpose.  Same inputs (host arrays), same index arrays
+ * bit for bit, same graph object.  Synchronous: returns when the graph is complete (no hgnn_graph_wait needed);
+ * allocates device scratch that the context keeps.  gpu_ms (may be NULL): device time of the build between two
+ * events on `stream`, uploads of the inputs included, the copy of the results back to the host views excluded.
+ * Errors as for hgnn_build_semantic_csr, except that a bad edge is reported by kind, not by position. */
+hgnn_status hgnn_build_semantic_csr_device(hgnn_ctx *ctx, void *stream, int32_t num_layers,
+                                           const hgnn_coo_layer *layers, hgnn_graph **out, float *gpu_ms);
+
 /* Registers the graph's global edge-type table (Algorithm 2's EdgeType, one entry per edge of the whole graph):
  * the context keeps a compact copy (one byte per edge), so that later hgnn_coo_layer entries may pass edge_id
  * alone.  The look-up EdgeType[EdgeID] is a random access per sampled edge; the compact table keeps most of it

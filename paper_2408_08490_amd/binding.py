@@ -90,6 +90,7 @@ def _load():
         "hgnn_merge_features": [vp, vp, C.POINTER(vp), C.POINTER(i32), C.POINTER(vp), C.POINTER(i64), vp,
                                 C.POINTER(i32), C.POINTER(i64)],
         "hgnn_build_semantic_csr": [vp, i32, C.POINTER(CooLayer), C.POINTER(vp)],
+        "hgnn_build_semantic_csr_device": [vp, vp, i32, C.POINTER(CooLayer), C.POINTER(vp), C.POINTER(C.c_float)],
         "hgnn_set_edge_types": [vp, vp, i64],
         "hgnn_set_build_permutation": [vp, i32],
         "hgnn_graph_wait": [vp, vp],
@@ -136,7 +137,7 @@ def _load():
 
 lib = _load()
 
-EXPORTS = ["hgnn_create", "hgnn_destroy", "hgnn_last_error", "hgnn_merge_features", "hgnn_layer_fwd_gather", "hgnn_layer_bwd_gather", "hgnn_set_edge_types",
+EXPORTS = ["hgnn_create", "hgnn_destroy", "hgnn_last_error", "hgnn_merge_features", "hgnn_build_semantic_csr_device", "hgnn_layer_fwd_gather", "hgnn_layer_bwd_gather", "hgnn_set_edge_types",
            "hgnn_build_semantic_csr", "hgnn_sampler_create", "hgnn_sampler_destroy", "hgnn_sample_and_build",
            "hgnn_graph_ids", "hgnn_graph_minibatch_view", "hgnn_graph_wait_stream",
            "hgnn_set_build_permutation", "hgnn_graph_wait", "hgnn_graph_host_view", "hgnn_graph_release", "hgnn_layer_workspace_bytes",
@@ -390,7 +391,7 @@ class Context:
     def hgnn_set_build_permutation(self, enabled: bool):
         _check(lib.hgnn_set_build_permutation(self.handle, 1 if enabled else 0))
 
-    def hgnn_build_semantic_csr(self, blocks, global_edge_type=None, use_edge_id=False, transpose_types=None) -> Graph:
+    def hgnn_build_semantic_csr(self, blocks, global_edge_type=None, use_edge_id=False, transpose_types=None, on_device=False) -> Graph:
         """blocks: objects with n_src, n_dst, edge_index (2 x E, int64 or int32), edge_type / edge_id.
         use_edge_id with global_edge_type None: the table registered with hgnn_set_edge_types is used.
         transpose_types: per layer, None or a 0/1 list per vertex type (hgnn_coo_layer.transpose_types)."""
@@ -428,8 +429,18 @@ class Context:
                 keep.append(tta)
                 arr[i].transpose_types = tta.ctypes.data
         h = C.c_void_p()
+        if on_device:
+            ms = C.c_float()
+            _check(lib.hgnn_build_semantic_csr_device(self.handle, _stream_ptr(self.device), n, arr, C.byref(h), C.byref(ms)))
+            gr = Graph(self, h, keep)
+            gr.build_gpu_ms = ms.value
+            return gr
         _check(lib.hgnn_build_semantic_csr(self.handle, n, arr, C.byref(h)))
         return Graph(self, h, keep)
+
+    def hgnn_build_semantic_csr_device(self, blocks, global_edge_type=None, use_edge_id=False, transpose_types=None) -> Graph:
+        """The same build by device kernels on the current stream; the graph carries build_gpu_ms."""
+        return self.hgnn_build_semantic_csr(blocks, global_edge_type, use_edge_id, transpose_types, on_device=True)
 
     # ---- layer calls ----
     def hgnn_layer_workspace_bytes(self, graph: Graph, layer: int, lp: Layer):

@@ -14,7 +14,7 @@ CSRC = os.path.join(HERE, "csrc")
 OBJ = os.path.join(HERE, "_build")
 LIB = os.path.join(HERE, "libhgnn.so")
 SOURCES = ["api.cpp", "host_build.cpp", "sampler.cpp", "noalloc.hip", "kernels_mem.hip", "kernels_spmm.hip", "kernels_gemm.hip", "kernels_gemm2.hip",
-           "kernels_attn.hip", "kernels_optim.hip"]
+           "kernels_attn.hip", "kernels_optim.hip", "device_build.hip"]
 FLAGS = ["-O3", "-std=c++20", "--offload-arch=gfx950", "-fPIC", "-Wno-inline-asm", "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops"]
 NOISE = "packed-fp32-ops"
 

@@ -692,6 +692,8 @@ void hgnn_destroy(hgnn_ctx *c) {
     (void)hipEventDestroy(pr.second);
   }
   if (c->side) (void)hipStreamDestroy(c->side);
+  if (c->dev_tmp) (void)hipFree(c->dev_tmp);
+  if (c->dev_types8) (void)hipFree(c->dev_types8);
   delete c;
 }
 
@@ -1001,6 +1003,7 @@ hgnn_status hgnn_set_edge_types(hgnn_ctx *ctx, const int32_t *global_edge_type, 
     t[(size_t)i] = (uint8_t)r;
   }
   ctx->edge_types8.swap(t);
+  ++ctx->types_version;
   index_edge_type_runs(ctx);
   return HGNN_OK;
 }

@@ -254,6 +254,12 @@ struct hgnn_ctx {
   std::vector<hipEvent_t> free_events;
   bool build_perm = true;            // later builds produce perm / cperm (hgnn_set_build_permutation)
   std::vector<uint8_t> edge_types8;  // compact copy of the registered global edge-type table
+  uint64_t types_version = 1;        // bumped whenever that table is replaced
+  // device-side index build (hgnn_build_semantic_csr_device): its scratch and its copy of the table above
+  void *dev_tmp = nullptr;
+  size_t dev_tmp_cap = 0;
+  uint8_t *dev_types8 = nullptr;
+  uint64_t dev_types8_version = 0;
   // the same table as runs of equal type, kept when there are few of them (edge ids grouped by relation, the usual
   // case): type of id = run_rel[j], j = the run that holds id, found from run_lut[id >> run_shift] (the run in which
   // that block of ids starts) by stepping over at most the few boundaries inside the block; a few hundred cached

@@ -197,6 +197,7 @@ hgnn_status hgnn_sampler_create(hgnn_ctx *ctx, const hgnn_host_graph *graph, hgn
   for (int r = 0; r < R; ++r)
     std::memset(types.data() + s->edge_off[r], r, (size_t)(s->edge_off[r + 1] - s->edge_off[r]));
   ctx->edge_types8.swap(types);
+  ++ctx->types_version;
   index_edge_type_runs(ctx);
   *out = s;
   return HGNN_OK;

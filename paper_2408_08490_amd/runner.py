@@ -176,12 +176,13 @@ class Model:
         return raw[: numel * es].view(_tdtype(self.dtype))
 
     # ---- host side of a step: upload ids / labels, start the semantic graph build ----
-    def prepare(self, mb, global_edge_type=None, use_edge_id=False) -> Batch:
+    def prepare(self, mb, global_edge_type=None, use_edge_id=False, device_build=False) -> Batch:
         b = Batch()
         b.ids_dev = [torch.from_numpy(np.ascontiguousarray(i, dtype=np.int64)).to(self.dev) for i in mb.ids]
         b.n_rows = [len(i) for i in mb.ids]
         b.blocks = mb.blocks
-        b.graph = self.ctx.hgnn_build_semantic_csr(mb.blocks, global_edge_type, use_edge_id, self.transpose_types(len(mb.blocks)))
+        b.graph = self.ctx.hgnn_build_semantic_csr(mb.blocks, global_edge_type, use_edge_id, self.transpose_types(len(mb.blocks)),
+                                                   on_device=device_build)
         if mb.labels is not None:
             b.labels_dev = torch.from_numpy(mb.labels.astype(np.int64)).to(self.dev)
         if mb.grad_out is not None:

@@ -162,7 +162,7 @@ def oracle_run(cfg, g, mb, ws, input_grad=None, layerwise=False):
 
 def run_case(index, scale=1.0, batch=None, verbose=False, use_edge_id=True, check_naive=False, graph=None,
              input_grad=None, backward=True, cfg_edit=None, grad_tol=None, sampled=None, need_input_grad=True,
-             check_two_step=False, build_permutation=False, band_max_frac=None, layerwise=False, check_gather=False):
+             check_two_step=False, build_permutation=False, band_max_frac=None, layerwise=False, check_gather=False, device_build=False):
     """cfg_edit(cfg, g, mb, ws): optional hook that changes the prepared inputs (e.g. the storage type) before
     both sides run.  grad_tol: optional {substring of a gradient's name: tolerance or None}; a matching
     gradient is held to that tolerance instead of the storage type's (None: reported only).  band_max_frac:
@@ -171,6 +171,8 @@ def run_case(index, scale=1.0, batch=None, verbose=False, use_edge_id=True, chec
     sampler on the HIP side and by the sampler oracle on the other.  need_input_grad=False: the first layer's
     backward gets no input-gradient buffer (its weight and bias gradients are still checked).
     layerwise=True: every layer is run and compared on inputs that both sides share (layerwise_oracle).
+    device_build=True: the index arrays come from hgnn_build_semantic_csr_device (and are compared bit for bit like the
+    host build's; everything downstream then runs on that graph).
     check_gather=True: a second run whose first layer reads the feature stores directly (hgnn_layer_fwd_gather /
     hgnn_layer_bwd_gather, feature merge of the destination rows only) gets the same checks, and its layer outputs
     and input gradients must equal the first run's bit for bit."""
@@ -199,7 +201,7 @@ def run_case(index, scale=1.0, batch=None, verbose=False, use_edge_id=True, chec
         sampler = model.ctx.hgnn_sampler_create(g.num_nodes, g.in_indptr, g.in_nbr, g.edge_off)
         bt = model.prepare_sampled(sampler, targets, fanouts, sampled["seed"], labels=mb.labels, grad_out=mb.grad_out)
     else:
-        bt = model.prepare(mb, g.edge_type, use_edge_id=use_edge_id)
+        bt = model.prepare(mb, g.edge_type, use_edge_id=use_edge_id, device_build=device_build)
     inject = {}
     if layerwise:
         from paper_2408_08490_amd.runner import to_device
