@@ -25,7 +25,10 @@ Pins (see tests/test_oracle_*.py): a hand-worked 4-vertex example, dense
 adjacency-matrix brute force, a scipy.sparse reduction for one relation,
 merged-vs-unmerged equality, constant-feature means, permutation equivariance,
 project/aggregate commutation, finite-difference gradients, numpy.lexsort for
-the index outputs, closed forms for the cross-entropy.
+the index outputs, closed forms for the cross-entropy; for the optional
+`relu_mask` of the backward functions: the layer's own decisions reproduce the
+plain backward bit for bit, and flipping one unit moves exactly that unit's
+terms (closed form).
 
 Parity unpinned by the paper: the attention variant's definition (functions
 `rgat_*`): the paper cites R-GAT without equations, so those functions follow
