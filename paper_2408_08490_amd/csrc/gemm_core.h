@@ -26,10 +26,18 @@ template <> struct Mma<bf16> {
 template <> struct Mma<float> {
   static constexpr int BK = 32, KSTEP = 2, VEC = 4, PKC = BK + 4, KSPAD = 4;
 };
+// LDS pitch (elements) of an operand tile kept with its OUTPUT index contiguous ("KS": rows = k).  A 128-wide bf16
+// tile is kept unpadded (a row = 64 dwords = the LDS's 64 banks) with the four 64-byte column blocks of a row
+// XOR-swizzled by the row's low two bits: the transposing fragment read touches four consecutive k-rows at one
+// column block per 32 lanes, which then sit on four different quarters of the banks (with a 16-element pad they
+// overlapped in pairs: a quarter of the weight-gradient kernel's LDS cycles were bank conflicts).  Other shapes
+// keep the pad.
+template <typename T> constexpr bool ks_swizzled(int extent) { return sizeof(T) == 2 && extent == 128; }
+template <typename T> constexpr int ks_pitch(int extent) { return ks_swizzled<T>(extent) ? extent : extent + Mma<T>::KSPAD; }
+__device__ __forceinline__ int ks_swizzle_col(int col, int row) { return (((col >> 5) ^ (row & 3)) << 5) | (col & 31); }
 // elements of one LDS stage of an operand tile with `extent` output indices, in either orientation
 template <typename T> constexpr int lds_elems(int extent) {
-  return (extent * Mma<T>::PKC > Mma<T>::BK * (extent + Mma<T>::KSPAD)) ? extent * Mma<T>::PKC
-                                                                        : Mma<T>::BK * (extent + Mma<T>::KSPAD);
+  return (extent * Mma<T>::PKC > Mma<T>::BK * ks_pitch<T>(extent)) ? extent * Mma<T>::PKC : Mma<T>::BK * ks_pitch<T>(extent);
 }
 
 // One K-segment of a tile's reduction: sum over k in [kb, ke) of Aop[.][k] * Bop[.][k].
@@ -122,7 +130,9 @@ struct TileMover {
 #pragma unroll
     for (int i = 0; i < NV; ++i) {
       const int v = threadIdx.x + i * kThreads;
-      T *q = lds + (v / VPR) * PITCH + (v % VPR) * VEC;
+      int col = (v % VPR) * VEC;
+      if constexpr (!KC && ks_swizzled<T>(COLS)) col = ks_swizzle_col(col, v / VPR);
+      T *q = lds + (v / VPR) * PITCH + col;
       if constexpr ((PITCH * sizeof(T)) % 16 == 0) {
         *reinterpret_cast<u32x4 *>(q) = reg[i];
       } else {
@@ -146,7 +156,10 @@ template <bool KC, int PITCH> __device__ __forceinline__ bf16x8_t frag_bf16(cons
     typedef short v4i16 __attribute__((ext_vector_type(4)));
     typedef __attribute__((address_space(3))) v4i16 *lds_v4;
     const int p = lane & 15;
-    const bf16 *q = s + (ks * 16 + 8 * (lane >> 5) + (p >> 2)) * PITCH + o + 16 * ((lane >> 4) & 1) + 4 * (p & 3);
+    const int row = ks * 16 + 8 * (lane >> 5) + (p >> 2);
+    int col = o + 16 * ((lane >> 4) & 1) + 4 * (p & 3);
+    if constexpr (PITCH == 128) col = ks_swizzle_col(col, row);  // the unpadded, swizzled 128-wide tile (row + 4 has the same low bits)
+    const bf16 *q = s + row * PITCH + col;
     union { bf16x8_t v; v4i16 h[2]; } u;
     u.h[0] = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_v4)q);
     u.h[1] = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_v4)(q + 4 * PITCH));
@@ -161,7 +174,7 @@ template <bool KC, int PITCH> __device__ __forceinline__ float frag_f32(const fl
 template <typename T, bool AKC, bool BKC, int MI, int NI>
 __device__ __forceinline__ void mma_tile(f32x16 (&acc)[MI][NI], const T *As, const T *Bs, int wm, int wn, int lane) {
   using M = Mma<T>;
-  constexpr int PA = AKC ? M::PKC : 64 * MI + M::KSPAD, PB = BKC ? M::PKC : 64 * NI + M::KSPAD;
+  constexpr int PA = AKC ? M::PKC : ks_pitch<T>(64 * MI), PB = BKC ? M::PKC : ks_pitch<T>(64 * NI);
 #pragma unroll
   for (int ks = 0; ks < M::BK / M::KSTEP; ++ks) {
     if constexpr (sizeof(T) == 2) {
@@ -214,8 +227,8 @@ __device__ __forceinline__ void gemm_run(f32x16 (&acc)[MI][NI], GemmLds<T, MI, N
   constexpr int TM = 64 * MI, TN = 64 * NI;
   const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
   const int wm = (wave >> 1) * 32 * MI, wn = (wave & 1) * 32 * NI;
-  using MoverA = TileMover<T, AKC ? TM : M::BK, AKC ? M::BK : TM, AKC ? M::PKC : TM + M::KSPAD, AKC>;
-  using MoverB = TileMover<T, BKC ? TN : M::BK, BKC ? M::BK : TN, BKC ? M::PKC : TN + M::KSPAD, BKC>;
+  using MoverA = TileMover<T, AKC ? TM : M::BK, AKC ? M::BK : TM, AKC ? M::PKC : ks_pitch<T>(TM), AKC>;
+  using MoverB = TileMover<T, BKC ? TN : M::BK, BKC ? M::BK : TN, BKC ? M::PKC : ks_pitch<T>(TN), BKC>;
   MoverA ta0, ta1;
   MoverB tb0, tb1;
   int total = 0;
