@@ -1284,6 +1284,29 @@ static void seg_tiles_da(hgnn_ctx *ctx, const Plan &pl, const hgnn_layer_params 
   }
 }
 
+// The same tiles grouped for the merged backward launch: per destination type, per 128-row block, the column blocks
+// of every live segment whose input gradient is wanted.
+static void grouped_tiles_da(hgnn_ctx *ctx, const Plan &pl, const SegTab &by_seg, DwTab &tl) {
+  const int R = ctx->R, T = ctx->T;
+  std::memset(&tl, 0, sizeof(tl));
+  int ne = 0;
+  for (int d = 0; d < T; ++d) {
+    tl.first[d] = (uint16_t)ne;
+    int u = 0;
+    for (int sgi = 0; sgi < R + T; ++sgi) {
+      const bool is_rel = sgi < R;
+      if ((is_rel ? ctx->rel_dst[sgi] : sgi - R) != d || by_seg.tile_off[sgi + 1] == by_seg.tile_off[sgi]) continue;
+      tl.seg[ne] = (uint8_t)sgi;
+      tl.u_off[ne] = (uint16_t)u;
+      u += (pl.tt.in_dim[is_rel ? ctx->rel_src[sgi] : d] + 127) / 128;
+      ++ne;
+    }
+    tl.u_total[d] = (uint16_t)u;
+    tl.tile_off[d + 1] = tl.tile_off[d] + u * ((pl.tt.n_dst[d] + 127) / 128);
+  }
+  tl.first[T] = (uint16_t)ne;
+}
+
 static hgnn_status bwd_common(hgnn_ctx *ctx, void *stream, hgnn_graph *g, int32_t layer, const hgnn_layer_params *p,
                               const void *x_merged, const void *h_out, const void *saved, const void *grad_h,
                               void *grad_x_merged, const hgnn_layer_grads *go, void *scratch, size_t scratch_bytes, bool naive,
@@ -1492,7 +1515,9 @@ static hgnn_status bwd_common(hgnn_ctx *ctx, void *stream, hgnn_graph *g, int32_
     Probe pb(ctx, s, HGNN_K_GEMM_DW, layer);
     if (want_dx && da_tl.tile_off[da_tl.num_segs] > 0 && tl.tile_off[T] > 0) {
       // both backward GEMMs read G' and are independent of each other: one launch
-      if ((st = launch_gemm_bwd(s, ctx->dtype, pl.dev, pl.tt, pl.rt, wpt, da_tl, gt, tl, split_rows, pl.H, ldg, fast, x_merged,
+      DwTab da_grouped;
+      grouped_tiles_da(ctx, pl, da_tl, da_grouped);
+      if ((st = launch_gemm_bwd(s, ctx->dtype, pl.dev, pl.tt, pl.rt, wpt, da_grouped, gt, tl, split_rows, pl.H, ldg, fast, x_merged,
                                 saved, gp, dz, bpart, rpb)) != HGNN_OK) return st;
       da_done = true;
       bpart = nullptr;

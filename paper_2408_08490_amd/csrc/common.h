@@ -374,7 +374,7 @@ hgnn_status launch_bias_act(hipStream_t s, int dtype, const TypeTab &tt, const P
 hgnn_status launch_gemm_da(hipStream_t s, int dtype, const LayerDev &L, const TypeTab &tt, const RelTab &rt,
                            const PtrTab &pt, const SegTab &tiles, int ldg, bool fast, const void *gp, void *dz);
 hgnn_status launch_gemm_bwd(hipStream_t s, int dtype, const LayerDev &L, const TypeTab &tt, const RelTab &rt,
-                            const PtrTab &pt, const SegTab &da_tiles, const GradPtrTab &gt, const DwTab &dw_tiles,
+                            const PtrTab &pt, const DwTab &da_tiles, const GradPtrTab &gt, const DwTab &dw_tiles,
                             int split_rows, int H, int ldg, bool fast, const void *x, const void *z, const void *gp, void *dz,
                             const float *bpart, int rpb);  // bpart != NULL: the launch also reduces the partial bias sums
 hgnn_status launch_gemm_dw(hipStream_t s, int dtype, const LayerDev &L, const TypeTab &tt, const RelTab &rt,

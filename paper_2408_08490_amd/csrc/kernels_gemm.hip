@@ -145,23 +145,18 @@ __device__ __forceinline__ int find_seg(const SegTab &tiles, int tile) {
 // dZ_s = (G' W_s^T) / deg.  G' has leading dimension ldg (>= H; the columns H..ldg-1 are zero), and so have
 // the weights handed in through `pt` (the caller's own when H is a multiple of 16 bytes, zero-padded copies
 // otherwise), so that the reduction simply runs over ldg.
+// One tile of dZ_seg: destination rows m0.., columns n0.. of the segment's input width.
 template <typename T, bool FAST, int MI>
-__device__ __forceinline__ void da_tile(GemmLds<T, MI, MI> &sm, int bid, int nblocks, const LayerDev &L, const TypeTab &tt,
-                                        const RelTab &rt, const PtrTab &pt, const SegTab &tiles, int ldg,
-                                        const T *__restrict__ gp, T *__restrict__ dz) {
-  constexpr int BM = 64 * MI, BN = 64 * MI;
-  const int tile = xcd_tile(bid, nblocks);
+__device__ __forceinline__ void da_tile_at(GemmLds<T, MI, MI> &sm, int seg, int m0, int n0, const LayerDev &L, const TypeTab &tt,
+                                           const RelTab &rt, const PtrTab &pt, int ldg, const T *__restrict__ gp,
+                                           T *__restrict__ dz) {
+  constexpr int BM = 64 * MI;
   const int R = rt.num_rels;
-  if (tile >= tiles.tile_off[tiles.num_segs]) return;
-  const int seg = find_seg(tiles, tile);
   const bool is_rel = seg < R;
   const int d = is_rel ? rt.dst[seg] : seg - R;
   const int F = tt.in_dim[is_rel ? rt.src[seg] : d];
   const T *W = reinterpret_cast<const T *>(is_rel ? pt.w_rel[seg] : pt.w_root[d]);
   const int M = tt.n_dst[d];
-  const int tiles_n = (F + BN - 1) / BN;
-  const int local = tile - tiles.tile_off[seg];
-  const int m0 = (local / tiles_n) * BM, n0 = (local % tiles_n) * BN;
   f32x16 acc[MI][MI];
   zero_acc(acc);
   if (threadIdx.x == 0) put_seg(sm.seg[0], gp + (int64_t)tt.out_row_off[d] * ldg, ldg, W, ldg, 0, ldg);
@@ -180,6 +175,41 @@ __device__ __forceinline__ void da_tile(GemmLds<T, MI, MI> &sm, int bid, int nbl
   T *out = dz + (int64_t)(is_rel ? rt.z_off4[seg] : rt.zroot_off4[d]) * 4;
   write_tile(acc, sm, out + (int64_t)m0 * F + n0, F, M - m0, F - n0,
              [&](float v, int row, int) { return v * sm.rowscale[row]; });
+}
+
+// Tiles in segment order (all row blocks of a segment, then the next segment).
+template <typename T, bool FAST, int MI>
+__device__ __forceinline__ void da_tile(GemmLds<T, MI, MI> &sm, int bid, int nblocks, const LayerDev &L, const TypeTab &tt,
+                                        const RelTab &rt, const PtrTab &pt, const SegTab &tiles, int ldg,
+                                        const T *__restrict__ gp, T *__restrict__ dz) {
+  constexpr int BM = 64 * MI, BN = 64 * MI;
+  const int tile = xcd_tile(bid, nblocks);
+  const int R = rt.num_rels;
+  if (tile >= tiles.tile_off[tiles.num_segs]) return;
+  const int seg = find_seg(tiles, tile);
+  const bool is_rel = seg < R;
+  const int F = tt.in_dim[is_rel ? rt.src[seg] : seg - R];
+  const int tiles_n = (F + BN - 1) / BN;
+  const int local = tile - tiles.tile_off[seg];
+  da_tile_at<T, FAST, MI>(sm, seg, (local / tiles_n) * BM, (local % tiles_n) * BN, L, tt, rt, pt, ldg, gp, dz);
+}
+
+// Tiles grouped by destination type and row block (the DwTab's `u` then runs over the column blocks of all the
+// type's segments): the tiles that read the same 128 rows of G' are neighbours, in one XCD, and fetch them once.
+template <typename T, bool FAST, int MI>
+__device__ __forceinline__ void da_tile_grouped(GemmLds<T, MI, MI> &sm, int bid, int nblocks, const LayerDev &L, const TypeTab &tt,
+                                                const RelTab &rt, const PtrTab &pt, const DwTab &tiles, int ldg,
+                                                const T *__restrict__ gp, T *__restrict__ dz) {
+  constexpr int BM = 64 * MI, BN = 64 * MI;
+  const int tile = xcd_tile(bid, nblocks);
+  if (tile >= tiles.tile_off[tt.num_types]) return;
+  int d = 0;
+  while (tile >= tiles.tile_off[d + 1]) ++d;
+  const int local = tile - tiles.tile_off[d];
+  const int u = local % tiles.u_total[d], mt = local / tiles.u_total[d];
+  int e = tiles.first[d];
+  while (e + 1 < tiles.first[d + 1] && u >= tiles.u_off[e + 1]) ++e;
+  da_tile_at<T, FAST, MI>(sm, tiles.seg[e], mt * BM, (u - tiles.u_off[e]) * BN, L, tt, rt, pt, ldg, gp, dz);
 }
 
 template <typename T, bool FAST, int MI>
@@ -264,7 +294,7 @@ __global__ void __launch_bounds__(kThreads, MI == 1 ? 4 : 2) gemm_dw_kernel(Type
 // The last n_bias blocks (when bpart is given) add up the partial bias-gradient sums that the row pass over G'
 // left: a few microseconds of work that would otherwise be a launch of its own.
 template <typename T, bool FAST>
-__global__ void __launch_bounds__(kThreads, 2) gemm_bwd_kernel(LayerDev L, TypeTab tt, RelTab rt, PtrTab pt, SegTab da_tiles,
+__global__ void __launch_bounds__(kThreads, 2) gemm_bwd_kernel(LayerDev L, TypeTab tt, RelTab rt, PtrTab pt, DwTab da_tiles,
                                                             GradPtrTab gt, DwTab dw_tiles, XcdMap xmap, int n_dw, int split_rows,
                                                             int H, int ldg, const T *__restrict__ x, const T *__restrict__ z,
                                                             const T *__restrict__ gp, T *__restrict__ dz,
@@ -276,7 +306,7 @@ __global__ void __launch_bounds__(kThreads, 2) gemm_bwd_kernel(LayerDev L, TypeT
     return;
   }
   if ((int)blockIdx.x < n_dw) dw_tile<T, FAST, 2>(sm, blockIdx.x, tt, rt, gt, dw_tiles, xmap, split_rows, H, ldg, x, z, gp);
-  else da_tile<T, FAST, 2>(sm, blockIdx.x - n_dw, n_gemm - n_dw, L, tt, rt, pt, da_tiles, ldg, gp, dz);
+  else da_tile_grouped<T, FAST, 2>(sm, blockIdx.x - n_dw, n_gemm - n_dw, L, tt, rt, pt, da_tiles, ldg, gp, dz);
 }
 
 static int dw_blocks(int dtype, const TypeTab &tt, const DwTab &tiles, int split_rows, XcdMap &xmap) {
@@ -291,12 +321,12 @@ static int dw_blocks(int dtype, const TypeTab &tt, const DwTab &tiles, int split
 }
 
 hgnn_status launch_gemm_bwd(hipStream_t s, int dtype, const LayerDev &L, const TypeTab &tt, const RelTab &rt,
-                            const PtrTab &pt, const SegTab &da_tiles, const GradPtrTab &gt, const DwTab &dw_tiles,
+                            const PtrTab &pt, const DwTab &da_tiles, const GradPtrTab &gt, const DwTab &dw_tiles,
                             int split_rows, int H, int ldg, bool fast, const void *x, const void *z, const void *gp, void *dz,
                             const float *bpart, int rpb) {
   XcdMap xmap;
   const int n_dw = dw_blocks(dtype, tt, dw_tiles, split_rows, xmap);
-  const int n_da = round_up8(da_tiles.tile_off[da_tiles.num_segs]);
+  const int n_da = round_up8(da_tiles.tile_off[tt.num_types]);
   const int n_bias = bpart ? bias_reduce_blocks(tt.num_types, H) : 0;
   dim3 grid(n_dw + n_da + n_bias), blk(kThreads);
 #define HGNN_BWD(TY, FA)                                                                                             \
