@@ -336,7 +336,7 @@ void make_transpose_jobs(const TypeTab &tt, const RelTab &rt, const PtrTab &pt, 
   const int R = rt.num_rels, tiles_h = (H + 31) / 32;
   for (int seg = 0; seg < R + tt.num_types; ++seg) {
     const void *w = seg < R ? pt.w_rel[seg] : pt.w_root[seg - R];
-    if (!w) continue;
+    if (!w || tt.n_dst[seg < R ? rt.dst[seg] : seg - R] == 0) continue;  // no destination rows: no tile reads this weight
     const int F = tt.in_dim[seg < R ? rt.src[seg] : seg - R];
     tj.w[tj.n] = w;
     tj.F[tj.n] = F;
