@@ -763,10 +763,14 @@ hgnn_status launch_bias_act(hipStream_t s, int dtype, const TypeTab &tt, const P
 }
 
 // ------------------------------------------------------------------------------------------
-// Mean softmax cross-entropy and its gradient; one wavefront per row.
+// Mean softmax cross-entropy and its gradient.
 // ------------------------------------------------------------------------------------------
-// V = values a lane keeps (C <= 64 V): the row is read once, into registers, and the label with it, so a row costs one
-// memory round trip; V = 0 is the form for any C, which re-reads the row for each of its three passes.
+// V = values a lane keeps per row (C <= 64 V).  A wavefront takes kXentRows rows at a time: their values and labels are
+// read with unconditional loads (clamped indices) that are all in flight together, so a trip costs one memory round
+// trip, and the arithmetic runs out of registers.  The loss leaves a block as ONE atomic add, and the grid is kept to
+// 256 blocks: adds to one address are serialised by the memory system at ~11 ns each (1024 blocks of one row per
+// wavefront spent 11 of their 16 us there).  V = 0 is the form for any C, which re-reads a row for each of its passes.
+constexpr int kXentRows = 4;
 template <typename T, int V>
 __global__ void __launch_bounds__(256) xent_kernel(const T *__restrict__ logits, const int64_t *__restrict__ labels,
                                                     int64_t rows, int C, float *loss, T *__restrict__ grad) {
@@ -774,41 +778,54 @@ __global__ void __launch_bounds__(256) xent_kernel(const T *__restrict__ logits,
   const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
   const float inv_rows = 1.0f / (float)rows;
   float my_loss = 0.f;
-  for (int64_t row = (int64_t)blockIdx.x * 4 + wave; row < rows; row += (int64_t)gridDim.x * 4) {
-    const T *z = logits + row * C;
-    const int lab = (int)labels[row];
-    if constexpr (V > 0) {
-      float x[V];
+  if constexpr (V > 0) {
+    for (int64_t row0 = ((int64_t)blockIdx.x * 4 + wave) * kXentRows; row0 < rows; row0 += (int64_t)gridDim.x * 4 * kXentRows) {
+      float x[kXentRows][V];
+      int lab[kXentRows];
 #pragma unroll
-      for (int i = 0; i < V; ++i) {
-        const int c = lane + 64 * i;
-        x[i] = c < C ? to_float(z[c]) : -INFINITY;
-      }
-      float m = x[0];
+      for (int j = 0; j < kXentRows; ++j) {
+        const int64_t row = min(row0 + j, rows - 1);
+        lab[j] = (int)labels[row];
 #pragma unroll
-      for (int i = 1; i < V; ++i) m = fmaxf(m, x[i]);
-      for (int o = 32; o > 0; o >>= 1) m = fmaxf(m, __shfl_xor(m, o));
-      float sum = 0.f, zl = 0.f;
+        for (int i = 0; i < V; ++i) {
+          const int c = lane + 64 * i;
+          const float v = to_float(logits[row * C + min(c, C - 1)]);
+          x[j][i] = c < C ? v : -INFINITY;
+        }
+      }
 #pragma unroll
-      for (int i = 0; i < V; ++i) {
-        if (lane + 64 * i == lab) zl = x[i];
-        x[i] = __expf(x[i] - m);   // exp(-inf) = 0 beyond the row
-        sum += x[i];
-      }
-      for (int o = 32; o > 0; o >>= 1) {
-        sum += __shfl_xor(sum, o);
-        zl += __shfl_xor(zl, o);
-      }
-      const float inv_sum = 1.0f / sum;
+      for (int j = 0; j < kXentRows; ++j) {
+        if (row0 + j >= rows) break;
+        float m = x[j][0];
 #pragma unroll
-      for (int i = 0; i < V; ++i) {
-        const int c = lane + 64 * i;
-        float p = x[i] * inv_sum;
-        if (c == lab) p -= 1.0f;
-        if (c < C) grad[row * C + c] = from_float<T>(p * inv_rows);
+        for (int i = 1; i < V; ++i) m = fmaxf(m, x[j][i]);
+        for (int o = 32; o > 0; o >>= 1) m = fmaxf(m, __shfl_xor(m, o));
+        float sum = 0.f, zl = 0.f;
+#pragma unroll
+        for (int i = 0; i < V; ++i) {
+          if (lane + 64 * i == lab[j]) zl = x[j][i];
+          x[j][i] = __expf(x[j][i] - m);   // exp(-inf) = 0 beyond the row
+          sum += x[j][i];
+        }
+        for (int o = 32; o > 0; o >>= 1) {
+          sum += __shfl_xor(sum, o);
+          zl += __shfl_xor(zl, o);
+        }
+        const float inv_sum = 1.0f / sum;
+#pragma unroll
+        for (int i = 0; i < V; ++i) {
+          const int c = lane + 64 * i;
+          float p = x[j][i] * inv_sum;
+          if (c == lab[j]) p -= 1.0f;
+          if (c < C) grad[(row0 + j) * C + c] = from_float<T>(p * inv_rows);
+        }
+        my_loss += (logf(sum) + m - zl) * inv_rows;
       }
-      my_loss += (logf(sum) + m - zl) * inv_rows;
-    } else {
+    }
+  } else {
+    for (int64_t row = (int64_t)blockIdx.x * 4 + wave; row < rows; row += (int64_t)gridDim.x * 4) {
+      const T *z = logits + row * C;
+      const int lab = (int)labels[row];
       float m = -INFINITY;
       for (int c = lane; c < C; c += 64) m = fmaxf(m, to_float(z[c]));
       for (int o = 32; o > 0; o >>= 1) m = fmaxf(m, __shfl_xor(m, o));
@@ -831,14 +848,12 @@ __global__ void __launch_bounds__(256) xent_kernel(const T *__restrict__ logits,
 
 template <typename T>
 static void launch_xent_typed(hipStream_t s, const void *logits, const int64_t *labels, int64_t rows, int C, float *loss, void *grad) {
-  // one wavefront per row while that gives at most 8192 blocks (more rows: several per wavefront)
-  dim3 grid((unsigned)std::min<int64_t>(8192, (rows + 3) / 4));
+  dim3 grid((unsigned)std::min<int64_t>(256, (rows + 4 * kXentRows - 1) / (4 * kXentRows)));
 #define HGNN_XENT(V_) HGNN_LAUNCH((xent_kernel<T, V_>), grid, dim3(256), 0, s, (const T *)logits, labels, rows, C, loss, (T *)grad)
   if (C <= 128) HGNN_XENT(2);
   else if (C <= 256) HGNN_XENT(4);
   else if (C <= 384) HGNN_XENT(6);
   else if (C <= 512) HGNN_XENT(8);
-  else if (C <= 1024) HGNN_XENT(16);
   else HGNN_XENT(0);
 #undef HGNN_XENT
 }
