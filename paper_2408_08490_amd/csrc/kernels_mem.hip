@@ -376,7 +376,7 @@ __device__ __forceinline__ void pad_weights_part(const TypeTab &tt, const RelTab
                                                  int Hp, T *out, int seg, int bx, int gx) {
   const int R = rt.num_rels;
   const T *w = (const T *)(seg < R ? pt.w_rel[seg] : pt.w_root[seg - R]);
-  if (!w) return;
+  if (!w || tt.n_dst[seg < R ? rt.dst[seg] : seg - R] == 0) return;  // no destination rows: no tile reads this copy
   const int F = tt.in_dim[seg < R ? rt.src[seg] : seg - R];
   T *o = out + (int64_t)(seg < R ? wo.rel4[seg] : wo.root4[seg - R]) * 4;
   // a block takes whole rows (no division per element)
