@@ -504,7 +504,33 @@ def main():
                 model.run(batch_of(slots[i % len(slots)], graphs[i % len(slots)]), backward=True, gather=not model.gather)
             step_other(0)
             step_other_merge_ms = gpu_ms(step_other, n_ab)
+        # index-first feature layout: the rows of all types interleaved in one buffer, then a selection pass per step that
+        # puts them type-first for the layer calls (the type-first merge does this in one pass)
+        index_first_ms = type_first_merge_ms = None
+        if len(set(g.feat_dim)) == 1:
+            sl0 = slots[0]
+            n0 = [len(i) for i in sl0.mb.ids]
+            tot0, F0 = sum(n0), g.feat_dim[0]
+            key = np.concatenate([(np.arange(k) + 0.5) / max(k, 1) for k in n0])
+            rank = np.empty(tot0, np.int64)
+            rank[np.argsort(key, kind="stable")] = np.arange(tot0)
+            offs = np.concatenate([[0], np.cumsum(n0)])
+            pos = [torch.from_numpy(rank[offs[t]: offs[t + 1]].astype(np.int32)).to(model.dev) for t in range(len(n0))]
+            x_int = torch.empty(tot0 * F0, device=model.dev, dtype=model.stores[0].dtype)
+            x_tf = torch.empty(tot0 * F0, device=model.dev, dtype=model.stores[0].dtype)
+
+            def index_first(i):
+                ctx.hgnn_merge_features_index_first(model.stores, sl0.ids_dev, pos, x_int, g.feat_dim)
+                ctx.hgnn_select_type_first(x_int, pos, x_tf, g.feat_dim)
+
+            def type_first(i):
+                ctx.hgnn_merge_features(model.stores, sl0.ids_dev, x_tf, g.feat_dim)
+            index_first(0)
+            index_first_ms = gpu_ms(index_first, n_ab)
+            type_first_merge_ms = gpu_ms(type_first, n_ab)
         abl = dict(steps_timed=n_ab, forward_merged_ms=round(merged_fwd_ms, 4),
+                   feature_stage_type_first_ms=None if type_first_merge_ms is None else round(type_first_merge_ms, 4),
+                   feature_stage_index_first_ms=None if index_first_ms is None else round(index_first_ms, 4),
                    step_merged_launches_ms=round(step_merged_ms, 4),
                    first_layer_input=("destination rows merged, aggregation reads the feature stores" if model.gather
                                       else "every source row merged"),
@@ -521,6 +547,8 @@ def main():
                         "the same with loss and backward, merged launches against the per-relation / per-type launch loop; two_step: "
                         "the aggregation as Algorithm 1 states it (source rows of all semantic graphs gathered into "
                         "FeatureCat, then reduced by destination) instead of the fused gather-mean; "
+                        "feature_stage_*: the feature merge alone, type-first in one pass (hgnn_merge_features) against an index-first "
+                        "buffer (rows of all types interleaved) followed by the per-type selection the layer calls need; "
                         "serial: every step builds its index arrays with one builder, waits, computes, waits; "
                         "device_build: every step builds them with device kernels on the compute stream "
                         "(hgnn_build_semantic_csr_device: keys, two radix sorts, prefix sums), then computes; device_build_gpu_ms "

@@ -97,6 +97,23 @@ hgnn_status hgnn_merge_features(hgnn_ctx *ctx, void *stream, const void *const *
                                 const int64_t *n_rows, void *x_merged, int32_t *row_off,
                                 int64_t *elem_off);
 
+/* Index-first baseline of the same stage (what Section 4.2's reorganisation replaces; kept for the ablation): the
+ * mini-batch's rows of ALL types in one buffer in an interleaved order, as a framework that keeps features by global
+ * vertex index has them.  pos: host array [T] of device int32 arrays, pos[t][i] = row of the interleaved buffer
+ * that holds row i of type t (together a permutation of 0 .. sum n_rows - 1; positions outside are clamped into
+ * the buffer).  One width for all types (HGNN_EUNSUPPORTED otherwise).  hgnn_merge_features_index_first gathers
+ * the store rows into that order; hgnn_select_type_first then copies them into the type-first x_merged the
+ * layer calls read -- the per-type selection pass that the type-first merge makes unnecessary -- and returns the
+ * same offsets as hgnn_merge_features.  Both enqueue on `stream` and return. */
+hgnn_status hgnn_merge_features_index_first(hgnn_ctx *ctx, void *stream, const void *const *store,
+                                            const int32_t *feat_dim, const int64_t *const *ids,
+                                            const int64_t *n_rows, const int32_t *const *pos,
+                                            void *x_interleaved);
+hgnn_status hgnn_select_type_first(hgnn_ctx *ctx, void *stream, const void *x_interleaved,
+                                   const int32_t *feat_dim, const int32_t *const *pos,
+                                   const int64_t *n_rows, void *x_merged, int32_t *row_off,
+                                   int64_t *elem_off);
+
 /* ---- Stage 1: semantic graph build on the host (Section 4.3, Algorithm 2) ----------------
  * One mini-batch layer as the sampler hands it over: a COO edge list mixing all relations. */
 typedef struct {

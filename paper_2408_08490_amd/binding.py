@@ -89,6 +89,8 @@ def _load():
         "hgnn_create": [C.POINTER(vp), C.POINTER(Schema), C.c_int, C.c_int, C.c_int],
         "hgnn_merge_features": [vp, vp, C.POINTER(vp), C.POINTER(i32), C.POINTER(vp), C.POINTER(i64), vp,
                                 C.POINTER(i32), C.POINTER(i64)],
+        "hgnn_merge_features_index_first": [vp, vp, C.POINTER(vp), C.POINTER(i32), C.POINTER(vp), C.POINTER(i64), C.POINTER(vp), vp],
+        "hgnn_select_type_first": [vp, vp, vp, C.POINTER(i32), C.POINTER(vp), C.POINTER(i64), vp, C.POINTER(i32), C.POINTER(i64)],
         "hgnn_build_semantic_csr": [vp, i32, C.POINTER(CooLayer), C.POINTER(vp)],
         "hgnn_build_semantic_csr_device": [vp, vp, i32, C.POINTER(CooLayer), C.POINTER(vp), C.POINTER(C.c_float)],
         "hgnn_set_edge_types": [vp, vp, i64],
@@ -137,7 +139,7 @@ def _load():
 
 lib = _load()
 
-EXPORTS = ["hgnn_create", "hgnn_destroy", "hgnn_last_error", "hgnn_merge_features", "hgnn_build_semantic_csr_device", "hgnn_layer_fwd_gather", "hgnn_layer_bwd_gather", "hgnn_set_edge_types",
+EXPORTS = ["hgnn_create", "hgnn_destroy", "hgnn_last_error", "hgnn_merge_features", "hgnn_merge_features_index_first", "hgnn_select_type_first", "hgnn_build_semantic_csr_device", "hgnn_layer_fwd_gather", "hgnn_layer_bwd_gather", "hgnn_set_edge_types",
            "hgnn_build_semantic_csr", "hgnn_sampler_create", "hgnn_sampler_destroy", "hgnn_sample_and_build",
            "hgnn_graph_ids", "hgnn_graph_minibatch_view", "hgnn_graph_wait_stream",
            "hgnn_set_build_permutation", "hgnn_graph_wait", "hgnn_graph_host_view", "hgnn_graph_release", "hgnn_layer_workspace_bytes",
@@ -324,6 +326,28 @@ class Context:
         row_off = (C.c_int32 * (T + 1))()
         elem_off = (C.c_int64 * (T + 1))()
         _check(lib.hgnn_merge_features(self.handle, _stream_ptr(self.device), st, fd, idp, nr, _ptr(x_merged), row_off, elem_off))
+        return np.array(row_off[:], dtype=np.int32), np.array(elem_off[:], dtype=np.int64)
+
+    def hgnn_merge_features_index_first(self, stores, ids, pos, x_interleaved, feat_dim=None):
+        """pos: per type a device int32 tensor, the interleaved-buffer row of each of the type's rows."""
+        T = self.num_types
+        feat_dim = [s.shape[1] for s in stores] if feat_dim is None else feat_dim
+        st = (C.c_void_p * T)(*[_ptr(s) for s in stores])
+        idp = (C.c_void_p * T)(*[(_ptr(i) if i is not None and i.numel() > 0 else None) for i in ids])
+        pp = (C.c_void_p * T)(*[(_ptr(q) if q is not None and q.numel() > 0 else None) for q in pos])
+        fd = (C.c_int32 * T)(*feat_dim)
+        nr = (C.c_int64 * T)(*[(0 if i is None else i.numel()) for i in ids])
+        _check(lib.hgnn_merge_features_index_first(self.handle, _stream_ptr(self.device), st, fd, idp, nr, pp, _ptr(x_interleaved)))
+
+    def hgnn_select_type_first(self, x_interleaved, pos, x_merged, feat_dim):
+        T = self.num_types
+        pp = (C.c_void_p * T)(*[(_ptr(q) if q is not None and q.numel() > 0 else None) for q in pos])
+        fd = (C.c_int32 * T)(*feat_dim)
+        nr = (C.c_int64 * T)(*[(0 if q is None else q.numel()) for q in pos])
+        row_off = (C.c_int32 * (T + 1))()
+        elem_off = (C.c_int64 * (T + 1))()
+        _check(lib.hgnn_select_type_first(self.handle, _stream_ptr(self.device), _ptr(x_interleaved), fd, pp, nr, _ptr(x_merged),
+                                          row_off, elem_off))
         return np.array(row_off[:], dtype=np.int32), np.array(elem_off[:], dtype=np.int64)
 
     # ---- parameter update ----

@@ -731,6 +731,63 @@ hgnn_status hgnn_merge_features(hgnn_ctx *ctx, void *stream, const void *const *
   return HGNN_OK;
 }
 
+// The two halves of the index-first baseline: offsets as hgnn_merge_features computes them, one width for all types.
+static hgnn_status index_first_common(hgnn_ctx *ctx, const int32_t *feat_dim, const int64_t *n_rows, const int32_t *const *pos,
+                                      int64_t *tmp_eo, int32_t *tmp_ro) {
+  const int T = ctx->T, vec = 16 / esize(ctx->dtype);
+  int64_t ro = 0, eo = 0;
+  for (int t = 0; t < T; ++t) {
+    if (n_rows[t] < 0) HGNN_FAIL(HGNN_EINVAL, "n_rows[%d] is negative", t);
+    if (feat_dim[t] <= 0 || feat_dim[t] % vec != 0)
+      HGNN_FAIL(HGNN_EINVAL, "feat_dim[%d]=%d is not a positive multiple of %d", t, feat_dim[t], vec);
+    if (feat_dim[t] != feat_dim[0]) HGNN_FAIL(HGNN_EUNSUPPORTED, "an interleaved buffer needs one width for all types");
+    if (n_rows[t] > 0 && !pos[t]) HGNN_FAIL(HGNN_EINVAL, "type %d has rows but a NULL position list", t);
+    tmp_ro[t] = (int32_t)ro;
+    tmp_eo[t] = eo;
+    ro += n_rows[t];
+    eo += n_rows[t] * (int64_t)feat_dim[t];
+    if (ro > INT32_MAX) HGNN_FAIL(HGNN_EOVERFLOW, "more than 2^31-1 merged rows");
+  }
+  tmp_ro[T] = (int32_t)ro;
+  tmp_eo[T] = eo;
+  if (ctx->device < 0) HGNN_FAIL(HGNN_EUNSUPPORTED, "host-only context cannot run device work");
+  return HGNN_OK;
+}
+
+hgnn_status hgnn_merge_features_index_first(hgnn_ctx *ctx, void *stream, const void *const *store, const int32_t *feat_dim,
+                                            const int64_t *const *ids, const int64_t *n_rows, const int32_t *const *pos,
+                                            void *x_interleaved) {
+  if (!ctx || !store || !feat_dim || !ids || !n_rows || !pos) HGNN_FAIL(HGNN_EINVAL, "NULL argument");
+  int64_t tmp_eo[kMaxT + 1];
+  int32_t tmp_ro[kMaxT + 1];
+  hgnn_status st = index_first_common(ctx, feat_dim, n_rows, pos, tmp_eo, tmp_ro);
+  if (st != HGNN_OK) return st;
+  for (int t = 0; t < ctx->T; ++t)
+    if (n_rows[t] > 0 && (!store[t] || !ids[t])) HGNN_FAIL(HGNN_EINVAL, "type %d has rows but a NULL store or id list", t);
+  if (tmp_ro[ctx->T] > 0 && !x_interleaved) HGNN_FAIL(HGNN_EINVAL, "x_interleaved is NULL");
+  Probe pb(ctx, (hipStream_t)stream, HGNN_K_MERGE, -1);
+  return launch_merge((hipStream_t)stream, ctx->dtype, ctx->T, store, feat_dim, ids, n_rows, tmp_eo, x_interleaved, 1, pos, nullptr);
+}
+
+hgnn_status hgnn_select_type_first(hgnn_ctx *ctx, void *stream, const void *x_interleaved, const int32_t *feat_dim,
+                                   const int32_t *const *pos, const int64_t *n_rows, void *x_merged, int32_t *row_off,
+                                   int64_t *elem_off) {
+  if (!ctx || !feat_dim || !pos || !n_rows || !row_off || !elem_off) HGNN_FAIL(HGNN_EINVAL, "NULL argument");
+  int64_t tmp_eo[kMaxT + 1];
+  int32_t tmp_ro[kMaxT + 1];
+  hgnn_status st = index_first_common(ctx, feat_dim, n_rows, pos, tmp_eo, tmp_ro);
+  if (st != HGNN_OK) return st;
+  if (tmp_ro[ctx->T] > 0 && (!x_interleaved || !x_merged)) HGNN_FAIL(HGNN_EINVAL, "NULL buffer");
+  {
+    Probe pb(ctx, (hipStream_t)stream, HGNN_K_MERGE, -1);
+    st = launch_merge((hipStream_t)stream, ctx->dtype, ctx->T, nullptr, feat_dim, nullptr, n_rows, tmp_eo, x_merged, 2, pos, x_interleaved);
+  }
+  if (st != HGNN_OK) return st;
+  std::memcpy(row_off, tmp_ro, sizeof(int32_t) * (ctx->T + 1));
+  std::memcpy(elem_off, tmp_eo, sizeof(int64_t) * (ctx->T + 1));
+  return HGNN_OK;
+}
+
 extern "C++" {
 namespace hgnn {
 constexpr size_t kMaxTypeRuns = 32;

@@ -299,8 +299,11 @@ hgnn_status layer_fwd_static_area(hgnn_ctx *ctx, void *stream, hgnn_graph *g, in
                                   const void *x, void *h, void *saved, size_t saved_bytes, void *area, size_t area_bytes);
 
 // ---- kernel launchers (kernels_*.hip); all enqueue on `s` and return ----
+// mode 0: rows ids[t][i] of store t -> type-first `out`; mode 1: the same rows -> row pos[t][i] of one interleaved buffer
+// `out` (all types one width); mode 2: row pos[t][i] of `interleaved` -> type-first `out`
 hgnn_status launch_merge(hipStream_t s, int dtype, int T, const void *const *store, const int32_t *feat_dim,
-                         const int64_t *const *ids, const int64_t *n_rows, const int64_t *elem_off, void *out);
+                         const int64_t *const *ids, const int64_t *n_rows, const int64_t *elem_off, void *out, int mode = 0,
+                         const int32_t *const *pos = nullptr, const void *interleaved = nullptr);
 // rows [row_begin,row_end) of the merged CSR: z[row] = mean of the x rows in colidx (rounded to the storage type);
 // zlo (optional, same layout): what that rounding dropped, rounded in turn
 // tj (optional): weight transposes that ride in the same launch as its first blocks (in a launch of their own when

@@ -16,10 +16,13 @@ namespace hgnn {
 struct MergeTab {
   const void *store[kMaxT];
   const int64_t *ids[kMaxT];
+  const int32_t *pos[kMaxT];   // index-first baseline: row of the interleaved buffer that holds row i of type t
+  const char *inter;           // mode 2: the interleaved buffer rows are read from
   int64_t elem_off[kMaxT + 1];
   int32_t row_off[kMaxT + 1];
   int32_t dim[kMaxT];
   int32_t num_types;
+  int32_t mode;                // 0: stores -> type-first buffer; 1: stores -> interleaved buffer; 2: interleaved -> type-first
 };
 
 __global__ void __launch_bounds__(256) merge_kernel(MergeTab mt, char *out, int esize, int lpr_log2) {
@@ -30,10 +33,13 @@ __global__ void __launch_bounds__(256) merge_kernel(MergeTab mt, char *out, int 
   int t = 0;
   while (row >= mt.row_off[t + 1]) ++t;
   const int i = row - mt.row_off[t];
-  const int64_t id = mt.ids[t][i];
   const int nvec = (mt.dim[t] * esize) >> 4;
-  const uint4 *src = reinterpret_cast<const uint4 *>(mt.store[t]) + id * nvec;
-  uint4 *dst = reinterpret_cast<uint4 *>(out + mt.elem_off[t] * esize) + (int64_t)i * nvec;
+  // interleaved position, clamped into the buffer (a caller's bad position cannot leave it)
+  const int64_t at = mt.mode ? min(max(mt.pos[t][i], 0), mt.row_off[mt.num_types] - 1) : 0;
+  const uint4 *src = mt.mode == 2 ? reinterpret_cast<const uint4 *>(mt.inter) + at * nvec
+                                  : reinterpret_cast<const uint4 *>(mt.store[t]) + mt.ids[t][i] * nvec;
+  uint4 *dst = mt.mode == 1 ? reinterpret_cast<uint4 *>(out) + at * nvec
+                            : reinterpret_cast<uint4 *>(out + mt.elem_off[t] * esize) + (int64_t)i * nvec;
   for (int c = lane; c < nvec; c += 2 * lpr) {  // both loads before the stores
     const int c2 = c + lpr;
     const uint4 a = src[c];
@@ -44,14 +50,19 @@ __global__ void __launch_bounds__(256) merge_kernel(MergeTab mt, char *out, int 
 }
 
 hgnn_status launch_merge(hipStream_t s, int dtype, int T, const void *const *store, const int32_t *feat_dim,
-                         const int64_t *const *ids, const int64_t *n_rows, const int64_t *elem_off, void *out) {
+                         const int64_t *const *ids, const int64_t *n_rows, const int64_t *elem_off, void *out, int mode,
+                         const int32_t *const *pos, const void *interleaved) {
   MergeTab mt;
+  std::memset(&mt, 0, sizeof(mt));
   const int es = dtype == HGNN_BF16 ? 2 : 4;
   int maxd = 0;
   mt.row_off[0] = 0;
+  mt.mode = mode;
+  mt.inter = (const char *)interleaved;
   for (int t = 0; t < T; ++t) {
-    mt.store[t] = store[t];
-    mt.ids[t] = ids[t];
+    mt.store[t] = store ? store[t] : nullptr;
+    mt.ids[t] = ids ? ids[t] : nullptr;
+    mt.pos[t] = pos ? pos[t] : nullptr;
     mt.elem_off[t] = elem_off[t];
     mt.row_off[t + 1] = mt.row_off[t] + (int32_t)n_rows[t];
     mt.dim[t] = feat_dim[t];

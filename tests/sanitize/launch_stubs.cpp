@@ -4,7 +4,8 @@
 
 namespace hgnn {
 hgnn_status launch_merge(hipStream_t s, int dtype, int T, const void *const *store, const int32_t *feat_dim,
-                         const int64_t *const *ids, const int64_t *n_rows, const int64_t *elem_off, void *out) { return HGNN_EUNSUPPORTED; }
+                         const int64_t *const *ids, const int64_t *n_rows, const int64_t *elem_off, void *out, int mode,
+                         const int32_t *const *pos, const void *interleaved) { return HGNN_EUNSUPPORTED; }
 hgnn_status launch_spmm_fwd(hipStream_t s, int dtype, const LayerDev &L, const TypeTab &tt, const RelTab &rt,
                             int max_dim, const void *x, void *z, void *zlo, int row_begin, int row_end, const TransposeJobs *tj) { return HGNN_EUNSUPPORTED; }
 hgnn_status launch_aggregate_literal(hipStream_t s, int dtype, const LayerDev &L, int F, const void *x, void *feature_cat,

@@ -252,3 +252,51 @@ def test_single_target_minibatch():
     assert r["ok"], r
     r = run_case(2, scale=0.05, batch=1, verbose=True)
     assert r["ok"], r
+
+
+def test_index_first_baseline_round_trip():
+    """The index-first baseline of the feature stage (hgnn_merge_features_index_first + hgnn_select_type_first): rows of
+    all types interleaved in one buffer, then selected back per type, give hgnn_merge_features' x_merged and offsets
+    bit for bit; the interleaved buffer holds every row at its stated position."""
+    import torch
+    import paper_2408_08490_amd.binding as B
+    from paper_2408_08490_amd.runner import to_device
+    from workloads import make_config, build_graph, sample_minibatch, bf16_round
+    for dtype in ("f32", "bf16"):
+        cfg = make_config(2, scale=0.02, batch=256)
+        g = build_graph(cfg)
+        mb = sample_minibatch(cfg, g)
+        sch = g.schema
+        T = sch.num_types
+        dev = torch.device("cuda", 0)
+        ctx = B.Context(sch.rel_src, sch.rel_dst, T, dtype, device=0, host_threads=1)
+        stores_np = [bf16_round(s) if dtype == "bf16" else np.asarray(s, np.float32) for s in g.stores]
+        stores = [to_device(s, dtype, dev) for s in stores_np]
+        ids = [torch.from_numpy(np.ascontiguousarray(i, dtype=np.int64)).to(dev) for i in mb.ids]
+        n = [len(i) for i in mb.ids]
+        total, F = sum(n), g.feat_dim[0]
+        # proportional interleaving of the types (a permutation of 0 .. total - 1)
+        key = np.concatenate([(np.arange(k) + 0.5) / max(k, 1) for k in n])
+        order = np.argsort(key, kind="stable")
+        rank = np.empty(total, np.int64); rank[order] = np.arange(total)
+        off = np.concatenate([[0], np.cumsum(n)])
+        pos_np = [rank[off[t]: off[t + 1]].astype(np.int32) for t in range(T)]
+        pos = [torch.from_numpy(p).to(dev) for p in pos_np]
+        tdt = torch.float32 if dtype == "f32" else torch.bfloat16
+        x_int = torch.empty(total * F, device=dev, dtype=tdt)
+        x_sel = torch.empty(total * F, device=dev, dtype=tdt)
+        x_ref = torch.empty(total * F, device=dev, dtype=tdt)
+        ctx.hgnn_merge_features_index_first(stores, ids, pos, x_int, g.feat_dim)
+        ro, eo = ctx.hgnn_select_type_first(x_int, pos, x_sel, g.feat_dim)
+        ro2, eo2 = ctx.hgnn_merge_features(stores, ids, x_ref, g.feat_dim)
+        torch.cuda.synchronize()
+        assert np.array_equal(ro, ro2) and np.array_equal(eo, eo2)
+        assert torch.equal(x_sel.view(torch.uint8), x_ref.view(torch.uint8))
+        want = np.empty((total, F), np.float32)
+        for t in range(T):
+            want[pos_np[t]] = stores_np[t][mb.ids[t]]
+        assert np.array_equal(x_int.float().cpu().numpy().reshape(total, F), want)
+        # ragged widths are refused
+        with pytest.raises(B.HgnnError):
+            ctx.hgnn_merge_features_index_first(stores, ids, pos, x_int, [F] * (T - 1) + [F * 2])
+        ctx.close()
