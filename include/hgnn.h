@@ -354,10 +354,12 @@ hgnn_status hgnn_layer_bwd_gather(hgnn_ctx *ctx, void *stream, hgnn_graph *g, in
  *   m_v^r = concat_k sum_u softmax_u(e) z_u^k                         (empty neighbourhood: 0)
  *   w_r = mean_v q . tanh(m_v^r W_s + b_s),  beta = softmax over the relations ending in type(v)
  *   h_v = act( sum_r beta_r m_v^r + b_type(v) )
- * and its gradients.  The arithmetic and everything kept between the stages is fp32 in both storage types:
- * with dtype = HGNN_BF16 the inputs, parameters and incoming gradients are bf16 and are widened (exactly) into
- * the scratch area, and h_out / grad_x_merged are rounded once on the way out (the gradients of a_src / a_dst
- * are the remainder of a cancellation between a vertex's neighbours, which bf16 intermediates do not carry).
+ * and its gradients.  Everything kept between the stages (z, m, the scores, every gradient between them) is fp32
+ * in both storage types: with dtype = HGNN_BF16 the inputs, parameters and incoming gradients are bf16, the
+ * projection multiplies them as they are (bf16 MFMA, fp32 result), the small parameters and the incoming gradient
+ * are widened (exactly) into the scratch area, h_out is rounded once on the way out, and the projection's backward
+ * runs on dZ rounded to bf16 (the gradients of a_src / a_dst are the remainder of a cancellation between a
+ * vertex's neighbours, which bf16 intermediates do not carry; the projection's own gradients are plain sums).
  * Requirements: D a multiple of 4 scalars and a power of two times that, H / 4 a power of two <= 64; every
  * in_dim and H a multiple of 16 bytes of dtype; weight pointers 16-byte aligned; the graph built with
  * transpose entries for every type.  hgnn_layer_fwd_naive is not available for this variant. */

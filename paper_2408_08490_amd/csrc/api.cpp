@@ -233,7 +233,7 @@ struct AttnPlan {
   size_t c_gp = 0, c_small = 0, c_du = 0, c_dm = 0, c_alpha = 0, c_ds = 0, c_dsum = 0, c_dz = 0, c_partial = 0, scratch_bytes = 0;
   // fp32 copies of what the boundary holds in bf16 (scratch; bf16 storage only)
   bool widen = false;
-  size_t c_x32 = 0, c_w32 = 0, c_h32 = 0, c_g32 = 0, c_dx32 = 0;
+  size_t c_w32 = 0, c_h32 = 0, c_g32 = 0, c_dz16 = 0;
 };
 constexpr int kSemDimHost = 128;
 
@@ -315,30 +315,28 @@ static hgnn_status make_attn_plan(hgnn_ctx *ctx, hgnn_graph *g, int32_t layer, c
   pl.c_partial = take(o, (size_t)L.max_chunks * H * 4);
   if (pl.widen) {
     if (pl.H % vec_io) HGNN_FAIL(HGNN_EUNSUPPORTED, "out_dim %d is not a multiple of %d", pl.H, vec_io);
-    size_t wf = (size_t)2 * R * H + H * kSemDimHost + 2 * kSemDimHost;
-    for (int t = 0; t < T; ++t) wf += (size_t)p->in_dim[t] * H + H;
-    pl.c_x32 = take(o, (size_t)eo * 4);
+    size_t wf = (size_t)2 * R * H + H * kSemDimHost + 2 * kSemDimHost + (size_t)T * H;
     pl.c_w32 = take(o, wf * 4);
     pl.c_h32 = take(o, (size_t)pl.total_dst * H * 4);
     pl.c_g32 = take(o, (size_t)pl.total_dst * H * 4);
-    pl.c_dx32 = take(o, (size_t)eo * 4);
+    pl.c_dz16 = take(o, (size_t)pl.src_rows * H * 2);   // the projected features' gradient rounded for the projection's backward
   }
   pl.scratch_bytes = o;
   if (need_built) return layer_dev(ctx, g, layer, pl.dev);
   return HGNN_OK;
 }
 
-// fp32 stand-ins of a bf16 layer's parameters and input (in the scratch area); `q` then takes the place of the
-// caller's parameter block.  Not copyable: q points into the arrays beside it.
+// fp32 stand-ins (in the scratch area) of the parameters of a bf16 layer that its fp32 kernels read: attention vectors,
+// semantic-attention parameters, biases.  `q` then takes the place of the caller's parameter block for those kernels.
+// The per-type projection weights and the input stay bf16: the projection and its backward run on the bf16 MFMA kernels
+// (a product of two bf16 numbers is exact in fp32).  Not copyable: q points into the arrays beside it.
 struct AttnWide {
   hgnn_layer_params q;
-  const void *w_type[kMaxT], *bias[kMaxT], *a_src[kMaxR], *a_dst[kMaxR];
-  const void *x = nullptr;
+  const void *bias[kMaxT], *a_src[kMaxR], *a_dst[kMaxR];
   AttnWide() = default;
   AttnWide(const AttnWide &) = delete;
 };
-static hgnn_status attn_widen(hgnn_ctx *ctx, hipStream_t s, AttnPlan &pl, const hgnn_layer_params *p, const void *x, char *sc,
-                              AttnWide &w) {
+static hgnn_status attn_widen(hgnn_ctx *ctx, hipStream_t s, AttnPlan &pl, const hgnn_layer_params *p, char *sc, AttnWide &w) {
   const int T = ctx->T, R = ctx->R;
   const int64_t H = pl.H;
   std::vector<const void *> src;
@@ -354,26 +352,19 @@ static hgnn_status attn_widen(hgnn_ctx *ctx, hipStream_t s, AttnPlan &pl, const 
   };
   w.q = *p;
   for (int t = 0; t < T; ++t) {
-    w.w_type[t] = put(p->w_type[t], (int64_t)p->in_dim[t] * H);
     w.bias[t] = put(p->bias ? p->bias[t] : nullptr, H);
-    pl.pt.w_root[t] = w.w_type[t];
     pl.pt.bias[t] = w.bias[t];
   }
   for (int r = 0; r < R; ++r) {
     w.a_src[r] = put(p->a_src[r], H);
     w.a_dst[r] = put(p->a_dst[r], H);
   }
-  w.q.w_type = w.w_type;
   w.q.bias = p->bias ? w.bias : nullptr;
   w.q.a_src = w.a_src;
   w.q.a_dst = w.a_dst;
   w.q.w_sem = put(p->w_sem, H * kSemDimHost);
   w.q.b_sem = put(p->b_sem, kSemDimHost);
   w.q.q_sem = put(p->q_sem, kSemDimHost);
-  if (x && pl.tt.elem_off[T] > 0) {
-    src.push_back(x); dst.push_back(sc + pl.c_x32); cnt.push_back(pl.tt.elem_off[T]);
-    w.x = sc + pl.c_x32;
-  }
   return launch_convert(s, true, src.data(), dst.data(), cnt.data(), (int)src.size());
 }
 
@@ -396,9 +387,8 @@ static hgnn_status attn_fwd(hgnn_ctx *ctx, void *stream, hgnn_graph *g, int32_t 
   AttnWide wide;
   void *h_io = h;
   if (pl.widen) {
-    if ((st = attn_widen(ctx, s, pl, p, x, (char *)scratch, wide)) != HGNN_OK) return st;
+    if ((st = attn_widen(ctx, s, pl, p, (char *)scratch, wide)) != HGNN_OK) return st;
     p = &wide.q;
-    x = wide.x;
     h = (char *)scratch + pl.c_h32;
   }
   SegTab tl;   // projection tiles: every source row of every type
@@ -408,7 +398,8 @@ static hgnn_status attn_fwd(hgnn_ctx *ctx, void *stream, hgnn_graph *g, int32_t 
   for (int t = 0; t < T; ++t) tl.tile_off[t + 1] = tl.tile_off[t] + (int)((g->L[layer].n_src[t] + 127) / 128) * tn;
   {
     Probe pb(ctx, s, HGNN_K_GEMM_FWD, layer);
-    if ((st = launch_attn_proj(s, HGNN_F32, pl.tt, pl.pt, tl, pl.H, x, sv + pl.s_z)) != HGNN_OK) return st;
+    // bf16 storage: bf16 operands straight from the caller's buffers, fp32 result
+    if ((st = launch_attn_proj(s, ctx->dtype, pl.tt, pl.pt, tl, pl.H, x, sv + pl.s_z, pl.widen)) != HGNN_OK) return st;
   }
   {
     Probe pb(ctx, s, HGNN_K_SPMM_FWD, layer);
@@ -448,11 +439,9 @@ static hgnn_status attn_bwd(hgnn_ctx *ctx, void *stream, hgnn_graph *g, int32_t 
   char *sc = (char *)scratch;
   const LayerHost &L = g->L[layer];
   AttnWide wide;
-  void *grad_x_io = grad_x;
   if (pl.widen) {
-    if ((st = attn_widen(ctx, s, pl, p, x, sc, wide)) != HGNN_OK) return st;
+    if ((st = attn_widen(ctx, s, pl, p, sc, wide)) != HGNN_OK) return st;
     p = &wide.q;
-    x = wide.x;
     // incoming gradient and (for the ReLU decisions, a sign test that the rounding of the output keeps) the output
     const void *src[2] = {grad_h, p->relu ? h_out : nullptr};
     void *dst[2] = {sc + pl.c_g32, sc + pl.c_h32};
@@ -460,7 +449,6 @@ static hgnn_status attn_bwd(hgnn_ctx *ctx, void *stream, hgnn_graph *g, int32_t 
     if ((st = launch_convert(s, true, src, dst, n, 2)) != HGNN_OK) return st;
     grad_h = dst[0];
     h_out = dst[1];
-    if (grad_x) grad_x = sc + pl.c_dx32;
   }
   float *dbeta = (float *)(sc + pl.c_small), *coef = dbeta + kMaxR;
   const float *beta = (const float *)(sv + pl.s_beta);
@@ -553,7 +541,19 @@ static hgnn_status attn_bwd(hgnn_ctx *ctx, void *stream, hgnn_graph *g, int32_t 
     }
     for (int t = 0; t < T; ++t)
       dt.tile_off[t + 1] = dt.tile_off[t] + dt.u_total[t] * tiles_h * (int)((L.n_src[t] + split_rows - 1) / split_rows);
-    if ((st = launch_gemm_dw(s, HGNN_F32, pl.dev, tt2, rt2, gt, dt, split_rows, H, H, true, x, nullptr, sc + pl.c_dz)) != HGNN_OK) return st;
+    // bf16 storage: both GEMMs run on the bf16 MFMA kernels, on the caller's own x and weights and on dZ rounded to
+    // bf16 (a relative 2^-9 per element of a gradient that is summed over the rows; no decision hangs on it), and the
+    // input gradient leaves in the storage type directly
+    const void *dzp = sc + pl.c_dz;
+    const int gdt = pl.widen ? HGNN_BF16 : HGNN_F32;
+    if (pl.widen) {
+      const void *src = dzp;
+      void *dst = sc + pl.c_dz16;
+      const int64_t n = pl.src_rows * (int64_t)H;
+      if ((st = launch_convert(s, false, &src, &dst, &n, 1)) != HGNN_OK) return st;
+      dzp = dst;
+    }
+    if ((st = launch_gemm_dw(s, gdt, pl.dev, tt2, rt2, gt, dt, split_rows, H, H, true, x, nullptr, dzp)) != HGNN_OK) return st;
     if (grad_x) {
       SegTab tl;
       std::memset(&tl, 0, sizeof(tl));
@@ -567,19 +567,7 @@ static hgnn_status attn_bwd(hgnn_ctx *ctx, void *stream, hgnn_graph *g, int32_t 
         }
         tl.tile_off[sgi + 1] = tl.tile_off[sgi] + cnt;
       }
-      if ((st = launch_gemm_da(s, HGNN_F32, pl.dev, tt2, rt2, pl.pt, tl, H, true, sc + pl.c_dz, grad_x)) != HGNN_OK) return st;
-      if (pl.widen) {   // round the input gradient of the wanted types into the caller's buffer
-        std::vector<const void *> src;
-        std::vector<void *> dst;
-        std::vector<int64_t> cnt;
-        for (int t = 0; t < T; ++t) {
-          if ((p->input_grad && !p->input_grad[t]) || L.n_src[t] == 0) continue;
-          src.push_back((const float *)grad_x + pl.tt.elem_off[t]);
-          dst.push_back((char *)grad_x_io + pl.tt.elem_off[t] * 2);
-          cnt.push_back(L.n_src[t] * (int64_t)p->in_dim[t]);
-        }
-        if ((st = launch_convert(s, false, src.data(), dst.data(), cnt.data(), (int)src.size())) != HGNN_OK) return st;
-      }
+      if ((st = launch_gemm_da(s, gdt, pl.dev, tt2, rt2, pl.pt, tl, H, true, dzp, grad_x)) != HGNN_OK) return st;
     }
   }
   return HGNN_OK;

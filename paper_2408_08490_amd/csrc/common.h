@@ -349,7 +349,7 @@ bool launch_gemm2_fwd(hipStream_t s, const TypeTab &tt, const RelTab &rt, const 
                       int H, int relu, const void *x, const void *z, const void *zlo, const void *wt_buf, void *h, hgnn_status *st);
 // attention variant
 hgnn_status launch_attn_proj(hipStream_t s, int dtype, const TypeTab &tt, const PtrTab &w_type_as_root, const SegTab &tiles, int H,
-                             const void *x, void *z);
+                             const void *x, void *z, bool z_f32 = false);
 hgnn_status launch_attn_agg(hipStream_t s, int dtype, const LayerDev &L, const TypeTab &tt, const RelTab &rt,
                             const void *const *a_src, const void *const *a_dst, int H, int heads, const void *z, void *mout,
                             float *mx, float *ls);

@@ -317,13 +317,13 @@ template <int MI, int NI> __device__ __forceinline__ void zero_acc(f32x16 (&acc)
 // Writes the block's tile `out[(row0 + r) * ld + col0 + c] = f(acc, r, c)` for r < rows, c < cols.
 // When rows of `out` are 16-byte aligned the tile goes through LDS (the K loop's stages are free by then)
 // and leaves as whole 16-byte pieces; otherwise element by element.  `f(val, row, col)` returns the value.
-// The staged tile is fp32 whatever T is: 32-bit LDS writes with a pitch that puts the two half-waves
+// The output type TO may differ from the operands' T (bf16 operands, fp32 result).  The staged tile is fp32 whatever T is: 32-bit LDS writes with a pitch that puts the two half-waves
 // (rows r and r + 4 of one store) on disjoint banks; two lanes writing the halves of one dword would be
 // serialised.  Conversion to T happens on the way out.
-template <typename T, typename F, int MI, int NI>
-__device__ __forceinline__ void write_tile(f32x16 (&acc)[MI][NI], GemmLds<T, MI, NI> &sm, T *out, int64_t ld, int rows, int cols, F f) {
+template <typename T, typename TO, typename F, int MI, int NI>
+__device__ __forceinline__ void write_tile(f32x16 (&acc)[MI][NI], GemmLds<T, MI, NI> &sm, TO *out, int64_t ld, int rows, int cols, F f) {
   constexpr int TM = 64 * MI, TN = 64 * NI;
-  constexpr int V = 16 / sizeof(T), P = TN + kOutPitchPad;
+  constexpr int V = 16 / sizeof(TO), P = TN + kOutPitchPad;
   static_assert(sizeof(sm.a) + sizeof(sm.b) >= sizeof(float) * P * TM, "fp32 output tile must fit the stages");
   const bool vec = (ld % V) == 0 && (reinterpret_cast<uintptr_t>(out) & 15) == 0;
   if (vec) {
@@ -338,20 +338,20 @@ __device__ __forceinline__ void write_tile(f32x16 (&acc)[MI][NI], GemmLds<T, MI,
       if (r < rows && c < cols) {
         const float *sp = stage + r * P + c;
         u32x4 piece;
-        if constexpr (sizeof(T) == 4) {
+        if constexpr (sizeof(TO) == 4) {
           piece = *reinterpret_cast<const u32x4 *>(sp);
         } else {
           const f32x4 lo = *reinterpret_cast<const f32x4 *>(sp), hi = *reinterpret_cast<const f32x4 *>(sp + 4);
           piece = u32x4{pack2(lo.x, lo.y), pack2(lo.z, lo.w), pack2(hi.x, hi.y), pack2(hi.z, hi.w)};
         }
-        T *dst = out + (int64_t)r * ld + c;
+        TO *dst = out + (int64_t)r * ld + c;
         if (c + V <= cols) {
           *reinterpret_cast<u32x4 *>(dst) = piece;
         } else {  // last, partial piece of a row: element by element out of the registers
 #pragma unroll
           for (int j = 0; j < V; ++j) {
             if (c + j < cols) {
-              if constexpr (sizeof(T) == 4) {
+              if constexpr (sizeof(TO) == 4) {
                 reinterpret_cast<unsigned *>(dst)[j] = piece[j];
               } else {
                 const unsigned w = piece[j >> 1];
@@ -364,7 +364,7 @@ __device__ __forceinline__ void write_tile(f32x16 (&acc)[MI][NI], GemmLds<T, MI,
     }
   } else {
     HGNN_FOR_EACH_ACC({
-      if (row < rows && col < cols) out[(int64_t)row * ld + col] = from_float<T>(f(val, row, col));
+      if (row < rows && col < cols) out[(int64_t)row * ld + col] = from_float<TO>(f(val, row, col));
     })
   }
 }

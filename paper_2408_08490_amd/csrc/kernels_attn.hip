@@ -62,9 +62,11 @@ __device__ __forceinline__ int find_le(const int32_t *off, int n, int x) {  // l
 
 // ------------------------------------------------------------------------------------------
 // Projection: Z[row_off[t] + i, :] = X_t[i, :] W_t for every source row of every type.
-template <typename T>
+// TO = type of Z: fp32 with bf16 operands when the layer computes in fp32 on bf16 storage (the products of two bf16
+// numbers are exact in fp32, so this is the fp32 projection of the widened inputs up to the order of the adds).
+template <typename T, typename TO>
 __global__ void __launch_bounds__(kThreads, 2) attn_proj_kernel(TypeTab tt, PtrTab pt, SegTab tiles, int H, const T *__restrict__ x,
-                                                              T *__restrict__ z) {
+                                                              TO *__restrict__ z) {
   __shared__ GemmLds<T> sm;
   const int tile = xcd_tile(blockIdx.x, gridDim.x);
   const int T_ = tt.num_types;
@@ -281,12 +283,16 @@ static int log2_exact(int n) {
 }
 
 hgnn_status launch_attn_proj(hipStream_t s, int dtype, const TypeTab &tt, const PtrTab &w_type_as_root, const SegTab &tiles, int H,
-                             const void *x, void *z) {
+                             const void *x, void *z, bool z_f32) {
   const int n = tiles.tile_off[tt.num_types];
   if (n == 0) return HGNN_OK;
   dim3 grid(round_up8(n)), blk(kThreads);
-  if (dtype == HGNN_BF16) HGNN_LAUNCH(attn_proj_kernel<bf16>, grid, blk, 0, s, tt, w_type_as_root, tiles, H, (const bf16 *)x, (bf16 *)z);
-  else HGNN_LAUNCH(attn_proj_kernel<float>, grid, blk, 0, s, tt, w_type_as_root, tiles, H, (const float *)x, (float *)z);
+  if (dtype == HGNN_BF16 && z_f32)
+    HGNN_LAUNCH((attn_proj_kernel<bf16, float>), grid, blk, 0, s, tt, w_type_as_root, tiles, H, (const bf16 *)x, (float *)z);
+  else if (dtype == HGNN_BF16)
+    HGNN_LAUNCH((attn_proj_kernel<bf16, bf16>), grid, blk, 0, s, tt, w_type_as_root, tiles, H, (const bf16 *)x, (bf16 *)z);
+  else
+    HGNN_LAUNCH((attn_proj_kernel<float, float>), grid, blk, 0, s, tt, w_type_as_root, tiles, H, (const float *)x, (float *)z);
   HGNN_HIP(hipGetLastError());
   return HGNN_OK;
 }
