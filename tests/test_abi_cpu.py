@@ -342,6 +342,37 @@ def test_feature_widths_off_the_16_byte_grid_are_refused(B, dtype, width, vec):
     ctx.close()
 
 
+def test_ablation_entry_points_validate_before_touching_the_device(B):
+    """The baselines' entry points on a host-only context: argument errors come first, then the refusal to run device
+    work (never a crash): the device-side index build, the index-first feature stage, the gather-from-stores layer."""
+    cfg = make_config(0)
+    g = build_graph(cfg)
+    mb = sample_minibatch(cfg, g)
+    sch = g.schema
+    T = sch.num_types
+    ctx = _host_ctx(B, sch)
+    with pytest.raises(B.HgnnError) as e:
+        B._check(B.lib.hgnn_build_semantic_csr_device(ctx.handle, None, 1, (B.CooLayer * 1)(), C.byref(C.c_void_p()), None))
+    assert e.value.status == -6 and "host-only" in str(e.value)
+    vp = C.c_void_p
+    none = (vp * T)(*[None] * T)
+    nr = (C.c_int64 * T)(*[0] * T)
+    ro, eo = (C.c_int32 * (T + 1))(), (C.c_int64 * (T + 1))()
+    ragged = (C.c_int32 * T)(*([64] * (T - 1) + [32]))
+    st = B.lib.hgnn_merge_features_index_first(ctx.handle, None, none, ragged, none, nr, none, None)
+    assert st == -6 and b"one width" in B.lib.hgnn_last_error()
+    st = B.lib.hgnn_select_type_first(ctx.handle, None, None, ragged, none, nr, None, ro, eo)
+    assert st == -6 and b"one width" in B.lib.hgnn_last_error()
+    same = (C.c_int32 * T)(*[64] * T)
+    st = B.lib.hgnn_merge_features_index_first(ctx.handle, None, none, same, none, nr, None, None)
+    assert st == -1                                   # NULL position table
+    st = B.lib.hgnn_select_type_first(ctx.handle, None, None, same, none, nr, None, ro, eo)
+    assert st == -6 and b"host-only" in B.lib.hgnn_last_error()
+    st = B.lib.hgnn_layer_fwd_gather(ctx.handle, None, None, 0, None, None, None, None, None, None, 0, None, 0)
+    assert st == -1
+    ctx.close()
+
+
 # ---- sampling in the loop: the library's sampler against the sampler oracle, bit for bit ----
 def _sampler(B, ctx, g):
     return ctx.hgnn_sampler_create(g.num_nodes, g.in_indptr, g.in_nbr, g.edge_off)
