@@ -353,6 +353,8 @@ def run_case(index, scale=1.0, batch=None, verbose=False, use_edge_id=True, chec
                 chk2(f"L{l}.dx", got_dx, np.concatenate([d.ravel() for d in gr["dx"]]),
                      np.concatenate([d.ravel() for d in gt["dx"]]))
     check_run(out)
+    # the runner reuses its buffers from run to run: what later comparisons need of this run is copied now
+    first = dict(h=[h.clone() for h in out["h"]], dx=[None if d is None else d.clone() for d in out.get("dx", [])])
     if cfg.loss == "xent":
         chk("loss", out["loss"].cpu().numpy(), np.array([ref["loss"]]))
     if check_naive:
@@ -371,7 +373,6 @@ def run_case(index, scale=1.0, batch=None, verbose=False, use_edge_id=True, chec
         report["merged_launches"] = [model.ctx.hgnn_layer_launch_count(bt.graph, l, model.layers[l])
                                      for l in range(len(ws))]
     if check_gather:
-        first = dict(h=[h.clone() for h in out["h"]], dx=[None if d is None else d.clone() for d in out.get("dx", [])])
         out4 = model.run(bt, backward=backward, need_input_grad=need_input_grad, gather=True)
         torch.cuda.synchronize()
         check_run(out4, "_gather")
@@ -386,7 +387,7 @@ def run_case(index, scale=1.0, batch=None, verbose=False, use_edge_id=True, chec
     if check_two_step:
         # Algorithm 1 in its two stated steps (FeatureCat, then reduce): against the oracle like the fused path,
         # and bit for bit against the fused path's outputs
-        fused = [h.clone() for h in out["h"]]
+        fused = first["h"]
         out3 = model.run(bt, backward=False, two_step=True)
         torch.cuda.synchronize()
         for l in range(len(ws)):

@@ -55,7 +55,7 @@ def test_first_layer_gathers_from_the_feature_stores():
     """hgnn_layer_fwd_gather / hgnn_layer_bwd_gather: the aggregation reads source rows through per-edge addresses into
     the per-type stores and only the destination rows are merged; same checks against the oracle, same bits as the
     fully merged path.  fp32 (config 1), bf16 with remainder planes (config 2), sampled in the loop (device ids)."""
-    _assert_ok(run_case(1, scale=0.05, batch=256, verbose=True, check_gather=True))
+    _assert_ok(run_case(1, scale=0.05, batch=256, verbose=True, check_gather=True, check_naive=True))
     _assert_ok(run_case(2, scale=0.05, batch=512, verbose=True, check_gather=True))
     _assert_ok(run_case(2, scale=0.05, batch=512, verbose=True, check_gather=True, sampled=dict(seed=5)))
 
