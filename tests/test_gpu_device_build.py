@@ -69,3 +69,16 @@ def test_device_build_reports_bad_edges():
     assert v["rowptr"][-1] == mb.blocks[0].edge_index.shape[1]
     gr.release()
     ctx.close()
+
+
+def test_device_build_degenerate_and_int32_inputs():
+    """A block without any edge, a relation that lost its edges, a single target, int32 COO indices with per-edge types."""
+    from tests.test_gpu_parity import _drop_edges
+
+    def as_i32(cfg, g, mb, ws):
+        for b in mb.blocks:
+            b.edge_index = b.edge_index.astype(np.int32)
+    _assert_ok(run_case(0, verbose=True, device_build=True, cfg_edit=_drop_edges(lambda t: False)))
+    _assert_ok(run_case(0, verbose=True, device_build=True, cfg_edit=_drop_edges(lambda t: t != 1), check_naive=True))
+    _assert_ok(run_case(2, scale=0.02, batch=1, verbose=True, device_build=True, check_gather=True))
+    _assert_ok(run_case(2, scale=0.05, batch=512, verbose=True, device_build=True, cfg_edit=as_i32, use_edge_id=False))
