@@ -25,7 +25,7 @@ struct LiveMask {
 };
 
 template <typename T, bool FAST, int MI>
-__global__ void __launch_bounds__(kThreads, MI == 1 ? 4 : 2) gemm_fwd_kernel(TypeTab tt, RelTab rt, PtrTab pt, WtTab wt, SegTab tiles, XcdMap xmap, LiveMask live,
+__global__ void __launch_bounds__(kThreads, MI == 1 ? 3 : 2) gemm_fwd_kernel(TypeTab tt, RelTab rt, PtrTab pt, WtTab wt, SegTab tiles, XcdMap xmap, LiveMask live,
                                                             int H, int relu, const T *__restrict__ x, const T *__restrict__ z,
                                                             const T *__restrict__ zlo, const T *__restrict__ wtb,
                                                             T *__restrict__ h, int only_seg,
